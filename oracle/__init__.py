@@ -1,0 +1,9 @@
+"""CPU oracle for the vector-quantised matrix-vector path (TEST INFRASTRUCTURE).
+
+Only tests, the smoke check and the bench's CPU-baseline leg may import this
+package.  It shares no code with the GPU library and never calls it.
+"""
+from .vq_oracle import (  # noqa: F401
+    VQFormat, bits_per_value, canonical_sizes, unpack_indices, decode_dense,
+    gemv, gemm, decode_element, normwise_rel_err,
+)

@@ -1,0 +1,180 @@
+"""Plain CPU oracle: what the VQ decode + matrix-vector path computes.
+
+TEST INFRASTRUCTURE.  Slow, straightforward NumPy in fp64; imported only by
+tests, the smoke check and the bench's CPU-baseline leg.  Nothing here is
+shared with, derived from, or fed by the GPU library.
+
+What is computed (paper passages followed, restated):
+
+* Sec. 2.1: a codebook C_d = {c_1..c_k} holds k centroids of d values each;
+  every run of d values of the tensor is replaced by the index of one
+  centroid, stored in ceil(log2 k) bits.
+* Sec. 3.1: the tensor is split into groups; each group is stored as a
+  tuple (indices, lookup table, scale).  Here centroids are fp16 with the
+  scale already folded in, so a group is (indices, table).
+* Sec. 4 (GPTVQ paragraph): a vector spans d consecutive *columns* of one
+  row (the input dimension); groups are at most 256 columns wide, e.g.
+  2,048 weights = 8 rows x 256 columns.
+* Sec. 4 (Total bits per value): bpv = log2(k)/d + k*d*b_c/l.
+* Sec. 3.2: at inference a block is decoded by table lookup to the native
+  type and then used in the matrix-vector product.
+
+Decoding is a table copy, so the result has a plain definition and the
+oracle is that definition written out:
+
+    W[r, c + t] = C_g[ I_g[v] ][t],   y = W x  (fp64 accumulate).
+
+Canonical byte order (the paper only says indices are "packed tightly";
+these are the readings this build fixes):
+
+* groups tile W row-block-major: g = (r // gr) * (in // gc) + (c // gc);
+* inside a group vectors are row-major: v = (r % gr) * (gc // d) + (c % gc) // d;
+* a group's indices form a little-endian bit stream: vector v occupies bits
+  [v*b, (v+1)*b) of the group's bytes, bit 0 = least significant bit of
+  byte 0 (for b=4: even v in the low nibble, odd v in the high nibble;
+  for b=8: byte v); groups are concatenated in g order;
+* codebooks: cb[g, j, t] fp16, contiguous, same g order.
+
+Parity pins (tests/test_oracle_*.py): hand-written tiny cases stored under
+tests/golden/, a coordinate-revealing codebook, one-centroid and
+identity-like codebooks, relabelling invariance, the bpv closed form,
+unit-vector probes and a per-element scalar walk.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+import numpy as np
+
+
+@dataclass(frozen=True)
+class VQFormat:
+    """Shape of one vector-quantised matrix W[out_features, in_features]."""
+    out_features: int
+    in_features: int
+    k: int
+    index_bits: int
+    group_rows: int = 8
+    group_cols: int = 256
+    d: int = 2
+
+    def __post_init__(self):
+        if self.out_features % self.group_rows or self.in_features % self.group_cols:
+            raise ValueError("matrix shape must be a multiple of the group shape")
+        if self.group_cols % self.d:
+            raise ValueError("group_cols must be a multiple of d")
+        if self.k > (1 << self.index_bits):
+            raise ValueError("index_bits too small for k")
+        if (self.vectors_per_group * self.index_bits) % 8:
+            raise ValueError("a group's index stream must end on a byte boundary")
+
+    @property
+    def groups_per_row(self) -> int:
+        return self.in_features // self.group_cols
+
+    @property
+    def n_groups(self) -> int:
+        return (self.out_features // self.group_rows) * self.groups_per_row
+
+    @property
+    def vectors_per_row(self) -> int:
+        """Vectors of one row inside one group."""
+        return self.group_cols // self.d
+
+    @property
+    def vectors_per_group(self) -> int:
+        return self.group_rows * self.vectors_per_row
+
+    @property
+    def group_index_bytes(self) -> int:
+        return self.vectors_per_group * self.index_bits // 8
+
+
+def canonical_sizes(f: VQFormat) -> tuple[int, int]:
+    """(bytes of packed indices, bytes of fp16 codebooks) for the whole matrix."""
+    return f.n_groups * f.group_index_bytes, f.n_groups * f.k * f.d * 2
+
+
+def bits_per_value(k: int, d: int, codebook_bits: int, group_size: int) -> float:
+    """Sec. 4, Total bits per value: log2(k)/d + k*d*b_c/l."""
+    return float(np.log2(k)) / d + k * d * codebook_bits / group_size
+
+
+def unpack_indices(f: VQFormat, idx: np.ndarray) -> np.ndarray:
+    """Packed index bytes -> int64[n_groups, vectors_per_group].
+
+    Each group's bytes are expanded to a little-endian bit stream and cut into
+    consecutive fields of ``index_bits`` bits (Sec. 2.1: one index of
+    ceil(log2 k) bits per vector; Sec. 3.2: packed tightly).
+    """
+    idx = np.ascontiguousarray(idx, dtype=np.uint8)
+    if idx.size != f.n_groups * f.group_index_bytes:
+        raise ValueError("index buffer has the wrong size")
+    per_group = idx.reshape(f.n_groups, f.group_index_bytes)
+    bits = np.unpackbits(per_group, axis=1, bitorder="little")
+    fields = bits.reshape(f.n_groups, f.vectors_per_group, f.index_bits).astype(np.int64)
+    weights = (1 << np.arange(f.index_bits, dtype=np.int64))
+    out = fields @ weights
+    if out.size and out.max() >= f.k:
+        raise ValueError("index out of range for this codebook")
+    return out
+
+
+def decode_dense(f: VQFormat, idx: np.ndarray, cb: np.ndarray) -> np.ndarray:
+    """Rebuild dense W as raw fp16 bit patterns, uint16[out, in] (Sec. 3.2 decode).
+
+    W[r, c + t] = cb[g, I_g[v], t] with g, v as in the module header.  Pure
+    copying of 16-bit patterns: subnormals, -0 and NaN payloads survive.
+    """
+    cb_bits = np.ascontiguousarray(cb).view(np.uint16).reshape(f.n_groups, f.k, f.d)
+    I = unpack_indices(f, idx)                                  # [g, v]
+    vecs = cb_bits[np.arange(f.n_groups)[:, None], I]           # [g, v, d]
+    n_rb, n_cb = f.out_features // f.group_rows, f.groups_per_row
+    # [row-block, col-block, row in group, vector in row, t] -> [row-block, row, col-block, vector, t]
+    vecs = vecs.reshape(n_rb, n_cb, f.group_rows, f.vectors_per_row, f.d)
+    W = vecs.transpose(0, 2, 1, 3, 4).reshape(f.out_features, f.in_features)
+    return np.ascontiguousarray(W)
+
+
+def decode_element(f: VQFormat, idx: np.ndarray, cb: np.ndarray, r: int, c: int) -> int:
+    """One element of W (raw fp16 bits) by walking the definition with scalars.
+
+    Used for sampled checks at sizes where a full decode is too slow elsewhere.
+    """
+    g = (r // f.group_rows) * f.groups_per_row + (c // f.group_cols)
+    v = (r % f.group_rows) * f.vectors_per_row + (c % f.group_cols) // f.d
+    t = (c % f.group_cols) % f.d
+    base = g * f.group_index_bytes
+    j = 0
+    for b in range(f.index_bits):
+        bit = v * f.index_bits + b
+        byte = int(idx[base + bit // 8])
+        j |= ((byte >> (bit % 8)) & 1) << b
+    cb_bits = np.ascontiguousarray(cb).view(np.uint16).reshape(f.n_groups, f.k, f.d)
+    return int(cb_bits[g, j, t])
+
+
+def gemv(f: VQFormat, idx: np.ndarray, cb: np.ndarray, x: np.ndarray) -> np.ndarray:
+    """y = W x in fp64, W decoded as above (fp16 -> fp64 widening is exact)."""
+    W = decode_dense(f, idx, cb).view(np.float16).astype(np.float64)
+    x64 = np.asarray(x, dtype=np.float16).astype(np.float64)
+    if x64.shape != (f.in_features,):
+        raise ValueError("x has the wrong shape")
+    return W @ x64
+
+
+def gemm(f: VQFormat, idx: np.ndarray, cb: np.ndarray, X: np.ndarray) -> np.ndarray:
+    """Y[out, B] = W X[in, B] in fp64."""
+    W = decode_dense(f, idx, cb).view(np.float16).astype(np.float64)
+    X64 = np.asarray(X, dtype=np.float16).astype(np.float64)
+    if X64.ndim != 2 or X64.shape[0] != f.in_features:
+        raise ValueError("X has the wrong shape")
+    return W @ X64
+
+
+def normwise_rel_err(y, y_ref) -> float:
+    """||y - y_ref||_2 / ||y_ref||_2 (Frobenius for matrices), computed in fp64."""
+    y = np.asarray(y, dtype=np.float64).ravel()
+    y_ref = np.asarray(y_ref, dtype=np.float64).ravel()
+    den = float(np.linalg.norm(y_ref))
+    num = float(np.linalg.norm(y - y_ref))
+    return num / den if den > 0 else (0.0 if num == 0 else float("inf"))

@@ -1,0 +1,278 @@
+"""Pins for the CPU oracle: values and identities fixed by the paper and by
+arithmetic, none of them computed by the oracle itself.
+
+Each test names the mistake it is meant to catch.
+"""
+import math
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+import oracle
+from oracle import VQFormat
+import workloads
+from golden_io import read_case, read_bpv_table
+
+GOLDEN_CASES = ["decode_2x4_k4_b2.txt", "decode_1x8_k16_b4.txt", "decode_1x16_k8_b3.txt"]
+
+
+def _fmt(case):
+    f = case["format"]
+    return VQFormat(f["out"], f["in"], f["k"], f["index_bits"], f["group_rows"], f["group_cols"], f["d"])
+
+
+# ---------------------------------------------------------------- hand-worked values
+@pytest.mark.parametrize("name", GOLDEN_CASES)
+def test_golden_decode(name):
+    """Wrong group order, vector order, nibble/bit order or (j,t) transposition fails here."""
+    case = read_case(name)
+    f = _fmt(case)
+    cb = case["codebook"].astype(np.float16)
+    W = oracle.decode_dense(f, case["idx"], cb).view(np.float16).astype(np.float64)
+    np.testing.assert_array_equal(W, case["W"])
+
+
+@pytest.mark.parametrize("name", GOLDEN_CASES)
+def test_golden_gemv_and_gemm(name):
+    """Transposed operand / dropped column fails here (values are exact in fp64)."""
+    case = read_case(name)
+    f = _fmt(case)
+    cb = case["codebook"].astype(np.float16)
+    y = oracle.gemv(f, case["idx"], cb, case["x"].astype(np.float16))
+    np.testing.assert_array_equal(y, case["y"])
+    X = np.stack([case["x"], 2 * case["x"], -case["x"]], axis=1).astype(np.float16)
+    Y = oracle.gemm(f, case["idx"], cb, X)
+    np.testing.assert_array_equal(Y, np.stack([case["y"], 2 * case["y"], -case["y"]], axis=1))
+
+
+@pytest.mark.parametrize("name", GOLDEN_CASES)
+def test_golden_decode_element(name):
+    case = read_case(name)
+    f = _fmt(case)
+    cb = case["codebook"].astype(np.float16)
+    for r in range(f.out_features):
+        for c in range(f.in_features):
+            bits = oracle.decode_element(f, case["idx"], cb, r, c)
+            assert np.array([bits], dtype=np.uint16).view(np.float16)[0] == case["W"][r, c]
+
+
+# ---------------------------------------------------------------- closed forms
+def test_bpv_paper_rows():
+    """Sec. 4 formula against the bits-per-value the paper prints."""
+    for bpv, d, k, l, bc in read_bpv_table():
+        assert oracle.bits_per_value(k, d, bc, l) == pytest.approx(bpv, abs=1e-12), (bpv, d, k, l)
+
+
+@pytest.mark.parametrize("key,bpv", [
+    ("tiny_256x256_k16", 2.25), ("attn_4096x4096_k16", 2.25),
+    ("mlp_up_11008x4096_k256", 8.0), ("mlp_down_4096x11008_k256", 8.0),
+    ("mlp_up_11008x4096_k16", 2.25), ("mlp_down_4096x11008_k16", 2.25),
+])
+def test_buffer_sizes_reproduce_bpv(key, bpv):
+    """Stored bytes*8/weights must equal the closed form with fp16 centroids (b_c = 16)."""
+    s = workloads.CONFIGS[key]
+    f = VQFormat(s.out_features, s.in_features, s.k, s.index_bits, s.group_rows, s.group_cols, s.d)
+    ib, cb = oracle.canonical_sizes(f)
+    assert (ib, cb) == workloads.canonical_sizes(s)
+    assert (ib + cb) * 8 / (s.out_features * s.in_features) == bpv
+    assert oracle.bits_per_value(s.k, s.d, 16, s.group_rows * s.group_cols) == bpv
+
+
+def test_algorithmic_bytes_of_the_configs():
+    """Byte counts used for the roofline (indices + codebooks + x + y as fp16)."""
+    def total(key):
+        s = workloads.CONFIGS[key]
+        ib, cb = workloads.canonical_sizes(s)
+        return ib + cb + 2 * s.in_features + 2 * s.out_features
+    assert total("tiny_256x256_k16") == 19456
+    assert total("attn_4096x4096_k16") == 4734976
+    assert total("mlp_up_11008x4096_k256") == 45118976
+    assert total("mlp_down_4096x11008_k256") == 45118976
+    per_layer = sum(total(k) for _, k in workloads.LLAMA7B_LAYER)
+    assert per_layer == 57074176
+    assert per_layer * workloads.LLAMA7B_N_LAYERS == 1826373632
+    assert len(workloads.llama7b_pass_shapes()) == 224
+
+
+def test_fp16_widening_is_the_ieee_value():
+    """fp16 -> fp64 spot values from the binary16 definition (sign, 5-bit exponent bias 15, 10-bit fraction)."""
+    bits = np.array([0x3C00, 0xC000, 0x7BFF, 0x0001, 0x0400, 0x8000, 0x3555], dtype=np.uint16)
+    want = [1.0, -2.0, 65504.0, 2.0 ** -24, 2.0 ** -14, -0.0, (1 + 0x155 / 1024) * 2.0 ** -2]
+    got = bits.view(np.float16).astype(np.float64)
+    assert list(got) == want
+    assert math.copysign(1.0, got[5]) == -1.0
+
+
+# ---------------------------------------------------------------- structural invariants
+def _bit_pack(indices, bits):
+    """Test-local packer (little-endian bit stream), scalar Python on purpose."""
+    total = len(indices) * bits
+    assert total % 8 == 0
+    out = bytearray(total // 8)
+    for v, j in enumerate(indices):
+        for b in range(bits):
+            if (int(j) >> b) & 1:
+                pos = v * bits + b
+                out[pos // 8] |= 1 << (pos % 8)
+    return np.frombuffer(bytes(out), dtype=np.uint8)
+
+
+SMALL_FORMATS = [
+    VQFormat(16, 512, 16, 4),            # 2 x 2 groups of 8 x 256
+    VQFormat(8, 768, 256, 8),            # 1 x 3 groups
+    VQFormat(6, 24, 64, 6, 2, 12, 2),    # 6-bit indices, 3 x 2 groups of 2 x 12
+    VQFormat(4, 16, 4, 2, 4, 8, 4),      # d = 4
+    VQFormat(3, 8, 8, 3, 1, 8, 1),       # d = 1
+]
+
+
+@pytest.mark.parametrize("f", SMALL_FORMATS, ids=str)
+def test_coordinate_revealing_codebook(f):
+    """Centroid (g, j) stores values that spell out g, j and t, so each decoded element
+    names the group, index and lane that produced it; the expected triple is
+    recomputed here element by element with divmod."""
+    rng = np.random.default_rng(7)
+    per_group = [rng.integers(0, f.k, size=f.vectors_per_group) for _ in range(f.n_groups)]
+    idx = np.concatenate([_bit_pack(p, f.index_bits) for p in per_group])
+    # value = g*k*d + j*d + t  (all < 2048 for these formats, exact in fp16)
+    cb = np.arange(f.n_groups * f.k * f.d, dtype=np.float64).reshape(f.n_groups, f.k, f.d)
+    assert cb.max() < 2048
+    W = oracle.decode_dense(f, idx, cb.astype(np.float16)).view(np.float16).astype(np.int64)
+    for r in range(f.out_features):
+        rb, lr = divmod(r, f.group_rows)
+        for c in range(f.in_features):
+            cblk, lc = divmod(c, f.group_cols)
+            vec, t = divmod(lc, f.d)
+            g = rb * (f.in_features // f.group_cols) + cblk
+            j = per_group[g][lr * (f.group_cols // f.d) + vec]
+            assert W[r, c] == (g * f.k + j) * f.d + t, (r, c)
+
+
+@pytest.mark.parametrize("f", SMALL_FORMATS, ids=str)
+def test_one_centroid_codebook_gives_constant_rows(f):
+    """All k entries equal => W is the centroid tiled, whatever the indices; and
+    y[r] = sum_t a_t * (sum of x over columns congruent to t mod d)."""
+    rng = np.random.default_rng(11)
+    nb = oracle.canonical_sizes(f)[0]
+    if f.k == 1 << f.index_bits:
+        idx = rng.integers(0, 256, size=nb, dtype=np.uint8)
+    else:
+        idx = np.zeros(nb, dtype=np.uint8)
+    a = np.array([0.375, -1.25, 2.5, -0.0625][: f.d])
+    cb = np.broadcast_to(a, (f.n_groups, f.k, f.d)).astype(np.float16)
+    W = oracle.decode_dense(f, idx, cb).view(np.float16).astype(np.float64)
+    np.testing.assert_array_equal(W, np.tile(a, (f.out_features, f.in_features // f.d)))
+    x = rng.integers(-8, 9, size=f.in_features).astype(np.float16)
+    y = oracle.gemv(f, idx, cb, x)
+    want = sum(a[t] * x[t::f.d].astype(np.float64).sum() for t in range(f.d))
+    np.testing.assert_array_equal(y, np.full(f.out_features, want))
+
+
+@pytest.mark.parametrize("f", SMALL_FORMATS, ids=str)
+def test_identity_like_codebook_reconstructs_exactly(f):
+    """Build W whose d-vectors take at most k distinct values per group, encode it with
+    a test-local encoder, and require decode == W bit for bit."""
+    rng = np.random.default_rng(13)
+    n_cb = f.in_features // f.group_cols
+    W = np.zeros((f.out_features, f.in_features), dtype=np.float16)
+    cb = np.zeros((f.n_groups, f.k, f.d), dtype=np.float16)
+    chunks = []
+    for g in range(f.n_groups):
+        rb, cblk = divmod(g, n_cb)
+        palette = rng.standard_normal((f.k, f.d)).astype(np.float16)
+        cb[g] = palette
+        choice = rng.integers(0, f.k, size=(f.group_rows, f.group_cols // f.d))
+        tile = palette[choice].reshape(f.group_rows, f.group_cols)
+        W[rb * f.group_rows:(rb + 1) * f.group_rows, cblk * f.group_cols:(cblk + 1) * f.group_cols] = tile
+        chunks.append(_bit_pack(choice.ravel(), f.index_bits))
+    idx = np.concatenate(chunks)
+    got = oracle.decode_dense(f, idx, cb)
+    np.testing.assert_array_equal(got, W.view(np.uint16))
+    # and the matvec is the dense matvec of that W (brute force with exact rationals)
+    x = rng.integers(-4, 5, size=f.in_features).astype(np.float16)
+    y = oracle.gemv(f, idx, cb, x)
+    for r in range(f.out_features):
+        exact = sum(Fraction(float(W[r, c])) * Fraction(float(x[c])) for c in range(f.in_features))
+        assert abs(Fraction(float(y[r])) - exact) <= abs(exact) * Fraction(1, 10 ** 12) + Fraction(1, 10 ** 15)
+
+
+def test_relabelling_a_codebook_does_not_change_W():
+    """Permute each codebook and remap its indices: the decoded matrix must not move."""
+    f = VQFormat(16, 512, 256, 8)
+    rng = np.random.default_rng(17)
+    idx = rng.integers(0, 256, size=oracle.canonical_sizes(f)[0], dtype=np.uint8)
+    cb = rng.standard_normal((f.n_groups, f.k, f.d)).astype(np.float16)
+    W0 = oracle.decode_dense(f, idx, cb)
+    idx2 = idx.copy().reshape(f.n_groups, -1)
+    cb2 = cb.copy()
+    for g in range(f.n_groups):
+        perm = rng.permutation(f.k)          # new position of old entry j is perm[j]
+        cb2[g, perm] = cb[g]
+        idx2[g] = perm[idx2[g]].astype(np.uint8)
+    np.testing.assert_array_equal(oracle.decode_dense(f, idx2.ravel(), cb2), W0)
+
+
+def test_unit_vectors_pick_out_columns():
+    """x = e_c must return column c of the decoded matrix (catches W^T x and index slips)."""
+    s = workloads.CONFIGS["tiny_256x256_k16"]
+    f = VQFormat(s.out_features, s.in_features, s.k, s.index_bits)
+    idx, cb = workloads.make_weights(s, 3)
+    W = oracle.decode_dense(f, idx, cb).view(np.float16).astype(np.float64)
+    for c in (0, 1, 2, 127, 128, 255):
+        e = np.zeros(f.in_features, dtype=np.float16)
+        e[c] = 1
+        np.testing.assert_array_equal(oracle.gemv(f, idx, cb, e), W[:, c])
+
+
+def test_gemv_matches_scalar_walk_with_fsum():
+    """Every y[r] against math.fsum over decode_element (different code path, exact summation)."""
+    s = workloads.CONFIGS["tiny_256x256_k16"]
+    f = VQFormat(s.out_features, s.in_features, s.k, s.index_bits)
+    idx, cb = workloads.make_weights(s, 5)
+    x = workloads.make_x(s.in_features, 5)
+    y = oracle.gemv(f, idx, cb, x)
+    x64 = x.astype(np.float64)
+    for r in (0, 7, 8, 100, 255):
+        row = [np.array([oracle.decode_element(f, idx, cb, r, c)], dtype=np.uint16).view(np.float16)[0]
+               for c in range(f.in_features)]
+        exact = math.fsum(float(w) * float(xc) for w, xc in zip(row, x64))
+        assert y[r] == pytest.approx(exact, rel=1e-12, abs=1e-15)
+
+
+def test_gemm_columns_are_gemvs():
+    f = VQFormat(16, 512, 256, 8)
+    rng = np.random.default_rng(19)
+    idx = rng.integers(0, 256, size=oracle.canonical_sizes(f)[0], dtype=np.uint8)
+    cb = (0.02 * rng.standard_normal((f.n_groups, f.k, f.d))).astype(np.float16)
+    X = workloads.make_X(f.in_features, 5, 1)
+    Y = oracle.gemm(f, idx, cb, X)
+    for b in range(5):
+        np.testing.assert_allclose(Y[:, b], oracle.gemv(f, idx, cb, X[:, b]), rtol=1e-13, atol=1e-16)
+
+
+def test_planted_mistakes_are_caught_by_the_goldens():
+    """Sanity of the pins themselves: plausible wrong readings disagree with the fixtures."""
+    case = read_case("decode_1x8_k16_b4.txt")
+    f = _fmt(case)
+    swapped = ((case["idx"] << 4) | (case["idx"] >> 4)).astype(np.uint8)   # high nibble first
+    W = oracle.decode_dense(f, swapped, case["codebook"].astype(np.float16)).view(np.float16)
+    assert not np.array_equal(W.astype(np.float64), case["W"])
+    case = read_case("decode_2x4_k4_b2.txt")
+    f = _fmt(case)
+    cb_t = case["codebook"].astype(np.float16)[:, :, ::-1].copy()           # (t) order flipped
+    W = oracle.decode_dense(f, case["idx"], cb_t).view(np.float16)
+    assert not np.array_equal(W.astype(np.float64), case["W"])
+
+
+def test_bad_inputs_raise():
+    with pytest.raises(ValueError):
+        VQFormat(10, 256, 16, 4)
+    with pytest.raises(ValueError):
+        VQFormat(8, 256, 32, 4)
+    f = VQFormat(8, 256, 16, 4)
+    with pytest.raises(ValueError):
+        oracle.unpack_indices(f, np.zeros(3, dtype=np.uint8))
+    f3 = VQFormat(1, 16, 5, 3, 1, 16, 2)
+    with pytest.raises(ValueError):
+        oracle.unpack_indices(f3, np.full(3, 0xFF, dtype=np.uint8))
