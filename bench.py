@@ -1,0 +1,269 @@
+#!/usr/bin/env python3
+"""Benchmark of the VQ GEMV hot path on one MI355X.
+
+A "step" is one per-token weight pass of a synthetic Llama-7B decoder: 32 layers x
+{q,k,v,o 4096x4096; gate,up 11008x4096; down 4096x11008}, 2-D VQ, k=16, 8x256 groups,
+224 batch-1 products y = W x over 1.83 GB of distinct packed weights (so the pass is
+HBM-cold by construction).  The pass is issued through vq_gemv_multi (the whole pass
+in a handful of launches).  The JSON line also carries per-shape us/call of single
+vq_gemv calls (HBM-cold rotation and cache-resident), the k=256 MLP shapes, the
+batched GEMM, the roofline of the dominant kernel and the CPU oracle timed on the
+host cores.
+
+Contract: python bench.py --gpus 1 --steps K --warmup W  -> one JSON line on stdout.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+MFMA_F16_PEAK_TFLOPS = 2500.0  # MI355X published dense fp16 matrix peak
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def algorithmic_bytes(s) -> int:
+    """indices + codebooks + x + y(fp16), each counted once."""
+    import workloads
+    ib, cb = workloads.canonical_sizes(s)
+    return ib + cb + 2 * s.in_features + 2 * s.out_features
+
+
+class Timer:
+    """HIP-event timing on torch's current stream (the stream the kernels are launched on)."""
+
+    def __init__(self, torch):
+        self.torch = torch
+
+    def run(self, fn, iters, warmup):
+        t = self.torch
+        for _ in range(warmup):
+            fn()
+        t.cuda.synchronize()
+        e0, e1 = t.cuda.Event(enable_timing=True), t.cuda.Event(enable_timing=True)
+        wall0 = time.perf_counter()
+        e0.record()
+        for _ in range(iters):
+            fn()
+        e1.record()
+        t.cuda.synchronize()
+        wall = time.perf_counter() - wall0
+        return e0.elapsed_time(e1) / iters, wall * 1e3 / iters   # ms per iteration (device, wall)
+
+
+def build_pass(torch, vq, vqdev, n_layers):
+    """Device-resident weights of the 7B pass: list of (name, shape, desc, idx_d, cb_d)."""
+    import workloads
+    mats = []
+    t0 = time.time()
+    for (layer, name, s, seed) in workloads.llama7b_pass_shapes():
+        if layer >= n_layers:
+            break
+        idx, cb = workloads.make_weights(s, seed)
+        desc = vqdev.desc_from_shape(s)
+        idx_d, cb_d = vqdev.upload_and_pack(desc, idx, cb)
+        mats.append((f"L{layer}.{name}", s, desc, idx_d, cb_d))
+    log(f"[bench] built {len(mats)} matrices in {time.time() - t0:.1f}s")
+    return mats
+
+
+def time_cpu_baseline(budget_s=20.0):
+    """The CPU oracle (decode -> dense fp16 W -> fp64 y = W x) timed on the host cores, on a
+    bounded sample of the same workload: whole matrices of layer 0 of the pass, in order,
+    until the time budget is used.  Input generation is not timed."""
+    import oracle
+    import workloads
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = 1
+    done_bytes, spent, names = 0, 0.0, []
+    for (layer, name, s, seed) in workloads.llama7b_pass_shapes():
+        if layer > 0 or spent >= budget_s:
+            break
+        idx, cb = workloads.make_weights(s, seed)
+        x = workloads.make_x(s.in_features, seed)
+        f = oracle.VQFormat(s.out_features, s.in_features, s.k, s.index_bits)
+        t1 = time.perf_counter()
+        oracle.gemv(f, idx, cb, x)
+        spent += time.perf_counter() - t1
+        done_bytes += algorithmic_bytes(s)
+        names.append(name)
+    return {
+        "value": done_bytes / spent / 1e9, "unit": "GB/s", "cores": threads, "kind": "oracle",
+        "sample": f"layer 0 of the pass: {'+'.join(names)} ({done_bytes} algorithmic bytes in "
+                  f"{spent:.2f} s of oracle time, {os.cpu_count()} host cpus visible)",
+        "seconds": spent,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--layers", type=int, default=32, help="layers of the 7B pass (32 = the workload)")
+    ap.add_argument("--no-extras", action="store_true", help="skip per-shape / GEMM side measurements")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--cpu-budget", type=float, default=15.0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import workloads
+    import paper_2402_15319_amd as vq
+    from paper_2402_15319_amd import device as vqdev
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    vq.lib()
+    torch.cuda.set_device(0)
+    timer = Timer(torch)
+    dev = "cuda:0"
+
+    # ------------------------------------------------------------------ the pass
+    mats = build_pass(torch, vq, vqdev, args.layers)
+    xs = {n: torch.randn(n, device=dev, dtype=torch.float32, generator=torch.Generator(dev).manual_seed(1)).half()
+          for n in (4096, 11008)}
+    ys = [torch.empty(s.out_features, dtype=torch.float16, device=dev) for (_, s, _, _, _) in mats]
+    margs = vq.GemvMultiArgs([m[2] for m in mats], [m[3] for m in mats], [m[4] for m in mats],
+                             [xs[m[1].in_features] for m in mats], ys)
+    pass_bytes = sum(algorithmic_bytes(m[1]) for m in mats)
+    n_launch = (len(mats) + 63) // 64
+
+    def step_multi():
+        vq.vq_gemv_multi(margs)
+
+    ms_multi, wall_multi = timer.run(step_multi, args.steps, args.warmup)
+    log(f"[bench] pass via vq_gemv_multi: {ms_multi * 1e3:.1f} us/step, {pass_bytes / ms_multi / 1e6:.0f} GB/s")
+
+    extras = {}
+    if not args.no_extras:
+        # the same pass as 224 separate vq_gemv calls (plain stream launches)
+        def step_single():
+            for i, (_, s, desc, idx_d, cb_d) in enumerate(mats):
+                vq.vq_gemv(desc, idx_d, cb_d, xs[s.in_features], ys[i])
+        ms_single, wall_single = timer.run(step_single, max(2, args.steps // 4), 1)
+        extras["pass_as_separate_vq_gemv_calls"] = {
+            "us_per_pass": ms_single * 1e3, "GB/s": pass_bytes / ms_single / 1e6,
+            "us_per_call": ms_single * 1e3 / len(mats), "wall_us_per_pass": wall_single * 1e3}
+        log(f"[bench] pass via {len(mats)} vq_gemv calls: {ms_single * 1e3:.1f} us/step")
+
+        # per-shape us/call: HBM-cold (rotate over the distinct matrices of the pass) and
+        # cache-resident (same matrix every call)
+        per_shape = {}
+        for key in ("attn_4096x4096_k16", "mlp_up_11008x4096_k16", "mlp_down_4096x11008_k16"):
+            s0 = workloads.CONFIGS[key]
+            sel = [i for i, m in enumerate(mats) if m[1] == s0]
+            if not sel:
+                continue
+            state = {"i": 0}
+
+            def cold():
+                i = sel[state["i"] % len(sel)]
+                state["i"] += 1
+                m = mats[i]
+                vq.vq_gemv(m[2], m[3], m[4], xs[s0.in_features], ys[i])
+
+            def hot():
+                m = mats[sel[0]]
+                vq.vq_gemv(m[2], m[3], m[4], xs[s0.in_features], ys[sel[0]])
+            nb = algorithmic_bytes(s0)
+            ms_c, _ = timer.run(cold, 4 * len(sel), len(sel))
+            ms_h, _ = timer.run(hot, 500, 20)
+            per_shape[key] = {"bytes": nb, "distinct_copies": len(sel),
+                              "cold_us": ms_c * 1e3, "cold_GB/s": nb / ms_c / 1e6,
+                              "cold_frac_hbm": nb / ms_c / 1e6 / HBM_PEAK_GBS,
+                              "hot_us": ms_h * 1e3, "hot_GB/s": nb / ms_h / 1e6}
+            log(f"[bench] {key}: cold {ms_c * 1e3:.2f} us, hot {ms_h * 1e3:.2f} us")
+
+        # k = 256 MLP shapes (8 bits per weight): 12 distinct copies each (> 512 MB in total)
+        for key in ("mlp_up_11008x4096_k256", "mlp_down_4096x11008_k256"):
+            s0 = workloads.CONFIGS[key]
+            desc = vqdev.desc_from_shape(s0)
+            copies = []
+            for j in range(12):
+                idx, cb = workloads.make_weights(s0, workloads.seed_for(key, j))
+                copies.append(vqdev.upload_and_pack(desc, idx, cb))
+            y = torch.empty(s0.out_features, dtype=torch.float16, device=dev)
+            state = {"i": 0}
+
+            def cold():
+                a, b = copies[state["i"] % len(copies)]
+                state["i"] += 1
+                vq.vq_gemv(desc, a, b, xs[s0.in_features], y)
+
+            def hot():
+                vq.vq_gemv(desc, copies[0][0], copies[0][1], xs[s0.in_features], y)
+            nb = algorithmic_bytes(s0)
+            ms_c, _ = timer.run(cold, 120, 12)
+            ms_h, _ = timer.run(hot, 200, 10)
+            per_shape[key] = {"bytes": nb, "distinct_copies": len(copies),
+                              "cold_us": ms_c * 1e3, "cold_GB/s": nb / ms_c / 1e6,
+                              "cold_frac_hbm": nb / ms_c / 1e6 / HBM_PEAK_GBS,
+                              "hot_us": ms_h * 1e3, "hot_GB/s": nb / ms_h / 1e6}
+            log(f"[bench] {key}: cold {ms_c * 1e3:.2f} us, hot {ms_h * 1e3:.2f} us")
+            if key == "mlp_up_11008x4096_k256":
+                # batched / prefill GEMM on the same matrix, next to a dense fp16 GEMM on decoded W
+                Wd = torch.empty((s0.out_features, s0.in_features), dtype=torch.float16, device=dev)
+                vq.vq_decode_dense(desc, copies[0][0], copies[0][1], Wd)
+                gemm = {}
+                for B in (16, 256, 2048):
+                    X = torch.randn((s0.in_features, B), device=dev, dtype=torch.float32).half()
+                    Y = torch.empty((s0.out_features, B), dtype=torch.float16, device=dev)
+                    ms_g, _ = timer.run(lambda: vq.vq_gemm_batched(desc, copies[0][0], copies[0][1], X, B, B, Y, B),
+                                        10, 2)
+                    ms_d, _ = timer.run(lambda: torch.matmul(Wd, X, out=Y), 10, 2)
+                    fl = 2.0 * s0.out_features * s0.in_features * B
+                    gemm[f"B{B}"] = {"us": ms_g * 1e3, "TFLOP/s": fl / ms_g / 1e9,
+                                     "frac_mfma_f16": fl / ms_g / 1e9 / MFMA_F16_PEAK_TFLOPS,
+                                     "dense_fp16_matmul_us": ms_d * 1e3}
+                    log(f"[bench] gemm B={B}: {ms_g * 1e3:.1f} us vs dense {ms_d * 1e3:.1f} us")
+                extras["gemm_11008x4096_k256"] = gemm
+                del Wd
+            del copies
+        extras["per_shape_vq_gemv"] = per_shape
+
+    cpu = None if args.no_cpu else time_cpu_baseline(args.cpu_budget)
+
+    gbs = pass_bytes / ms_multi / 1e6
+    kernel_us = ms_multi * 1e3 / n_launch
+    out = {
+        "metric": "VQ GEMV effective HBM GB/s on the compressed stream (us per call alongside), "
+                  "Llama-7B shapes, batch 1",
+        "value": gbs, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_multi, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f16 (fp32 accumulate)", "data": "synthetic",
+        "config": {"workload": f"llama7b_full_weight_pass_k16 ({len(mats)} GEMVs, {args.layers} layers, "
+                               f"d=2, 8x256 groups, 2.25 bpv) via vq_gemv_multi",
+                   "bytes_per_step": pass_bytes, "launches_per_step": n_launch,
+                   "us_per_call": ms_multi * 1e3 / len(mats),
+                   "tokens_per_s_weight_stream": 1e3 / ms_multi},
+        "roofline": {"bound": "hbm", "achieved": pass_bytes / n_launch / kernel_us / 1e3,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": pass_bytes / n_launch / kernel_us / 1e3 / HBM_PEAK_GBS,
+                     "traffic": None, "kernel": "gemv_kernel<16>",
+                     "kernel_avg_us": kernel_us, "bytes_per_launch": pass_bytes / n_launch},
+        "cpu_baseline": cpu,
+        "extras": extras,
+    }
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

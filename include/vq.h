@@ -1,0 +1,142 @@
+/*
+ * vq.h -- C ABI of the MI355X (gfx950) vector-quantised matrix-vector library.
+ *
+ * The library implements the decode-time hot path of GPTVQ (arXiv 2402.15319):
+ * y = W x where W[out,in] is never stored densely.  W is tiled into groups of
+ * group_rows x group_cols weights (Sec. 4: "8 rows by 256 columns"); each group
+ * owns a codebook of k centroids of d fp16 values (Sec. 2.1) and stores one
+ * index of index_bits = log2(k) bits for every run of d consecutive columns of
+ * a row (Sec. 4: d columns are quantised at a time).  At inference a group is
+ * decoded by table lookup to the native type and used in the matrix-vector
+ * product (Sec. 3.2).
+ *
+ * Conventions common to every entry point
+ *   - plain C, no C++/torch types; every pointer is a DEVICE pointer unless a
+ *     comment says "host";
+ *   - the caller owns all buffers; the library allocates nothing and keeps no
+ *     state between calls;
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream); calls
+ *     enqueue work and return without synchronising;
+ *   - return value: VQ_OK (0) or a negative vq_status.  Arguments are validated
+ *     on the host before anything is launched, so every error except VQ_ERR_HIP
+ *     can be provoked without a GPU.  No exception crosses the boundary.
+ *
+ * Canonical (interchange) format, used only as the input of vq_pack_layout
+ *   - groups are numbered row-block-major: g = (r / group_rows) * (in / group_cols) + c / group_cols;
+ *   - inside a group vectors are row-major: v = (r % group_rows) * (group_cols / d) + (c % group_cols) / d;
+ *   - indices: group g owns bytes [g*GB, (g+1)*GB), GB = group_rows*group_cols/d*index_bits/8,
+ *     read as a little-endian bit stream: vector v is bits [v*index_bits, (v+1)*index_bits)
+ *     (4-bit: even v in the low nibble; 8-bit: byte v);
+ *   - codebooks: fp16 cb[g][j][t], j < k, t < d, contiguous, same g order.
+ * The device layout written by vq_pack_layout is private to the library.
+ */
+#ifndef VQ_H_
+#define VQ_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define VQ_API __attribute__((visibility("default")))
+
+typedef enum vq_status {
+  VQ_OK = 0,
+  VQ_ERR_NULL = -1,        /* a required pointer is NULL                                  */
+  VQ_ERR_BAD_DESC = -2,    /* descriptor is inconsistent (non-positive size, k != 2^bits) */
+  VQ_ERR_UNSUPPORTED = -3, /* consistent but not implemented (shape not a multiple of the
+                              group, d != 2, group != 8x256, k not in {16,256}, dtype)    */
+  VQ_ERR_ALIGN = -4,       /* a device pointer is not 16-byte aligned / bad leading dim   */
+  VQ_ERR_HIP = -5,         /* the HIP runtime refused the launch (see hipGetLastError)    */
+  VQ_ERR_BAD_ARG = -6      /* a scalar argument is out of range (batch, count, dtype)     */
+} vq_status;
+
+typedef enum vq_dtype { VQ_F16 = 1, VQ_F32 = 2 } vq_dtype;
+
+/* Shape of one vector-quantised matrix (Sec. 2.1, Sec. 3.1, Sec. 4). */
+typedef struct vq_desc {
+  int32_t out_features;   /* rows of W (length of y)                                */
+  int32_t in_features;    /* columns of W (length of x)                             */
+  int32_t group_rows;     /* 8                                                      */
+  int32_t group_cols;     /* 256 (Sec. 4: at most 256 columns per group)            */
+  int32_t d;              /* VQ dimensionality, 2                                   */
+  int32_t k;              /* centroids per codebook, 16 or 256                      */
+  int32_t index_bits;     /* log2(k): 4 or 8                                        */
+  int32_t codebook_dtype; /* VQ_F16                                                 */
+} vq_desc;
+
+/* Human-readable name of a status code (host pointer to a static string). */
+VQ_API const char* vq_status_string(int status);
+
+/* Library ABI version (increments when a signature or the device layout changes). */
+VQ_API int vq_version(void);
+
+/*
+ * Sizes in bytes of the canonical arrays and of the device-layout arrays for
+ * `desc` (host pointers; any output pointer may be NULL).  By Sec. 4's
+ * bits-per-value formula (idx + cb) * 8 / (out*in) = log2(k)/d + k*d*16/(rows*cols);
+ * the device layout adds no padding, so both pairs are equal.
+ */
+VQ_API int vq_canonical_bytes(const vq_desc* desc, size_t* idx_bytes, size_t* cb_bytes);
+VQ_API int vq_layout_bytes(const vq_desc* desc, size_t* idx_bytes, size_t* cb_bytes);
+
+/*
+ * One-time re-layout (off the hot path): canonical indices/codebooks ->
+ * device layout (Sec. 3.2: indices and tables are "organized to enable
+ * efficient vectorization").  All four buffers are device memory, 16-byte
+ * aligned, sized as reported above; input and output must not overlap.
+ */
+VQ_API int vq_pack_layout(const vq_desc* desc, const void* idx_canon, const void* cb_canon,
+                   void* idx_dev, void* cb_dev, void* stream);
+
+/*
+ * y[out] = W x[in]  (Sec. 3.2: decode by lookup, then matrix-vector product;
+ * batch 1).  x is fp16; products are accumulated in fp32; y is written as
+ * y_dtype (VQ_F16 or VQ_F32).  idx_dev/cb_dev come from vq_pack_layout.  x and
+ * y are 16-byte aligned and must not alias.  One kernel launch, deterministic
+ * (no atomics).
+ */
+VQ_API int vq_gemv(const vq_desc* desc, const void* idx_dev, const void* cb_dev,
+            const void* x_f16, void* y, int y_dtype, void* stream);
+
+/*
+ * `count` independent products y_i = W_i x_i enqueued as few launches as
+ * possible (the q/k/v or gate/up projections of a decoder layer, or a whole
+ * per-token weight pass replayed back to back; Sec. 1: every weight is loaded
+ * once per generated token).  descs/idx_dev/cb_dev/x_f16/y are HOST arrays of
+ * length `count` holding descriptors and device pointers; they are read
+ * during the call and need not outlive it (the problem table travels in the
+ * kernel arguments, up to 64 problems per launch).  All y_i share y_dtype and
+ * all descriptors share k.  Each product obeys the rules of vq_gemv.
+ * count in [1, 65536].
+ */
+VQ_API int vq_gemv_multi(int count, const vq_desc* descs, const void* const* idx_dev,
+                  const void* const* cb_dev, const void* const* x_f16, void* const* y,
+                  int y_dtype, void* stream);
+
+/*
+ * Y[out, B] = W X[in, B]  (the batched / prefill form of the same product; a
+ * dense contraction, decoded tiles go through LDS to the matrix cores).
+ * X is fp16 with row stride ldx >= B elements (batch index contiguous), Y has
+ * row stride ldy >= B and dtype y_dtype; accumulation is fp32.  ldx and ldy
+ * are multiples of 8 elements and the X buffer spans in*ldx elements (rows are
+ * read in 8-element pieces up to the stride).  B in [1, 65536].
+ */
+VQ_API int vq_gemm_batched(const vq_desc* desc, const void* idx_dev, const void* cb_dev,
+                    const void* X_f16, int B, int ldx, void* Y, int ldy, int y_dtype,
+                    void* stream);
+
+/*
+ * Dense reconstruction W[out, in], fp16 row-major: W[r, c+t] = cb[g][I_g[v]][t]
+ * copied bit for bit (Sec. 3.2 decode step on its own; the appendix "Further
+ * on-device results" times exactly this transfer + decode on a 11008x4096 layer).
+ */
+VQ_API int vq_decode_dense(const vq_desc* desc, const void* idx_dev, const void* cb_dev,
+                    void* W_f16, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VQ_H_ */

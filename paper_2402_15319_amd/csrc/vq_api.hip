@@ -1,0 +1,176 @@
+// C ABI of libvq: argument validation on the host, then one launch per call.
+// Nothing here allocates, synchronises or keeps state.
+#include <string.h>
+#include "vq_internal.h"
+
+namespace {
+
+using namespace vq;
+
+bool is_pow2(int v) { return v > 0 && (v & (v - 1)) == 0; }
+
+int check_desc(const vq_desc* d) {
+  if (!d) return VQ_ERR_NULL;
+  if (d->out_features <= 0 || d->in_features <= 0 || d->group_rows <= 0 || d->group_cols <= 0 ||
+      d->d <= 0 || d->k <= 0 || d->index_bits <= 0 || d->index_bits > 16)
+    return VQ_ERR_BAD_DESC;
+  if (!is_pow2(d->k) || d->k != (1 << d->index_bits)) return VQ_ERR_BAD_DESC;
+  if (d->group_cols % d->d) return VQ_ERR_BAD_DESC;
+  if (d->codebook_dtype != VQ_F16) return VQ_ERR_UNSUPPORTED;
+  if (d->d != 2 || d->group_rows != kGroupRows || d->group_cols != kGroupCols) return VQ_ERR_UNSUPPORTED;
+  if (d->k != 16 && d->k != 256) return VQ_ERR_UNSUPPORTED;
+  if (d->out_features % kGroupRows || d->in_features % kGroupCols) return VQ_ERR_UNSUPPORTED;
+  // index arithmetic inside the kernels uses 32-bit element offsets into x / rows
+  if ((long long)d->out_features * d->in_features > (1ll << 40)) return VQ_ERR_UNSUPPORTED;
+  return VQ_OK;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+void sizes(const vq_desc& d, size_t* idx_bytes, size_t* cb_bytes) {
+  const size_t n_groups = (size_t)(d.out_features / d.group_rows) * (d.in_features / d.group_cols);
+  const size_t vecs = (size_t)d.group_rows * d.group_cols / d.d;
+  if (idx_bytes) *idx_bytes = n_groups * (vecs * d.index_bits / 8);
+  if (cb_bytes) *cb_bytes = n_groups * (size_t)d.k * d.d * 2;
+}
+
+int choose_splits(long long total_row_blocks) {
+  // Enough waves to cover 256 CUs several times over; few row-blocks -> split K.
+  if (total_row_blocks >= 4096) return 1;
+  if (total_row_blocks >= 2048) return 2;
+  return 4;
+}
+
+int hip_status(hipError_t e) { return e == hipSuccess ? VQ_OK : VQ_ERR_HIP; }
+
+}  // namespace
+
+extern "C" {
+
+const char* vq_status_string(int status) {
+  switch (status) {
+    case VQ_OK: return "VQ_OK";
+    case VQ_ERR_NULL: return "VQ_ERR_NULL: required pointer is NULL";
+    case VQ_ERR_BAD_DESC: return "VQ_ERR_BAD_DESC: inconsistent descriptor";
+    case VQ_ERR_UNSUPPORTED: return "VQ_ERR_UNSUPPORTED: configuration not implemented";
+    case VQ_ERR_ALIGN: return "VQ_ERR_ALIGN: pointer or leading dimension misaligned";
+    case VQ_ERR_HIP: return "VQ_ERR_HIP: HIP runtime error at launch";
+    case VQ_ERR_BAD_ARG: return "VQ_ERR_BAD_ARG: scalar argument out of range";
+    default: return "unknown vq_status";
+  }
+}
+
+int vq_version(void) { return 1; }
+
+int vq_canonical_bytes(const vq_desc* desc, size_t* idx_bytes, size_t* cb_bytes) {
+  // The canonical format is defined for any consistent descriptor, also ones the
+  // kernels do not implement.
+  if (!desc) return VQ_ERR_NULL;
+  const int st = check_desc(desc);
+  if (st == VQ_ERR_BAD_DESC) return st;
+  if (desc->out_features % desc->group_rows || desc->in_features % desc->group_cols)
+    return VQ_ERR_UNSUPPORTED;
+  if (((size_t)desc->group_rows * desc->group_cols / desc->d * desc->index_bits) % 8)
+    return VQ_ERR_UNSUPPORTED;
+  sizes(*desc, idx_bytes, cb_bytes);
+  return VQ_OK;
+}
+
+int vq_layout_bytes(const vq_desc* desc, size_t* idx_bytes, size_t* cb_bytes) {
+  const int st = check_desc(desc);
+  if (st != VQ_OK) return st;
+  sizes(*desc, idx_bytes, cb_bytes);
+  return VQ_OK;
+}
+
+int vq_pack_layout(const vq_desc* desc, const void* idx_canon, const void* cb_canon,
+                   void* idx_dev, void* cb_dev, void* stream) {
+  const int st = check_desc(desc);
+  if (st != VQ_OK) return st;
+  if (!idx_canon || !cb_canon || !idx_dev || !cb_dev) return VQ_ERR_NULL;
+  if (!aligned16(idx_canon) || !aligned16(cb_canon) || !aligned16(idx_dev) || !aligned16(cb_dev))
+    return VQ_ERR_ALIGN;
+  if (idx_canon == idx_dev || cb_canon == cb_dev) return VQ_ERR_BAD_ARG;
+  return hip_status(launch_pack(*desc, idx_canon, cb_canon, idx_dev, cb_dev, (hipStream_t)stream));
+}
+
+int vq_gemv_multi(int count, const vq_desc* descs, const void* const* idx_dev,
+                  const void* const* cb_dev, const void* const* x_f16, void* const* y,
+                  int y_dtype, void* stream) {
+  if (count < 1 || count > 65536) return VQ_ERR_BAD_ARG;
+  if (!descs || !idx_dev || !cb_dev || !x_f16 || !y) return VQ_ERR_NULL;
+  if (y_dtype != VQ_F16 && y_dtype != VQ_F32) return VQ_ERR_BAD_ARG;
+  for (int i = 0; i < count; ++i) {
+    const int st = check_desc(&descs[i]);
+    if (st != VQ_OK) return st;
+    if (descs[i].k != descs[0].k) return VQ_ERR_BAD_ARG;
+    if (!idx_dev[i] || !cb_dev[i] || !x_f16[i] || !y[i]) return VQ_ERR_NULL;
+    if (!aligned16(idx_dev[i]) || !aligned16(cb_dev[i]) || !aligned16(x_f16[i]) || !aligned16(y[i]))
+      return VQ_ERR_ALIGN;
+    if (x_f16[i] == (const void*)y[i]) return VQ_ERR_BAD_ARG;
+  }
+  for (int first = 0; first < count; first += kMaxProblemsPerLaunch) {
+    const int n = count - first < kMaxProblemsPerLaunch ? count - first : kMaxProblemsPerLaunch;
+    long long rb_launch = 0;
+    for (int i = 0; i < n; ++i) rb_launch += descs[first + i].out_features / kGroupRows;
+    const int splits = choose_splits(rb_launch);
+    GemvBatch batch;
+    memset(&batch, 0, sizeof(batch));
+    batch.count = n;
+    batch.y_f32 = (y_dtype == VQ_F32);
+    long long wgs = 0;
+    for (int i = 0; i < n; ++i) {
+      const vq_desc& d = descs[first + i];
+      GemvProblem& p = batch.p[i];
+      p.idx = (const uint8_t*)idx_dev[first + i];
+      p.cb = (const uint32_t*)cb_dev[first + i];
+      p.x = (const uint16_t*)x_f16[first + i];
+      p.y = y[first + i];
+      p.n_rb = d.out_features / kGroupRows;
+      p.n_cb = d.in_features / kGroupCols;
+      p.splits = splits;
+      p.wg_begin = (int32_t)wgs;
+      const int rb_per_wg = 4 / splits;
+      wgs += (p.n_rb + rb_per_wg - 1) / rb_per_wg;
+    }
+    if (wgs > 0x7fffffffll) return VQ_ERR_UNSUPPORTED;
+    batch.total_wgs = (int32_t)wgs;
+    const hipError_t e = launch_gemv(descs[0].k, batch, (hipStream_t)stream);
+    if (e != hipSuccess) return VQ_ERR_HIP;
+  }
+  return VQ_OK;
+}
+
+int vq_gemv(const vq_desc* desc, const void* idx_dev, const void* cb_dev, const void* x_f16,
+            void* y, int y_dtype, void* stream) {
+  if (!desc) return VQ_ERR_NULL;
+  return vq_gemv_multi(1, desc, &idx_dev, &cb_dev, &x_f16, &y, y_dtype, stream);
+}
+
+int vq_gemm_batched(const vq_desc* desc, const void* idx_dev, const void* cb_dev,
+                    const void* X_f16, int B, int ldx, void* Y, int ldy, int y_dtype,
+                    void* stream) {
+  const int st = check_desc(desc);
+  if (st != VQ_OK) return st;
+  if (!idx_dev || !cb_dev || !X_f16 || !Y) return VQ_ERR_NULL;
+  if (y_dtype != VQ_F16 && y_dtype != VQ_F32) return VQ_ERR_BAD_ARG;
+  if (B < 1 || B > 65536) return VQ_ERR_BAD_ARG;
+  if (ldx < B || ldy < B) return VQ_ERR_BAD_ARG;
+  if ((ldx & 7) || (ldy & 7)) return VQ_ERR_ALIGN;
+  if (!aligned16(idx_dev) || !aligned16(cb_dev) || !aligned16(X_f16) || !aligned16(Y))
+    return VQ_ERR_ALIGN;
+  if (X_f16 == (const void*)Y) return VQ_ERR_BAD_ARG;
+  return hip_status(launch_gemm(*desc, idx_dev, cb_dev, X_f16, B, ldx, Y, ldy,
+                                y_dtype == VQ_F32, (hipStream_t)stream));
+}
+
+int vq_decode_dense(const vq_desc* desc, const void* idx_dev, const void* cb_dev, void* W_f16,
+                    void* stream) {
+  const int st = check_desc(desc);
+  if (st != VQ_OK) return st;
+  if (!idx_dev || !cb_dev || !W_f16) return VQ_ERR_NULL;
+  if (!aligned16(idx_dev) || !aligned16(cb_dev) || !aligned16(W_f16)) return VQ_ERR_ALIGN;
+  return hip_status(launch_decode(*desc, idx_dev, cb_dev, W_f16, (hipStream_t)stream));
+}
+
+}  // extern "C"

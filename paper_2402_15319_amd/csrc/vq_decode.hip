@@ -1,0 +1,67 @@
+// Dense reconstruction W[out,in] (fp16, row-major) from the device layout:
+// the decode step of Sec. 3.2 on its own, W[r, c+t] = cb[g][I_g[v]][t], a pure
+// copy of 16-bit patterns.  One wave per group; a row of a group is written as
+// one contiguous 512-byte segment.
+#include "vq_device.h"
+#include "vq_internal.h"
+
+namespace vq {
+namespace {
+
+template <int K>
+__global__ __launch_bounds__(256) void decode_kernel(const uint8_t* __restrict__ idx,
+                                                     const uint32_t* __restrict__ cb,
+                                                     uint16_t* __restrict__ W, int n_cb,
+                                                     long long n_groups, int in_features) {
+  __shared__ uint32_t lut_all[4][K];
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  uint32_t* lut = lut_all[wave];
+  const long long g = (long long)blockIdx.x * 4 + wave;
+  if (g >= n_groups) return;   // whole waves leave; no workgroup barrier below
+  const long long rb = g / n_cb;
+  const int c = (int)(g - rb * n_cb);
+  uint16_t* out = W + (size_t)rb * 8 * in_features + (size_t)c * 256 + lane * 4;
+
+  if (K == 16) {
+    if (lane < 16) lut[lane] = cb[g * 16 + lane];
+    const uint2 w = *reinterpret_cast<const uint2*>(idx + rb * n_cb * 512 + k16_chunk_offset(c, n_cb, lane));
+    wave_lds_sync();
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+      const uint32_t word = r < 4 ? w.x : w.y;
+      const uint32_t lo = (word >> (8 * (r & 3))) & 15u;
+      const uint32_t hi = (word >> (8 * (r & 3) + 4)) & 15u;
+      *reinterpret_cast<uint2*>(out + (size_t)r * in_features) = make_uint2(lut[lo], lut[hi]);
+    }
+  } else {
+    *reinterpret_cast<uint4*>(lut + lane * 4) = *reinterpret_cast<const uint4*>(cb + g * 256 + lane * 4);
+    const uint4 w = *reinterpret_cast<const uint4*>(idx + g * 1024 + lane * 16);
+    wave_lds_sync();
+    const uint32_t ws[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+      const uint32_t half = ws[r >> 1] >> (16 * (r & 1));
+      *reinterpret_cast<uint2*>(out + (size_t)r * in_features) =
+          make_uint2(lut[half & 255u], lut[(half >> 8) & 255u]);
+    }
+  }
+}
+
+}  // namespace
+
+hipError_t launch_decode(const vq_desc& d, const void* idx_dev, const void* cb_dev, void* W,
+                         hipStream_t s) {
+  const int n_cb = d.in_features / kGroupCols;
+  const long long n_groups = (long long)(d.out_features / kGroupRows) * n_cb;
+  const unsigned grid = (unsigned)((n_groups + 3) / 4);
+  if (d.k == 16)
+    hipLaunchKernelGGL(decode_kernel<16>, dim3(grid), dim3(256), 0, s, (const uint8_t*)idx_dev,
+                       (const uint32_t*)cb_dev, (uint16_t*)W, n_cb, n_groups, d.in_features);
+  else
+    hipLaunchKernelGGL(decode_kernel<256>, dim3(grid), dim3(256), 0, s, (const uint8_t*)idx_dev,
+                       (const uint32_t*)cb_dev, (uint16_t*)W, n_cb, n_groups, d.in_features);
+  return hipGetLastError();
+}
+
+}  // namespace vq

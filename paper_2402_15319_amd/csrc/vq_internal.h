@@ -1,0 +1,43 @@
+// Internal declarations shared by the translation units of libvq (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "../../include/vq.h"
+
+namespace vq {
+
+constexpr int kGroupRows = 8;
+constexpr int kGroupCols = 256;
+constexpr int kMaxProblemsPerLaunch = 64;
+
+// One matrix-vector product as the kernels see it (lives in the kernel arguments).
+struct GemvProblem {
+  const uint8_t* idx;   // device-layout indices
+  const uint32_t* cb;   // codebooks, one dword (fp16 pair) per centroid
+  const uint16_t* x;    // fp16 activations
+  void* y;              // fp16 or fp32 output
+  int32_t n_rb;         // row-blocks  (out / 8)
+  int32_t n_cb;         // col-blocks  (in / 256)
+  int32_t wg_begin;     // first workgroup of this problem inside the launch
+  int32_t splits;       // waves sharing one row-block: 1, 2 or 4
+};
+
+struct GemvBatch {
+  int32_t count;
+  int32_t y_f32;
+  int32_t total_wgs;
+  int32_t pad;
+  GemvProblem p[kMaxProblemsPerLaunch];
+};
+
+// Launchers (each returns the hipError_t of its launch).
+hipError_t launch_pack(const vq_desc& d, const void* idx_canon, const void* cb_canon,
+                       void* idx_dev, void* cb_dev, hipStream_t s);
+hipError_t launch_decode(const vq_desc& d, const void* idx_dev, const void* cb_dev,
+                         void* W, hipStream_t s);
+hipError_t launch_gemv(int k, const GemvBatch& batch, hipStream_t s);
+hipError_t launch_gemm(const vq_desc& d, const void* idx_dev, const void* cb_dev,
+                       const void* X, int B, int ldx, void* Y, int ldy, int y_f32,
+                       hipStream_t s);
+
+}  // namespace vq

@@ -1,0 +1,229 @@
+"""GPU parity: every entry point of libvq against the CPU oracle, through the C ABI.
+
+Decode must be bit-exact.  GEMV/GEMM must be within 2e-3 normwise relative error of
+the fp64 oracle (fp16 output: each element is rounded once, 2^-11 relative, so the
+normwise error is about 3e-4; fp32 accumulation over <= 11008 terms adds ~1e-6).
+With fp32 output only the accumulation error remains and the bound is 2e-5.
+"""
+import numpy as np
+import pytest
+
+import oracle
+import workloads
+
+pytestmark = pytest.mark.gpu
+
+TOL_F16 = 2e-3
+TOL_F32 = 2e-5
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    import paper_2402_15319_amd as vq
+    from paper_2402_15319_amd import device as vqdev
+    assert torch.cuda.is_available()
+    vq.lib()   # fails loudly if the HIP library is not built
+    return torch, vq, vqdev
+
+
+def _fmt(s):
+    return oracle.VQFormat(s.out_features, s.in_features, s.k, s.index_bits,
+                           s.group_rows, s.group_cols, s.d)
+
+
+def _shape(o, i, k):
+    return workloads.VQShape(o, i, k, 4 if k == 16 else 8)
+
+
+# small shapes: several tiles, ragged tails (odd col-block counts, row-block counts
+# that are not a multiple of the 4 waves of a workgroup), both codebook sizes
+SMALL = [
+    _shape(256, 256, 16), _shape(8, 256, 16), _shape(40, 768, 16), _shape(24, 2816, 16),
+    _shape(264, 1024, 16), _shape(8, 256, 256), _shape(40, 768, 256), _shape(72, 1280, 256),
+]
+FULL = ["attn_4096x4096_k16", "mlp_up_11008x4096_k256", "mlp_down_4096x11008_k256",
+        "mlp_up_11008x4096_k16", "mlp_down_4096x11008_k16"]
+
+
+def _setup(env, s, seed):
+    torch, vq, vqdev = env
+    idx, cb = workloads.make_weights(s, seed)
+    desc = vqdev.desc_from_shape(s)
+    idx_d, cb_d = vqdev.upload_and_pack(desc, idx, cb)
+    return desc, idx, cb, idx_d, cb_d
+
+
+def _gpu_decode(env, desc, idx_d, cb_d):
+    torch, vq, _ = env
+    W = torch.full((desc.out_features, desc.in_features), -1, dtype=torch.int16, device="cuda:0")
+    vq.vq_decode_dense(desc, idx_d, cb_d, W)
+    torch.cuda.synchronize()
+    return W.cpu().numpy().view(np.uint16)
+
+
+def _gpu_gemv(env, desc, idx_d, cb_d, x, f32):
+    torch, vq, vqdev = env
+    x_d = vqdev.to_device_bytes(x)
+    # canary-padded output: the kernel must write exactly out_features elements
+    n = desc.out_features
+    y = torch.full((n + 64,), 12345.0, dtype=torch.float32 if f32 else torch.float16, device="cuda:0")
+    vq.vq_gemv(desc, idx_d, cb_d, x_d, y, vq.VQ_F32 if f32 else vq.VQ_F16)
+    torch.cuda.synchronize()
+    out = y.cpu().numpy()
+    assert np.all(out[n:] == 12345.0), "wrote past the end of y"
+    return out[:n].astype(np.float64)
+
+
+@pytest.mark.parametrize("s", SMALL, ids=str)
+def test_decode_bit_exact_small(env, s):
+    desc, idx, cb, idx_d, cb_d = _setup(env, s, 101)
+    np.testing.assert_array_equal(_gpu_decode(env, desc, idx_d, cb_d), oracle.decode_dense(_fmt(s), idx, cb))
+
+
+@pytest.mark.parametrize("key", FULL)
+def test_decode_bit_exact_full(env, key):
+    s = workloads.CONFIGS[key]
+    desc, idx, cb, idx_d, cb_d = _setup(env, s, workloads.seed_for(key))
+    got = _gpu_decode(env, desc, idx_d, cb_d)
+    want = oracle.decode_dense(_fmt(s), idx, cb)
+    assert np.array_equal(got, want)
+    # and a few elements one by one with the scalar walk
+    rng = np.random.default_rng(1)
+    for _ in range(64):
+        r, c = int(rng.integers(s.out_features)), int(rng.integers(s.in_features))
+        assert got[r, c] == oracle.decode_element(_fmt(s), idx, cb, r, c)
+
+
+def test_decode_keeps_special_bit_patterns(env):
+    """Subnormals, -0, inf and NaN payloads are copied, not computed on."""
+    s = _shape(16, 512, 256)
+    idx, cb = workloads.make_weights(s, 7)
+    cbu = cb.view(np.uint16)
+    cbu[:, 0, 0] = 0x8000
+    cbu[:, 1, 1] = 0x0001
+    cbu[:, 2, 0] = 0x7C00
+    cbu[:, 3, 1] = 0x7E01
+    cbu[:, 4, 0] = 0xFFFF
+    torch, vq, vqdev = env
+    desc = vqdev.desc_from_shape(s)
+    idx_d, cb_d = vqdev.upload_and_pack(desc, idx, cb)
+    np.testing.assert_array_equal(_gpu_decode(env, desc, idx_d, cb_d), oracle.decode_dense(_fmt(s), idx, cb))
+
+
+@pytest.mark.parametrize("f32", [False, True], ids=["y16", "y32"])
+@pytest.mark.parametrize("s", SMALL, ids=str)
+def test_gemv_small(env, s, f32):
+    desc, idx, cb, idx_d, cb_d = _setup(env, s, 202)
+    x = workloads.make_x(s.in_features, 202)
+    y = _gpu_gemv(env, desc, idx_d, cb_d, x, f32)
+    ref = oracle.gemv(_fmt(s), idx, cb, x)
+    assert oracle.normwise_rel_err(y, ref) <= (TOL_F32 if f32 else TOL_F16)
+
+
+@pytest.mark.parametrize("f32", [False, True], ids=["y16", "y32"])
+@pytest.mark.parametrize("key", ["tiny_256x256_k16"] + FULL)
+def test_gemv_configs(env, key, f32):
+    s = workloads.CONFIGS[key]
+    seed = workloads.seed_for(key)
+    desc, idx, cb, idx_d, cb_d = _setup(env, s, seed)
+    x = workloads.make_x(s.in_features, seed)
+    y = _gpu_gemv(env, desc, idx_d, cb_d, x, f32)
+    ref = oracle.gemv(_fmt(s), idx, cb, x)
+    err = oracle.normwise_rel_err(y, ref)
+    print(f"{key} f32={f32} normwise rel err {err:.3e} max abs {np.max(np.abs(y - ref)):.3e}")
+    assert err <= (TOL_F32 if f32 else TOL_F16)
+
+
+def test_gemv_one_centroid_closed_form(env):
+    """All centroids equal (a, b): y[r] = a*sum(x_even) + b*sum(x_odd) whatever the indices."""
+    s = _shape(64, 1024, 16)
+    idx, _ = workloads.make_weights(s, 5)
+    cb = np.broadcast_to(np.array([0.5, -0.25], dtype=np.float16), (s.n_groups, s.k, s.d)).copy()
+    torch, vq, vqdev = env
+    desc = vqdev.desc_from_shape(s)
+    idx_d, cb_d = vqdev.upload_and_pack(desc, idx, cb)
+    x = np.random.default_rng(5).integers(-3, 4, size=s.in_features).astype(np.float16)
+    y = _gpu_gemv(env, desc, idx_d, cb_d, x, True)
+    want = 0.5 * x[0::2].astype(np.float64).sum() - 0.25 * x[1::2].astype(np.float64).sum()
+    np.testing.assert_array_equal(y, np.full(s.out_features, want))
+
+
+def test_gemv_unit_vectors_pick_columns(env):
+    s = _shape(40, 768, 256)
+    desc, idx, cb, idx_d, cb_d = _setup(env, s, 9)
+    W = oracle.decode_dense(_fmt(s), idx, cb).view(np.float16).astype(np.float64)
+    for c in (0, 1, 255, 256, 513, 767):
+        e = np.zeros(s.in_features, dtype=np.float16)
+        e[c] = 1
+        np.testing.assert_array_equal(_gpu_gemv(env, desc, idx_d, cb_d, e, True), W[:, c])
+
+
+@pytest.mark.parametrize("k", [16, 256])
+def test_gemv_multi_matches_oracle(env, k):
+    torch, vq, vqdev = env
+    shapes = [_shape(64, 512, k), _shape(64, 512, k), _shape(176, 512, k), _shape(64, 1280, k),
+              _shape(8, 256, k)] * 15          # 75 problems: more than one launch of 64
+    descs, idxs, cbs, xs, ys, refs = [], [], [], [], [], []
+    for i, s in enumerate(shapes):
+        idx, cb = workloads.make_weights(s, 300 + i)
+        x = workloads.make_x(s.in_features, 300 + i)
+        desc = vqdev.desc_from_shape(s)
+        idx_d, cb_d = vqdev.upload_and_pack(desc, idx, cb)
+        descs.append(desc); idxs.append(idx_d); cbs.append(cb_d)
+        xs.append(vqdev.to_device_bytes(x))
+        ys.append(torch.zeros(s.out_features, dtype=torch.float16, device="cuda:0"))
+        if i < 10 or i >= 70:
+            refs.append((i, oracle.gemv(_fmt(s), idx, cb, x)))
+    vq.vq_gemv_multi(descs, idxs, cbs, xs, ys)
+    torch.cuda.synchronize()
+    for i, ref in refs:
+        assert oracle.normwise_rel_err(ys[i].cpu().numpy(), ref) <= TOL_F16, i
+
+
+def _gpu_gemm(env, desc, idx_d, cb_d, X, f32, pad=0):
+    torch, vq, vqdev = env
+    in_f, B = X.shape
+    ld = ((B + 7) // 8) * 8 + pad
+    Xp = np.zeros((in_f, ld), dtype=np.float16)
+    Xp[:, :B] = X
+    X_d = vqdev.to_device_bytes(Xp)
+    Y = torch.full((desc.out_features, ld), 777.0, dtype=torch.float32 if f32 else torch.float16, device="cuda:0")
+    vq.vq_gemm_batched(desc, idx_d, cb_d, X_d, B, ld, Y, ld, vq.VQ_F32 if f32 else vq.VQ_F16)
+    torch.cuda.synchronize()
+    out = Y.cpu().numpy()
+    assert np.all(out[:, B:] == 777.0), "wrote outside the B columns"
+    return out[:, :B].astype(np.float64)
+
+
+@pytest.mark.parametrize("f32", [False, True], ids=["y16", "y32"])
+@pytest.mark.parametrize("B", [1, 16, 40, 130, 256])
+@pytest.mark.parametrize("s", [_shape(40, 768, 16), _shape(72, 512, 256), _shape(264, 1024, 256)], ids=str)
+def test_gemm_small(env, s, B, f32):
+    desc, idx, cb, idx_d, cb_d = _setup(env, s, 404)
+    X = workloads.make_X(s.in_features, B, 404)
+    Y = _gpu_gemm(env, desc, idx_d, cb_d, X, f32, pad=8 if B == 40 else 0)
+    ref = oracle.gemm(_fmt(s), idx, cb, X)
+    assert oracle.normwise_rel_err(Y, ref) <= (TOL_F32 if f32 else TOL_F16)
+
+
+@pytest.mark.parametrize("B", [16, 256, 2048])
+def test_gemm_config5(env, B):
+    """W[11008,4096] k=256 times X[4096,B].  The oracle computes the whole Y for B <= 256
+    and 48 sampled columns of it for B = 2048 (column b of Y depends on column b of X only)."""
+    key = "mlp_up_11008x4096_k256"
+    s = workloads.CONFIGS[key]
+    seed = workloads.seed_for(key)
+    desc, idx, cb, idx_d, cb_d = _setup(env, s, seed)
+    X = workloads.make_X(s.in_features, B, seed)
+    Y = _gpu_gemm(env, desc, idx_d, cb_d, X, False)
+    assert np.all(np.isfinite(Y))
+    if B <= 256:
+        cols = np.arange(B)
+    else:
+        cols = np.unique(np.concatenate([np.arange(8), np.arange(B - 8, B),
+                                         np.random.default_rng(2).integers(0, B, 32)]))
+    ref = oracle.gemm(_fmt(s), idx, cb, X[:, cols])
+    err = oracle.normwise_rel_err(Y[:, cols], ref)
+    print(f"gemm B={B} normwise rel err {err:.3e}")
+    assert err <= TOL_F16
