@@ -29,12 +29,87 @@ __device__ __forceinline__ float dot2(uint32_t c, uint32_t x, float acc) {
   return __builtin_amdgcn_fdot2(__builtin_bit_cast(h2_t, c), __builtin_bit_cast(h2_t, x), acc, false);
 }
 
+typedef __attribute__((address_space(3))) uint32_t lds_u32;
+
+// LDS byte address of a pointer into a __shared__ array, made wave-uniform (SGPR).
+__device__ __forceinline__ uint32_t lds_addr(const uint32_t* p) {
+  const uint32_t a = (uint32_t)(uintptr_t)(lds_u32*)p;
+  return __builtin_amdgcn_readfirstlane(a);
+}
+
 // Orders this wave's LDS writes before its later LDS reads (other lanes' data).
 __device__ __forceinline__ void wave_lds_sync() {
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
   __builtin_amdgcn_wave_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
+
+// ---------------------------------------------------------------------------
+// k = 16 inner block: all 16 lookups + dot products of one lane's share of one
+// group (two dwords = 8 rows x 2 vectors), hand-scheduled.
+//
+//   w0, w1   the lane's 8 index bytes (byte r: low nibble = vector 2L, high = 2L+1)
+//   base     LDS byte address of this wave's table region (wave-uniform, SGPR)
+//   OFF      byte offset of the group's 16-entry table inside the region (immediate)
+//   x0, x1   fp16 pairs of the activations of vectors 2L and 2L+1
+//   acc      the 8 row accumulators (fp32)
+//
+// Per dword, (w << 2) & 0x3c3c3c3c and (w >> 2) & 0x3c3c3c3c leave index*4 of the
+// low / high nibbles in the four bytes; one SDWA add per lookup then picks a byte
+// and adds the table base, and the table offset rides in the ds_read immediate:
+// 2.5 VALU instructions per vector including the dot2.  LDS reads are kept 8-12
+// deep ahead of the dot products (lgkmcnt is a 4-bit counter).  The trailing
+// s_nop covers the dot-result-read-by-other-VALU wait states, which the
+// compiler cannot see inside an asm statement.
+#define VQ_SDWA_RD(R, T, B, OFF)                                                          \
+  "v_add_u32_sdwa " R ", %[base], " T                                                     \
+  " dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_" #B "\n"            \
+  "ds_read_b32 " R ", " R " offset:" OFF "\n"
+#define VQ_MASKS(W)                                  \
+  "v_lshlrev_b32 %[ta], 2, " W "\n"                  \
+  "v_lshrrev_b32 %[tb], 2, " W "\n"                  \
+  "v_and_b32 %[ta], 0x3c3c3c3c, %[ta]\n"             \
+  "v_and_b32 %[tb], 0x3c3c3c3c, %[tb]\n"
+#define VQ_DOT(ACC, R, X) "v_dot2c_f32_f16 " ACC ", " R ", " X "\n"
+
+template <int OFF>
+__device__ __forceinline__ void k16_group(uint32_t w0, uint32_t w1, uint32_t base, uint32_t x0,
+                                          uint32_t x1, float (&acc)[8]) {
+  uint32_t ta, tb, r0, r1, r2, r3, r4, r5, r6, r7, r8, r9, r10, r11;
+  asm volatile(
+      VQ_MASKS("%[w0]")
+      VQ_SDWA_RD("%[r0]", "%[ta]", 0, "%[off]") VQ_SDWA_RD("%[r1]", "%[tb]", 0, "%[off]")
+      VQ_SDWA_RD("%[r2]", "%[ta]", 1, "%[off]") VQ_SDWA_RD("%[r3]", "%[tb]", 1, "%[off]")
+      VQ_SDWA_RD("%[r4]", "%[ta]", 2, "%[off]") VQ_SDWA_RD("%[r5]", "%[tb]", 2, "%[off]")
+      VQ_SDWA_RD("%[r6]", "%[ta]", 3, "%[off]") VQ_SDWA_RD("%[r7]", "%[tb]", 3, "%[off]")
+      VQ_MASKS("%[w1]")
+      VQ_SDWA_RD("%[r8]", "%[ta]", 0, "%[off]") VQ_SDWA_RD("%[r9]", "%[tb]", 0, "%[off]")
+      VQ_SDWA_RD("%[r10]", "%[ta]", 1, "%[off]") VQ_SDWA_RD("%[r11]", "%[tb]", 1, "%[off]")
+      "s_waitcnt lgkmcnt(4)\n"
+      VQ_DOT("%[a0]", "%[r0]", "%[x0]") VQ_DOT("%[a1]", "%[r2]", "%[x0]")
+      VQ_DOT("%[a2]", "%[r4]", "%[x0]") VQ_DOT("%[a3]", "%[r6]", "%[x0]")
+      VQ_DOT("%[a0]", "%[r1]", "%[x1]") VQ_DOT("%[a1]", "%[r3]", "%[x1]")
+      VQ_DOT("%[a2]", "%[r5]", "%[x1]") VQ_DOT("%[a3]", "%[r7]", "%[x1]")
+      VQ_SDWA_RD("%[r0]", "%[ta]", 2, "%[off]") VQ_SDWA_RD("%[r1]", "%[tb]", 2, "%[off]")
+      VQ_SDWA_RD("%[r2]", "%[ta]", 3, "%[off]") VQ_SDWA_RD("%[r3]", "%[tb]", 3, "%[off]")
+      "s_waitcnt lgkmcnt(4)\n"
+      VQ_DOT("%[a4]", "%[r8]", "%[x0]") VQ_DOT("%[a5]", "%[r10]", "%[x0]")
+      VQ_DOT("%[a4]", "%[r9]", "%[x1]") VQ_DOT("%[a5]", "%[r11]", "%[x1]")
+      "s_waitcnt lgkmcnt(0)\n"
+      VQ_DOT("%[a6]", "%[r0]", "%[x0]") VQ_DOT("%[a7]", "%[r2]", "%[x0]")
+      VQ_DOT("%[a6]", "%[r1]", "%[x1]") VQ_DOT("%[a7]", "%[r3]", "%[x1]")
+      "s_nop 2\n"
+      : [a0] "+v"(acc[0]), [a1] "+v"(acc[1]), [a2] "+v"(acc[2]), [a3] "+v"(acc[3]),
+        [a4] "+v"(acc[4]), [a5] "+v"(acc[5]), [a6] "+v"(acc[6]), [a7] "+v"(acc[7]),
+        [ta] "=&v"(ta), [tb] "=&v"(tb), [r0] "=&v"(r0), [r1] "=&v"(r1), [r2] "=&v"(r2),
+        [r3] "=&v"(r3), [r4] "=&v"(r4), [r5] "=&v"(r5), [r6] "=&v"(r6), [r7] "=&v"(r7),
+        [r8] "=&v"(r8), [r9] "=&v"(r9), [r10] "=&v"(r10), [r11] "=&v"(r11)
+      : [w0] "v"(w0), [w1] "v"(w1), [base] "s"(base), [x0] "v"(x0), [x1] "v"(x1), [off] "n"(OFF)
+      : "memory");
+}
+#undef VQ_SDWA_RD
+#undef VQ_MASKS
+#undef VQ_DOT
 
 // Byte offset of lane `lane`'s 8-byte share of 4-bit group (row-block base + ...).
 __device__ __forceinline__ size_t k16_chunk_offset(int c, int n_cb, int lane) {
