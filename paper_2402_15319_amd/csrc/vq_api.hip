@@ -114,11 +114,12 @@ int vq_gemv_multi(int count, const vq_desc* descs, const void* const* idx_dev,
     long long rb_launch = 0;
     for (int i = 0; i < n; ++i) rb_launch += descs[first + i].out_features / kGroupRows;
     const int splits = choose_splits(rb_launch);
+    const bool stream_mode = splits == 1;
     GemvBatch batch;
     memset(&batch, 0, sizeof(batch));
     batch.count = n;
     batch.y_f32 = (y_dtype == VQ_F32);
-    long long wgs = 0;
+    long long items = 0;   // row-blocks (stream mode) or workgroups (split mode)
     for (int i = 0; i < n; ++i) {
       const vq_desc& d = descs[first + i];
       GemvProblem& p = batch.p[i];
@@ -129,13 +130,19 @@ int vq_gemv_multi(int count, const vq_desc* descs, const void* const* idx_dev,
       p.n_rb = d.out_features / kGroupRows;
       p.n_cb = d.in_features / kGroupCols;
       p.splits = splits;
-      p.wg_begin = (int32_t)wgs;
+      p.wg_begin = (int32_t)items;
       const int rb_per_wg = 4 / splits;
-      wgs += (p.n_rb + rb_per_wg - 1) / rb_per_wg;
+      items += stream_mode ? p.n_rb : (p.n_rb + rb_per_wg - 1) / rb_per_wg;
     }
-    if (wgs > 0x7fffffffll) return VQ_ERR_UNSUPPORTED;
-    batch.total_wgs = (int32_t)wgs;
-    const hipError_t e = launch_gemv(descs[0].k, batch, (hipStream_t)stream);
+    if (items > 0x7fffffffll) return VQ_ERR_UNSUPPORTED;
+    batch.total_wgs = (int32_t)items;
+    int grid = (int)items;
+    if (stream_mode) {
+      const long long want = (items + 3) / 4;
+      const int resident = gemv_stream_resident_wgs(descs[0].k);
+      grid = (int)(want < resident ? want : resident);
+    }
+    const hipError_t e = launch_gemv(descs[0].k, batch, stream_mode ? 1 : 0, grid, (hipStream_t)stream);
     if (e != hipSuccess) return VQ_ERR_HIP;
   }
   return VQ_OK;

@@ -111,6 +111,56 @@ __device__ __forceinline__ void k16_group(uint32_t w0, uint32_t w1, uint32_t bas
 #undef VQ_MASKS
 #undef VQ_DOT
 
+// ---------------------------------------------------------------------------
+// k = 256 inner block: the 16 lookups + dot products of one lane's share of one
+// group (four dwords; byte 2r+e = row r, vector 2L+e), hand-scheduled like
+// k16_group.  Address = base + OFF + 4*index: one v_bfe_u32 and one
+// v_lshl_add_u32 per lookup (3 VALU instructions per vector with the dot2).
+#define VQ_BFE_RD(R, W, BIT, OFF)                        \
+  "v_bfe_u32 " R ", " W ", " #BIT ", 8\n"                \
+  "v_lshl_add_u32 " R ", " R ", 2, %[base]\n"            \
+  "ds_read_b32 " R ", " R " offset:" OFF "\n"
+#define VQ_DOT(ACC, R, X) "v_dot2c_f32_f16 " ACC ", " R ", " X "\n"
+
+template <int OFF>
+__device__ __forceinline__ void k256_group(uint32_t w0, uint32_t w1, uint32_t w2, uint32_t w3,
+                                           uint32_t base, uint32_t x0, uint32_t x1,
+                                           float (&acc)[8]) {
+  uint32_t r0, r1, r2, r3, r4, r5, r6, r7, r8, r9, r10, r11;
+  asm volatile(
+      VQ_BFE_RD("%[r0]", "%[w0]", 0, "%[off]") VQ_BFE_RD("%[r1]", "%[w0]", 8, "%[off]")
+      VQ_BFE_RD("%[r2]", "%[w0]", 16, "%[off]") VQ_BFE_RD("%[r3]", "%[w0]", 24, "%[off]")
+      VQ_BFE_RD("%[r4]", "%[w1]", 0, "%[off]") VQ_BFE_RD("%[r5]", "%[w1]", 8, "%[off]")
+      VQ_BFE_RD("%[r6]", "%[w1]", 16, "%[off]") VQ_BFE_RD("%[r7]", "%[w1]", 24, "%[off]")
+      VQ_BFE_RD("%[r8]", "%[w2]", 0, "%[off]") VQ_BFE_RD("%[r9]", "%[w2]", 8, "%[off]")
+      VQ_BFE_RD("%[r10]", "%[w2]", 16, "%[off]") VQ_BFE_RD("%[r11]", "%[w2]", 24, "%[off]")
+      "s_waitcnt lgkmcnt(8)\n"
+      VQ_DOT("%[a0]", "%[r0]", "%[x0]") VQ_DOT("%[a1]", "%[r2]", "%[x0]")
+      VQ_DOT("%[a0]", "%[r1]", "%[x1]") VQ_DOT("%[a1]", "%[r3]", "%[x1]")
+      VQ_BFE_RD("%[r0]", "%[w3]", 0, "%[off]") VQ_BFE_RD("%[r1]", "%[w3]", 8, "%[off]")
+      VQ_BFE_RD("%[r2]", "%[w3]", 16, "%[off]") VQ_BFE_RD("%[r3]", "%[w3]", 24, "%[off]")
+      "s_waitcnt lgkmcnt(8)\n"
+      VQ_DOT("%[a2]", "%[r4]", "%[x0]") VQ_DOT("%[a3]", "%[r6]", "%[x0]")
+      VQ_DOT("%[a2]", "%[r5]", "%[x1]") VQ_DOT("%[a3]", "%[r7]", "%[x1]")
+      "s_waitcnt lgkmcnt(4)\n"
+      VQ_DOT("%[a4]", "%[r8]", "%[x0]") VQ_DOT("%[a5]", "%[r10]", "%[x0]")
+      VQ_DOT("%[a4]", "%[r9]", "%[x1]") VQ_DOT("%[a5]", "%[r11]", "%[x1]")
+      "s_waitcnt lgkmcnt(0)\n"
+      VQ_DOT("%[a6]", "%[r0]", "%[x0]") VQ_DOT("%[a7]", "%[r2]", "%[x0]")
+      VQ_DOT("%[a6]", "%[r1]", "%[x1]") VQ_DOT("%[a7]", "%[r3]", "%[x1]")
+      "s_nop 2\n"
+      : [a0] "+v"(acc[0]), [a1] "+v"(acc[1]), [a2] "+v"(acc[2]), [a3] "+v"(acc[3]),
+        [a4] "+v"(acc[4]), [a5] "+v"(acc[5]), [a6] "+v"(acc[6]), [a7] "+v"(acc[7]),
+        [r0] "=&v"(r0), [r1] "=&v"(r1), [r2] "=&v"(r2), [r3] "=&v"(r3), [r4] "=&v"(r4),
+        [r5] "=&v"(r5), [r6] "=&v"(r6), [r7] "=&v"(r7), [r8] "=&v"(r8), [r9] "=&v"(r9),
+        [r10] "=&v"(r10), [r11] "=&v"(r11)
+      : [w0] "v"(w0), [w1] "v"(w1), [w2] "v"(w2), [w3] "v"(w3), [base] "s"(base), [x0] "v"(x0),
+        [x1] "v"(x1), [off] "n"(OFF)
+      : "memory");
+}
+#undef VQ_BFE_RD
+#undef VQ_DOT
+
 // Byte offset of lane `lane`'s 8-byte share of 4-bit group (row-block base + ...).
 __device__ __forceinline__ size_t k16_chunk_offset(int c, int n_cb, int lane) {
   const int n_pairs = n_cb >> 1;

@@ -18,14 +18,14 @@ struct GemvProblem {
   void* y;              // fp16 or fp32 output
   int32_t n_rb;         // row-blocks  (out / 8)
   int32_t n_cb;         // col-blocks  (in / 256)
-  int32_t wg_begin;     // first workgroup of this problem inside the launch
+  int32_t wg_begin;     // first work item of this problem inside the launch (see launch_gemv)
   int32_t splits;       // waves sharing one row-block: 1, 2 or 4
 };
 
 struct GemvBatch {
   int32_t count;
   int32_t y_f32;
-  int32_t total_wgs;
+  int32_t total_wgs;    // work items in the launch
   int32_t pad;
   GemvProblem p[kMaxProblemsPerLaunch];
 };
@@ -35,7 +35,12 @@ hipError_t launch_pack(const vq_desc& d, const void* idx_canon, const void* cb_c
                        void* idx_dev, void* cb_dev, hipStream_t s);
 hipError_t launch_decode(const vq_desc& d, const void* idx_dev, const void* cb_dev,
                          void* W, hipStream_t s);
-hipError_t launch_gemv(int k, const GemvBatch& batch, hipStream_t s);
+// stream_mode != 0: persistent kernel, wg_begin/total_wgs count row-blocks, grid_wgs workgroups;
+// stream_mode == 0: split-K kernel, wg_begin/total_wgs count workgroups (= grid_wgs).
+hipError_t launch_gemv(int k, const GemvBatch& batch, int stream_mode, int grid_wgs,
+                       hipStream_t s);
+// Workgroups of the persistent GEMV kernel that fit on the current device at once.
+int gemv_stream_resident_wgs(int k);
 hipError_t launch_gemm(const vq_desc& d, const void* idx_dev, const void* cb_dev,
                        const void* X, int B, int ldx, void* Y, int ldy, int y_f32,
                        hipStream_t s);

@@ -181,6 +181,47 @@ def test_gemv_multi_matches_oracle(env, k):
         assert oracle.normwise_rel_err(ys[i].cpu().numpy(), ref) <= TOL_F16, i
 
 
+# Launches with >= 4096 row-blocks take the persistent streaming kernel (one wave per
+# row-block, chunks prefetched across row-blocks); these shapes reach it with ragged strips:
+# one col-block, an odd count (pair + tail), exactly one chunk, chunk + ragged end.
+STREAM = [_shape(32776, 256, 16), _shape(32776, 768, 16), _shape(32776, 2048, 16),
+          _shape(32776, 2816, 16), _shape(32776, 256, 256), _shape(32776, 768, 256),
+          _shape(33000, 1280, 256)]
+
+
+@pytest.mark.parametrize("f32", [False, True], ids=["y16", "y32"])
+@pytest.mark.parametrize("s", STREAM, ids=str)
+def test_gemv_streaming_kernel(env, s, f32):
+    desc, idx, cb, idx_d, cb_d = _setup(env, s, 505)
+    x = workloads.make_x(s.in_features, 505)
+    y = _gpu_gemv(env, desc, idx_d, cb_d, x, f32)
+    ref = oracle.gemv(_fmt(s), idx, cb, x)
+    assert oracle.normwise_rel_err(y, ref) <= (TOL_F32 if f32 else TOL_F16)
+
+
+def test_gemv_multi_llama_layer(env):
+    """The 7 matrices of one decoder layer in one vq_gemv_multi call (5312 row-blocks:
+    the launch configuration bench.py times), every output against the oracle."""
+    torch, vq, vqdev = env
+    descs, idxs, cbs, xs, ys, refs = [], [], [], [], [], []
+    for m, (name, key) in enumerate(workloads.LLAMA7B_LAYER):
+        s = workloads.CONFIGS[key]
+        seed = workloads.seed_for(key, 0, m)
+        idx, cb = workloads.make_weights(s, seed)
+        x = workloads.make_x(s.in_features, seed)
+        desc = vqdev.desc_from_shape(s)
+        idx_d, cb_d = vqdev.upload_and_pack(desc, idx, cb)
+        descs.append(desc); idxs.append(idx_d); cbs.append(cb_d)
+        xs.append(vqdev.to_device_bytes(x))
+        ys.append(torch.full((s.out_features,), 7.0, dtype=torch.float16, device="cuda:0"))
+        refs.append(oracle.gemv(_fmt(s), idx, cb, x))
+    vq.vq_gemv_multi(descs, idxs, cbs, xs, ys)
+    torch.cuda.synchronize()
+    for i, ref in enumerate(refs):
+        err = oracle.normwise_rel_err(ys[i].cpu().numpy(), ref)
+        assert err <= TOL_F16, (i, err)
+
+
 def _gpu_gemm(env, desc, idx_d, cb_d, X, f32, pad=0):
     torch, vq, vqdev = env
     in_f, B = X.shape
