@@ -120,6 +120,7 @@ int vq_gemv_multi(int count, const vq_desc* descs, const void* const* idx_dev,
     batch.count = n;
     batch.y_f32 = (y_dtype == VQ_F32);
     long long items = 0;   // row-blocks (stream mode) or workgroups (split mode)
+    long long cost = 0;    // groups
     for (int i = 0; i < n; ++i) {
       const vq_desc& d = descs[first + i];
       GemvProblem& p = batch.p[i];
@@ -131,11 +132,14 @@ int vq_gemv_multi(int count, const vq_desc* descs, const void* const* idx_dev,
       p.n_cb = d.in_features / kGroupCols;
       p.splits = splits;
       p.wg_begin = (int32_t)items;
+      p.cost_begin = (int32_t)cost;
+      cost += (long long)p.n_rb * p.n_cb;
       const int rb_per_wg = 4 / splits;
       items += stream_mode ? p.n_rb : (p.n_rb + rb_per_wg - 1) / rb_per_wg;
     }
-    if (items > 0x7fffffffll) return VQ_ERR_UNSUPPORTED;
+    if (items > 0x7fffffffll || cost > 0x3fffffffll) return VQ_ERR_UNSUPPORTED;
     batch.total_wgs = (int32_t)items;
+    batch.total_cost = (int32_t)cost;
     int grid = (int)items;
     if (stream_mode) {
       const long long want = (items + 3) / 4;

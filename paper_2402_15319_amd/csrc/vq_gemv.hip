@@ -26,58 +26,76 @@
 namespace vq {
 namespace {
 
-// A strip as wave-uniform scalars.
+// A strip as wave-uniform scalars.  Units are col-block pairs (k=16) or col-blocks (k=256).
 struct Strip {
   const uint8_t* idx_rb;   // indices of the row-block
   const uint32_t* cb_rb;   // codebooks of the row-block (dwords)
   const uint16_t* x;
-  int u;                   // next unit to load: col-block pair (k=16) or col-block (k=256)
-  int u_end;               // end of the units, counting the odd tail group of k=16 as one
-  int u_pairs_end;         // k=16: end of the full pairs of this strip
+  int u;                   // next unit to load
+  int u_end;               // end of this strip's units
+  int chunks_left;         // chunks still to load (>= 1 for a fresh strip)
   int n_pairs;             // k=16: pairs in the whole row-block (locates the tail's bytes)
   int tail_c;              // k=16: col-block of the odd tail group in this strip, or -1
 };
 
 template <int K> struct Chunk;
 
+// Every chunk issues the same loads whatever its shape: absent parts read a harmless
+// in-bounds address and are zeroed afterwards.  The loads of two chunks overlap the
+// consumption of a third, and the compiler can only keep a partial vmcnt wait (instead
+// of waiting for every outstanding load) if the number of loads in flight is static.
+__device__ __forceinline__ uint2 zero_unless(bool keep, uint2 v) {
+  return keep ? v : make_uint2(0, 0);
+}
+__device__ __forceinline__ uint4 zero_unless(bool keep, uint4 v) {
+  return keep ? v : make_uint4(0, 0, 0, 0);
+}
+
 // ---- k = 16 --------------------------------------------------------------
+// Chunk = up to 4 col-block pairs; the last chunk of a strip also carries the odd
+// tail group, if the strip has one.
 template <> struct Chunk<16> {
-  static constexpr int kUnits = 4;       // col-block pairs per chunk
-  static constexpr int kLutDwords = 128; // 8 groups x 16 centroids
-  uint4 w[4];     // slot s: the lane's 16 index bytes of pair u+s (8 bytes + zeros for the tail)
+  static constexpr int kUnits = 4;
+  static constexpr int kLutDwords = 144;  // 8 groups + the tail group, 16 centroids each
+  uint4 w[4];     // slot s: the lane's 16 index bytes of pair u+s
   uint2 xa[4];    // activations of the first group of the slot
   uint2 xb[4];    // ... and of the second
-  uint4 cbv;      // this lane's 16 bytes of the chunk's codebooks (lanes 0..31)
+  uint4 cbv;      // this lane's 16 bytes of the pairs' codebooks (lanes 0..31)
+  uint2 wt, xt;   // the tail group: 8 index bytes, activations
+  uint32_t cbt;   // its codebook (lanes 0..15)
+  bool has_tail;  // wave-uniform
 
   __device__ __forceinline__ void load(const Strip& S, int u, int lane) {
-    const int n_groups = 2 * max(0, min(4, S.u_pairs_end - u)) +
-                         ((S.tail_c >= 0 && S.u_pairs_end - u >= 0 && S.u_pairs_end - u < 4) ? 1 : 0);
-    cbv = make_uint4(0, 0, 0, 0);
-    if (lane * 16 < n_groups * 64)
-      cbv = *reinterpret_cast<const uint4*>(S.cb_rb + (size_t)u * 32 + lane * 4);
+    const int np = min(4, S.u_end - u);                         // pairs present, 0..4
+    has_tail = S.tail_c >= 0 && S.chunks_left == 1;
+    // codebooks of the 2*np groups: 32*np dwords, 4 per lane
+    const int cb_off = min(lane * 4, max(np * 32 - 4, 0));
+    const bool cb_keep = lane * 4 < np * 32;
+    // a 16-byte read that is in bounds for every lane of every row-block (its first 512 bytes)
+    const uint8_t* dummy = S.idx_rb + (lane & 31) * 16;
+    cbv = zero_unless(cb_keep && np > 0,
+                      *reinterpret_cast<const uint4*>(np > 0 ? S.cb_rb + (size_t)u * 32 + cb_off
+                                                             : S.cb_rb + (lane & 3) * 4));
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
+      const bool ok = s < np;
       const int q = u + s;
-      w[s] = make_uint4(0, 0, 0, 0);
-      xa[s] = make_uint2(0, 0);
-      xb[s] = make_uint2(0, 0);
-      if (q < S.u_pairs_end) {
-        w[s] = *reinterpret_cast<const uint4*>(S.idx_rb + (size_t)q * 1024 + lane * 16);
-        xa[s] = *reinterpret_cast<const uint2*>(S.x + (2 * q) * 256 + lane * 4);
-        xb[s] = *reinterpret_cast<const uint2*>(S.x + (2 * q + 1) * 256 + lane * 4);
-      } else if (q == S.u_pairs_end && S.tail_c >= 0) {
-        const uint2 t = *reinterpret_cast<const uint2*>(S.idx_rb + (size_t)S.n_pairs * 1024 + lane * 8);
-        w[s] = make_uint4(t.x, t.y, 0, 0);
-        xa[s] = *reinterpret_cast<const uint2*>(S.x + S.tail_c * 256 + lane * 4);
-      }
+      w[s] = *reinterpret_cast<const uint4*>(ok ? S.idx_rb + (size_t)q * 1024 + lane * 16 : dummy);
+      xa[s] = zero_unless(ok, *reinterpret_cast<const uint2*>(S.x + (ok ? (2 * q) * 256 : 0) + lane * 4));
+      xb[s] = zero_unless(ok, *reinterpret_cast<const uint2*>(S.x + (ok ? (2 * q + 1) * 256 : 0) + lane * 4));
     }
+    const int tc = has_tail ? S.tail_c : 0;
+    wt = *reinterpret_cast<const uint2*>(S.idx_rb + (has_tail ? (size_t)S.n_pairs * 1024 : 0) + lane * 8);
+    xt = zero_unless(has_tail, *reinterpret_cast<const uint2*>(S.x + tc * 256 + lane * 4));
+    cbt = S.cb_rb[tc * 16 + (lane & 15)];
   }
 
   // Stages the codebooks in this wave's table region (`lut`, LDS byte address `base`)
-  // and consumes the chunk.
+  // and consumes the chunk.  Absent pairs look up a zeroed table with zero activations.
   __device__ __forceinline__ void consume(uint32_t* lut, uint32_t base, int lane,
                                           float (&acc)[8]) const {
     if (lane < 32) *reinterpret_cast<uint4*>(lut + lane * 4) = cbv;
+    if (lane < 16) lut[128 + lane] = cbt;
     wave_lds_sync();
     k16_group<0>(w[0].x, w[0].y, base, xa[0].x, xa[0].y, acc);
     k16_group<64>(w[0].z, w[0].w, base, xb[0].x, xb[0].y, acc);
@@ -87,12 +105,14 @@ template <> struct Chunk<16> {
     k16_group<320>(w[2].z, w[2].w, base, xb[2].x, xb[2].y, acc);
     k16_group<384>(w[3].x, w[3].y, base, xa[3].x, xa[3].y, acc);
     k16_group<448>(w[3].z, w[3].w, base, xb[3].x, xb[3].y, acc);
+    if (has_tail) k16_group<512>(wt.x, wt.y, base, xt.x, xt.y, acc);
   }
 };
 
 // ---- k = 256 -------------------------------------------------------------
+// Chunk = up to 2 groups.
 template <> struct Chunk<256> {
-  static constexpr int kUnits = 2;        // groups per chunk
+  static constexpr int kUnits = 2;
   static constexpr int kLutDwords = 512;  // 2 groups x 256 centroids
   uint4 w[2];     // the lane's 16 index bytes of group u+s
   uint2 xv[2];    // its activations
@@ -101,15 +121,11 @@ template <> struct Chunk<256> {
   __device__ __forceinline__ void load(const Strip& S, int u, int lane) {
 #pragma unroll
     for (int s = 0; s < 2; ++s) {
-      const int c = u + s;
-      w[s] = make_uint4(0, 0, 0, 0);
-      xv[s] = make_uint2(0, 0);
-      cbv[s] = make_uint4(0, 0, 0, 0);
-      if (c < S.u_end) {
-        w[s] = *reinterpret_cast<const uint4*>(S.idx_rb + (size_t)c * 1024 + lane * 16);
-        cbv[s] = *reinterpret_cast<const uint4*>(S.cb_rb + (size_t)c * 256 + lane * 4);
-        xv[s] = *reinterpret_cast<const uint2*>(S.x + c * 256 + lane * 4);
-      }
+      const bool ok = u + s < S.u_end;
+      const int c = ok ? u + s : u;     // u itself is always present
+      w[s] = *reinterpret_cast<const uint4*>(S.idx_rb + (size_t)c * 1024 + lane * 16);
+      cbv[s] = zero_unless(ok, *reinterpret_cast<const uint4*>(S.cb_rb + (size_t)c * 256 + lane * 4));
+      xv[s] = zero_unless(ok, *reinterpret_cast<const uint2*>(S.x + c * 256 + lane * 4));
     }
   }
 
@@ -123,7 +139,8 @@ template <> struct Chunk<256> {
   }
 };
 
-// Strip (row-block rb, K-split `split` of `splits`) of problem P.
+// Strip (row-block rb, K-split `split` of `splits`) of problem P.  May be empty
+// (chunks_left == 0) only for k=256 splits wider than the row-block.
 template <int K>
 __device__ __forceinline__ Strip make_strip(const GemvProblem& P, int rb, int split, int splits) {
   Strip S;
@@ -134,18 +151,19 @@ __device__ __forceinline__ Strip make_strip(const GemvProblem& P, int rb, int sp
     S.idx_rb = P.idx + (size_t)rb * n_cb * 512;
     S.cb_rb = P.cb + (size_t)rb * n_cb * 16;
     S.u = (n_pairs * split) / splits;
-    S.u_pairs_end = (n_pairs * (split + 1)) / splits;
+    S.u_end = (n_pairs * (split + 1)) / splits;
     S.n_pairs = n_pairs;
     S.tail_c = ((n_cb & 1) && split == splits - 1) ? n_cb - 1 : -1;
-    S.u_end = S.u_pairs_end + (S.tail_c >= 0 ? 1 : 0);
+    S.chunks_left = (S.u_end - S.u + 3) >> 2;
+    if (S.chunks_left == 0 && S.tail_c >= 0) S.chunks_left = 1;   // a tail-only strip
   } else {
     S.idx_rb = P.idx + (size_t)rb * n_cb * 1024;
     S.cb_rb = P.cb + (size_t)rb * n_cb * 256;
     S.u = (n_cb * split) / splits;
     S.u_end = (n_cb * (split + 1)) / splits;
-    S.u_pairs_end = S.u_end;
     S.n_pairs = 0;
     S.tail_c = -1;
+    S.chunks_left = (S.u_end - S.u + 1) >> 1;
   }
   return S;
 }
@@ -170,93 +188,123 @@ __device__ __forceinline__ int find_problem(const GemvBatch& batch, int item) {
 }
 
 // ---- persistent streaming kernel (one wave per row-block) ------------------
-// Work item i of the launch = row-block (i - p.wg_begin) of problem p (here wg_begin
-// counts row-blocks).  Wave `gw` of `n_waves` handles items gw, gw + n_waves, ...
+// The launch's work is the concatenation of all row-blocks of all problems, measured
+// in groups (a row-block of problem p costs n_cb[p] groups; cost_begin[p] is the prefix
+// sum).  Wave gw of N takes the row-blocks whose first group falls in
+// [gw*C/N, (gw+1)*C/N): contiguous row-blocks, balanced to within one row-block, found
+// with one binary search per wave; moving to the next row-block is scalar arithmetic.
 template <int K>
-struct Cursor {
-  Strip S;          // strip being loaded from
+struct Loader {
+  Strip S;            // strip the next chunk is loaded from
+  const uint8_t* idx; // fields of the current problem
+  const uint32_t* cb;
+  const uint16_t* x;
   void* y;
-  int rb;
-  int item;         // current item, or >= total when exhausted
-};
+  int n_cb;
+  int pi;             // current problem
+  int rb, rb_hi;      // current row-block and end of this wave's row-blocks in the problem
+  int lo, hi;         // this wave's cost range
+  bool ok;            // false once the range is exhausted
 
-template <int K>
-__device__ __forceinline__ bool open_item(const GemvBatch& batch, Cursor<K>& C) {
-  if (C.item >= batch.total_wgs) return false;
-  const int pi = find_problem(batch, C.item);
-  const GemvProblem& P = batch.p[pi];
-  C.rb = C.item - P.wg_begin;
-  C.y = P.y;
-  C.S = make_strip<K>(P, C.rb, 0, 1);
-  return true;
-}
+  __device__ __forceinline__ void set_strip() {
+    GemvProblem P;
+    P.idx = idx; P.cb = cb; P.x = x; P.y = y; P.n_cb = n_cb;
+    S = make_strip<K>(P, rb, 0, 1);
+  }
+  // Position on the first row-block of problem `pi` (or a later one) inside [lo, hi).
+  __device__ __forceinline__ void open_problem(const GemvBatch& batch) {
+    ok = false;
+    while (pi < batch.count) {
+      const GemvProblem& P = batch.p[pi];
+      const int c0 = P.cost_begin;
+      if (c0 >= hi) return;
+      const int c1 = c0 + P.n_rb * P.n_cb;
+      const int a = max(lo, c0) - c0, b = min(hi, c1) - c0;
+      rb = (a + P.n_cb - 1) / P.n_cb;
+      rb_hi = (b + P.n_cb - 1) / P.n_cb;
+      if (rb < rb_hi) {
+        idx = P.idx; cb = P.cb; x = P.x; y = P.y; n_cb = P.n_cb;
+        set_strip();
+        ok = true;
+        return;
+      }
+      ++pi;
+    }
+  }
+  __device__ __forceinline__ void next_row_block(const GemvBatch& batch) {
+    if (++rb < rb_hi) {
+      set_strip();
+    } else {
+      ++pi;
+      open_problem(batch);
+    }
+  }
+};
 
 template <int K>
 __global__ __launch_bounds__(256) void gemv_stream_kernel(const GemvBatch batch) {
   __shared__ __attribute__((aligned(16))) uint32_t lut_all[4][2 * Chunk<K>::kLutDwords];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int n_waves = gridDim.x * 4;
+  const long long n_waves = (long long)gridDim.x * 4;
+  const long long gw = (long long)blockIdx.x * 4 + wave;
   uint32_t* lut_a = lut_all[wave];
   uint32_t* lut_b = lut_a + Chunk<K>::kLutDwords;
   const uint32_t base_a = lds_addr(lut_a), base_b = lds_addr(lut_b);
 
-  // The loader runs one chunk ahead of the consumer; both walk the same item sequence.
-  Cursor<K> L;                       // where the next load comes from
-  L.item = blockIdx.x * 4 + wave;
-  bool l_ok = open_item<K>(batch, L);
-  // consumer side: (y, rb, chunks left) of the item being consumed
-  void* c_y = L.y;
-  int c_rb = L.rb;
-  int c_left = l_ok ? (L.S.u_end - L.S.u + Chunk<K>::kUnits - 1) / Chunk<K>::kUnits : 0;
+  Loader<K> L;
+  L.lo = (int)(gw * batch.total_cost / n_waves);
+  L.hi = (int)((gw + 1) * batch.total_cost / n_waves);
+  {  // first problem whose cost range ends after lo
+    int lo_p = 0, hi_p = batch.count;
+    while (hi_p - lo_p > 1) {
+      const int mid = (lo_p + hi_p) >> 1;
+      if (batch.p[mid].cost_begin <= L.lo) lo_p = mid; else hi_p = mid;
+    }
+    L.pi = lo_p;
+  }
+  L.open_problem(batch);
 
   float acc[8];
 #pragma unroll
   for (int r = 0; r < 8; ++r) acc[r] = 0.f;
 
+  // Each buffer carries, as scalars, where its row sums go once it is the last chunk
+  // of its row-block.
   Chunk<K> A, B;
-  // helper semantics (written out twice below for the two buffers):
-  //   load next chunk of L into buffer; advance L (to the next item when the strip ends)
-#define VQ_LOAD_NEXT(BUF, OK)                                            \
+  bool a_ok, b_ok, a_last = false, b_last = false;
+  void *a_y = nullptr, *b_y = nullptr;
+  int a_rb = 0, b_rb = 0;
+
+#define VQ_LOAD_NEXT(BUF, OK, LAST, Y, RB)                               \
   do {                                                                   \
-    OK = l_ok;                                                           \
-    if (l_ok) {                                                          \
+    OK = L.ok;                                                           \
+    if (L.ok) {                                                          \
       BUF.load(L.S, L.S.u, lane);                                        \
       L.S.u += Chunk<K>::kUnits;                                         \
-      if (L.S.u >= L.S.u_end) {                                          \
-        L.item += n_waves;                                               \
-        l_ok = open_item<K>(batch, L);                                   \
-      }                                                                  \
+      LAST = --L.S.chunks_left == 0;                                     \
+      Y = L.y;                                                           \
+      RB = L.rb;                                                         \
+      if (LAST) L.next_row_block(batch);                                 \
     }                                                                    \
   } while (0)
-  //   consume a buffer; when it was the last chunk of its item: reduce, store, move on
-#define VQ_CONSUME(BUF, LUT, BASE)                                       \
+#define VQ_CONSUME(BUF, LUT, BASE, LAST, Y, RB)                          \
   do {                                                                   \
     BUF.consume(LUT, BASE, lane, acc);                                   \
-    if (--c_left == 0) {                                                 \
+    if (LAST) {                                                          \
       const float v = wave_reduce8(acc, lane);                           \
-      store_rows(c_y, batch.y_f32, c_rb, lane, v);                       \
+      store_rows(Y, batch.y_f32, RB, lane, v);                           \
       _Pragma("unroll") for (int r = 0; r < 8; ++r) acc[r] = 0.f;        \
-      c_item += n_waves;                                                 \
-      if (c_item < batch.total_wgs) {                                    \
-        const GemvProblem& Pn = batch.p[find_problem(batch, c_item)];    \
-        c_rb = c_item - Pn.wg_begin;                                     \
-        c_y = Pn.y;                                                      \
-        const Strip Sn = make_strip<K>(Pn, c_rb, 0, 1);                  \
-        c_left = (Sn.u_end - Sn.u + Chunk<K>::kUnits - 1) / Chunk<K>::kUnits; \
-      }                                                                  \
     }                                                                    \
   } while (0)
 
-  int c_item = L.item;
-  bool a_ok, b_ok;
-  VQ_LOAD_NEXT(A, a_ok);
+  VQ_LOAD_NEXT(A, a_ok, a_last, a_y, a_rb);
   while (a_ok) {
-    VQ_LOAD_NEXT(B, b_ok);
-    VQ_CONSUME(A, lut_a, base_a);
-    VQ_LOAD_NEXT(A, a_ok);
+    VQ_LOAD_NEXT(B, b_ok, b_last, b_y, b_rb);
+    VQ_CONSUME(A, lut_a, base_a, a_last, a_y, a_rb);
+    VQ_LOAD_NEXT(A, a_ok, a_last, a_y, a_rb);
     if (!b_ok) break;
-    VQ_CONSUME(B, lut_b, base_b);
+    VQ_CONSUME(B, lut_b, base_b, b_last, b_y, b_rb);
   }
 #undef VQ_LOAD_NEXT
 #undef VQ_CONSUME
@@ -287,15 +335,22 @@ __global__ __launch_bounds__(256) void gemv_split_kernel(const GemvBatch batch) 
 
   if (rb < P.n_rb) {
     Strip S = make_strip<K>(P, rb, split, splits);
-    if (S.u < S.u_end) {
+    if (S.chunks_left > 0) {
       constexpr int U = Chunk<K>::kUnits;
       Chunk<K> A, B;
       A.load(S, S.u, lane);
-      for (int u = S.u; u < S.u_end; u += 2 * U) {
-        if (u + U < S.u_end) B.load(S, u + U, lane);
+      while (true) {
+        // invariant: A holds the chunk at S.u, chunks_left counts it
+        const bool more1 = S.chunks_left > 1;
+        if (more1) { --S.chunks_left; B.load(S, S.u + U, lane); ++S.chunks_left; }
         A.consume(lut_a, base_a, lane, acc);
-        if (u + 2 * U < S.u_end) A.load(S, u + 2 * U, lane);
-        if (u + U < S.u_end) B.consume(lut_b, base_b, lane, acc);
+        if (!more1) break;
+        S.u += U; --S.chunks_left;            // B is now current
+        const bool more2 = S.chunks_left > 1;
+        if (more2) { --S.chunks_left; A.load(S, S.u + U, lane); ++S.chunks_left; }
+        B.consume(lut_b, base_b, lane, acc);
+        if (!more2) break;
+        S.u += U; --S.chunks_left;            // A is current again
       }
     }
   }

@@ -20,13 +20,15 @@ struct GemvProblem {
   int32_t n_cb;         // col-blocks  (in / 256)
   int32_t wg_begin;     // first work item of this problem inside the launch (see launch_gemv)
   int32_t splits;       // waves sharing one row-block: 1, 2 or 4
+  int32_t cost_begin;   // groups of all earlier problems of the launch (streaming kernel)
+  int32_t pad;
 };
 
 struct GemvBatch {
   int32_t count;
   int32_t y_f32;
   int32_t total_wgs;    // work items in the launch
-  int32_t pad;
+  int32_t total_cost;   // groups in the launch
   GemvProblem p[kMaxProblemsPerLaunch];
 };
 
