@@ -113,8 +113,14 @@ int vq_gemv_multi(int count, const vq_desc* descs, const void* const* idx_dev,
     const int n = count - first < kMaxProblemsPerLaunch ? count - first : kMaxProblemsPerLaunch;
     long long rb_launch = 0;
     for (int i = 0; i < n; ++i) rb_launch += descs[first + i].out_features / kGroupRows;
+    int max_n_cb = 0;
+    for (int i = 0; i < n; ++i) {
+      const int c = descs[first + i].in_features / kGroupCols;
+      if (c > max_n_cb) max_n_cb = c;
+    }
     const int splits = choose_splits(rb_launch);
-    const bool stream_mode = splits == 1;
+    const bool stream_mode = splits == 1 && max_n_cb <= kStreamMaxColBlocks &&
+                             gemv_stream_lds_bytes(descs[0].k, max_n_cb) <= 65536;
     GemvBatch batch;
     memset(&batch, 0, sizeof(batch));
     batch.count = n;
@@ -143,10 +149,11 @@ int vq_gemv_multi(int count, const vq_desc* descs, const void* const* idx_dev,
     int grid = (int)items;
     if (stream_mode) {
       const long long want = (items + 3) / 4;
-      const int resident = gemv_stream_resident_wgs(descs[0].k);
+      const int resident = gemv_stream_resident_wgs(descs[0].k, max_n_cb);
       grid = (int)(want < resident ? want : resident);
     }
-    const hipError_t e = launch_gemv(descs[0].k, batch, stream_mode ? 1 : 0, grid, (hipStream_t)stream);
+    const hipError_t e = launch_gemv(descs[0].k, batch, stream_mode ? 1 : 0, grid, max_n_cb,
+                                     (hipStream_t)stream);
     if (e != hipSuccess) return VQ_ERR_HIP;
   }
   return VQ_OK;

@@ -161,6 +161,113 @@ __device__ __forceinline__ void k256_group(uint32_t w0, uint32_t w1, uint32_t w2
 #undef VQ_BFE_RD
 #undef VQ_DOT
 
+// ---------------------------------------------------------------------------
+// Variants of the two inner blocks that fetch the lane's activations from LDS
+// themselves (two dword reads at xaddr + XOFF, issued before the table reads, so
+// they are back by the first wait).  Used by the streaming kernel, whose workgroup
+// keeps x in LDS; saves the vector-memory instructions and the registers that
+// per-chunk activation loads would cost.
+#define VQ_SDWA_RD(R, T, B)                                                               \
+  "v_add_u32_sdwa " R ", %[base], " T                                                     \
+  " dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_" #B "\n"            \
+  "ds_read_b32 " R ", " R " offset:%[off]\n"
+#define VQ_MASKS(W)                                  \
+  "v_lshlrev_b32 %[ta], 2, " W "\n"                  \
+  "v_lshrrev_b32 %[tb], 2, " W "\n"                  \
+  "v_and_b32 %[ta], 0x3c3c3c3c, %[ta]\n"             \
+  "v_and_b32 %[tb], 0x3c3c3c3c, %[tb]\n"
+#define VQ_DOT(ACC, R, X) "v_dot2c_f32_f16 " ACC ", " R ", " X "\n"
+#define VQ_XRD                                        \
+  "ds_read_b32 %[x0], %[xa] offset:%[xoff]\n"         \
+  "ds_read_b32 %[x1], %[xa] offset:%[xoff]+4\n"
+
+template <int OFF, int XOFF>
+__device__ __forceinline__ void k16_group_lx(uint32_t w0, uint32_t w1, uint32_t base,
+                                             uint32_t xaddr, float (&acc)[8]) {
+  uint32_t ta, tb, x0, x1, r0, r1, r2, r3, r4, r5, r6, r7, r8, r9;
+  asm volatile(
+      VQ_XRD
+      VQ_MASKS("%[w0]")
+      VQ_SDWA_RD("%[r0]", "%[ta]", 0) VQ_SDWA_RD("%[r1]", "%[tb]", 0)
+      VQ_SDWA_RD("%[r2]", "%[ta]", 1) VQ_SDWA_RD("%[r3]", "%[tb]", 1)
+      VQ_SDWA_RD("%[r4]", "%[ta]", 2) VQ_SDWA_RD("%[r5]", "%[tb]", 2)
+      VQ_SDWA_RD("%[r6]", "%[ta]", 3) VQ_SDWA_RD("%[r7]", "%[tb]", 3)
+      VQ_MASKS("%[w1]")
+      VQ_SDWA_RD("%[r8]", "%[ta]", 0) VQ_SDWA_RD("%[r9]", "%[tb]", 0)
+      "s_waitcnt lgkmcnt(6)\n"     // x0, x1, r0..r3 are back
+      VQ_DOT("%[a0]", "%[r0]", "%[x0]") VQ_DOT("%[a1]", "%[r2]", "%[x0]")
+      VQ_DOT("%[a0]", "%[r1]", "%[x1]") VQ_DOT("%[a1]", "%[r3]", "%[x1]")
+      VQ_SDWA_RD("%[r0]", "%[ta]", 1) VQ_SDWA_RD("%[r1]", "%[tb]", 1)
+      "s_waitcnt lgkmcnt(4)\n"     // r4..r7
+      VQ_DOT("%[a2]", "%[r4]", "%[x0]") VQ_DOT("%[a3]", "%[r6]", "%[x0]")
+      VQ_DOT("%[a2]", "%[r5]", "%[x1]") VQ_DOT("%[a3]", "%[r7]", "%[x1]")
+      VQ_SDWA_RD("%[r2]", "%[ta]", 2) VQ_SDWA_RD("%[r3]", "%[tb]", 2)
+      VQ_SDWA_RD("%[r4]", "%[ta]", 3) VQ_SDWA_RD("%[r5]", "%[tb]", 3)
+      "s_waitcnt lgkmcnt(6)\n"     // r8, r9
+      VQ_DOT("%[a4]", "%[r8]", "%[x0]") VQ_DOT("%[a4]", "%[r9]", "%[x1]")
+      "s_waitcnt lgkmcnt(4)\n"     // r0, r1
+      VQ_DOT("%[a5]", "%[r0]", "%[x0]") VQ_DOT("%[a5]", "%[r1]", "%[x1]")
+      "s_waitcnt lgkmcnt(0)\n"
+      VQ_DOT("%[a6]", "%[r2]", "%[x0]") VQ_DOT("%[a7]", "%[r4]", "%[x0]")
+      VQ_DOT("%[a6]", "%[r3]", "%[x1]") VQ_DOT("%[a7]", "%[r5]", "%[x1]")
+      "s_nop 2\n"
+      : [a0] "+v"(acc[0]), [a1] "+v"(acc[1]), [a2] "+v"(acc[2]), [a3] "+v"(acc[3]),
+        [a4] "+v"(acc[4]), [a5] "+v"(acc[5]), [a6] "+v"(acc[6]), [a7] "+v"(acc[7]),
+        [ta] "=&v"(ta), [tb] "=&v"(tb), [x0] "=&v"(x0), [x1] "=&v"(x1), [r0] "=&v"(r0),
+        [r1] "=&v"(r1), [r2] "=&v"(r2), [r3] "=&v"(r3), [r4] "=&v"(r4), [r5] "=&v"(r5),
+        [r6] "=&v"(r6), [r7] "=&v"(r7), [r8] "=&v"(r8), [r9] "=&v"(r9)
+      : [w0] "v"(w0), [w1] "v"(w1), [base] "s"(base), [xa] "v"(xaddr), [off] "n"(OFF),
+        [xoff] "n"(XOFF)
+      : "memory");
+}
+#undef VQ_SDWA_RD
+#undef VQ_MASKS
+
+#define VQ_BFE_RD(R, W, BIT)                             \
+  "v_bfe_u32 " R ", " W ", " #BIT ", 8\n"                \
+  "v_lshl_add_u32 " R ", " R ", 2, %[base]\n"            \
+  "ds_read_b32 " R ", " R " offset:%[off]\n"
+
+template <int OFF, int XOFF>
+__device__ __forceinline__ void k256_group_lx(uint32_t w0, uint32_t w1, uint32_t w2, uint32_t w3,
+                                              uint32_t base, uint32_t xaddr, float (&acc)[8]) {
+  uint32_t x0, x1, r0, r1, r2, r3, r4, r5, r6, r7, r8, r9, r10, r11;
+  asm volatile(
+      VQ_XRD
+      VQ_BFE_RD("%[r0]", "%[w0]", 0) VQ_BFE_RD("%[r1]", "%[w0]", 8)
+      VQ_BFE_RD("%[r2]", "%[w0]", 16) VQ_BFE_RD("%[r3]", "%[w0]", 24)
+      VQ_BFE_RD("%[r4]", "%[w1]", 0) VQ_BFE_RD("%[r5]", "%[w1]", 8)
+      VQ_BFE_RD("%[r6]", "%[w1]", 16) VQ_BFE_RD("%[r7]", "%[w1]", 24)
+      VQ_BFE_RD("%[r8]", "%[w2]", 0) VQ_BFE_RD("%[r9]", "%[w2]", 8)
+      VQ_BFE_RD("%[r10]", "%[w2]", 16) VQ_BFE_RD("%[r11]", "%[w2]", 24)
+      "s_waitcnt lgkmcnt(8)\n"
+      VQ_DOT("%[a0]", "%[r0]", "%[x0]") VQ_DOT("%[a1]", "%[r2]", "%[x0]")
+      VQ_DOT("%[a0]", "%[r1]", "%[x1]") VQ_DOT("%[a1]", "%[r3]", "%[x1]")
+      VQ_BFE_RD("%[r0]", "%[w3]", 0) VQ_BFE_RD("%[r1]", "%[w3]", 8)
+      VQ_BFE_RD("%[r2]", "%[w3]", 16) VQ_BFE_RD("%[r3]", "%[w3]", 24)
+      "s_waitcnt lgkmcnt(8)\n"
+      VQ_DOT("%[a2]", "%[r4]", "%[x0]") VQ_DOT("%[a3]", "%[r6]", "%[x0]")
+      VQ_DOT("%[a2]", "%[r5]", "%[x1]") VQ_DOT("%[a3]", "%[r7]", "%[x1]")
+      "s_waitcnt lgkmcnt(4)\n"
+      VQ_DOT("%[a4]", "%[r8]", "%[x0]") VQ_DOT("%[a5]", "%[r10]", "%[x0]")
+      VQ_DOT("%[a4]", "%[r9]", "%[x1]") VQ_DOT("%[a5]", "%[r11]", "%[x1]")
+      "s_waitcnt lgkmcnt(0)\n"
+      VQ_DOT("%[a6]", "%[r0]", "%[x0]") VQ_DOT("%[a7]", "%[r2]", "%[x0]")
+      VQ_DOT("%[a6]", "%[r1]", "%[x1]") VQ_DOT("%[a7]", "%[r3]", "%[x1]")
+      "s_nop 2\n"
+      : [a0] "+v"(acc[0]), [a1] "+v"(acc[1]), [a2] "+v"(acc[2]), [a3] "+v"(acc[3]),
+        [a4] "+v"(acc[4]), [a5] "+v"(acc[5]), [a6] "+v"(acc[6]), [a7] "+v"(acc[7]),
+        [x0] "=&v"(x0), [x1] "=&v"(x1), [r0] "=&v"(r0), [r1] "=&v"(r1), [r2] "=&v"(r2),
+        [r3] "=&v"(r3), [r4] "=&v"(r4), [r5] "=&v"(r5), [r6] "=&v"(r6), [r7] "=&v"(r7),
+        [r8] "=&v"(r8), [r9] "=&v"(r9), [r10] "=&v"(r10), [r11] "=&v"(r11)
+      : [w0] "v"(w0), [w1] "v"(w1), [w2] "v"(w2), [w3] "v"(w3), [base] "s"(base),
+        [xa] "v"(xaddr), [off] "n"(OFF), [xoff] "n"(XOFF)
+      : "memory");
+}
+#undef VQ_BFE_RD
+#undef VQ_DOT
+#undef VQ_XRD
+
 // Byte offset of lane `lane`'s 8-byte share of 4-bit group (row-block base + ...).
 __device__ __forceinline__ size_t k16_chunk_offset(int c, int n_cb, int lane) {
   const int n_pairs = n_cb >> 1;

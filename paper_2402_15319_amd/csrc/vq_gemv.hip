@@ -13,10 +13,10 @@
 // consume step is branch-free.
 //
 // Two kernels share this code:
-//   * gemv_stream_kernel (splits == 1): a persistent grid; every wave walks a
-//     list of whole row-blocks, possibly across several matrices, and the first
-//     chunk of its next row-block is already loading while the last chunk of
-//     the current one is consumed.
+//   * gemv_stream_kernel (many row-blocks): a persistent grid; a workgroup owns a
+//     contiguous, cost-balanced run of row-blocks, possibly across several
+//     matrices, keeps x in LDS, and each of its waves has the first chunk of its
+//     next row-block loading while the last chunk of the current one is consumed.
 //   * gemv_split_kernel (few row-blocks): one workgroup per `4/splits`
 //     row-blocks; `splits` waves share a row-block and their partial sums meet
 //     in LDS in a fixed order, so the result is deterministic.
@@ -187,127 +187,229 @@ __device__ __forceinline__ int find_problem(const GemvBatch& batch, int item) {
   return lo;
 }
 
-// ---- persistent streaming kernel (one wave per row-block) ------------------
-// The launch's work is the concatenation of all row-blocks of all problems, measured
-// in groups (a row-block of problem p costs n_cb[p] groups; cost_begin[p] is the prefix
-// sum).  Wave gw of N takes the row-blocks whose first group falls in
-// [gw*C/N, (gw+1)*C/N): contiguous row-blocks, balanced to within one row-block, found
-// with one binary search per wave; moving to the next row-block is scalar arithmetic.
-template <int K>
-struct Loader {
-  Strip S;            // strip the next chunk is loaded from
-  const uint8_t* idx; // fields of the current problem
-  const uint32_t* cb;
-  const uint16_t* x;
-  void* y;
-  int n_cb;
-  int pi;             // current problem
-  int rb, rb_hi;      // current row-block and end of this wave's row-blocks in the problem
-  int lo, hi;         // this wave's cost range
-  bool ok;            // false once the range is exhausted
+// ---- persistent streaming kernel -------------------------------------------
+// The launch's work is the concatenation of all row-blocks of all problems, measured in
+// groups (a row-block of problem p costs n_cb[p] groups; cost_begin[p] is the prefix
+// sum).  Workgroup g of G takes the row-blocks whose first group falls in
+// [g*C/G, (g+1)*C/G): contiguous row-blocks, balanced to within one row-block.  Inside
+// a problem the workgroup keeps x in LDS (staged once), and its 4 waves draw row-blocks
+// from an LDS counter, so a wave that finishes early takes the next one.  Each wave
+// keeps two chunk buffers in flight across row-block boundaries.
+//
+// Chunks of the streaming kernel hold no activations: the inner blocks read them from
+// LDS.  Index and codebook loads are non-temporal (each byte is used once).
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint4 stream_load16(const void* p) {
+  const u32x4_t t = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
+  return make_uint4(t.x, t.y, t.z, t.w);
+}
+__device__ __forceinline__ uint2 stream_load8(const void* p) {
+  const u32x2_t t = __builtin_nontemporal_load(reinterpret_cast<const u32x2_t*>(p));
+  return make_uint2(t.x, t.y);
+}
 
-  __device__ __forceinline__ void set_strip() {
-    GemvProblem P;
-    P.idx = idx; P.cb = cb; P.x = x; P.y = y; P.n_cb = n_cb;
-    S = make_strip<K>(P, rb, 0, 1);
+template <int K> struct ChunkS;
+
+template <> struct ChunkS<16> {
+  static constexpr int kUnits = 4;
+  static constexpr int kLutDwords = 144;
+  uint4 w[4];
+  uint4 cbv;
+  uint2 wt;
+  uint32_t cbt;
+  // wave-uniform description of what was loaded
+  int np;          // pairs present (0..4)
+  int u0;          // first pair (locates the activations in LDS)
+  int tail_c;      // col-block of the tail group carried by this chunk, or -1
+
+  __device__ __forceinline__ void load(const Strip& S, int u, int lane) {
+    np = min(4, S.u_end - u);
+    u0 = u;
+    tail_c = (S.tail_c >= 0 && S.chunks_left == 1) ? S.tail_c : -1;
+    const int cb_off = min(lane * 4, max(np * 32 - 4, 0));
+    const uint8_t* dummy = S.idx_rb + (lane & 31) * 16;
+    cbv = stream_load16(np > 0 ? S.cb_rb + (size_t)u * 32 + cb_off : S.cb_rb + (lane & 3) * 4);
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+      w[s] = stream_load16(s < np ? S.idx_rb + (size_t)(u + s) * 1024 + lane * 16 : dummy);
+    const int tc = tail_c >= 0 ? tail_c : 0;
+    wt = stream_load8(S.idx_rb + (tail_c >= 0 ? (size_t)S.n_pairs * 1024 : 0) + lane * 8);
+    cbt = S.cb_rb[tc * 16 + (lane & 15)];
   }
-  // Position on the first row-block of problem `pi` (or a later one) inside [lo, hi).
-  __device__ __forceinline__ void open_problem(const GemvBatch& batch) {
-    ok = false;
-    while (pi < batch.count) {
-      const GemvProblem& P = batch.p[pi];
-      const int c0 = P.cost_begin;
-      if (c0 >= hi) return;
-      const int c1 = c0 + P.n_rb * P.n_cb;
-      const int a = max(lo, c0) - c0, b = min(hi, c1) - c0;
-      rb = (a + P.n_cb - 1) / P.n_cb;
-      rb_hi = (b + P.n_cb - 1) / P.n_cb;
-      if (rb < rb_hi) {
-        idx = P.idx; cb = P.cb; x = P.x; y = P.y; n_cb = P.n_cb;
-        set_strip();
-        ok = true;
-        return;
-      }
-      ++pi;
-    }
-  }
-  __device__ __forceinline__ void next_row_block(const GemvBatch& batch) {
-    if (++rb < rb_hi) {
-      set_strip();
+
+  // x_lds: LDS byte address of the workgroup's copy of x.
+  __device__ __forceinline__ void consume(uint32_t* lut, uint32_t base, uint32_t x_lds, int lane,
+                                          float (&acc)[8]) const {
+    if (lane < 32) *reinterpret_cast<uint4*>(lut + lane * 4) = cbv;
+    if (lane < 16) lut[128 + lane] = cbt;
+    wave_lds_sync();
+    const uint32_t xa = x_lds + u0 * 1024 + lane * 8;   // pair p starts at column 512 p
+    if (np == 4) {
+      k16_group_lx<0, 0>(w[0].x, w[0].y, base, xa, acc);
+      k16_group_lx<64, 512>(w[0].z, w[0].w, base, xa, acc);
+      k16_group_lx<128, 1024>(w[1].x, w[1].y, base, xa, acc);
+      k16_group_lx<192, 1536>(w[1].z, w[1].w, base, xa, acc);
+      k16_group_lx<256, 2048>(w[2].x, w[2].y, base, xa, acc);
+      k16_group_lx<320, 2560>(w[2].z, w[2].w, base, xa, acc);
+      k16_group_lx<384, 3072>(w[3].x, w[3].y, base, xa, acc);
+      k16_group_lx<448, 3584>(w[3].z, w[3].w, base, xa, acc);
     } else {
-      ++pi;
-      open_problem(batch);
+      if (np > 0) {
+        k16_group_lx<0, 0>(w[0].x, w[0].y, base, xa, acc);
+        k16_group_lx<64, 512>(w[0].z, w[0].w, base, xa, acc);
+      }
+      if (np > 1) {
+        k16_group_lx<128, 1024>(w[1].x, w[1].y, base, xa, acc);
+        k16_group_lx<192, 1536>(w[1].z, w[1].w, base, xa, acc);
+      }
+      if (np > 2) {
+        k16_group_lx<256, 2048>(w[2].x, w[2].y, base, xa, acc);
+        k16_group_lx<320, 2560>(w[2].z, w[2].w, base, xa, acc);
+      }
     }
+    if (tail_c >= 0) {
+      const uint32_t xt = x_lds + tail_c * 512 + lane * 8;
+      k16_group_lx<512, 0>(wt.x, wt.y, base, xt, acc);
+    }
+  }
+};
+
+template <> struct ChunkS<256> {
+  static constexpr int kUnits = 2;
+  static constexpr int kLutDwords = 512;
+  uint4 w[2];
+  uint4 cbv[2];
+  int ng;          // groups present (1..2)
+  int u0;          // first col-block
+
+  __device__ __forceinline__ void load(const Strip& S, int u, int lane) {
+    ng = min(2, S.u_end - u);
+    u0 = u;
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+      const int c = s < ng ? u + s : 0;     // an absent group re-reads col-block 0
+      w[s] = stream_load16(S.idx_rb + (size_t)c * 1024 + lane * 16);
+      cbv[s] = stream_load16(S.cb_rb + (size_t)c * 256 + lane * 4);
+    }
+  }
+
+  __device__ __forceinline__ void consume(uint32_t* lut, uint32_t base, uint32_t x_lds, int lane,
+                                          float (&acc)[8]) const {
+    *reinterpret_cast<uint4*>(lut + lane * 4) = cbv[0];
+    *reinterpret_cast<uint4*>(lut + 256 + lane * 4) = cbv[1];
+    wave_lds_sync();
+    const uint32_t xa = x_lds + u0 * 512 + lane * 8;
+    k256_group_lx<0, 0>(w[0].x, w[0].y, w[0].z, w[0].w, base, xa, acc);
+    if (ng > 1) k256_group_lx<1024, 512>(w[1].x, w[1].y, w[1].z, w[1].w, base, xa, acc);
   }
 };
 
 template <int K>
 __global__ __launch_bounds__(256) void gemv_stream_kernel(const GemvBatch batch) {
-  __shared__ __attribute__((aligned(16))) uint32_t lut_all[4][2 * Chunk<K>::kLutDwords];
+  // dynamic LDS: [4 waves x 2 table regions][row-block counter][x of the current problem]
+  extern __shared__ __attribute__((aligned(16))) uint32_t smem[];
+  constexpr int kLut = ChunkS<K>::kLutDwords;
+  uint32_t* const counter = smem + 4 * 2 * kLut;          // 4 dwords reserved
+  uint32_t* const x_s = counter + 4;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const long long n_waves = (long long)gridDim.x * 4;
-  const long long gw = (long long)blockIdx.x * 4 + wave;
-  uint32_t* lut_a = lut_all[wave];
-  uint32_t* lut_b = lut_a + Chunk<K>::kLutDwords;
-  const uint32_t base_a = lds_addr(lut_a), base_b = lds_addr(lut_b);
+  uint32_t* lut_a = smem + wave * 2 * kLut;
+  uint32_t* lut_b = lut_a + kLut;
+  const uint32_t base_a = lds_addr(lut_a), base_b = lds_addr(lut_b), x_lds = lds_addr(x_s);
 
-  Loader<K> L;
-  L.lo = (int)(gw * batch.total_cost / n_waves);
-  L.hi = (int)((gw + 1) * batch.total_cost / n_waves);
-  {  // first problem whose cost range ends after lo
+  const int lo = (int)((long long)blockIdx.x * batch.total_cost / gridDim.x);
+  const int hi = (int)((long long)(blockIdx.x + 1) * batch.total_cost / gridDim.x);
+  int pi;
+  {  // last problem that starts at or before lo
     int lo_p = 0, hi_p = batch.count;
     while (hi_p - lo_p > 1) {
       const int mid = (lo_p + hi_p) >> 1;
-      if (batch.p[mid].cost_begin <= L.lo) lo_p = mid; else hi_p = mid;
+      if (batch.p[mid].cost_begin <= lo) lo_p = mid; else hi_p = mid;
     }
-    L.pi = lo_p;
+    pi = lo_p;
   }
-  L.open_problem(batch);
 
   float acc[8];
 #pragma unroll
   for (int r = 0; r < 8; ++r) acc[r] = 0.f;
 
-  // Each buffer carries, as scalars, where its row sums go once it is the last chunk
-  // of its row-block.
-  Chunk<K> A, B;
-  bool a_ok, b_ok, a_last = false, b_last = false;
-  void *a_y = nullptr, *b_y = nullptr;
-  int a_rb = 0, b_rb = 0;
+  for (; pi < batch.count; ++pi) {
+    const GemvProblem& P = batch.p[pi];
+    const int c0 = P.cost_begin;
+    if (c0 >= hi) break;
+    const int n_cb = P.n_cb;
+    const int c1 = c0 + P.n_rb * n_cb;
+    const int rb_lo = (max(lo, c0) - c0 + n_cb - 1) / n_cb;
+    const int rb_hi = (min(hi, c1) - c0 + n_cb - 1) / n_cb;
+    if (rb_lo >= rb_hi) continue;
 
-#define VQ_LOAD_NEXT(BUF, OK, LAST, Y, RB)                               \
-  do {                                                                   \
-    OK = L.ok;                                                           \
-    if (L.ok) {                                                          \
-      BUF.load(L.S, L.S.u, lane);                                        \
-      L.S.u += Chunk<K>::kUnits;                                         \
-      LAST = --L.S.chunks_left == 0;                                     \
-      Y = L.y;                                                           \
-      RB = L.rb;                                                         \
-      if (LAST) L.next_row_block(batch);                                 \
-    }                                                                    \
-  } while (0)
-#define VQ_CONSUME(BUF, LUT, BASE, LAST, Y, RB)                          \
-  do {                                                                   \
-    BUF.consume(LUT, BASE, lane, acc);                                   \
-    if (LAST) {                                                          \
-      const float v = wave_reduce8(acc, lane);                           \
-      store_rows(Y, batch.y_f32, RB, lane, v);                           \
-      _Pragma("unroll") for (int r = 0; r < 8; ++r) acc[r] = 0.f;        \
-    }                                                                    \
-  } while (0)
+    // ---- the workgroup enters problem pi: stage x, reset the row-block counter
+    __syncthreads();                       // everyone is done with the previous x
+    {
+      const uint4* xg = reinterpret_cast<const uint4*>(P.x);
+      uint4* xl = reinterpret_cast<uint4*>(x_s);
+      const int n16 = n_cb * 32;           // 256 halfs = 32 x 16 bytes per col-block
+      for (int i = threadIdx.x; i < n16; i += 256) xl[i] = xg[i];
+      if (threadIdx.x == 0) counter[0] = rb_lo + 4;   // waves start on rb_lo + wave
+    }
+    __syncthreads();
 
-  VQ_LOAD_NEXT(A, a_ok, a_last, a_y, a_rb);
-  while (a_ok) {
-    VQ_LOAD_NEXT(B, b_ok, b_last, b_y, b_rb);
-    VQ_CONSUME(A, lut_a, base_a, a_last, a_y, a_rb);
-    VQ_LOAD_NEXT(A, a_ok, a_last, a_y, a_rb);
-    if (!b_ok) break;
-    VQ_CONSUME(B, lut_b, base_b, b_last, b_y, b_rb);
-  }
+    // ---- per-wave pipeline over row-blocks drawn from the counter
+    int l_rb = rb_lo + wave;
+    bool l_ok = l_rb < rb_hi;
+    Strip S = make_strip<K>(P, l_ok ? l_rb : rb_lo, 0, 1);
+    if (!l_ok) {              // park on a valid row-block with nothing left to load
+      S.u = S.u_end;
+      S.chunks_left = 0;
+    }
+    void* const y = P.y;
+
+    ChunkS<K> A, B;
+    bool a_ok, b_ok, a_last = false, b_last = false;
+    int a_rb = 0, b_rb = 0;
+
+    // The loads are issued whether or not a chunk is left (an exhausted strip makes them
+    // harmless dummy reads): a branch around them would hide the number of loads in
+    // flight from the compiler, which would then wait for all of them before every use.
+#define VQ_LOAD_NEXT(BUF, OK, LAST, RB)                                          \
+    do {                                                                         \
+      OK = l_ok;                                                                 \
+      BUF.load(S, S.u, lane);                                                    \
+      if (l_ok) {                                                                \
+        S.u += ChunkS<K>::kUnits;                                                \
+        LAST = --S.chunks_left == 0;                                             \
+        RB = l_rb;                                                               \
+        if (LAST) {                                                              \
+          uint32_t nxt = 0;                                                      \
+          if (lane == 0) nxt = atomicAdd(counter, 1u);                           \
+          l_rb = __builtin_amdgcn_readfirstlane(nxt);                            \
+          l_ok = l_rb < rb_hi;                                                   \
+          if (l_ok) S = make_strip<K>(P, l_rb, 0, 1);                            \
+        }                                                                        \
+      }                                                                          \
+    } while (0)
+#define VQ_CONSUME(BUF, LUT, BASE, LAST, RB)                                     \
+    do {                                                                         \
+      BUF.consume(LUT, BASE, x_lds, lane, acc);                                  \
+      if (LAST) {                                                                \
+        const float v = wave_reduce8(acc, lane);                                 \
+        store_rows(y, batch.y_f32, RB, lane, v);                                 \
+        _Pragma("unroll") for (int r = 0; r < 8; ++r) acc[r] = 0.f;              \
+      }                                                                          \
+    } while (0)
+
+    VQ_LOAD_NEXT(A, a_ok, a_last, a_rb);
+    while (a_ok) {
+      VQ_LOAD_NEXT(B, b_ok, b_last, b_rb);
+      VQ_CONSUME(A, lut_a, base_a, a_last, a_rb);
+      VQ_LOAD_NEXT(A, a_ok, a_last, a_rb);
+      if (!b_ok) break;
+      VQ_CONSUME(B, lut_b, base_b, b_last, b_rb);
+    }
 #undef VQ_LOAD_NEXT
 #undef VQ_CONSUME
+  }
 }
 
 // ---- split-K kernel (few row-blocks) ---------------------------------------
@@ -374,19 +476,26 @@ __global__ __launch_bounds__(256) void gemv_split_kernel(const GemvBatch batch) 
 
 }  // namespace
 
-int gemv_stream_resident_wgs(int k) {
-  // Occupancy of the persistent kernel, asked once per device and kernel (a pure function
-  // of the code object and the device; caching it keeps the hot path free of runtime queries).
-  static int cached[2][16];
+size_t gemv_stream_lds_bytes(int k, int max_n_cb) {
+  const size_t lut = (size_t)4 * 2 * (k == 16 ? ChunkS<16>::kLutDwords : ChunkS<256>::kLutDwords) * 4;
+  return lut + 16 + (size_t)max_n_cb * 512;
+}
+
+int gemv_stream_resident_wgs(int k, int max_n_cb) {
+  // Occupancy of the persistent kernel for this LDS size, asked once per (device, k, size):
+  // a pure function of the code object and the device, cached so that the hot path makes
+  // no runtime queries.  Benign if two threads fill the same slot at once.
+  static int cached[2][16][kStreamMaxColBlocks + 1];
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) dev = 0;
-  int& slot = cached[k == 16 ? 0 : 1][dev];
+  int& slot = cached[k == 16 ? 0 : 1][dev][max_n_cb];
   if (slot == 0) {
     int per_cu = 0, cus = 0;
+    const size_t lds = gemv_stream_lds_bytes(k, max_n_cb);
     hipError_t e = k == 16
-        ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gemv_stream_kernel<16>, 256, 0)
-        : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gemv_stream_kernel<256>, 256, 0);
-    if (e != hipSuccess || per_cu < 1) per_cu = 2;
+        ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gemv_stream_kernel<16>, 256, lds)
+        : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gemv_stream_kernel<256>, 256, lds);
+    if (e != hipSuccess || per_cu < 1) per_cu = 1;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
       cus = 256;
     (void)hipGetLastError();
@@ -396,11 +505,12 @@ int gemv_stream_resident_wgs(int k) {
 }
 
 hipError_t launch_gemv(int k, const GemvBatch& batch, int stream_mode, int grid_wgs,
-                       hipStream_t s) {
+                       int max_n_cb, hipStream_t s) {
   const dim3 grid(grid_wgs), block(256);
   if (stream_mode) {
-    if (k == 16) hipLaunchKernelGGL(gemv_stream_kernel<16>, grid, block, 0, s, batch);
-    else hipLaunchKernelGGL(gemv_stream_kernel<256>, grid, block, 0, s, batch);
+    const size_t lds = gemv_stream_lds_bytes(k, max_n_cb);
+    if (k == 16) hipLaunchKernelGGL(gemv_stream_kernel<16>, grid, block, lds, s, batch);
+    else hipLaunchKernelGGL(gemv_stream_kernel<256>, grid, block, lds, s, batch);
   } else {
     if (k == 16) hipLaunchKernelGGL(gemv_split_kernel<16>, grid, block, 0, s, batch);
     else hipLaunchKernelGGL(gemv_split_kernel<256>, grid, block, 0, s, batch);
