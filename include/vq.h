@@ -76,8 +76,11 @@ VQ_API int vq_version(void);
 /*
  * Sizes in bytes of the canonical arrays and of the device-layout arrays for
  * `desc` (host pointers; any output pointer may be NULL).  By Sec. 4's
- * bits-per-value formula (idx + cb) * 8 / (out*in) = log2(k)/d + k*d*16/(rows*cols);
- * the device layout adds no padding, so both pairs are equal.
+ * bits-per-value formula the canonical pair obeys
+ * (idx + cb) * 8 / (out*in) = log2(k)/d + k*d*16/(rows*cols).  The device layout
+ * is as large, except that 4-bit row-blocks with an odd number of 256-column
+ * blocks are padded to a whole pair of blocks (one zero group and one zero
+ * codebook per row-block: +2.3 % for in = 11008).
  */
 VQ_API int vq_canonical_bytes(const vq_desc* desc, size_t* idx_bytes, size_t* cb_bytes);
 VQ_API int vq_layout_bytes(const vq_desc* desc, size_t* idx_bytes, size_t* cb_bytes);

@@ -79,7 +79,12 @@ int vq_canonical_bytes(const vq_desc* desc, size_t* idx_bytes, size_t* cb_bytes)
 int vq_layout_bytes(const vq_desc* desc, size_t* idx_bytes, size_t* cb_bytes) {
   const int st = check_desc(desc);
   if (st != VQ_OK) return st;
-  sizes(*desc, idx_bytes, cb_bytes);
+  // 4-bit row-blocks are stored as whole col-block pairs (an odd last one is padded)
+  const size_t n_rb = desc->out_features / kGroupRows;
+  const size_t n_cb = desc->in_features / kGroupCols;
+  const size_t slots = desc->k == 16 ? 2 * ((n_cb + 1) / 2) : n_cb;
+  if (idx_bytes) *idx_bytes = n_rb * slots * (1024 * (size_t)desc->index_bits / 8);
+  if (cb_bytes) *cb_bytes = n_rb * slots * (size_t)desc->k * 4;
   return VQ_OK;
 }
 

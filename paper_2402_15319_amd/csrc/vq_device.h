@@ -4,16 +4,21 @@
 // Device layout of the packed indices (what vq_pack_layout writes).  A group is
 // 8 rows x 128 vectors.  Lane L of a wave owns the two vectors 2L, 2L+1 of every
 // row of a group, so that its activations (x[4L..4L+3] of the group's columns)
-// stay in two registers and one lane keeps 8 row accumulators.
-//   4-bit (k=16): a lane's share of a group is 8 bytes, byte r = row r,
-//     low nibble = vector 2L, high nibble = vector 2L+1 (= canonical byte
-//     r*64 + L of the group).  Two horizontally adjacent groups (col-blocks
-//     2p, 2p+1 of one row-block) are interleaved per lane: 16 bytes per lane,
-//     1 KB per wave-wide 128-bit load.  If the number of col-blocks is odd the
-//     last group of the row-block follows as 64 x 8 bytes.
+// are two dwords and one lane keeps 8 row accumulators.
+//   4-bit (k=16): a lane's share of a group is 8 bytes = 2 dwords of 4 rows each.
+//     Inside a dword, row b's two indices lo (vector 2L) and hi (vector 2L+1) are
+//     stored pre-scaled for the table lookup: bits [8b+5:8b+2] = lo, bits
+//     [8b+7:8b+6] = hi[1:0], bits [8b'+1:8b'] = hi[3:2] with b' = (b+1) mod 4.  Then
+//     w & 0x3c3c3c3c holds 4*lo in every byte and ror(w,4) & 0x3c3c3c3c holds 4*hi:
+//     three VALU instructions per 8 indices.  Two horizontally adjacent groups
+//     (col-blocks 2p, 2p+1 of one row-block) are interleaved per lane: 16 bytes per
+//     lane, 1 KB per wave-wide 128-bit load.  A row-block always holds
+//     ceil(n_cb/2) such pairs: if the number of col-blocks is odd, the missing
+//     group is stored as zero indices with an all-zero codebook, so it adds
+//     exactly 0 and no kernel needs a special case.
 //   8-bit (k=256): a lane's share is 16 bytes, byte 2r+e = row r, vector 2L+e
 //     (= canonical byte r*128 + 2L + e); one group per wave-wide 128-bit load.
-// Codebooks keep the canonical order (one dword per centroid).
+// Codebooks keep the canonical order (one dword per centroid), padded as above.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -54,10 +59,10 @@ __device__ __forceinline__ void wave_lds_sync() {
 //   x0, x1   fp16 pairs of the activations of vectors 2L and 2L+1
 //   acc      the 8 row accumulators (fp32)
 //
-// Per dword, (w << 2) & 0x3c3c3c3c and (w >> 2) & 0x3c3c3c3c leave index*4 of the
-// low / high nibbles in the four bytes; one SDWA add per lookup then picks a byte
-// and adds the table base, and the table offset rides in the ds_read immediate:
-// 2.5 VALU instructions per vector including the dot2.  LDS reads are kept 8-12
+// Per dword, w & 0x3c3c3c3c and ror(w, 4) & 0x3c3c3c3c leave index*4 of the two
+// vectors of each row in the four bytes (see the layout above); one SDWA add per
+// lookup then picks a byte and adds the table base, and the table offset rides in
+// the ds_read immediate: 2.4 VALU instructions per vector including the dot2.  LDS reads are kept 8-12
 // deep ahead of the dot products (lgkmcnt is a 4-bit counter).  The trailing
 // s_nop covers the dot-result-read-by-other-VALU wait states, which the
 // compiler cannot see inside an asm statement.
@@ -66,9 +71,8 @@ __device__ __forceinline__ void wave_lds_sync() {
   " dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_" #B "\n"            \
   "ds_read_b32 " R ", " R " offset:" OFF "\n"
 #define VQ_MASKS(W)                                  \
-  "v_lshlrev_b32 %[ta], 2, " W "\n"                  \
-  "v_lshrrev_b32 %[tb], 2, " W "\n"                  \
-  "v_and_b32 %[ta], 0x3c3c3c3c, %[ta]\n"             \
+  "v_and_b32 %[ta], 0x3c3c3c3c, " W "\n"             \
+  "v_alignbit_b32 %[tb], " W ", " W ", 4\n"          \
   "v_and_b32 %[tb], 0x3c3c3c3c, %[tb]\n"
 #define VQ_DOT(ACC, R, X) "v_dot2c_f32_f16 " ACC ", " R ", " X "\n"
 
@@ -163,8 +167,8 @@ __device__ __forceinline__ void k256_group(uint32_t w0, uint32_t w1, uint32_t w2
 
 // ---------------------------------------------------------------------------
 // Variants of the two inner blocks that fetch the lane's activations from LDS
-// themselves (two dword reads at xaddr + XOFF, issued before the table reads, so
-// they are back by the first wait).  Used by the streaming kernel, whose workgroup
+// themselves (two dword reads, at xaddr + XOFF and xaddr + XOFF + 256: the two planes
+// of a col-block, issued before the table reads, so they are back by the first wait).  Used by the streaming kernel, whose workgroup
 // keeps x in LDS; saves the vector-memory instructions and the registers that
 // per-chunk activation loads would cost.
 #define VQ_SDWA_RD(R, T, B)                                                               \
@@ -172,14 +176,13 @@ __device__ __forceinline__ void k256_group(uint32_t w0, uint32_t w1, uint32_t w2
   " dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_" #B "\n"            \
   "ds_read_b32 " R ", " R " offset:%[off]\n"
 #define VQ_MASKS(W)                                  \
-  "v_lshlrev_b32 %[ta], 2, " W "\n"                  \
-  "v_lshrrev_b32 %[tb], 2, " W "\n"                  \
-  "v_and_b32 %[ta], 0x3c3c3c3c, %[ta]\n"             \
+  "v_and_b32 %[ta], 0x3c3c3c3c, " W "\n"             \
+  "v_alignbit_b32 %[tb], " W ", " W ", 4\n"          \
   "v_and_b32 %[tb], 0x3c3c3c3c, %[tb]\n"
 #define VQ_DOT(ACC, R, X) "v_dot2c_f32_f16 " ACC ", " R ", " X "\n"
 #define VQ_XRD                                        \
   "ds_read_b32 %[x0], %[xa] offset:%[xoff]\n"         \
-  "ds_read_b32 %[x1], %[xa] offset:%[xoff]+4\n"
+  "ds_read_b32 %[x1], %[xa] offset:%[xoff]+256\n"
 
 template <int OFF, int XOFF>
 __device__ __forceinline__ void k16_group_lx(uint32_t w0, uint32_t w1, uint32_t base,
@@ -268,11 +271,29 @@ __device__ __forceinline__ void k256_group_lx(uint32_t w0, uint32_t w1, uint32_t
 #undef VQ_DOT
 #undef VQ_XRD
 
-// Byte offset of lane `lane`'s 8-byte share of 4-bit group (row-block base + ...).
-__device__ __forceinline__ size_t k16_chunk_offset(int c, int n_cb, int lane) {
-  const int n_pairs = n_cb >> 1;
-  if (c < 2 * n_pairs) return (size_t)(c >> 1) * 1024 + lane * 16 + (c & 1) * 8;
-  return (size_t)n_pairs * 1024 + lane * 8;
+// Pairs of col-blocks a k=16 row-block is stored as (the last one half-empty if n_cb is odd).
+__host__ __device__ __forceinline__ int k16_pairs(int n_cb) { return (n_cb + 1) >> 1; }
+
+// Byte offset, inside its row-block, of lane `lane`'s 8-byte share of 4-bit group c.
+__device__ __forceinline__ size_t k16_chunk_offset(int c, int lane) {
+  return (size_t)(c >> 1) * 1024 + lane * 16 + (c & 1) * 8;
+}
+
+// One device dword of 4-bit indices from its 4 (lo, hi) index pairs, and back to
+// "4*index per byte" form (a: the lo indices, b: the hi indices).
+__device__ __forceinline__ uint32_t k16_encode_dword(const uint32_t lo[4], const uint32_t hi[4]) {
+  uint32_t w = 0;
+#pragma unroll
+  for (int b = 0; b < 4; ++b) {
+    w |= (lo[b] << 2) << (8 * b);
+    w |= (hi[b] & 3u) << (8 * b + 6);
+    w |= (hi[b] >> 2) << (8 * ((b + 1) & 3));
+  }
+  return w;
+}
+__device__ __forceinline__ void k16_split_dword(uint32_t w, uint32_t& a, uint32_t& b) {
+  a = w & 0x3c3c3c3cu;
+  b = __builtin_amdgcn_alignbit(w, w, 4) & 0x3c3c3c3cu;
 }
 
 // Sum 8 per-lane row accumulators over the 64 lanes.  Returns, in every lane, the

@@ -55,16 +55,22 @@ __global__ __launch_bounds__(256) void gemm_kernel(const uint8_t* __restrict__ i
     if (rb_ok) {
       const long long g = (long long)rb * n_cb + c;
       if (K == 16) {
-        if (lane < 16) lut[lane] = cb[g * 16 + lane];
-        const uint2 w = *reinterpret_cast<const uint2*>(idx + (size_t)rb * n_cb * 512 +
-                                                        k16_chunk_offset(c, n_cb, lane));
+        const int slots = 2 * k16_pairs(n_cb);
+        if (lane < 16) lut[lane] = cb[((size_t)rb * slots + c) * 16 + lane];
+        const uint2 w = *reinterpret_cast<const uint2*>(idx + (size_t)rb * slots * 512 +
+                                                        k16_chunk_offset(c, lane));
         wave_lds_sync();
+        const char* lutb = reinterpret_cast<const char*>(lut);
 #pragma unroll
-        for (int r = 0; r < 8; ++r) {
-          const uint32_t word = r < 4 ? w.x : w.y;
-          const uint32_t lo = (word >> (8 * (r & 3))) & 15u;
-          const uint32_t hi = (word >> (8 * (r & 3) + 4)) & 15u;
-          *reinterpret_cast<uint2*>(wrow + r * WS) = make_uint2(lut[lo], lut[hi]);
+        for (int h = 0; h < 2; ++h) {
+          uint32_t a, b;
+          k16_split_dword(h ? w.y : w.x, a, b);
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const uint32_t lo = *reinterpret_cast<const uint32_t*>(lutb + ((a >> (8 * r)) & 0xffu));
+            const uint32_t hi = *reinterpret_cast<const uint32_t*>(lutb + ((b >> (8 * r)) & 0xffu));
+            *reinterpret_cast<uint2*>(wrow + (4 * h + r) * WS) = make_uint2(lo, hi);
+          }
         }
       } else {
         *reinterpret_cast<uint4*>(lut + lane * 4) =

@@ -33,69 +33,62 @@ struct Strip {
   const uint16_t* x;
   int u;                   // next unit to load
   int u_end;               // end of this strip's units
-  int chunks_left;         // chunks still to load (>= 1 for a fresh strip)
-  int n_pairs;             // k=16: pairs in the whole row-block (locates the tail's bytes)
-  int tail_c;              // k=16: col-block of the odd tail group in this strip, or -1
+  int chunks_left;         // chunks still to load
+  int n_cb;                // col-blocks of the matrix (k=16: the pad group has no activations)
 };
 
-template <int K> struct Chunk;
-
-// Every chunk issues the same loads whatever its shape: absent parts read a harmless
-// in-bounds address and are zeroed afterwards.  The loads of two chunks overlap the
-// consumption of a third, and the compiler can only keep a partial vmcnt wait (instead
-// of waiting for every outstanding load) if the number of loads in flight is static.
+// Every chunk issues the same loads whatever its shape: absent units read a harmless
+// in-bounds address.  The loads of one chunk overlap the consumption of the other, and
+// the compiler can only keep a partial vmcnt wait (instead of waiting for every
+// outstanding load) if the number of loads in flight is static.  For k=16 absent units
+// are also *consumed*: their table and activations are zero, so they add exactly 0 and
+// the consume step has no branches (branches around the inline-asm blocks cost register
+// copies of all 8 accumulators at every merge).
 __device__ __forceinline__ uint2 zero_unless(bool keep, uint2 v) {
   return keep ? v : make_uint2(0, 0);
 }
 __device__ __forceinline__ uint4 zero_unless(bool keep, uint4 v) {
   return keep ? v : make_uint4(0, 0, 0, 0);
 }
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+// Streaming (non-temporal) 16-byte load: index and codebook bytes are used exactly once.
+__device__ __forceinline__ uint4 stream_load16(const void* p) {
+  const u32x4_t t = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
+  return make_uint4(t.x, t.y, t.z, t.w);
+}
 
-// ---- k = 16 --------------------------------------------------------------
-// Chunk = up to 4 col-block pairs; the last chunk of a strip also carries the odd
-// tail group, if the strip has one.
+// ---- chunks with activations in registers (split-K kernel) ------------------
+template <int K> struct Chunk;
+
 template <> struct Chunk<16> {
-  static constexpr int kUnits = 4;
-  static constexpr int kLutDwords = 144;  // 8 groups + the tail group, 16 centroids each
+  static constexpr int kUnits = 4;        // col-block pairs per chunk
+  static constexpr int kLutDwords = 128;  // 8 groups x 16 centroids
   uint4 w[4];     // slot s: the lane's 16 index bytes of pair u+s
   uint2 xa[4];    // activations of the first group of the slot
   uint2 xb[4];    // ... and of the second
-  uint4 cbv;      // this lane's 16 bytes of the pairs' codebooks (lanes 0..31)
-  uint2 wt, xt;   // the tail group: 8 index bytes, activations
-  uint32_t cbt;   // its codebook (lanes 0..15)
-  bool has_tail;  // wave-uniform
+  uint4 cbv;      // this lane's 16 bytes of the chunk's codebooks (lanes 0..31)
 
   __device__ __forceinline__ void load(const Strip& S, int u, int lane) {
-    const int np = min(4, S.u_end - u);                         // pairs present, 0..4
-    has_tail = S.tail_c >= 0 && S.chunks_left == 1;
-    // codebooks of the 2*np groups: 32*np dwords, 4 per lane
+    const int np = max(0, min(4, S.u_end - u));                 // pairs present
     const int cb_off = min(lane * 4, max(np * 32 - 4, 0));
-    const bool cb_keep = lane * 4 < np * 32;
-    // a 16-byte read that is in bounds for every lane of every row-block (its first 512 bytes)
-    const uint8_t* dummy = S.idx_rb + (lane & 31) * 16;
-    cbv = zero_unless(cb_keep && np > 0,
-                      *reinterpret_cast<const uint4*>(np > 0 ? S.cb_rb + (size_t)u * 32 + cb_off
-                                                             : S.cb_rb + (lane & 3) * 4));
+    cbv = zero_unless(lane * 4 < np * 32,
+                      stream_load16(S.cb_rb + (size_t)(np > 0 ? u : 0) * 32 + cb_off));
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
       const bool ok = s < np;
-      const int q = u + s;
-      w[s] = *reinterpret_cast<const uint4*>(ok ? S.idx_rb + (size_t)q * 1024 + lane * 16 : dummy);
-      xa[s] = zero_unless(ok, *reinterpret_cast<const uint2*>(S.x + (ok ? (2 * q) * 256 : 0) + lane * 4));
-      xb[s] = zero_unless(ok, *reinterpret_cast<const uint2*>(S.x + (ok ? (2 * q + 1) * 256 : 0) + lane * 4));
+      const int q = ok ? u + s : 0;                              // pair 0 always exists
+      const bool ok_b = ok && 2 * q + 1 < S.n_cb;                // the pad group has no x
+      w[s] = stream_load16(S.idx_rb + (size_t)q * 1024 + lane * 16);
+      xa[s] = zero_unless(ok, *reinterpret_cast<const uint2*>(S.x + (2 * q) * 256 + lane * 4));
+      xb[s] = zero_unless(ok_b, *reinterpret_cast<const uint2*>(S.x + (ok_b ? 2 * q + 1 : 0) * 256 + lane * 4));
     }
-    const int tc = has_tail ? S.tail_c : 0;
-    wt = *reinterpret_cast<const uint2*>(S.idx_rb + (has_tail ? (size_t)S.n_pairs * 1024 : 0) + lane * 8);
-    xt = zero_unless(has_tail, *reinterpret_cast<const uint2*>(S.x + tc * 256 + lane * 4));
-    cbt = S.cb_rb[tc * 16 + (lane & 15)];
   }
 
   // Stages the codebooks in this wave's table region (`lut`, LDS byte address `base`)
-  // and consumes the chunk.  Absent pairs look up a zeroed table with zero activations.
+  // and consumes the chunk.
   __device__ __forceinline__ void consume(uint32_t* lut, uint32_t base, int lane,
                                           float (&acc)[8]) const {
     if (lane < 32) *reinterpret_cast<uint4*>(lut + lane * 4) = cbv;
-    if (lane < 16) lut[128 + lane] = cbt;
     wave_lds_sync();
     k16_group<0>(w[0].x, w[0].y, base, xa[0].x, xa[0].y, acc);
     k16_group<64>(w[0].z, w[0].w, base, xb[0].x, xb[0].y, acc);
@@ -105,14 +98,11 @@ template <> struct Chunk<16> {
     k16_group<320>(w[2].z, w[2].w, base, xb[2].x, xb[2].y, acc);
     k16_group<384>(w[3].x, w[3].y, base, xa[3].x, xa[3].y, acc);
     k16_group<448>(w[3].z, w[3].w, base, xb[3].x, xb[3].y, acc);
-    if (has_tail) k16_group<512>(wt.x, wt.y, base, xt.x, xt.y, acc);
   }
 };
 
-// ---- k = 256 -------------------------------------------------------------
-// Chunk = up to 2 groups.
 template <> struct Chunk<256> {
-  static constexpr int kUnits = 2;
+  static constexpr int kUnits = 2;        // groups per chunk
   static constexpr int kLutDwords = 512;  // 2 groups x 256 centroids
   uint4 w[2];     // the lane's 16 index bytes of group u+s
   uint2 xv[2];    // its activations
@@ -122,9 +112,9 @@ template <> struct Chunk<256> {
 #pragma unroll
     for (int s = 0; s < 2; ++s) {
       const bool ok = u + s < S.u_end;
-      const int c = ok ? u + s : u;     // u itself is always present
-      w[s] = *reinterpret_cast<const uint4*>(S.idx_rb + (size_t)c * 1024 + lane * 16);
-      cbv[s] = zero_unless(ok, *reinterpret_cast<const uint4*>(S.cb_rb + (size_t)c * 256 + lane * 4));
+      const int c = ok ? u + s : 0;
+      w[s] = stream_load16(S.idx_rb + (size_t)c * 1024 + lane * 16);
+      cbv[s] = zero_unless(ok, stream_load16(S.cb_rb + (size_t)c * 256 + lane * 4));
       xv[s] = zero_unless(ok, *reinterpret_cast<const uint2*>(S.x + c * 256 + lane * 4));
     }
   }
@@ -139,30 +129,25 @@ template <> struct Chunk<256> {
   }
 };
 
-// Strip (row-block rb, K-split `split` of `splits`) of problem P.  May be empty
-// (chunks_left == 0) only for k=256 splits wider than the row-block.
+// Strip (row-block rb, K-split `split` of `splits`) of problem P; may be empty.
 template <int K>
 __device__ __forceinline__ Strip make_strip(const GemvProblem& P, int rb, int split, int splits) {
   Strip S;
   const int n_cb = P.n_cb;
   S.x = P.x;
+  S.n_cb = n_cb;
   if (K == 16) {
-    const int n_pairs = n_cb >> 1;
-    S.idx_rb = P.idx + (size_t)rb * n_cb * 512;
-    S.cb_rb = P.cb + (size_t)rb * n_cb * 16;
+    const int n_pairs = k16_pairs(n_cb);
+    S.idx_rb = P.idx + (size_t)rb * n_pairs * 1024;
+    S.cb_rb = P.cb + (size_t)rb * n_pairs * 32;
     S.u = (n_pairs * split) / splits;
     S.u_end = (n_pairs * (split + 1)) / splits;
-    S.n_pairs = n_pairs;
-    S.tail_c = ((n_cb & 1) && split == splits - 1) ? n_cb - 1 : -1;
     S.chunks_left = (S.u_end - S.u + 3) >> 2;
-    if (S.chunks_left == 0 && S.tail_c >= 0) S.chunks_left = 1;   // a tail-only strip
   } else {
     S.idx_rb = P.idx + (size_t)rb * n_cb * 1024;
     S.cb_rb = P.cb + (size_t)rb * n_cb * 256;
     S.u = (n_cb * split) / splits;
     S.u_end = (n_cb * (split + 1)) / splits;
-    S.n_pairs = 0;
-    S.tail_c = -1;
     S.chunks_left = (S.u_end - S.u + 1) >> 1;
   }
   return S;
@@ -197,81 +182,44 @@ __device__ __forceinline__ int find_problem(const GemvBatch& batch, int item) {
 // keeps two chunk buffers in flight across row-block boundaries.
 //
 // Chunks of the streaming kernel hold no activations: the inner blocks read them from
-// LDS.  Index and codebook loads are non-temporal (each byte is used once).
-typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
-typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
-__device__ __forceinline__ uint4 stream_load16(const void* p) {
-  const u32x4_t t = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
-  return make_uint4(t.x, t.y, t.z, t.w);
-}
-__device__ __forceinline__ uint2 stream_load8(const void* p) {
-  const u32x2_t t = __builtin_nontemporal_load(reinterpret_cast<const u32x2_t*>(p));
-  return make_uint2(t.x, t.y);
-}
-
+// the workgroup's LDS copy of x, which is stored per col-block as two planes of 64
+// dwords (plane e = the fp16 pair of vector 2L+e of lane L) so that the dword reads
+// of a wave hit 64 consecutive banks, and is followed by zeroed col-blocks that the
+// absent units of a ragged chunk read.
 template <int K> struct ChunkS;
 
 template <> struct ChunkS<16> {
   static constexpr int kUnits = 4;
-  static constexpr int kLutDwords = 144;
+  static constexpr int kLutDwords = 128;
   uint4 w[4];
   uint4 cbv;
-  uint2 wt;
-  uint32_t cbt;
-  // wave-uniform description of what was loaded
-  int np;          // pairs present (0..4)
-  int u0;          // first pair (locates the activations in LDS)
-  int tail_c;      // col-block of the tail group carried by this chunk, or -1
+  int u0;          // first pair (locates the activations in LDS), wave-uniform
 
   __device__ __forceinline__ void load(const Strip& S, int u, int lane) {
-    np = min(4, S.u_end - u);
+    const int np = max(0, min(4, S.u_end - u));
     u0 = u;
-    tail_c = (S.tail_c >= 0 && S.chunks_left == 1) ? S.tail_c : -1;
     const int cb_off = min(lane * 4, max(np * 32 - 4, 0));
-    const uint8_t* dummy = S.idx_rb + (lane & 31) * 16;
-    cbv = stream_load16(np > 0 ? S.cb_rb + (size_t)u * 32 + cb_off : S.cb_rb + (lane & 3) * 4);
+    cbv = zero_unless(lane * 4 < np * 32,
+                      stream_load16(S.cb_rb + (size_t)(np > 0 ? u : 0) * 32 + cb_off));
 #pragma unroll
     for (int s = 0; s < 4; ++s)
-      w[s] = stream_load16(s < np ? S.idx_rb + (size_t)(u + s) * 1024 + lane * 16 : dummy);
-    const int tc = tail_c >= 0 ? tail_c : 0;
-    wt = stream_load8(S.idx_rb + (tail_c >= 0 ? (size_t)S.n_pairs * 1024 : 0) + lane * 8);
-    cbt = S.cb_rb[tc * 16 + (lane & 15)];
+      w[s] = stream_load16(S.idx_rb + (size_t)(s < np ? u + s : 0) * 1024 + lane * 16);
   }
 
   // x_lds: LDS byte address of the workgroup's copy of x.
   __device__ __forceinline__ void consume(uint32_t* lut, uint32_t base, uint32_t x_lds, int lane,
                                           float (&acc)[8]) const {
     if (lane < 32) *reinterpret_cast<uint4*>(lut + lane * 4) = cbv;
-    if (lane < 16) lut[128 + lane] = cbt;
     wave_lds_sync();
-    const uint32_t xa = x_lds + u0 * 1024 + lane * 8;   // pair p starts at column 512 p
-    if (np == 4) {
-      k16_group_lx<0, 0>(w[0].x, w[0].y, base, xa, acc);
-      k16_group_lx<64, 512>(w[0].z, w[0].w, base, xa, acc);
-      k16_group_lx<128, 1024>(w[1].x, w[1].y, base, xa, acc);
-      k16_group_lx<192, 1536>(w[1].z, w[1].w, base, xa, acc);
-      k16_group_lx<256, 2048>(w[2].x, w[2].y, base, xa, acc);
-      k16_group_lx<320, 2560>(w[2].z, w[2].w, base, xa, acc);
-      k16_group_lx<384, 3072>(w[3].x, w[3].y, base, xa, acc);
-      k16_group_lx<448, 3584>(w[3].z, w[3].w, base, xa, acc);
-    } else {
-      if (np > 0) {
-        k16_group_lx<0, 0>(w[0].x, w[0].y, base, xa, acc);
-        k16_group_lx<64, 512>(w[0].z, w[0].w, base, xa, acc);
-      }
-      if (np > 1) {
-        k16_group_lx<128, 1024>(w[1].x, w[1].y, base, xa, acc);
-        k16_group_lx<192, 1536>(w[1].z, w[1].w, base, xa, acc);
-      }
-      if (np > 2) {
-        k16_group_lx<256, 2048>(w[2].x, w[2].y, base, xa, acc);
-        k16_group_lx<320, 2560>(w[2].z, w[2].w, base, xa, acc);
-      }
-    }
-    if (tail_c >= 0) {
-      const uint32_t xt = x_lds + tail_c * 512 + lane * 8;
-      k16_group_lx<512, 0>(wt.x, wt.y, base, xt, acc);
-    }
+    const uint32_t xa = x_lds + u0 * 1024 + lane * 4;   // pair p starts at col-block 2p
+    k16_group_lx<0, 0>(w[0].x, w[0].y, base, xa, acc);
+    k16_group_lx<64, 512>(w[0].z, w[0].w, base, xa, acc);
+    k16_group_lx<128, 1024>(w[1].x, w[1].y, base, xa, acc);
+    k16_group_lx<192, 1536>(w[1].z, w[1].w, base, xa, acc);
+    k16_group_lx<256, 2048>(w[2].x, w[2].y, base, xa, acc);
+    k16_group_lx<320, 2560>(w[2].z, w[2].w, base, xa, acc);
+    k16_group_lx<384, 3072>(w[3].x, w[3].y, base, xa, acc);
+    k16_group_lx<448, 3584>(w[3].z, w[3].w, base, xa, acc);
   }
 };
 
@@ -280,17 +228,16 @@ template <> struct ChunkS<256> {
   static constexpr int kLutDwords = 512;
   uint4 w[2];
   uint4 cbv[2];
-  int ng;          // groups present (1..2)
   int u0;          // first col-block
 
   __device__ __forceinline__ void load(const Strip& S, int u, int lane) {
-    ng = min(2, S.u_end - u);
     u0 = u;
 #pragma unroll
     for (int s = 0; s < 2; ++s) {
-      const int c = s < ng ? u + s : 0;     // an absent group re-reads col-block 0
+      const bool ok = u + s < S.u_end;
+      const int c = ok ? u + s : 0;
       w[s] = stream_load16(S.idx_rb + (size_t)c * 1024 + lane * 16);
-      cbv[s] = stream_load16(S.cb_rb + (size_t)c * 256 + lane * 4);
+      cbv[s] = zero_unless(ok, stream_load16(S.cb_rb + (size_t)c * 256 + lane * 4));
     }
   }
 
@@ -299,11 +246,14 @@ template <> struct ChunkS<256> {
     *reinterpret_cast<uint4*>(lut + lane * 4) = cbv[0];
     *reinterpret_cast<uint4*>(lut + 256 + lane * 4) = cbv[1];
     wave_lds_sync();
-    const uint32_t xa = x_lds + u0 * 512 + lane * 8;
+    const uint32_t xa = x_lds + u0 * 512 + lane * 4;
     k256_group_lx<0, 0>(w[0].x, w[0].y, w[0].z, w[0].w, base, xa, acc);
-    if (ng > 1) k256_group_lx<1024, 512>(w[1].x, w[1].y, w[1].z, w[1].w, base, xa, acc);
+    k256_group_lx<1024, 512>(w[1].x, w[1].y, w[1].z, w[1].w, base, xa, acc);
   }
 };
+
+// Zeroed col-blocks kept behind x in LDS (absent units of a ragged chunk read them).
+constexpr int kXPadColBlocks = 8;
 
 template <int K>
 __global__ __launch_bounds__(256) void gemv_stream_kernel(const GemvBatch batch) {
@@ -347,10 +297,17 @@ __global__ __launch_bounds__(256) void gemv_stream_kernel(const GemvBatch batch)
     // ---- the workgroup enters problem pi: stage x, reset the row-block counter
     __syncthreads();                       // everyone is done with the previous x
     {
+      // col-block c of x -> LDS dwords [128c, 128c+64) = pairs of vectors 2L (plane 0) and
+      // [128c+64, 128c+128) = pairs of vectors 2L+1 (plane 1); then kXPadColBlocks of zeros
       const uint4* xg = reinterpret_cast<const uint4*>(P.x);
-      uint4* xl = reinterpret_cast<uint4*>(x_s);
-      const int n16 = n_cb * 32;           // 256 halfs = 32 x 16 bytes per col-block
-      for (int i = threadIdx.x; i < n16; i += 256) xl[i] = xg[i];
+      const int n16 = n_cb * 32;           // 16-byte pieces of x
+      for (int i = threadIdx.x; i < n16 + kXPadColBlocks * 32; i += 256) {
+        const uint4 v = i < n16 ? xg[i] : make_uint4(0, 0, 0, 0);
+        const int c = i >> 5, j = i & 31;  // piece j of col-block c covers lanes 2j, 2j+1
+        uint32_t* dst = x_s + c * 128 + 2 * j;
+        *reinterpret_cast<uint2*>(dst) = make_uint2(v.x, v.z);
+        *reinterpret_cast<uint2*>(dst + 64) = make_uint2(v.y, v.w);
+      }
       if (threadIdx.x == 0) counter[0] = rb_lo + 4;   // waves start on rb_lo + wave
     }
     __syncthreads();
@@ -478,7 +435,7 @@ __global__ __launch_bounds__(256) void gemv_split_kernel(const GemvBatch batch) 
 
 size_t gemv_stream_lds_bytes(int k, int max_n_cb) {
   const size_t lut = (size_t)4 * 2 * (k == 16 ? ChunkS<16>::kLutDwords : ChunkS<256>::kLutDwords) * 4;
-  return lut + 16 + (size_t)max_n_cb * 512;
+  return lut + 16 + (size_t)(max_n_cb + kXPadColBlocks) * 512;
 }
 
 int gemv_stream_resident_wgs(int k, int max_n_cb) {

@@ -38,13 +38,23 @@ def test_desc_struct_matches_header_size():
 
 
 def test_sizes_follow_the_bpv_closed_form():
-    # Sec. 4: bpv = log2(k)/d + k*d*b_c/l with fp16 centroids
+    # Sec. 4: bpv = log2(k)/d + k*d*b_c/l with fp16 centroids, for the canonical arrays
     for (o, i, k, b, bpv) in [(4096, 4096, 16, 4, 2.25), (11008, 4096, 256, 8, 8.0),
                               (4096, 11008, 16, 4, 2.25), (256, 256, 16, 4, 2.25)]:
         d = vq.make_desc(o, i, k, b)
-        ib, cb = vq.vq_layout_bytes(d)
+        ib, cb = vq.vq_canonical_bytes(d)
         assert (ib + cb) * 8 / (o * i) == bpv
-        assert vq.vq_canonical_bytes(d) == (ib, cb)
+
+
+def test_device_layout_pads_odd_4bit_row_blocks_to_whole_pairs():
+    # even number of col-blocks, or 8-bit indices: no padding
+    for (o, i, k, b) in [(4096, 4096, 16, 4), (11008, 4096, 256, 8), (4096, 11008, 256, 8)]:
+        d = vq.make_desc(o, i, k, b)
+        assert vq.vq_layout_bytes(d) == vq.vq_canonical_bytes(d)
+    # 43 col-blocks of 4-bit indices are stored as 22 pairs: one extra group per row-block
+    d = vq.make_desc(4096, 11008, 16, 4)
+    ib, cb = vq.vq_canonical_bytes(d)
+    assert vq.vq_layout_bytes(d) == (ib + 512 * 512, cb + 512 * 64)
 
 
 A = 0x1000  # a fake, 16-byte aligned, non-NULL address; validation fails before any launch
