@@ -27,6 +27,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+# HBM bytes one launch of the dominant kernel moves (56 matrices = 8 layers of the pass), from
+# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled by a copy kernel of known size; the summary
+# and the commands are in profiles/gemv_stream_k16_llama7b_pass.md
+TRAFFIC_BYTES_PER_LAUNCH = None
 MFMA_F16_PEAK_TFLOPS = 2500.0  # MI355X published dense fp16 matrix peak
 
 
@@ -81,8 +85,8 @@ def build_pass(torch, vq, vqdev, n_layers):
 
 def time_cpu_baseline(budget_s=20.0):
     """The CPU oracle (decode -> dense fp16 W -> fp64 y = W x) timed on the host cores, on a
-    bounded sample of the same workload: whole matrices of layer 0 of the pass, in order,
-    until the time budget is used.  Input generation is not timed."""
+    bounded sample of the same workload: whole matrices of the pass, in order, until the
+    time budget is used.  Input generation is not timed."""
     import oracle
     import workloads
     try:
@@ -90,9 +94,9 @@ def time_cpu_baseline(budget_s=20.0):
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         threads = 1
-    done_bytes, spent, names = 0, 0.0, []
+    done_bytes, spent, n_mats = 0, 0.0, 0
     for (layer, name, s, seed) in workloads.llama7b_pass_shapes():
-        if layer > 0 or spent >= budget_s:
+        if spent >= budget_s:
             break
         idx, cb = workloads.make_weights(s, seed)
         x = workloads.make_x(s.in_features, seed)
@@ -101,11 +105,12 @@ def time_cpu_baseline(budget_s=20.0):
         oracle.gemv(f, idx, cb, x)
         spent += time.perf_counter() - t1
         done_bytes += algorithmic_bytes(s)
-        names.append(name)
+        n_mats += 1
     return {
         "value": done_bytes / spent / 1e9, "unit": "GB/s", "cores": threads, "kind": "oracle",
-        "sample": f"layer 0 of the pass: {'+'.join(names)} ({done_bytes} algorithmic bytes in "
-                  f"{spent:.2f} s of oracle time, {os.cpu_count()} host cpus visible)",
+        "sample": f"the first {n_mats} matrices of the pass in order ({n_mats / 7:.1f} layers, "
+                  f"{done_bytes} algorithmic bytes) in {spent:.2f} s of oracle time; "
+                  f"{os.cpu_count()} host cpus visible",
         "seconds": spent,
     }
 
@@ -113,12 +118,16 @@ def time_cpu_baseline(budget_s=20.0):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=50,
+                    help="untimed passes first; the GPU needs some tens of ms of load to settle its clocks")
     ap.add_argument("--layers", type=int, default=32, help="layers of the 7B pass (32 = the workload)")
     ap.add_argument("--no-extras", action="store_true", help="skip per-shape / GEMM side measurements")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
-    ap.add_argument("--cpu-budget", type=float, default=15.0)
+    ap.add_argument("--cpu-budget", type=float, default=12.0, help="seconds of oracle time to spend")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run a plain device copy of 1 GiB (a kernel of known traffic, for scaling "
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
@@ -153,6 +162,19 @@ def main():
     log(f"[bench] pass via vq_gemv_multi: {ms_multi * 1e3:.1f} us/step, {pass_bytes / ms_multi / 1e6:.0f} GB/s")
 
     extras = {}
+    if args.pmc_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)          # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
+    # the achievable ceiling next to the nominal peak: a plain read of 1.75 GiB
+    probe = torch.empty(1792 << 20, dtype=torch.uint8, device=dev).fill_(3)
+    ms_probe, _ = timer.run(lambda: vq.vq_stream_read_probe(probe, probe.numel()), 10, 3)
+    stream_read_gbs = probe.numel() / ms_probe / 1e6
+    del probe
+    log(f"[bench] stream-read ceiling: {stream_read_gbs:.0f} GB/s")
     if not args.no_extras:
         # the same pass as 224 separate vq_gemv calls (plain stream launches)
         def step_single():
@@ -248,17 +270,21 @@ def main():
                   "Llama-7B shapes, batch 1",
         "value": gbs, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_multi, "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "f16 (fp32 accumulate)", "data": "synthetic",
+        "vs_baseline": None, "dtype": "f16", "data": "synthetic",
         "config": {"workload": f"llama7b_full_weight_pass_k16 ({len(mats)} GEMVs, {args.layers} layers, "
                                f"d=2, 8x256 groups, 2.25 bpv) via vq_gemv_multi",
+                   "accumulate": "f32", "y_dtype": "f16",
                    "bytes_per_step": pass_bytes, "launches_per_step": n_launch,
                    "us_per_call": ms_multi * 1e3 / len(mats),
                    "tokens_per_s_weight_stream": 1e3 / ms_multi},
         "roofline": {"bound": "hbm", "achieved": pass_bytes / n_launch / kernel_us / 1e3,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": pass_bytes / n_launch / kernel_us / 1e3 / HBM_PEAK_GBS,
-                     "traffic": None, "kernel": "gemv_kernel<16>",
-                     "kernel_avg_us": kernel_us, "bytes_per_launch": pass_bytes / n_launch},
+                     "traffic": TRAFFIC_BYTES_PER_LAUNCH if args.layers == 32 else None,
+                     "kernel": "gemv_stream_kernel<16>",
+                     "kernel_avg_us": kernel_us, "bytes_per_launch": pass_bytes / n_launch,
+                     "measured_stream_read_GB/s": stream_read_gbs,
+                     "frac_of_measured_stream_read": pass_bytes / n_launch / kernel_us / 1e3 / stream_read_gbs},
         "cpu_baseline": cpu,
         "extras": extras,
     }

@@ -139,6 +139,15 @@ VQ_API int vq_gemm_batched(const vq_desc* desc, const void* idx_dev, const void*
 VQ_API int vq_decode_dense(const vq_desc* desc, const void* idx_dev, const void* cb_dev,
                     void* W_f16, void* stream);
 
+/*
+ * Measurement aid, not part of the method: reads `bytes` bytes (a multiple of 16)
+ * of device memory once with the same non-temporal 128-bit loads the GEMV kernels
+ * stream their indices with, and discards them.  Timing it over a buffer much
+ * larger than the caches gives the HBM read rate this GPU can actually sustain,
+ * which the bench reports next to the nominal peak.
+ */
+VQ_API int vq_stream_read_probe(const void* buf, size_t bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

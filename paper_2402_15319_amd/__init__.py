@@ -14,7 +14,7 @@ from typing import Sequence
 __all__ = [
     "VQDesc", "VQError", "VQ_F16", "VQ_F32", "lib", "lib_path", "make_desc",
     "vq_status_string", "vq_version", "vq_canonical_bytes", "vq_layout_bytes",
-    "vq_pack_layout", "vq_gemv", "vq_gemv_multi", "GemvMultiArgs", "vq_gemm_batched", "vq_decode_dense",
+    "vq_pack_layout", "vq_gemv", "vq_gemv_multi", "GemvMultiArgs", "vq_stream_read_probe", "vq_gemm_batched", "vq_decode_dense",
 ]
 
 VQ_F16 = 1
@@ -72,6 +72,8 @@ def lib() -> ctypes.CDLL:
                                     ctypes.POINTER(vp), ctypes.POINTER(vp), i32, vp]
         L.vq_gemm_batched.restype = i32
         L.vq_gemm_batched.argtypes = [dp, vp, vp, vp, i32, i32, vp, i32, i32, vp]
+        L.vq_stream_read_probe.restype = i32
+        L.vq_stream_read_probe.argtypes = [vp, ctypes.c_size_t, vp]
         L.vq_decode_dense.restype = i32
         L.vq_decode_dense.argtypes = [dp, vp, vp, vp, vp]
         _lib = L
@@ -173,3 +175,7 @@ def vq_gemm_batched(desc: VQDesc, idx_dev, cb_dev, X, B: int, ldx: int, Y, ldy: 
 def vq_decode_dense(desc: VQDesc, idx_dev, cb_dev, W, stream=None) -> None:
     _check(lib().vq_decode_dense(ctypes.byref(desc), _ptr(idx_dev), _ptr(cb_dev), _ptr(W),
                                  _stream(stream)), "vq_decode_dense")
+
+
+def vq_stream_read_probe(buf, nbytes: int, stream=None) -> None:
+    _check(lib().vq_stream_read_probe(_ptr(buf), nbytes, _stream(stream)), "vq_stream_read_probe")

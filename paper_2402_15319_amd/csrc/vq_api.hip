@@ -153,7 +153,7 @@ int vq_gemv_multi(int count, const vq_desc* descs, const void* const* idx_dev,
     batch.total_cost = (int32_t)cost;
     int grid = (int)items;
     if (stream_mode) {
-      const long long want = (items + 3) / 4;
+      const long long want = (items + 7) / 8;   // at least one row-block per wave
       const int resident = gemv_stream_resident_wgs(descs[0].k, max_n_cb);
       grid = (int)(want < resident ? want : resident);
     }
@@ -194,6 +194,13 @@ int vq_decode_dense(const vq_desc* desc, const void* idx_dev, const void* cb_dev
   if (!idx_dev || !cb_dev || !W_f16) return VQ_ERR_NULL;
   if (!aligned16(idx_dev) || !aligned16(cb_dev) || !aligned16(W_f16)) return VQ_ERR_ALIGN;
   return hip_status(launch_decode(*desc, idx_dev, cb_dev, W_f16, (hipStream_t)stream));
+}
+
+int vq_stream_read_probe(const void* buf, size_t bytes, void* stream) {
+  if (!buf) return VQ_ERR_NULL;
+  if (!aligned16(buf)) return VQ_ERR_ALIGN;
+  if (bytes == 0 || (bytes & 15)) return VQ_ERR_BAD_ARG;
+  return hip_status(launch_stream_read(buf, bytes, (hipStream_t)stream));
 }
 
 }  // extern "C"

@@ -177,7 +177,7 @@ __device__ __forceinline__ int find_problem(const GemvBatch& batch, int item) {
 // groups (a row-block of problem p costs n_cb[p] groups; cost_begin[p] is the prefix
 // sum).  Workgroup g of G takes the row-blocks whose first group falls in
 // [g*C/G, (g+1)*C/G): contiguous row-blocks, balanced to within one row-block.  Inside
-// a problem the workgroup keeps x in LDS (staged once), and its 4 waves draw row-blocks
+// a problem the workgroup keeps x in LDS (staged once), and its waves draw row-blocks
 // from an LDS counter, so a wave that finishes early takes the next one.  Each wave
 // keeps two chunk buffers in flight across row-block boundaries.
 //
@@ -255,12 +255,16 @@ template <> struct ChunkS<256> {
 // Zeroed col-blocks kept behind x in LDS (absent units of a ragged chunk read them).
 constexpr int kXPadColBlocks = 8;
 
+// Waves per workgroup of the streaming kernel: 8 share one LDS copy of x, which lets 24
+// waves (6 per SIMD) fit on a CU next to 3 copies of a 22 KB x.
+constexpr int kStreamWaves = 8;
+
 template <int K>
-__global__ __launch_bounds__(256) void gemv_stream_kernel(const GemvBatch batch) {
-  // dynamic LDS: [4 waves x 2 table regions][row-block counter][x of the current problem]
+__global__ __launch_bounds__(kStreamWaves * 64) void gemv_stream_kernel(const GemvBatch batch) {
+  // dynamic LDS: [kStreamWaves x 2 table regions][row-block counter][x of the current problem]
   extern __shared__ __attribute__((aligned(16))) uint32_t smem[];
   constexpr int kLut = ChunkS<K>::kLutDwords;
-  uint32_t* const counter = smem + 4 * 2 * kLut;          // 4 dwords reserved
+  uint32_t* const counter = smem + kStreamWaves * 2 * kLut;          // 4 dwords reserved
   uint32_t* const x_s = counter + 4;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -301,14 +305,14 @@ __global__ __launch_bounds__(256) void gemv_stream_kernel(const GemvBatch batch)
       // [128c+64, 128c+128) = pairs of vectors 2L+1 (plane 1); then kXPadColBlocks of zeros
       const uint4* xg = reinterpret_cast<const uint4*>(P.x);
       const int n16 = n_cb * 32;           // 16-byte pieces of x
-      for (int i = threadIdx.x; i < n16 + kXPadColBlocks * 32; i += 256) {
+      for (int i = threadIdx.x; i < n16 + kXPadColBlocks * 32; i += kStreamWaves * 64) {
         const uint4 v = i < n16 ? xg[i] : make_uint4(0, 0, 0, 0);
         const int c = i >> 5, j = i & 31;  // piece j of col-block c covers lanes 2j, 2j+1
         uint32_t* dst = x_s + c * 128 + 2 * j;
         *reinterpret_cast<uint2*>(dst) = make_uint2(v.x, v.z);
         *reinterpret_cast<uint2*>(dst + 64) = make_uint2(v.y, v.w);
       }
-      if (threadIdx.x == 0) counter[0] = rb_lo + 4;   // waves start on rb_lo + wave
+      if (threadIdx.x == 0) counter[0] = rb_lo + kStreamWaves;   // waves start on rb_lo + wave
     }
     __syncthreads();
 
@@ -434,7 +438,7 @@ __global__ __launch_bounds__(256) void gemv_split_kernel(const GemvBatch batch) 
 }  // namespace
 
 size_t gemv_stream_lds_bytes(int k, int max_n_cb) {
-  const size_t lut = (size_t)4 * 2 * (k == 16 ? ChunkS<16>::kLutDwords : ChunkS<256>::kLutDwords) * 4;
+  const size_t lut = (size_t)kStreamWaves * 2 * (k == 16 ? ChunkS<16>::kLutDwords : ChunkS<256>::kLutDwords) * 4;
   return lut + 16 + (size_t)(max_n_cb + kXPadColBlocks) * 512;
 }
 
@@ -450,8 +454,8 @@ int gemv_stream_resident_wgs(int k, int max_n_cb) {
     int per_cu = 0, cus = 0;
     const size_t lds = gemv_stream_lds_bytes(k, max_n_cb);
     hipError_t e = k == 16
-        ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gemv_stream_kernel<16>, 256, lds)
-        : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gemv_stream_kernel<256>, 256, lds);
+        ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gemv_stream_kernel<16>, kStreamWaves * 64, lds)
+        : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gemv_stream_kernel<256>, kStreamWaves * 64, lds);
     if (e != hipSuccess || per_cu < 1) per_cu = 1;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
       cus = 256;
@@ -466,8 +470,9 @@ hipError_t launch_gemv(int k, const GemvBatch& batch, int stream_mode, int grid_
   const dim3 grid(grid_wgs), block(256);
   if (stream_mode) {
     const size_t lds = gemv_stream_lds_bytes(k, max_n_cb);
-    if (k == 16) hipLaunchKernelGGL(gemv_stream_kernel<16>, grid, block, lds, s, batch);
-    else hipLaunchKernelGGL(gemv_stream_kernel<256>, grid, block, lds, s, batch);
+    const dim3 sblock(kStreamWaves * 64);
+    if (k == 16) hipLaunchKernelGGL(gemv_stream_kernel<16>, grid, sblock, lds, s, batch);
+    else hipLaunchKernelGGL(gemv_stream_kernel<256>, grid, sblock, lds, s, batch);
   } else {
     if (k == 16) hipLaunchKernelGGL(gemv_split_kernel<16>, grid, block, 0, s, batch);
     else hipLaunchKernelGGL(gemv_split_kernel<256>, grid, block, 0, s, batch);

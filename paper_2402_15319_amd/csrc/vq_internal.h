@@ -51,4 +51,6 @@ hipError_t launch_gemm(const vq_desc& d, const void* idx_dev, const void* cb_dev
                        const void* X, int B, int ldx, void* Y, int ldy, int y_f32,
                        hipStream_t s);
 
+hipError_t launch_stream_read(const void* buf, size_t bytes, hipStream_t s);
+
 }  // namespace vq
