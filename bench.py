@@ -30,7 +30,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 # HBM bytes one launch of the dominant kernel moves (56 matrices = 8 layers of the pass), from
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled by a copy kernel of known size; the summary
 # and the commands are in profiles/gemv_stream_k16_llama7b_pass.md
-TRAFFIC_BYTES_PER_LAUNCH = None
+TRAFFIC_BYTES_PER_LAUNCH = 468916224
 MFMA_F16_PEAK_TFLOPS = 2500.0  # MI355X published dense fp16 matrix peak
 
 
