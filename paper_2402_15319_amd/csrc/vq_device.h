@@ -42,6 +42,10 @@ __device__ __forceinline__ uint32_t lds_addr(const uint32_t* p) {
   return __builtin_amdgcn_readfirstlane(a);
 }
 
+// Wait states between the last v_dot2c of an inline-asm block and ordinary VALU code
+// that reads the accumulators.
+__device__ __forceinline__ void acc_hazard_fence() { asm volatile("s_nop 3" ::: "memory"); }
+
 // Orders this wave's LDS writes before its later LDS reads (other lanes' data).
 __device__ __forceinline__ void wave_lds_sync() {
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -63,9 +67,10 @@ __device__ __forceinline__ void wave_lds_sync() {
 // vectors of each row in the four bytes (see the layout above); one SDWA add per
 // lookup then picks a byte and adds the table base, and the table offset rides in
 // the ds_read immediate: 2.4 VALU instructions per vector including the dot2.  LDS reads are kept 8-12
-// deep ahead of the dot products (lgkmcnt is a 4-bit counter).  The trailing
-// s_nop covers the dot-result-read-by-other-VALU wait states, which the
-// compiler cannot see inside an asm statement.
+// deep ahead of the dot products (lgkmcnt is a 4-bit counter).  A dot2c result
+// may be consumed by the next dot2c at once, but other VALU instructions need
+// wait states the compiler cannot see inside an asm statement: callers run
+// acc_hazard_fence() before ordinary code reads the accumulators.
 #define VQ_SDWA_RD(R, T, B, OFF)                                                          \
   "v_add_u32_sdwa " R ", %[base], " T                                                     \
   " dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_" #B "\n"            \
@@ -102,7 +107,6 @@ __device__ __forceinline__ void k16_group(uint32_t w0, uint32_t w1, uint32_t bas
       "s_waitcnt lgkmcnt(0)\n"
       VQ_DOT("%[a6]", "%[r0]", "%[x0]") VQ_DOT("%[a7]", "%[r2]", "%[x0]")
       VQ_DOT("%[a6]", "%[r1]", "%[x1]") VQ_DOT("%[a7]", "%[r3]", "%[x1]")
-      "s_nop 2\n"
       : [a0] "+v"(acc[0]), [a1] "+v"(acc[1]), [a2] "+v"(acc[2]), [a3] "+v"(acc[3]),
         [a4] "+v"(acc[4]), [a5] "+v"(acc[5]), [a6] "+v"(acc[6]), [a7] "+v"(acc[7]),
         [ta] "=&v"(ta), [tb] "=&v"(tb), [r0] "=&v"(r0), [r1] "=&v"(r1), [r2] "=&v"(r2),
@@ -152,7 +156,6 @@ __device__ __forceinline__ void k256_group(uint32_t w0, uint32_t w1, uint32_t w2
       "s_waitcnt lgkmcnt(0)\n"
       VQ_DOT("%[a6]", "%[r0]", "%[x0]") VQ_DOT("%[a7]", "%[r2]", "%[x0]")
       VQ_DOT("%[a6]", "%[r1]", "%[x1]") VQ_DOT("%[a7]", "%[r3]", "%[x1]")
-      "s_nop 2\n"
       : [a0] "+v"(acc[0]), [a1] "+v"(acc[1]), [a2] "+v"(acc[2]), [a3] "+v"(acc[3]),
         [a4] "+v"(acc[4]), [a5] "+v"(acc[5]), [a6] "+v"(acc[6]), [a7] "+v"(acc[7]),
         [r0] "=&v"(r0), [r1] "=&v"(r1), [r2] "=&v"(r2), [r3] "=&v"(r3), [r4] "=&v"(r4),
@@ -213,7 +216,6 @@ __device__ __forceinline__ void k16_group_lx(uint32_t w0, uint32_t w1, uint32_t 
       "s_waitcnt lgkmcnt(0)\n"
       VQ_DOT("%[a6]", "%[r2]", "%[x0]") VQ_DOT("%[a7]", "%[r4]", "%[x0]")
       VQ_DOT("%[a6]", "%[r3]", "%[x1]") VQ_DOT("%[a7]", "%[r5]", "%[x1]")
-      "s_nop 2\n"
       : [a0] "+v"(acc[0]), [a1] "+v"(acc[1]), [a2] "+v"(acc[2]), [a3] "+v"(acc[3]),
         [a4] "+v"(acc[4]), [a5] "+v"(acc[5]), [a6] "+v"(acc[6]), [a7] "+v"(acc[7]),
         [ta] "=&v"(ta), [tb] "=&v"(tb), [x0] "=&v"(x0), [x1] "=&v"(x1), [r0] "=&v"(r0),
@@ -257,7 +259,6 @@ __device__ __forceinline__ void k256_group_lx(uint32_t w0, uint32_t w1, uint32_t
       "s_waitcnt lgkmcnt(0)\n"
       VQ_DOT("%[a6]", "%[r0]", "%[x0]") VQ_DOT("%[a7]", "%[r2]", "%[x0]")
       VQ_DOT("%[a6]", "%[r1]", "%[x1]") VQ_DOT("%[a7]", "%[r3]", "%[x1]")
-      "s_nop 2\n"
       : [a0] "+v"(acc[0]), [a1] "+v"(acc[1]), [a2] "+v"(acc[2]), [a3] "+v"(acc[3]),
         [a4] "+v"(acc[4]), [a5] "+v"(acc[5]), [a6] "+v"(acc[6]), [a7] "+v"(acc[7]),
         [x0] "=&v"(x0), [x1] "=&v"(x1), [r0] "=&v"(r0), [r1] "=&v"(r1), [r2] "=&v"(r2),

@@ -182,10 +182,8 @@ __device__ __forceinline__ int find_problem(const GemvBatch& batch, int item) {
 // keeps two chunk buffers in flight across row-block boundaries.
 //
 // Chunks of the streaming kernel hold no activations: the inner blocks read them from
-// the workgroup's LDS copy of x, which is stored per col-block as two planes of 64
-// dwords (plane e = the fp16 pair of vector 2L+e of lane L) so that the dword reads
-// of a wave hit 64 consecutive banks, and is followed by zeroed col-blocks that the
-// absent units of a ragged chunk read.
+// the workgroup's LDS copy of x (natural order, read 64 bits per lane), which is followed
+// by zeroed col-blocks that the absent units of a ragged chunk read.
 template <int K> struct ChunkS;
 
 template <> struct ChunkS<16> {
@@ -206,20 +204,29 @@ template <> struct ChunkS<16> {
       w[s] = stream_load16(S.idx_rb + (size_t)(s < np ? u + s : 0) * 1024 + lane * 16);
   }
 
-  // x_lds: LDS byte address of the workgroup's copy of x.
-  __device__ __forceinline__ void consume(uint32_t* lut, uint32_t base, uint32_t x_lds, int lane,
+  // x_s: the workgroup's LDS copy of x (natural order: lane L's 4 halfs of col-block c
+  // are the 8 bytes at c*512 + 8L, so a wave-wide 64-bit read is conflict-free).  The
+  // read for block b+1 is issued before block b, so only the first one is waited for.
+  __device__ __forceinline__ void consume(uint32_t* lut, uint32_t base, const uint32_t* x_s, int lane,
                                           float (&acc)[8]) const {
     if (lane < 32) *reinterpret_cast<uint4*>(lut + lane * 4) = cbv;
     wave_lds_sync();
-    const uint32_t xa = x_lds + u0 * 1024 + lane * 4;   // pair p starts at col-block 2p
-    k16_group_lx<0, 0>(w[0].x, w[0].y, base, xa, acc);
-    k16_group_lx<64, 512>(w[0].z, w[0].w, base, xa, acc);
-    k16_group_lx<128, 1024>(w[1].x, w[1].y, base, xa, acc);
-    k16_group_lx<192, 1536>(w[1].z, w[1].w, base, xa, acc);
-    k16_group_lx<256, 2048>(w[2].x, w[2].y, base, xa, acc);
-    k16_group_lx<320, 2560>(w[2].z, w[2].w, base, xa, acc);
-    k16_group_lx<384, 3072>(w[3].x, w[3].y, base, xa, acc);
-    k16_group_lx<448, 3584>(w[3].z, w[3].w, base, xa, acc);
+    const uint2* xp = reinterpret_cast<const uint2*>(x_s) + u0 * 128 + lane;   // 64 uint2 per col-block
+    uint2 x0 = xp[0], x1 = xp[64];
+    k16_group<0>(w[0].x, w[0].y, base, x0.x, x0.y, acc);
+    x0 = xp[128];
+    k16_group<64>(w[0].z, w[0].w, base, x1.x, x1.y, acc);
+    x1 = xp[192];
+    k16_group<128>(w[1].x, w[1].y, base, x0.x, x0.y, acc);
+    x0 = xp[256];
+    k16_group<192>(w[1].z, w[1].w, base, x1.x, x1.y, acc);
+    x1 = xp[320];
+    k16_group<256>(w[2].x, w[2].y, base, x0.x, x0.y, acc);
+    x0 = xp[384];
+    k16_group<320>(w[2].z, w[2].w, base, x1.x, x1.y, acc);
+    x1 = xp[448];
+    k16_group<384>(w[3].x, w[3].y, base, x0.x, x0.y, acc);
+    k16_group<448>(w[3].z, w[3].w, base, x1.x, x1.y, acc);
   }
 };
 
@@ -241,14 +248,15 @@ template <> struct ChunkS<256> {
     }
   }
 
-  __device__ __forceinline__ void consume(uint32_t* lut, uint32_t base, uint32_t x_lds, int lane,
+  __device__ __forceinline__ void consume(uint32_t* lut, uint32_t base, const uint32_t* x_s, int lane,
                                           float (&acc)[8]) const {
     *reinterpret_cast<uint4*>(lut + lane * 4) = cbv[0];
     *reinterpret_cast<uint4*>(lut + 256 + lane * 4) = cbv[1];
     wave_lds_sync();
-    const uint32_t xa = x_lds + u0 * 512 + lane * 4;
-    k256_group_lx<0, 0>(w[0].x, w[0].y, w[0].z, w[0].w, base, xa, acc);
-    k256_group_lx<1024, 512>(w[1].x, w[1].y, w[1].z, w[1].w, base, xa, acc);
+    const uint2* xp = reinterpret_cast<const uint2*>(x_s) + u0 * 64 + lane;
+    const uint2 x0 = xp[0], x1 = xp[64];
+    k256_group<0>(w[0].x, w[0].y, w[0].z, w[0].w, base, x0.x, x0.y, acc);
+    k256_group<1024>(w[1].x, w[1].y, w[1].z, w[1].w, base, x1.x, x1.y, acc);
   }
 };
 
@@ -270,7 +278,7 @@ __global__ __launch_bounds__(kStreamWaves * 64) void gemv_stream_kernel(const Ge
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   uint32_t* lut_a = smem + wave * 2 * kLut;
   uint32_t* lut_b = lut_a + kLut;
-  const uint32_t base_a = lds_addr(lut_a), base_b = lds_addr(lut_b), x_lds = lds_addr(x_s);
+  const uint32_t base_a = lds_addr(lut_a), base_b = lds_addr(lut_b);
 
   const int lo = (int)((long long)blockIdx.x * batch.total_cost / gridDim.x);
   const int hi = (int)((long long)(blockIdx.x + 1) * batch.total_cost / gridDim.x);
@@ -301,17 +309,12 @@ __global__ __launch_bounds__(kStreamWaves * 64) void gemv_stream_kernel(const Ge
     // ---- the workgroup enters problem pi: stage x, reset the row-block counter
     __syncthreads();                       // everyone is done with the previous x
     {
-      // col-block c of x -> LDS dwords [128c, 128c+64) = pairs of vectors 2L (plane 0) and
-      // [128c+64, 128c+128) = pairs of vectors 2L+1 (plane 1); then kXPadColBlocks of zeros
+      // x, then kXPadColBlocks col-blocks of zeros
       const uint4* xg = reinterpret_cast<const uint4*>(P.x);
+      uint4* xl = reinterpret_cast<uint4*>(x_s);
       const int n16 = n_cb * 32;           // 16-byte pieces of x
-      for (int i = threadIdx.x; i < n16 + kXPadColBlocks * 32; i += kStreamWaves * 64) {
-        const uint4 v = i < n16 ? xg[i] : make_uint4(0, 0, 0, 0);
-        const int c = i >> 5, j = i & 31;  // piece j of col-block c covers lanes 2j, 2j+1
-        uint32_t* dst = x_s + c * 128 + 2 * j;
-        *reinterpret_cast<uint2*>(dst) = make_uint2(v.x, v.z);
-        *reinterpret_cast<uint2*>(dst + 64) = make_uint2(v.y, v.w);
-      }
+      for (int i = threadIdx.x; i < n16 + kXPadColBlocks * 32; i += kStreamWaves * 64)
+        xl[i] = i < n16 ? xg[i] : make_uint4(0, 0, 0, 0);
       if (threadIdx.x == 0) counter[0] = rb_lo + kStreamWaves;   // waves start on rb_lo + wave
     }
     __syncthreads();
@@ -352,8 +355,9 @@ __global__ __launch_bounds__(kStreamWaves * 64) void gemv_stream_kernel(const Ge
     } while (0)
 #define VQ_CONSUME(BUF, LUT, BASE, LAST, RB)                                     \
     do {                                                                         \
-      BUF.consume(LUT, BASE, x_lds, lane, acc);                                  \
+      BUF.consume(LUT, BASE, x_s, lane, acc);                                    \
       if (LAST) {                                                                \
+        acc_hazard_fence();                                                      \
         const float v = wave_reduce8(acc, lane);                                 \
         store_rows(y, batch.y_f32, RB, lane, v);                                 \
         _Pragma("unroll") for (int r = 0; r < 8; ++r) acc[r] = 0.f;              \
@@ -418,6 +422,7 @@ __global__ __launch_bounds__(256) void gemv_split_kernel(const GemvBatch batch) 
     }
   }
 
+  acc_hazard_fence();
   const float v = wave_reduce8(acc, lane);
   if ((lane & 7) == 0) part[wave][lane >> 3] = v;
   __syncthreads();
