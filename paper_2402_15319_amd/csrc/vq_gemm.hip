@@ -1,164 +1,286 @@
 // Batched / prefill product Y[out,B] = W X[in,B] on vector-quantised W: the one
 // place on this path that is a dense contraction.  Each workgroup decodes tiles
 // of W (table lookup, Sec. 3.2) into LDS as fp16 and feeds them to the fp16
-// matrix cores with fp32 accumulation.
+// matrix cores (v_mfma_f32_32x32x16_f16) with fp32 accumulation.
 //
-// Tile: 32 rows (4 row-blocks, one per wave to decode) x 128 batch columns
-// (one 32x32 MFMA accumulator per wave), K walked one col-block (256) at a time
-// in four 64-deep sub-steps.  X is batch-contiguous, while the MFMA operands
-// want 4 consecutive k per lane, so X is interleaved in registers on its way to
-// LDS as Xs[k/4][n][k%4].
+// A workgroup has 4 waves and owns an MT x NT tile of Y, MT = 32*RBW rows.  K is
+// walked one col-block (256 columns) at a time:
+//   * every wave decodes RBW groups (its own row-blocks of the tile) of the
+//     col-block into the LDS tile Wt[MT][256]: indices and codebooks were loaded
+//     into registers one col-block earlier, all 16 lookups of a lane are issued
+//     before the first result is used;
+//   * X is batch-contiguous, while an MFMA operand wants 8 consecutive k per lane,
+//     so X goes through registers on its way to LDS: a thread loads 8 rows x 4
+//     columns, transposes them with v_perm and writes 4 x 16 bytes, giving
+//     Xs[k/8][n][k%8]; the next piece is already loading while the current one is
+//     multiplied;
+//   * NT = 128: the col-block is consumed in four 64-deep sub-steps, wave w owns
+//     batch columns [32w, 32w+32) and all MT rows (RBW accumulator tiles);
+//     NT = 32 (small batches, bandwidth-bound): all 256 k are staged at once and
+//     wave w multiplies its own quarter of k; the four partial tiles meet in LDS
+//     at the end.
 #include "vq_device.h"
 #include "vq_internal.h"
 
 namespace vq {
 namespace {
 
-constexpr int MT = 32;    // rows per workgroup
-constexpr int NT = 128;   // batch columns per workgroup
+typedef _Float16 h8_t __attribute__((ext_vector_type(8)));
+
 constexpr int WS = 264;   // LDS row stride of the decoded W tile, in halfs (256 + 8 pad)
-constexpr int KS = 64;    // k per sub-step
+
+// What one wave needs to decode one group: the lane's index bytes and codebook piece.
+template <int K> struct GroupRegs;
+template <> struct GroupRegs<16> {
+  uint2 w;
+  uint32_t cbv;   // lanes 0..15: one centroid each
+};
+template <> struct GroupRegs<256> {
+  uint4 w;
+  uint4 cbv;      // 4 centroids per lane
+};
 
 template <int K>
+__device__ __forceinline__ void load_group(GroupRegs<K>& g, const uint8_t* idx, const uint32_t* cb,
+                                           long long rb, int c, int n_cb, int lane) {
+  if constexpr (K == 16) {
+    const int slots = 2 * k16_pairs(n_cb);
+    g.w = *reinterpret_cast<const uint2*>(idx + (size_t)rb * slots * 512 + k16_chunk_offset(c, lane));
+    g.cbv = cb[((size_t)rb * slots + c) * 16 + (lane & 15)];
+  } else {
+    const size_t gi = (size_t)rb * n_cb + c;
+    g.w = *reinterpret_cast<const uint4*>(idx + gi * 1024 + lane * 16);
+    g.cbv = *reinterpret_cast<const uint4*>(cb + gi * 256 + lane * 4);
+  }
+}
+
+// Decodes one group into 8 rows of the W tile (wrow = &Wt[first row][4*lane]).
+template <int K>
+__device__ __forceinline__ void decode_group(const GroupRegs<K>& g, uint32_t* lut, uint16_t* wrow,
+                                             int lane) {
+  const char* lutb = reinterpret_cast<const char*>(lut);
+  uint32_t v[16];
+  if constexpr (K == 16) {
+    const GroupRegs<16>& q = g;
+    if (lane < 16) lut[lane] = q.cbv;
+    wave_lds_sync();
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      uint32_t a, b;
+      k16_split_dword(h ? q.w.y : q.w.x, a, b);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        v[8 * h + 2 * r] = *reinterpret_cast<const uint32_t*>(lutb + ((a >> (8 * r)) & 0xffu));
+        v[8 * h + 2 * r + 1] = *reinterpret_cast<const uint32_t*>(lutb + ((b >> (8 * r)) & 0xffu));
+      }
+    }
+  } else {
+    const GroupRegs<256>& q = g;
+    *reinterpret_cast<uint4*>(lut + lane * 4) = q.cbv;
+    wave_lds_sync();
+    const uint32_t ws[4] = {q.w.x, q.w.y, q.w.z, q.w.w};
+#pragma unroll
+    for (int i = 0; i < 16; ++i) v[i] = lut[(ws[i >> 2] >> (8 * (i & 3))) & 0xffu];
+  }
+#pragma unroll
+  for (int r = 0; r < 8; ++r)
+    *reinterpret_cast<uint2*>(wrow + r * WS) = make_uint2(v[2 * r], v[2 * r + 1]);
+}
+
+// One thread's piece of an X sub-tile: 8 consecutive k x 4 consecutive batch columns.
+struct XPiece {
+  uint2 r[8];
+};
+__device__ __forceinline__ void load_xpiece(XPiece& p, const uint16_t* X, size_t k0, int ldx, int n0,
+                                            bool ok) {
+#pragma unroll
+  for (int j = 0; j < 8; ++j)
+    p.r[j] = ok ? *reinterpret_cast<const uint2*>(X + (k0 + j) * ldx + n0) : make_uint2(0, 0);
+}
+// Writes the piece transposed: 4 columns x 8 k (16 bytes per column) at dst, dst + 4 dwords, ...
+__device__ __forceinline__ void store_xpiece(const XPiece& p, uint32_t* dst) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const uint32_t sel = (i & 1) ? 0x07060302u : 0x05040100u;   // high or low halves of a dword pair
+    uint4 o;
+    o.x = __builtin_amdgcn_perm(i < 2 ? p.r[1].x : p.r[1].y, i < 2 ? p.r[0].x : p.r[0].y, sel);
+    o.y = __builtin_amdgcn_perm(i < 2 ? p.r[3].x : p.r[3].y, i < 2 ? p.r[2].x : p.r[2].y, sel);
+    o.z = __builtin_amdgcn_perm(i < 2 ? p.r[5].x : p.r[5].y, i < 2 ? p.r[4].x : p.r[4].y, sel);
+    o.w = __builtin_amdgcn_perm(i < 2 ? p.r[7].x : p.r[7].y, i < 2 ? p.r[6].x : p.r[6].y, sel);
+    *reinterpret_cast<uint4*>(dst + i * 4) = o;
+  }
+}
+
+template <int K, int RBW, int NT>
 __global__ __launch_bounds__(256) void gemm_kernel(const uint8_t* __restrict__ idx,
                                                    const uint32_t* __restrict__ cb,
                                                    const uint16_t* __restrict__ X, int B, int ldx,
                                                    void* __restrict__ Y, int ldy, int y_f32,
                                                    int n_rb, int n_cb, int n_tiles_n) {
+  constexpr int MT = 32 * RBW;
+  constexpr int KS = NT == 128 ? 64 : 256;       // k per X staging step
+  constexpr int NSUB = 256 / KS;
+  static_assert(KS * NT == 64 * 128, "an X sub-tile is 8192 halfs: one 8x4 piece per thread");
   __shared__ __attribute__((aligned(16))) uint16_t Wt[MT * WS];
-  __shared__ __attribute__((aligned(16))) uint32_t Xs[(KS / 4) * NT * 2];
+  __shared__ __attribute__((aligned(16))) uint32_t Xs[KS * NT / 2];          // [KS/8][NT][8 halfs]
   __shared__ __attribute__((aligned(16))) uint32_t lut_all[4][K];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int wave = tid >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int mt = blockIdx.x / n_tiles_n;
   const int nt = blockIdx.x - mt * n_tiles_n;
   uint32_t* lut = lut_all[wave];
 
-  const int rb = mt * 4 + wave;          // the row-block this wave decodes
-  const bool rb_ok = rb < n_rb;
-  uint16_t* wrow = Wt + (wave * 8) * WS + lane * 4;
+  // X staging role: k-octet ko of the sub-tile, 4 batch columns from n_loc
+  const int ko = tid / (NT / 4);
+  const int n_loc = (tid % (NT / 4)) * 4;
+  const int n_glob = nt * NT + n_loc;
+  const bool n_ok = n_glob < B;
+  uint32_t* xs_dst = Xs + (ko * NT + n_loc) * 4;
 
-  // X staging role of this thread: k-quad kq (4 rows of X), 8 batch columns from n0
-  const int kq = tid >> 4;
-  const int n0 = nt * NT + (tid & 15) * 8;
-  const bool n_ok = n0 < B;
-
-  f16v_t acc;
+  f16v_t acc[RBW];
 #pragma unroll
-  for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+  for (int a = 0; a < RBW; ++a)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[a][i] = 0.f;
+
+  // prologue: registers for col-block 0
+  GroupRegs<K> g[RBW];
+  long long rbs[RBW];
+  bool rb_ok[RBW];
+#pragma unroll
+  for (int a = 0; a < RBW; ++a) {
+    rbs[a] = (long long)mt * (4 * RBW) + wave * RBW + a;
+    rb_ok[a] = rbs[a] < n_rb;
+    load_group<K>(g[a], idx, cb, rb_ok[a] ? rbs[a] : 0, 0, n_cb, lane);
+  }
+  XPiece xp;
+  load_xpiece(xp, X, (size_t)ko * 8, ldx, n_glob, n_ok);
 
   for (int c = 0; c < n_cb; ++c) {
-    __syncthreads();   // all MFMA reads of Wt / Xs from the previous col-block are done
-    // ---- decode this wave's group (rb, c) into Wt rows [8*wave, 8*wave+8)
-    if (rb_ok) {
-      const long long g = (long long)rb * n_cb + c;
-      if (K == 16) {
-        const int slots = 2 * k16_pairs(n_cb);
-        if (lane < 16) lut[lane] = cb[((size_t)rb * slots + c) * 16 + lane];
-        const uint2 w = *reinterpret_cast<const uint2*>(idx + (size_t)rb * slots * 512 +
-                                                        k16_chunk_offset(c, lane));
-        wave_lds_sync();
-        const char* lutb = reinterpret_cast<const char*>(lut);
+    __syncthreads();   // MFMA reads of Wt from the previous col-block are done
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-          uint32_t a, b;
-          k16_split_dword(h ? w.y : w.x, a, b);
+    for (int a = 0; a < RBW; ++a) {
+      uint16_t* wrow = Wt + ((wave * RBW + a) * 8) * WS + lane * 4;
+      if (rb_ok[a]) {
+        decode_group<K>(g[a], lut, wrow, lane);
+      } else {
 #pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            const uint32_t lo = *reinterpret_cast<const uint32_t*>(lutb + ((a >> (8 * r)) & 0xffu));
-            const uint32_t hi = *reinterpret_cast<const uint32_t*>(lutb + ((b >> (8 * r)) & 0xffu));
-            *reinterpret_cast<uint2*>(wrow + (4 * h + r) * WS) = make_uint2(lo, hi);
+        for (int r = 0; r < 8; ++r) *reinterpret_cast<uint2*>(wrow + r * WS) = make_uint2(0u, 0u);
+      }
+      // next col-block's registers (clamped on the last one: a harmless re-read)
+      load_group<K>(g[a], idx, cb, rb_ok[a] ? rbs[a] : 0, min(c + 1, n_cb - 1), n_cb, lane);
+    }
+
+#pragma unroll
+    for (int sub = 0; sub < NSUB; ++sub) {
+      if (sub) __syncthreads();   // MFMA reads of Xs from the previous sub-step are done
+      store_xpiece(xp, xs_dst);
+      {  // next piece: next sub-step, or the first one of the next col-block
+        const int cn = sub + 1 < NSUB ? c : min(c + 1, n_cb - 1);
+        const int sn = sub + 1 < NSUB ? sub + 1 : 0;
+        load_xpiece(xp, X, (size_t)cn * 256 + sn * KS + ko * 8, ldx, n_glob, n_ok);
+      }
+      __syncthreads();
+      if (NT == 128) {
+        // wave w: batch columns [32w, 32w+32), all MT rows, the KS k of this sub-step
+#pragma unroll
+        for (int kk = 0; kk < KS / 16; ++kk) {
+          const h8_t b = *reinterpret_cast<const h8_t*>(
+              Xs + ((2 * kk + (lane >> 5)) * NT + wave * 32 + (lane & 31)) * 4);
+#pragma unroll
+          for (int a = 0; a < RBW; ++a) {
+            const h8_t av = *reinterpret_cast<const h8_t*>(
+                Wt + (32 * a + (lane & 31)) * WS + sub * KS + 16 * kk + 8 * (lane >> 5));
+            acc[a] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av, b, acc[a], 0, 0, 0);
           }
         }
       } else {
-        *reinterpret_cast<uint4*>(lut + lane * 4) =
-            *reinterpret_cast<const uint4*>(cb + g * 256 + lane * 4);
-        const uint4 w = *reinterpret_cast<const uint4*>(idx + g * 1024 + lane * 16);
-        wave_lds_sync();
-        const uint32_t ws[4] = {w.x, w.y, w.z, w.w};
+        // wave w: k in [64w, 64w+64) of the col-block, all 32 batch columns
 #pragma unroll
-        for (int r = 0; r < 8; ++r) {
-          const uint32_t half = ws[r >> 1] >> (16 * (r & 1));
-          *reinterpret_cast<uint2*>(wrow + r * WS) =
-              make_uint2(lut[half & 255u], lut[(half >> 8) & 255u]);
+        for (int kk = 0; kk < 4; ++kk) {
+          const int k16 = wave * 4 + kk;
+          const h8_t b = *reinterpret_cast<const h8_t*>(
+              Xs + ((2 * k16 + (lane >> 5)) * NT + (lane & 31)) * 4);
+#pragma unroll
+          for (int a = 0; a < RBW; ++a) {
+            const h8_t av = *reinterpret_cast<const h8_t*>(
+                Wt + (32 * a + (lane & 31)) * WS + 16 * k16 + 8 * (lane >> 5));
+            acc[a] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av, b, acc[a], 0, 0, 0);
+          }
         }
-      }
-    } else {
-#pragma unroll
-      for (int r = 0; r < 8; ++r) *reinterpret_cast<uint2*>(wrow + r * WS) = make_uint2(0u, 0u);
-    }
-
-    for (int sub = 0; sub < 256 / KS; ++sub) {
-      if (sub) __syncthreads();   // MFMA reads of Xs from the previous sub-step are done
-      // ---- stage X rows [k0, k0+4) x columns [n0, n0+8), interleaved to [n][k%4]
-      {
-        uint4 r0 = make_uint4(0, 0, 0, 0), r1 = r0, r2 = r0, r3 = r0;
-        if (n_ok) {
-          const uint16_t* src = X + (size_t)(c * 256 + sub * KS + kq * 4) * ldx + n0;
-          r0 = *reinterpret_cast<const uint4*>(src);
-          r1 = *reinterpret_cast<const uint4*>(src + ldx);
-          r2 = *reinterpret_cast<const uint4*>(src + 2 * (size_t)ldx);
-          r3 = *reinterpret_cast<const uint4*>(src + 3 * (size_t)ldx);
-        }
-        const uint32_t a0[4] = {r0.x, r0.y, r0.z, r0.w}, a1[4] = {r1.x, r1.y, r1.z, r1.w};
-        const uint32_t a2[4] = {r2.x, r2.y, r2.z, r2.w}, a3[4] = {r3.x, r3.y, r3.z, r3.w};
-        uint32_t* dst = Xs + (kq * NT + (tid & 15) * 8) * 2;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          uint4 o;
-          o.x = (a0[q] & 0xffffu) | (a1[q] << 16);          // n = 2q   : k+0, k+1
-          o.y = (a2[q] & 0xffffu) | (a3[q] << 16);          //            k+2, k+3
-          o.z = (a0[q] >> 16) | (a1[q] & 0xffff0000u);      // n = 2q+1
-          o.w = (a2[q] >> 16) | (a3[q] & 0xffff0000u);
-          *reinterpret_cast<uint4*>(dst + q * 4) = o;
-        }
-      }
-      __syncthreads();
-      // ---- 8 MFMAs of depth 8: A = decoded W (row lane%32), B = X (column lane%32)
-#pragma unroll
-      for (int mf = 0; mf < KS / 8; ++mf) {
-        const h4_t a = *reinterpret_cast<const h4_t*>(Wt + (lane & 31) * WS + sub * KS + mf * 8 +
-                                                      4 * (lane >> 5));
-        const h4_t b = *reinterpret_cast<const h4_t*>(
-            Xs + ((mf * 2 + (lane >> 5)) * NT + wave * 32 + (lane & 31)) * 2);
-        acc = __builtin_amdgcn_mfma_f32_32x32x8f16(a, b, acc, 0, 0, 0);
       }
     }
   }
 
   // ---- store: accumulator register i holds row 8*(i/4) + 4*(lane/32) + i%4, column lane%32
-  const int n = nt * NT + wave * 32 + (lane & 31);
-  if (n < B) {
+  if (NT == 128) {
+    const int n = nt * NT + wave * 32 + (lane & 31);
+    if (n < B) {
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int row = mt * MT + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
-      if (row < n_rb * 8) {
+      for (int a = 0; a < RBW; ++a)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int row = mt * MT + 32 * a + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
+          if (row < n_rb * 8) {
+            const size_t o = (size_t)row * ldy + n;
+            if (y_f32) reinterpret_cast<float*>(Y)[o] = acc[a][i];
+            else reinterpret_cast<_Float16*>(Y)[o] = (_Float16)acc[a][i];
+          }
+        }
+    }
+  } else {
+    // four partial MT x 32 tiles (one per wave) -> LDS (the W tile is free now) -> sum -> Y
+    __syncthreads();
+    float* part = reinterpret_cast<float*>(Wt);            // [4][MT][32] floats = 16 KB * RBW
+    static_assert(4 * MT * 32 * 4 <= MT * WS * 2, "partial tiles must fit in the W tile");
+#pragma unroll
+    for (int a = 0; a < RBW; ++a)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int m = 32 * a + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
+        part[(wave * MT + m) * 32 + (lane & 31)] = acc[a][i];
+      }
+    __syncthreads();
+    for (int e = tid; e < MT * 32; e += 256) {
+      const int m = e >> 5, nl = e & 31;
+      const float s = part[e] + part[MT * 32 + e] + part[2 * MT * 32 + e] + part[3 * MT * 32 + e];
+      const int row = mt * MT + m, n = nt * NT + nl;
+      if (row < n_rb * 8 && n < B) {
         const size_t o = (size_t)row * ldy + n;
-        if (y_f32) reinterpret_cast<float*>(Y)[o] = acc[i];
-        else reinterpret_cast<_Float16*>(Y)[o] = (_Float16)acc[i];
+        if (y_f32) reinterpret_cast<float*>(Y)[o] = s;
+        else reinterpret_cast<_Float16*>(Y)[o] = (_Float16)s;
       }
     }
   }
+}
+
+template <int K, int RBW, int NT>
+hipError_t launch_one(const vq_desc& d, const void* idx_dev, const void* cb_dev, const void* X, int B,
+                      int ldx, void* Y, int ldy, int y_f32, hipStream_t s) {
+  const int n_rb = d.out_features / kGroupRows, n_cb = d.in_features / kGroupCols;
+  const int tiles_m = (n_rb + 4 * RBW - 1) / (4 * RBW), tiles_n = (B + NT - 1) / NT;
+  hipLaunchKernelGGL((gemm_kernel<K, RBW, NT>), dim3((unsigned)(tiles_m * tiles_n)), dim3(256), 0, s,
+                     (const uint8_t*)idx_dev, (const uint32_t*)cb_dev, (const uint16_t*)X, B, ldx, Y,
+                     ldy, y_f32, n_rb, n_cb, tiles_n);
+  return hipGetLastError();
 }
 
 }  // namespace
 
 hipError_t launch_gemm(const vq_desc& d, const void* idx_dev, const void* cb_dev, const void* X,
                        int B, int ldx, void* Y, int ldy, int y_f32, hipStream_t s) {
-  const int n_rb = d.out_features / kGroupRows, n_cb = d.in_features / kGroupCols;
-  const int tiles_m = (n_rb + 3) / 4, tiles_n = (B + NT - 1) / NT;
-  const dim3 grid((unsigned)(tiles_m * tiles_n)), block(256);
-  if (d.k == 16)
-    hipLaunchKernelGGL(gemm_kernel<16>, grid, block, 0, s, (const uint8_t*)idx_dev,
-                       (const uint32_t*)cb_dev, (const uint16_t*)X, B, ldx, Y, ldy, y_f32, n_rb,
-                       n_cb, tiles_n);
-  else
-    hipLaunchKernelGGL(gemm_kernel<256>, grid, block, 0, s, (const uint8_t*)idx_dev,
-                       (const uint32_t*)cb_dev, (const uint16_t*)X, B, ldx, Y, ldy, y_f32, n_rb,
-                       n_cb, tiles_n);
-  return hipGetLastError();
+  // small batches are bandwidth-bound: 32-row tiles (many workgroups), 32 batch columns;
+  // large ones are matrix-core-bound: 64 x 128 tiles
+  if (d.k == 16) {
+    if (B <= 32) return launch_one<16, 1, 32>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);
+    if (B <= 128) return launch_one<16, 1, 128>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);
+    return launch_one<16, 2, 128>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);
+  }
+  if (B <= 32) return launch_one<256, 1, 32>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);
+  if (B <= 128) return launch_one<256, 1, 128>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);
+  return launch_one<256, 2, 128>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);
 }
 
 }  // namespace vq

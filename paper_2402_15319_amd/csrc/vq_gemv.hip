@@ -67,9 +67,10 @@ template <> struct Chunk<16> {
   uint2 xa[4];    // activations of the first group of the slot
   uint2 xb[4];    // ... and of the second
   uint4 cbv;      // this lane's 16 bytes of the chunk's codebooks (lanes 0..31)
+  int np;         // pairs present (wave-uniform)
 
   __device__ __forceinline__ void load(const Strip& S, int u, int lane) {
-    const int np = max(0, min(4, S.u_end - u));                 // pairs present
+    np = max(0, min(4, S.u_end - u));
     const int cb_off = min(lane * 4, max(np * 32 - 4, 0));
     cbv = zero_unless(lane * 4 < np * 32,
                       stream_load16(S.cb_rb + (size_t)(np > 0 ? u : 0) * 32 + cb_off));
@@ -94,6 +95,7 @@ template <> struct Chunk<16> {
     k16_group<64>(w[0].z, w[0].w, base, xb[0].x, xb[0].y, acc);
     k16_group<128>(w[1].x, w[1].y, base, xa[1].x, xa[1].y, acc);
     k16_group<192>(w[1].z, w[1].w, base, xb[1].x, xb[1].y, acc);
+    if (np <= 2) return;      // short strips of a finely split row-block: half the work
     k16_group<256>(w[2].x, w[2].y, base, xa[2].x, xa[2].y, acc);
     k16_group<320>(w[2].z, w[2].w, base, xb[2].x, xb[2].y, acc);
     k16_group<384>(w[3].x, w[3].y, base, xa[3].x, xa[3].y, acc);
