@@ -14,8 +14,9 @@
 //     columns, transposes them with v_perm and writes 4 x 16 bytes, giving
 //     Xs[k/8][n][k%8]; the next piece is already loading while the current one is
 //     multiplied;
-//   * NT = 128: the col-block is consumed in four 64-deep sub-steps, wave w owns
-//     batch columns [32w, 32w+32) and all MT rows (RBW accumulator tiles);
+//   * NT = 128 / 256: the col-block is consumed in 64- / 32-deep sub-steps through two
+//     X buffers (one barrier per sub-step), wave w owns a quarter of the batch
+//     columns and all MT rows (RBW x NT/128 accumulator tiles);
 //     NT = 32 (small batches, bandwidth-bound): all 256 k are staged at once and
 //     wave w multiplies its own quarter of k; the four partial tiles meet in LDS
 //     at the end.
@@ -27,7 +28,14 @@ namespace {
 
 typedef _Float16 h8_t __attribute__((ext_vector_type(8)));
 
-constexpr int WS = 264;   // LDS row stride of the decoded W tile, in halfs (256 + 8 pad)
+constexpr int WS = 256;   // LDS row stride of the decoded W tile, in halfs (no padding)
+
+// The W tile is stored without padding; 16-byte chunk q of row m lives at chunk q ^ (m & 7),
+// so the 8 lanes of one LDS pass of a 128-bit operand read (rows m..m+7, same k) and the
+// lanes of a decode write (same row, consecutive columns) all hit distinct banks.
+__device__ __forceinline__ int wt_half_index(int m, int k) {   // k in halfs
+  return m * WS + ((((k >> 3) ^ (m & 7)) << 3) | (k & 7));
+}
 
 // What one wave needs to decode one group: the lane's index bytes and codebook piece.
 template <int K> struct GroupRegs;
@@ -54,10 +62,10 @@ __device__ __forceinline__ void load_group(GroupRegs<K>& g, const uint8_t* idx, 
   }
 }
 
-// Decodes one group into 8 rows of the W tile (wrow = &Wt[first row][4*lane]).
+// Decodes one group into rows [m0, m0+8) of the W tile (lane L owns columns 4L..4L+3).
 template <int K>
-__device__ __forceinline__ void decode_group(const GroupRegs<K>& g, uint32_t* lut, uint16_t* wrow,
-                                             int lane) {
+__device__ __forceinline__ void decode_group(const GroupRegs<K>& g, uint32_t* lut, uint16_t* Wt,
+                                             int m0, int lane) {
   const char* lutb = reinterpret_cast<const char*>(lut);
   uint32_t v[16];
   if constexpr (K == 16) {
@@ -84,7 +92,7 @@ __device__ __forceinline__ void decode_group(const GroupRegs<K>& g, uint32_t* lu
   }
 #pragma unroll
   for (int r = 0; r < 8; ++r)
-    *reinterpret_cast<uint2*>(wrow + r * WS) = make_uint2(v[2 * r], v[2 * r + 1]);
+    *reinterpret_cast<uint2*>(Wt + wt_half_index(m0 + r, 4 * lane)) = make_uint2(v[2 * r], v[2 * r + 1]);
 }
 
 // One thread's piece of an X sub-tile: 8 consecutive k x 4 consecutive batch columns.
@@ -112,38 +120,42 @@ __device__ __forceinline__ void store_xpiece(const XPiece& p, uint32_t* dst) {
 }
 
 template <int K, int RBW, int NT>
-__global__ __launch_bounds__(256) void gemm_kernel(const uint8_t* __restrict__ idx,
+__global__ __launch_bounds__(256, 2) void gemm_kernel(const uint8_t* __restrict__ idx,
                                                    const uint32_t* __restrict__ cb,
                                                    const uint16_t* __restrict__ X, int B, int ldx,
                                                    void* __restrict__ Y, int ldy, int y_f32,
                                                    int n_rb, int n_cb, int n_tiles_n) {
   constexpr int MT = 32 * RBW;
-  constexpr int KS = NT == 128 ? 64 : 256;       // k per X staging step
+  constexpr int KS = 8192 / NT;                  // k per X staging step: 256, 64 or 32
   constexpr int NSUB = 256 / KS;
-  static_assert(KS * NT == 64 * 128, "an X sub-tile is 8192 halfs: one 8x4 piece per thread");
+  constexpr int NB = NT == 32 ? 1 : NT / 128;    // 32-column accumulator tiles per wave
+  constexpr int XBUFS = NT == 32 ? 1 : 2;        // X sub-tiles in LDS (double-buffered when NSUB > 1)
   __shared__ __attribute__((aligned(16))) uint16_t Wt[MT * WS];
-  __shared__ __attribute__((aligned(16))) uint32_t Xs[KS * NT / 2];          // [KS/8][NT][8 halfs]
-  __shared__ __attribute__((aligned(16))) uint32_t lut_all[4][K];
+  __shared__ __attribute__((aligned(16))) uint32_t Xs_all[XBUFS][4096];     // [KS/8][NT][8 halfs] each
+  // NT = 32: the tables have their own LDS; otherwise they live in the X buffer that is idle
+  // while a col-block is being decoded (the one the last MFMA step has just finished reading)
+  __shared__ __attribute__((aligned(16))) uint32_t lut_own[NT == 32 ? 4 * K : 4];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int mt = blockIdx.x / n_tiles_n;
   const int nt = blockIdx.x - mt * n_tiles_n;
-  uint32_t* lut = lut_all[wave];
 
   // X staging role: k-octet ko of the sub-tile, 4 batch columns from n_loc
   const int ko = tid / (NT / 4);
   const int n_loc = (tid % (NT / 4)) * 4;
   const int n_glob = nt * NT + n_loc;
   const bool n_ok = n_glob < B;
-  uint32_t* xs_dst = Xs + (ko * NT + n_loc) * 4;
+  const int xs_off = (ko * NT + n_loc) * 4;
 
-  f16v_t acc[RBW];
+  f16v_t acc[RBW][NB];
 #pragma unroll
   for (int a = 0; a < RBW; ++a)
 #pragma unroll
-    for (int i = 0; i < 16; ++i) acc[a][i] = 0.f;
+    for (int b = 0; b < NB; ++b)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
 
   // prologue: registers for col-block 0
   GroupRegs<K> g[RBW];
@@ -157,43 +169,61 @@ __global__ __launch_bounds__(256) void gemm_kernel(const uint8_t* __restrict__ i
   }
   XPiece xp;
   load_xpiece(xp, X, (size_t)ko * 8, ldx, n_glob, n_ok);
+  int cur = 0;   // X buffer the next MFMA step reads
 
   for (int c = 0; c < n_cb; ++c) {
-    __syncthreads();   // MFMA reads of Wt from the previous col-block are done
+    // every wave is past its MFMA reads of Wt (barrier at the end of the last sub-step)
+    uint32_t* lut = (NT == 32 ? lut_own : Xs_all[XBUFS - 1 - cur] + 0) + wave * K;
+    static_assert(4 * K <= 4096, "four tables must fit in one X buffer");
 #pragma unroll
     for (int a = 0; a < RBW; ++a) {
-      uint16_t* wrow = Wt + ((wave * RBW + a) * 8) * WS + lane * 4;
+      const int m0 = (wave * RBW + a) * 8;
       if (rb_ok[a]) {
-        decode_group<K>(g[a], lut, wrow, lane);
+        decode_group<K>(g[a], lut, Wt, m0, lane);
       } else {
 #pragma unroll
-        for (int r = 0; r < 8; ++r) *reinterpret_cast<uint2*>(wrow + r * WS) = make_uint2(0u, 0u);
+        for (int r = 0; r < 8; ++r)
+          *reinterpret_cast<uint2*>(Wt + wt_half_index(m0 + r, 4 * lane)) = make_uint2(0u, 0u);
       }
       // next col-block's registers (clamped on the last one: a harmless re-read)
       load_group<K>(g[a], idx, cb, rb_ok[a] ? rbs[a] : 0, min(c + 1, n_cb - 1), n_cb, lane);
     }
+    if (XBUFS == 1 || c == 0) {   // the first X piece of the run (later ones are staged one step ahead)
+      store_xpiece(xp, Xs_all[cur] + xs_off);
+      const int cn = NSUB > 1 ? c : min(c + 1, n_cb - 1);
+      const int sn = NSUB > 1 ? 1 : 0;
+      load_xpiece(xp, X, (size_t)cn * 256 + sn * KS + ko * 8, ldx, n_glob, n_ok);
+    }
+    __syncthreads();   // Wt (and the X piece) of this col-block are complete
 
 #pragma unroll
     for (int sub = 0; sub < NSUB; ++sub) {
-      if (sub) __syncthreads();   // MFMA reads of Xs from the previous sub-step are done
-      store_xpiece(xp, xs_dst);
-      {  // next piece: next sub-step, or the first one of the next col-block
-        const int cn = sub + 1 < NSUB ? c : min(c + 1, n_cb - 1);
-        const int sn = sub + 1 < NSUB ? sub + 1 : 0;
+      const uint32_t* Xs = Xs_all[cur];
+      if (XBUFS == 2) {
+        // stage the next sub-tile into the other buffer while this one is multiplied
+        const bool last = (sub + 1 == NSUB) && (c + 1 == n_cb);
+        if (!last) store_xpiece(xp, Xs_all[cur ^ 1] + xs_off);
+        const int s2 = sub + 2;                       // the piece after the one just stored
+        const int cn = s2 < NSUB ? c : min(c + 1, n_cb - 1);
+        const int sn = s2 < NSUB ? s2 : s2 - NSUB;
         load_xpiece(xp, X, (size_t)cn * 256 + sn * KS + ko * 8, ldx, n_glob, n_ok);
       }
-      __syncthreads();
-      if (NT == 128) {
-        // wave w: batch columns [32w, 32w+32), all MT rows, the KS k of this sub-step
+      if (NT != 32) {
+        // wave w: batch columns [32*NB*w, 32*NB*(w+1)), all MT rows, the KS k of this sub-step
 #pragma unroll
         for (int kk = 0; kk < KS / 16; ++kk) {
-          const h8_t b = *reinterpret_cast<const h8_t*>(
-              Xs + ((2 * kk + (lane >> 5)) * NT + wave * 32 + (lane & 31)) * 4);
+          h8_t bv[NB];
+#pragma unroll
+          for (int b = 0; b < NB; ++b)
+            bv[b] = *reinterpret_cast<const h8_t*>(
+                Xs + ((2 * kk + (lane >> 5)) * NT + (wave * NB + b) * 32 + (lane & 31)) * 4);
 #pragma unroll
           for (int a = 0; a < RBW; ++a) {
             const h8_t av = *reinterpret_cast<const h8_t*>(
-                Wt + (32 * a + (lane & 31)) * WS + sub * KS + 16 * kk + 8 * (lane >> 5));
-            acc[a] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av, b, acc[a], 0, 0, 0);
+                Wt + wt_half_index(32 * a + (lane & 31), sub * KS + 16 * kk + 8 * (lane >> 5)));
+#pragma unroll
+            for (int b = 0; b < NB; ++b)
+              acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av, bv[b], acc[a][b], 0, 0, 0);
           }
         }
       } else {
@@ -201,46 +231,50 @@ __global__ __launch_bounds__(256) void gemm_kernel(const uint8_t* __restrict__ i
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
           const int k16 = wave * 4 + kk;
-          const h8_t b = *reinterpret_cast<const h8_t*>(
+          const h8_t bv = *reinterpret_cast<const h8_t*>(
               Xs + ((2 * k16 + (lane >> 5)) * NT + (lane & 31)) * 4);
 #pragma unroll
           for (int a = 0; a < RBW; ++a) {
             const h8_t av = *reinterpret_cast<const h8_t*>(
-                Wt + (32 * a + (lane & 31)) * WS + 16 * k16 + 8 * (lane >> 5));
-            acc[a] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av, b, acc[a], 0, 0, 0);
+                Wt + wt_half_index(32 * a + (lane & 31), 16 * k16 + 8 * (lane >> 5)));
+            acc[a][0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av, bv, acc[a][0], 0, 0, 0);
           }
         }
       }
+      __syncthreads();   // reads of Xs[cur] (and, on the last sub-step, of Wt) done; Xs[cur^1] complete
+      if (XBUFS == 2) cur ^= 1;
     }
   }
 
   // ---- store: accumulator register i holds row 8*(i/4) + 4*(lane/32) + i%4, column lane%32
-  if (NT == 128) {
-    const int n = nt * NT + wave * 32 + (lane & 31);
-    if (n < B) {
+  if (NT != 32) {
 #pragma unroll
-      for (int a = 0; a < RBW; ++a)
+    for (int b = 0; b < NB; ++b) {
+      const int n = nt * NT + (wave * NB + b) * 32 + (lane & 31);
+      if (n < B) {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int row = mt * MT + 32 * a + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
-          if (row < n_rb * 8) {
-            const size_t o = (size_t)row * ldy + n;
-            if (y_f32) reinterpret_cast<float*>(Y)[o] = acc[a][i];
-            else reinterpret_cast<_Float16*>(Y)[o] = (_Float16)acc[a][i];
+        for (int a = 0; a < RBW; ++a)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            const int row = mt * MT + 32 * a + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
+            if (row < n_rb * 8) {
+              const size_t o = (size_t)row * ldy + n;
+              if (y_f32) reinterpret_cast<float*>(Y)[o] = acc[a][b][i];
+              else reinterpret_cast<_Float16*>(Y)[o] = (_Float16)acc[a][b][i];
+            }
           }
-        }
+      }
     }
   } else {
     // four partial MT x 32 tiles (one per wave) -> LDS (the W tile is free now) -> sum -> Y
-    __syncthreads();
-    float* part = reinterpret_cast<float*>(Wt);            // [4][MT][32] floats = 16 KB * RBW
+    float* part = reinterpret_cast<float*>(Wt);            // [4][MT][32] floats
     static_assert(4 * MT * 32 * 4 <= MT * WS * 2, "partial tiles must fit in the W tile");
 #pragma unroll
     for (int a = 0; a < RBW; ++a)
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
         const int m = 32 * a + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
-        part[(wave * MT + m) * 32 + (lane & 31)] = acc[a][i];
+        part[(wave * MT + m) * 32 + (lane & 31)] = acc[a][0][i];
       }
     __syncthreads();
     for (int e = tid; e < MT * 32; e += 256) {
@@ -254,6 +288,114 @@ __global__ __launch_bounds__(256) void gemm_kernel(const uint8_t* __restrict__ i
       }
     }
   }
+}
+
+// ---- small batches (B <= 32): bandwidth-bound ---------------------------------
+// 32 rows x 32 batch columns per workgroup (many workgroups, so that every CU streams
+// weights); the whole col-block of X is staged at once and wave w multiplies its own
+// quarter of k; the four partial tiles meet in LDS at the end.  W tile and X tile are
+// double-buffered: decoding col-block c+1 overlaps the MFMAs of col-block c and one
+// barrier per col-block is enough.
+template <int K>
+__global__ __launch_bounds__(256, 2) void gemm_small_kernel(const uint8_t* __restrict__ idx,
+                                                            const uint32_t* __restrict__ cb,
+                                                            const uint16_t* __restrict__ X, int B,
+                                                            int ldx, void* __restrict__ Y, int ldy,
+                                                            int y_f32, int n_rb, int n_cb,
+                                                            int n_tiles_n) {
+  constexpr int MT = 32, NT = 32;
+  __shared__ __attribute__((aligned(16))) uint16_t Wt_all[2][MT * WS];
+  __shared__ __attribute__((aligned(16))) uint32_t Xs_all[2][4096];     // [32 k-octets][32 n][8 halfs]
+  __shared__ __attribute__((aligned(16))) uint32_t lut_all[4][K];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int mt = blockIdx.x / n_tiles_n;
+  const int nt = blockIdx.x - mt * n_tiles_n;
+  uint32_t* lut = lut_all[wave];
+
+  const int ko = tid / (NT / 4);             // k-octet of the col-block, 0..31
+  const int n_loc = (tid % (NT / 4)) * 4;
+  const int n_glob = nt * NT + n_loc;
+  const bool n_ok = n_glob < B;
+  const int xs_off = (ko * NT + n_loc) * 4;
+
+  f16v_t acc;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+
+  const long long rb = (long long)mt * 4 + wave;
+  const bool rb_ok = rb < n_rb;
+  const long long rb_ld = rb_ok ? rb : 0;
+  const int m0 = wave * 8;
+
+  GroupRegs<K> g;
+  XPiece xp;
+  load_group<K>(g, idx, cb, rb_ld, 0, n_cb, lane);
+  load_xpiece(xp, X, (size_t)ko * 8, ldx, n_glob, n_ok);
+
+  auto stage = [&](int buf, int c_next) {
+    // registers (col-block staged now) -> LDS buffer `buf`; then refill them for c_next
+    if (rb_ok) {
+      decode_group<K>(g, lut, Wt_all[buf], m0, lane);
+    } else {
+#pragma unroll
+      for (int r = 0; r < 8; ++r)
+        *reinterpret_cast<uint2*>(Wt_all[buf] + wt_half_index(m0 + r, 4 * lane)) = make_uint2(0u, 0u);
+    }
+    store_xpiece(xp, Xs_all[buf] + xs_off);
+    load_group<K>(g, idx, cb, rb_ld, c_next, n_cb, lane);
+    load_xpiece(xp, X, (size_t)c_next * 256 + ko * 8, ldx, n_glob, n_ok);
+  };
+
+  stage(0, min(1, n_cb - 1));
+  __syncthreads();
+  for (int c = 0; c < n_cb; ++c) {
+    const int cur = c & 1;
+    if (c + 1 < n_cb) stage(cur ^ 1, min(c + 2, n_cb - 1));
+    const uint16_t* Wt = Wt_all[cur];
+    const uint32_t* Xs = Xs_all[cur];
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      const int k16 = wave * 4 + kk;
+      const h8_t bv = *reinterpret_cast<const h8_t*>(Xs + ((2 * k16 + (lane >> 5)) * NT + (lane & 31)) * 4);
+      const h8_t av = *reinterpret_cast<const h8_t*>(
+          Wt + wt_half_index(lane & 31, 16 * k16 + 8 * (lane >> 5)));
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(av, bv, acc, 0, 0, 0);
+    }
+    __syncthreads();   // buffer cur may be overwritten next time; buffer cur^1 is complete
+  }
+
+  // four partial 32 x 32 tiles (one per wave) -> LDS -> sum -> Y
+  float* part = reinterpret_cast<float*>(Wt_all[0]);      // 4 x 32 x 32 floats = 16 KB
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const int m = 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
+    part[(wave * MT + m) * 32 + (lane & 31)] = acc[i];
+  }
+  __syncthreads();
+  for (int e = tid; e < MT * 32; e += 256) {
+    const int m = e >> 5, nl = e & 31;
+    const float sum = part[e] + part[MT * 32 + e] + part[2 * MT * 32 + e] + part[3 * MT * 32 + e];
+    const int row = mt * MT + m, n = nt * NT + nl;
+    if (row < n_rb * 8 && n < B) {
+      const size_t o = (size_t)row * ldy + n;
+      if (y_f32) reinterpret_cast<float*>(Y)[o] = sum;
+      else reinterpret_cast<_Float16*>(Y)[o] = (_Float16)sum;
+    }
+  }
+}
+
+template <int K>
+hipError_t launch_small(const vq_desc& d, const void* idx_dev, const void* cb_dev, const void* X,
+                        int B, int ldx, void* Y, int ldy, int y_f32, hipStream_t s) {
+  const int n_rb = d.out_features / kGroupRows, n_cb = d.in_features / kGroupCols;
+  const int tiles_m = (n_rb + 3) / 4, tiles_n = (B + 31) / 32;
+  hipLaunchKernelGGL((gemm_small_kernel<K>), dim3((unsigned)(tiles_m * tiles_n)), dim3(256), 0, s,
+                     (const uint8_t*)idx_dev, (const uint32_t*)cb_dev, (const uint16_t*)X, B, ldx, Y,
+                     ldy, y_f32, n_rb, n_cb, tiles_n);
+  return hipGetLastError();
 }
 
 template <int K, int RBW, int NT>
@@ -274,13 +416,15 @@ hipError_t launch_gemm(const vq_desc& d, const void* idx_dev, const void* cb_dev
   // small batches are bandwidth-bound: 32-row tiles (many workgroups), 32 batch columns;
   // large ones are matrix-core-bound: 64 x 128 tiles
   if (d.k == 16) {
-    if (B <= 32) return launch_one<16, 1, 32>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);
+    if (B <= 32) return launch_small<16>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);
     if (B <= 128) return launch_one<16, 1, 128>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);
-    return launch_one<16, 2, 128>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);
+    if (B <= 512) return launch_one<16, 2, 128>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);
+    return launch_one<16, 2, 256>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);
   }
-  if (B <= 32) return launch_one<256, 1, 32>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);
+  if (B <= 32) return launch_small<256>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);
   if (B <= 128) return launch_one<256, 1, 128>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);
-  return launch_one<256, 2, 128>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);
+  if (B <= 512) return launch_one<256, 2, 128>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);
+  return launch_one<256, 2, 256>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);
 }
 
 }  // namespace vq

@@ -238,7 +238,7 @@ def _gpu_gemm(env, desc, idx_d, cb_d, X, f32, pad=0):
 
 
 @pytest.mark.parametrize("f32", [False, True], ids=["y16", "y32"])
-@pytest.mark.parametrize("B", [1, 16, 40, 130, 256])
+@pytest.mark.parametrize("B", [1, 16, 40, 130, 256, 600])
 @pytest.mark.parametrize("s", [_shape(40, 768, 16), _shape(72, 512, 256), _shape(264, 1024, 256)], ids=str)
 def test_gemm_small(env, s, B, f32):
     desc, idx, cb, idx_d, cb_d = _setup(env, s, 404)
