@@ -153,7 +153,7 @@ def main():
     margs = vq.GemvMultiArgs([m[2] for m in mats], [m[3] for m in mats], [m[4] for m in mats],
                              [xs[m[1].in_features] for m in mats], ys)
     pass_bytes = sum(algorithmic_bytes(m[1]) for m in mats)
-    n_launch = (len(mats) + 63) // 64
+    n_launch = (len(mats) + 255) // 256
 
     def step_multi():
         vq.vq_gemv_multi(margs)

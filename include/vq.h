@@ -111,7 +111,7 @@ VQ_API int vq_gemv(const vq_desc* desc, const void* idx_dev, const void* cb_dev,
  * once per generated token).  descs/idx_dev/cb_dev/x_f16/y are HOST arrays of
  * length `count` holding descriptors and device pointers; they are read
  * during the call and need not outlive it (the problem table travels in the
- * kernel arguments, up to 64 problems per launch).  All y_i share y_dtype and
+ * kernel arguments, up to 256 problems per launch).  All y_i share y_dtype and
  * all descriptors share k.  Each product obeys the rules of vq_gemv.
  * count in [1, 65536].
  */

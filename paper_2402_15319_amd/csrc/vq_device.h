@@ -70,7 +70,9 @@ __device__ __forceinline__ void wave_lds_sync() {
 // deep ahead of the dot products (lgkmcnt is a 4-bit counter).  A dot2c result
 // may be consumed by the next dot2c at once, but other VALU instructions need
 // wait states the compiler cannot see inside an asm statement: callers run
-// acc_hazard_fence() before ordinary code reads the accumulators.
+// acc_hazard_fence() after the last block of a straight run of blocks, i.e. before any
+// point where the compiler may place code of its own that reads an accumulator (a loop
+// edge or branch merge can make it copy accumulators between registers).
 #define VQ_SDWA_RD(R, T, B, OFF)                                                          \
   "v_add_u32_sdwa " R ", %[base], " T                                                     \
   " dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_" #B "\n"            \

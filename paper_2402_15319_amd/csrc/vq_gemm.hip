@@ -330,42 +330,80 @@ __global__ __launch_bounds__(256, 2) void gemm_small_kernel(const uint8_t* __res
   const long long rb_ld = rb_ok ? rb : 0;
   const int m0 = wave * 8;
 
-  GroupRegs<K> g;
-  XPiece xp;
-  load_group<K>(g, idx, cb, rb_ld, 0, n_cb, lane);
-  load_xpiece(xp, X, (size_t)ko * 8, ldx, n_glob, n_ok);
-
-  auto stage = [&](int buf, int c_next) {
-    // registers (col-block staged now) -> LDS buffer `buf`; then refill them for c_next
-    if (rb_ok) {
-      decode_group<K>(g, lut, Wt_all[buf], m0, lane);
-    } else {
+  // Few workgroups are resident per CU here, so memory latency is hidden by depth
+  // instead: a ring of D col-blocks (indices, codebook and the X piece) is kept in
+  // flight in registers.  Loads are unconditional (clamped to the last col-block) so
+  // that the compiler can count them and wait only for the oldest.
+  constexpr int D = 4;
+  const int n_ld = n_ok ? n_glob : 0;
+  GroupRegs<K> g[D];
+  XPiece xp[D];
 #pragma unroll
-      for (int r = 0; r < 8; ++r)
-        *reinterpret_cast<uint2*>(Wt_all[buf] + wt_half_index(m0 + r, 4 * lane)) = make_uint2(0u, 0u);
-    }
-    store_xpiece(xp, Xs_all[buf] + xs_off);
-    load_group<K>(g, idx, cb, rb_ld, c_next, n_cb, lane);
-    load_xpiece(xp, X, (size_t)c_next * 256 + ko * 8, ldx, n_glob, n_ok);
-  };
-
-  stage(0, min(1, n_cb - 1));
-  __syncthreads();
-  for (int c = 0; c < n_cb; ++c) {
-    const int cur = c & 1;
-    if (c + 1 < n_cb) stage(cur ^ 1, min(c + 2, n_cb - 1));
-    const uint16_t* Wt = Wt_all[cur];
-    const uint32_t* Xs = Xs_all[cur];
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-      const int k16 = wave * 4 + kk;
-      const h8_t bv = *reinterpret_cast<const h8_t*>(Xs + ((2 * k16 + (lane >> 5)) * NT + (lane & 31)) * 4);
-      const h8_t av = *reinterpret_cast<const h8_t*>(
-          Wt + wt_half_index(lane & 31, 16 * k16 + 8 * (lane >> 5)));
-      acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(av, bv, acc, 0, 0, 0);
-    }
-    __syncthreads();   // buffer cur may be overwritten next time; buffer cur^1 is complete
+  for (int j = 0; j < D; ++j) {
+    const int cj = min(j, n_cb - 1);
+    load_group<K>(g[j], idx, cb, rb_ld, cj, n_cb, lane);
+    load_xpiece(xp[j], X, (size_t)cj * 256 + ko * 8, ldx, n_ld, true);
   }
+
+  // Ring slot j (col-block c) -> LDS buffer j & 1 (D is even); with REFILL the slot is
+  // then reloaded with col-block c + D.  Everything that loads is branch-free: col-blocks
+  // past the end are clamped reads whose tiles are staged but never multiplied.
+  const uint32_t n_mask = n_ok ? 0xffffffffu : 0u;
+#define VQ_STAGE(j, c, REFILL)                                                                  \
+  {                                                                                             \
+    uint16_t* Wt_w = Wt_all[(j) & 1];                                                           \
+    if (rb_ok) {                                                                                \
+      decode_group<K>(g[j], lut, Wt_w, m0, lane);                                               \
+    } else {                                                                                    \
+      _Pragma("unroll") for (int r = 0; r < 8; ++r)                                             \
+          *reinterpret_cast<uint2*>(Wt_w + wt_half_index(m0 + r, 4 * lane)) = make_uint2(0u, 0u); \
+    }                                                                                           \
+    _Pragma("unroll") for (int r = 0; r < 8; ++r) {                                             \
+      xp[j].r[r].x &= n_mask;                                                                   \
+      xp[j].r[r].y &= n_mask;                                                                   \
+    }                                                                                           \
+    store_xpiece(xp[j], Xs_all[(j) & 1] + xs_off);                                              \
+    if (REFILL) {                                                                               \
+      const int cn = min((c) + D, n_cb - 1);                                                    \
+      load_group<K>(g[j], idx, cb, rb_ld, cn, n_cb, lane);                                      \
+      load_xpiece(xp[j], X, (size_t)cn * 256 + ko * 8, ldx, n_ld, true);                        \
+    }                                                                                           \
+  }
+  // multiply col-block c (staged in buffer j & 1) if it exists, then release the buffer
+#define VQ_MULTIPLY(j, c)                                                                       \
+  {                                                                                             \
+    if ((c) < n_cb) {                                                                           \
+      const uint16_t* Wt = Wt_all[(j) & 1];                                                     \
+      const uint32_t* Xs = Xs_all[(j) & 1];                                                     \
+      _Pragma("unroll") for (int kk = 0; kk < 4; ++kk) {                                        \
+        const int k16 = wave * 4 + kk;                                                          \
+        const h8_t bv = *reinterpret_cast<const h8_t*>(                                         \
+            Xs + ((2 * k16 + (lane >> 5)) * NT + (lane & 31)) * 4);                             \
+        const h8_t av = *reinterpret_cast<const h8_t*>(                                         \
+            Wt + wt_half_index(lane & 31, 16 * k16 + 8 * (lane >> 5)));                         \
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(av, bv, acc, 0, 0, 0);                     \
+      }                                                                                         \
+    }                                                                                           \
+    __syncthreads();                                                                            \
+  }
+
+  const int n_pad = (n_cb + D - 1) / D * D;
+  VQ_STAGE(0, 0, true)
+  __syncthreads();
+  int c0 = 0;
+  for (; c0 + D < n_pad; c0 += D) {
+    VQ_STAGE(1, c0 + 1, true) VQ_MULTIPLY(0, c0)
+    VQ_STAGE(2, c0 + 2, true) VQ_MULTIPLY(1, c0 + 1)
+    VQ_STAGE(3, c0 + 3, true) VQ_MULTIPLY(2, c0 + 2)
+    VQ_STAGE(0, c0 + 4, true) VQ_MULTIPLY(3, c0 + 3)
+  }
+  VQ_STAGE(1, c0 + 1, false) VQ_MULTIPLY(0, c0)
+  VQ_STAGE(2, c0 + 2, false) VQ_MULTIPLY(1, c0 + 1)
+  VQ_STAGE(3, c0 + 3, false) VQ_MULTIPLY(2, c0 + 2)
+  VQ_MULTIPLY(3, c0 + 3)
+#undef VQ_STAGE
+#undef VQ_MULTIPLY
+  static_assert(D == 4, "the unrolled ring above is written for four slots");
 
   // four partial 32 x 32 tiles (one per wave) -> LDS -> sum -> Y
   float* part = reinterpret_cast<float*>(Wt_all[0]);      // 4 x 32 x 32 floats = 16 KB

@@ -95,11 +95,15 @@ template <> struct Chunk<16> {
     k16_group<64>(w[0].z, w[0].w, base, xb[0].x, xb[0].y, acc);
     k16_group<128>(w[1].x, w[1].y, base, xa[1].x, xa[1].y, acc);
     k16_group<192>(w[1].z, w[1].w, base, xb[1].x, xb[1].y, acc);
-    if (np <= 2) return;      // short strips of a finely split row-block: half the work
+    if (np <= 2) {            // short strips of a finely split row-block: half the work
+      acc_hazard_fence();
+      return;
+    }
     k16_group<256>(w[2].x, w[2].y, base, xa[2].x, xa[2].y, acc);
     k16_group<320>(w[2].z, w[2].w, base, xb[2].x, xb[2].y, acc);
     k16_group<384>(w[3].x, w[3].y, base, xa[3].x, xa[3].y, acc);
     k16_group<448>(w[3].z, w[3].w, base, xb[3].x, xb[3].y, acc);
+    acc_hazard_fence();
   }
 };
 
@@ -128,6 +132,7 @@ template <> struct Chunk<256> {
     wave_lds_sync();
     k256_group<0>(w[0].x, w[0].y, w[0].z, w[0].w, base, xv[0].x, xv[0].y, acc);
     k256_group<1024>(w[1].x, w[1].y, w[1].z, w[1].w, base, xv[1].x, xv[1].y, acc);
+    acc_hazard_fence();
   }
 };
 
@@ -229,6 +234,7 @@ template <> struct ChunkS<16> {
     x1 = xp[448];
     k16_group<384>(w[3].x, w[3].y, base, x0.x, x0.y, acc);
     k16_group<448>(w[3].z, w[3].w, base, x1.x, x1.y, acc);
+    acc_hazard_fence();
   }
 };
 
@@ -259,6 +265,7 @@ template <> struct ChunkS<256> {
     const uint2 x0 = xp[0], x1 = xp[64];
     k256_group<0>(w[0].x, w[0].y, w[0].z, w[0].w, base, x0.x, x0.y, acc);
     k256_group<1024>(w[1].x, w[1].y, w[1].z, w[1].w, base, x1.x, x1.y, acc);
+    acc_hazard_fence();
   }
 };
 
@@ -359,7 +366,6 @@ __global__ __launch_bounds__(kStreamWaves * 64) void gemv_stream_kernel(const Ge
     do {                                                                         \
       BUF.consume(LUT, BASE, x_s, lane, acc);                                    \
       if (LAST) {                                                                \
-        acc_hazard_fence();                                                      \
         const float v = wave_reduce8(acc, lane);                                 \
         store_rows(y, batch.y_f32, RB, lane, v);                                 \
         _Pragma("unroll") for (int r = 0; r < 8; ++r) acc[r] = 0.f;              \

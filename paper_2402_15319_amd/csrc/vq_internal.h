@@ -8,7 +8,7 @@ namespace vq {
 
 constexpr int kGroupRows = 8;
 constexpr int kGroupCols = 256;
-constexpr int kMaxProblemsPerLaunch = 64;
+constexpr int kMaxProblemsPerLaunch = 256;  // the problem table travels in the kernel arguments (14 KB)
 constexpr int kStreamMaxColBlocks = 96;   // widest x the streaming kernel stages in LDS (48 KB)
 
 // One matrix-vector product as the kernels see it (lives in the kernel arguments).
