@@ -5,7 +5,7 @@ A "step" is one per-token weight pass of a synthetic Llama-7B decoder: 32 layers
 {q,k,v,o 4096x4096; gate,up 11008x4096; down 4096x11008}, 2-D VQ, k=16, 8x256 groups,
 224 batch-1 products y = W x over 1.83 GB of distinct packed weights (so the pass is
 HBM-cold by construction).  The pass is issued through vq_gemv_multi (the whole pass
-in a handful of launches).  The JSON line also carries per-shape us/call of single
+in one launch: up to 256 products per launch).  The JSON line also carries per-shape us/call of single
 vq_gemv calls (HBM-cold rotation and cache-resident), the k=256 MLP shapes, the
 batched GEMM, the roofline of the dominant kernel and the CPU oracle timed on the
 host cores.
@@ -27,10 +27,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
-# HBM bytes one launch of the dominant kernel moves (56 matrices = 8 layers of the pass), from
+# HBM bytes one launch of the dominant kernel moves (the whole pass of 224 matrices), from
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled by a copy kernel of known size; the summary
 # and the commands are in profiles/gemv_stream_k16_llama7b_pass.md
-TRAFFIC_BYTES_PER_LAUNCH = 468916224
+TRAFFIC_BYTES_PER_LAUNCH = 1857648128
 MFMA_F16_PEAK_TFLOPS = 2500.0  # MI355X published dense fp16 matrix peak
 
 

@@ -300,30 +300,39 @@ __device__ __forceinline__ void k16_split_dword(uint32_t w, uint32_t& a, uint32_
 }
 
 // Sum 8 per-lane row accumulators over the 64 lanes.  Returns, in every lane, the
-// total of row (lane >> 3) & 7.  Halving exchange: 4 + 2 + 1 swaps, then 3 butterflies.
+// total of row (lane >> 3) & 7.  Halving exchange without LDS traffic: the two
+// cross-row steps use the gfx950 lane-swap instructions (v_permlane32_swap exchanges
+// the upper half of its first operand with the lower half of its second, so that
+// "first + second" adds lanes l and l^32 of one accumulator in the lower half and of
+// the other accumulator in the upper half; v_permlane16_swap does the same for the
+// odd rows of the first operand and the even rows of the second), the steps inside
+// a row of 16 lanes use DPP.  The s_nop around the swaps are the wait states between a
+// VALU write and a lane swap (and back) that the compiler cannot see inside asm.
+template <int CTRL> __device__ __forceinline__ float dpp_read(float v) {
+  return __builtin_bit_cast(
+      float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
+}
 __device__ __forceinline__ float wave_reduce8(const float (&a)[8], int lane) {
   float b[4], c[2];
-  bool up = lane & 32;
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    float send = up ? a[i] : a[i + 4];
-    float keep = up ? a[i + 4] : a[i];
-    b[i] = keep + __shfl_xor(send, 32);
+    float lo = a[i], hi = a[i + 4];
+    asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(lo), "+v"(hi));
+    b[i] = lo + hi;            // lanes 0..31: row i, lanes 32..63: row i + 4
   }
-  up = lane & 16;
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
-    float send = up ? b[i] : b[i + 2];
-    float keep = up ? b[i + 2] : b[i];
-    c[i] = keep + __shfl_xor(send, 16);
+    float lo = b[i], hi = b[i + 2];
+    asm volatile("s_nop 1\n\tv_permlane16_swap_b32 %0, %1\n\ts_nop 1" : "+v"(lo), "+v"(hi));
+    c[i] = lo + hi;            // even rows of 16 lanes: row i (+4), odd rows: row i + 2 (+4)
   }
-  up = lane & 8;
-  float send = up ? c[0] : c[1];
-  float keep = up ? c[1] : c[0];
-  float v = keep + __shfl_xor(send, 8);
-  v += __shfl_xor(v, 4);
-  v += __shfl_xor(v, 2);
-  v += __shfl_xor(v, 1);
+  const bool up = lane & 8;
+  const float send = up ? c[0] : c[1];
+  const float keep = up ? c[1] : c[0];
+  float v = keep + dpp_read<0x128>(send);      // row_ror:8 = lane ^ 8 inside a row of 16
+  v += dpp_read<0x141>(v);                      // row_half_mirror: the other quad of the 8 lanes
+  v += dpp_read<0x4E>(v);                       // quad_perm [2,3,0,1]
+  v += dpp_read<0xB1>(v);                       // quad_perm [1,0,3,2]
   return v;
 }
 

@@ -95,10 +95,8 @@ template <> struct Chunk<16> {
     k16_group<64>(w[0].z, w[0].w, base, xb[0].x, xb[0].y, acc);
     k16_group<128>(w[1].x, w[1].y, base, xa[1].x, xa[1].y, acc);
     k16_group<192>(w[1].z, w[1].w, base, xb[1].x, xb[1].y, acc);
-    if (np <= 2) {            // short strips of a finely split row-block: half the work
-      acc_hazard_fence();
-      return;
-    }
+    acc_hazard_fence();       // before the branch: the compiler may copy accumulators at it
+    if (np <= 2) return;      // short strips of a finely split row-block: half the work
     k16_group<256>(w[2].x, w[2].y, base, xa[2].x, xa[2].y, acc);
     k16_group<320>(w[2].z, w[2].w, base, xb[2].x, xb[2].y, acc);
     k16_group<384>(w[3].x, w[3].y, base, xa[3].x, xa[3].y, acc);
