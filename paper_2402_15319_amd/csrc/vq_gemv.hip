@@ -204,9 +204,13 @@ template <> struct ChunkS<16> {
     const int cb_off = min(lane * 4, max(np * 32 - 4, 0));
     cbv = zero_unless(lane * 4 < np * 32,
                       stream_load16(S.cb_rb + (size_t)(np > 0 ? u : 0) * 32 + cb_off));
+    // uniform base + 32-bit lane offset: the opaque copy keeps the zero-extension next to the
+    // load, where it folds into the scalar-base addressing mode (no 64-bit vector adds)
+    uint32_t voff = (uint32_t)lane * 16u;
+    asm volatile("" : "+v"(voff));
 #pragma unroll
     for (int s = 0; s < 4; ++s)
-      w[s] = stream_load16(S.idx_rb + (size_t)(s < np ? u + s : 0) * 1024 + lane * 16);
+      w[s] = stream_load16(S.idx_rb + (size_t)(s < np ? u + s : 0) * 1024 + voff);
   }
 
   // x_s: the workgroup's LDS copy of x (natural order: lane L's 4 halfs of col-block c
@@ -245,12 +249,14 @@ template <> struct ChunkS<256> {
 
   __device__ __forceinline__ void load(const Strip& S, int u, int lane) {
     u0 = u;
+    uint32_t voff = (uint32_t)lane * 16u;      // see ChunkS<16>::load
+    asm volatile("" : "+v"(voff));
 #pragma unroll
     for (int s = 0; s < 2; ++s) {
       const bool ok = u + s < S.u_end;
       const int c = ok ? u + s : 0;
-      w[s] = stream_load16(S.idx_rb + (size_t)c * 1024 + lane * 16);
-      cbv[s] = zero_unless(ok, stream_load16(S.cb_rb + (size_t)c * 256 + lane * 4));
+      w[s] = stream_load16(S.idx_rb + (size_t)c * 1024 + voff);
+      cbv[s] = zero_unless(ok, stream_load16(reinterpret_cast<const uint8_t*>(S.cb_rb + (size_t)c * 256) + voff));
     }
   }
 
