@@ -176,6 +176,27 @@ def main():
     del probe
     log(f"[bench] stream-read ceiling: {stream_read_gbs:.0f} GB/s")
     if not args.no_extras:
+        # 8 layers of the same model with k = 256 (8-bit indices, 1 KB codebook per group:
+        # 8 bits per value, 1.62 GB, HBM-cold): a quarter of the lookups per byte
+        s256 = [workloads.VQShape(workloads.CONFIGS[key].out_features, workloads.CONFIGS[key].in_features, 256, 8)
+                for _ in range(8) for (_, key) in workloads.LLAMA7B_LAYER]
+        m256 = []
+        for s in s256:
+            desc = vqdev.desc_from_shape(s)
+            ib, cbb = vq.vq_layout_bytes(desc)
+            m256.append((s, desc, torch.randint(0, 256, (ib,), dtype=torch.uint8, device=dev),
+                         (torch.randn(cbb // 2, device=dev) * 0.02).half().view(torch.uint8)))
+        y256 = [torch.empty(s.out_features, dtype=torch.float16, device=dev) for s in s256]
+        a256 = vq.GemvMultiArgs([m[1] for m in m256], [m[2] for m in m256], [m[3] for m in m256],
+                                [xs[m[0].in_features] for m in m256], y256)
+        b256 = sum(algorithmic_bytes(s) for s in s256)
+        ms256, _ = timer.run(lambda: vq.vq_gemv_multi(a256), max(10, args.steps // 4), 20)
+        extras["llama7b_8_layers_k256_via_vq_gemv_multi"] = {
+            "us": ms256 * 1e3, "bytes": b256, "GB/s": b256 / ms256 / 1e6,
+            "frac_hbm": b256 / ms256 / 1e6 / HBM_PEAK_GBS, "kernel": "gemv_stream_kernel<256>"}
+        log(f"[bench] 8 layers with k=256: {ms256 * 1e3:.1f} us, {b256 / ms256 / 1e6:.0f} GB/s")
+        del m256, y256, a256
+
         # the same pass as 224 separate vq_gemv calls (plain stream launches)
         def step_single():
             for i, (_, s, desc, idx_d, cb_d) in enumerate(mats):
@@ -185,6 +206,18 @@ def main():
             "us_per_pass": ms_single * 1e3, "GB/s": pass_bytes / ms_single / 1e6,
             "us_per_call": ms_single * 1e3 / len(mats), "wall_us_per_pass": wall_single * 1e3}
         log(f"[bench] pass via {len(mats)} vq_gemv calls: {ms_single * 1e3:.1f} us/step")
+
+        # the same 224 separate launches captured once in a HIP graph and replayed: what the
+        # per-matrix path costs without the host launch path
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step_single()
+        ms_graph, _ = timer.run(graph.replay, max(2, args.steps // 4), 2)
+        extras["pass_as_separate_vq_gemv_calls_in_hip_graph"] = {
+            "us_per_pass": ms_graph * 1e3, "GB/s": pass_bytes / ms_graph / 1e6,
+            "us_per_call": ms_graph * 1e3 / len(mats)}
+        log(f"[bench] pass via {len(mats)} vq_gemv calls in a HIP graph: {ms_graph * 1e3:.1f} us/step")
+        del graph
 
         # per-shape us/call: HBM-cold (rotate over the distinct matrices of the pass) and
         # cache-resident (same matrix every call)
@@ -243,14 +276,25 @@ def main():
             if key == "mlp_up_11008x4096_k256":
                 # batched / prefill GEMM on the same matrix, next to a dense fp16 GEMM on decoded W
                 Wd = torch.empty((s0.out_features, s0.in_features), dtype=torch.float16, device=dev)
+
+                def decode_cold():
+                    a, b = copies[state["i"] % len(copies)]
+                    state["i"] += 1
+                    vq.vq_decode_dense(desc, a, b, Wd)
+                ms_dec, _ = timer.run(decode_cold, 60, 12)
+                nb_dec = nb + 2 * s0.out_features * s0.in_features      # compressed in, fp16 W out
+                extras["decode_dense_11008x4096_k256"] = {
+                    "us": ms_dec * 1e3, "bytes_in_plus_out": nb_dec, "GB/s": nb_dec / ms_dec / 1e6,
+                    "frac_hbm": nb_dec / ms_dec / 1e6 / HBM_PEAK_GBS}
+                log(f"[bench] decode_dense {key}: {ms_dec * 1e3:.1f} us, {nb_dec / ms_dec / 1e6:.0f} GB/s in+out")
                 vq.vq_decode_dense(desc, copies[0][0], copies[0][1], Wd)
                 gemm = {}
                 for B in (16, 256, 2048):
                     X = torch.randn((s0.in_features, B), device=dev, dtype=torch.float32).half()
                     Y = torch.empty((s0.out_features, B), dtype=torch.float16, device=dev)
                     ms_g, _ = timer.run(lambda: vq.vq_gemm_batched(desc, copies[0][0], copies[0][1], X, B, B, Y, B),
-                                        10, 2)
-                    ms_d, _ = timer.run(lambda: torch.matmul(Wd, X, out=Y), 10, 2)
+                                        40, 10)
+                    ms_d, _ = timer.run(lambda: torch.matmul(Wd, X, out=Y), 40, 10)
                     fl = 2.0 * s0.out_features * s0.in_features * B
                     gemm[f"B{B}"] = {"us": ms_g * 1e3, "TFLOP/s": fl / ms_g / 1e9,
                                      "frac_mfma_f16": fl / ms_g / 1e9 / MFMA_F16_PEAK_TFLOPS,

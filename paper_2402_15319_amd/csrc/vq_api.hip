@@ -1,5 +1,6 @@
 // C ABI of libvq: argument validation on the host, then one launch per call.
 // Nothing here allocates, synchronises or keeps state.
+#include <stddef.h>
 #include <string.h>
 #include "vq_internal.h"
 
@@ -126,8 +127,8 @@ int vq_gemv_multi(int count, const vq_desc* descs, const void* const* idx_dev,
     const int splits = choose_splits(rb_launch);
     const bool stream_mode = splits == 1 && max_n_cb <= kStreamMaxColBlocks &&
                              gemv_stream_lds_bytes(descs[0].k, max_n_cb) <= 65536;
-    GemvBatch batch;
-    memset(&batch, 0, sizeof(batch));
+    GemvBatch batch;                       // 14 KB on the stack; only the used entries are filled
+    memset(&batch, 0, offsetof(GemvBatch, p) + (size_t)n * sizeof(GemvProblem));
     batch.count = n;
     batch.y_f32 = (y_dtype == VQ_F32);
     long long items = 0;   // row-blocks (stream mode) or workgroups (split mode)

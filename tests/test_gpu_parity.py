@@ -268,3 +268,66 @@ def test_gemm_config5(env, B):
     err = oracle.normwise_rel_err(Y[:, cols], ref)
     print(f"gemm B={B} normwise rel err {err:.3e}")
     assert err <= TOL_F16
+
+
+def test_entry_points_replay_in_a_hip_graph(env):
+    """Every hot-path entry point captured in one HIP graph (they allocate nothing and only
+    enqueue kernels on the given stream); each replay, with eager work in between, must
+    reproduce the eager results bit for bit (the kernels are deterministic) and match the oracle."""
+    torch, vq, vqdev = env
+    dev = "cuda:0"
+    shapes = [_shape(40, 768, 16), _shape(264, 1024, 16), _shape(72, 1280, 256)]
+    mats = []
+    for i, s in enumerate(shapes):
+        desc, idx, cb, idx_d, cb_d = _setup(env, s, 900 + i)
+        x = workloads.make_x(s.in_features, 900 + i)
+        mats.append((s, desc, idx, cb, idx_d, cb_d, x, vqdev.to_device_bytes(x)))
+    big = _shape(32776, 768, 16)                       # reaches the persistent streaming kernel
+    bdesc, bidx, bcb, bidx_d, bcb_d = _setup(env, big, 903)
+    bx = workloads.make_x(big.in_features, 903)
+    bx_d = vqdev.to_device_bytes(bx)
+    B = 40
+    X = workloads.make_X(shapes[1].in_features, B, 904)
+    X_d = vqdev.to_device_bytes(X)
+
+    def outputs():
+        return ([torch.zeros(m[0].out_features, dtype=torch.float16, device=dev) for m in mats],
+                [torch.zeros(m[0].out_features, dtype=torch.float16, device=dev) for m in mats[:2]],
+                torch.zeros(big.out_features, dtype=torch.float16, device=dev),
+                torch.zeros((shapes[1].out_features, B), dtype=torch.float16, device=dev),
+                torch.zeros((shapes[0].out_features, shapes[0].in_features), dtype=torch.int16, device=dev))
+
+    def enqueue(o):
+        ys, ym, yb, Y, W = o
+        for m, y in zip(mats, ys):
+            vq.vq_gemv(m[1], m[4], m[5], m[7], y)
+        vq.vq_gemv_multi([m[1] for m in mats[:2]], [m[4] for m in mats[:2]], [m[5] for m in mats[:2]],
+                         [m[7] for m in mats[:2]], ym)
+        vq.vq_gemv(bdesc, bidx_d, bcb_d, bx_d, yb)
+        vq.vq_gemm_batched(mats[1][1], mats[1][4], mats[1][5], X_d, B, B, Y, B)
+        vq.vq_decode_dense(mats[0][1], mats[0][4], mats[0][5], W)
+
+    def flat(o):
+        ys, ym, yb, Y, W = o
+        return [t.cpu().numpy().copy() for t in (*ys, *ym, yb, Y, W)]
+
+    eager = outputs()
+    enqueue(eager)                     # also warms every cached launch parameter
+    torch.cuda.synchronize()
+    want = flat(eager)
+    for m, y in zip(mats, want[:3]):
+        assert oracle.normwise_rel_err(y, oracle.gemv(_fmt(m[0]), m[2], m[3], m[6])) <= TOL_F16
+    assert oracle.normwise_rel_err(want[5], oracle.gemv(_fmt(big), bidx, bcb, bx)) <= TOL_F16
+
+    captured = outputs()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        enqueue(captured)
+    for replay in range(3):
+        for t in (*captured[0], *captured[1], captured[2], captured[3], captured[4]):
+            t.fill_(3)                  # eager work between replays; stale results cannot pass
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for a, b in zip(flat(captured), want):
+            np.testing.assert_array_equal(a.view(np.uint16), b.view(np.uint16))
