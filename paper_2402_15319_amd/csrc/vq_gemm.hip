@@ -290,6 +290,134 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const uint8_t* __restrict_
   }
 }
 
+// ---- tiny batches (B <= 16 per workgroup column): latency- and bandwidth-bound --------
+// 16 rows (two row-blocks) x 16 batch columns per workgroup, v_mfma_f32_16x16x32_f16.  The
+// four waves split K by col-block (wave w takes col-blocks w, w+4, ...) and share nothing
+// until the end: each wave decodes its two groups into a private LDS tile Wt[16][256],
+// transposes its X tile into a private Xt[16 columns][256 k], and multiplies; there is
+// no workgroup barrier inside the K loop, so the waves of a CU run out of step and hide
+// each other's latencies.  Indices, codebooks and X of the wave's next col-block load
+// into registers while the current one is processed.  The four partial 16 x 16 tiles meet
+// in LDS at the end.  Many small workgroups (out/16 per 16 columns) keep every CU streaming.
+typedef float f4v_t __attribute__((ext_vector_type(4)));
+
+// Writes a piece (8 k x 4 columns, transposed in registers) as 4 rows of Xt[column][k].
+__device__ __forceinline__ void store_xpiece_rows(const XPiece& p, uint16_t* Xt, int n_loc, int k0) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const uint32_t sel = (i & 1) ? 0x07060302u : 0x05040100u;
+    uint4 o;
+    o.x = __builtin_amdgcn_perm(i < 2 ? p.r[1].x : p.r[1].y, i < 2 ? p.r[0].x : p.r[0].y, sel);
+    o.y = __builtin_amdgcn_perm(i < 2 ? p.r[3].x : p.r[3].y, i < 2 ? p.r[2].x : p.r[2].y, sel);
+    o.z = __builtin_amdgcn_perm(i < 2 ? p.r[5].x : p.r[5].y, i < 2 ? p.r[4].x : p.r[4].y, sel);
+    o.w = __builtin_amdgcn_perm(i < 2 ? p.r[7].x : p.r[7].y, i < 2 ? p.r[6].x : p.r[6].y, sel);
+    *reinterpret_cast<uint4*>(Xt + wt_half_index(n_loc + i, k0)) = o;
+  }
+}
+
+template <int K>
+__global__ __launch_bounds__(256, 2) void gemm_tiny_kernel(const uint8_t* __restrict__ idx,
+                                                           const uint32_t* __restrict__ cb,
+                                                           const uint16_t* __restrict__ X, int B,
+                                                           int ldx, void* __restrict__ Y, int ldy,
+                                                           int y_f32, int n_rb, int n_cb) {
+  __shared__ __attribute__((aligned(16))) uint16_t Wt_all[4][16 * WS];
+  __shared__ __attribute__((aligned(16))) uint16_t Xt_all[4][16 * WS];
+  __shared__ __attribute__((aligned(16))) uint32_t lut_all[4][2 * K];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  uint16_t* Wt = Wt_all[wave];
+  uint16_t* Xt = Xt_all[wave];
+  uint32_t* lut = lut_all[wave];
+
+  const long long rb0 = 2ll * blockIdx.x;
+  const long long rb1 = min(rb0 + 1, (long long)n_rb - 1);   // odd tail: decoded twice, stored once
+  const int n0 = blockIdx.y * 16;
+
+  // the lane's two X pieces of a col-block: k-octets o and o + 16, columns 4q..4q+3
+  const int q = lane & 3, o = lane >> 2;
+  const int n_glob = n0 + 4 * q;
+  const bool n_ok = n_glob < B;
+  const int n_ld = n_ok ? n_glob : 0;
+  const uint32_t n_mask = n_ok ? 0xffffffffu : 0u;
+
+  f4v_t acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+  GroupRegs<K> g[2][2];
+  XPiece xp[2][2];
+
+  // every load is issued whether or not the col-block exists (clamped), so that the number
+  // of loads in flight is static and the waits stay partial
+#define VQ_ISSUE(SLOT, C)                                                              \
+  {                                                                                    \
+    const int cc = min((C), n_cb - 1);                                                 \
+    load_group<K>(g[SLOT][0], idx, cb, rb0, cc, n_cb, lane);                           \
+    load_group<K>(g[SLOT][1], idx, cb, rb1, cc, n_cb, lane);                           \
+    load_xpiece(xp[SLOT][0], X, (size_t)cc * 256 + 8 * o, ldx, n_ld, true);            \
+    load_xpiece(xp[SLOT][1], X, (size_t)cc * 256 + 8 * (o + 16), ldx, n_ld, true);     \
+  }
+#define VQ_PROCESS(SLOT)                                                               \
+  {                                                                                    \
+    decode_group<K>(g[SLOT][0], lut, Wt, 0, lane);                                     \
+    decode_group<K>(g[SLOT][1], lut + K, Wt, 8, lane);                                 \
+    _Pragma("unroll") for (int h = 0; h < 2; ++h) {                                    \
+      _Pragma("unroll") for (int r = 0; r < 8; ++r) {                                  \
+        xp[SLOT][h].r[r].x &= n_mask;                                                  \
+        xp[SLOT][h].r[r].y &= n_mask;                                                  \
+      }                                                                                \
+      store_xpiece_rows(xp[SLOT][h], Xt, 4 * q, 8 * (o + 16 * h));                     \
+    }                                                                                  \
+    wave_lds_sync();                                                                   \
+    _Pragma("unroll") for (int kk = 0; kk < 8; ++kk) {                                 \
+      const int k0 = 32 * kk + 8 * (lane >> 4);                                        \
+      const h8_t av = *reinterpret_cast<const h8_t*>(Wt + wt_half_index(lane & 15, k0)); \
+      const h8_t bv = *reinterpret_cast<const h8_t*>(Xt + wt_half_index(lane & 15, k0)); \
+      if (kk & 1) acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bv, acc1, 0, 0, 0); \
+      else acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bv, acc0, 0, 0, 0);       \
+    }                                                                                  \
+  }
+
+  VQ_ISSUE(0, wave)
+  for (int c = wave; c < n_cb; c += 8) {
+    VQ_ISSUE(1, c + 4)
+    VQ_PROCESS(0)
+    VQ_ISSUE(0, c + 8)
+    if (c + 4 < n_cb) VQ_PROCESS(1)
+  }
+#undef VQ_ISSUE
+#undef VQ_PROCESS
+
+  // four partial 16 x 16 tiles -> LDS -> sum -> Y   (lane l holds rows 4*(l/16)+i, column l%16)
+  __syncthreads();
+  float* part = reinterpret_cast<float*>(Wt_all[0]);      // 4 x 256 floats
+  const f4v_t acc = acc0 + acc1;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) part[wave * 256 + (4 * (lane >> 4) + i) * 16 + (lane & 15)] = acc[i];
+  __syncthreads();
+  {
+    const int m = tid >> 4, nl = tid & 15;
+    const float sum = part[tid] + part[256 + tid] + part[512 + tid] + part[768 + tid];
+    const long long row = rb0 * 8 + m;
+    const int n = n0 + nl;
+    if (row < (long long)n_rb * 8 && n < B) {
+      const size_t off = (size_t)row * ldy + n;
+      if (y_f32) reinterpret_cast<float*>(Y)[off] = sum;
+      else reinterpret_cast<_Float16*>(Y)[off] = (_Float16)sum;
+    }
+  }
+}
+
+template <int K>
+hipError_t launch_tiny(const vq_desc& d, const void* idx_dev, const void* cb_dev, const void* X,
+                       int B, int ldx, void* Y, int ldy, int y_f32, hipStream_t s) {
+  const int n_rb = d.out_features / kGroupRows, n_cb = d.in_features / kGroupCols;
+  const dim3 grid((unsigned)((n_rb + 1) / 2), (unsigned)((B + 15) / 16));
+  hipLaunchKernelGGL((gemm_tiny_kernel<K>), grid, dim3(256), 0, s, (const uint8_t*)idx_dev,
+                     (const uint32_t*)cb_dev, (const uint16_t*)X, B, ldx, Y, ldy, y_f32, n_rb, n_cb);
+  return hipGetLastError();
+}
+
 // ---- small batches (B <= 32): bandwidth-bound ---------------------------------
 // 32 rows x 32 batch columns per workgroup (many workgroups, so that every CU streams
 // weights); the whole col-block of X is staged at once and wave w multiplies its own
@@ -451,14 +579,22 @@ hipError_t launch_one(const vq_desc& d, const void* idx_dev, const void* cb_dev,
 
 hipError_t launch_gemm(const vq_desc& d, const void* idx_dev, const void* cb_dev, const void* X,
                        int B, int ldx, void* Y, int ldy, int y_f32, hipStream_t s) {
-  // small batches are bandwidth-bound: 32-row tiles (many workgroups), 32 batch columns;
-  // large ones are matrix-core-bound: 64 x 128 tiles
+  // B <= 16: 16 x 16 tiles, barrier-free (gemm_tiny_kernel).  It re-decodes W once per 16
+  // columns, which still pays up to 64 columns when the matrix is too short to fill the CUs
+  // with the 32-row tiles of the other kernels (measured on 4096 x 4096 and 11008 x 4096).
+  // Then 32 x 32 tiles (small batches, bandwidth-bound), and 32/64-row x 128/256-column
+  // tiles for the matrix-core-bound sizes.
+  const int n_rb = d.out_features / kGroupRows;
+  const bool short_matrix = n_rb < 1024;
+  const bool tiny = B <= 16 || (B <= 64 && short_matrix);
   if (d.k == 16) {
+    if (tiny) return launch_tiny<16>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);
     if (B <= 32) return launch_small<16>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);
     if (B <= 128) return launch_one<16, 1, 128>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);
     if (B <= 512) return launch_one<16, 2, 128>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);
     return launch_one<16, 2, 256>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);
   }
+  if (tiny) return launch_tiny<256>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);
   if (B <= 32) return launch_small<256>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);
   if (B <= 128) return launch_one<256, 1, 128>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);
   if (B <= 512) return launch_one<256, 2, 128>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);

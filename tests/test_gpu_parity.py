@@ -248,6 +248,18 @@ def test_gemm_small(env, s, B, f32):
     assert oracle.normwise_rel_err(Y, ref) <= (TOL_F32 if f32 else TOL_F16)
 
 
+# 1025 row-blocks: tall enough for the 32-row small-batch kernel (B = 24) and the 128-column
+# kernel at B = 48 / 100; shorter matrices take the 16 x 16-tile kernel up to 64 columns
+@pytest.mark.parametrize("B", [16, 24, 48, 100])
+@pytest.mark.parametrize("s", [_shape(8200, 512, 16), _shape(8200, 768, 256)], ids=str)
+def test_gemm_tall(env, s, B):
+    desc, idx, cb, idx_d, cb_d = _setup(env, s, 405)
+    X = workloads.make_X(s.in_features, B, 405)
+    Y = _gpu_gemm(env, desc, idx_d, cb_d, X, False)
+    ref = oracle.gemm(_fmt(s), idx, cb, X)
+    assert oracle.normwise_rel_err(Y, ref) <= TOL_F16
+
+
 @pytest.mark.parametrize("B", [16, 256, 2048])
 def test_gemm_config5(env, B):
     """W[11008,4096] k=256 times X[4096,B].  The oracle computes the whole Y for B <= 256
