@@ -10,8 +10,10 @@ What is computed (paper passages followed, restated):
   every run of d values of the tensor is replaced by the index of one
   centroid, stored in ceil(log2 k) bits.
 * Sec. 3.1: the tensor is split into groups; each group is stored as a
-  tuple (indices, lookup table, scale).  Here centroids are fp16 with the
-  scale already folded in, so a group is (indices, table).
+  tuple (indices, lookup table, scale).  Two table types: fp16 centroids
+  with the scale already folded in (a group is (indices, table)), or int8
+  tables with an fp16 scale per group (dequantise_codebooks turns the
+  latter into the former; everything downstream is shared).
 * Sec. 4 (GPTVQ paragraph): a vector spans d consecutive *columns* of one
   row (the input dimension); groups are at most 256 columns wide, e.g.
   2,048 weights = 8 rows x 256 columns.
@@ -169,6 +171,37 @@ def gemm(f: VQFormat, idx: np.ndarray, cb: np.ndarray, X: np.ndarray) -> np.ndar
     if X64.ndim != 2 or X64.shape[0] != f.in_features:
         raise ValueError("X has the wrong shape")
     return W @ X64
+
+
+def dequantise_codebooks(q: np.ndarray, scale: np.ndarray) -> np.ndarray:
+    """Integer lookup tables with a scale factor per group -> fp16 codebooks.
+
+    Sec. 3.1: a group is stored as the tuple (indices, lookup table, quantisation
+    scale factor); the appendix on codebook compression makes 8-bit integer tables the
+    default.  Sec. 3.2 decodes an index to a signed 8-bit integer.  On this path the
+    native type is fp16, so a centroid value is the product scale_g * q taken exactly
+    and rounded ONCE to fp16 (round to nearest even); this is what the dense
+    reconstruction returns bit for bit.  q: int8[n_groups, k, d], scale: fp16[n_groups].
+    """
+    q = np.asarray(q)
+    scale = np.asarray(scale)
+    if q.dtype != np.int8 or scale.dtype != np.float16:
+        raise ValueError("q must be int8 and scale fp16")
+    if q.ndim != 3 or scale.shape != (q.shape[0],):
+        raise ValueError("q is [n_groups, k, d], scale is [n_groups]")
+    # fp16 (11 significant bits) times int8 is exact in fp64; the cast rounds once
+    exact = scale.astype(np.float64)[:, None, None] * q.astype(np.float64)
+    return exact.astype(np.float16)
+
+
+def canonical_sizes_i8(f: VQFormat) -> tuple[int, int]:
+    """(index bytes, table bytes) with int8 tables and one fp16 scale per group.
+
+    The table buffer holds q[n_groups, k, d] int8, zero-padded to a multiple of 16
+    bytes, followed by scale[n_groups] fp16.
+    """
+    q_bytes = f.n_groups * f.k * f.d
+    return f.n_groups * f.group_index_bytes, (q_bytes + 15) // 16 * 16 + 2 * f.n_groups
 
 
 def normwise_rel_err(y, y_ref) -> float:

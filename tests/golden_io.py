@@ -7,7 +7,7 @@ GOLDEN_DIR = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
 
 def read_case(name):
     """Parse a decode_*.txt fixture into a dict of plain arrays."""
-    out = {"codebook": [], "W": []}
+    out = {"codebook": [], "W": [], "q": []}
     with open(os.path.join(GOLDEN_DIR, name)) as fh:
         for line in fh:
             line = line.strip()
@@ -21,12 +21,17 @@ def read_case(name):
                 out["idx"] = np.array([int(t, 16) for t in rest.split()], dtype=np.uint8)
             elif key in ("codebook", "W"):
                 out[key].append([float(t) for t in rest.split()])
+            elif key == "q":          # int8 lookup table of one group
+                out["q"].append([int(t) for t in rest.split()])
+            elif key == "scale":      # one scale per group
+                out["scale"] = np.array([float(t) for t in rest.split()], dtype=np.float64)
             elif key in ("x", "y"):
                 out[key] = np.array([float(t) for t in rest.split()], dtype=np.float64)
             else:
                 raise ValueError(f"unknown key {key!r} in {name}")
     fmt = out["format"]
     out["codebook"] = np.array(out["codebook"], dtype=np.float64).reshape(-1, fmt["k"], fmt["d"])
+    out["q"] = np.array(out["q"], dtype=np.int64).reshape(-1, fmt["k"], fmt["d"])
     out["W"] = np.array(out["W"], dtype=np.float64)
     return out
 

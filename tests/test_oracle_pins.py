@@ -276,3 +276,104 @@ def test_bad_inputs_raise():
     f3 = VQFormat(1, 16, 5, 3, 1, 16, 2)
     with pytest.raises(ValueError):
         oracle.unpack_indices(f3, np.full(3, 0xFF, dtype=np.uint8))
+
+
+# ---------------------------------------------------------------- 6-bit indices, int8 tables with a scale
+def test_golden_six_bit_indices():
+    """The paper's deployed index width: fields that straddle byte boundaries in a 3-byte stream."""
+    case = read_case("decode_1x8_k64_b6.txt")
+    f = _fmt(case)
+    cb = case["codebook"].astype(np.float16)
+    np.testing.assert_array_equal(oracle.unpack_indices(f, case["idx"]), [[37, 2, 63, 40]])
+    W = oracle.decode_dense(f, case["idx"], cb).view(np.float16).astype(np.float64)
+    np.testing.assert_array_equal(W, case["W"])
+    np.testing.assert_array_equal(oracle.gemv(f, case["idx"], cb, case["x"].astype(np.float16)), case["y"])
+
+
+def test_golden_int8_tables_with_scale():
+    """A dropped scale, a scale applied per matrix instead of per group, truncation instead of
+    round-to-nearest-even (the 3*s entry is an exact tie) or a double rounding fails here."""
+    case = read_case("decode_2x8_k4_b2_i8.txt")
+    f = _fmt(case)
+    cb = oracle.dequantise_codebooks(case["q"].astype(np.int8), case["scale"].astype(np.float16))
+    assert cb.dtype == np.float16 and cb.shape == (2, 4, 2)
+    W = oracle.decode_dense(f, case["idx"], cb).view(np.float16).astype(np.float64)
+    np.testing.assert_array_equal(W, case["W"])
+    np.testing.assert_array_equal(oracle.gemv(f, case["idx"], cb, case["x"].astype(np.float16)), case["y"])
+
+
+def _fp16_nearest_even(value: Fraction) -> float:
+    """Round an exact rational to fp16 by searching the table of all finite fp16 values
+    (no float cast involved): nearest, ties to the value whose bit pattern is even."""
+    bits = np.arange(0, 0x7C00, dtype=np.uint16)                 # non-negative finite patterns, ascending
+    vals = bits.view(np.float16).astype(np.float64)
+    sign = -1 if value < 0 else 1
+    mag = abs(value)
+    hi = int(np.searchsorted(vals, float(mag), side="left"))     # float(mag) is exact here (< 2^53 scale)
+    if hi < len(vals) and Fraction(vals[hi]) == mag:
+        return sign * vals[hi]
+    lo = hi - 1
+    assert 0 <= lo and hi < len(vals)
+    d_lo, d_hi = mag - Fraction(vals[lo]), Fraction(vals[hi]) - mag
+    pick = lo if d_lo < d_hi else hi if d_hi < d_lo else (lo if bits[lo] % 2 == 0 else hi)
+    return sign * vals[pick]
+
+
+def test_dequantise_is_one_correct_rounding_of_the_exact_product():
+    """Exact rational product, rounded by table search, against the oracle on random and
+    adversarial (scale, q) pairs: subnormal results, ties, the largest magnitudes."""
+    rng = np.random.default_rng(7)
+    scales = np.concatenate([
+        rng.uniform(1e-4, 2.0, 40), [6.1e-5, 5.96e-8, 3e-7, 0.1, 1.0, 255.0, 500.0]]).astype(np.float16)
+    q = rng.integers(-128, 128, size=(len(scales), 8, 2), dtype=np.int8)
+    q[:, 0, 0], q[:, 0, 1], q[:, 1, 0], q[:, 1, 1] = 127, -128, 3, 1
+    got = oracle.dequantise_codebooks(q, scales).astype(np.float64)
+    for g in range(len(scales)):
+        s = Fraction(float(scales[g]))
+        for j in range(8):
+            for t in range(2):
+                assert got[g, j, t] == _fp16_nearest_even(s * int(q[g, j, t])), (float(scales[g]), int(q[g, j, t]))
+
+
+def test_dequantise_special_scales():
+    """scale 1 returns the integers, a power of two scales exactly, negating q negates W."""
+    q = np.arange(-128, 128, dtype=np.int8).reshape(1, 128, 2)
+    one = oracle.dequantise_codebooks(q, np.array([1.0], dtype=np.float16)).astype(np.float64)
+    np.testing.assert_array_equal(one, q.astype(np.float64))
+    eighth = oracle.dequantise_codebooks(q, np.array([0.125], dtype=np.float16)).astype(np.float64)
+    np.testing.assert_array_equal(eighth, q.astype(np.float64) / 8)
+    s = np.array([0.0371], dtype=np.float16)
+    qq = np.arange(-127, 127, dtype=np.int8).reshape(1, 127, 2)
+    np.testing.assert_array_equal(oracle.dequantise_codebooks((-qq).astype(np.int8), s).astype(np.float64),
+                                  -oracle.dequantise_codebooks(qq, s).astype(np.float64))
+    with pytest.raises(ValueError):
+        oracle.dequantise_codebooks(q.astype(np.int16), np.array([1.0], dtype=np.float16))
+    with pytest.raises(ValueError):
+        oracle.dequantise_codebooks(q, np.array([1.0, 2.0], dtype=np.float16))
+
+
+def test_deployed_format_sizes_follow_the_bpv_formula():
+    """2-D VQ, 6-bit indices, int8 tables, groups of 8,192 weights: 3.125 bits per value
+    (Sec. 5.1) plus the 16-bit scale per group that the formula leaves out."""
+    for key in ("attn_4096x4096_k64_i8", "mlp_up_11008x4096_k64_i8", "mlp_down_4096x11008_k64_i8"):
+        s = workloads.CONFIGS[key]
+        f = VQFormat(s.out_features, s.in_features, s.k, s.index_bits, s.group_rows, s.group_cols, s.d)
+        ib, tb = oracle.canonical_sizes_i8(f)
+        assert (ib, tb) == workloads.canonical_sizes(s)
+        n = s.out_features * s.in_features
+        bits = Fraction((ib + tb) * 8, n)
+        want = Fraction(6, 2) + Fraction(64 * 2 * 8 + 16, 8192)
+        pad_bits = Fraction(((-(f.n_groups * 128)) % 16) * 8, n)
+        assert bits == want + pad_bits
+        assert math.isclose(oracle.bits_per_value(64, 2, 8, 8192), 3.125)
+
+
+def test_i8_workload_generator_shapes():
+    s = workloads.CONFIGS["tiny_64x512_k64_i8"]
+    idx, q, scale = workloads.make_weights_i8(s, 3)
+    assert idx.dtype == np.uint8 and idx.size == 2 * 2 * 3072
+    assert q.dtype == np.int8 and q.shape == (4, 64, 2) and q.min() >= -127
+    assert scale.dtype == np.float16 and scale.shape == (4,) and (scale > 0).all()
+    f = VQFormat(64, 512, 64, 6, 32, 256, 2)
+    I = oracle.unpack_indices(f, idx)
+    assert I.shape == (4, 4096) and I.max() == 63 and I.min() == 0

@@ -12,7 +12,7 @@ rows by 256 columns"); every group owns a codebook of ``k`` centroids of
 of ``d`` consecutive columns (Sec. 4: d columns are quantised at a time).
 The byte-level order inside those arrays is fixed by the oracle, not here:
 the generators only need the total sizes, because a uniformly random byte
-stream *is* a uniformly random stream of 4- or 8-bit indices.
+stream *is* a uniformly random stream of b-bit indices whenever k = 2^b.
 """
 from __future__ import annotations
 
@@ -21,7 +21,8 @@ import numpy as np
 
 __all__ = [
     "VQShape", "CONFIGS", "LLAMA7B_LAYER", "seed_for", "canonical_sizes",
-    "make_weights", "make_x", "make_X", "llama7b_pass_shapes",
+    "make_weights", "make_weights_i8", "make_x", "make_X", "llama7b_pass_shapes",
+    "LLAMA7B_LAYER_K64",
 ]
 
 
@@ -35,6 +36,7 @@ class VQShape:
     group_rows: int = 8
     group_cols: int = 256
     d: int = 2
+    int8_tables: bool = False     # int8 centroids with one fp16 scale per group (Sec. 3.1)
 
     @property
     def n_groups(self) -> int:
@@ -49,6 +51,8 @@ def canonical_sizes(s: VQShape) -> tuple[int, int]:
     """(index bytes, codebook bytes) of the canonical arrays for shape ``s``."""
     idx_group_bits = s.vectors_per_group * s.index_bits
     assert idx_group_bits % 8 == 0
+    if s.int8_tables:    # int8 tables padded to 16 bytes, then one fp16 scale per group
+        return s.n_groups * (idx_group_bits // 8), (s.n_groups * s.k * s.d + 15) // 16 * 16 + 2 * s.n_groups
     return s.n_groups * (idx_group_bits // 8), s.n_groups * s.k * s.d * 2
 
 
@@ -60,6 +64,12 @@ CONFIGS = {
     "mlp_down_4096x11008_k256": VQShape(4096, 11008, 256, 8),
     "mlp_up_11008x4096_k16": VQShape(11008, 4096, 16, 4),
     "mlp_down_4096x11008_k16": VQShape(4096, 11008, 16, 4),
+    # the paper's deployed representation (Sec. 3.1, Sec. 5.1): 2-D VQ, 6-bit indices, int8
+    # tables with a scale per group, groups of 8,192 weights (32 rows x 256 columns): 3.125 bpv
+    "tiny_64x512_k64_i8": VQShape(64, 512, 64, 6, 32, 256, 2, True),
+    "attn_4096x4096_k64_i8": VQShape(4096, 4096, 64, 6, 32, 256, 2, True),
+    "mlp_up_11008x4096_k64_i8": VQShape(11008, 4096, 64, 6, 32, 256, 2, True),
+    "mlp_down_4096x11008_k64_i8": VQShape(4096, 11008, 64, 6, 32, 256, 2, True),
 }
 
 # One Llama-7B decoder layer as (name, shape key) in execution order.
@@ -72,6 +82,7 @@ LLAMA7B_LAYER = (
     ("up_proj", "mlp_up_11008x4096_k16"),
     ("down_proj", "mlp_down_4096x11008_k16"),
 )
+LLAMA7B_LAYER_K64 = tuple((n, k.replace("_k16", "_k64_i8")) for n, k in LLAMA7B_LAYER)
 LLAMA7B_N_LAYERS = 32
 
 _BASE_SEED = 15319 * 10
@@ -89,12 +100,29 @@ def make_weights(s: VQShape, seed: int, cb_std: float = 0.02):
     Indices are uniform (every byte uniform in [0,256) gives uniform 4- or 8-bit
     indices); centroids are N(0, cb_std) rounded to fp16.
     """
-    assert s.index_bits in (4, 8), "byte-uniform draw is only uniform for 4/8-bit indices"
+    assert s.k == 1 << s.index_bits, "a uniform byte stream is a uniform index stream only if k = 2^bits"
+    assert not s.int8_tables
     rng = np.random.default_rng(seed)
     idx_bytes, _ = canonical_sizes(s)
     idx = rng.integers(0, 256, size=idx_bytes, dtype=np.uint8)
     cb = rng.normal(0.0, cb_std, size=(s.n_groups, s.k, s.d)).astype(np.float16)
     return idx, cb
+
+
+def make_weights_i8(s: VQShape, seed: int, w_std: float = 0.02):
+    """Random canonical (idx_bytes uint8[...], q int8[n_groups,k,d], scale float16[n_groups]).
+
+    Indices uniform; table entries uniform in [-127, 127]; the scale of a group is drawn so
+    that scale * 127 is about 3 standard deviations of an N(0, w_std) weight, varying by
+    a factor of up to about 2 between groups.
+    """
+    assert s.k == 1 << s.index_bits and s.int8_tables
+    rng = np.random.default_rng(seed)
+    idx_bytes, _ = canonical_sizes(s)
+    idx = rng.integers(0, 256, size=idx_bytes, dtype=np.uint8)
+    q = rng.integers(-127, 128, size=(s.n_groups, s.k, s.d), dtype=np.int8)
+    scale = (3.0 * w_std / 127.0 * np.exp2(rng.uniform(-0.5, 0.5, size=s.n_groups))).astype(np.float16)
+    return idx, q, scale
 
 
 def make_x(n: int, seed: int) -> np.ndarray:
