@@ -27,8 +27,18 @@
  *   - indices: group g owns bytes [g*GB, (g+1)*GB), GB = group_rows*group_cols/d*index_bits/8,
  *     read as a little-endian bit stream: vector v is bits [v*index_bits, (v+1)*index_bits)
  *     (4-bit: even v in the low nibble; 8-bit: byte v);
- *   - codebooks: fp16 cb[g][j][t], j < k, t < d, contiguous, same g order.
+ *   - codebooks (VQ_F16): fp16 cb[g][j][t], j < k, t < d, contiguous, same g order;
+ *   - codebooks (VQ_I8; Sec. 3.1: a group is the tuple indices, lookup table, scale; the
+ *     appendix on codebook compression makes 8-bit tables the default): int8 q[g][j][t],
+ *     zero-padded to a multiple of 16 bytes, followed by one fp16 scale[g] per group.  The
+ *     centroid value is scale[g] * q taken exactly and rounded once to fp16 (nearest even);
+ *     that fp16 matrix is W for every entry point.
  * The device layout written by vq_pack_layout is private to the library.
+ *
+ * Implemented representations: VQ_F16 with 8 x 256 groups and k = 16 or 256; VQ_I8 with
+ * k = 64 (6-bit indices) and groups of 8, 16 or 32 rows x 256 columns (32 rows: the
+ * 8,192-weight groups and 3.125 bits per value of Sec. 5.1) for vq_pack_layout, vq_gemv,
+ * vq_gemv_multi and vq_decode_dense (vq_gemm_batched returns VQ_ERR_UNSUPPORTED for it).
  */
 #ifndef VQ_H_
 #define VQ_H_
@@ -53,18 +63,19 @@ typedef enum vq_status {
   VQ_ERR_BAD_ARG = -6      /* a scalar argument is out of range (batch, count, dtype)     */
 } vq_status;
 
-typedef enum vq_dtype { VQ_F16 = 1, VQ_F32 = 2 } vq_dtype;
+/* VQ_I8 as codebook_dtype: int8 lookup tables with one fp16 scale per group (Sec. 3.1). */
+typedef enum vq_dtype { VQ_F16 = 1, VQ_F32 = 2, VQ_I8 = 3 } vq_dtype;
 
 /* Shape of one vector-quantised matrix (Sec. 2.1, Sec. 3.1, Sec. 4). */
 typedef struct vq_desc {
   int32_t out_features;   /* rows of W (length of y)                                */
   int32_t in_features;    /* columns of W (length of x)                             */
-  int32_t group_rows;     /* 8                                                      */
+  int32_t group_rows;     /* 8 (VQ_I8: 8, 16 or 32)                                 */
   int32_t group_cols;     /* 256 (Sec. 4: at most 256 columns per group)            */
   int32_t d;              /* VQ dimensionality, 2                                   */
-  int32_t k;              /* centroids per codebook, 16 or 256                      */
-  int32_t index_bits;     /* log2(k): 4 or 8                                        */
-  int32_t codebook_dtype; /* VQ_F16                                                 */
+  int32_t k;              /* centroids per codebook: 16 or 256 (VQ_F16), 64 (VQ_I8) */
+  int32_t index_bits;     /* log2(k): 4, 8 or 6                                     */
+  int32_t codebook_dtype; /* VQ_F16 or VQ_I8                                        */
 } vq_desc;
 
 /* Human-readable name of a status code (host pointer to a static string). */

@@ -10,6 +10,12 @@ using namespace vq;
 
 bool is_pow2(int v) { return v > 0 && (v & (v - 1)) == 0; }
 
+// The two representations the kernels implement:
+//   fp16 codebooks, 8 x 256 groups, k = 16 (4-bit indices) or 256 (8-bit);
+//   int8 tables with one fp16 scale per group, k = 64 (6-bit indices), groups of 8, 16 or 32
+//   rows x 256 columns (32 rows = the 8,192-weight groups of Sec. 5.1).
+bool is_i8(const vq_desc& d) { return d.codebook_dtype == VQ_I8; }
+
 int check_desc(const vq_desc* d) {
   if (!d) return VQ_ERR_NULL;
   if (d->out_features <= 0 || d->in_features <= 0 || d->group_rows <= 0 || d->group_cols <= 0 ||
@@ -17,10 +23,16 @@ int check_desc(const vq_desc* d) {
     return VQ_ERR_BAD_DESC;
   if (!is_pow2(d->k) || d->k != (1 << d->index_bits)) return VQ_ERR_BAD_DESC;
   if (d->group_cols % d->d) return VQ_ERR_BAD_DESC;
-  if (d->codebook_dtype != VQ_F16) return VQ_ERR_UNSUPPORTED;
-  if (d->d != 2 || d->group_rows != kGroupRows || d->group_cols != kGroupCols) return VQ_ERR_UNSUPPORTED;
-  if (d->k != 16 && d->k != 256) return VQ_ERR_UNSUPPORTED;
-  if (d->out_features % kGroupRows || d->in_features % kGroupCols) return VQ_ERR_UNSUPPORTED;
+  if (d->codebook_dtype != VQ_F16 && d->codebook_dtype != VQ_I8) return VQ_ERR_UNSUPPORTED;
+  if (d->d != 2 || d->group_cols != kGroupCols) return VQ_ERR_UNSUPPORTED;
+  if (is_i8(*d)) {
+    if (d->k != 64) return VQ_ERR_UNSUPPORTED;
+    if (d->group_rows != 8 && d->group_rows != 16 && d->group_rows != 32) return VQ_ERR_UNSUPPORTED;
+  } else {
+    if (d->k != 16 && d->k != 256) return VQ_ERR_UNSUPPORTED;
+    if (d->group_rows != kGroupRows) return VQ_ERR_UNSUPPORTED;
+  }
+  if (d->out_features % d->group_rows || d->in_features % kGroupCols) return VQ_ERR_UNSUPPORTED;
   // index arithmetic inside the kernels uses 32-bit element offsets into x / rows
   if ((long long)d->out_features * d->in_features > (1ll << 40)) return VQ_ERR_UNSUPPORTED;
   return VQ_OK;
@@ -32,7 +44,12 @@ void sizes(const vq_desc& d, size_t* idx_bytes, size_t* cb_bytes) {
   const size_t n_groups = (size_t)(d.out_features / d.group_rows) * (d.in_features / d.group_cols);
   const size_t vecs = (size_t)d.group_rows * d.group_cols / d.d;
   if (idx_bytes) *idx_bytes = n_groups * (vecs * d.index_bits / 8);
-  if (cb_bytes) *cb_bytes = n_groups * (size_t)d.k * d.d * 2;
+  if (cb_bytes) {
+    if (is_i8(d))   // int8 tables padded to 16 bytes, then one fp16 scale per group
+      *cb_bytes = (n_groups * (size_t)d.k * d.d + 15) / 16 * 16 + 2 * n_groups;
+    else
+      *cb_bytes = n_groups * (size_t)d.k * d.d * 2;
+  }
 }
 
 int choose_splits(long long total_row_blocks) {
@@ -73,6 +90,7 @@ int vq_canonical_bytes(const vq_desc* desc, size_t* idx_bytes, size_t* cb_bytes)
     return VQ_ERR_UNSUPPORTED;
   if (((size_t)desc->group_rows * desc->group_cols / desc->d * desc->index_bits) % 8)
     return VQ_ERR_UNSUPPORTED;
+  if (desc->codebook_dtype != VQ_F16 && desc->codebook_dtype != VQ_I8) return VQ_ERR_UNSUPPORTED;
   sizes(*desc, idx_bytes, cb_bytes);
   return VQ_OK;
 }
@@ -83,6 +101,12 @@ int vq_layout_bytes(const vq_desc* desc, size_t* idx_bytes, size_t* cb_bytes) {
   // 4-bit row-blocks are stored as whole col-block pairs (an odd last one is padded)
   const size_t n_rb = desc->out_features / kGroupRows;
   const size_t n_cb = desc->in_features / kGroupCols;
+  if (desc->k == 64) {   // quads of 4 col-blocks: 3 KB of indices per 8-row block, 528 B of tables per group row
+    const size_t n_quads = (n_cb + 3) / 4;
+    if (idx_bytes) *idx_bytes = n_rb * n_quads * 3072;
+    if (cb_bytes) *cb_bytes = (size_t)(desc->out_features / desc->group_rows) * n_quads * 528;
+    return VQ_OK;
+  }
   const size_t slots = desc->k == 16 ? 2 * ((n_cb + 1) / 2) : n_cb;
   if (idx_bytes) *idx_bytes = n_rb * slots * (1024 * (size_t)desc->index_bits / 8);
   if (cb_bytes) *cb_bytes = n_rb * slots * (size_t)desc->k * 4;
@@ -109,7 +133,8 @@ int vq_gemv_multi(int count, const vq_desc* descs, const void* const* idx_dev,
   for (int i = 0; i < count; ++i) {
     const int st = check_desc(&descs[i]);
     if (st != VQ_OK) return st;
-    if (descs[i].k != descs[0].k) return VQ_ERR_BAD_ARG;
+    if (descs[i].k != descs[0].k || descs[i].codebook_dtype != descs[0].codebook_dtype)
+      return VQ_ERR_BAD_ARG;
     if (!idx_dev[i] || !cb_dev[i] || !x_f16[i] || !y[i]) return VQ_ERR_NULL;
     if (!aligned16(idx_dev[i]) || !aligned16(cb_dev[i]) || !aligned16(x_f16[i]) || !aligned16(y[i]))
       return VQ_ERR_ALIGN;
@@ -143,6 +168,7 @@ int vq_gemv_multi(int count, const vq_desc* descs, const void* const* idx_dev,
       p.n_rb = d.out_features / kGroupRows;
       p.n_cb = d.in_features / kGroupCols;
       p.splits = splits;
+      p.rb_per_cb = d.group_rows / kGroupRows;
       p.wg_begin = (int32_t)items;
       p.cost_begin = (int32_t)cost;
       cost += (long long)p.n_rb * p.n_cb;
@@ -176,6 +202,7 @@ int vq_gemm_batched(const vq_desc* desc, const void* idx_dev, const void* cb_dev
                     void* stream) {
   const int st = check_desc(desc);
   if (st != VQ_OK) return st;
+  if (desc->k == 64) return VQ_ERR_UNSUPPORTED;   // the batched product exists for fp16 codebooks only
   if (!idx_dev || !cb_dev || !X_f16 || !Y) return VQ_ERR_NULL;
   if (y_dtype != VQ_F16 && y_dtype != VQ_F32) return VQ_ERR_BAD_ARG;
   if (B < 1 || B > 65536) return VQ_ERR_BAD_ARG;

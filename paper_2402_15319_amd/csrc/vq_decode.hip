@@ -54,13 +54,66 @@ __global__ __launch_bounds__(256) void decode_kernel(const uint8_t* __restrict__
   }
 }
 
+// k = 64 (6-bit indices, int8 tables with a scale): one wave per (8-row block, col-block).
+// Lane L dequantises table entry L (fp16(scale * q), one rounding) and then copies.
+__global__ __launch_bounds__(256) void decode64_kernel(const uint8_t* __restrict__ idx,
+                                                       const uint8_t* __restrict__ tab,
+                                                       uint16_t* __restrict__ W, int n_cb,
+                                                       long long n_items, int in_features, int rpc) {
+  __shared__ uint32_t lut_all[4][64];
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  uint32_t* lut = lut_all[wave];
+  const long long item = (long long)blockIdx.x * 4 + wave;
+  if (item >= n_items) return;   // whole waves leave; no workgroup barrier below
+  const long long rb8 = item / n_cb;
+  const int c = (int)(item - rb8 * n_cb);
+  const int n_quads = k64_quads(n_cb), q = c >> 2, j = c & 3;
+  const uint8_t* tq = tab + (size_t)((rb8 / rpc) * n_quads + q) * kK64QuadTabBytes;
+  const uint32_t two = *reinterpret_cast<const uint16_t*>(tq + j * 128 + lane * 2);
+  const _Float16 scale = __builtin_bit_cast(_Float16, *reinterpret_cast<const uint16_t*>(tq + 512 + 2 * j));
+  lut[lane] = k64_dequant_pair(two, scale);
+  const uint8_t* iq = idx + (size_t)(rb8 * n_quads + q) * kK64QuadIdxBytes + lane * 16;
+  uint32_t d[12];
+#pragma unroll
+  for (int p = 0; p < 3; ++p) {
+    const uint4 v = *reinterpret_cast<const uint4*>(iq + p * 1024);
+    d[4 * p] = v.x; d[4 * p + 1] = v.y; d[4 * p + 2] = v.z; d[4 * p + 3] = v.w;
+  }
+  uint32_t d0 = 0, d1 = 0, d2 = 0;
+#pragma unroll
+  for (int jj = 0; jj < 4; ++jj)
+    if (jj == j) { d0 = d[3 * jj]; d1 = d[3 * jj + 1]; d2 = d[3 * jj + 2]; }
+  wave_lds_sync();
+  const unsigned long long lo = d0 | ((unsigned long long)d1 << 32);
+  uint16_t* out = W + (size_t)rb8 * 8 * in_features + (size_t)c * 256 + lane * 4;
+#pragma unroll
+  for (int r = 0; r < 8; ++r) {
+    uint32_t id[2];
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+      const int pos = 6 * (2 * r + e);
+      unsigned long long v = pos < 64 ? lo >> pos : (unsigned long long)(d2 >> (pos - 64));
+      if (pos < 64 && pos > 58) v |= (unsigned long long)d2 << (64 - pos);
+      id[e] = (uint32_t)v & 63u;
+    }
+    *reinterpret_cast<uint2*>(out + (size_t)r * in_features) = make_uint2(lut[id[0]], lut[id[1]]);
+  }
+}
+
 }  // namespace
 
 hipError_t launch_decode(const vq_desc& d, const void* idx_dev, const void* cb_dev, void* W,
                          hipStream_t s) {
   const int n_cb = d.in_features / kGroupCols;
-  const long long n_groups = (long long)(d.out_features / kGroupRows) * n_cb;
+  const long long n_groups = (long long)(d.out_features / kGroupRows) * n_cb;   // 8-row items
   const unsigned grid = (unsigned)((n_groups + 3) / 4);
+  if (d.k == 64) {
+    hipLaunchKernelGGL(decode64_kernel, dim3(grid), dim3(256), 0, s, (const uint8_t*)idx_dev,
+                       (const uint8_t*)cb_dev, (uint16_t*)W, n_cb, n_groups, d.in_features,
+                       d.group_rows / kGroupRows);
+    return hipGetLastError();
+  }
   if (d.k == 16)
     hipLaunchKernelGGL(decode_kernel<16>, dim3(grid), dim3(256), 0, s, (const uint8_t*)idx_dev,
                        (const uint32_t*)cb_dev, (uint16_t*)W, n_cb, n_groups, d.in_features);

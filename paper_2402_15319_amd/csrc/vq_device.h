@@ -171,87 +171,34 @@ __device__ __forceinline__ void k256_group(uint32_t w0, uint32_t w1, uint32_t w2
 #undef VQ_DOT
 
 // ---------------------------------------------------------------------------
-// Variants of the two inner blocks that fetch the lane's activations from LDS
-// themselves (two dword reads, at xaddr + XOFF and xaddr + XOFF + 256: the two planes
-// of a col-block, issued before the table reads, so they are back by the first wait).  Used by the streaming kernel, whose workgroup
-// keeps x in LDS; saves the vector-memory instructions and the registers that
-// per-chunk activation loads would cost.
-#define VQ_SDWA_RD(R, T, B)                                                               \
-  "v_add_u32_sdwa " R ", %[base], " T                                                     \
-  " dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_" #B "\n"            \
-  "ds_read_b32 " R ", " R " offset:%[off]\n"
-#define VQ_MASKS(W)                                  \
-  "v_and_b32 %[ta], 0x3c3c3c3c, " W "\n"             \
-  "v_alignbit_b32 %[tb], " W ", " W ", 4\n"          \
-  "v_and_b32 %[tb], 0x3c3c3c3c, %[tb]\n"
-#define VQ_DOT(ACC, R, X) "v_dot2c_f32_f16 " ACC ", " R ", " X "\n"
-#define VQ_XRD                                        \
-  "ds_read_b32 %[x0], %[xa] offset:%[xoff]\n"         \
-  "ds_read_b32 %[x1], %[xa] offset:%[xoff]+256\n"
-
-template <int OFF, int XOFF>
-__device__ __forceinline__ void k16_group_lx(uint32_t w0, uint32_t w1, uint32_t base,
-                                             uint32_t xaddr, float (&acc)[8]) {
-  uint32_t ta, tb, x0, x1, r0, r1, r2, r3, r4, r5, r6, r7, r8, r9;
-  asm volatile(
-      VQ_XRD
-      VQ_MASKS("%[w0]")
-      VQ_SDWA_RD("%[r0]", "%[ta]", 0) VQ_SDWA_RD("%[r1]", "%[tb]", 0)
-      VQ_SDWA_RD("%[r2]", "%[ta]", 1) VQ_SDWA_RD("%[r3]", "%[tb]", 1)
-      VQ_SDWA_RD("%[r4]", "%[ta]", 2) VQ_SDWA_RD("%[r5]", "%[tb]", 2)
-      VQ_SDWA_RD("%[r6]", "%[ta]", 3) VQ_SDWA_RD("%[r7]", "%[tb]", 3)
-      VQ_MASKS("%[w1]")
-      VQ_SDWA_RD("%[r8]", "%[ta]", 0) VQ_SDWA_RD("%[r9]", "%[tb]", 0)
-      "s_waitcnt lgkmcnt(6)\n"     // x0, x1, r0..r3 are back
-      VQ_DOT("%[a0]", "%[r0]", "%[x0]") VQ_DOT("%[a1]", "%[r2]", "%[x0]")
-      VQ_DOT("%[a0]", "%[r1]", "%[x1]") VQ_DOT("%[a1]", "%[r3]", "%[x1]")
-      VQ_SDWA_RD("%[r0]", "%[ta]", 1) VQ_SDWA_RD("%[r1]", "%[tb]", 1)
-      "s_waitcnt lgkmcnt(4)\n"     // r4..r7
-      VQ_DOT("%[a2]", "%[r4]", "%[x0]") VQ_DOT("%[a3]", "%[r6]", "%[x0]")
-      VQ_DOT("%[a2]", "%[r5]", "%[x1]") VQ_DOT("%[a3]", "%[r7]", "%[x1]")
-      VQ_SDWA_RD("%[r2]", "%[ta]", 2) VQ_SDWA_RD("%[r3]", "%[tb]", 2)
-      VQ_SDWA_RD("%[r4]", "%[ta]", 3) VQ_SDWA_RD("%[r5]", "%[tb]", 3)
-      "s_waitcnt lgkmcnt(6)\n"     // r8, r9
-      VQ_DOT("%[a4]", "%[r8]", "%[x0]") VQ_DOT("%[a4]", "%[r9]", "%[x1]")
-      "s_waitcnt lgkmcnt(4)\n"     // r0, r1
-      VQ_DOT("%[a5]", "%[r0]", "%[x0]") VQ_DOT("%[a5]", "%[r1]", "%[x1]")
-      "s_waitcnt lgkmcnt(0)\n"
-      VQ_DOT("%[a6]", "%[r2]", "%[x0]") VQ_DOT("%[a7]", "%[r4]", "%[x0]")
-      VQ_DOT("%[a6]", "%[r3]", "%[x1]") VQ_DOT("%[a7]", "%[r5]", "%[x1]")
-      : [a0] "+v"(acc[0]), [a1] "+v"(acc[1]), [a2] "+v"(acc[2]), [a3] "+v"(acc[3]),
-        [a4] "+v"(acc[4]), [a5] "+v"(acc[5]), [a6] "+v"(acc[6]), [a7] "+v"(acc[7]),
-        [ta] "=&v"(ta), [tb] "=&v"(tb), [x0] "=&v"(x0), [x1] "=&v"(x1), [r0] "=&v"(r0),
-        [r1] "=&v"(r1), [r2] "=&v"(r2), [r3] "=&v"(r3), [r4] "=&v"(r4), [r5] "=&v"(r5),
-        [r6] "=&v"(r6), [r7] "=&v"(r7), [r8] "=&v"(r8), [r9] "=&v"(r9)
-      : [w0] "v"(w0), [w1] "v"(w1), [base] "s"(base), [xa] "v"(xaddr), [off] "n"(OFF),
-        [xoff] "n"(XOFF)
-      : "memory");
-}
-#undef VQ_SDWA_RD
-#undef VQ_MASKS
-
-#define VQ_BFE_RD(R, W, BIT)                             \
-  "v_bfe_u32 " R ", " W ", " #BIT ", 8\n"                \
+// k = 64 inner block (6-bit indices): the lane's 16 indices of one 8-row block of a group
+// are a little-endian 6-bit stream in three dwords d0..d2, index i = 2*row + e (vector
+// 2L+e) at bits [6i, 6i+6).  Fields 5 and 10 straddle a dword boundary; the caller passes
+// them aligned to bit 0 in t5 = alignbit(d1, d0, 30) and t10 = alignbit(d2, d1, 28).
+// Per lookup: v_bfe_u32, v_lshl_add_u32 (index*4 + table base), ds_read_b32, v_dot2c.
+#define VQ_BF6_RD(R, W, BIT, OFF)                        \
+  "v_bfe_u32 " R ", " W ", " #BIT ", 6\n"                \
   "v_lshl_add_u32 " R ", " R ", 2, %[base]\n"            \
-  "ds_read_b32 " R ", " R " offset:%[off]\n"
+  "ds_read_b32 " R ", " R " offset:" OFF "\n"
+#define VQ_DOT(ACC, R, X) "v_dot2c_f32_f16 " ACC ", " R ", " X "\n"
 
-template <int OFF, int XOFF>
-__device__ __forceinline__ void k256_group_lx(uint32_t w0, uint32_t w1, uint32_t w2, uint32_t w3,
-                                              uint32_t base, uint32_t xaddr, float (&acc)[8]) {
-  uint32_t x0, x1, r0, r1, r2, r3, r4, r5, r6, r7, r8, r9, r10, r11;
+template <int OFF>
+__device__ __forceinline__ void k64_group(uint32_t d0, uint32_t d1, uint32_t d2, uint32_t t5,
+                                          uint32_t t10, uint32_t base, uint32_t x0, uint32_t x1,
+                                          float (&acc)[8]) {
+  uint32_t r0, r1, r2, r3, r4, r5, r6, r7, r8, r9, r10, r11;
   asm volatile(
-      VQ_XRD
-      VQ_BFE_RD("%[r0]", "%[w0]", 0) VQ_BFE_RD("%[r1]", "%[w0]", 8)
-      VQ_BFE_RD("%[r2]", "%[w0]", 16) VQ_BFE_RD("%[r3]", "%[w0]", 24)
-      VQ_BFE_RD("%[r4]", "%[w1]", 0) VQ_BFE_RD("%[r5]", "%[w1]", 8)
-      VQ_BFE_RD("%[r6]", "%[w1]", 16) VQ_BFE_RD("%[r7]", "%[w1]", 24)
-      VQ_BFE_RD("%[r8]", "%[w2]", 0) VQ_BFE_RD("%[r9]", "%[w2]", 8)
-      VQ_BFE_RD("%[r10]", "%[w2]", 16) VQ_BFE_RD("%[r11]", "%[w2]", 24)
+      VQ_BF6_RD("%[r0]", "%[d0]", 0, "%[off]") VQ_BF6_RD("%[r1]", "%[d0]", 6, "%[off]")
+      VQ_BF6_RD("%[r2]", "%[d0]", 12, "%[off]") VQ_BF6_RD("%[r3]", "%[d0]", 18, "%[off]")
+      VQ_BF6_RD("%[r4]", "%[d0]", 24, "%[off]") VQ_BF6_RD("%[r5]", "%[t5]", 0, "%[off]")
+      VQ_BF6_RD("%[r6]", "%[d1]", 4, "%[off]") VQ_BF6_RD("%[r7]", "%[d1]", 10, "%[off]")
+      VQ_BF6_RD("%[r8]", "%[d1]", 16, "%[off]") VQ_BF6_RD("%[r9]", "%[d1]", 22, "%[off]")
+      VQ_BF6_RD("%[r10]", "%[t10]", 0, "%[off]") VQ_BF6_RD("%[r11]", "%[d2]", 2, "%[off]")
       "s_waitcnt lgkmcnt(8)\n"
       VQ_DOT("%[a0]", "%[r0]", "%[x0]") VQ_DOT("%[a1]", "%[r2]", "%[x0]")
       VQ_DOT("%[a0]", "%[r1]", "%[x1]") VQ_DOT("%[a1]", "%[r3]", "%[x1]")
-      VQ_BFE_RD("%[r0]", "%[w3]", 0) VQ_BFE_RD("%[r1]", "%[w3]", 8)
-      VQ_BFE_RD("%[r2]", "%[w3]", 16) VQ_BFE_RD("%[r3]", "%[w3]", 24)
+      VQ_BF6_RD("%[r0]", "%[d2]", 8, "%[off]") VQ_BF6_RD("%[r1]", "%[d2]", 14, "%[off]")
+      VQ_BF6_RD("%[r2]", "%[d2]", 20, "%[off]") VQ_BF6_RD("%[r3]", "%[d2]", 26, "%[off]")
       "s_waitcnt lgkmcnt(8)\n"
       VQ_DOT("%[a2]", "%[r4]", "%[x0]") VQ_DOT("%[a3]", "%[r6]", "%[x0]")
       VQ_DOT("%[a2]", "%[r5]", "%[x1]") VQ_DOT("%[a3]", "%[r7]", "%[x1]")
@@ -263,16 +210,36 @@ __device__ __forceinline__ void k256_group_lx(uint32_t w0, uint32_t w1, uint32_t
       VQ_DOT("%[a6]", "%[r1]", "%[x1]") VQ_DOT("%[a7]", "%[r3]", "%[x1]")
       : [a0] "+v"(acc[0]), [a1] "+v"(acc[1]), [a2] "+v"(acc[2]), [a3] "+v"(acc[3]),
         [a4] "+v"(acc[4]), [a5] "+v"(acc[5]), [a6] "+v"(acc[6]), [a7] "+v"(acc[7]),
-        [x0] "=&v"(x0), [x1] "=&v"(x1), [r0] "=&v"(r0), [r1] "=&v"(r1), [r2] "=&v"(r2),
-        [r3] "=&v"(r3), [r4] "=&v"(r4), [r5] "=&v"(r5), [r6] "=&v"(r6), [r7] "=&v"(r7),
-        [r8] "=&v"(r8), [r9] "=&v"(r9), [r10] "=&v"(r10), [r11] "=&v"(r11)
-      : [w0] "v"(w0), [w1] "v"(w1), [w2] "v"(w2), [w3] "v"(w3), [base] "s"(base),
-        [xa] "v"(xaddr), [off] "n"(OFF), [xoff] "n"(XOFF)
+        [r0] "=&v"(r0), [r1] "=&v"(r1), [r2] "=&v"(r2), [r3] "=&v"(r3), [r4] "=&v"(r4),
+        [r5] "=&v"(r5), [r6] "=&v"(r6), [r7] "=&v"(r7), [r8] "=&v"(r8), [r9] "=&v"(r9),
+        [r10] "=&v"(r10), [r11] "=&v"(r11)
+      : [d0] "v"(d0), [d1] "v"(d1), [d2] "v"(d2), [t5] "v"(t5), [t10] "v"(t10), [base] "s"(base),
+        [x0] "v"(x0), [x1] "v"(x1), [off] "n"(OFF)
       : "memory");
 }
-#undef VQ_BFE_RD
+#undef VQ_BF6_RD
 #undef VQ_DOT
-#undef VQ_XRD
+
+// ---- 6-bit / int8-table device layout (k = 64) -------------------------------------------
+// Indices: per (8-row block, quad of 4 col-blocks) three planes of 1 KB; the lane's 48 bytes
+// are planes' bytes [16p, 16p+16), and col-block j of the quad is its dwords 3j..3j+2 (the
+// 6-bit stream described at k64_group).  Tables: per (group row, quad) 528 bytes: four
+// tables of 64 int8 pairs (128 B each), four fp16 scales, 8 bytes of padding.  Quads past
+// the last col-block hold zero indices, zero tables and zero scales.
+constexpr int kK64QuadIdxBytes = 3072;
+constexpr int kK64QuadTabBytes = 528;
+__host__ __device__ __forceinline__ int k64_quads(int n_cb) { return (n_cb + 3) >> 2; }
+
+// Centroid pair from two int8 table entries and the group's scale (Sec. 3.1: table and
+// scale factor per group): the integers convert to fp16 exactly and one fp16 multiply
+// rounds the exact product once, to nearest even.
+__device__ __forceinline__ uint32_t k64_dequant_pair(uint32_t two_bytes, _Float16 scale) {
+  h2_t v;
+  v.x = (_Float16)(short)(signed char)(two_bytes & 0xffu);
+  v.y = (_Float16)(short)(signed char)((two_bytes >> 8) & 0xffu);
+  v = v * h2_t{scale, scale};
+  return __builtin_bit_cast(uint32_t, v);
+}
 
 // Pairs of col-blocks a k=16 row-block is stored as (the last one half-empty if n_cb is odd).
 __host__ __device__ __forceinline__ int k16_pairs(int n_cb) { return (n_cb + 1) >> 1; }

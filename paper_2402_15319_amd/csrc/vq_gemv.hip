@@ -134,6 +134,50 @@ template <> struct Chunk<256> {
   }
 };
 
+template <> struct Chunk<64> {
+  static constexpr int kUnits = 1;        // quads of 4 col-blocks per chunk
+  static constexpr int kLutDwords = 256;  // 4 groups x 64 centroids
+  uint4 w[3];     // the lane's three index planes of the quad
+  uint2 xv[4];    // activations of the quad's four col-blocks
+  uint2 tab;      // 4 int8 centroid pairs: entries 4*(lane%16).. of table lane/16
+  uint32_t sc;    // that table's fp16 scale (low 16 bits)
+
+  __device__ __forceinline__ void load(const Strip& S, int u, int lane) {
+    const bool ok = u < S.u_end;
+    const int q = ok ? u : 0;
+    const uint8_t* tq = reinterpret_cast<const uint8_t*>(S.cb_rb) + (size_t)q * kK64QuadTabBytes;
+    tab = zero_unless(ok, *reinterpret_cast<const uint2*>(tq + lane * 8));
+    sc = *reinterpret_cast<const uint16_t*>(tq + 512 + (lane >> 4) * 2);
+#pragma unroll
+    for (int p = 0; p < 3; ++p)
+      w[p] = stream_load16(S.idx_rb + (size_t)q * kK64QuadIdxBytes + p * 1024 + lane * 16);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const bool okx = ok && 4 * q + j < S.n_cb;
+      xv[j] = zero_unless(okx, *reinterpret_cast<const uint2*>(S.x + (okx ? 4 * q + j : 0) * 256 + lane * 4));
+    }
+  }
+
+  __device__ __forceinline__ void consume(uint32_t* lut, uint32_t base, int lane,
+                                          float (&acc)[8]) const {
+    const _Float16 scale = __builtin_bit_cast(_Float16, (uint16_t)sc);
+    *reinterpret_cast<uint4*>(lut + lane * 4) =
+        make_uint4(k64_dequant_pair(tab.x, scale), k64_dequant_pair(tab.x >> 16, scale),
+                   k64_dequant_pair(tab.y, scale), k64_dequant_pair(tab.y >> 16, scale));
+    wave_lds_sync();
+    const uint32_t d[12] = {w[0].x, w[0].y, w[0].z, w[0].w, w[1].x, w[1].y,
+                            w[1].z, w[1].w, w[2].x, w[2].y, w[2].z, w[2].w};
+#define VQ_G64(J)                                                                              \
+    k64_group<256 * J>(d[3 * J], d[3 * J + 1], d[3 * J + 2],                                   \
+                       __builtin_amdgcn_alignbit(d[3 * J + 1], d[3 * J], 30),                  \
+                       __builtin_amdgcn_alignbit(d[3 * J + 2], d[3 * J + 1], 28), base,        \
+                       xv[J].x, xv[J].y, acc);
+    VQ_G64(0) VQ_G64(1) VQ_G64(2) VQ_G64(3)
+#undef VQ_G64
+    acc_hazard_fence();
+  }
+};
+
 // Strip (row-block rb, K-split `split` of `splits`) of problem P; may be empty.
 template <int K>
 __device__ __forceinline__ Strip make_strip(const GemvProblem& P, int rb, int split, int splits) {
@@ -148,6 +192,13 @@ __device__ __forceinline__ Strip make_strip(const GemvProblem& P, int rb, int sp
     S.u = (n_pairs * split) / splits;
     S.u_end = (n_pairs * (split + 1)) / splits;
     S.chunks_left = (S.u_end - S.u + 3) >> 2;
+  } else if (K == 64) {
+    const int n_quads = k64_quads(n_cb);
+    S.idx_rb = P.idx + (size_t)rb * n_quads * kK64QuadIdxBytes;
+    S.cb_rb = P.cb + (size_t)(rb / P.rb_per_cb) * n_quads * (kK64QuadTabBytes / 4);
+    S.u = (n_quads * split) / splits;
+    S.u_end = (n_quads * (split + 1)) / splits;
+    S.chunks_left = S.u_end - S.u;
   } else {
     S.idx_rb = P.idx + (size_t)rb * n_cb * 1024;
     S.cb_rb = P.cb + (size_t)rb * n_cb * 256;
@@ -269,6 +320,56 @@ template <> struct ChunkS<256> {
     const uint2 x0 = xp[0], x1 = xp[64];
     k256_group<0>(w[0].x, w[0].y, w[0].z, w[0].w, base, x0.x, x0.y, acc);
     k256_group<1024>(w[1].x, w[1].y, w[1].z, w[1].w, base, x1.x, x1.y, acc);
+    acc_hazard_fence();
+  }
+};
+
+template <> struct ChunkS<64> {
+  static constexpr int kUnits = 1;
+  static constexpr int kLutDwords = 256;
+  uint4 w[3];
+  uint2 tab;
+  uint32_t sc;
+  int u0;          // the quad (locates the activations in LDS), wave-uniform
+
+  __device__ __forceinline__ void load(const Strip& S, int u, int lane) {
+    const bool ok = u < S.u_end;
+    const int q = ok ? u : 0;
+    u0 = u;
+    const uint8_t* tq = reinterpret_cast<const uint8_t*>(S.cb_rb) + (size_t)q * kK64QuadTabBytes;
+    uint32_t voff = (uint32_t)lane * 16u;      // see ChunkS<16>::load
+    asm volatile("" : "+v"(voff));
+    tab = zero_unless(ok, *reinterpret_cast<const uint2*>(tq + (voff >> 1)));
+    sc = *reinterpret_cast<const uint16_t*>(tq + 512 + (lane >> 4) * 2);
+#pragma unroll
+    for (int p = 0; p < 3; ++p)
+      w[p] = stream_load16(S.idx_rb + (size_t)q * kK64QuadIdxBytes + p * 1024 + voff);
+  }
+
+  // An absent quad is consumed with a zero table against the zeroed col-blocks behind x.
+  __device__ __forceinline__ void consume(uint32_t* lut, uint32_t base, const uint32_t* x_s, int lane,
+                                          float (&acc)[8]) const {
+    const _Float16 scale = __builtin_bit_cast(_Float16, (uint16_t)sc);
+    *reinterpret_cast<uint4*>(lut + lane * 4) =
+        make_uint4(k64_dequant_pair(tab.x, scale), k64_dequant_pair(tab.x >> 16, scale),
+                   k64_dequant_pair(tab.y, scale), k64_dequant_pair(tab.y >> 16, scale));
+    wave_lds_sync();
+    const uint2* xp = reinterpret_cast<const uint2*>(x_s) + u0 * 256 + lane;   // 64 uint2 per col-block
+    const uint32_t d[12] = {w[0].x, w[0].y, w[0].z, w[0].w, w[1].x, w[1].y,
+                            w[1].z, w[1].w, w[2].x, w[2].y, w[2].z, w[2].w};
+    uint2 x0 = xp[0], x1 = xp[64];
+#define VQ_G64(J, X)                                                                           \
+    k64_group<256 * J>(d[3 * J], d[3 * J + 1], d[3 * J + 2],                                   \
+                       __builtin_amdgcn_alignbit(d[3 * J + 1], d[3 * J], 30),                  \
+                       __builtin_amdgcn_alignbit(d[3 * J + 2], d[3 * J + 1], 28), base,        \
+                       X.x, X.y, acc);
+    VQ_G64(0, x0)
+    x0 = xp[128];
+    VQ_G64(1, x1)
+    x1 = xp[192];
+    VQ_G64(2, x0)
+    VQ_G64(3, x1)
+#undef VQ_G64
     acc_hazard_fence();
   }
 };
@@ -455,24 +556,28 @@ __global__ __launch_bounds__(256) void gemv_split_kernel(const GemvBatch batch) 
 }  // namespace
 
 size_t gemv_stream_lds_bytes(int k, int max_n_cb) {
-  const size_t lut = (size_t)kStreamWaves * 2 * (k == 16 ? ChunkS<16>::kLutDwords : ChunkS<256>::kLutDwords) * 4;
-  return lut + 16 + (size_t)(max_n_cb + kXPadColBlocks) * 512;
+  const int lut_dwords = k == 16 ? ChunkS<16>::kLutDwords : k == 64 ? ChunkS<64>::kLutDwords
+                                                                    : ChunkS<256>::kLutDwords;
+  return (size_t)kStreamWaves * 2 * lut_dwords * 4 + 16 + (size_t)(max_n_cb + kXPadColBlocks) * 512;
 }
 
 int gemv_stream_resident_wgs(int k, int max_n_cb) {
   // Occupancy of the persistent kernel for this LDS size, asked once per (device, k, size):
   // a pure function of the code object and the device, cached so that the hot path makes
   // no runtime queries.  Benign if two threads fill the same slot at once.
-  static int cached[2][16][kStreamMaxColBlocks + 1];
+  static int cached[3][16][kStreamMaxColBlocks + 1];
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) dev = 0;
-  int& slot = cached[k == 16 ? 0 : 1][dev][max_n_cb];
+  int& slot = cached[k == 16 ? 0 : k == 64 ? 1 : 2][dev][max_n_cb];
   if (slot == 0) {
     int per_cu = 0, cus = 0;
     const size_t lds = gemv_stream_lds_bytes(k, max_n_cb);
+    const int threads = kStreamWaves * 64;
     hipError_t e = k == 16
-        ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gemv_stream_kernel<16>, kStreamWaves * 64, lds)
-        : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gemv_stream_kernel<256>, kStreamWaves * 64, lds);
+        ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gemv_stream_kernel<16>, threads, lds)
+        : k == 64
+        ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gemv_stream_kernel<64>, threads, lds)
+        : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gemv_stream_kernel<256>, threads, lds);
     if (e != hipSuccess || per_cu < 1) per_cu = 1;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
       cus = 256;
@@ -489,9 +594,11 @@ hipError_t launch_gemv(int k, const GemvBatch& batch, int stream_mode, int grid_
     const size_t lds = gemv_stream_lds_bytes(k, max_n_cb);
     const dim3 sblock(kStreamWaves * 64);
     if (k == 16) hipLaunchKernelGGL(gemv_stream_kernel<16>, grid, sblock, lds, s, batch);
+    else if (k == 64) hipLaunchKernelGGL(gemv_stream_kernel<64>, grid, sblock, lds, s, batch);
     else hipLaunchKernelGGL(gemv_stream_kernel<256>, grid, sblock, lds, s, batch);
   } else {
     if (k == 16) hipLaunchKernelGGL(gemv_split_kernel<16>, grid, block, 0, s, batch);
+    else if (k == 64) hipLaunchKernelGGL(gemv_split_kernel<64>, grid, block, 0, s, batch);
     else hipLaunchKernelGGL(gemv_split_kernel<256>, grid, block, 0, s, batch);
   }
   return hipGetLastError();

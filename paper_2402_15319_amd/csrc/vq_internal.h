@@ -22,7 +22,7 @@ struct GemvProblem {
   int32_t wg_begin;     // first work item of this problem inside the launch (see launch_gemv)
   int32_t splits;       // waves sharing one row-block: 1, 2 or 4
   int32_t cost_begin;   // groups of all earlier problems of the launch (streaming kernel)
-  int32_t pad;
+  int32_t rb_per_cb;    // 8-row blocks that share one codebook (group_rows / 8)
 };
 
 struct GemvBatch {

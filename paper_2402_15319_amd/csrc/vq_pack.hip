@@ -69,6 +69,74 @@ __global__ __launch_bounds__(256) void pack_cb_kernel(const uint4* __restrict__ 
   dst[t] = c < n_cb ? src[(rb * n_cb + c) * per_group + piece] : make_uint4(0, 0, 0, 0);
 }
 
+// ---- k = 64: 6-bit indices, int8 tables with a scale per group, groups of 8*rpc rows -------
+// One thread per (8-row block, quad of col-blocks, lane): gathers the lane's 4 x 16 indices
+// from the canonical little-endian 6-bit stream of their groups and re-packs them as four
+// 96-bit streams (index 2*row + e at bits [6i, 6i+6)), written as three 16-byte planes.
+__global__ __launch_bounds__(256) void pack_idx64_kernel(const uint8_t* __restrict__ canon,
+                                                         uint8_t* __restrict__ dev, int n_cb,
+                                                         long long n_rb8, int rpc) {
+  const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
+  const long long slot = t >> 6;
+  const int lane = (int)(t & 63);
+  const int n_quads = k64_quads(n_cb);
+  if (slot >= n_rb8 * n_quads) return;
+  const long long rb8 = slot / n_quads;
+  const int q = (int)(slot - rb8 * n_quads);
+  const long long grow = rb8 / rpc;              // row of groups
+  const int sub = (int)(rb8 - grow * rpc);       // 8-row block inside the group
+  const size_t group_bytes = (size_t)rpc * 8 * 96;   // rows x 128 vectors x 6 bits
+  uint32_t d[12];
+#pragma unroll
+  for (int i = 0; i < 12; ++i) d[i] = 0u;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int c = 4 * q + j;
+    if (c >= n_cb) continue;
+    const uint8_t* g = canon + (size_t)(grow * n_cb + c) * group_bytes;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int v = (sub * 8 + (i >> 1)) * 128 + 2 * lane + (i & 1);
+      const int bit = 6 * v, b = bit >> 3, sh = bit & 7;
+      uint32_t val = g[b] >> sh;
+      if (sh > 2) val |= (uint32_t)g[b + 1] << (8 - sh);   // the field continues in the next byte
+      val &= 63u;
+      const int pos = 6 * i, dw = 3 * j + (pos >> 5), off = pos & 31;
+      d[dw] |= val << off;
+      if (off > 26) d[dw + 1] |= val >> (32 - off);
+    }
+  }
+#pragma unroll
+  for (int p = 0; p < 3; ++p)
+    *reinterpret_cast<uint4*>(dev + ((size_t)slot * 3 + p) * 1024 + lane * 16) =
+        make_uint4(d[4 * p], d[4 * p + 1], d[4 * p + 2], d[4 * p + 3]);
+}
+
+// Tables: per (row of groups, quad) four int8 tables of 128 bytes, then their four scales.
+__global__ __launch_bounds__(256) void pack_tab64_kernel(const uint8_t* __restrict__ q_canon,
+                                                         const uint16_t* __restrict__ scale_canon,
+                                                         uint8_t* __restrict__ dev, int n_cb,
+                                                         long long n_grow) {
+  const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
+  const long long slot = t >> 6;
+  const int lane = (int)(t & 63);
+  const int n_quads = k64_quads(n_cb);
+  if (slot >= n_grow * n_quads) return;
+  const long long grow = slot / n_quads;
+  const int q = (int)(slot - grow * n_quads);
+  const int c = 4 * q + (lane >> 4);
+  uint8_t* dst = dev + (size_t)slot * kK64QuadTabBytes;
+  const uint2 v = c < n_cb
+      ? *reinterpret_cast<const uint2*>(q_canon + (size_t)(grow * n_cb + c) * 128 + (lane & 15) * 8)
+      : make_uint2(0u, 0u);
+  *reinterpret_cast<uint2*>(dst + lane * 8) = v;
+  if (lane < 8) {
+    const int cs = 4 * q + lane;
+    reinterpret_cast<uint16_t*>(dst + 512)[lane] =
+        (lane < 4 && cs < n_cb) ? scale_canon[grow * n_cb + cs] : (uint16_t)0;
+  }
+}
+
 // Reads n16 16-byte pieces once (non-temporal) and keeps the optimiser from dropping the loads.
 typedef unsigned int probe_u32x4_t __attribute__((ext_vector_type(4)));
 __global__ __launch_bounds__(256) void stream_read_kernel(const probe_u32x4_t* __restrict__ p,
@@ -100,6 +168,21 @@ hipError_t launch_pack(const vq_desc& d, const void* idx_canon, const void* cb_c
                        void* idx_dev, void* cb_dev, hipStream_t s) {
   const int n_cb = d.in_features / kGroupCols;
   const long long n_rb = d.out_features / kGroupRows;
+  if (d.k == 64) {
+    const int rpc = d.group_rows / kGroupRows;
+    const long long n_grow = d.out_features / d.group_rows;
+    const int n_quads = k64_quads(n_cb);
+    hipLaunchKernelGGL(pack_idx64_kernel, dim3((unsigned)((n_rb * n_quads * 64 + 255) / 256)), dim3(256),
+                       0, s, (const uint8_t*)idx_canon, (uint8_t*)idx_dev, n_cb, n_rb, rpc);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const size_t q_bytes = ((size_t)n_grow * n_cb * 128 + 15) / 16 * 16;   // scales follow the tables
+    hipLaunchKernelGGL(pack_tab64_kernel, dim3((unsigned)((n_grow * n_quads * 64 + 255) / 256)),
+                       dim3(256), 0, s, (const uint8_t*)cb_canon,
+                       (const uint16_t*)((const uint8_t*)cb_canon + q_bytes), (uint8_t*)cb_dev, n_cb,
+                       n_grow);
+    return hipGetLastError();
+  }
   const long long n_slots = n_rb * (d.k == 16 ? 2 * k16_pairs(n_cb) : n_cb);
   const unsigned grid = (unsigned)((n_slots * 64 + 255) / 256);
   if (d.k == 16)

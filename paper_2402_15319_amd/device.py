@@ -4,13 +4,29 @@ from __future__ import annotations
 import numpy as np
 import torch
 
-from . import VQDesc, make_desc, vq_layout_bytes, vq_pack_layout
+from . import VQDesc, VQ_F16, VQ_I8, make_desc, vq_canonical_bytes, vq_layout_bytes, vq_pack_layout
 
 
 def desc_from_shape(s) -> VQDesc:
     """VQDesc from any object with out_features/in_features/k/index_bits/group_* /d fields."""
     return make_desc(s.out_features, s.in_features, s.k, s.index_bits,
-                     s.group_rows, s.group_cols, s.d)
+                     s.group_rows, s.group_cols, s.d,
+                     VQ_I8 if getattr(s, "int8_tables", False) else VQ_F16)
+
+
+def canonical_tables_i8(desc: VQDesc, q: np.ndarray, scale: np.ndarray) -> np.ndarray:
+    """Canonical table buffer of the VQ_I8 representation: the int8 tables q[g, k, d],
+    zero-padded to a multiple of 16 bytes, then the fp16 scales scale[g] (byte copy only)."""
+    assert q.dtype == np.int8 and scale.dtype == np.float16
+    _, cb_bytes = vq_canonical_bytes(desc)
+    buf = np.zeros(cb_bytes, dtype=np.uint8)
+    qb = np.ascontiguousarray(q).view(np.uint8).reshape(-1)
+    sb = np.ascontiguousarray(scale).view(np.uint8).reshape(-1)
+    buf[:qb.size] = qb
+    off = (qb.size + 15) // 16 * 16
+    assert off + sb.size == cb_bytes
+    buf[off:] = sb
+    return buf
 
 
 def to_device_bytes(a: np.ndarray, device="cuda:0") -> torch.Tensor:

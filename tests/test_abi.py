@@ -67,7 +67,10 @@ A = 0x1000  # a fake, 16-byte aligned, non-NULL address; validation fails before
     (dict(d=4), -3),
     (dict(group_rows=4), -3),
     (dict(group_cols=128), -3),
-    (dict(k=64, index_bits=6), -3),
+    (dict(k=64, index_bits=6), -3),                                       # k = 64 needs int8 tables
+    (dict(codebook_dtype=3), -3),                                         # int8 tables need k = 64
+    (dict(k=64, index_bits=6, codebook_dtype=3, group_rows=24), -3),
+    (dict(k=64, index_bits=6, codebook_dtype=3, group_rows=32, out_features=4112), -3),
     (dict(out_features=4100), -3),
     (dict(in_features=4000), -3),
     (dict(codebook_dtype=2), -3),
@@ -82,6 +85,33 @@ def test_bad_descriptors(mutate, status):
     assert L.vq_decode_dense(ctypes.byref(d), A, A, A, 0) == status
     assert L.vq_gemm_batched(ctypes.byref(d), A, A, A, 16, 16, A + 16, 16, vq.VQ_F16, 0) == status
     assert L.vq_pack_layout(ctypes.byref(d), A, A, A + 16, A + 32, 0) == status
+
+
+def test_int8_table_representation_sizes_and_entry_points():
+    """k = 64, 6-bit indices, int8 tables + scale, 32 x 256 groups: canonical sizes follow
+    log2(k)/d + (k*d*8 + 16)/8192 bits per value; the device layout stores quads of four
+    col-blocks; the batched product is not offered for this representation."""
+    L = vq.lib()
+    for out_f, in_f in ((4096, 4096), (11008, 4096), (4096, 11008)):
+        d = vq.make_desc(out_f, in_f, 64, 6, group_rows=32, codebook_dtype=vq.VQ_I8)
+        ib, cbb = vq.vq_canonical_bytes(d)
+        n_groups = (out_f // 32) * (in_f // 256)
+        assert ib == n_groups * 3072
+        assert cbb == (n_groups * 128 + 15) // 16 * 16 + 2 * n_groups
+        dib, dcb = vq.vq_layout_bytes(d)
+        quads = (in_f // 256 + 3) // 4
+        assert dib == (out_f // 8) * quads * 3072 and dcb == (out_f // 32) * quads * 528
+        r = ctypes.byref(d)
+        assert L.vq_gemm_batched(r, A, A, A, 16, 16, A + 16, 16, vq.VQ_F16, 0) == -3
+        assert L.vq_gemv(r, A, A, A + 2, A + 16, vq.VQ_F16, 0) == -4       # validated like the others
+    for rows in (8, 16):
+        d = vq.make_desc(4096, 4096, 64, 6, group_rows=rows, codebook_dtype=vq.VQ_I8)
+        assert vq.vq_layout_bytes(d)[1] == (4096 // rows) * 4 * 528
+    d16 = vq.make_desc(4096, 4096, 16, 4)
+    d64 = vq.make_desc(4096, 4096, 64, 6, group_rows=32, codebook_dtype=vq.VQ_I8)
+    descs = (vq.VQDesc * 2)(d64, d16)
+    arr = ctypes.c_void_p * 2
+    assert L.vq_gemv_multi(2, descs, arr(A, A), arr(A, A), arr(A, A), arr(A + 16, A + 32), vq.VQ_F16, 0) == -6
 
 
 def test_null_alignment_and_scalar_errors():

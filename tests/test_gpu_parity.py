@@ -343,3 +343,92 @@ def test_entry_points_replay_in_a_hip_graph(env):
         torch.cuda.synchronize()
         for a, b in zip(flat(captured), want):
             np.testing.assert_array_equal(a.view(np.uint16), b.view(np.uint16))
+
+
+# ---------------------------------------------------------------- int8 tables + scale, 6-bit indices
+def _shape64(o, i, rows=32):
+    return workloads.VQShape(o, i, 64, 6, rows, 256, 2, True)
+
+
+def _setup_i8(env, s, seed):
+    """Canonical arrays, the oracle's fp16 codebooks (scale * q rounded once), device buffers."""
+    torch, vq, vqdev = env
+    idx, q, scale = workloads.make_weights_i8(s, seed)
+    desc = vqdev.desc_from_shape(s)
+    idx_d, cb_d = vqdev.upload_and_pack(desc, idx, vqdev.canonical_tables_i8(desc, q, scale))
+    return desc, idx, oracle.dequantise_codebooks(q, scale), idx_d, cb_d
+
+
+# one group; two quads with a ragged second one (11 and 5 col-blocks); 8- and 16-row groups;
+# row counts that are not a multiple of the 4 waves of a workgroup
+SMALL64 = [_shape64(32, 256), _shape64(64, 512), _shape64(96, 2816), _shape64(160, 1280),
+           _shape64(40, 768, 8), _shape64(48, 1024, 16)]
+FULL64 = ["attn_4096x4096_k64_i8", "mlp_up_11008x4096_k64_i8", "mlp_down_4096x11008_k64_i8"]
+
+
+@pytest.mark.parametrize("s", SMALL64 + [workloads.CONFIGS[k] for k in FULL64], ids=str)
+def test_k64_decode_bit_exact(env, s):
+    desc, idx, cb, idx_d, cb_d = _setup_i8(env, s, 640)
+    np.testing.assert_array_equal(_gpu_decode(env, desc, idx_d, cb_d), oracle.decode_dense(_fmt(s), idx, cb))
+
+
+def test_k64_decode_rounds_like_the_oracle_on_every_table_value(env):
+    """All 256 int8 values against scales that give ties, subnormal and large products."""
+    torch, vq, vqdev = env
+    s = _shape64(32, 1024)                      # 4 groups
+    rng = np.random.default_rng(641)
+    idx = rng.integers(0, 256, size=workloads.canonical_sizes(s)[0], dtype=np.uint8)
+    q = np.zeros((4, 64, 2), dtype=np.int8)
+    q.reshape(4, 128)[:] = np.arange(-128, 128, dtype=np.int16).reshape(2, 128).astype(np.int8)[[0, 1, 0, 1]]
+    scale = np.array([0.0999755859375, 0.0999755859375, 6.1e-5, 255.0], dtype=np.float16)
+    desc = vqdev.desc_from_shape(s)
+    idx_d, cb_d = vqdev.upload_and_pack(desc, idx, vqdev.canonical_tables_i8(desc, q, scale))
+    want = oracle.decode_dense(_fmt(s), idx, oracle.dequantise_codebooks(q, scale))
+    np.testing.assert_array_equal(_gpu_decode(env, desc, idx_d, cb_d), want)
+
+
+@pytest.mark.parametrize("f32", [False, True], ids=["y16", "y32"])
+@pytest.mark.parametrize("s", SMALL64 + [workloads.CONFIGS[k] for k in FULL64], ids=str)
+def test_k64_gemv(env, s, f32):
+    desc, idx, cb, idx_d, cb_d = _setup_i8(env, s, 642)
+    x = workloads.make_x(s.in_features, 642)
+    y = _gpu_gemv(env, desc, idx_d, cb_d, x, f32)
+    ref = oracle.gemv(_fmt(s), idx, cb, x)
+    assert oracle.normwise_rel_err(y, ref) <= (TOL_F32 if f32 else TOL_F16)
+
+
+def test_k64_gemv_unit_vectors_pick_columns(env):
+    s = _shape64(64, 1280)
+    desc, idx, cb, idx_d, cb_d = _setup_i8(env, s, 643)
+    W = oracle.decode_dense(_fmt(s), idx, cb).view(np.float16).astype(np.float64)
+    for c in (0, 1, 255, 256, 1023, 1024, 1279):
+        e = np.zeros(s.in_features, dtype=np.float16)
+        e[c] = 1
+        np.testing.assert_array_equal(_gpu_gemv(env, desc, idx_d, cb_d, e, True), W[:, c])
+
+
+@pytest.mark.parametrize("s", [_shape64(32800, 256), _shape64(32800, 1280), _shape64(32768 + 64, 2816, 16)], ids=str)
+def test_k64_streaming_kernel(env, s):
+    desc, idx, cb, idx_d, cb_d = _setup_i8(env, s, 644)
+    x = workloads.make_x(s.in_features, 644)
+    y = _gpu_gemv(env, desc, idx_d, cb_d, x, False)
+    assert oracle.normwise_rel_err(y, oracle.gemv(_fmt(s), idx, cb, x)) <= TOL_F16
+
+
+def test_k64_gemv_multi_llama_layer(env):
+    """The 7 matrices of one decoder layer in the deployed representation, one launch."""
+    torch, vq, vqdev = env
+    descs, idxs, cbs, xs, ys, refs = [], [], [], [], [], []
+    for m, (name, key) in enumerate(workloads.LLAMA7B_LAYER_K64):
+        s = workloads.CONFIGS[key]
+        desc, idx, cb, idx_d, cb_d = _setup_i8(env, s, workloads.seed_for(key, 0, m))
+        x = workloads.make_x(s.in_features, 650 + m)
+        descs.append(desc); idxs.append(idx_d); cbs.append(cb_d)
+        xs.append(vqdev.to_device_bytes(x))
+        ys.append(torch.full((s.out_features,), 7.0, dtype=torch.float16, device="cuda:0"))
+        refs.append(oracle.gemv(_fmt(s), idx, cb, x))
+    vq.vq_gemv_multi(descs, idxs, cbs, xs, ys)
+    torch.cuda.synchronize()
+    for i, ref in enumerate(refs):
+        err = oracle.normwise_rel_err(ys[i].cpu().numpy(), ref)
+        assert err <= TOL_F16, (i, err)
