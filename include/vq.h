@@ -37,8 +37,9 @@
  *
  * Implemented representations: VQ_F16 with 8 x 256 groups and k = 16 or 256; VQ_I8 with
  * k = 64 (6-bit indices) and groups of 8, 16 or 32 rows x 256 columns (32 rows: the
- * 8,192-weight groups and 3.125 bits per value of Sec. 5.1) for vq_pack_layout, vq_gemv,
- * vq_gemv_multi and vq_decode_dense (vq_gemm_batched returns VQ_ERR_UNSUPPORTED for it).
+ * 8,192-weight groups and 3.125 bits per value of Sec. 5.1), and VQ_I8 with k = 16 and
+ * 8 x 256 groups (2.125 bits per value), for vq_pack_layout, vq_gemv, vq_gemv_multi and
+ * vq_decode_dense (vq_gemm_batched returns VQ_ERR_UNSUPPORTED for VQ_I8).
  */
 #ifndef VQ_H_
 #define VQ_H_
@@ -73,7 +74,7 @@ typedef struct vq_desc {
   int32_t group_rows;     /* 8 (VQ_I8: 8, 16 or 32)                                 */
   int32_t group_cols;     /* 256 (Sec. 4: at most 256 columns per group)            */
   int32_t d;              /* VQ dimensionality, 2                                   */
-  int32_t k;              /* centroids per codebook: 16 or 256 (VQ_F16), 64 (VQ_I8) */
+  int32_t k;              /* centroids: 16 or 256 (VQ_F16), 64 or 16 (VQ_I8)        */
   int32_t index_bits;     /* log2(k): 4, 8 or 6                                     */
   int32_t codebook_dtype; /* VQ_F16 or VQ_I8                                        */
 } vq_desc;

@@ -12,8 +12,9 @@ bool is_pow2(int v) { return v > 0 && (v & (v - 1)) == 0; }
 
 // The two representations the kernels implement:
 //   fp16 codebooks, 8 x 256 groups, k = 16 (4-bit indices) or 256 (8-bit);
-//   int8 tables with one fp16 scale per group, k = 64 (6-bit indices), groups of 8, 16 or 32
-//   rows x 256 columns (32 rows = the 8,192-weight groups of Sec. 5.1).
+//   int8 tables with one fp16 scale per group: k = 64 (6-bit indices), groups of 8, 16 or 32
+//   rows x 256 columns (32 rows = the 8,192-weight groups of Sec. 5.1), or k = 16 with 8 x 256
+//   groups (2.125 bits per value).
 bool is_i8(const vq_desc& d) { return d.codebook_dtype == VQ_I8; }
 
 int check_desc(const vq_desc* d) {
@@ -26,8 +27,13 @@ int check_desc(const vq_desc* d) {
   if (d->codebook_dtype != VQ_F16 && d->codebook_dtype != VQ_I8) return VQ_ERR_UNSUPPORTED;
   if (d->d != 2 || d->group_cols != kGroupCols) return VQ_ERR_UNSUPPORTED;
   if (is_i8(*d)) {
-    if (d->k != 64) return VQ_ERR_UNSUPPORTED;
-    if (d->group_rows != 8 && d->group_rows != 16 && d->group_rows != 32) return VQ_ERR_UNSUPPORTED;
+    if (d->k == 64) {
+      if (d->group_rows != 8 && d->group_rows != 16 && d->group_rows != 32) return VQ_ERR_UNSUPPORTED;
+    } else if (d->k == 16) {
+      if (d->group_rows != kGroupRows) return VQ_ERR_UNSUPPORTED;
+    } else {
+      return VQ_ERR_UNSUPPORTED;
+    }
   } else {
     if (d->k != 16 && d->k != 256) return VQ_ERR_UNSUPPORTED;
     if (d->group_rows != kGroupRows) return VQ_ERR_UNSUPPORTED;
@@ -109,7 +115,7 @@ int vq_layout_bytes(const vq_desc* desc, size_t* idx_bytes, size_t* cb_bytes) {
   }
   const size_t slots = desc->k == 16 ? 2 * ((n_cb + 1) / 2) : n_cb;
   if (idx_bytes) *idx_bytes = n_rb * slots * (1024 * (size_t)desc->index_bits / 8);
-  if (cb_bytes) *cb_bytes = n_rb * slots * (size_t)desc->k * 4;
+  if (cb_bytes) *cb_bytes = is_i8(*desc) ? n_rb * slots * 34 : n_rb * slots * (size_t)desc->k * 4;
   return VQ_OK;
 }
 
@@ -150,8 +156,9 @@ int vq_gemv_multi(int count, const vq_desc* descs, const void* const* idx_dev,
       if (c > max_n_cb) max_n_cb = c;
     }
     const int splits = choose_splits(rb_launch);
+    const int fmt = (descs[0].k == 16 && is_i8(descs[0])) ? kFmtK16I8 : descs[0].k;   // kernel format tag
     const bool stream_mode = splits == 1 && max_n_cb <= kStreamMaxColBlocks &&
-                             gemv_stream_lds_bytes(descs[0].k, max_n_cb) <= 65536;
+                             gemv_stream_lds_bytes(fmt, max_n_cb) <= 65536;
     GemvBatch batch;                       // 14 KB on the stack; only the used entries are filled
     memset(&batch, 0, offsetof(GemvBatch, p) + (size_t)n * sizeof(GemvProblem));
     batch.count = n;
@@ -181,10 +188,10 @@ int vq_gemv_multi(int count, const vq_desc* descs, const void* const* idx_dev,
     int grid = (int)items;
     if (stream_mode) {
       const long long want = (items + 7) / 8;   // at least one row-block per wave
-      const int resident = gemv_stream_resident_wgs(descs[0].k, max_n_cb);
+      const int resident = gemv_stream_resident_wgs(fmt, max_n_cb);
       grid = (int)(want < resident ? want : resident);
     }
-    const hipError_t e = launch_gemv(descs[0].k, batch, stream_mode ? 1 : 0, grid, max_n_cb,
+    const hipError_t e = launch_gemv(fmt, batch, stream_mode ? 1 : 0, grid, max_n_cb,
                                      (hipStream_t)stream);
     if (e != hipSuccess) return VQ_ERR_HIP;
   }
@@ -202,7 +209,7 @@ int vq_gemm_batched(const vq_desc* desc, const void* idx_dev, const void* cb_dev
                     void* stream) {
   const int st = check_desc(desc);
   if (st != VQ_OK) return st;
-  if (desc->k == 64) return VQ_ERR_UNSUPPORTED;   // the batched product exists for fp16 codebooks only
+  if (is_i8(*desc)) return VQ_ERR_UNSUPPORTED;   // the batched product exists for fp16 codebooks only
   if (!idx_dev || !cb_dev || !X_f16 || !Y) return VQ_ERR_NULL;
   if (y_dtype != VQ_F16 && y_dtype != VQ_F32) return VQ_ERR_BAD_ARG;
   if (B < 1 || B > 65536) return VQ_ERR_BAD_ARG;

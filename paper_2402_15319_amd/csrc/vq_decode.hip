@@ -8,12 +8,14 @@
 namespace vq {
 namespace {
 
+// K: 16 or 256 with fp16 codebooks, kFmtK16I8 for k = 16 with int8 tables and a scale per group
+// (32 bytes per group slot, then one fp16 scale per slot behind all the tables).
 template <int K>
 __global__ __launch_bounds__(256) void decode_kernel(const uint8_t* __restrict__ idx,
                                                      const uint32_t* __restrict__ cb,
                                                      uint16_t* __restrict__ W, int n_cb,
                                                      long long n_groups, int in_features) {
-  __shared__ uint32_t lut_all[4][K];
+  __shared__ uint32_t lut_all[4][K == kFmtK16I8 ? 16 : K];
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   uint32_t* lut = lut_all[wave];
@@ -23,9 +25,18 @@ __global__ __launch_bounds__(256) void decode_kernel(const uint8_t* __restrict__
   const int c = (int)(g - rb * n_cb);
   uint16_t* out = W + (size_t)rb * 8 * in_features + (size_t)c * 256 + lane * 4;
 
-  if (K == 16) {
+  if (K == 16 || K == kFmtK16I8) {
     const int slots = 2 * k16_pairs(n_cb);                  // group slots per row-block
-    if (lane < 16) lut[lane] = cb[(rb * slots + c) * 16 + lane];
+    if (K == 16) {
+      if (lane < 16) lut[lane] = cb[(rb * slots + c) * 16 + lane];
+    } else if (lane < 16) {
+      const long long n_rb = n_groups / n_cb;
+      const uint8_t* tq = reinterpret_cast<const uint8_t*>(cb) + (size_t)(rb * slots + c) * 32;
+      const uint16_t* sc = reinterpret_cast<const uint16_t*>(reinterpret_cast<const uint8_t*>(cb) +
+                                                             (size_t)n_rb * slots * 32);
+      lut[lane] = k64_dequant_pair(*reinterpret_cast<const uint16_t*>(tq + lane * 2),
+                                   __builtin_bit_cast(_Float16, sc[rb * slots + c]));
+    }
     const uint2 w = *reinterpret_cast<const uint2*>(idx + rb * slots * 512 + k16_chunk_offset(c, lane));
     wave_lds_sync();
     const char* lutb = reinterpret_cast<const char*>(lut);
@@ -114,7 +125,10 @@ hipError_t launch_decode(const vq_desc& d, const void* idx_dev, const void* cb_d
                        d.group_rows / kGroupRows);
     return hipGetLastError();
   }
-  if (d.k == 16)
+  if (d.k == 16 && d.codebook_dtype == VQ_I8)
+    hipLaunchKernelGGL(decode_kernel<kFmtK16I8>, dim3(grid), dim3(256), 0, s, (const uint8_t*)idx_dev,
+                       (const uint32_t*)cb_dev, (uint16_t*)W, n_cb, n_groups, d.in_features);
+  else if (d.k == 16)
     hipLaunchKernelGGL(decode_kernel<16>, dim3(grid), dim3(256), 0, s, (const uint8_t*)idx_dev,
                        (const uint32_t*)cb_dev, (uint16_t*)W, n_cb, n_groups, d.in_features);
   else

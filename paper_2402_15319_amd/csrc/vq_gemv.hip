@@ -29,7 +29,8 @@ namespace {
 // A strip as wave-uniform scalars.  Units are col-block pairs (k=16) or col-blocks (k=256).
 struct Strip {
   const uint8_t* idx_rb;   // indices of the row-block
-  const uint32_t* cb_rb;   // codebooks of the row-block (dwords)
+  const uint32_t* cb_rb;   // codebooks / int8 tables of the row-block (dwords)
+  const uint16_t* sc_rb;   // fp16 scales of the row-block's groups (k=16 with int8 tables)
   const uint16_t* x;
   int u;                   // next unit to load
   int u_end;               // end of this strip's units
@@ -47,6 +48,7 @@ struct Strip {
 __device__ __forceinline__ uint2 zero_unless(bool keep, uint2 v) {
   return keep ? v : make_uint2(0, 0);
 }
+__device__ __forceinline__ uint32_t zero_unless(bool keep, uint32_t v) { return keep ? v : 0u; }
 __device__ __forceinline__ uint4 zero_unless(bool keep, uint4 v) {
   return keep ? v : make_uint4(0, 0, 0, 0);
 }
@@ -60,20 +62,45 @@ __device__ __forceinline__ uint4 stream_load16(const void* p) {
 // ---- chunks with activations in registers (split-K kernel) ------------------
 template <int K> struct Chunk;
 
-template <> struct Chunk<16> {
+// k = 16.  I8: the tables are int8 with a scale per group (32 + 2 bytes per group instead of
+// 64), dequantised into the LDS table when the chunk is consumed.
+template <bool I8> struct Chunk16T {
   static constexpr int kUnits = 4;        // col-block pairs per chunk
   static constexpr int kLutDwords = 128;  // 8 groups x 16 centroids
   uint4 w[4];     // slot s: the lane's 16 index bytes of pair u+s
   uint2 xa[4];    // activations of the first group of the slot
   uint2 xb[4];    // ... and of the second
-  uint4 cbv;      // this lane's 16 bytes of the chunk's codebooks (lanes 0..31)
+  uint4 cbv;      // fp16: this lane's 16 bytes of the chunk's codebooks (lanes 0..31)
+  uint32_t tab;   // int8: this lane's two centroid pairs (4 bytes of the chunk's tables)
+  uint32_t sc;    // int8: the fp16 scale of the group those pairs belong to
   int np;         // pairs present (wave-uniform)
+
+  // The chunk's tables: pairs u .. u+np-1 of the row-block (np may be 0: nothing is kept).
+  __device__ __forceinline__ void load_tables(const Strip& S, int u, int lane, int np_) {
+    const int u_ld = np_ > 0 ? u : 0;
+    if constexpr (I8) {
+      const uint8_t* tq = reinterpret_cast<const uint8_t*>(S.cb_rb) + (size_t)u_ld * 64;
+      tab = zero_unless(lane * 4 < np_ * 64,
+                        *reinterpret_cast<const uint32_t*>(tq + min(lane * 4, max(np_ * 64 - 4, 0))));
+      sc = S.sc_rb[u_ld * 2 + min(lane >> 3, max(2 * np_ - 1, 0))];
+    } else {
+      const int cb_off = min(lane * 4, max(np_ * 32 - 4, 0));
+      cbv = zero_unless(lane * 4 < np_ * 32, stream_load16(S.cb_rb + (size_t)u_ld * 32 + cb_off));
+    }
+  }
+  __device__ __forceinline__ void stage_tables(uint32_t* lut, int lane) const {
+    if constexpr (I8) {
+      const _Float16 scale = __builtin_bit_cast(_Float16, (uint16_t)sc);
+      *reinterpret_cast<uint2*>(lut + lane * 2) =
+          make_uint2(k64_dequant_pair(tab, scale), k64_dequant_pair(tab >> 16, scale));
+    } else {
+      if (lane < 32) *reinterpret_cast<uint4*>(lut + lane * 4) = cbv;
+    }
+  }
 
   __device__ __forceinline__ void load(const Strip& S, int u, int lane) {
     np = max(0, min(4, S.u_end - u));
-    const int cb_off = min(lane * 4, max(np * 32 - 4, 0));
-    cbv = zero_unless(lane * 4 < np * 32,
-                      stream_load16(S.cb_rb + (size_t)(np > 0 ? u : 0) * 32 + cb_off));
+    load_tables(S, u, lane, np);
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
       const bool ok = s < np;
@@ -89,7 +116,7 @@ template <> struct Chunk<16> {
   // and consumes the chunk.
   __device__ __forceinline__ void consume(uint32_t* lut, uint32_t base, int lane,
                                           float (&acc)[8]) const {
-    if (lane < 32) *reinterpret_cast<uint4*>(lut + lane * 4) = cbv;
+    stage_tables(lut, lane);
     wave_lds_sync();
     k16_group<0>(w[0].x, w[0].y, base, xa[0].x, xa[0].y, acc);
     k16_group<64>(w[0].z, w[0].w, base, xb[0].x, xb[0].y, acc);
@@ -104,6 +131,8 @@ template <> struct Chunk<16> {
     acc_hazard_fence();
   }
 };
+template <> struct Chunk<16> : Chunk16T<false> {};
+template <> struct Chunk<kFmtK16I8> : Chunk16T<true> {};
 
 template <> struct Chunk<256> {
   static constexpr int kUnits = 2;        // groups per chunk
@@ -185,10 +214,17 @@ __device__ __forceinline__ Strip make_strip(const GemvProblem& P, int rb, int sp
   const int n_cb = P.n_cb;
   S.x = P.x;
   S.n_cb = n_cb;
-  if (K == 16) {
+  S.sc_rb = nullptr;
+  if (K == 16 || K == kFmtK16I8) {
     const int n_pairs = k16_pairs(n_cb);
     S.idx_rb = P.idx + (size_t)rb * n_pairs * 1024;
-    S.cb_rb = P.cb + (size_t)rb * n_pairs * 32;
+    if (K == 16) {
+      S.cb_rb = P.cb + (size_t)rb * n_pairs * 32;
+    } else {   // int8 tables: 32 bytes per group slot, then all the scales (2 bytes per slot)
+      S.cb_rb = P.cb + (size_t)rb * n_pairs * 16;
+      S.sc_rb = reinterpret_cast<const uint16_t*>(P.cb + (size_t)P.n_rb * n_pairs * 16) +
+                (size_t)rb * n_pairs * 2;
+    }
     S.u = (n_pairs * split) / splits;
     S.u_end = (n_pairs * (split + 1)) / splits;
     S.chunks_left = (S.u_end - S.u + 3) >> 2;
@@ -242,19 +278,28 @@ __device__ __forceinline__ int find_problem(const GemvBatch& batch, int item) {
 // by zeroed col-blocks that the absent units of a ragged chunk read.
 template <int K> struct ChunkS;
 
-template <> struct ChunkS<16> {
+template <bool I8> struct ChunkS16T {
   static constexpr int kUnits = 4;
   static constexpr int kLutDwords = 128;
   uint4 w[4];
-  uint4 cbv;
+  uint4 cbv;       // fp16 codebooks (lanes 0..31), or
+  uint32_t tab;    // two int8 centroid pairs and
+  uint32_t sc;     // their group's fp16 scale
   int u0;          // first pair (locates the activations in LDS), wave-uniform
 
   __device__ __forceinline__ void load(const Strip& S, int u, int lane) {
     const int np = max(0, min(4, S.u_end - u));
     u0 = u;
-    const int cb_off = min(lane * 4, max(np * 32 - 4, 0));
-    cbv = zero_unless(lane * 4 < np * 32,
-                      stream_load16(S.cb_rb + (size_t)(np > 0 ? u : 0) * 32 + cb_off));
+    const int u_ld = np > 0 ? u : 0;
+    if constexpr (I8) {
+      const uint8_t* tq = reinterpret_cast<const uint8_t*>(S.cb_rb) + (size_t)u_ld * 64;
+      tab = zero_unless(lane * 4 < np * 64,
+                        *reinterpret_cast<const uint32_t*>(tq + min(lane * 4, max(np * 64 - 4, 0))));
+      sc = S.sc_rb[u_ld * 2 + min(lane >> 3, max(2 * np - 1, 0))];
+    } else {
+      const int cb_off = min(lane * 4, max(np * 32 - 4, 0));
+      cbv = zero_unless(lane * 4 < np * 32, stream_load16(S.cb_rb + (size_t)u_ld * 32 + cb_off));
+    }
     // uniform base + 32-bit lane offset: the opaque copy keeps the zero-extension next to the
     // load, where it folds into the scalar-base addressing mode (no 64-bit vector adds)
     uint32_t voff = (uint32_t)lane * 16u;
@@ -269,7 +314,13 @@ template <> struct ChunkS<16> {
   // read for block b+1 is issued before block b, so only the first one is waited for.
   __device__ __forceinline__ void consume(uint32_t* lut, uint32_t base, const uint32_t* x_s, int lane,
                                           float (&acc)[8]) const {
-    if (lane < 32) *reinterpret_cast<uint4*>(lut + lane * 4) = cbv;
+    if constexpr (I8) {
+      const _Float16 scale = __builtin_bit_cast(_Float16, (uint16_t)sc);
+      *reinterpret_cast<uint2*>(lut + lane * 2) =
+          make_uint2(k64_dequant_pair(tab, scale), k64_dequant_pair(tab >> 16, scale));
+    } else {
+      if (lane < 32) *reinterpret_cast<uint4*>(lut + lane * 4) = cbv;
+    }
     wave_lds_sync();
     const uint2* xp = reinterpret_cast<const uint2*>(x_s) + u0 * 128 + lane;   // 64 uint2 per col-block
     uint2 x0 = xp[0], x1 = xp[64];
@@ -290,6 +341,8 @@ template <> struct ChunkS<16> {
     acc_hazard_fence();
   }
 };
+template <> struct ChunkS<16> : ChunkS16T<false> {};
+template <> struct ChunkS<kFmtK16I8> : ChunkS16T<true> {};
 
 template <> struct ChunkS<256> {
   static constexpr int kUnits = 2;
@@ -556,8 +609,8 @@ __global__ __launch_bounds__(256) void gemv_split_kernel(const GemvBatch batch) 
 }  // namespace
 
 size_t gemv_stream_lds_bytes(int k, int max_n_cb) {
-  const int lut_dwords = k == 16 ? ChunkS<16>::kLutDwords : k == 64 ? ChunkS<64>::kLutDwords
-                                                                    : ChunkS<256>::kLutDwords;
+  const int lut_dwords = (k == 16 || k == kFmtK16I8) ? ChunkS<16>::kLutDwords
+                         : k == 64 ? ChunkS<64>::kLutDwords : ChunkS<256>::kLutDwords;
   return (size_t)kStreamWaves * 2 * lut_dwords * 4 + 16 + (size_t)(max_n_cb + kXPadColBlocks) * 512;
 }
 
@@ -565,10 +618,10 @@ int gemv_stream_resident_wgs(int k, int max_n_cb) {
   // Occupancy of the persistent kernel for this LDS size, asked once per (device, k, size):
   // a pure function of the code object and the device, cached so that the hot path makes
   // no runtime queries.  Benign if two threads fill the same slot at once.
-  static int cached[3][16][kStreamMaxColBlocks + 1];
+  static int cached[4][16][kStreamMaxColBlocks + 1];
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) dev = 0;
-  int& slot = cached[k == 16 ? 0 : k == 64 ? 1 : 2][dev][max_n_cb];
+  int& slot = cached[k == 16 ? 0 : k == 64 ? 1 : k == kFmtK16I8 ? 3 : 2][dev][max_n_cb];
   if (slot == 0) {
     int per_cu = 0, cus = 0;
     const size_t lds = gemv_stream_lds_bytes(k, max_n_cb);
@@ -577,6 +630,8 @@ int gemv_stream_resident_wgs(int k, int max_n_cb) {
         ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gemv_stream_kernel<16>, threads, lds)
         : k == 64
         ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gemv_stream_kernel<64>, threads, lds)
+        : k == kFmtK16I8
+        ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gemv_stream_kernel<kFmtK16I8>, threads, lds)
         : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gemv_stream_kernel<256>, threads, lds);
     if (e != hipSuccess || per_cu < 1) per_cu = 1;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
@@ -595,10 +650,12 @@ hipError_t launch_gemv(int k, const GemvBatch& batch, int stream_mode, int grid_
     const dim3 sblock(kStreamWaves * 64);
     if (k == 16) hipLaunchKernelGGL(gemv_stream_kernel<16>, grid, sblock, lds, s, batch);
     else if (k == 64) hipLaunchKernelGGL(gemv_stream_kernel<64>, grid, sblock, lds, s, batch);
+    else if (k == kFmtK16I8) hipLaunchKernelGGL(gemv_stream_kernel<kFmtK16I8>, grid, sblock, lds, s, batch);
     else hipLaunchKernelGGL(gemv_stream_kernel<256>, grid, sblock, lds, s, batch);
   } else {
     if (k == 16) hipLaunchKernelGGL(gemv_split_kernel<16>, grid, block, 0, s, batch);
     else if (k == 64) hipLaunchKernelGGL(gemv_split_kernel<64>, grid, block, 0, s, batch);
+    else if (k == kFmtK16I8) hipLaunchKernelGGL(gemv_split_kernel<kFmtK16I8>, grid, block, 0, s, batch);
     else hipLaunchKernelGGL(gemv_split_kernel<256>, grid, block, 0, s, batch);
   }
   return hipGetLastError();

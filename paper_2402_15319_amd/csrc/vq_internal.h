@@ -9,6 +9,9 @@ namespace vq {
 constexpr int kGroupRows = 8;
 constexpr int kGroupCols = 256;
 constexpr int kMaxProblemsPerLaunch = 256;  // the problem table travels in the kernel arguments (14 KB)
+// Kernel format tags: the codebook size for fp16 codebooks (16, 256) and for k = 64 (always int8
+// tables); k = 16 with int8 tables has a tag of its own.
+constexpr int kFmtK16I8 = 1016;
 constexpr int kStreamMaxColBlocks = 96;   // widest x the streaming kernel stages in LDS (48 KB)
 
 // One matrix-vector product as the kernels see it (lives in the kernel arguments).
@@ -41,7 +44,7 @@ hipError_t launch_decode(const vq_desc& d, const void* idx_dev, const void* cb_d
 // stream_mode != 0: persistent kernel (total_cost/cost_begin are used, grid_wgs workgroups,
 // x of up to max_n_cb col-blocks staged in LDS); stream_mode == 0: split-K kernel,
 // wg_begin/total_wgs count workgroups (= grid_wgs).
-hipError_t launch_gemv(int k, const GemvBatch& batch, int stream_mode, int grid_wgs,
+hipError_t launch_gemv(int fmt, const GemvBatch& batch, int stream_mode, int grid_wgs,
                        int max_n_cb, hipStream_t s);
 // Dynamic LDS of the persistent GEMV kernel for x of up to max_n_cb col-blocks.
 size_t gemv_stream_lds_bytes(int k, int max_n_cb);

@@ -69,6 +69,29 @@ __global__ __launch_bounds__(256) void pack_cb_kernel(const uint4* __restrict__ 
   dst[t] = c < n_cb ? src[(rb * n_cb + c) * per_group + piece] : make_uint4(0, 0, 0, 0);
 }
 
+// k = 16 with int8 tables: 32 bytes per group slot (zero for the pad group), then one fp16
+// scale per slot.  One thread per dword of tables; the first n_slots threads also copy a scale.
+__global__ __launch_bounds__(256) void pack_tab16_kernel(const uint32_t* __restrict__ q_canon,
+                                                         const uint16_t* __restrict__ scale_canon,
+                                                         uint32_t* __restrict__ dev, int n_cb,
+                                                         long long n_slots) {
+  const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (t >= n_slots * 8) return;
+  const int slots_per_rb = 2 * k16_pairs(n_cb);
+  {
+    const long long slot = t >> 3;
+    const int piece = (int)(t & 7);
+    const long long rb = slot / slots_per_rb;
+    const int c = (int)(slot - rb * slots_per_rb);
+    dev[t] = c < n_cb ? q_canon[(rb * n_cb + c) * 8 + piece] : 0u;
+  }
+  if (t < n_slots) {
+    const long long rb = t / slots_per_rb;
+    const int c = (int)(t - rb * slots_per_rb);
+    reinterpret_cast<uint16_t*>(dev + n_slots * 8)[t] = c < n_cb ? scale_canon[rb * n_cb + c] : (uint16_t)0;
+  }
+}
+
 // ---- k = 64: 6-bit indices, int8 tables with a scale per group, groups of 8*rpc rows -------
 // One thread per (8-row block, quad of col-blocks, lane): gathers the lane's 4 x 16 indices
 // from the canonical little-endian 6-bit stream of their groups and re-packs them as four
@@ -184,6 +207,17 @@ hipError_t launch_pack(const vq_desc& d, const void* idx_canon, const void* cb_c
     return hipGetLastError();
   }
   const long long n_slots = n_rb * (d.k == 16 ? 2 * k16_pairs(n_cb) : n_cb);
+  if (d.k == 16 && d.codebook_dtype == VQ_I8) {
+    hipLaunchKernelGGL(pack_idx_kernel<16>, dim3((unsigned)((n_slots * 64 + 255) / 256)), dim3(256), 0, s,
+                       (const uint8_t*)idx_canon, (uint8_t*)idx_dev, n_cb, n_slots);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const size_t q_bytes = ((size_t)n_rb * n_cb * 32 + 15) / 16 * 16;      // scales follow the tables
+    hipLaunchKernelGGL(pack_tab16_kernel, dim3((unsigned)((n_slots * 8 + 255) / 256)), dim3(256), 0, s,
+                       (const uint32_t*)cb_canon, (const uint16_t*)((const uint8_t*)cb_canon + q_bytes),
+                       (uint32_t*)cb_dev, n_cb, n_slots);
+    return hipGetLastError();
+  }
   const unsigned grid = (unsigned)((n_slots * 64 + 255) / 256);
   if (d.k == 16)
     hipLaunchKernelGGL(pack_idx_kernel<16>, dim3(grid), dim3(256), 0, s,

@@ -68,7 +68,8 @@ A = 0x1000  # a fake, 16-byte aligned, non-NULL address; validation fails before
     (dict(group_rows=4), -3),
     (dict(group_cols=128), -3),
     (dict(k=64, index_bits=6), -3),                                       # k = 64 needs int8 tables
-    (dict(codebook_dtype=3), -3),                                         # int8 tables need k = 64
+    (dict(k=256, index_bits=8, codebook_dtype=3), -3),                    # int8 tables: k = 16 or 64
+    (dict(codebook_dtype=3, group_rows=32), -3),                          # k = 16 int8: 8-row groups
     (dict(k=64, index_bits=6, codebook_dtype=3, group_rows=24), -3),
     (dict(k=64, index_bits=6, codebook_dtype=3, group_rows=32, out_features=4112), -3),
     (dict(out_features=4100), -3),
@@ -107,6 +108,12 @@ def test_int8_table_representation_sizes_and_entry_points():
     for rows in (8, 16):
         d = vq.make_desc(4096, 4096, 64, 6, group_rows=rows, codebook_dtype=vq.VQ_I8)
         assert vq.vq_layout_bytes(d)[1] == (4096 // rows) * 4 * 528
+    # k = 16 with int8 tables: 2 + (16*2*8 + 16)/2048 bits per value; 34 bytes per device slot
+    d = vq.make_desc(4096, 11008, 16, 4, codebook_dtype=vq.VQ_I8)
+    ib, cbb = vq.vq_canonical_bytes(d)
+    assert (ib + cbb) * 8 * 2048 == 4096 * 11008 * (2 * 2048 + 16 * 2 * 8 + 16)
+    assert vq.vq_layout_bytes(d) == (512 * 44 * 512, 512 * 44 * 34)
+    assert L.vq_gemm_batched(ctypes.byref(d), A, A, A, 16, 16, A + 16, 16, vq.VQ_F16, 0) == -3
     d16 = vq.make_desc(4096, 4096, 16, 4)
     d64 = vq.make_desc(4096, 4096, 64, 6, group_rows=32, codebook_dtype=vq.VQ_I8)
     descs = (vq.VQDesc * 2)(d64, d16)

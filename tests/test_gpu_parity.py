@@ -350,6 +350,10 @@ def _shape64(o, i, rows=32):
     return workloads.VQShape(o, i, 64, 6, rows, 256, 2, True)
 
 
+def _shape16i8(o, i):
+    return workloads.VQShape(o, i, 16, 4, 8, 256, 2, True)
+
+
 def _setup_i8(env, s, seed):
     """Canonical arrays, the oracle's fp16 codebooks (scale * q rounded once), device buffers."""
     torch, vq, vqdev = env
@@ -423,6 +427,53 @@ def test_k64_gemv_multi_llama_layer(env):
         s = workloads.CONFIGS[key]
         desc, idx, cb, idx_d, cb_d = _setup_i8(env, s, workloads.seed_for(key, 0, m))
         x = workloads.make_x(s.in_features, 650 + m)
+        descs.append(desc); idxs.append(idx_d); cbs.append(cb_d)
+        xs.append(vqdev.to_device_bytes(x))
+        ys.append(torch.full((s.out_features,), 7.0, dtype=torch.float16, device="cuda:0"))
+        refs.append(oracle.gemv(_fmt(s), idx, cb, x))
+    vq.vq_gemv_multi(descs, idxs, cbs, xs, ys)
+    torch.cuda.synchronize()
+    for i, ref in enumerate(refs):
+        err = oracle.normwise_rel_err(ys[i].cpu().numpy(), ref)
+        assert err <= TOL_F16, (i, err)
+
+
+# ---------------------------------------------------------------- k = 16 with int8 tables (2.125 bpv)
+SMALL16I8 = [_shape16i8(8, 256), _shape16i8(40, 768), _shape16i8(24, 2816), _shape16i8(264, 1024)]
+FULL16I8 = ["attn_4096x4096_k16_i8", "mlp_up_11008x4096_k16_i8", "mlp_down_4096x11008_k16_i8"]
+
+
+@pytest.mark.parametrize("s", SMALL16I8 + [workloads.CONFIGS[k] for k in FULL16I8], ids=str)
+def test_k16_int8_decode_bit_exact(env, s):
+    desc, idx, cb, idx_d, cb_d = _setup_i8(env, s, 660)
+    np.testing.assert_array_equal(_gpu_decode(env, desc, idx_d, cb_d), oracle.decode_dense(_fmt(s), idx, cb))
+
+
+@pytest.mark.parametrize("f32", [False, True], ids=["y16", "y32"])
+@pytest.mark.parametrize("s", SMALL16I8 + [workloads.CONFIGS[k] for k in FULL16I8], ids=str)
+def test_k16_int8_gemv(env, s, f32):
+    desc, idx, cb, idx_d, cb_d = _setup_i8(env, s, 661)
+    x = workloads.make_x(s.in_features, 661)
+    y = _gpu_gemv(env, desc, idx_d, cb_d, x, f32)
+    ref = oracle.gemv(_fmt(s), idx, cb, x)
+    assert oracle.normwise_rel_err(y, ref) <= (TOL_F32 if f32 else TOL_F16)
+
+
+@pytest.mark.parametrize("s", [_shape16i8(32776, 256), _shape16i8(32776, 768), _shape16i8(32776, 2816)], ids=str)
+def test_k16_int8_streaming_kernel(env, s):
+    desc, idx, cb, idx_d, cb_d = _setup_i8(env, s, 662)
+    x = workloads.make_x(s.in_features, 662)
+    y = _gpu_gemv(env, desc, idx_d, cb_d, x, False)
+    assert oracle.normwise_rel_err(y, oracle.gemv(_fmt(s), idx, cb, x)) <= TOL_F16
+
+
+def test_k16_int8_gemv_multi_llama_layer(env):
+    torch, vq, vqdev = env
+    descs, idxs, cbs, xs, ys, refs = [], [], [], [], [], []
+    for m, (name, key) in enumerate(workloads.LLAMA7B_LAYER_K16_I8):
+        s = workloads.CONFIGS[key]
+        desc, idx, cb, idx_d, cb_d = _setup_i8(env, s, workloads.seed_for(key, 0, m))
+        x = workloads.make_x(s.in_features, 670 + m)
         descs.append(desc); idxs.append(idx_d); cbs.append(cb_d)
         xs.append(vqdev.to_device_bytes(x))
         ys.append(torch.full((s.out_features,), 7.0, dtype=torch.float16, device="cuda:0"))

@@ -22,7 +22,7 @@ import numpy as np
 __all__ = [
     "VQShape", "CONFIGS", "LLAMA7B_LAYER", "seed_for", "canonical_sizes",
     "make_weights", "make_weights_i8", "make_x", "make_X", "llama7b_pass_shapes",
-    "LLAMA7B_LAYER_K64",
+    "LLAMA7B_LAYER_K64", "LLAMA7B_LAYER_K16_I8",
 ]
 
 
@@ -66,6 +66,10 @@ CONFIGS = {
     "mlp_down_4096x11008_k16": VQShape(4096, 11008, 16, 4),
     # the paper's deployed representation (Sec. 3.1, Sec. 5.1): 2-D VQ, 6-bit indices, int8
     # tables with a scale per group, groups of 8,192 weights (32 rows x 256 columns): 3.125 bpv
+    # the paper's 2.125-bit setting: 2-D VQ, k = 16, int8 tables, groups of 2,048 weights
+    "attn_4096x4096_k16_i8": VQShape(4096, 4096, 16, 4, 8, 256, 2, True),
+    "mlp_up_11008x4096_k16_i8": VQShape(11008, 4096, 16, 4, 8, 256, 2, True),
+    "mlp_down_4096x11008_k16_i8": VQShape(4096, 11008, 16, 4, 8, 256, 2, True),
     "tiny_64x512_k64_i8": VQShape(64, 512, 64, 6, 32, 256, 2, True),
     "attn_4096x4096_k64_i8": VQShape(4096, 4096, 64, 6, 32, 256, 2, True),
     "mlp_up_11008x4096_k64_i8": VQShape(11008, 4096, 64, 6, 32, 256, 2, True),
@@ -83,6 +87,7 @@ LLAMA7B_LAYER = (
     ("down_proj", "mlp_down_4096x11008_k16"),
 )
 LLAMA7B_LAYER_K64 = tuple((n, k.replace("_k16", "_k64_i8")) for n, k in LLAMA7B_LAYER)
+LLAMA7B_LAYER_K16_I8 = tuple((n, k + "_i8") for n, k in LLAMA7B_LAYER)
 LLAMA7B_N_LAYERS = 32
 
 _BASE_SEED = 15319 * 10
