@@ -197,33 +197,43 @@ def main():
         log(f"[bench] 8 layers with k=256: {ms256 * 1e3:.1f} us, {b256 / ms256 / 1e6:.0f} GB/s")
         del m256, y256, a256
 
-        # the whole pass in the paper's deployed representation (6-bit indices, int8 tables with
-        # a scale per group, 32 x 256 groups: 3.125 bits per value, 2.54 GB).  Timing only, so
-        # the device-layout buffers are filled with random bytes directly (every index and
-        # int8 pattern is valid); the fp16 scale slots are set to 2^-8.
-        m64 = []
-        for _ in range(workloads.LLAMA7B_N_LAYERS if args.layers == 32 else args.layers):
-            for (_, key) in workloads.LLAMA7B_LAYER_K64:
-                s = workloads.CONFIGS[key]
-                desc = vqdev.desc_from_shape(s)
-                ib, cbb = vq.vq_layout_bytes(desc)
-                tab = torch.randint(0, 256, (cbb,), dtype=torch.uint8, device=dev)
-                tv = tab.view(-1, 528)
-                tv[:, 512:528] = 0
-                tv[:, 513:520:2] = 0x1C
-                m64.append((s, desc, torch.randint(0, 256, (ib,), dtype=torch.uint8, device=dev), tab))
-        y64 = [torch.empty(m[0].out_features, dtype=torch.float16, device=dev) for m in m64]
-        a64 = vq.GemvMultiArgs([m[1] for m in m64], [m[2] for m in m64], [m[3] for m in m64],
-                               [xs[m[0].in_features] for m in m64], y64)
-        b64 = sum(sum(workloads.canonical_sizes(m[0])) + 2 * m[0].in_features + 2 * m[0].out_features
-                  for m in m64)
-        ms64, _ = timer.run(lambda: vq.vq_gemv_multi(a64), max(10, args.steps // 2), 50)
-        extras["llama7b_pass_k64_int8_tables_3.125bpv_via_vq_gemv_multi"] = {
-            "us": ms64 * 1e3, "bytes": b64, "GB/s": b64 / ms64 / 1e6,
-            "frac_hbm": b64 / ms64 / 1e6 / HBM_PEAK_GBS, "tokens_per_s_weight_stream": 1e3 / ms64,
-            "kernel": "gemv_stream_kernel<64>"}
-        log(f"[bench] pass with k=64 / int8 tables: {ms64 * 1e3:.1f} us, {b64 / ms64 / 1e6:.0f} GB/s")
-        del m64, y64, a64
+        # the whole pass with int8 lookup tables and a scale per group, the paper's own table
+        # type: k = 64, 6-bit indices, 32 x 256 groups (the deployed representation, 3.125 bits
+        # per value, 2.54 GB) and k = 16, 8 x 256 groups (2.125 bits per value, 1.73 GB).  Timing
+        # only, so the device-layout buffers are filled with random bytes directly (every index
+        # and int8 pattern is valid); the fp16 scales are set to 2^-8.
+        for label, layer_keys, kernel in (
+                ("llama7b_pass_k64_int8_tables_3.125bpv_via_vq_gemv_multi", workloads.LLAMA7B_LAYER_K64,
+                 "gemv_stream_kernel<64>"),
+                ("llama7b_pass_k16_int8_tables_2.125bpv_via_vq_gemv_multi", workloads.LLAMA7B_LAYER_K16_I8,
+                 "gemv_stream_kernel<k16,int8>")):
+            mi8 = []
+            for _ in range(args.layers):
+                for (_, key) in layer_keys:
+                    s = workloads.CONFIGS[key]
+                    desc = vqdev.desc_from_shape(s)
+                    ib, cbb = vq.vq_layout_bytes(desc)
+                    tab = torch.randint(0, 256, (cbb,), dtype=torch.uint8, device=dev)
+                    if s.k == 64:                       # 528-byte records: 4 tables, 4 scales, padding
+                        tv = tab.view(-1, 528)
+                        tv[:, 512:528] = 0
+                        tv[:, 513:520:2] = 0x1C
+                    else:                               # 32 bytes per slot, then 2 bytes of scale per slot
+                        n_slots = cbb // 34
+                        tab[n_slots * 32::2] = 0
+                        tab[n_slots * 32 + 1::2] = 0x1C
+                    mi8.append((s, desc, torch.randint(0, 256, (ib,), dtype=torch.uint8, device=dev), tab))
+            yi8 = [torch.empty(m[0].out_features, dtype=torch.float16, device=dev) for m in mi8]
+            ai8 = vq.GemvMultiArgs([m[1] for m in mi8], [m[2] for m in mi8], [m[3] for m in mi8],
+                                   [xs[m[0].in_features] for m in mi8], yi8)
+            bi8 = sum(sum(workloads.canonical_sizes(m[0])) + 2 * m[0].in_features + 2 * m[0].out_features
+                      for m in mi8)
+            msi8, _ = timer.run(lambda: vq.vq_gemv_multi(ai8), max(10, args.steps // 2), 50)
+            extras[label] = {"us": msi8 * 1e3, "bytes": bi8, "GB/s": bi8 / msi8 / 1e6,
+                             "frac_hbm": bi8 / msi8 / 1e6 / HBM_PEAK_GBS,
+                             "tokens_per_s_weight_stream": 1e3 / msi8, "kernel": kernel}
+            log(f"[bench] {label}: {msi8 * 1e3:.1f} us, {bi8 / msi8 / 1e6:.0f} GB/s")
+            del mi8, yi8, ai8
 
         # the same pass as 224 separate vq_gemv calls (plain stream launches)
         def step_single():
