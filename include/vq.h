@@ -38,8 +38,7 @@
  * Implemented representations: VQ_F16 with 8 x 256 groups and k = 16 or 256; VQ_I8 with
  * k = 64 (6-bit indices) and groups of 8, 16 or 32 rows x 256 columns (32 rows: the
  * 8,192-weight groups and 3.125 bits per value of Sec. 5.1), and VQ_I8 with k = 16 and
- * 8 x 256 groups (2.125 bits per value), for vq_pack_layout, vq_gemv, vq_gemv_multi and
- * vq_decode_dense (vq_gemm_batched returns VQ_ERR_UNSUPPORTED for VQ_I8).
+ * 8 x 256 groups (2.125 bits per value).  Every entry point takes all of them.
  */
 #ifndef VQ_H_
 #define VQ_H_

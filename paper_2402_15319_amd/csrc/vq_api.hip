@@ -209,7 +209,6 @@ int vq_gemm_batched(const vq_desc* desc, const void* idx_dev, const void* cb_dev
                     void* stream) {
   const int st = check_desc(desc);
   if (st != VQ_OK) return st;
-  if (is_i8(*desc)) return VQ_ERR_UNSUPPORTED;   // the batched product exists for fp16 codebooks only
   if (!idx_dev || !cb_dev || !X_f16 || !Y) return VQ_ERR_NULL;
   if (y_dtype != VQ_F16 && y_dtype != VQ_F32) return VQ_ERR_BAD_ARG;
   if (B < 1 || B > 65536) return VQ_ERR_BAD_ARG;

@@ -37,6 +37,10 @@ __device__ __forceinline__ int wt_half_index(int m, int k) {   // k in halfs
   return m * WS + ((((k >> 3) ^ (m & 7)) << 3) | (k & 7));
 }
 
+// K is the kernel format tag: 16 / 256 (fp16 codebooks), 64 (6-bit indices, int8 tables with a
+// scale per group, groups of 8*rpc rows), kFmtK16I8 (k = 16 with int8 tables).
+template <int K> constexpr int lut_dwords() { return K == kFmtK16I8 ? 16 : K; }
+
 // What one wave needs to decode one group: the lane's index bytes and codebook piece.
 template <int K> struct GroupRegs;
 template <> struct GroupRegs<16> {
@@ -47,14 +51,42 @@ template <> struct GroupRegs<256> {
   uint4 w;
   uint4 cbv;      // 4 centroids per lane
 };
+template <> struct GroupRegs<64> {
+  uint32_t d0, d1, d2;   // the lane's 16 six-bit indices of the 8-row block
+  uint32_t two;          // int8 pair of table entry `lane`
+  uint32_t sc;           // the group's fp16 scale
+};
+template <> struct GroupRegs<kFmtK16I8> {
+  uint2 w;
+  uint32_t two;          // int8 pair of table entry lane & 15
+  uint32_t sc;
+};
 
 template <int K>
 __device__ __forceinline__ void load_group(GroupRegs<K>& g, const uint8_t* idx, const uint32_t* cb,
-                                           long long rb, int c, int n_cb, int lane) {
+                                           long long rb, int c, int n_cb, int lane, int n_rb,
+                                           int rpc) {
   if constexpr (K == 16) {
     const int slots = 2 * k16_pairs(n_cb);
     g.w = *reinterpret_cast<const uint2*>(idx + (size_t)rb * slots * 512 + k16_chunk_offset(c, lane));
     g.cbv = cb[((size_t)rb * slots + c) * 16 + (lane & 15)];
+  } else if constexpr (K == kFmtK16I8) {
+    const int slots = 2 * k16_pairs(n_cb);
+    const uint8_t* tabs = reinterpret_cast<const uint8_t*>(cb);
+    g.w = *reinterpret_cast<const uint2*>(idx + (size_t)rb * slots * 512 + k16_chunk_offset(c, lane));
+    g.two = *reinterpret_cast<const uint16_t*>(tabs + ((size_t)rb * slots + c) * 32 + (lane & 15) * 2);
+    g.sc = reinterpret_cast<const uint16_t*>(tabs + (size_t)n_rb * slots * 32)[(size_t)rb * slots + c];
+  } else if constexpr (K == 64) {
+    const int n_quads = k64_quads(n_cb), q = c >> 2, j = c & 3;
+    const uint8_t* iq = idx + ((size_t)rb * n_quads + q) * kK64QuadIdxBytes + lane * 16;
+    const int w0 = 3 * j, w1 = 3 * j + 1, w2 = 3 * j + 2;     // the lane's dwords of col-block j
+    g.d0 = *reinterpret_cast<const uint32_t*>(iq + (w0 >> 2) * 1024 + (w0 & 3) * 4);
+    g.d1 = *reinterpret_cast<const uint32_t*>(iq + (w1 >> 2) * 1024 + (w1 & 3) * 4);
+    g.d2 = *reinterpret_cast<const uint32_t*>(iq + (w2 >> 2) * 1024 + (w2 & 3) * 4);
+    const uint8_t* tq = reinterpret_cast<const uint8_t*>(cb) +
+                        ((size_t)(rb / rpc) * n_quads + q) * kK64QuadTabBytes;
+    g.two = *reinterpret_cast<const uint16_t*>(tq + j * 128 + lane * 2);
+    g.sc = *reinterpret_cast<const uint16_t*>(tq + 512 + 2 * j);
   } else {
     const size_t gi = (size_t)rb * n_cb + c;
     g.w = *reinterpret_cast<const uint4*>(idx + gi * 1024 + lane * 16);
@@ -68,9 +100,24 @@ __device__ __forceinline__ void decode_group(const GroupRegs<K>& g, uint32_t* lu
                                              int m0, int lane) {
   const char* lutb = reinterpret_cast<const char*>(lut);
   uint32_t v[16];
-  if constexpr (K == 16) {
-    const GroupRegs<16>& q = g;
-    if (lane < 16) lut[lane] = q.cbv;
+  if constexpr (K == 64) {
+    lut[lane] = k64_dequant_pair(g.two, __builtin_bit_cast(_Float16, (uint16_t)g.sc));
+    wave_lds_sync();
+    const unsigned long long lo = g.d0 | ((unsigned long long)g.d1 << 32);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int pos = 6 * i;
+      unsigned long long t = pos < 64 ? lo >> pos : (unsigned long long)(g.d2 >> (pos - 64));
+      if (pos < 64 && pos > 58) t |= (unsigned long long)g.d2 << (64 - pos);
+      v[i] = lut[(uint32_t)t & 63u];
+    }
+  } else if constexpr (K == 16 || K == kFmtK16I8) {
+    if constexpr (K == 16) {
+      if (lane < 16) lut[lane] = g.cbv;
+    } else {
+      if (lane < 16) lut[lane] = k64_dequant_pair(g.two, __builtin_bit_cast(_Float16, (uint16_t)g.sc));
+    }
+    const auto& q = g;
     wave_lds_sync();
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
@@ -124,7 +171,7 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const uint8_t* __restrict_
                                                    const uint32_t* __restrict__ cb,
                                                    const uint16_t* __restrict__ X, int B, int ldx,
                                                    void* __restrict__ Y, int ldy, int y_f32,
-                                                   int n_rb, int n_cb, int n_tiles_n) {
+                                                   int n_rb, int n_cb, int n_tiles_n, int rpc) {
   constexpr int MT = 32 * RBW;
   constexpr int KS = 8192 / NT;                  // k per X staging step: 256, 64 or 32
   constexpr int NSUB = 256 / KS;
@@ -134,7 +181,7 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const uint8_t* __restrict_
   __shared__ __attribute__((aligned(16))) uint32_t Xs_all[XBUFS][4096];     // [KS/8][NT][8 halfs] each
   // NT = 32: the tables have their own LDS; otherwise they live in the X buffer that is idle
   // while a col-block is being decoded (the one the last MFMA step has just finished reading)
-  __shared__ __attribute__((aligned(16))) uint32_t lut_own[NT == 32 ? 4 * K : 4];
+  __shared__ __attribute__((aligned(16))) uint32_t lut_own[NT == 32 ? 4 * lut_dwords<K>() : 4];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -165,7 +212,7 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const uint8_t* __restrict_
   for (int a = 0; a < RBW; ++a) {
     rbs[a] = (long long)mt * (4 * RBW) + wave * RBW + a;
     rb_ok[a] = rbs[a] < n_rb;
-    load_group<K>(g[a], idx, cb, rb_ok[a] ? rbs[a] : 0, 0, n_cb, lane);
+    load_group<K>(g[a], idx, cb, rb_ok[a] ? rbs[a] : 0, 0, n_cb, lane, n_rb, rpc);
   }
   XPiece xp;
   load_xpiece(xp, X, (size_t)ko * 8, ldx, n_glob, n_ok);
@@ -173,8 +220,8 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const uint8_t* __restrict_
 
   for (int c = 0; c < n_cb; ++c) {
     // every wave is past its MFMA reads of Wt (barrier at the end of the last sub-step)
-    uint32_t* lut = (NT == 32 ? lut_own : Xs_all[XBUFS - 1 - cur] + 0) + wave * K;
-    static_assert(4 * K <= 4096, "four tables must fit in one X buffer");
+    uint32_t* lut = (NT == 32 ? lut_own : Xs_all[XBUFS - 1 - cur] + 0) + wave * lut_dwords<K>();
+    static_assert(4 * lut_dwords<K>() <= 4096, "four tables must fit in one X buffer");
 #pragma unroll
     for (int a = 0; a < RBW; ++a) {
       const int m0 = (wave * RBW + a) * 8;
@@ -186,7 +233,7 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const uint8_t* __restrict_
           *reinterpret_cast<uint2*>(Wt + wt_half_index(m0 + r, 4 * lane)) = make_uint2(0u, 0u);
       }
       // next col-block's registers (clamped on the last one: a harmless re-read)
-      load_group<K>(g[a], idx, cb, rb_ok[a] ? rbs[a] : 0, min(c + 1, n_cb - 1), n_cb, lane);
+      load_group<K>(g[a], idx, cb, rb_ok[a] ? rbs[a] : 0, min(c + 1, n_cb - 1), n_cb, lane, n_rb, rpc);
     }
     if (XBUFS == 1 || c == 0) {   // the first X piece of the run (later ones are staged one step ahead)
       store_xpiece(xp, Xs_all[cur] + xs_off);
@@ -320,10 +367,10 @@ __global__ __launch_bounds__(256, 2) void gemm_tiny_kernel(const uint8_t* __rest
                                                            const uint32_t* __restrict__ cb,
                                                            const uint16_t* __restrict__ X, int B,
                                                            int ldx, void* __restrict__ Y, int ldy,
-                                                           int y_f32, int n_rb, int n_cb) {
+                                                           int y_f32, int n_rb, int n_cb, int rpc) {
   __shared__ __attribute__((aligned(16))) uint16_t Wt_all[4][16 * WS];
   __shared__ __attribute__((aligned(16))) uint16_t Xt_all[4][16 * WS];
-  __shared__ __attribute__((aligned(16))) uint32_t lut_all[4][2 * K];
+  __shared__ __attribute__((aligned(16))) uint32_t lut_all[4][2 * lut_dwords<K>()];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -352,15 +399,15 @@ __global__ __launch_bounds__(256, 2) void gemm_tiny_kernel(const uint8_t* __rest
 #define VQ_ISSUE(SLOT, C)                                                              \
   {                                                                                    \
     const int cc = min((C), n_cb - 1);                                                 \
-    load_group<K>(g[SLOT][0], idx, cb, rb0, cc, n_cb, lane);                           \
-    load_group<K>(g[SLOT][1], idx, cb, rb1, cc, n_cb, lane);                           \
+    load_group<K>(g[SLOT][0], idx, cb, rb0, cc, n_cb, lane, n_rb, rpc);                           \
+    load_group<K>(g[SLOT][1], idx, cb, rb1, cc, n_cb, lane, n_rb, rpc);                           \
     load_xpiece(xp[SLOT][0], X, (size_t)cc * 256 + 8 * o, ldx, n_ld, true);            \
     load_xpiece(xp[SLOT][1], X, (size_t)cc * 256 + 8 * (o + 16), ldx, n_ld, true);     \
   }
 #define VQ_PROCESS(SLOT)                                                               \
   {                                                                                    \
     decode_group<K>(g[SLOT][0], lut, Wt, 0, lane);                                     \
-    decode_group<K>(g[SLOT][1], lut + K, Wt, 8, lane);                                 \
+    decode_group<K>(g[SLOT][1], lut + lut_dwords<K>(), Wt, 8, lane);                                 \
     _Pragma("unroll") for (int h = 0; h < 2; ++h) {                                    \
       _Pragma("unroll") for (int r = 0; r < 8; ++r) {                                  \
         xp[SLOT][h].r[r].x &= n_mask;                                                  \
@@ -414,7 +461,7 @@ hipError_t launch_tiny(const vq_desc& d, const void* idx_dev, const void* cb_dev
   const int n_rb = d.out_features / kGroupRows, n_cb = d.in_features / kGroupCols;
   const dim3 grid((unsigned)((n_rb + 1) / 2), (unsigned)((B + 15) / 16));
   hipLaunchKernelGGL((gemm_tiny_kernel<K>), grid, dim3(256), 0, s, (const uint8_t*)idx_dev,
-                     (const uint32_t*)cb_dev, (const uint16_t*)X, B, ldx, Y, ldy, y_f32, n_rb, n_cb);
+                     (const uint32_t*)cb_dev, (const uint16_t*)X, B, ldx, Y, ldy, y_f32, n_rb, n_cb, d.group_rows / kGroupRows);
   return hipGetLastError();
 }
 
@@ -430,11 +477,11 @@ __global__ __launch_bounds__(256, 2) void gemm_small_kernel(const uint8_t* __res
                                                             const uint16_t* __restrict__ X, int B,
                                                             int ldx, void* __restrict__ Y, int ldy,
                                                             int y_f32, int n_rb, int n_cb,
-                                                            int n_tiles_n) {
+                                                            int n_tiles_n, int rpc) {
   constexpr int MT = 32, NT = 32;
   __shared__ __attribute__((aligned(16))) uint16_t Wt_all[2][MT * WS];
   __shared__ __attribute__((aligned(16))) uint32_t Xs_all[2][4096];     // [32 k-octets][32 n][8 halfs]
-  __shared__ __attribute__((aligned(16))) uint32_t lut_all[4][K];
+  __shared__ __attribute__((aligned(16))) uint32_t lut_all[4][lut_dwords<K>()];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -469,7 +516,7 @@ __global__ __launch_bounds__(256, 2) void gemm_small_kernel(const uint8_t* __res
 #pragma unroll
   for (int j = 0; j < D; ++j) {
     const int cj = min(j, n_cb - 1);
-    load_group<K>(g[j], idx, cb, rb_ld, cj, n_cb, lane);
+    load_group<K>(g[j], idx, cb, rb_ld, cj, n_cb, lane, n_rb, rpc);
     load_xpiece(xp[j], X, (size_t)cj * 256 + ko * 8, ldx, n_ld, true);
   }
 
@@ -493,7 +540,7 @@ __global__ __launch_bounds__(256, 2) void gemm_small_kernel(const uint8_t* __res
     store_xpiece(xp[j], Xs_all[(j) & 1] + xs_off);                                              \
     if (REFILL) {                                                                               \
       const int cn = min((c) + D, n_cb - 1);                                                    \
-      load_group<K>(g[j], idx, cb, rb_ld, cn, n_cb, lane);                                      \
+      load_group<K>(g[j], idx, cb, rb_ld, cn, n_cb, lane, n_rb, rpc);                                      \
       load_xpiece(xp[j], X, (size_t)cn * 256 + ko * 8, ldx, n_ld, true);                        \
     }                                                                                           \
   }
@@ -560,7 +607,7 @@ hipError_t launch_small(const vq_desc& d, const void* idx_dev, const void* cb_de
   const int tiles_m = (n_rb + 3) / 4, tiles_n = (B + 31) / 32;
   hipLaunchKernelGGL((gemm_small_kernel<K>), dim3((unsigned)(tiles_m * tiles_n)), dim3(256), 0, s,
                      (const uint8_t*)idx_dev, (const uint32_t*)cb_dev, (const uint16_t*)X, B, ldx, Y,
-                     ldy, y_f32, n_rb, n_cb, tiles_n);
+                     ldy, y_f32, n_rb, n_cb, tiles_n, d.group_rows / kGroupRows);
   return hipGetLastError();
 }
 
@@ -571,7 +618,7 @@ hipError_t launch_one(const vq_desc& d, const void* idx_dev, const void* cb_dev,
   const int tiles_m = (n_rb + 4 * RBW - 1) / (4 * RBW), tiles_n = (B + NT - 1) / NT;
   hipLaunchKernelGGL((gemm_kernel<K, RBW, NT>), dim3((unsigned)(tiles_m * tiles_n)), dim3(256), 0, s,
                      (const uint8_t*)idx_dev, (const uint32_t*)cb_dev, (const uint16_t*)X, B, ldx, Y,
-                     ldy, y_f32, n_rb, n_cb, tiles_n);
+                     ldy, y_f32, n_rb, n_cb, tiles_n, d.group_rows / kGroupRows);
   return hipGetLastError();
 }
 
@@ -587,18 +634,19 @@ hipError_t launch_gemm(const vq_desc& d, const void* idx_dev, const void* cb_dev
   const int n_rb = d.out_features / kGroupRows;
   const bool short_matrix = n_rb < 1024;
   const bool tiny = B <= 16 || (B <= 64 && short_matrix);
-  if (d.k == 16) {
-    if (tiny) return launch_tiny<16>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);
-    if (B <= 32) return launch_small<16>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);
-    if (B <= 128) return launch_one<16, 1, 128>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);
-    if (B <= 512) return launch_one<16, 2, 128>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);
-    return launch_one<16, 2, 256>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);
+#define VQ_GEMM_DISPATCH(K)                                                                       \
+  {                                                                                               \
+    if (tiny) return launch_tiny<K>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);             \
+    if (B <= 32) return launch_small<K>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);         \
+    if (B <= 128) return launch_one<K, 1, 128>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);  \
+    if (B <= 512) return launch_one<K, 2, 128>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);  \
+    return launch_one<K, 2, 256>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);                \
   }
-  if (tiny) return launch_tiny<256>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);
-  if (B <= 32) return launch_small<256>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);
-  if (B <= 128) return launch_one<256, 1, 128>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);
-  if (B <= 512) return launch_one<256, 2, 128>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);
-  return launch_one<256, 2, 256>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);
+  if (d.k == 64) VQ_GEMM_DISPATCH(64)
+  if (d.k == 16 && d.codebook_dtype == VQ_I8) VQ_GEMM_DISPATCH(kFmtK16I8)
+  if (d.k == 16) VQ_GEMM_DISPATCH(16)
+  VQ_GEMM_DISPATCH(256)
+#undef VQ_GEMM_DISPATCH
 }
 
 }  // namespace vq

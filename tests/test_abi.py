@@ -91,7 +91,7 @@ def test_bad_descriptors(mutate, status):
 def test_int8_table_representation_sizes_and_entry_points():
     """k = 64, 6-bit indices, int8 tables + scale, 32 x 256 groups: canonical sizes follow
     log2(k)/d + (k*d*8 + 16)/8192 bits per value; the device layout stores quads of four
-    col-blocks; the batched product is not offered for this representation."""
+    col-blocks."""
     L = vq.lib()
     for out_f, in_f in ((4096, 4096), (11008, 4096), (4096, 11008)):
         d = vq.make_desc(out_f, in_f, 64, 6, group_rows=32, codebook_dtype=vq.VQ_I8)
@@ -103,7 +103,7 @@ def test_int8_table_representation_sizes_and_entry_points():
         quads = (in_f // 256 + 3) // 4
         assert dib == (out_f // 8) * quads * 3072 and dcb == (out_f // 32) * quads * 528
         r = ctypes.byref(d)
-        assert L.vq_gemm_batched(r, A, A, A, 16, 16, A + 16, 16, vq.VQ_F16, 0) == -3
+        assert L.vq_gemm_batched(r, A, A, A, 16, 20, A + 16, 16, vq.VQ_F16, 0) == -4   # accepted, then ldx % 8
         assert L.vq_gemv(r, A, A, A + 2, A + 16, vq.VQ_F16, 0) == -4       # validated like the others
     for rows in (8, 16):
         d = vq.make_desc(4096, 4096, 64, 6, group_rows=rows, codebook_dtype=vq.VQ_I8)
@@ -113,7 +113,7 @@ def test_int8_table_representation_sizes_and_entry_points():
     ib, cbb = vq.vq_canonical_bytes(d)
     assert (ib + cbb) * 8 * 2048 == 4096 * 11008 * (2 * 2048 + 16 * 2 * 8 + 16)
     assert vq.vq_layout_bytes(d) == (512 * 44 * 512, 512 * 44 * 34)
-    assert L.vq_gemm_batched(ctypes.byref(d), A, A, A, 16, 16, A + 16, 16, vq.VQ_F16, 0) == -3
+    assert L.vq_gemm_batched(ctypes.byref(d), A, A, A, 0, 16, A + 16, 16, vq.VQ_F16, 0) == -6   # accepted, then B < 1
     d16 = vq.make_desc(4096, 4096, 16, 4)
     d64 = vq.make_desc(4096, 4096, 64, 6, group_rows=32, codebook_dtype=vq.VQ_I8)
     descs = (vq.VQDesc * 2)(d64, d16)

@@ -483,3 +483,32 @@ def test_k16_int8_gemv_multi_llama_layer(env):
     for i, ref in enumerate(refs):
         err = oracle.normwise_rel_err(ys[i].cpu().numpy(), ref)
         assert err <= TOL_F16, (i, err)
+
+
+# ---------------------------------------------------------------- batched product, int8-table formats
+@pytest.mark.parametrize("B", [1, 16, 40, 130, 600])
+@pytest.mark.parametrize("s", [_shape64(96, 768), _shape64(64, 2816, 16), _shape16i8(40, 768), _shape16i8(264, 1024)],
+                         ids=str)
+def test_int8_tables_gemm_small(env, s, B):
+    desc, idx, cb, idx_d, cb_d = _setup_i8(env, s, 680)
+    X = workloads.make_X(s.in_features, B, 680)
+    Y = _gpu_gemm(env, desc, idx_d, cb_d, X, False, pad=8 if B == 40 else 0)
+    assert oracle.normwise_rel_err(Y, oracle.gemm(_fmt(s), idx, cb, X)) <= TOL_F16
+
+
+@pytest.mark.parametrize("B", [16, 24, 100])
+@pytest.mark.parametrize("s", [_shape64(8224, 512), _shape16i8(8200, 512)], ids=str)
+def test_int8_tables_gemm_tall(env, s, B):
+    desc, idx, cb, idx_d, cb_d = _setup_i8(env, s, 681)
+    X = workloads.make_X(s.in_features, B, 681)
+    Y = _gpu_gemm(env, desc, idx_d, cb_d, X, False)
+    assert oracle.normwise_rel_err(Y, oracle.gemm(_fmt(s), idx, cb, X)) <= TOL_F16
+
+
+@pytest.mark.parametrize("B", [16, 2048])
+def test_int8_tables_gemm_deployed_config(env, B):
+    s = workloads.CONFIGS["mlp_up_11008x4096_k64_i8"]
+    desc, idx, cb, idx_d, cb_d = _setup_i8(env, s, 682)
+    X = workloads.make_X(s.in_features, B, 682)
+    Y = _gpu_gemm(env, desc, idx_d, cb_d, X, False)
+    assert oracle.normwise_rel_err(Y, oracle.gemm(_fmt(s), idx, cb, X)) <= TOL_F16
