@@ -257,6 +257,32 @@ def main():
         log(f"[bench] pass via {len(mats)} vq_gemv calls in a HIP graph: {ms_graph * 1e3:.1f} us/step")
         del graph
 
+        # a decode-like launch sequence: per layer q/k/v in one launch, o, gate/up in one launch,
+        # down (what the data dependencies of a decoder allow), replayed from a HIP graph
+        if args.layers == 32:
+            seq = []
+            for l in range(args.layers):
+                for sel in ((0, 1, 2), (3,), (4, 5), (6,)):
+                    ii = [7 * l + i for i in sel]
+                    seq.append(vq.GemvMultiArgs([mats[i][2] for i in ii], [mats[i][3] for i in ii],
+                                                [mats[i][4] for i in ii],
+                                                [xs[mats[i][1].in_features] for i in ii], [ys[i] for i in ii]))
+
+            def step_layerwise():
+                for a in seq:
+                    vq.vq_gemv_multi(a)
+            step_layerwise()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                step_layerwise()
+            ms_lw, _ = timer.run(graph.replay, max(2, args.steps // 4), 3)
+            extras["pass_as_4_launches_per_layer_in_hip_graph"] = {
+                "us_per_pass": ms_lw * 1e3, "GB/s": pass_bytes / ms_lw / 1e6, "launches": len(seq),
+                "us_per_launch": ms_lw * 1e3 / len(seq), "tokens_per_s_weight_stream": 1e3 / ms_lw}
+            log(f"[bench] pass as {len(seq)} launches (qkv | o | gate,up | down) in a HIP graph: "
+                f"{ms_lw * 1e3:.1f} us/step")
+            del graph, seq
+
         # per-shape us/call: HBM-cold (rotate over the distinct matrices of the pass) and
         # cache-resident (same matrix every call)
         per_shape = {}

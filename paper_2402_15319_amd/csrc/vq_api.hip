@@ -58,11 +58,9 @@ void sizes(const vq_desc& d, size_t* idx_bytes, size_t* cb_bytes) {
   }
 }
 
-int choose_splits(long long total_row_blocks) {
-  // Enough waves to cover 256 CUs several times over; few row-blocks -> split K.
-  if (total_row_blocks >= 4096) return 1;
-  if (total_row_blocks >= 2048) return 2;
-  return 4;
+// Units a row-block of `n_cb` col-blocks is cut into (what the strips of the GEMV kernels count).
+int strip_units(int fmt, int n_cb) {
+  return (fmt == 16 || fmt == kFmtK16I8) ? (n_cb + 1) / 2 : fmt == 64 ? (n_cb + 3) / 4 : n_cb;
 }
 
 int hip_status(hipError_t e) { return e == hipSuccess ? VQ_OK : VQ_ERR_HIP; }
@@ -155,9 +153,31 @@ int vq_gemv_multi(int count, const vq_desc* descs, const void* const* idx_dev,
       const int c = descs[first + i].in_features / kGroupCols;
       if (c > max_n_cb) max_n_cb = c;
     }
-    const int splits = choose_splits(rb_launch);
     const int fmt = (descs[0].k == 16 && is_i8(descs[0])) ? kFmtK16I8 : descs[0].k;   // kernel format tag
-    const bool stream_mode = splits == 1 && max_n_cb <= kStreamMaxColBlocks &&
+    const long long stream_from = 4096;   // row-blocks from which the persistent kernel pays
+    // Split-K kernel: `splits` waves share a row-block.  A wave is most efficient with exactly
+    // one full chunk (its fixed costs are spread over 8 groups and nothing is double-buffered),
+    // so take the fewest waves per row-block whose strips still fit in one chunk, and 4 if no
+    // choice does (measured on the q/k/v, o, gate/up and down launches of a 7B layer).  If every
+    // strip fits in one chunk the one-chunk variant of the kernel is used (half the registers).
+    int splits = 4, one_chunk = 0;
+    {
+      int max_units = 0;
+      for (int i = 0; i < n; ++i) {
+        const int units = strip_units(fmt, descs[first + i].in_features / kGroupCols);
+        max_units = units > max_units ? units : max_units;
+      }
+      const int cu = gemv_chunk_units(fmt);
+      for (int sp = 1; sp <= 4; sp <<= 1) {
+        if ((max_units + sp - 1) / sp <= cu) {
+          splits = sp;
+          break;
+        }
+      }
+      one_chunk = (max_units + splits - 1) / splits <= cu;
+    }
+    // many row-blocks: the persistent streaming kernel
+    const bool stream_mode = rb_launch >= stream_from && max_n_cb <= kStreamMaxColBlocks &&
                              gemv_stream_lds_bytes(fmt, max_n_cb) <= 65536;
     GemvBatch batch;                       // 14 KB on the stack; only the used entries are filled
     memset(&batch, 0, offsetof(GemvBatch, p) + (size_t)n * sizeof(GemvProblem));
@@ -174,12 +194,12 @@ int vq_gemv_multi(int count, const vq_desc* descs, const void* const* idx_dev,
       p.y = y[first + i];
       p.n_rb = d.out_features / kGroupRows;
       p.n_cb = d.in_features / kGroupCols;
-      p.splits = splits;
+      p.splits = stream_mode ? 1 : splits;
       p.rb_per_cb = d.group_rows / kGroupRows;
       p.wg_begin = (int32_t)items;
       p.cost_begin = (int32_t)cost;
       cost += (long long)p.n_rb * p.n_cb;
-      const int rb_per_wg = 4 / splits;
+      const int rb_per_wg = 4 / p.splits;
       items += stream_mode ? p.n_rb : (p.n_rb + rb_per_wg - 1) / rb_per_wg;
     }
     if (items > 0x7fffffffll || cost > 0x3fffffffll) return VQ_ERR_UNSUPPORTED;
@@ -191,7 +211,7 @@ int vq_gemv_multi(int count, const vq_desc* descs, const void* const* idx_dev,
       const int resident = gemv_stream_resident_wgs(fmt, max_n_cb);
       grid = (int)(want < resident ? want : resident);
     }
-    const hipError_t e = launch_gemv(fmt, batch, stream_mode ? 1 : 0, grid, max_n_cb,
+    const hipError_t e = launch_gemv(fmt, batch, stream_mode ? 1 : one_chunk ? 2 : 0, grid, max_n_cb,
                                      (hipStream_t)stream);
     if (e != hipSuccess) return VQ_ERR_HIP;
   }

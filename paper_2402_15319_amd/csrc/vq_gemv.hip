@@ -544,9 +544,11 @@ __global__ __launch_bounds__(kStreamWaves * 64) void gemv_stream_kernel(const Ge
 }
 
 // ---- split-K kernel (few row-blocks) ---------------------------------------
-template <int K>
+// ONE: the host guarantees that no strip of the launch is longer than one chunk; the second
+// chunk buffer and its registers disappear, and more workgroups fit on a CU.
+template <int K, bool ONE>
 __global__ __launch_bounds__(256) void gemv_split_kernel(const GemvBatch batch) {
-  __shared__ __attribute__((aligned(16))) uint32_t lut_all[4][2 * Chunk<K>::kLutDwords];
+  __shared__ __attribute__((aligned(16))) uint32_t lut_all[4][(ONE ? 1 : 2) * Chunk<K>::kLutDwords];
   __shared__ float part[4][8];
 
   const int lane = threadIdx.x & 63;
@@ -559,7 +561,7 @@ __global__ __launch_bounds__(256) void gemv_split_kernel(const GemvBatch batch) 
   const int rb = wg_local * rb_per_wg + wave / splits;
   const int split = wave % splits;
   uint32_t* lut_a = lut_all[wave];
-  uint32_t* lut_b = lut_a + Chunk<K>::kLutDwords;
+  uint32_t* lut_b = lut_a + (ONE ? 0 : Chunk<K>::kLutDwords);
   const uint32_t base_a = lds_addr(lut_a), base_b = lds_addr(lut_b);
 
   float acc[8];
@@ -568,7 +570,13 @@ __global__ __launch_bounds__(256) void gemv_split_kernel(const GemvBatch batch) 
 
   if (rb < P.n_rb) {
     Strip S = make_strip<K>(P, rb, split, splits);
-    if (S.chunks_left > 0) {
+    if (ONE) {
+      if (S.chunks_left > 0) {
+        Chunk<K> A;
+        A.load(S, S.u, lane);
+        A.consume(lut_a, base_a, lane, acc);
+      }
+    } else if (S.chunks_left > 0) {
       constexpr int U = Chunk<K>::kUnits;
       Chunk<K> A, B;
       A.load(S, S.u, lane);
@@ -642,21 +650,31 @@ int gemv_stream_resident_wgs(int k, int max_n_cb) {
   return slot;
 }
 
-hipError_t launch_gemv(int k, const GemvBatch& batch, int stream_mode, int grid_wgs,
-                       int max_n_cb, hipStream_t s) {
+int gemv_chunk_units(int fmt) {
+  return (fmt == 16 || fmt == kFmtK16I8) ? Chunk<16>::kUnits : fmt == 64 ? Chunk<64>::kUnits
+                                                                        : Chunk<256>::kUnits;
+}
+
+hipError_t launch_gemv(int k, const GemvBatch& batch, int mode, int grid_wgs, int max_n_cb,
+                       hipStream_t s) {
   const dim3 grid(grid_wgs), block(256);
-  if (stream_mode) {
+  if (mode == 1) {
     const size_t lds = gemv_stream_lds_bytes(k, max_n_cb);
     const dim3 sblock(kStreamWaves * 64);
     if (k == 16) hipLaunchKernelGGL(gemv_stream_kernel<16>, grid, sblock, lds, s, batch);
     else if (k == 64) hipLaunchKernelGGL(gemv_stream_kernel<64>, grid, sblock, lds, s, batch);
     else if (k == kFmtK16I8) hipLaunchKernelGGL(gemv_stream_kernel<kFmtK16I8>, grid, sblock, lds, s, batch);
     else hipLaunchKernelGGL(gemv_stream_kernel<256>, grid, sblock, lds, s, batch);
+  } else if (mode == 2) {
+    if (k == 16) hipLaunchKernelGGL((gemv_split_kernel<16, true>), grid, block, 0, s, batch);
+    else if (k == 64) hipLaunchKernelGGL((gemv_split_kernel<64, true>), grid, block, 0, s, batch);
+    else if (k == kFmtK16I8) hipLaunchKernelGGL((gemv_split_kernel<kFmtK16I8, true>), grid, block, 0, s, batch);
+    else hipLaunchKernelGGL((gemv_split_kernel<256, true>), grid, block, 0, s, batch);
   } else {
-    if (k == 16) hipLaunchKernelGGL(gemv_split_kernel<16>, grid, block, 0, s, batch);
-    else if (k == 64) hipLaunchKernelGGL(gemv_split_kernel<64>, grid, block, 0, s, batch);
-    else if (k == kFmtK16I8) hipLaunchKernelGGL(gemv_split_kernel<kFmtK16I8>, grid, block, 0, s, batch);
-    else hipLaunchKernelGGL(gemv_split_kernel<256>, grid, block, 0, s, batch);
+    if (k == 16) hipLaunchKernelGGL((gemv_split_kernel<16, false>), grid, block, 0, s, batch);
+    else if (k == 64) hipLaunchKernelGGL((gemv_split_kernel<64, false>), grid, block, 0, s, batch);
+    else if (k == kFmtK16I8) hipLaunchKernelGGL((gemv_split_kernel<kFmtK16I8, false>), grid, block, 0, s, batch);
+    else hipLaunchKernelGGL((gemv_split_kernel<256, false>), grid, block, 0, s, batch);
   }
   return hipGetLastError();
 }

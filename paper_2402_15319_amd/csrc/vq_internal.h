@@ -41,15 +41,17 @@ hipError_t launch_pack(const vq_desc& d, const void* idx_canon, const void* cb_c
                        void* idx_dev, void* cb_dev, hipStream_t s);
 hipError_t launch_decode(const vq_desc& d, const void* idx_dev, const void* cb_dev,
                          void* W, hipStream_t s);
-// stream_mode != 0: persistent kernel (total_cost/cost_begin are used, grid_wgs workgroups,
-// x of up to max_n_cb col-blocks staged in LDS); stream_mode == 0: split-K kernel,
-// wg_begin/total_wgs count workgroups (= grid_wgs).
-hipError_t launch_gemv(int fmt, const GemvBatch& batch, int stream_mode, int grid_wgs,
+// mode 1: persistent streaming kernel (total_cost/cost_begin are used, grid_wgs workgroups, x
+// of up to max_n_cb col-blocks staged in LDS); mode 0: split-K kernel, wg_begin/total_wgs count
+// workgroups (= grid_wgs); mode 2: split-K kernel for launches whose strips all fit in one chunk.
+hipError_t launch_gemv(int fmt, const GemvBatch& batch, int mode, int grid_wgs,
                        int max_n_cb, hipStream_t s);
 // Dynamic LDS of the persistent GEMV kernel for x of up to max_n_cb col-blocks.
 size_t gemv_stream_lds_bytes(int k, int max_n_cb);
 // Workgroups of the persistent GEMV kernel that fit on the current device at once.
 int gemv_stream_resident_wgs(int k, int max_n_cb);
+// Units (col-block pairs, quads or col-blocks, by format) that one chunk of the GEMV kernels holds.
+int gemv_chunk_units(int fmt);
 hipError_t launch_gemm(const vq_desc& d, const void* idx_dev, const void* cb_dev,
                        const void* X, int B, int ldx, void* Y, int ldy, int y_f32,
                        hipStream_t s);
