@@ -512,3 +512,66 @@ def test_int8_tables_gemm_deployed_config(env, B):
     X = workloads.make_X(s.in_features, B, 682)
     Y = _gpu_gemm(env, desc, idx_d, cb_d, X, False)
     assert oracle.normwise_rel_err(Y, oracle.gemm(_fmt(s), idx, cb, X)) <= TOL_F16
+
+
+def test_gemv_index_array_beyond_4_gib_sampled_rows(env):
+    """2,359,304 x 8192, k = 16: 4.8 GB of packed indices, so byte offsets pass 2^32 in both the
+    canonical and the device array.  The oracle checks sampled row-blocks (first, around the
+    2^32-byte mark, last) on the slices of the canonical arrays that define them."""
+    torch, vq, vqdev = env
+    out_f, in_f = 2_359_304, 8192
+    s = _shape(out_f, in_f, 16)
+    n_rb, n_cb = out_f // 8, in_f // 256
+    rng = np.random.default_rng(909)
+    idx = rng.integers(0, 256, size=n_rb * n_cb * 512, dtype=np.uint8)
+    cb = (rng.standard_normal((n_rb * n_cb, 16, 2), dtype=np.float32) * 0.02).astype(np.float16)
+    x = workloads.make_x(in_f, 909)
+    desc = vqdev.desc_from_shape(s)
+    idx_d, cb_d = vqdev.upload_and_pack(desc, idx, cb)
+    y = torch.zeros(out_f, dtype=torch.float16, device="cuda:0")
+    vq.vq_gemv(desc, idx_d, cb_d, vqdev.to_device_bytes(x), y)
+    torch.cuda.synchronize()
+    y = y.cpu().numpy().astype(np.float64)
+    at_4gib = (1 << 32) // (n_cb * 512)              # the row-block whose indices straddle byte 2^32
+    sub = oracle.VQFormat(8, in_f, 16, 4)
+    for rb in (0, 1, at_4gib - 1, at_4gib, at_4gib + 1, n_rb // 3, n_rb - 2, n_rb - 1):
+        ref = oracle.gemv(sub, idx[rb * n_cb * 512:(rb + 1) * n_cb * 512], cb[rb * n_cb:(rb + 1) * n_cb], x)
+        assert oracle.normwise_rel_err(y[rb * 8:(rb + 1) * 8], ref) <= TOL_F16, rb
+    assert np.all(y[::4099] != 0)                    # every sampled row was written
+
+
+def _random_cases(seed, n):
+    """Seeded random (shape, is_int8) cases over every implemented representation."""
+    rng = np.random.default_rng(seed)
+    cases = []
+    for _ in range(n):
+        kind = int(rng.integers(0, 4))
+        n_cb = int(rng.integers(1, 14))
+        if kind == 0:
+            cases.append((_shape(8 * int(rng.integers(1, 70)), 256 * n_cb, 16), False))
+        elif kind == 1:
+            cases.append((_shape(8 * int(rng.integers(1, 40)), 256 * n_cb, 256), False))
+        elif kind == 2:
+            rows = int(rng.choice([8, 16, 32]))
+            cases.append((_shape64(rows * int(rng.integers(1, 20)), 256 * n_cb, rows), True))
+        else:
+            cases.append((_shape16i8(8 * int(rng.integers(1, 70)), 256 * n_cb), True))
+    return cases
+
+
+@pytest.mark.parametrize("case", _random_cases(20240, 24), ids=lambda c: str(c[0]))
+def test_random_shapes_every_entry_point(env, case):
+    """Decode (bit-exact), GEMV (fp16 and fp32 y) and the batched product on random shapes."""
+    s, is_i8 = case
+    seed = 7000 + s.out_features + s.in_features + s.k
+    desc, idx, cb, idx_d, cb_d = (_setup_i8 if is_i8 else _setup)(env, s, seed)
+    f = _fmt(s)
+    np.testing.assert_array_equal(_gpu_decode(env, desc, idx_d, cb_d), oracle.decode_dense(f, idx, cb))
+    x = workloads.make_x(s.in_features, seed)
+    ref = oracle.gemv(f, idx, cb, x)
+    assert oracle.normwise_rel_err(_gpu_gemv(env, desc, idx_d, cb_d, x, False), ref) <= TOL_F16
+    assert oracle.normwise_rel_err(_gpu_gemv(env, desc, idx_d, cb_d, x, True), ref) <= TOL_F32
+    B = int(np.random.default_rng(seed).choice([1, 3, 8, 17, 33, 72, 200]))
+    X = workloads.make_X(s.in_features, B, seed)
+    Y = _gpu_gemm(env, desc, idx_d, cb_d, X, True)
+    assert oracle.normwise_rel_err(Y, oracle.gemm(f, idx, cb, X)) <= TOL_F32
