@@ -360,9 +360,15 @@ def main():
                                         40, 10)
                     ms_d, _ = timer.run(lambda: torch.matmul(Wd, X, out=Y), 40, 10)
                     fl = 2.0 * s0.out_features * s0.in_features * B
+                    # the two-step alternative with a caller-owned dense buffer: decode, then dense GEMM
+                    def two_step():
+                        vq.vq_decode_dense(desc, copies[0][0], copies[0][1], Wd)
+                        torch.matmul(Wd, X, out=Y)
+                    ms_2, _ = timer.run(two_step, 40, 10)
                     gemm[f"B{B}"] = {"us": ms_g * 1e3, "TFLOP/s": fl / ms_g / 1e9,
                                      "frac_mfma_f16": fl / ms_g / 1e9 / MFMA_F16_PEAK_TFLOPS,
-                                     "dense_fp16_matmul_us": ms_d * 1e3}
+                                     "dense_fp16_matmul_us": ms_d * 1e3,
+                                     "vq_decode_dense_then_dense_matmul_us": ms_2 * 1e3}
                     log(f"[bench] gemm B={B}: {ms_g * 1e3:.1f} us vs dense {ms_d * 1e3:.1f} us")
                 extras["gemm_11008x4096_k256"] = gemm
                 del Wd

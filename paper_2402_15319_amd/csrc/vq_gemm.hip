@@ -9,17 +9,15 @@
 //     col-block into the LDS tile Wt[MT][256]: indices and codebooks were loaded
 //     into registers one col-block earlier, all 16 lookups of a lane are issued
 //     before the first result is used;
-//   * X is batch-contiguous, while an MFMA operand wants 8 consecutive k per lane,
-//     so X goes through registers on its way to LDS: a thread loads 8 rows x 4
-//     columns, transposes them with v_perm and writes 4 x 16 bytes, giving
-//     Xs[k/8][n][k%8]; the next piece is already loading while the current one is
-//     multiplied;
-//   * NT = 128 / 256: the col-block is consumed in 64- / 32-deep sub-steps through two
-//     X buffers (one barrier per sub-step), wave w owns a quarter of the batch
-//     columns and all MT rows (RBW x NT/128 accumulator tiles);
-//     NT = 32 (small batches, bandwidth-bound): all 256 k are staged at once and
-//     wave w multiplies its own quarter of k; the four partial tiles meet in LDS
-//     at the end.
+//   * X is batch-contiguous, while an MFMA operand wants 8 consecutive k per lane.
+//     gemm_kernel (NT = 128 / 256) copies X sub-tiles to LDS unchanged (16-byte loads, four
+//     sub-tiles ahead in registers, 16-byte LDS stores) and forms the operand with the
+//     transposing LDS read ds_read_b64_tr_b16; the col-block is consumed in 64- / 32-deep
+//     sub-steps through two X buffers (one barrier per sub-step), wave w owns a quarter of
+//     the batch columns and all MT rows (RBW x NT/128 accumulator tiles);
+//   * gemm_small_kernel (32 x 32 tiles, bandwidth-bound batches) and gemm_tiny_kernel
+//     (16 x 16) transpose X in registers instead: a thread loads 8 rows x 4 columns, swaps
+//     halves with v_perm and writes 4 x 16 bytes, giving Xs[k/8][n][k%8].
 #include "vq_device.h"
 #include "vq_internal.h"
 
@@ -152,8 +150,17 @@ __device__ __forceinline__ void load_xpiece(XPiece& p, const uint16_t* X, size_t
   for (int j = 0; j < 8; ++j)
     p.r[j] = ok ? *reinterpret_cast<const uint2*>(X + (k0 + j) * ldx + n0) : make_uint2(0, 0);
 }
-// Writes the piece transposed: 4 columns x 8 k (16 bytes per column) at dst, dst + 4 dwords, ...
-__device__ __forceinline__ void store_xpiece(const XPiece& p, uint32_t* dst) {
+// The X sub-tile is Xs[k/8][column][8 halfs]: 16-byte units, one per (k-octet, column).  Inside
+// a k-octet row the unit of column n sits at n ^ ((n >> 3) & 3): a thread stores 4 consecutive
+// columns (units 64 bytes apart from its neighbour's), and without the swizzle the 8 lanes of one
+// pass of a 128-bit store would use only two of the eight 16-byte bank groups (4-way conflict);
+// with it they use all eight, and the 8 consecutive columns an MFMA operand read covers per pass
+// still map to eight distinct units.
+__device__ __forceinline__ int xs_unit(int n) { return n ^ ((n >> 3) & 3); }
+
+// Writes the piece transposed: 4 columns x 8 k (16 bytes per column).  dst points at the unit
+// of the piece's first column n0 (a multiple of 4) before swizzling; c = (n0 >> 3) & 3.
+__device__ __forceinline__ void store_xpiece(const XPiece& p, uint32_t* dst, int c) {
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const uint32_t sel = (i & 1) ? 0x07060302u : 0x05040100u;   // high or low halves of a dword pair
@@ -162,8 +169,46 @@ __device__ __forceinline__ void store_xpiece(const XPiece& p, uint32_t* dst) {
     o.y = __builtin_amdgcn_perm(i < 2 ? p.r[3].x : p.r[3].y, i < 2 ? p.r[2].x : p.r[2].y, sel);
     o.z = __builtin_amdgcn_perm(i < 2 ? p.r[5].x : p.r[5].y, i < 2 ? p.r[4].x : p.r[4].y, sel);
     o.w = __builtin_amdgcn_perm(i < 2 ? p.r[7].x : p.r[7].y, i < 2 ? p.r[6].x : p.r[6].y, sel);
-    *reinterpret_cast<uint4*>(dst + i * 4) = o;
+    *reinterpret_cast<uint4*>(dst + (i ^ c) * 4) = o;
   }
+}
+
+// ---- X staging of gemm_kernel -----------------------------------------------------------
+// An X sub-tile lives in LDS as it is in memory, Xs[k][NT] halfs with the batch index
+// contiguous, and the matrix-core operand (8 consecutive k of one column per lane) is formed by
+// the transposing LDS read ds_read_b64_tr_b16.  In each block of 16 lanes, lane i hands in the
+// address of 4 consecutive halfs, row i / 4 and column fragment i % 4 of a 4 x 16 tile, and
+// gets back column i of that tile (4 rows).  To keep the four rows of a tile in different
+// banks, the 32-byte chunk c of row k is stored at chunk c ^ (k & 3).
+typedef short s4_t __attribute__((ext_vector_type(4)));
+typedef short s8_t __attribute__((ext_vector_type(8)));
+
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+struct XRows {
+  u32x4_t r[4];   // 16 bytes (8 batch columns) of four rows of the sub-tile, one per pass
+};
+
+// Rows row0 + j * RPP (j = 0..3) are wave-uniform; voff is the lane's part in bytes.
+template <int RPP>
+__device__ __forceinline__ void load_xrows(XRows& p, const uint16_t* X, long long row0, int ldx,
+                                           uint32_t voff) {
+  const char* base = reinterpret_cast<const char*>(X) + (size_t)row0 * ldx * 2;
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+    p.r[j] = *reinterpret_cast<const u32x4_t*>(base + (size_t)j * RPP * ldx * 2 + voff);
+}
+template <int RPP, int NT>
+__device__ __forceinline__ void store_xrows(const XRows& p, char* dst) {
+#pragma unroll
+  for (int j = 0; j < 4; ++j) *reinterpret_cast<u32x4_t*>(dst + j * RPP * NT * 2) = p.r[j];
+}
+// 8 consecutive k (two 4-row tiles, 4 * NT * 2 bytes apart) of the lane's column.
+template <int NT>
+__device__ __forceinline__ h8_t read_x_operand(const char* src) {
+  typedef s4_t __attribute__((address_space(3))) * lds_s4_ptr;
+  const s4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4_ptr)(src));
+  const s4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4_ptr)(src + 4 * NT * 2));
+  return __builtin_bit_cast(h8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
 }
 
 template <int K, int RBW, int NT>
@@ -172,16 +217,15 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const uint8_t* __restrict_
                                                    const uint16_t* __restrict__ X, int B, int ldx,
                                                    void* __restrict__ Y, int ldy, int y_f32,
                                                    int n_rb, int n_cb, int n_tiles_n, int rpc) {
+  static_assert(NT == 128 || NT == 256, "column tile");
   constexpr int MT = 32 * RBW;
-  constexpr int KS = 8192 / NT;                  // k per X staging step: 256, 64 or 32
-  constexpr int NSUB = 256 / KS;
-  constexpr int NB = NT == 32 ? 1 : NT / 128;    // 32-column accumulator tiles per wave
-  constexpr int XBUFS = NT == 32 ? 1 : 2;        // X sub-tiles in LDS (double-buffered when NSUB > 1)
+  constexpr int KS = 8192 / NT;                  // k per X sub-tile: 64 or 32
+  constexpr int NSUB = 256 / KS;                 // sub-steps per col-block: 4 or 8
+  constexpr int NB = NT / 128;                   // 32-column accumulator tiles per wave
+  constexpr int D = 4;                           // X pieces in flight per thread (sub-tiles ahead)
+  static_assert(NSUB % D == 0, "ring slot must be a compile-time constant");
   __shared__ __attribute__((aligned(16))) uint16_t Wt[MT * WS];
-  __shared__ __attribute__((aligned(16))) uint32_t Xs_all[XBUFS][4096];     // [KS/8][NT][8 halfs] each
-  // NT = 32: the tables have their own LDS; otherwise they live in the X buffer that is idle
-  // while a col-block is being decoded (the one the last MFMA step has just finished reading)
-  __shared__ __attribute__((aligned(16))) uint32_t lut_own[NT == 32 ? 4 * lut_dwords<K>() : 4];
+  __shared__ __attribute__((aligned(16))) uint32_t Xs_all[2][4096];     // [KS][NT] halfs each
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -189,12 +233,26 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const uint8_t* __restrict_
   const int mt = blockIdx.x / n_tiles_n;
   const int nt = blockIdx.x - mt * n_tiles_n;
 
-  // X staging role: k-octet ko of the sub-tile, 4 batch columns from n_loc
-  const int ko = tid / (NT / 4);
-  const int n_loc = (tid % (NT / 4)) * 4;
+  // X staging role: a sub-tile is copied in 4 passes of RPP rows; the thread owns 16 bytes
+  // (8 batch columns from n_loc) of row x_row of every pass.  Columns at or beyond B are
+  // loaded from column 0 instead: they only reach accumulator columns that are never written.
+  constexpr int RPP = 2048 / NT;                 // rows per pass: 8 or 16
+  const int x_row = tid / (NT / 8);
+  const int n_loc = (tid % (NT / 8)) * 8;
   const int n_glob = nt * NT + n_loc;
-  const bool n_ok = n_glob < B;
-  const int xs_off = (ko * NT + n_loc) * 4;
+  const int x_row_wave = wave * (RPP / 4);       // first row of the wave inside a pass
+  const int xs_off = x_row * NT * 2 + ((((n_loc >> 4) ^ (x_row & 3)) << 5) | ((n_loc & 8) << 1));
+  uint32_t x_voff = (uint32_t)(((x_row - x_row_wave) * ldx + (n_glob < B ? n_glob : 0)) * 2);
+  asm volatile("" : "+v"(x_voff));   // keep it one 32-bit register next to scalar row bases
+  // operand role: lane i of a 16-lane block addresses row i / 4, fragment i % 4 of a 4 x 16 tile
+  int xr_off[NB];
+#pragma unroll
+  for (int b = 0; b < NB; ++b) {
+    const int kq = (lane & 15) >> 2;
+    const int chunk = ((wave * NB + b) * 32 + (lane & 16)) >> 4;
+    xr_off[b] = (8 * (lane >> 5) + kq) * NT * 2 + ((chunk ^ kq) << 5) + (lane & 3) * 8;
+  }
+  const int n_subtiles = n_cb * NSUB;
 
   f16v_t acc[RBW][NB];
 #pragma unroll
@@ -204,7 +262,7 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const uint8_t* __restrict_
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
 
-  // prologue: registers for col-block 0
+  // prologue: registers for col-block 0, X sub-tile 0 into buffer 0, sub-tiles 1..D in flight
   GroupRegs<K> g[RBW];
   long long rbs[RBW];
   bool rb_ok[RBW];
@@ -214,13 +272,21 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const uint8_t* __restrict_
     rb_ok[a] = rbs[a] < n_rb;
     load_group<K>(g[a], idx, cb, rb_ok[a] ? rbs[a] : 0, 0, n_cb, lane, n_rb, rpc);
   }
-  XPiece xp;
-  load_xpiece(xp, X, (size_t)ko * 8, ldx, n_glob, n_ok);
+  XRows ring[D];   // slot t % D holds sub-tile t + 1 when sub-step t starts
+  {
+    XRows first;
+    load_xrows<RPP>(first, X, x_row_wave, ldx, x_voff);
+#pragma unroll
+    for (int i = 0; i < D; ++i)
+      load_xrows<RPP>(ring[i], X, (long long)min(i + 1, n_subtiles - 1) * KS + x_row_wave, ldx, x_voff);
+    store_xrows<RPP, NT>(first, reinterpret_cast<char*>(Xs_all[0]) + xs_off);
+  }
   int cur = 0;   // X buffer the next MFMA step reads
 
   for (int c = 0; c < n_cb; ++c) {
-    // every wave is past its MFMA reads of Wt (barrier at the end of the last sub-step)
-    uint32_t* lut = (NT == 32 ? lut_own : Xs_all[XBUFS - 1 - cur] + 0) + wave * lut_dwords<K>();
+    // every wave is past its MFMA reads of Wt (barrier at the end of the last sub-step); the
+    // tables live in the X buffer that is idle while a col-block is being decoded
+    uint32_t* lut = Xs_all[1 - cur] + wave * lut_dwords<K>();
     static_assert(4 * lut_dwords<K>() <= 4096, "four tables must fit in one X buffer");
 #pragma unroll
     for (int a = 0; a < RBW; ++a) {
@@ -235,104 +301,55 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const uint8_t* __restrict_
       // next col-block's registers (clamped on the last one: a harmless re-read)
       load_group<K>(g[a], idx, cb, rb_ok[a] ? rbs[a] : 0, min(c + 1, n_cb - 1), n_cb, lane, n_rb, rpc);
     }
-    if (XBUFS == 1 || c == 0) {   // the first X piece of the run (later ones are staged one step ahead)
-      store_xpiece(xp, Xs_all[cur] + xs_off);
-      const int cn = NSUB > 1 ? c : min(c + 1, n_cb - 1);
-      const int sn = NSUB > 1 ? 1 : 0;
-      load_xpiece(xp, X, (size_t)cn * 256 + sn * KS + ko * 8, ldx, n_glob, n_ok);
-    }
-    __syncthreads();   // Wt (and the X piece) of this col-block are complete
+    __syncthreads();   // Wt of this col-block and the X sub-tile in Xs[cur] are complete
 
 #pragma unroll
     for (int sub = 0; sub < NSUB; ++sub) {
-      const uint32_t* Xs = Xs_all[cur];
-      if (XBUFS == 2) {
-        // stage the next sub-tile into the other buffer while this one is multiplied
-        const bool last = (sub + 1 == NSUB) && (c + 1 == n_cb);
-        if (!last) store_xpiece(xp, Xs_all[cur ^ 1] + xs_off);
-        const int s2 = sub + 2;                       // the piece after the one just stored
-        const int cn = s2 < NSUB ? c : min(c + 1, n_cb - 1);
-        const int sn = s2 < NSUB ? s2 : s2 - NSUB;
-        load_xpiece(xp, X, (size_t)cn * 256 + sn * KS + ko * 8, ldx, n_glob, n_ok);
-      }
-      if (NT != 32) {
-        // wave w: batch columns [32*NB*w, 32*NB*(w+1)), all MT rows, the KS k of this sub-step
+      const char* Xs = reinterpret_cast<const char*>(Xs_all[cur]);
+      // stage sub-tile t + 1 (loaded D sub-steps ago) into the other buffer while this one is
+      // multiplied (after the last sub-tile this rewrites it: nobody reads that copy), and start
+      // loading sub-tile t + 1 + D into the slot it leaves
+      const int t = c * NSUB + sub;
+      XRows& slot = ring[sub % D];
+      store_xrows<RPP, NT>(slot, reinterpret_cast<char*>(Xs_all[cur ^ 1]) + xs_off);
+      load_xrows<RPP>(slot, X, (long long)min(t + 1 + D, n_subtiles - 1) * KS + x_row_wave, ldx, x_voff);
+      // wave w: batch columns [32*NB*w, 32*NB*(w+1)), all MT rows, the KS k of this sub-step
 #pragma unroll
-        for (int kk = 0; kk < KS / 16; ++kk) {
-          h8_t bv[NB];
+      for (int kk = 0; kk < KS / 16; ++kk) {
+        h8_t bv[NB];
+#pragma unroll
+        for (int b = 0; b < NB; ++b)
+          bv[b] = read_x_operand<NT>(Xs + xr_off[b] + 16 * kk * NT * 2);
+#pragma unroll
+        for (int a = 0; a < RBW; ++a) {
+          const h8_t av = *reinterpret_cast<const h8_t*>(
+              Wt + wt_half_index(32 * a + (lane & 31), sub * KS + 16 * kk + 8 * (lane >> 5)));
 #pragma unroll
           for (int b = 0; b < NB; ++b)
-            bv[b] = *reinterpret_cast<const h8_t*>(
-                Xs + ((2 * kk + (lane >> 5)) * NT + (wave * NB + b) * 32 + (lane & 31)) * 4);
-#pragma unroll
-          for (int a = 0; a < RBW; ++a) {
-            const h8_t av = *reinterpret_cast<const h8_t*>(
-                Wt + wt_half_index(32 * a + (lane & 31), sub * KS + 16 * kk + 8 * (lane >> 5)));
-#pragma unroll
-            for (int b = 0; b < NB; ++b)
-              acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av, bv[b], acc[a][b], 0, 0, 0);
-          }
-        }
-      } else {
-        // wave w: k in [64w, 64w+64) of the col-block, all 32 batch columns
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-          const int k16 = wave * 4 + kk;
-          const h8_t bv = *reinterpret_cast<const h8_t*>(
-              Xs + ((2 * k16 + (lane >> 5)) * NT + (lane & 31)) * 4);
-#pragma unroll
-          for (int a = 0; a < RBW; ++a) {
-            const h8_t av = *reinterpret_cast<const h8_t*>(
-                Wt + wt_half_index(32 * a + (lane & 31), 16 * k16 + 8 * (lane >> 5)));
-            acc[a][0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av, bv, acc[a][0], 0, 0, 0);
-          }
+            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av, bv[b], acc[a][b], 0, 0, 0);
         }
       }
       __syncthreads();   // reads of Xs[cur] (and, on the last sub-step, of Wt) done; Xs[cur^1] complete
-      if (XBUFS == 2) cur ^= 1;
+      cur ^= 1;
     }
   }
 
   // ---- store: accumulator register i holds row 8*(i/4) + 4*(lane/32) + i%4, column lane%32
-  if (NT != 32) {
 #pragma unroll
-    for (int b = 0; b < NB; ++b) {
-      const int n = nt * NT + (wave * NB + b) * 32 + (lane & 31);
-      if (n < B) {
+  for (int b = 0; b < NB; ++b) {
+    const int n = nt * NT + (wave * NB + b) * 32 + (lane & 31);
+    if (n < B) {
 #pragma unroll
-        for (int a = 0; a < RBW; ++a)
+      for (int a = 0; a < RBW; ++a)
 #pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            const int row = mt * MT + 32 * a + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
-            if (row < n_rb * 8) {
-              const size_t o = (size_t)row * ldy + n;
-              if (y_f32) reinterpret_cast<float*>(Y)[o] = acc[a][b][i];
-              else reinterpret_cast<_Float16*>(Y)[o] = (_Float16)acc[a][b][i];
-            }
+        for (int i = 0; i < 16; ++i) {
+          const int row = mt * MT + 32 * a + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
+          if (row < n_rb * 8) {
+            const size_t o = (size_t)row * ldy + n;
+            if (y_f32) reinterpret_cast<float*>(Y)[o] = acc[a][b][i];
+            else reinterpret_cast<_Float16*>(Y)[o] = (_Float16)acc[a][b][i];
           }
-      }
-    }
-  } else {
-    // four partial MT x 32 tiles (one per wave) -> LDS (the W tile is free now) -> sum -> Y
-    float* part = reinterpret_cast<float*>(Wt);            // [4][MT][32] floats
-    static_assert(4 * MT * 32 * 4 <= MT * WS * 2, "partial tiles must fit in the W tile");
-#pragma unroll
-    for (int a = 0; a < RBW; ++a)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int m = 32 * a + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
-        part[(wave * MT + m) * 32 + (lane & 31)] = acc[a][0][i];
-      }
-    __syncthreads();
-    for (int e = tid; e < MT * 32; e += 256) {
-      const int m = e >> 5, nl = e & 31;
-      const float s = part[e] + part[MT * 32 + e] + part[2 * MT * 32 + e] + part[3 * MT * 32 + e];
-      const int row = mt * MT + m, n = nt * NT + nl;
-      if (row < n_rb * 8 && n < B) {
-        const size_t o = (size_t)row * ldy + n;
-        if (y_f32) reinterpret_cast<float*>(Y)[o] = s;
-        else reinterpret_cast<_Float16*>(Y)[o] = (_Float16)s;
-      }
+        }
     }
   }
 }
@@ -537,7 +554,7 @@ __global__ __launch_bounds__(256, 2) void gemm_small_kernel(const uint8_t* __res
       xp[j].r[r].x &= n_mask;                                                                   \
       xp[j].r[r].y &= n_mask;                                                                   \
     }                                                                                           \
-    store_xpiece(xp[j], Xs_all[(j) & 1] + xs_off);                                              \
+    store_xpiece(xp[j], Xs_all[(j) & 1] + xs_off, (n_loc >> 3) & 3);                            \
     if (REFILL) {                                                                               \
       const int cn = min((c) + D, n_cb - 1);                                                    \
       load_group<K>(g[j], idx, cb, rb_ld, cn, n_cb, lane, n_rb, rpc);                                      \
@@ -553,7 +570,7 @@ __global__ __launch_bounds__(256, 2) void gemm_small_kernel(const uint8_t* __res
       _Pragma("unroll") for (int kk = 0; kk < 4; ++kk) {                                        \
         const int k16 = wave * 4 + kk;                                                          \
         const h8_t bv = *reinterpret_cast<const h8_t*>(                                         \
-            Xs + ((2 * k16 + (lane >> 5)) * NT + (lane & 31)) * 4);                             \
+            Xs + ((2 * k16 + (lane >> 5)) * NT + xs_unit(lane & 31)) * 4);                      \
         const h8_t av = *reinterpret_cast<const h8_t*>(                                         \
             Wt + wt_half_index(lane & 31, 16 * k16 + 8 * (lane >> 5)));                         \
         acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(av, bv, acc, 0, 0, 0);                     \
@@ -628,18 +645,25 @@ hipError_t launch_gemm(const vq_desc& d, const void* idx_dev, const void* cb_dev
                        int B, int ldx, void* Y, int ldy, int y_f32, hipStream_t s) {
   // B <= 16: 16 x 16 tiles, barrier-free (gemm_tiny_kernel).  It re-decodes W once per 16
   // columns, which still pays up to 64 columns when the matrix is too short to fill the CUs
-  // with the 32-row tiles of the other kernels (measured on 4096 x 4096 and 11008 x 4096).
-  // Then 32 x 32 tiles (small batches, bandwidth-bound), and 32/64-row x 128/256-column
-  // tiles for the matrix-core-bound sizes.
+  // with the 32-row tiles of the other kernels.  Then 32 x 32 tiles (gemm_small_kernel,
+  // bandwidth-bound) while they are few enough to run in about one wave of workgroups, and
+  // 32 x 128, 64 x 128 and 64 x 256 tiles (gemm_kernel) as the tile count grows: a larger tile
+  // reads X and the decoded W less often per product, a smaller one fills the 256 CUs sooner.
+  // The thresholds are measured on 4096 x 4096, 11008 x 4096 and 4096 x 11008, B = 24..4096.
   const int n_rb = d.out_features / kGroupRows;
   const bool short_matrix = n_rb < 1024;
   const bool tiny = B <= 16 || (B <= 64 && short_matrix);
+  const long long tiles_small = (long long)((n_rb + 3) / 4) * ((B + 31) / 32);
+  const long long tiles_64x128 = (long long)((n_rb + 7) / 8) * ((B + 127) / 128);
+  const bool small = B <= 32 || tiles_small <= 768;
 #define VQ_GEMM_DISPATCH(K)                                                                       \
   {                                                                                               \
     if (tiny) return launch_tiny<K>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);             \
-    if (B <= 32) return launch_small<K>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);         \
-    if (B <= 128) return launch_one<K, 1, 128>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);  \
-    if (B <= 512) return launch_one<K, 2, 128>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);  \
+    if (small) return launch_small<K>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);           \
+    if (tiles_64x128 <= 128)                                                                      \
+      return launch_one<K, 1, 128>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);              \
+    if (tiles_64x128 < 1024)                                                                      \
+      return launch_one<K, 2, 128>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);              \
     return launch_one<K, 2, 256>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);                \
   }
   if (d.k == 64) VQ_GEMM_DISPATCH(64)

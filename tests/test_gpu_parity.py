@@ -505,6 +505,22 @@ def test_int8_tables_gemm_tall(env, s, B):
     assert oracle.normwise_rel_err(Y, oracle.gemm(_fmt(s), idx, cb, X)) <= TOL_F16
 
 
+# The matrix-core kernels with 128- and 256-column tiles are chosen by tile count, so a short
+# matrix reaches them only with a wide batch: 1000 columns -> 32 x 128 tiles, 1300 -> 64 x 128,
+# 10100 -> 64 x 256 (ragged last column tile in each; 101 row-blocks leave a ragged row tile).
+@pytest.mark.parametrize("B", [1000, 1300, 10100])
+@pytest.mark.parametrize("s", [_shape(800, 512, 16), _shape(808, 768, 256), _shape64(800, 512),
+                               _shape16i8(808, 512)], ids=str)
+def test_gemm_wide_batches(env, s, B):
+    if s.int8_tables:
+        desc, idx, cb, idx_d, cb_d = _setup_i8(env, s, 690)
+    else:
+        desc, idx, cb, idx_d, cb_d = _setup(env, s, 690)
+    X = workloads.make_X(s.in_features, B, 690)
+    Y = _gpu_gemm(env, desc, idx_d, cb_d, X, False, pad=8 if B == 1300 else 0)
+    assert oracle.normwise_rel_err(Y, oracle.gemm(_fmt(s), idx, cb, X)) <= TOL_F16
+
+
 @pytest.mark.parametrize("B", [16, 2048])
 def test_int8_tables_gemm_deployed_config(env, B):
     s = workloads.CONFIGS["mlp_up_11008x4096_k64_i8"]
