@@ -14,7 +14,8 @@ from oracle import VQFormat
 import workloads
 from golden_io import read_case, read_bpv_table
 
-GOLDEN_CASES = ["decode_2x4_k4_b2.txt", "decode_1x8_k16_b4.txt", "decode_1x16_k8_b3.txt"]
+GOLDEN_CASES = ["decode_2x4_k4_b2.txt", "decode_1x8_k16_b4.txt", "decode_1x16_k8_b3.txt",
+                "decode_2x8_k4_b2_d1.txt"]
 
 
 def _fmt(case):
@@ -377,3 +378,41 @@ def test_i8_workload_generator_shapes():
     f = VQFormat(64, 512, 64, 6, 32, 256, 2)
     I = oracle.unpack_indices(f, idx)
     assert I.shape == (4, 4096) and I.max() == 63 and I.min() == 0
+
+
+# ---------------------------------------------------------------- scalar codebooks (d = 1)
+def test_scalar_codebook_equals_pair_table_of_twice_the_index_width():
+    """Two neighbouring b-bit indices of a d = 1 stream are one 2b-bit index of a d = 2 stream
+    over the same bytes, with the table T[j] = (c[j % k], c[j // k]): the bit stream is
+    little-endian, so the lower column's index is the low half of the pair index.  A swapped
+    pair order or a big-endian reading of the stream fails here."""
+    rng = np.random.default_rng(41)
+    f1 = VQFormat(16, 512, 16, 4, 8, 256, 1)
+    f2 = VQFormat(16, 512, 256, 8, 8, 256, 2)
+    idx = rng.integers(0, 256, size=oracle.canonical_sizes(f1)[0], dtype=np.uint8)
+    assert oracle.canonical_sizes(f2)[0] == idx.size
+    c = rng.normal(0, 1, size=(f1.n_groups, 16, 1)).astype(np.float16)
+    j = np.arange(256)
+    T = np.stack([c[:, j % 16, 0], c[:, j // 16, 0]], axis=2)            # [g, 256, 2]
+    np.testing.assert_array_equal(oracle.decode_dense(f1, idx, c), oracle.decode_dense(f2, idx, T))
+    # and element by element against the nibbles read directly from the bytes
+    W = oracle.decode_dense(f1, idx, c).view(np.float16)
+    for (r, col) in [(0, 0), (0, 1), (3, 255), (9, 256), (15, 511), (8, 300)]:
+        g = (r // 8) * 2 + col // 256
+        v = (r % 8) * 256 + col % 256
+        byte = int(idx[g * 1024 + v // 2])
+        nib = (byte >> 4) if v % 2 else (byte & 15)
+        assert W[r, col] == c[g, nib, 0]
+
+
+def test_scalar_format_sizes_follow_the_bpv_formula():
+    """d = 1, k = 16, fp16 codebooks, 8 x 256 groups: 4 + 16*16/2048 = 4.125 bits per value
+    (the total of the 1D 4.125 row of the appendix table, which reaches the same overhead with
+    8-bit codebooks and groups of 1,024)."""
+    assert oracle.bits_per_value(16, 1, 16, 2048) == 4.125
+    assert oracle.bits_per_value(16, 1, 8, 1024) == 4.125
+    s = workloads.CONFIGS["mlp_up_11008x4096_d1_k16"]
+    ib, cbb = workloads.canonical_sizes(s)
+    assert (ib + cbb) * 8 / (s.out_features * s.in_features) == 4.125
+    f = VQFormat(s.out_features, s.in_features, s.k, s.index_bits, s.group_rows, s.group_cols, s.d)
+    assert oracle.canonical_sizes(f) == (ib, cbb)

@@ -22,7 +22,7 @@ import numpy as np
 __all__ = [
     "VQShape", "CONFIGS", "LLAMA7B_LAYER", "seed_for", "canonical_sizes",
     "make_weights", "make_weights_i8", "make_x", "make_X", "llama7b_pass_shapes",
-    "LLAMA7B_LAYER_K64", "LLAMA7B_LAYER_K16_I8",
+    "LLAMA7B_LAYER_K64", "LLAMA7B_LAYER_K16_I8", "LLAMA7B_LAYER_D1_K16",
 ]
 
 
@@ -70,6 +70,10 @@ CONFIGS = {
     "attn_4096x4096_k16_i8": VQShape(4096, 4096, 16, 4, 8, 256, 2, True),
     "mlp_up_11008x4096_k16_i8": VQShape(11008, 4096, 16, 4, 8, 256, 2, True),
     "mlp_down_4096x11008_k16_i8": VQShape(4096, 11008, 16, 4, 8, 256, 2, True),
+    # scalar codebooks (d = 1): 16 fp16 values per 8 x 256 group, 4-bit indices: 4.125 bpv
+    "attn_4096x4096_d1_k16": VQShape(4096, 4096, 16, 4, 8, 256, 1),
+    "mlp_up_11008x4096_d1_k16": VQShape(11008, 4096, 16, 4, 8, 256, 1),
+    "mlp_down_4096x11008_d1_k16": VQShape(4096, 11008, 16, 4, 8, 256, 1),
     "tiny_64x512_k64_i8": VQShape(64, 512, 64, 6, 32, 256, 2, True),
     "attn_4096x4096_k64_i8": VQShape(4096, 4096, 64, 6, 32, 256, 2, True),
     "mlp_up_11008x4096_k64_i8": VQShape(11008, 4096, 64, 6, 32, 256, 2, True),
@@ -88,6 +92,7 @@ LLAMA7B_LAYER = (
 )
 LLAMA7B_LAYER_K64 = tuple((n, k.replace("_k16", "_k64_i8")) for n, k in LLAMA7B_LAYER)
 LLAMA7B_LAYER_K16_I8 = tuple((n, k + "_i8") for n, k in LLAMA7B_LAYER)
+LLAMA7B_LAYER_D1_K16 = tuple((n, k.replace("_k16", "_d1_k16")) for n, k in LLAMA7B_LAYER)
 LLAMA7B_N_LAYERS = 32
 
 _BASE_SEED = 15319 * 10
