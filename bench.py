@@ -197,8 +197,8 @@ def main():
         log(f"[bench] 8 layers with k=256: {ms256 * 1e3:.1f} us, {b256 / ms256 / 1e6:.0f} GB/s")
         del m256, y256, a256
 
-        # the whole pass with int8 lookup tables and a scale per group, the paper's own table
-        # type: k = 64, 6-bit indices, 32 x 256 groups (the deployed representation, 3.125 bits
+        # the whole pass in the other representations.  Int8 lookup tables and a scale per group,
+        # the paper's own table type: k = 64, 6-bit indices, 32 x 256 groups (the deployed representation, 3.125 bits
         # per value, 2.54 GB) and k = 16, 8 x 256 groups (2.125 bits per value, 1.73 GB).  Timing
         # only, so the device-layout buffers are filled with random bytes directly (every index
         # and int8 pattern is valid); the fp16 scales are set to 2^-8.
@@ -206,7 +206,10 @@ def main():
                 ("llama7b_pass_k64_int8_tables_3.125bpv_via_vq_gemv_multi", workloads.LLAMA7B_LAYER_K64,
                  "gemv_stream_kernel<64>"),
                 ("llama7b_pass_k16_int8_tables_2.125bpv_via_vq_gemv_multi", workloads.LLAMA7B_LAYER_K16_I8,
-                 "gemv_stream_kernel<k16,int8>")):
+                 "gemv_stream_kernel<k16,int8>"),
+                # scalar codebooks (d = 1): 16 fp16 values per 8 x 256 group, 4-bit indices, 3.47 GB
+                ("llama7b_pass_d1_k16_4.125bpv_via_vq_gemv_multi", workloads.LLAMA7B_LAYER_D1_K16,
+                 "gemv_stream_kernel<d1,k16>")):
             mi8 = []
             for _ in range(args.layers):
                 for (_, key) in layer_keys:
@@ -214,7 +217,9 @@ def main():
                     desc = vqdev.desc_from_shape(s)
                     ib, cbb = vq.vq_layout_bytes(desc)
                     tab = torch.randint(0, 256, (cbb,), dtype=torch.uint8, device=dev)
-                    if s.k == 64:                       # 528-byte records: 4 tables, 4 scales, padding
+                    if s.d == 1:                        # fp16 scalars
+                        tab = (torch.randn(cbb // 2, device=dev) * 0.02).half().view(torch.uint8)
+                    elif s.k == 64:                       # 528-byte records: 4 tables, 4 scales, padding
                         tv = tab.view(-1, 528)
                         tv[:, 512:528] = 0
                         tv[:, 513:520:2] = 0x1C

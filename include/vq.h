@@ -35,10 +35,12 @@
  *     that fp16 matrix is W for every entry point.
  * The device layout written by vq_pack_layout is private to the library.
  *
- * Implemented representations: VQ_F16 with 8 x 256 groups and k = 16 or 256; VQ_I8 with
- * k = 64 (6-bit indices) and groups of 8, 16 or 32 rows x 256 columns (32 rows: the
- * 8,192-weight groups and 3.125 bits per value of Sec. 5.1), and VQ_I8 with k = 16 and
- * 8 x 256 groups (2.125 bits per value).  Every entry point takes all of them.
+ * Implemented representations (d = 2 unless stated): VQ_F16 with 8 x 256 groups and k = 16
+ * or 256; VQ_I8 with k = 64 (6-bit indices) and groups of 8, 16 or 32 rows x 256 columns
+ * (32 rows: the 8,192-weight groups and 3.125 bits per value of Sec. 5.1); VQ_I8 with k = 16
+ * and 8 x 256 groups (2.125 bits per value); and scalar codebooks, d = 1 (the 1D rows of the
+ * appendix table of VQ configurations): VQ_F16, k = 16, 4-bit indices, 8 x 256 groups, 4.125
+ * bits per value.  Every entry point takes all of them.
  */
 #ifndef VQ_H_
 #define VQ_H_
@@ -57,7 +59,8 @@ typedef enum vq_status {
   VQ_ERR_NULL = -1,        /* a required pointer is NULL                                  */
   VQ_ERR_BAD_DESC = -2,    /* descriptor is inconsistent (non-positive size, k != 2^bits) */
   VQ_ERR_UNSUPPORTED = -3, /* consistent but not implemented (shape not a multiple of the
-                              group, d != 2, group != 8x256, k not in {16,256}, dtype)    */
+                              group, or a d / k / group / dtype combination outside the
+                              list above)                                                  */
   VQ_ERR_ALIGN = -4,       /* a device pointer is not 16-byte aligned / bad leading dim   */
   VQ_ERR_HIP = -5,         /* the HIP runtime refused the launch (see hipGetLastError)    */
   VQ_ERR_BAD_ARG = -6      /* a scalar argument is out of range (batch, count, dtype)     */
@@ -72,7 +75,7 @@ typedef struct vq_desc {
   int32_t in_features;    /* columns of W (length of x)                             */
   int32_t group_rows;     /* 8 (VQ_I8: 8, 16 or 32)                                 */
   int32_t group_cols;     /* 256 (Sec. 4: at most 256 columns per group)            */
-  int32_t d;              /* VQ dimensionality, 2                                   */
+  int32_t d;              /* VQ dimensionality: 2, or 1 (scalar codebooks)          */
   int32_t k;              /* centroids: 16 or 256 (VQ_F16), 64 or 16 (VQ_I8)        */
   int32_t index_bits;     /* log2(k): 4, 8 or 6                                     */
   int32_t codebook_dtype; /* VQ_F16 or VQ_I8                                        */
@@ -123,7 +126,8 @@ VQ_API int vq_gemv(const vq_desc* desc, const void* idx_dev, const void* cb_dev,
  * length `count` holding descriptors and device pointers; they are read
  * during the call and need not outlive it (the problem table travels in the
  * kernel arguments, up to 256 problems per launch).  All y_i share y_dtype and
- * all descriptors share k.  Each product obeys the rules of vq_gemv.
+ * all descriptors share one representation (d, k, codebook_dtype).  Each
+ * product obeys the rules of vq_gemv.
  * count in [1, 65536].
  */
 VQ_API int vq_gemv_multi(int count, const vq_desc* descs, const void* const* idx_dev,

@@ -14,7 +14,9 @@ bool is_pow2(int v) { return v > 0 && (v & (v - 1)) == 0; }
 //   fp16 codebooks, 8 x 256 groups, k = 16 (4-bit indices) or 256 (8-bit);
 //   int8 tables with one fp16 scale per group: k = 64 (6-bit indices), groups of 8, 16 or 32
 //   rows x 256 columns (32 rows = the 8,192-weight groups of Sec. 5.1), or k = 16 with 8 x 256
-//   groups (2.125 bits per value).
+//   groups (2.125 bits per value);
+//   d = 1 (scalar codebooks): k = 16 fp16 values per 8 x 256 group, 4-bit indices (4.125 bits
+//   per value, the overhead of the 1D 4.125 row of the appendix table of VQ configurations).
 bool is_i8(const vq_desc& d) { return d.codebook_dtype == VQ_I8; }
 
 int check_desc(const vq_desc* d) {
@@ -25,8 +27,10 @@ int check_desc(const vq_desc* d) {
   if (!is_pow2(d->k) || d->k != (1 << d->index_bits)) return VQ_ERR_BAD_DESC;
   if (d->group_cols % d->d) return VQ_ERR_BAD_DESC;
   if (d->codebook_dtype != VQ_F16 && d->codebook_dtype != VQ_I8) return VQ_ERR_UNSUPPORTED;
-  if (d->d != 2 || d->group_cols != kGroupCols) return VQ_ERR_UNSUPPORTED;
-  if (is_i8(*d)) {
+  if ((d->d != 2 && d->d != 1) || d->group_cols != kGroupCols) return VQ_ERR_UNSUPPORTED;
+  if (d->d == 1) {
+    if (d->k != 16 || is_i8(*d) || d->group_rows != kGroupRows) return VQ_ERR_UNSUPPORTED;
+  } else if (is_i8(*d)) {
     if (d->k == 64) {
       if (d->group_rows != 8 && d->group_rows != 16 && d->group_rows != 32) return VQ_ERR_UNSUPPORTED;
     } else if (d->k == 16) {
@@ -111,6 +115,11 @@ int vq_layout_bytes(const vq_desc* desc, size_t* idx_bytes, size_t* cb_bytes) {
     if (cb_bytes) *cb_bytes = (size_t)(desc->out_features / desc->group_rows) * n_quads * 528;
     return VQ_OK;
   }
+  if (desc->d == 1) {    // 1 KB of indices and 16 fp16 scalars per group
+    if (idx_bytes) *idx_bytes = n_rb * n_cb * 1024;
+    if (cb_bytes) *cb_bytes = n_rb * n_cb * 32;
+    return VQ_OK;
+  }
   const size_t slots = desc->k == 16 ? 2 * ((n_cb + 1) / 2) : n_cb;
   if (idx_bytes) *idx_bytes = n_rb * slots * (1024 * (size_t)desc->index_bits / 8);
   if (cb_bytes) *cb_bytes = is_i8(*desc) ? n_rb * slots * 34 : n_rb * slots * (size_t)desc->k * 4;
@@ -137,8 +146,7 @@ int vq_gemv_multi(int count, const vq_desc* descs, const void* const* idx_dev,
   for (int i = 0; i < count; ++i) {
     const int st = check_desc(&descs[i]);
     if (st != VQ_OK) return st;
-    if (descs[i].k != descs[0].k || descs[i].codebook_dtype != descs[0].codebook_dtype)
-      return VQ_ERR_BAD_ARG;
+    if (format_tag(descs[i]) != format_tag(descs[0])) return VQ_ERR_BAD_ARG;
     if (!idx_dev[i] || !cb_dev[i] || !x_f16[i] || !y[i]) return VQ_ERR_NULL;
     if (!aligned16(idx_dev[i]) || !aligned16(cb_dev[i]) || !aligned16(x_f16[i]) || !aligned16(y[i]))
       return VQ_ERR_ALIGN;
@@ -153,7 +161,7 @@ int vq_gemv_multi(int count, const vq_desc* descs, const void* const* idx_dev,
       const int c = descs[first + i].in_features / kGroupCols;
       if (c > max_n_cb) max_n_cb = c;
     }
-    const int fmt = (descs[0].k == 16 && is_i8(descs[0])) ? kFmtK16I8 : descs[0].k;   // kernel format tag
+    const int fmt = format_tag(descs[0]);
     const long long stream_from = 4096;   // row-blocks from which the persistent kernel pays
     // Split-K kernel: `splits` waves share a row-block.  A wave is most efficient with exactly
     // one full chunk (its fixed costs are spread over 8 groups and nothing is double-buffered),

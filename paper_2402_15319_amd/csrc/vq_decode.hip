@@ -9,13 +9,14 @@ namespace vq {
 namespace {
 
 // K: 16 or 256 with fp16 codebooks, kFmtK16I8 for k = 16 with int8 tables and a scale per group
-// (32 bytes per group slot, then one fp16 scale per slot behind all the tables).
+// (32 bytes per group slot, then one fp16 scale per slot behind all the tables), kFmtD1K16 for
+// scalar codebooks (16 fp16 values per group; a byte of indices looks up a pair of them).
 template <int K>
 __global__ __launch_bounds__(256) void decode_kernel(const uint8_t* __restrict__ idx,
                                                      const uint32_t* __restrict__ cb,
                                                      uint16_t* __restrict__ W, int n_cb,
                                                      long long n_groups, int in_features) {
-  __shared__ uint32_t lut_all[4][K == kFmtK16I8 ? 16 : K];
+  __shared__ uint32_t lut_all[4][K == kFmtK16I8 ? 16 : K == kFmtD1K16 ? 256 : K];
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   uint32_t* lut = lut_all[wave];
@@ -52,7 +53,14 @@ __global__ __launch_bounds__(256) void decode_kernel(const uint8_t* __restrict__
       }
     }
   } else {
-    *reinterpret_cast<uint4*>(lut + lane * 4) = *reinterpret_cast<const uint4*>(cb + g * 256 + lane * 4);
+    if (K == kFmtD1K16) {
+      const uint8_t* cg = reinterpret_cast<const uint8_t*>(cb) + g * 32;
+      *reinterpret_cast<uint4*>(lut + lane * 4) =
+          d1_pair_entries(*reinterpret_cast<const uint2*>(cg + (lane & 3) * 8),
+                          *reinterpret_cast<const uint16_t*>(cg + (lane >> 2) * 2));
+    } else {
+      *reinterpret_cast<uint4*>(lut + lane * 4) = *reinterpret_cast<const uint4*>(cb + g * 256 + lane * 4);
+    }
     const uint4 w = *reinterpret_cast<const uint4*>(idx + g * 1024 + lane * 16);
     wave_lds_sync();
     const uint32_t ws[4] = {w.x, w.y, w.z, w.w};
@@ -119,21 +127,21 @@ hipError_t launch_decode(const vq_desc& d, const void* idx_dev, const void* cb_d
   const int n_cb = d.in_features / kGroupCols;
   const long long n_groups = (long long)(d.out_features / kGroupRows) * n_cb;   // 8-row items
   const unsigned grid = (unsigned)((n_groups + 3) / 4);
-  if (d.k == 64) {
+  const int fmt = format_tag(d);
+  if (fmt == 64) {
     hipLaunchKernelGGL(decode64_kernel, dim3(grid), dim3(256), 0, s, (const uint8_t*)idx_dev,
                        (const uint8_t*)cb_dev, (uint16_t*)W, n_cb, n_groups, d.in_features,
                        d.group_rows / kGroupRows);
     return hipGetLastError();
   }
-  if (d.k == 16 && d.codebook_dtype == VQ_I8)
-    hipLaunchKernelGGL(decode_kernel<kFmtK16I8>, dim3(grid), dim3(256), 0, s, (const uint8_t*)idx_dev,
-                       (const uint32_t*)cb_dev, (uint16_t*)W, n_cb, n_groups, d.in_features);
-  else if (d.k == 16)
-    hipLaunchKernelGGL(decode_kernel<16>, dim3(grid), dim3(256), 0, s, (const uint8_t*)idx_dev,
-                       (const uint32_t*)cb_dev, (uint16_t*)W, n_cb, n_groups, d.in_features);
-  else
-    hipLaunchKernelGGL(decode_kernel<256>, dim3(grid), dim3(256), 0, s, (const uint8_t*)idx_dev,
-                       (const uint32_t*)cb_dev, (uint16_t*)W, n_cb, n_groups, d.in_features);
+#define VQ_DECODE(K)                                                                                \
+  hipLaunchKernelGGL(decode_kernel<K>, dim3(grid), dim3(256), 0, s, (const uint8_t*)idx_dev,       \
+                     (const uint32_t*)cb_dev, (uint16_t*)W, n_cb, n_groups, d.in_features)
+  if (fmt == kFmtK16I8) VQ_DECODE(kFmtK16I8);
+  else if (fmt == kFmtD1K16) VQ_DECODE(kFmtD1K16);
+  else if (fmt == 16) VQ_DECODE(16);
+  else VQ_DECODE(256);
+#undef VQ_DECODE
   return hipGetLastError();
 }
 

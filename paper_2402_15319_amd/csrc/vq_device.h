@@ -122,6 +122,17 @@ __device__ __forceinline__ void k16_group(uint32_t w0, uint32_t w1, uint32_t bas
 #undef VQ_DOT
 
 // ---------------------------------------------------------------------------
+// d = 1, k = 16 (scalar codebooks): a byte of the index stream holds the 4-bit indices of two
+// neighbouring columns, low nibble first, and is used as one index into the 256-entry table
+// of fp16 pairs T[j] = (c[j % 16], c[j / 16]).  A lane builds entries 4L..4L+3: `lo` holds
+// c[4*(L%4) .. 4*(L%4)+3] (8 bytes at byte offset 8*(L%4) of the group's 32-byte codebook),
+// `hi` holds c[L/4] in its low half (2 bytes at offset 2*(L/4)).
+__device__ __forceinline__ uint4 d1_pair_entries(uint2 lo, uint32_t hi) {
+  const uint32_t h = hi << 16;
+  return make_uint4((lo.x & 0xffffu) | h, (lo.x >> 16) | h, (lo.y & 0xffffu) | h, (lo.y >> 16) | h);
+}
+
+// ---------------------------------------------------------------------------
 // k = 256 inner block: the 16 lookups + dot products of one lane's share of one
 // group (four dwords; byte 2r+e = row r, vector 2L+e), hand-scheduled like
 // k16_group.  Address = base + OFF + 4*index: one v_bfe_u32 and one

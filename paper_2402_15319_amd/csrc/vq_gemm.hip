@@ -37,7 +37,7 @@ __device__ __forceinline__ int wt_half_index(int m, int k) {   // k in halfs
 
 // K is the kernel format tag: 16 / 256 (fp16 codebooks), 64 (6-bit indices, int8 tables with a
 // scale per group, groups of 8*rpc rows), kFmtK16I8 (k = 16 with int8 tables).
-template <int K> constexpr int lut_dwords() { return K == kFmtK16I8 ? 16 : K; }
+template <int K> constexpr int lut_dwords() { return K == kFmtK16I8 ? 16 : K == kFmtD1K16 ? 256 : K; }
 
 // What one wave needs to decode one group: the lane's index bytes and codebook piece.
 template <int K> struct GroupRegs;
@@ -53,6 +53,11 @@ template <> struct GroupRegs<64> {
   uint32_t d0, d1, d2;   // the lane's 16 six-bit indices of the 8-row block
   uint32_t two;          // int8 pair of table entry `lane`
   uint32_t sc;           // the group's fp16 scale
+};
+template <> struct GroupRegs<kFmtD1K16> {
+  uint4 w;
+  uint2 clo;      // scalars 4*(lane%4) .. +3 of the group's 16
+  uint32_t chi;   // scalar lane/4
 };
 template <> struct GroupRegs<kFmtK16I8> {
   uint2 w;
@@ -74,6 +79,12 @@ __device__ __forceinline__ void load_group(GroupRegs<K>& g, const uint8_t* idx, 
     g.w = *reinterpret_cast<const uint2*>(idx + (size_t)rb * slots * 512 + k16_chunk_offset(c, lane));
     g.two = *reinterpret_cast<const uint16_t*>(tabs + ((size_t)rb * slots + c) * 32 + (lane & 15) * 2);
     g.sc = reinterpret_cast<const uint16_t*>(tabs + (size_t)n_rb * slots * 32)[(size_t)rb * slots + c];
+  } else if constexpr (K == kFmtD1K16) {
+    const size_t gi = (size_t)rb * n_cb + c;
+    const uint8_t* cg = reinterpret_cast<const uint8_t*>(cb) + gi * 32;
+    g.w = *reinterpret_cast<const uint4*>(idx + gi * 1024 + lane * 16);
+    g.clo = *reinterpret_cast<const uint2*>(cg + (lane & 3) * 8);
+    g.chi = *reinterpret_cast<const uint16_t*>(cg + (lane >> 2) * 2);
   } else if constexpr (K == 64) {
     const int n_quads = k64_quads(n_cb), q = c >> 2, j = c & 3;
     const uint8_t* iq = idx + ((size_t)rb * n_quads + q) * kK64QuadIdxBytes + lane * 16;
@@ -128,8 +139,9 @@ __device__ __forceinline__ void decode_group(const GroupRegs<K>& g, uint32_t* lu
       }
     }
   } else {
-    const GroupRegs<256>& q = g;
-    *reinterpret_cast<uint4*>(lut + lane * 4) = q.cbv;
+    const auto& q = g;
+    if constexpr (K == kFmtD1K16) *reinterpret_cast<uint4*>(lut + lane * 4) = d1_pair_entries(q.clo, q.chi);
+    else *reinterpret_cast<uint4*>(lut + lane * 4) = q.cbv;
     wave_lds_sync();
     const uint32_t ws[4] = {q.w.x, q.w.y, q.w.z, q.w.w};
 #pragma unroll
@@ -666,9 +678,11 @@ hipError_t launch_gemm(const vq_desc& d, const void* idx_dev, const void* cb_dev
       return launch_one<K, 2, 128>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);              \
     return launch_one<K, 2, 256>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);                \
   }
-  if (d.k == 64) VQ_GEMM_DISPATCH(64)
-  if (d.k == 16 && d.codebook_dtype == VQ_I8) VQ_GEMM_DISPATCH(kFmtK16I8)
-  if (d.k == 16) VQ_GEMM_DISPATCH(16)
+  const int fmt = format_tag(d);
+  if (fmt == 64) VQ_GEMM_DISPATCH(64)
+  if (fmt == kFmtK16I8) VQ_GEMM_DISPATCH(kFmtK16I8)
+  if (fmt == kFmtD1K16) VQ_GEMM_DISPATCH(kFmtD1K16)
+  if (fmt == 16) VQ_GEMM_DISPATCH(16)
   VQ_GEMM_DISPATCH(256)
 #undef VQ_GEMM_DISPATCH
 }

@@ -134,12 +134,16 @@ template <bool I8> struct Chunk16T {
 template <> struct Chunk<16> : Chunk16T<false> {};
 template <> struct Chunk<kFmtK16I8> : Chunk16T<true> {};
 
-template <> struct Chunk<256> {
+// k = 256 (D1 = false), and d = 1 with k = 16 (D1 = true): the same index bytes and inner
+// block; D1 builds the 256-entry pair table from the group's 16 scalars instead of loading it.
+template <bool D1> struct Chunk256T {
   static constexpr int kUnits = 2;        // groups per chunk
-  static constexpr int kLutDwords = 512;  // 2 groups x 256 centroids
+  static constexpr int kLutDwords = 512;  // 2 groups x 256 table entries
   uint4 w[2];     // the lane's 16 index bytes of group u+s
   uint2 xv[2];    // its activations
-  uint4 cbv[2];   // the lane's 16 bytes of the group's codebook
+  uint4 cbv[2];   // k = 256: the lane's 16 bytes of the group's codebook
+  uint2 clo[2];   // d = 1: scalars 4*(lane%4) .. +3 of the group
+  uint32_t chi[2];   // d = 1: scalar lane/4
 
   __device__ __forceinline__ void load(const Strip& S, int u, int lane) {
 #pragma unroll
@@ -147,21 +151,29 @@ template <> struct Chunk<256> {
       const bool ok = u + s < S.u_end;
       const int c = ok ? u + s : 0;
       w[s] = stream_load16(S.idx_rb + (size_t)c * 1024 + lane * 16);
-      cbv[s] = zero_unless(ok, stream_load16(S.cb_rb + (size_t)c * 256 + lane * 4));
+      if constexpr (D1) {
+        const uint8_t* cg = reinterpret_cast<const uint8_t*>(S.cb_rb) + (size_t)c * 32;
+        clo[s] = zero_unless(ok, *reinterpret_cast<const uint2*>(cg + (lane & 3) * 8));
+        chi[s] = zero_unless(ok, (uint32_t)*reinterpret_cast<const uint16_t*>(cg + (lane >> 2) * 2));
+      } else {
+        cbv[s] = zero_unless(ok, stream_load16(S.cb_rb + (size_t)c * 256 + lane * 4));
+      }
       xv[s] = zero_unless(ok, *reinterpret_cast<const uint2*>(S.x + c * 256 + lane * 4));
     }
   }
 
   __device__ __forceinline__ void consume(uint32_t* lut, uint32_t base, int lane,
                                           float (&acc)[8]) const {
-    *reinterpret_cast<uint4*>(lut + lane * 4) = cbv[0];
-    *reinterpret_cast<uint4*>(lut + 256 + lane * 4) = cbv[1];
+    *reinterpret_cast<uint4*>(lut + lane * 4) = D1 ? d1_pair_entries(clo[0], chi[0]) : cbv[0];
+    *reinterpret_cast<uint4*>(lut + 256 + lane * 4) = D1 ? d1_pair_entries(clo[1], chi[1]) : cbv[1];
     wave_lds_sync();
     k256_group<0>(w[0].x, w[0].y, w[0].z, w[0].w, base, xv[0].x, xv[0].y, acc);
     k256_group<1024>(w[1].x, w[1].y, w[1].z, w[1].w, base, xv[1].x, xv[1].y, acc);
     acc_hazard_fence();
   }
 };
+template <> struct Chunk<256> : Chunk256T<false> {};
+template <> struct Chunk<kFmtD1K16> : Chunk256T<true> {};
 
 template <> struct Chunk<64> {
   static constexpr int kUnits = 1;        // quads of 4 col-blocks per chunk
@@ -237,7 +249,7 @@ __device__ __forceinline__ Strip make_strip(const GemvProblem& P, int rb, int sp
     S.chunks_left = S.u_end - S.u;
   } else {
     S.idx_rb = P.idx + (size_t)rb * n_cb * 1024;
-    S.cb_rb = P.cb + (size_t)rb * n_cb * 256;
+    S.cb_rb = P.cb + (size_t)rb * n_cb * (K == kFmtD1K16 ? 8 : 256);   // dwords per group's codebook
     S.u = (n_cb * split) / splits;
     S.u_end = (n_cb * (split + 1)) / splits;
     S.chunks_left = (S.u_end - S.u + 1) >> 1;
@@ -344,11 +356,13 @@ template <bool I8> struct ChunkS16T {
 template <> struct ChunkS<16> : ChunkS16T<false> {};
 template <> struct ChunkS<kFmtK16I8> : ChunkS16T<true> {};
 
-template <> struct ChunkS<256> {
+template <bool D1> struct ChunkS256T {
   static constexpr int kUnits = 2;
   static constexpr int kLutDwords = 512;
   uint4 w[2];
   uint4 cbv[2];
+  uint2 clo[2];      // d = 1: see Chunk256T
+  uint32_t chi[2];
   int u0;          // first col-block
 
   __device__ __forceinline__ void load(const Strip& S, int u, int lane) {
@@ -360,14 +374,20 @@ template <> struct ChunkS<256> {
       const bool ok = u + s < S.u_end;
       const int c = ok ? u + s : 0;
       w[s] = stream_load16(S.idx_rb + (size_t)c * 1024 + voff);
-      cbv[s] = zero_unless(ok, stream_load16(reinterpret_cast<const uint8_t*>(S.cb_rb + (size_t)c * 256) + voff));
+      if constexpr (D1) {
+        const uint8_t* cg = reinterpret_cast<const uint8_t*>(S.cb_rb) + (size_t)c * 32;
+        clo[s] = zero_unless(ok, *reinterpret_cast<const uint2*>(cg + (lane & 3) * 8));
+        chi[s] = zero_unless(ok, (uint32_t)*reinterpret_cast<const uint16_t*>(cg + (lane >> 2) * 2));
+      } else {
+        cbv[s] = zero_unless(ok, stream_load16(reinterpret_cast<const uint8_t*>(S.cb_rb + (size_t)c * 256) + voff));
+      }
     }
   }
 
   __device__ __forceinline__ void consume(uint32_t* lut, uint32_t base, const uint32_t* x_s, int lane,
                                           float (&acc)[8]) const {
-    *reinterpret_cast<uint4*>(lut + lane * 4) = cbv[0];
-    *reinterpret_cast<uint4*>(lut + 256 + lane * 4) = cbv[1];
+    *reinterpret_cast<uint4*>(lut + lane * 4) = D1 ? d1_pair_entries(clo[0], chi[0]) : cbv[0];
+    *reinterpret_cast<uint4*>(lut + 256 + lane * 4) = D1 ? d1_pair_entries(clo[1], chi[1]) : cbv[1];
     wave_lds_sync();
     const uint2* xp = reinterpret_cast<const uint2*>(x_s) + u0 * 64 + lane;
     const uint2 x0 = xp[0], x1 = xp[64];
@@ -376,6 +396,8 @@ template <> struct ChunkS<256> {
     acc_hazard_fence();
   }
 };
+template <> struct ChunkS<256> : ChunkS256T<false> {};
+template <> struct ChunkS<kFmtD1K16> : ChunkS256T<true> {};
 
 template <> struct ChunkS<64> {
   static constexpr int kUnits = 1;
@@ -616,31 +638,41 @@ __global__ __launch_bounds__(256) void gemv_split_kernel(const GemvBatch batch) 
 
 }  // namespace
 
-size_t gemv_stream_lds_bytes(int k, int max_n_cb) {
-  const int lut_dwords = (k == 16 || k == kFmtK16I8) ? ChunkS<16>::kLutDwords
-                         : k == 64 ? ChunkS<64>::kLutDwords : ChunkS<256>::kLutDwords;
+// Calls F<tag>() for the kernel format tag `fmt`.
+#define VQ_FMT_SWITCH(fmt, F)                 \
+  switch (fmt) {                              \
+    case 16: F(16); break;                    \
+    case 64: F(64); break;                    \
+    case kFmtK16I8: F(kFmtK16I8); break;      \
+    case kFmtD1K16: F(kFmtD1K16); break;      \
+    default: F(256); break;                   \
+  }
+
+size_t gemv_stream_lds_bytes(int fmt, int max_n_cb) {
+  int lut_dwords = 0;
+#define VQ_F(K) lut_dwords = ChunkS<K>::kLutDwords
+  VQ_FMT_SWITCH(fmt, VQ_F)
+#undef VQ_F
   return (size_t)kStreamWaves * 2 * lut_dwords * 4 + 16 + (size_t)(max_n_cb + kXPadColBlocks) * 512;
 }
 
-int gemv_stream_resident_wgs(int k, int max_n_cb) {
-  // Occupancy of the persistent kernel for this LDS size, asked once per (device, k, size):
+int gemv_stream_resident_wgs(int fmt, int max_n_cb) {
+  // Occupancy of the persistent kernel for this LDS size, asked once per (device, format, size):
   // a pure function of the code object and the device, cached so that the hot path makes
   // no runtime queries.  Benign if two threads fill the same slot at once.
-  static int cached[4][16][kStreamMaxColBlocks + 1];
+  static int cached[5][16][kStreamMaxColBlocks + 1];
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) dev = 0;
-  int& slot = cached[k == 16 ? 0 : k == 64 ? 1 : k == kFmtK16I8 ? 3 : 2][dev][max_n_cb];
+  const int fi = fmt == 16 ? 0 : fmt == 64 ? 1 : fmt == kFmtK16I8 ? 3 : fmt == kFmtD1K16 ? 4 : 2;
+  int& slot = cached[fi][dev][max_n_cb];
   if (slot == 0) {
     int per_cu = 0, cus = 0;
-    const size_t lds = gemv_stream_lds_bytes(k, max_n_cb);
+    const size_t lds = gemv_stream_lds_bytes(fmt, max_n_cb);
     const int threads = kStreamWaves * 64;
-    hipError_t e = k == 16
-        ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gemv_stream_kernel<16>, threads, lds)
-        : k == 64
-        ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gemv_stream_kernel<64>, threads, lds)
-        : k == kFmtK16I8
-        ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gemv_stream_kernel<kFmtK16I8>, threads, lds)
-        : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gemv_stream_kernel<256>, threads, lds);
+    hipError_t e = hipSuccess;
+#define VQ_F(K) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gemv_stream_kernel<K>, threads, lds)
+    VQ_FMT_SWITCH(fmt, VQ_F)
+#undef VQ_F
     if (e != hipSuccess || per_cu < 1) per_cu = 1;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
       cus = 256;
@@ -651,30 +683,30 @@ int gemv_stream_resident_wgs(int k, int max_n_cb) {
 }
 
 int gemv_chunk_units(int fmt) {
-  return (fmt == 16 || fmt == kFmtK16I8) ? Chunk<16>::kUnits : fmt == 64 ? Chunk<64>::kUnits
-                                                                        : Chunk<256>::kUnits;
+  int units = 0;
+#define VQ_F(K) units = Chunk<K>::kUnits
+  VQ_FMT_SWITCH(fmt, VQ_F)
+#undef VQ_F
+  return units;
 }
 
-hipError_t launch_gemv(int k, const GemvBatch& batch, int mode, int grid_wgs, int max_n_cb,
+hipError_t launch_gemv(int fmt, const GemvBatch& batch, int mode, int grid_wgs, int max_n_cb,
                        hipStream_t s) {
   const dim3 grid(grid_wgs), block(256);
   if (mode == 1) {
-    const size_t lds = gemv_stream_lds_bytes(k, max_n_cb);
+    const size_t lds = gemv_stream_lds_bytes(fmt, max_n_cb);
     const dim3 sblock(kStreamWaves * 64);
-    if (k == 16) hipLaunchKernelGGL(gemv_stream_kernel<16>, grid, sblock, lds, s, batch);
-    else if (k == 64) hipLaunchKernelGGL(gemv_stream_kernel<64>, grid, sblock, lds, s, batch);
-    else if (k == kFmtK16I8) hipLaunchKernelGGL(gemv_stream_kernel<kFmtK16I8>, grid, sblock, lds, s, batch);
-    else hipLaunchKernelGGL(gemv_stream_kernel<256>, grid, sblock, lds, s, batch);
+#define VQ_F(K) hipLaunchKernelGGL(gemv_stream_kernel<K>, grid, sblock, lds, s, batch)
+    VQ_FMT_SWITCH(fmt, VQ_F)
+#undef VQ_F
   } else if (mode == 2) {
-    if (k == 16) hipLaunchKernelGGL((gemv_split_kernel<16, true>), grid, block, 0, s, batch);
-    else if (k == 64) hipLaunchKernelGGL((gemv_split_kernel<64, true>), grid, block, 0, s, batch);
-    else if (k == kFmtK16I8) hipLaunchKernelGGL((gemv_split_kernel<kFmtK16I8, true>), grid, block, 0, s, batch);
-    else hipLaunchKernelGGL((gemv_split_kernel<256, true>), grid, block, 0, s, batch);
+#define VQ_F(K) hipLaunchKernelGGL((gemv_split_kernel<K, true>), grid, block, 0, s, batch)
+    VQ_FMT_SWITCH(fmt, VQ_F)
+#undef VQ_F
   } else {
-    if (k == 16) hipLaunchKernelGGL((gemv_split_kernel<16, false>), grid, block, 0, s, batch);
-    else if (k == 64) hipLaunchKernelGGL((gemv_split_kernel<64, false>), grid, block, 0, s, batch);
-    else if (k == kFmtK16I8) hipLaunchKernelGGL((gemv_split_kernel<kFmtK16I8, false>), grid, block, 0, s, batch);
-    else hipLaunchKernelGGL((gemv_split_kernel<256, false>), grid, block, 0, s, batch);
+#define VQ_F(K) hipLaunchKernelGGL((gemv_split_kernel<K, false>), grid, block, 0, s, batch)
+    VQ_FMT_SWITCH(fmt, VQ_F)
+#undef VQ_F
   }
   return hipGetLastError();
 }

@@ -9,9 +9,18 @@ namespace vq {
 constexpr int kGroupRows = 8;
 constexpr int kGroupCols = 256;
 constexpr int kMaxProblemsPerLaunch = 256;  // the problem table travels in the kernel arguments (14 KB)
-// Kernel format tags: the codebook size for fp16 codebooks (16, 256) and for k = 64 (always int8
-// tables); k = 16 with int8 tables has a tag of its own.
+// Kernel format tags: the codebook size for d = 2 with fp16 codebooks (16, 256) and for k = 64
+// (always int8 tables); k = 16 with int8 tables and the scalar (d = 1) format have tags of
+// their own.  d = 1, k = 16: two neighbouring 4-bit indices form one byte, which indexes a
+// 256-entry table of fp16 pairs T[j] = (c[j % 16], c[j / 16]) that the kernels build in LDS from
+// the group's 16 scalars; from there on the work is that of d = 2, k = 256.
 constexpr int kFmtK16I8 = 1016;
+constexpr int kFmtD1K16 = 2016;
+inline int format_tag(const vq_desc& d) {
+  if (d.d == 1) return kFmtD1K16;
+  if (d.k == 16 && d.codebook_dtype == VQ_I8) return kFmtK16I8;
+  return d.k;
+}
 constexpr int kStreamMaxColBlocks = 96;   // widest x the streaming kernel stages in LDS (48 KB)
 
 // One matrix-vector product as the kernels see it (lives in the kernel arguments).
@@ -47,9 +56,9 @@ hipError_t launch_decode(const vq_desc& d, const void* idx_dev, const void* cb_d
 hipError_t launch_gemv(int fmt, const GemvBatch& batch, int mode, int grid_wgs,
                        int max_n_cb, hipStream_t s);
 // Dynamic LDS of the persistent GEMV kernel for x of up to max_n_cb col-blocks.
-size_t gemv_stream_lds_bytes(int k, int max_n_cb);
+size_t gemv_stream_lds_bytes(int fmt, int max_n_cb);
 // Workgroups of the persistent GEMV kernel that fit on the current device at once.
-int gemv_stream_resident_wgs(int k, int max_n_cb);
+int gemv_stream_resident_wgs(int fmt, int max_n_cb);
 // Units (col-block pairs, quads or col-blocks, by format) that one chunk of the GEMV kernels holds.
 int gemv_chunk_units(int fmt);
 hipError_t launch_gemm(const vq_desc& d, const void* idx_dev, const void* cb_dev,

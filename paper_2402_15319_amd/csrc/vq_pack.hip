@@ -54,14 +54,13 @@ __global__ __launch_bounds__(256) void pack_idx_kernel(const uint8_t* __restrict
 }
 
 // Codebooks: canonical order; k=16 row-blocks with an odd number of col-blocks get a
-// zero codebook for the pad group.  One thread per 16 bytes of the device array.
+// zero codebook for the pad group.  One thread per 16 bytes of the device array; a codebook
+// is `per_group` such pieces and a row-block has `slots_per_rb` group slots.
 __global__ __launch_bounds__(256) void pack_cb_kernel(const uint4* __restrict__ src,
-                                                      uint4* __restrict__ dst, int k, int n_cb,
-                                                      long long n16) {
+                                                      uint4* __restrict__ dst, int per_group,
+                                                      int slots_per_rb, int n_cb, long long n16) {
   const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
   if (t >= n16) return;
-  const int per_group = k / 4;                                  // 16-byte pieces per codebook
-  const int slots_per_rb = k == 16 ? 2 * k16_pairs(n_cb) : n_cb;
   const long long slot = t / per_group;
   const int piece = (int)(t - slot * per_group);
   const long long rb = slot / slots_per_rb;
@@ -206,8 +205,10 @@ hipError_t launch_pack(const vq_desc& d, const void* idx_canon, const void* cb_c
                        n_grow);
     return hipGetLastError();
   }
-  const long long n_slots = n_rb * (d.k == 16 ? 2 * k16_pairs(n_cb) : n_cb);
-  if (d.k == 16 && d.codebook_dtype == VQ_I8) {
+  const int fmt = format_tag(d);
+  const int slots_per_rb = (fmt == 16 || fmt == kFmtK16I8) ? 2 * k16_pairs(n_cb) : n_cb;
+  const long long n_slots = n_rb * slots_per_rb;
+  if (fmt == kFmtK16I8) {
     hipLaunchKernelGGL(pack_idx_kernel<16>, dim3((unsigned)((n_slots * 64 + 255) / 256)), dim3(256), 0, s,
                        (const uint8_t*)idx_canon, (uint8_t*)idx_dev, n_cb, n_slots);
     hipError_t e = hipGetLastError();
@@ -219,17 +220,18 @@ hipError_t launch_pack(const vq_desc& d, const void* idx_canon, const void* cb_c
     return hipGetLastError();
   }
   const unsigned grid = (unsigned)((n_slots * 64 + 255) / 256);
-  if (d.k == 16)
+  if (fmt == 16)
     hipLaunchKernelGGL(pack_idx_kernel<16>, dim3(grid), dim3(256), 0, s,
                        (const uint8_t*)idx_canon, (uint8_t*)idx_dev, n_cb, n_slots);
-  else
+  else   // k = 256 bytes, or d = 1: a byte holds the two 4-bit indices of a column pair
     hipLaunchKernelGGL(pack_idx_kernel<256>, dim3(grid), dim3(256), 0, s,
                        (const uint8_t*)idx_canon, (uint8_t*)idx_dev, n_cb, n_slots);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  const long long n16 = n_slots * d.k * 4 / 16;
+  const int per_group = d.k * d.d * 2 / 16;                      // 16-byte pieces of one fp16 codebook
+  const long long n16 = n_slots * per_group;
   hipLaunchKernelGGL(pack_cb_kernel, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, s,
-                     (const uint4*)cb_canon, (uint4*)cb_dev, d.k, n_cb, n16);
+                     (const uint4*)cb_canon, (uint4*)cb_dev, per_group, slots_per_rb, n_cb, n16);
   return hipGetLastError();
 }
 

@@ -65,6 +65,9 @@ A = 0x1000  # a fake, 16-byte aligned, non-NULL address; validation fails before
     (dict(out_features=0), -2),
     (dict(index_bits=0), -2),
     (dict(d=4), -3),
+    (dict(d=1, k=256, index_bits=8), -3),                                 # scalar codebooks: k = 16 only
+    (dict(d=1, codebook_dtype=3), -3),                                    # ... with fp16 values
+    (dict(d=1, group_rows=32), -3),
     (dict(group_rows=4), -3),
     (dict(group_cols=128), -3),
     (dict(k=64, index_bits=6), -3),                                       # k = 64 needs int8 tables
@@ -158,3 +161,25 @@ def test_status_strings():
     for s in range(-6, 0):
         assert vq.vq_status_string(s).startswith("VQ_ERR_")
     assert vq.vq_version() >= 1
+
+
+def test_scalar_codebook_representation_sizes_and_entry_points():
+    """d = 1, k = 16, 4-bit indices, fp16 codebooks, 8 x 256 groups: 1 KB of indices and 32 bytes
+    of codebook per group in both layouts (4.125 bits per value)."""
+    L = vq.lib()
+    for out_f, in_f in ((4096, 4096), (11008, 4096), (4096, 11008)):
+        d = vq.make_desc(out_f, in_f, 16, 4, d=1)
+        n_groups = (out_f // 8) * (in_f // 256)
+        assert vq.vq_canonical_bytes(d) == (n_groups * 1024, n_groups * 32)
+        assert vq.vq_layout_bytes(d) == (n_groups * 1024, n_groups * 32)
+        r = ctypes.byref(d)
+        assert L.vq_gemm_batched(r, A, A, A, 16, 20, A + 16, 16, vq.VQ_F16, 0) == -4   # accepted, then ldx % 8
+        assert L.vq_gemv(r, A, A, A + 2, A + 16, vq.VQ_F16, 0) == -4
+        assert L.vq_decode_dense(r, A, A, A + 2, 0) == -4
+    # one launch takes one representation
+    d1 = vq.make_desc(4096, 4096, 16, 4, d=1)
+    d2 = vq.make_desc(4096, 4096, 16, 4)
+    descs = (vq.VQDesc * 2)(d1, d2)
+    ptrs = (ctypes.c_void_p * 2)(A, A)
+    ys = (ctypes.c_void_p * 2)(A + 16, A + 32)
+    assert L.vq_gemv_multi(2, descs, ptrs, ptrs, ptrs, ys, vq.VQ_F16, 0) == -6

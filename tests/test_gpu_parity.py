@@ -36,14 +36,19 @@ def _shape(o, i, k):
     return workloads.VQShape(o, i, k, 4 if k == 16 else 8)
 
 
+def _shape_d1(o, i):
+    return workloads.VQShape(o, i, 16, 4, 8, 256, 1)   # scalar codebooks, 4-bit indices
+
+
 # small shapes: several tiles, ragged tails (odd col-block counts, row-block counts
 # that are not a multiple of the 4 waves of a workgroup), both codebook sizes
 SMALL = [
     _shape(256, 256, 16), _shape(8, 256, 16), _shape(40, 768, 16), _shape(24, 2816, 16),
     _shape(264, 1024, 16), _shape(8, 256, 256), _shape(40, 768, 256), _shape(72, 1280, 256),
+    _shape_d1(8, 256), _shape_d1(40, 768), _shape_d1(72, 1280),
 ]
 FULL = ["attn_4096x4096_k16", "mlp_up_11008x4096_k256", "mlp_down_4096x11008_k256",
-        "mlp_up_11008x4096_k16", "mlp_down_4096x11008_k16"]
+        "mlp_up_11008x4096_k16", "mlp_down_4096x11008_k16", "mlp_down_4096x11008_d1_k16"]
 
 
 def _setup(env, s, seed):
@@ -186,7 +191,7 @@ def test_gemv_multi_matches_oracle(env, k):
 # one col-block, an odd count (pair + tail), exactly one chunk, chunk + ragged end.
 STREAM = [_shape(32776, 256, 16), _shape(32776, 768, 16), _shape(32776, 2048, 16),
           _shape(32776, 2816, 16), _shape(32776, 256, 256), _shape(32776, 768, 256),
-          _shape(33000, 1280, 256)]
+          _shape(33000, 1280, 256), _shape_d1(32776, 768), _shape_d1(33000, 1280)]
 
 
 @pytest.mark.parametrize("f32", [False, True], ids=["y16", "y32"])
@@ -239,7 +244,8 @@ def _gpu_gemm(env, desc, idx_d, cb_d, X, f32, pad=0):
 
 @pytest.mark.parametrize("f32", [False, True], ids=["y16", "y32"])
 @pytest.mark.parametrize("B", [1, 16, 40, 130, 256, 600])
-@pytest.mark.parametrize("s", [_shape(40, 768, 16), _shape(72, 512, 256), _shape(264, 1024, 256)], ids=str)
+@pytest.mark.parametrize("s", [_shape(40, 768, 16), _shape(72, 512, 256), _shape(264, 1024, 256),
+                               _shape_d1(72, 768)], ids=str)
 def test_gemm_small(env, s, B, f32):
     desc, idx, cb, idx_d, cb_d = _setup(env, s, 404)
     X = workloads.make_X(s.in_features, B, 404)
@@ -251,7 +257,7 @@ def test_gemm_small(env, s, B, f32):
 # 1025 row-blocks: tall enough for the 32-row small-batch kernel (B = 24) and the 128-column
 # kernel at B = 48 / 100; shorter matrices take the 16 x 16-tile kernel up to 64 columns
 @pytest.mark.parametrize("B", [16, 24, 48, 100])
-@pytest.mark.parametrize("s", [_shape(8200, 512, 16), _shape(8200, 768, 256)], ids=str)
+@pytest.mark.parametrize("s", [_shape(8200, 512, 16), _shape(8200, 768, 256), _shape_d1(8200, 512)], ids=str)
 def test_gemm_tall(env, s, B):
     desc, idx, cb, idx_d, cb_d = _setup(env, s, 405)
     X = workloads.make_X(s.in_features, B, 405)
@@ -510,7 +516,7 @@ def test_int8_tables_gemm_tall(env, s, B):
 # 10100 -> 64 x 256 (ragged last column tile in each; 101 row-blocks leave a ragged row tile).
 @pytest.mark.parametrize("B", [1000, 1300, 10100])
 @pytest.mark.parametrize("s", [_shape(800, 512, 16), _shape(808, 768, 256), _shape64(800, 512),
-                               _shape16i8(808, 512)], ids=str)
+                               _shape16i8(808, 512), _shape_d1(808, 512)], ids=str)
 def test_gemm_wide_batches(env, s, B):
     if s.int8_tables:
         desc, idx, cb, idx_d, cb_d = _setup_i8(env, s, 690)
@@ -561,7 +567,7 @@ def _random_cases(seed, n):
     rng = np.random.default_rng(seed)
     cases = []
     for _ in range(n):
-        kind = int(rng.integers(0, 4))
+        kind = int(rng.integers(0, 5))
         n_cb = int(rng.integers(1, 14))
         if kind == 0:
             cases.append((_shape(8 * int(rng.integers(1, 70)), 256 * n_cb, 16), False))
@@ -570,12 +576,14 @@ def _random_cases(seed, n):
         elif kind == 2:
             rows = int(rng.choice([8, 16, 32]))
             cases.append((_shape64(rows * int(rng.integers(1, 20)), 256 * n_cb, rows), True))
-        else:
+        elif kind == 3:
             cases.append((_shape16i8(8 * int(rng.integers(1, 70)), 256 * n_cb), True))
+        else:
+            cases.append((_shape_d1(8 * int(rng.integers(1, 40)), 256 * n_cb), False))
     return cases
 
 
-@pytest.mark.parametrize("case", _random_cases(20240, 24), ids=lambda c: str(c[0]))
+@pytest.mark.parametrize("case", _random_cases(20240, 30), ids=lambda c: str(c[0]))
 def test_random_shapes_every_entry_point(env, case):
     """Decode (bit-exact), GEMV (fp16 and fp32 y) and the batched product on random shapes."""
     s, is_i8 = case
