@@ -37,6 +37,9 @@ these are the readings this build fixes):
   for b=8: byte v); groups are concatenated in g order;
 * codebooks: cb[g, j, t] fp16, contiguous, same g order.
 
+The quantiser's E- and M-step (paragraph "Codebook Initialization") follow at the end of the
+file with their own header: em_assign, em_update, em_objective.
+
 Parity pins (tests/test_oracle_*.py): hand-written tiny cases stored under
 tests/golden/, a coordinate-revealing codebook, one-centroid and
 identity-like codebooks, relabelling invariance, the bpv closed form,
@@ -211,3 +214,106 @@ def normwise_rel_err(y, y_ref) -> float:
     den = float(np.linalg.norm(y_ref))
     num = float(np.linalg.norm(y - y_ref))
     return num / den if den > 0 else (0.0 if num == 0 else float("inf"))
+
+
+# ---------------------------------------------------------------------------------------------
+# Codebook initialisation (Sec. 3.2 of the method, paragraph "Codebook Initialization"): the
+# E- and M-step of the Hessian-weighted EM, for one matrix tiled into groups as above.
+#
+# Data points are the d-dimensional vectors x_i of a group (d consecutive columns of one row);
+# D = diag(1 / [H^-1]_cc) has one weight per column, shared by all rows, and D_i is the d x d
+# block of D on the columns of x_i.  `hdiag[c]` is that weight 1 / [H^-1]_cc.
+#
+#   E-step (eq. "hessian_e_step"):  a_i = argmin_m (x_i - c_m)^T D_i (x_i - c_m)
+#   M-step (closed form below eq. "hessian_m_step"):
+#          c_m = (sum_{i in I_m} D_i)^+ (sum_{i in I_m} D_i x_i)      (+ : pseudoinverse)
+#
+# With a diagonal D_i this is  sum_t h_t (x_t - c_t)^2  and a weighted mean per coordinate; the
+# pseudoinverse of a zero diagonal entry is zero, so a coordinate no vector votes for (an empty
+# cluster, or weights that are all zero) becomes 0.
+#
+# Precision: the assignment is a decision taken in floating point, so it is taken in the
+# arithmetic of the GPU path, IEEE binary32 with every operation rounded separately and in this
+# order:  e_t = x_t - c_t;  q_t = e_t * e_t;  p_t = h_t * q_t;  dist = (p_0 + p_1) + ... ;
+# the smallest distance wins and the lowest m wins a tie.  The M-step has a plain definition
+# and is evaluated in binary64.
+def em_assign(f: VQFormat, W: np.ndarray, hdiag: np.ndarray, cb: np.ndarray) -> np.ndarray:
+    """E-step: index of the weighted-nearest centroid for every vector, uint8/uint16 [out, in/d]."""
+    W = np.asarray(W)
+    hdiag = np.asarray(hdiag)
+    cb = np.asarray(cb)
+    if W.dtype != np.float32 or hdiag.dtype != np.float32 or cb.dtype != np.float32:
+        raise ValueError("the E-step is defined on binary32 inputs")
+    if W.shape != (f.out_features, f.in_features) or hdiag.shape != (f.in_features,):
+        raise ValueError("W is [out, in], hdiag is [in]")
+    if cb.shape != (f.n_groups, f.k, f.d):
+        raise ValueError("cb is [n_groups, k, d]")
+    n_rb, n_cb = f.out_features // f.group_rows, f.groups_per_row
+    out = np.zeros((f.out_features, f.in_features // f.d), dtype=np.uint16 if f.k > 256 else np.uint8)
+    vpr = f.vectors_per_row
+    for rb in range(n_rb):
+        for cbk in range(n_cb):
+            g = rb * n_cb + cbk
+            rows = slice(rb * f.group_rows, (rb + 1) * f.group_rows)
+            cols = slice(cbk * f.group_cols, (cbk + 1) * f.group_cols)
+            x = W[rows, cols].reshape(f.group_rows, vpr, f.d)               # [r, v, t]
+            h = hdiag[cols].reshape(vpr, f.d)                               # [v, t]
+            e = x[:, :, None, :] - cb[g][None, None, :, :]                  # [r, v, m, t], binary32
+            q = e * e
+            p = h[None, :, None, :] * q
+            dist = p[..., 0]
+            for t in range(1, f.d):
+                dist = dist + p[..., t]
+            assert dist.dtype == np.float32
+            out[rows, cbk * vpr:(cbk + 1) * vpr] = np.argmin(dist, axis=2)  # first minimum = lowest m
+    return out
+
+
+def em_update(f: VQFormat, W: np.ndarray, hdiag: np.ndarray, assign: np.ndarray) -> np.ndarray:
+    """M-step: float64 centroids [n_groups, k, d] from the assignments of the E-step."""
+    W = np.asarray(W, dtype=np.float64)
+    hdiag = np.asarray(hdiag, dtype=np.float64)
+    assign = np.asarray(assign)
+    if W.shape != (f.out_features, f.in_features) or hdiag.shape != (f.in_features,):
+        raise ValueError("W is [out, in], hdiag is [in]")
+    if assign.shape != (f.out_features, f.in_features // f.d):
+        raise ValueError("assign is [out, in/d]")
+    if assign.size and int(assign.max()) >= f.k:
+        raise ValueError("assignment out of range")
+    n_rb, n_cb = f.out_features // f.group_rows, f.groups_per_row
+    vpr = f.vectors_per_row
+    cb = np.zeros((f.n_groups, f.k, f.d), dtype=np.float64)
+    for rb in range(n_rb):
+        for cbk in range(n_cb):
+            g = rb * n_cb + cbk
+            rows = slice(rb * f.group_rows, (rb + 1) * f.group_rows)
+            cols = slice(cbk * f.group_cols, (cbk + 1) * f.group_cols)
+            x = W[rows, cols].reshape(f.group_rows, vpr, f.d)
+            h = np.broadcast_to(hdiag[cols].reshape(1, vpr, f.d), x.shape)
+            a = assign[rows, cbk * vpr:(cbk + 1) * vpr]
+            for m in range(f.k):
+                sel = a == m
+                den = h[sel].sum(axis=0)                                    # sum of D_i (diagonal)
+                num = (h[sel] * x[sel]).sum(axis=0)                         # sum of D_i x_i
+                nz = den != 0
+                cb[g, m, nz] = num[nz] / den[nz]                            # pseudoinverse: 0 where den = 0
+    return cb
+
+
+def em_objective(f: VQFormat, W: np.ndarray, hdiag: np.ndarray, cb: np.ndarray,
+                 assign: np.ndarray) -> float:
+    """The EM objective (eq. "kmeans_objective") in binary64: sum_i (x_i - c_{a_i})^T D_i (x_i - c_{a_i})."""
+    W = np.asarray(W, dtype=np.float64)
+    hdiag = np.asarray(hdiag, dtype=np.float64)
+    cb = np.asarray(cb, dtype=np.float64)
+    n_cb = f.groups_per_row
+    vpr = f.vectors_per_row
+    total = 0.0
+    for r in range(f.out_features):
+        for cbk in range(n_cb):
+            g = (r // f.group_rows) * n_cb + cbk
+            x = W[r, cbk * f.group_cols:(cbk + 1) * f.group_cols].reshape(vpr, f.d)
+            h = hdiag[cbk * f.group_cols:(cbk + 1) * f.group_cols].reshape(vpr, f.d)
+            c = cb[g][assign[r, cbk * vpr:(cbk + 1) * vpr].astype(np.int64)]
+            total += float((h * (x - c) ** 2).sum())
+    return total
