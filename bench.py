@@ -32,6 +32,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 # and the commands are in profiles/gemv_stream_k16_llama7b_pass.md
 TRAFFIC_BYTES_PER_LAUNCH = 1857648128
 MFMA_F16_PEAK_TFLOPS = 2500.0  # MI355X published dense fp16 matrix peak
+FP32_VECTOR_PEAK_TFLOPS = 157.3   # published fp32 vector peak (fused multiply-add = 2 flops)
 
 
 def log(*a):
@@ -379,6 +380,31 @@ def main():
                 del Wd
             del copies
         extras["per_shape_vq_gemv"] = per_shape
+
+        # quantiser side: one E-step and one M-step of the Hessian-weighted EM on a 11008 x 4096
+        # layer in fp32 (22,016 groups of 8 x 256, d = 2).  The E-step is plain vector ALU work:
+        # 7 unfused fp32 operations per (vector, centroid); the chip's 157.3 TFLOP/s counts a
+        # fused multiply-add as two, so separately rounded operations peak at half of it.
+        em = {}
+        Wq = (torch.randn((11008, 4096), device=dev) * 0.02).contiguous()
+        hq = (torch.rand(4096, device=dev) * 4.8 + 0.2).contiguous()
+        for kq in (16, 256):
+            dq = vq.make_desc(11008, 4096, kq, 4 if kq == 16 else 8)
+            n_groups = (11008 // 8) * (4096 // 256)
+            cq = (torch.randn((n_groups, kq, 2), device=dev) * 0.02).contiguous()
+            aq = torch.empty((11008, 2048), dtype=torch.uint8, device=dev)
+            cq2 = torch.empty_like(cq)
+            ms_e, _ = timer.run(lambda: vq.vq_em_assign(dq, Wq, hq, cq, aq), 20, 5)
+            ms_m, _ = timer.run(lambda: vq.vq_em_update(dq, Wq, hq, aq, cq2), 20, 5)
+            fl = 7.0 * 11008 * 2048 * kq
+            em[f"k{kq}"] = {"e_step_us": ms_e * 1e3, "m_step_us": ms_m * 1e3,
+                            "e_step_TFLOP/s": fl / ms_e / 1e9,
+                            "e_step_frac_of_unfused_fp32_peak": fl / ms_e / 1e9 / (FP32_VECTOR_PEAK_TFLOPS / 2),
+                            "e_step_bytes": Wq.numel() * 4 + aq.numel() + cq.numel() * 4,
+                            "m_step_GB/s": (Wq.numel() * 4 + aq.numel() + cq.numel() * 4) / ms_m / 1e6}
+            log(f"[bench] EM k={kq}: E-step {ms_e * 1e3:.1f} us, M-step {ms_m * 1e3:.1f} us")
+        extras["em_step_11008x4096_fp32"] = em
+        del Wq, hq
 
     cpu = None if args.no_cpu else time_cpu_baseline(args.cpu_budget)
 

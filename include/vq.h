@@ -155,6 +155,33 @@ VQ_API int vq_decode_dense(const vq_desc* desc, const void* idx_dev, const void*
                     void* W_f16, void* stream);
 
 /*
+ * Quantiser side (offline; paragraph "Codebook Initialization"): the two steps of the
+ * Hessian-weighted EM that initialises the codebook of every group, for d = 2, 8 x 256 groups
+ * and k = 16, 64 or 256 (desc->codebook_dtype is ignored: weights and codebooks are fp32 here).
+ *
+ *   W_f32      fp32 W[out, in], row-major, contiguous
+ *   hdiag_f32  fp32 h[in], h[c] = 1 / [H^-1]_cc: the diagonal D of eq. "kmeans_objective"; the
+ *              vector on columns c, c+1 uses D_i = diag(h[c], h[c+1])
+ *   cb_f32     fp32 cb[g][m][t] in the canonical group order
+ *   assign_u8  one byte per vector, assign[r][c/2], row-major (out x in/2 bytes)
+ *
+ * vq_em_assign (E-step, eq. "hessian_e_step"; also the VQ_quant operation of Algorithm 2):
+ *   assign[r][v] = argmin_m  h[c]*(W[r][c] - cb[g][m][0])^2 + h[c+1]*(W[r][c+1] - cb[g][m][1])^2,
+ *   c = 2v, evaluated in binary32 with every operation rounded separately in the order
+ *   subtract, square, times weight, add; the lowest m wins a tie.
+ * vq_em_update (M-step, closed form below eq. "hessian_m_step"):
+ *   cb_out[g][m][t] = sum h[c+t]*W[r][c+t] / sum h[c+t] over the vectors of group g with
+ *   assign = m, and 0 where that sum of weights is 0 (the pseudoinverse of the text: an empty
+ *   cluster becomes the zero vector).  binary32 sums in a fixed order: deterministic.
+ *   Assignment bytes >= k are ignored.
+ * All pointers are device memory, 16-byte aligned; cb_out must not alias the inputs.
+ */
+VQ_API int vq_em_assign(const vq_desc* desc, const void* W_f32, const void* hdiag_f32,
+                        const void* cb_f32, void* assign_u8, void* stream);
+VQ_API int vq_em_update(const vq_desc* desc, const void* W_f32, const void* hdiag_f32,
+                        const void* assign_u8, void* cb_f32_out, void* stream);
+
+/*
  * Measurement aid, not part of the method: reads `bytes` bytes (a multiple of 16)
  * of device memory once with the same non-temporal 128-bit loads the GEMV kernels
  * stream their indices with, and discards them.  Timing it over a buffer much

@@ -14,7 +14,7 @@ from typing import Sequence
 __all__ = [
     "VQDesc", "VQError", "VQ_F16", "VQ_F32", "VQ_I8", "lib", "lib_path", "make_desc",
     "vq_status_string", "vq_version", "vq_canonical_bytes", "vq_layout_bytes",
-    "vq_pack_layout", "vq_gemv", "vq_gemv_multi", "GemvMultiArgs", "vq_stream_read_probe", "vq_gemm_batched", "vq_decode_dense",
+    "vq_pack_layout", "vq_gemv", "vq_gemv_multi", "GemvMultiArgs", "vq_stream_read_probe", "vq_gemm_batched", "vq_decode_dense", "vq_em_assign", "vq_em_update",
 ]
 
 VQ_F16 = 1
@@ -77,6 +77,10 @@ def lib() -> ctypes.CDLL:
         L.vq_stream_read_probe.argtypes = [vp, ctypes.c_size_t, vp]
         L.vq_decode_dense.restype = i32
         L.vq_decode_dense.argtypes = [dp, vp, vp, vp, vp]
+        L.vq_em_assign.restype = i32
+        L.vq_em_assign.argtypes = [dp, vp, vp, vp, vp, vp]
+        L.vq_em_update.restype = i32
+        L.vq_em_update.argtypes = [dp, vp, vp, vp, vp, vp]
         _lib = L
     return _lib
 
@@ -176,6 +180,16 @@ def vq_gemm_batched(desc: VQDesc, idx_dev, cb_dev, X, B: int, ldx: int, Y, ldy: 
 def vq_decode_dense(desc: VQDesc, idx_dev, cb_dev, W, stream=None) -> None:
     _check(lib().vq_decode_dense(ctypes.byref(desc), _ptr(idx_dev), _ptr(cb_dev), _ptr(W),
                                  _stream(stream)), "vq_decode_dense")
+
+
+def vq_em_assign(desc: VQDesc, W_f32, hdiag_f32, cb_f32, assign_u8, stream=None) -> None:
+    _check(lib().vq_em_assign(ctypes.byref(desc), _ptr(W_f32), _ptr(hdiag_f32), _ptr(cb_f32),
+                              _ptr(assign_u8), _stream(stream)), "vq_em_assign")
+
+
+def vq_em_update(desc: VQDesc, W_f32, hdiag_f32, assign_u8, cb_f32_out, stream=None) -> None:
+    _check(lib().vq_em_update(ctypes.byref(desc), _ptr(W_f32), _ptr(hdiag_f32), _ptr(assign_u8),
+                              _ptr(cb_f32_out), _stream(stream)), "vq_em_update")
 
 
 def vq_stream_read_probe(buf, nbytes: int, stream=None) -> None:

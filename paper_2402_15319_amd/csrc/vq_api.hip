@@ -69,6 +69,20 @@ int strip_units(int fmt, int n_cb) {
 
 int hip_status(hipError_t e) { return e == hipSuccess ? VQ_OK : VQ_ERR_HIP; }
 
+// The quantiser kernels work on fp32 weights and codebooks; codebook_dtype plays no part.
+int check_em_desc(const vq_desc* d) {
+  if (!d) return VQ_ERR_NULL;
+  if (d->out_features <= 0 || d->in_features <= 0 || d->group_rows <= 0 || d->group_cols <= 0 ||
+      d->d <= 0 || d->k <= 0 || d->index_bits <= 0 || d->index_bits > 16)
+    return VQ_ERR_BAD_DESC;
+  if (!is_pow2(d->k) || d->k != (1 << d->index_bits)) return VQ_ERR_BAD_DESC;
+  if (d->d != 2 || d->group_rows != kGroupRows || d->group_cols != kGroupCols) return VQ_ERR_UNSUPPORTED;
+  if (d->k != 16 && d->k != 64 && d->k != 256) return VQ_ERR_UNSUPPORTED;
+  if (d->out_features % kGroupRows || d->in_features % kGroupCols) return VQ_ERR_UNSUPPORTED;
+  if ((long long)d->out_features * d->in_features > (1ll << 40)) return VQ_ERR_UNSUPPORTED;
+  return VQ_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -256,6 +270,28 @@ int vq_decode_dense(const vq_desc* desc, const void* idx_dev, const void* cb_dev
   if (!idx_dev || !cb_dev || !W_f16) return VQ_ERR_NULL;
   if (!aligned16(idx_dev) || !aligned16(cb_dev) || !aligned16(W_f16)) return VQ_ERR_ALIGN;
   return hip_status(launch_decode(*desc, idx_dev, cb_dev, W_f16, (hipStream_t)stream));
+}
+
+int vq_em_assign(const vq_desc* desc, const void* W_f32, const void* hdiag_f32, const void* cb_f32,
+                 void* assign_u8, void* stream) {
+  const int st = check_em_desc(desc);
+  if (st != VQ_OK) return st;
+  if (!W_f32 || !hdiag_f32 || !cb_f32 || !assign_u8) return VQ_ERR_NULL;
+  if (!aligned16(W_f32) || !aligned16(hdiag_f32) || !aligned16(cb_f32) || !aligned16(assign_u8))
+    return VQ_ERR_ALIGN;
+  return hip_status(launch_em_assign(desc->k, desc->out_features, desc->in_features, W_f32, hdiag_f32,
+                                     cb_f32, assign_u8, (hipStream_t)stream));
+}
+
+int vq_em_update(const vq_desc* desc, const void* W_f32, const void* hdiag_f32, const void* assign_u8,
+                 void* cb_f32_out, void* stream) {
+  const int st = check_em_desc(desc);
+  if (st != VQ_OK) return st;
+  if (!W_f32 || !hdiag_f32 || !assign_u8 || !cb_f32_out) return VQ_ERR_NULL;
+  if (!aligned16(W_f32) || !aligned16(hdiag_f32) || !aligned16(assign_u8) || !aligned16(cb_f32_out))
+    return VQ_ERR_ALIGN;
+  return hip_status(launch_em_update(desc->k, desc->out_features, desc->in_features, W_f32, hdiag_f32,
+                                     assign_u8, cb_f32_out, (hipStream_t)stream));
 }
 
 int vq_stream_read_probe(const void* buf, size_t bytes, void* stream) {

@@ -1,0 +1,175 @@
+// Quantiser side: the E- and M-step of the Hessian-weighted EM that initialises a group's
+// codebook (paragraph "Codebook Initialization": eq. "hessian_e_step" and the closed form
+// below eq. "hessian_m_step"); the E-step is also the VQ_quant operation of Algorithm 2.
+//
+//   E-step:  a_i = argmin_m  sum_t h[c+t] * (x_i[t] - c_m[t])^2
+//   M-step:  c_m[t] = sum_{i in I_m} h[c_i+t] * x_i[t] / sum_{i in I_m} h[c_i+t]   (0 if the sum of weights is 0)
+//
+// with x_i = W[r, c .. c+d-1] and h[c] = 1 / [H^-1]_cc, the diagonal weight of column c.
+// d = 2, groups of 8 x 256 weights.  One wave per group, lane L owns columns 4L .. 4L+3 (two
+// vectors) of the group's 8 rows, exactly as in the matrix-vector kernels.
+//
+// The E-step is a decision taken in floating point, so its arithmetic is fixed: binary32,
+// every operation rounded on its own (no fused multiply-add), in the order subtract, square,
+// times weight, add; the smallest distance wins, the lowest m wins a tie.  The M-step sums in
+// binary32 in a fixed order (a lane's 16 vectors one after the other, then lanes 0..63), so it is
+// deterministic.
+#include "vq_device.h"
+#include "vq_internal.h"
+
+namespace vq {
+namespace {
+
+template <int K>
+__global__ __launch_bounds__(256) void em_assign_kernel(const float* __restrict__ W,
+                                                        const float* __restrict__ hdiag,
+                                                        const float* __restrict__ cb,
+                                                        uint8_t* __restrict__ assign, int n_cb,
+                                                        long long n_groups, int in_features) {
+#pragma clang fp contract(off)
+  __shared__ __attribute__((aligned(16))) float2 cbs_all[4][K];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  float2* cbs = cbs_all[wave];
+  const long long g = (long long)blockIdx.x * 4 + wave;
+  if (g >= n_groups) return;   // whole waves leave; no workgroup barrier below
+  const long long rb = g / n_cb;
+  const int c = (int)(g - rb * n_cb);
+
+  const float2* cg = reinterpret_cast<const float2*>(cb) + g * K;
+#pragma unroll
+  for (int i = 0; i < (K + 63) / 64; ++i)
+    if (i * 64 + lane < K) cbs[i * 64 + lane] = cg[i * 64 + lane];
+  const float4 h = *reinterpret_cast<const float4*>(hdiag + (size_t)c * 256 + lane * 4);
+  float4 x[8];
+#pragma unroll
+  for (int r = 0; r < 8; ++r)
+    x[r] = *reinterpret_cast<const float4*>(W + (size_t)(rb * 8 + r) * in_features + (size_t)c * 256 + lane * 4);
+  wave_lds_sync();
+
+  float best[16];
+  uint32_t arg[16];
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    best[v] = __builtin_inff();
+    arg[v] = 0;
+  }
+  for (int m = 0; m < K; ++m) {
+    const float2 cm = cbs[m];   // the same address in every lane: one broadcast read
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+      const float ea0 = x[r].x - cm.x, ea1 = x[r].y - cm.y;
+      const float eb0 = x[r].z - cm.x, eb1 = x[r].w - cm.y;
+      const float da = h.x * (ea0 * ea0) + h.y * (ea1 * ea1);
+      const float db = h.z * (eb0 * eb0) + h.w * (eb1 * eb1);
+      if (da < best[2 * r]) { best[2 * r] = da; arg[2 * r] = m; }
+      if (db < best[2 * r + 1]) { best[2 * r + 1] = db; arg[2 * r + 1] = m; }
+    }
+  }
+#pragma unroll
+  for (int r = 0; r < 8; ++r)
+    *reinterpret_cast<uint16_t*>(assign + (size_t)(rb * 8 + r) * (in_features / 2) + (size_t)c * 128 + lane * 2) =
+        (uint16_t)(arg[2 * r] | (arg[2 * r + 1] << 8));
+}
+
+constexpr int kRedStride = 68;   // floats per lane row of the reduction buffer: 16-byte aligned, conflict-free
+
+template <int K>
+__global__ __launch_bounds__(128) void em_update_kernel(const float* __restrict__ W,
+                                                        const float* __restrict__ hdiag,
+                                                        const uint8_t* __restrict__ assign,
+                                                        float* __restrict__ cb_out, int n_cb,
+                                                        long long n_groups, int in_features) {
+  __shared__ __attribute__((aligned(16))) float red_all[2][64 * kRedStride];
+  __shared__ float tot_all[2][64];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  float* red = red_all[wave];
+  float* tot = tot_all[wave];
+  const long long g = (long long)blockIdx.x * 2 + wave;
+  if (g >= n_groups) return;   // whole waves leave; no workgroup barrier below
+  const long long rb = g / n_cb;
+  const int c = (int)(g - rb * n_cb);
+
+  const float4 h = *reinterpret_cast<const float4*>(hdiag + (size_t)c * 256 + lane * 4);
+  float4 hx[8];
+  uint32_t aa[8], ab[8];
+#pragma unroll
+  for (int r = 0; r < 8; ++r) {
+    const float4 x = *reinterpret_cast<const float4*>(W + (size_t)(rb * 8 + r) * in_features + (size_t)c * 256 + lane * 4);
+    hx[r] = make_float4(h.x * x.x, h.y * x.y, h.z * x.z, h.w * x.w);
+    const uint32_t a2 = *reinterpret_cast<const uint16_t*>(assign + (size_t)(rb * 8 + r) * (in_features / 2) +
+                                                           (size_t)c * 128 + lane * 2);
+    aa[r] = a2 & 0xffu;
+    ab[r] = a2 >> 8;
+  }
+
+  float4* row = reinterpret_cast<float4*>(red + lane * kRedStride);   // this lane's 16 x 4 partial sums
+  for (int m0 = 0; m0 < K; m0 += 16) {
+    // this lane's part of (numerator t=0, numerator t=1, weight t=0, weight t=1) of 16
+    // centroids: its 16 vectors are added one after the other (rows 0..7, the vector on
+    // columns 4L, 4L+1 before the one on 4L+2, 4L+3) into the slot their assignment selects
+#pragma unroll
+    for (int j = 0; j < 16; ++j) row[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+      const uint32_t ja = aa[r] - m0, jb = ab[r] - m0;
+      if (ja < 16u) {   // also keeps an out-of-range assignment byte out of the table
+        float4 t = row[ja];
+        t.x += hx[r].x; t.y += hx[r].y; t.z += h.x; t.w += h.y;
+        row[ja] = t;
+      }
+      if (jb < 16u) {
+        float4 t = row[jb];
+        t.x += hx[r].z; t.y += hx[r].w; t.z += h.z; t.w += h.w;
+        row[jb] = t;
+      }
+    }
+    wave_lds_sync();
+    // lane j owns quantity j of the 64: sum over the 64 lanes in lane order
+    float s = 0.f;
+    for (int l = 0; l < 64; ++l) s += red[l * kRedStride + lane];
+    tot[lane] = s;
+    wave_lds_sync();
+    if (lane < 32) {
+      const int j = lane >> 1, t = lane & 1;
+      const float num = tot[4 * j + t], den = tot[4 * j + 2 + t];
+      cb_out[(g * K + m0 + j) * 2 + t] = den != 0.f ? num / den : 0.f;
+    }
+    wave_lds_sync();   // tot and red are rewritten by the next 16 centroids
+  }
+}
+
+}  // namespace
+
+hipError_t launch_em_assign(int k, int out_features, int in_features, const void* W, const void* hdiag,
+                            const void* cb, void* assign, hipStream_t s) {
+  const int n_cb = in_features / kGroupCols;
+  const long long n_groups = (long long)(out_features / kGroupRows) * n_cb;
+  const unsigned grid = (unsigned)((n_groups + 3) / 4);
+#define VQ_EM(K)                                                                                   \
+  hipLaunchKernelGGL(em_assign_kernel<K>, dim3(grid), dim3(256), 0, s, (const float*)W,            \
+                     (const float*)hdiag, (const float*)cb, (uint8_t*)assign, n_cb, n_groups, in_features)
+  if (k == 16) VQ_EM(16);
+  else if (k == 64) VQ_EM(64);
+  else VQ_EM(256);
+#undef VQ_EM
+  return hipGetLastError();
+}
+
+hipError_t launch_em_update(int k, int out_features, int in_features, const void* W, const void* hdiag,
+                            const void* assign, void* cb_out, hipStream_t s) {
+  const int n_cb = in_features / kGroupCols;
+  const long long n_groups = (long long)(out_features / kGroupRows) * n_cb;
+  const unsigned grid = (unsigned)((n_groups + 1) / 2);
+#define VQ_EM(K)                                                                                   \
+  hipLaunchKernelGGL(em_update_kernel<K>, dim3(grid), dim3(128), 0, s, (const float*)W,            \
+                     (const float*)hdiag, (const uint8_t*)assign, (float*)cb_out, n_cb, n_groups, in_features)
+  if (k == 16) VQ_EM(16);
+  else if (k == 64) VQ_EM(64);
+  else VQ_EM(256);
+#undef VQ_EM
+  return hipGetLastError();
+}
+
+}  // namespace vq

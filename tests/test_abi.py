@@ -183,3 +183,18 @@ def test_scalar_codebook_representation_sizes_and_entry_points():
     ptrs = (ctypes.c_void_p * 2)(A, A)
     ys = (ctypes.c_void_p * 2)(A + 16, A + 32)
     assert L.vq_gemv_multi(2, descs, ptrs, ptrs, ptrs, ys, vq.VQ_F16, 0) == -6
+
+
+def test_quantiser_entry_points_validate_before_launch():
+    L = vq.lib()
+    d = vq.make_desc(4096, 4096, 16, 4)
+    r = ctypes.byref(d)
+    assert L.vq_em_assign(r, A, A, A, 0, 0) == -1
+    assert L.vq_em_assign(r, A, A + 4, A, A, 0) == -4
+    assert L.vq_em_update(r, A, A, 0, A, 0) == -1
+    assert L.vq_em_update(r, A + 8, A, A, A, 0) == -4
+    for bad in (vq.make_desc(4096, 4096, 16, 4, d=1), vq.make_desc(4096, 4096, 64, 6, group_rows=32),
+                vq.make_desc(4096, 4096, 4, 2), vq.make_desc(4100, 4096, 16, 4)):
+        assert L.vq_em_assign(ctypes.byref(bad), A, A, A, A, 0) == -3
+        assert L.vq_em_update(ctypes.byref(bad), A, A, A, A, 0) == -3
+    assert L.vq_em_assign(ctypes.byref(vq.make_desc(4096, 4096, 32, 4)), A, A, A, A, 0) == -2

@@ -90,3 +90,27 @@ def test_no_instruction_reads_a_dot2c_result_early(tmp_path):
     assert sum("v_dot2c_f32_f16" in l for l in lines) > 100     # the kernels are in there
     bad = scan(lines)
     assert bad == [], bad[:10]
+
+
+@pytest.mark.skipif(shutil.which(os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")) is None,
+                    reason="hipcc not available")
+def test_e_step_kernel_has_no_fused_multiply_add(tmp_path):
+    """The E-step's distance is defined with every operation rounded on its own (the CPU
+    oracle takes the same decision with the same roundings); a contraction into a fused
+    multiply-add would change near-ties.  Checks the generated code of the assign kernels."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    out = tmp_path / "vq_em.s"
+    flags = [f for f in vqbuild.HIPCC_FLAGS if f != "-fPIC"]
+    cmd = [hipcc, *flags, "-S", "--cuda-device-only", "-o", str(out), os.path.join(vqbuild.CSRC, "vq_em.hip")]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    assert res.returncode == 0, res.stderr[-2000:]
+    inside, seen, fused = False, 0, []
+    for line in out.read_text().splitlines():
+        if re.match(r"^_ZN.*em_assign_kernel.*:", line):
+            inside, seen = True, seen + 1
+        elif inside and "s_endpgm" in line:
+            inside = False
+        elif inside and re.match(r"\s+v_(fma|fmac|mac|mad|pk_fma|pk_mul|pk_add)_f32", line):
+            fused.append(line.strip())
+    assert seen == 3                      # k = 16, 64, 256
+    assert fused == []
