@@ -38,7 +38,8 @@ these are the readings this build fixes):
 * codebooks: cb[g, j, t] fp16, contiguous, same g order.
 
 The quantiser's E- and M-step (paragraph "Codebook Initialization") follow at the end of the
-file with their own header: em_assign, em_update, em_objective.
+file with their own header: em_assign, em_update, em_objective; then the blockwise
+normalisation of the appendix: apply_block_scales, canonical_sizes_bn.
 
 Parity pins (tests/test_oracle_*.py): hand-written tiny cases stored under
 tests/golden/, a coordinate-revealing codebook, one-centroid and
@@ -317,3 +318,53 @@ def em_objective(f: VQFormat, W: np.ndarray, hdiag: np.ndarray, cb: np.ndarray,
             c = cb[g][assign[r, cbk * vpr:(cbk + 1) * vpr].astype(np.int64)]
             total += float((h * (x - c) ** 2).sum())
     return total
+
+
+# ---------------------------------------------------------------------------------------------
+# Blockwise data normalisation (appendix "Blockwise data normalization"): every sub-row of
+# `block` consecutive weights inside a group has a 4-bit code, the code selects one of the
+# group's 16 block scales (the appendix quantises the scales in the log domain, level j being
+# 2^(a*j + s_0) with a shared by the group; here the 16 levels themselves are stored, as fp16,
+# which contains that parameterisation and keeps the reconstruction exact to state), and "the
+# inverse scaling is applied at VQ decoding": the decoded weight is the centroid value times its
+# block's scale.  On this path the native type is fp16: the product of the two fp16 values is
+# taken exactly and rounded once to fp16 (nearest even).
+def apply_block_scales(f: VQFormat, W_bits: np.ndarray, levels: np.ndarray, codes: np.ndarray,
+                       block: int = 32) -> np.ndarray:
+    """Dense W (raw fp16 bits, uint16[out, in]) -> W with the block scales applied (same form).
+
+    levels: fp16[n_groups, 16]; codes: uint8[out, in / block], one 4-bit code per sub-row block
+    (values 0..15), row-major like W.  The group of element (r, c) is the usual
+    g = (r // group_rows) * (in // group_cols) + c // group_cols.
+    """
+    levels = np.asarray(levels)
+    codes = np.asarray(codes)
+    if levels.dtype != np.float16 or levels.shape != (f.n_groups, 16):
+        raise ValueError("levels is fp16 [n_groups, 16]")
+    if f.group_cols % block or codes.shape != (f.out_features, f.in_features // block):
+        raise ValueError("codes is [out, in / block] and blocks must tile a group's columns")
+    if codes.size and int(codes.max()) > 15:
+        raise ValueError("block codes are 4-bit")
+    W = np.ascontiguousarray(W_bits).view(np.float16).reshape(f.out_features, f.in_features)
+    rows = np.arange(f.out_features)[:, None]
+    blk = np.arange(f.in_features // block)[None, :]
+    g = (rows // f.group_rows) * f.groups_per_row + (blk * block) // f.group_cols    # [out, in/block]
+    S = levels[g, codes.astype(np.int64)]                                            # fp16 [out, in/block]
+    S_full = np.repeat(S, block, axis=1)
+    # fp16 x fp16 is exact in binary32 (22 significant bits); the cast rounds once
+    with np.errstate(over="ignore", invalid="ignore"):     # products beyond fp16 become inf, as on the device
+        out = (W.astype(np.float32) * S_full.astype(np.float32)).astype(np.float16)
+    return np.ascontiguousarray(out).view(np.uint16)
+
+
+def canonical_sizes_bn(f: VQFormat, block: int = 32) -> tuple[int, int]:
+    """(index bytes, table bytes) with int8 tables, a scale per group and blockwise normalisation.
+
+    Table buffer: q[n_groups, k, d] int8 padded to 16 bytes; scale[n_groups] fp16 padded to 16
+    bytes; levels[n_groups, 16] fp16; then the 4-bit block codes of the whole matrix, row-major
+    [out, in / block], two per byte (even block in the low nibble).
+    """
+    q_bytes = (f.n_groups * f.k * f.d + 15) // 16 * 16
+    s_bytes = (2 * f.n_groups + 15) // 16 * 16
+    code_bytes = f.out_features * (f.in_features // block) // 2
+    return f.n_groups * f.group_index_bytes, q_bytes + s_bytes + 32 * f.n_groups + code_bytes

@@ -416,3 +416,73 @@ def test_scalar_format_sizes_follow_the_bpv_formula():
     assert (ib + cbb) * 8 / (s.out_features * s.in_features) == 4.125
     f = VQFormat(s.out_features, s.in_features, s.k, s.index_bits, s.group_rows, s.group_cols, s.d)
     assert oracle.canonical_sizes(f) == (ib, cbb)
+
+
+# ---------------------------------------------------------------- blockwise normalisation
+def test_block_scales_hand_worked_products_and_roundings():
+    """Appendix "Blockwise data normalization": decoded weight = centroid value x the scale of
+    its sub-row block, here fp16 x fp16 rounded once to fp16.  One group of 2 x 8, blocks of 4.
+    Row 0: block 0 uses level 3 (= 2), block 1 level 0 (= 1/3 as fp16 = 1365/4096).
+    Row 1: block 0 uses level 15 (= 1 + 2^-10), block 1 level 3 (= 2).
+      3 x 1365/4096 = 4095/4096 needs 12 bits: a tie between 2047/2048 and 1 -> even -> 1.0
+      (1 + 2^-10)^2 = 1 + 2^-9 + 2^-20 -> 1 + 2^-9;  -0.5 x 2 = -1;  0.1(fp16) x 2 = 2 x 0.1(fp16)."""
+    f = VQFormat(2, 8, 4, 2, 2, 8, 2)
+    tenth = float(np.float16(0.1))
+    W = np.array([[1, -0.5, tenth, 4, 3, 3, -3, 0.75],
+                  [1 + 2.0 ** -10, 1, -1, 2, 5, -0.5, tenth, 0]], dtype=np.float16)
+    levels = np.ones((1, 16), dtype=np.float16)
+    levels[0, 0] = np.float16(1 / 3)
+    levels[0, 3] = 2
+    levels[0, 15] = 1 + 2.0 ** -10
+    codes = np.array([[3, 0], [15, 3]], dtype=np.uint8)
+    third = 1365 / 4096
+    assert float(levels[0, 0]) == third
+    # 0.75 x 1365/4096 = 4095/16384: 4095 needs 12 bits, again a tie, to even: 4096/16384 = 0.25
+    assert 0.75 * third == 4095 / 16384
+    want = np.array([[2, -1, 2 * tenth, 8, 1.0, 1.0, -1.0, 0.25],
+                     [1 + 2.0 ** -9, 1 + 2.0 ** -10, -(1 + 2.0 ** -10), 2 * (1 + 2.0 ** -10), 10, -1, 2 * tenth, 0]])
+    got = oracle.apply_block_scales(f, W.view(np.uint16), levels, codes, block=4).view(np.float16).astype(np.float64)
+    np.testing.assert_array_equal(got, want)
+
+
+def test_block_scales_unit_levels_keep_every_bit_and_powers_of_two_are_exact():
+    rng = np.random.default_rng(51)
+    f = VQFormat(16, 512, 64, 6, 8, 256, 2)
+    bits = rng.integers(0, 1 << 16, size=(16, 512), dtype=np.uint16)
+    bits[(bits & 0x7C00) == 0x7C00] = 0x3C00            # no inf / NaN here
+    codes = rng.integers(0, 16, size=(16, 16), dtype=np.uint8)
+    ones = np.ones((f.n_groups, 16), dtype=np.float16)
+    np.testing.assert_array_equal(oracle.apply_block_scales(f, bits, ones, codes), bits)   # subnormals, -0 included
+    pw = np.tile(np.exp2(np.arange(-4, 12) // 2).astype(np.float16), (f.n_groups, 1))      # 2^-2 .. 2^5
+    got = oracle.apply_block_scales(f, bits, pw, codes).view(np.float16).astype(np.float64)
+    e = (np.arange(-4, 12) // 2)[codes.astype(np.int64)]
+    want = np.ldexp(bits.view(np.float16).astype(np.float64), np.repeat(e, 32, axis=1))
+    ok = (np.abs(want) < 65504) & ((np.abs(want) >= 2.0 ** -14) | (want == 0))             # stays a normal fp16
+    np.testing.assert_array_equal(got[ok], want[ok])
+    assert ok.mean() > 0.9
+
+
+def test_block_scales_pick_the_level_of_the_right_group_and_block():
+    """W = 1 everywhere and level (g, j) = 32*g + j + 1 (exact in fp16): every output element
+    names its group and its block's code; expected values recomputed with divmod."""
+    f = VQFormat(64, 768, 64, 6, 32, 256, 2)
+    rng = np.random.default_rng(52)
+    codes = rng.integers(0, 16, size=(64, 24), dtype=np.uint8)
+    levels = (32 * np.arange(f.n_groups)[:, None] + np.arange(16)[None, :] + 1).astype(np.float16)
+    W = np.ones((64, 768), dtype=np.float16)
+    got = oracle.apply_block_scales(f, W.view(np.uint16), levels, codes).view(np.float16)
+    for (r, c) in [(0, 0), (0, 31), (0, 32), (31, 255), (32, 0), (33, 256), (63, 767), (40, 500)]:
+        g = (r // 32) * 3 + c // 256
+        assert got[r, c] == 32 * g + int(codes[r, c // 32]) + 1
+    with pytest.raises(ValueError):
+        oracle.apply_block_scales(f, W.view(np.uint16), levels, codes, block=48)   # 48 does not tile 256 columns
+
+
+def test_block_normalised_format_sizes():
+    """32 x 256 groups, k = 64, 6-bit: 3 + (64*2*8 + 16 + 16*16)/8192 + 4/32 = 3.283 bits per value
+    (index, int8 table, scale, 16 levels, one 4-bit code per 32 weights)."""
+    f = VQFormat(4096, 4096, 64, 6, 32, 256, 2)
+    ib, tb = oracle.canonical_sizes_bn(f)
+    assert ib == oracle.canonical_sizes_i8(f)[0]
+    assert tb == f.n_groups * 128 + f.n_groups * 2 + f.n_groups * 32 + 4096 * 128 // 2
+    assert (ib + tb) * 8 / (4096 * 4096) == 3 + (1024 + 16 + 256) / 8192 + 4 / 32
