@@ -33,6 +33,14 @@
  *     zero-padded to a multiple of 16 bytes, followed by one fp16 scale[g] per group.  The
  *     centroid value is scale[g] * q taken exactly and rounded once to fp16 (nearest even);
  *     that fp16 matrix is W for every entry point.
+ *   - codebooks (VQ_I8_BN; appendix "Blockwise data normalization": every sub-row block of 32
+ *     weights was divided by a scale that is quantised to 4 bits in the log domain, and "the
+ *     inverse scaling is applied at VQ decoding"): q and scale as for VQ_I8, each padded to a
+ *     multiple of 16 bytes, then fp16 level[g][16], the 16 block scales a code can select in
+ *     group g (level j = 2^(a_g*j + s_0) in the appendix's parameterisation; stored explicitly
+ *     so that the reconstruction is exact to state), then the 4-bit codes of the whole matrix,
+ *     row-major code[r][c/32], two per byte, even block in the low nibble.  The decoded weight
+ *     is fp16(scale*q) times level[g][code], the product of the two fp16 values rounded once.
  * The device layout written by vq_pack_layout is private to the library.
  *
  * Implemented representations (d = 2 unless stated): VQ_F16 with 8 x 256 groups and k = 16
@@ -40,7 +48,8 @@
  * (32 rows: the 8,192-weight groups and 3.125 bits per value of Sec. 5.1); VQ_I8 with k = 16
  * and 8 x 256 groups (2.125 bits per value); and scalar codebooks, d = 1 (the 1D rows of the
  * appendix table of VQ configurations): VQ_F16, k = 16, 4-bit indices, 8 x 256 groups, 4.125
- * bits per value.  Every entry point takes all of them.
+ * bits per value; VQ_I8_BN with k = 64 and groups of 8, 16 or 32 rows x 256 columns.  Every
+ * entry point takes all of them.
  */
 #ifndef VQ_H_
 #define VQ_H_
@@ -66,8 +75,9 @@ typedef enum vq_status {
   VQ_ERR_BAD_ARG = -6      /* a scalar argument is out of range (batch, count, dtype)     */
 } vq_status;
 
-/* VQ_I8 as codebook_dtype: int8 lookup tables with one fp16 scale per group (Sec. 3.1). */
-typedef enum vq_dtype { VQ_F16 = 1, VQ_F32 = 2, VQ_I8 = 3 } vq_dtype;
+/* VQ_I8 as codebook_dtype: int8 lookup tables with one fp16 scale per group (Sec. 3.1);
+ * VQ_I8_BN: the same plus blockwise normalisation (see the canonical format above). */
+typedef enum vq_dtype { VQ_F16 = 1, VQ_F32 = 2, VQ_I8 = 3, VQ_I8_BN = 4 } vq_dtype;
 
 /* Shape of one vector-quantised matrix (Sec. 2.1, Sec. 3.1, Sec. 4). */
 typedef struct vq_desc {
@@ -78,7 +88,7 @@ typedef struct vq_desc {
   int32_t d;              /* VQ dimensionality: 2, or 1 (scalar codebooks)          */
   int32_t k;              /* centroids: 16 or 256 (VQ_F16), 64 or 16 (VQ_I8)        */
   int32_t index_bits;     /* log2(k): 4, 8 or 6                                     */
-  int32_t codebook_dtype; /* VQ_F16 or VQ_I8                                        */
+  int32_t codebook_dtype; /* VQ_F16, VQ_I8 or VQ_I8_BN                              */
 } vq_desc;
 
 /* Human-readable name of a status code (host pointer to a static string). */

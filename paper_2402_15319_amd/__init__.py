@@ -12,14 +12,15 @@ import os
 from typing import Sequence
 
 __all__ = [
-    "VQDesc", "VQError", "VQ_F16", "VQ_F32", "VQ_I8", "lib", "lib_path", "make_desc",
+    "VQDesc", "VQError", "VQ_F16", "VQ_F32", "VQ_I8", "VQ_I8_BN", "lib", "lib_path", "make_desc",
     "vq_status_string", "vq_version", "vq_canonical_bytes", "vq_layout_bytes",
     "vq_pack_layout", "vq_gemv", "vq_gemv_multi", "GemvMultiArgs", "vq_stream_read_probe", "vq_gemm_batched", "vq_decode_dense", "vq_em_assign", "vq_em_update",
 ]
 
 VQ_F16 = 1
 VQ_F32 = 2
-VQ_I8 = 3     # codebook_dtype: int8 lookup tables with one fp16 scale per group
+VQ_I8 = 3
+VQ_I8_BN = 4   # int8 tables + scale + blockwise normalisation (16 levels per group, 4-bit code per 32 weights)     # codebook_dtype: int8 lookup tables with one fp16 scale per group
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libvq.so")

@@ -17,7 +17,8 @@ bool is_pow2(int v) { return v > 0 && (v & (v - 1)) == 0; }
 //   groups (2.125 bits per value);
 //   d = 1 (scalar codebooks): k = 16 fp16 values per 8 x 256 group, 4-bit indices (4.125 bits
 //   per value, the overhead of the 1D 4.125 row of the appendix table of VQ configurations).
-bool is_i8(const vq_desc& d) { return d.codebook_dtype == VQ_I8; }
+bool is_i8(const vq_desc& d) { return d.codebook_dtype == VQ_I8 || d.codebook_dtype == VQ_I8_BN; }
+bool is_bn(const vq_desc& d) { return d.codebook_dtype == VQ_I8_BN; }
 
 int check_desc(const vq_desc* d) {
   if (!d) return VQ_ERR_NULL;
@@ -26,14 +27,14 @@ int check_desc(const vq_desc* d) {
     return VQ_ERR_BAD_DESC;
   if (!is_pow2(d->k) || d->k != (1 << d->index_bits)) return VQ_ERR_BAD_DESC;
   if (d->group_cols % d->d) return VQ_ERR_BAD_DESC;
-  if (d->codebook_dtype != VQ_F16 && d->codebook_dtype != VQ_I8) return VQ_ERR_UNSUPPORTED;
+  if (d->codebook_dtype != VQ_F16 && !is_i8(*d)) return VQ_ERR_UNSUPPORTED;
   if ((d->d != 2 && d->d != 1) || d->group_cols != kGroupCols) return VQ_ERR_UNSUPPORTED;
   if (d->d == 1) {
     if (d->k != 16 || is_i8(*d) || d->group_rows != kGroupRows) return VQ_ERR_UNSUPPORTED;
   } else if (is_i8(*d)) {
     if (d->k == 64) {
       if (d->group_rows != 8 && d->group_rows != 16 && d->group_rows != 32) return VQ_ERR_UNSUPPORTED;
-    } else if (d->k == 16) {
+    } else if (d->k == 16 && !is_bn(*d)) {
       if (d->group_rows != kGroupRows) return VQ_ERR_UNSUPPORTED;
     } else {
       return VQ_ERR_UNSUPPORTED;
@@ -55,7 +56,10 @@ void sizes(const vq_desc& d, size_t* idx_bytes, size_t* cb_bytes) {
   const size_t vecs = (size_t)d.group_rows * d.group_cols / d.d;
   if (idx_bytes) *idx_bytes = n_groups * (vecs * d.index_bits / 8);
   if (cb_bytes) {
-    if (is_i8(d))   // int8 tables padded to 16 bytes, then one fp16 scale per group
+    if (is_bn(d))   // tables and scales padded to 16 bytes each, 16 fp16 levels per group, 4-bit codes
+      *cb_bytes = (n_groups * (size_t)d.k * d.d + 15) / 16 * 16 + (2 * n_groups + 15) / 16 * 16 +
+                  32 * n_groups + (size_t)d.out_features * (d.in_features / 32) / 2;
+    else if (is_i8(d))   // int8 tables padded to 16 bytes, then one fp16 scale per group
       *cb_bytes = (n_groups * (size_t)d.k * d.d + 15) / 16 * 16 + 2 * n_groups;
     else
       *cb_bytes = n_groups * (size_t)d.k * d.d * 2;
@@ -64,7 +68,7 @@ void sizes(const vq_desc& d, size_t* idx_bytes, size_t* cb_bytes) {
 
 // Units a row-block of `n_cb` col-blocks is cut into (what the strips of the GEMV kernels count).
 int strip_units(int fmt, int n_cb) {
-  return (fmt == 16 || fmt == kFmtK16I8) ? (n_cb + 1) / 2 : fmt == 64 ? (n_cb + 3) / 4 : n_cb;
+  return (fmt == 16 || fmt == kFmtK16I8) ? (n_cb + 1) / 2 : (fmt == 64 || fmt == kFmtK64BN) ? (n_cb + 3) / 4 : n_cb;
 }
 
 int hip_status(hipError_t e) { return e == hipSuccess ? VQ_OK : VQ_ERR_HIP; }
@@ -112,7 +116,8 @@ int vq_canonical_bytes(const vq_desc* desc, size_t* idx_bytes, size_t* cb_bytes)
     return VQ_ERR_UNSUPPORTED;
   if (((size_t)desc->group_rows * desc->group_cols / desc->d * desc->index_bits) % 8)
     return VQ_ERR_UNSUPPORTED;
-  if (desc->codebook_dtype != VQ_F16 && desc->codebook_dtype != VQ_I8) return VQ_ERR_UNSUPPORTED;
+  if (desc->codebook_dtype != VQ_F16 && !is_i8(*desc)) return VQ_ERR_UNSUPPORTED;
+  if (is_bn(*desc) && desc->group_cols % 32) return VQ_ERR_UNSUPPORTED;
   sizes(*desc, idx_bytes, cb_bytes);
   return VQ_OK;
 }
@@ -126,7 +131,9 @@ int vq_layout_bytes(const vq_desc* desc, size_t* idx_bytes, size_t* cb_bytes) {
   if (desc->k == 64) {   // quads of 4 col-blocks: 3 KB of indices per 8-row block, 528 B of tables per group row
     const size_t n_quads = (n_cb + 3) / 4;
     if (idx_bytes) *idx_bytes = n_rb * n_quads * 3072;
-    if (cb_bytes) *cb_bytes = (size_t)(desc->out_features / desc->group_rows) * n_quads * 528;
+    if (cb_bytes)   // with blockwise normalisation: 672-byte records, then 128 bytes of codes per (8-row block, quad)
+      *cb_bytes = is_bn(*desc) ? (size_t)(desc->out_features / desc->group_rows) * n_quads * 672 + n_rb * n_quads * 128
+                               : (size_t)(desc->out_features / desc->group_rows) * n_quads * 528;
     return VQ_OK;
   }
   if (desc->d == 1) {    // 1 KB of indices and 16 fp16 scalars per group

@@ -74,12 +74,14 @@ __global__ __launch_bounds__(256) void decode_kernel(const uint8_t* __restrict__
 }
 
 // k = 64 (6-bit indices, int8 tables with a scale): one wave per (8-row block, col-block).
-// Lane L dequantises table entry L (fp16(scale * q), one rounding) and then copies.
+// Lane L dequantises table entry L (fp16(scale * q), one rounding) and then copies.  BN: every
+// copied pair is first multiplied by the scale of its 32-weight block (one more fp16 rounding).
+template <bool BN>
 __global__ __launch_bounds__(256) void decode64_kernel(const uint8_t* __restrict__ idx,
                                                        const uint8_t* __restrict__ tab,
                                                        uint16_t* __restrict__ W, int n_cb,
                                                        long long n_items, int in_features, int rpc) {
-  __shared__ uint32_t lut_all[4][64];
+  __shared__ uint32_t lut_all[4][BN ? 80 : 64];
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   uint32_t* lut = lut_all[wave];
@@ -88,7 +90,14 @@ __global__ __launch_bounds__(256) void decode64_kernel(const uint8_t* __restrict
   const long long rb8 = item / n_cb;
   const int c = (int)(item - rb8 * n_cb);
   const int n_quads = k64_quads(n_cb), q = c >> 2, j = c & 3;
-  const uint8_t* tq = tab + (size_t)((rb8 / rpc) * n_quads + q) * kK64QuadTabBytes;
+  const uint8_t* tq = tab + (size_t)((rb8 / rpc) * n_quads + q) * (BN ? kK64NQuadTabBytes : kK64QuadTabBytes);
+  uint32_t cw = 0;
+  if (BN) {
+    const long long n_rb8 = n_items / n_cb;
+    if (lane < 16) lut[64 + lane] = *reinterpret_cast<const uint16_t*>(tq + kK64NLevelOffset + j * 32 + lane * 2) * 0x10001u;
+    cw = *reinterpret_cast<const uint32_t*>(tab + (size_t)(n_rb8 / rpc) * n_quads * kK64NQuadTabBytes +
+                                            (size_t)(rb8 * n_quads + q) * kK64NQuadCodeBytes + (lane >> 3) * 16 + j * 4);
+  }
   const uint32_t two = *reinterpret_cast<const uint16_t*>(tq + j * 128 + lane * 2);
   const _Float16 scale = __builtin_bit_cast(_Float16, *reinterpret_cast<const uint16_t*>(tq + 512 + 2 * j));
   lut[lane] = k64_dequant_pair(two, scale);
@@ -116,7 +125,13 @@ __global__ __launch_bounds__(256) void decode64_kernel(const uint8_t* __restrict
       if (pos < 64 && pos > 58) v |= (unsigned long long)d2 << (64 - pos);
       id[e] = (uint32_t)v & 63u;
     }
-    *reinterpret_cast<uint2*>(out + (size_t)r * in_features) = make_uint2(lut[id[0]], lut[id[1]]);
+    uint32_t p0 = lut[id[0]], p1 = lut[id[1]];
+    if (BN) {
+      const h2_t sc = __builtin_bit_cast(h2_t, lut[64 + ((cw >> (4 * r)) & 15u)]);
+      p0 = __builtin_bit_cast(uint32_t, __builtin_bit_cast(h2_t, p0) * sc);
+      p1 = __builtin_bit_cast(uint32_t, __builtin_bit_cast(h2_t, p1) * sc);
+    }
+    *reinterpret_cast<uint2*>(out + (size_t)r * in_features) = make_uint2(p0, p1);
   }
 }
 
@@ -128,10 +143,15 @@ hipError_t launch_decode(const vq_desc& d, const void* idx_dev, const void* cb_d
   const long long n_groups = (long long)(d.out_features / kGroupRows) * n_cb;   // 8-row items
   const unsigned grid = (unsigned)((n_groups + 3) / 4);
   const int fmt = format_tag(d);
-  if (fmt == 64) {
-    hipLaunchKernelGGL(decode64_kernel, dim3(grid), dim3(256), 0, s, (const uint8_t*)idx_dev,
-                       (const uint8_t*)cb_dev, (uint16_t*)W, n_cb, n_groups, d.in_features,
-                       d.group_rows / kGroupRows);
+  if (fmt == 64 || fmt == kFmtK64BN) {
+    if (fmt == 64)
+      hipLaunchKernelGGL(decode64_kernel<false>, dim3(grid), dim3(256), 0, s, (const uint8_t*)idx_dev,
+                         (const uint8_t*)cb_dev, (uint16_t*)W, n_cb, n_groups, d.in_features,
+                         d.group_rows / kGroupRows);
+    else
+      hipLaunchKernelGGL(decode64_kernel<true>, dim3(grid), dim3(256), 0, s, (const uint8_t*)idx_dev,
+                         (const uint8_t*)cb_dev, (uint16_t*)W, n_cb, n_groups, d.in_features,
+                         d.group_rows / kGroupRows);
     return hipGetLastError();
   }
 #define VQ_DECODE(K)                                                                                \

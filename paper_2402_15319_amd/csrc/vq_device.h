@@ -239,6 +239,15 @@ __device__ __forceinline__ void k64_group(uint32_t d0, uint32_t d1, uint32_t d2,
 // the last col-block hold zero indices, zero tables and zero scales.
 constexpr int kK64QuadIdxBytes = 3072;
 constexpr int kK64QuadTabBytes = 528;
+// With blockwise normalisation (appendix "Blockwise data normalization"; blocks of 32 weights,
+// i.e. the 4 columns of 8 neighbouring lanes): the table record grows to 672 bytes, bytes
+// [528, 656) being the four col-blocks' 16 fp16 block-scale levels; and behind all table records
+// sit the 4-bit block codes, 128 bytes per (8-row block, quad): dword 4*b + j holds the codes of
+// block b (lanes 8b .. 8b+7) of col-block j, row r in bits [4r, 4r+4), so a lane's four dwords
+// are one 16-byte load.
+constexpr int kK64NQuadTabBytes = 672;
+constexpr int kK64NLevelOffset = 528;
+constexpr int kK64NQuadCodeBytes = 128;
 __host__ __device__ __forceinline__ int k64_quads(int n_cb) { return (n_cb + 3) >> 2; }
 
 // Centroid pair from two int8 table entries and the group's scale (Sec. 3.1: table and
@@ -250,6 +259,36 @@ __device__ __forceinline__ uint32_t k64_dequant_pair(uint32_t two_bytes, _Float1
   v.y = (_Float16)(short)(signed char)((two_bytes >> 8) & 0xffu);
   v = v * h2_t{scale, scale};
   return __builtin_bit_cast(uint32_t, v);
+}
+
+// k = 64 inner block with block scales, written in plain C++ (the compiler schedules it and
+// takes care of the dot-product hazards itself): per row the lane's block scale S (fp16, both
+// halves of a dword) is looked up from the 16 levels at lev[], both looked-up centroid pairs
+// are multiplied by it (one fp16 rounding: exactly the decoded weight) and go into the dot2.
+// tab: this col-block's 64-entry table, lev: its 16 level dwords, cw: the lane's code dword.
+__device__ __forceinline__ void k64_group_scaled(uint32_t d0, uint32_t d1, uint32_t d2, uint32_t cw,
+                                                 const uint32_t* tab, const uint32_t* lev,
+                                                 uint32_t x0, uint32_t x1, float (&acc)[8]) {
+  const unsigned long long lo = d0 | ((unsigned long long)d1 << 32);
+  const h2_t xa = __builtin_bit_cast(h2_t, x0), xb = __builtin_bit_cast(h2_t, x1);
+  uint32_t t[16], sv[8];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const int pos = 6 * i;
+    unsigned long long f = pos < 64 ? lo >> pos : (unsigned long long)(d2 >> (pos - 64));
+    if (pos < 64 && pos > 58) f |= (unsigned long long)d2 << (64 - pos);
+    t[i] = tab[(uint32_t)f & 63u];
+  }
+#pragma unroll
+  for (int r = 0; r < 8; ++r) sv[r] = lev[(cw >> (4 * r)) & 15u];
+#pragma unroll
+  for (int r = 0; r < 8; ++r) {
+    const h2_t sc = __builtin_bit_cast(h2_t, sv[r]);
+    const h2_t ta = __builtin_bit_cast(h2_t, t[2 * r]) * sc;
+    const h2_t tb = __builtin_bit_cast(h2_t, t[2 * r + 1]) * sc;
+    acc[r] = __builtin_amdgcn_fdot2(ta, xa, acc[r], false);
+    acc[r] = __builtin_amdgcn_fdot2(tb, xb, acc[r], false);
+  }
 }
 
 // Pairs of col-blocks a k=16 row-block is stored as (the last one half-empty if n_cb is odd).

@@ -37,7 +37,9 @@ __device__ __forceinline__ int wt_half_index(int m, int k) {   // k in halfs
 
 // K is the kernel format tag: 16 / 256 (fp16 codebooks), 64 (6-bit indices, int8 tables with a
 // scale per group, groups of 8*rpc rows), kFmtK16I8 (k = 16 with int8 tables).
-template <int K> constexpr int lut_dwords() { return K == kFmtK16I8 ? 16 : K == kFmtD1K16 ? 256 : K; }
+template <int K> constexpr int lut_dwords() {
+  return K == kFmtK16I8 ? 16 : K == kFmtD1K16 ? 256 : K == kFmtK64BN ? 80 : K;   // BN: 64 centroids + 16 levels
+}
 
 // What one wave needs to decode one group: the lane's index bytes and codebook piece.
 template <int K> struct GroupRegs;
@@ -53,6 +55,11 @@ template <> struct GroupRegs<64> {
   uint32_t d0, d1, d2;   // the lane's 16 six-bit indices of the 8-row block
   uint32_t two;          // int8 pair of table entry `lane`
   uint32_t sc;           // the group's fp16 scale
+};
+template <> struct GroupRegs<kFmtK64BN> {
+  uint32_t d0, d1, d2, two, sc;   // as for k = 64
+  uint32_t cw;           // the lane's block codes of this col-block, row r in bits [4r, 4r+4)
+  uint32_t lev;          // block-scale level lane & 15 (fp16)
 };
 template <> struct GroupRegs<kFmtD1K16> {
   uint4 w;
@@ -85,7 +92,8 @@ __device__ __forceinline__ void load_group(GroupRegs<K>& g, const uint8_t* idx, 
     g.w = *reinterpret_cast<const uint4*>(idx + gi * 1024 + lane * 16);
     g.clo = *reinterpret_cast<const uint2*>(cg + (lane & 3) * 8);
     g.chi = *reinterpret_cast<const uint16_t*>(cg + (lane >> 2) * 2);
-  } else if constexpr (K == 64) {
+  } else if constexpr (K == 64 || K == kFmtK64BN) {
+    constexpr int tab_bytes = K == 64 ? kK64QuadTabBytes : kK64NQuadTabBytes;
     const int n_quads = k64_quads(n_cb), q = c >> 2, j = c & 3;
     const uint8_t* iq = idx + ((size_t)rb * n_quads + q) * kK64QuadIdxBytes + lane * 16;
     const int w0 = 3 * j, w1 = 3 * j + 1, w2 = 3 * j + 2;     // the lane's dwords of col-block j
@@ -93,9 +101,16 @@ __device__ __forceinline__ void load_group(GroupRegs<K>& g, const uint8_t* idx, 
     g.d1 = *reinterpret_cast<const uint32_t*>(iq + (w1 >> 2) * 1024 + (w1 & 3) * 4);
     g.d2 = *reinterpret_cast<const uint32_t*>(iq + (w2 >> 2) * 1024 + (w2 & 3) * 4);
     const uint8_t* tq = reinterpret_cast<const uint8_t*>(cb) +
-                        ((size_t)(rb / rpc) * n_quads + q) * kK64QuadTabBytes;
+                        ((size_t)(rb / rpc) * n_quads + q) * tab_bytes;
     g.two = *reinterpret_cast<const uint16_t*>(tq + j * 128 + lane * 2);
     g.sc = *reinterpret_cast<const uint16_t*>(tq + 512 + 2 * j);
+    if constexpr (K == kFmtK64BN) {
+      g.lev = *reinterpret_cast<const uint16_t*>(tq + kK64NLevelOffset + j * 32 + (lane & 15) * 2);
+      g.cw = *reinterpret_cast<const uint32_t*>(reinterpret_cast<const uint8_t*>(cb) +
+                                                (size_t)(n_rb / rpc) * n_quads * tab_bytes +
+                                                ((size_t)rb * n_quads + q) * kK64NQuadCodeBytes +
+                                                (lane >> 3) * 16 + j * 4);
+    }
   } else {
     const size_t gi = (size_t)rb * n_cb + c;
     g.w = *reinterpret_cast<const uint4*>(idx + gi * 1024 + lane * 16);
@@ -109,8 +124,11 @@ __device__ __forceinline__ void decode_group(const GroupRegs<K>& g, uint32_t* lu
                                              int m0, int lane) {
   const char* lutb = reinterpret_cast<const char*>(lut);
   uint32_t v[16];
-  if constexpr (K == 64) {
+  if constexpr (K == 64 || K == kFmtK64BN) {
     lut[lane] = k64_dequant_pair(g.two, __builtin_bit_cast(_Float16, (uint16_t)g.sc));
+    if constexpr (K == kFmtK64BN) {
+      if (lane < 16) lut[64 + lane] = g.lev * 0x10001u;
+    }
     wave_lds_sync();
     const unsigned long long lo = g.d0 | ((unsigned long long)g.d1 << 32);
 #pragma unroll
@@ -119,6 +137,14 @@ __device__ __forceinline__ void decode_group(const GroupRegs<K>& g, uint32_t* lu
       unsigned long long t = pos < 64 ? lo >> pos : (unsigned long long)(g.d2 >> (pos - 64));
       if (pos < 64 && pos > 58) t |= (unsigned long long)g.d2 << (64 - pos);
       v[i] = lut[(uint32_t)t & 63u];
+    }
+    if constexpr (K == kFmtK64BN) {     // times the block scale of the lane's 32-weight block, per row
+#pragma unroll
+      for (int r = 0; r < 8; ++r) {
+        const h2_t sc = __builtin_bit_cast(h2_t, lut[64 + ((g.cw >> (4 * r)) & 15u)]);
+        v[2 * r] = __builtin_bit_cast(uint32_t, __builtin_bit_cast(h2_t, v[2 * r]) * sc);
+        v[2 * r + 1] = __builtin_bit_cast(uint32_t, __builtin_bit_cast(h2_t, v[2 * r + 1]) * sc);
+      }
     }
   } else if constexpr (K == 16 || K == kFmtK16I8) {
     if constexpr (K == 16) {
@@ -682,6 +708,7 @@ hipError_t launch_gemm(const vq_desc& d, const void* idx_dev, const void* cb_dev
   if (fmt == 64) VQ_GEMM_DISPATCH(64)
   if (fmt == kFmtK16I8) VQ_GEMM_DISPATCH(kFmtK16I8)
   if (fmt == kFmtD1K16) VQ_GEMM_DISPATCH(kFmtD1K16)
+  if (fmt == kFmtK64BN) VQ_GEMM_DISPATCH(kFmtK64BN)
   if (fmt == 16) VQ_GEMM_DISPATCH(16)
   VQ_GEMM_DISPATCH(256)
 #undef VQ_GEMM_DISPATCH

@@ -31,6 +31,7 @@ struct Strip {
   const uint8_t* idx_rb;   // indices of the row-block
   const uint32_t* cb_rb;   // codebooks / int8 tables of the row-block (dwords)
   const uint16_t* sc_rb;   // fp16 scales of the row-block's groups (k=16 with int8 tables)
+  const uint8_t* codes_rb; // 4-bit block codes of the row-block (blockwise normalisation)
   const uint16_t* x;
   int u;                   // next unit to load
   int u_end;               // end of this strip's units
@@ -175,20 +176,29 @@ template <bool D1> struct Chunk256T {
 template <> struct Chunk<256> : Chunk256T<false> {};
 template <> struct Chunk<kFmtD1K16> : Chunk256T<true> {};
 
-template <> struct Chunk<64> {
+// k = 64 with int8 tables.  BN: blockwise normalisation on top (16 block-scale levels per
+// group, a 4-bit code per 32 weights); the plain C++ inner block replaces the hand-scheduled one.
+template <bool BN> struct Chunk64T {
   static constexpr int kUnits = 1;        // quads of 4 col-blocks per chunk
-  static constexpr int kLutDwords = 256;  // 4 groups x 64 centroids
+  static constexpr int kLutDwords = BN ? 320 : 256;  // 4 groups x 64 centroids (+ 4 x 16 levels)
+  static constexpr int kTabBytes = BN ? kK64NQuadTabBytes : kK64QuadTabBytes;
   uint4 w[3];     // the lane's three index planes of the quad
   uint2 xv[4];    // activations of the quad's four col-blocks
   uint2 tab;      // 4 int8 centroid pairs: entries 4*(lane%16).. of table lane/16
   uint32_t sc;    // that table's fp16 scale (low 16 bits)
+  uint4 cw;       // BN: the lane's block codes, one dword per col-block
+  uint32_t lev;   // BN: level lane%16 of col-block lane/16 (fp16)
 
   __device__ __forceinline__ void load(const Strip& S, int u, int lane) {
     const bool ok = u < S.u_end;
     const int q = ok ? u : 0;
-    const uint8_t* tq = reinterpret_cast<const uint8_t*>(S.cb_rb) + (size_t)q * kK64QuadTabBytes;
+    const uint8_t* tq = reinterpret_cast<const uint8_t*>(S.cb_rb) + (size_t)q * kTabBytes;
     tab = zero_unless(ok, *reinterpret_cast<const uint2*>(tq + lane * 8));
     sc = *reinterpret_cast<const uint16_t*>(tq + 512 + (lane >> 4) * 2);
+    if constexpr (BN) {
+      lev = zero_unless(ok, (uint32_t)*reinterpret_cast<const uint16_t*>(tq + kK64NLevelOffset + lane * 2));
+      cw = *reinterpret_cast<const uint4*>(S.codes_rb + (size_t)q * kK64NQuadCodeBytes + (lane >> 3) * 16);
+    }
 #pragma unroll
     for (int p = 0; p < 3; ++p)
       w[p] = stream_load16(S.idx_rb + (size_t)q * kK64QuadIdxBytes + p * 1024 + lane * 16);
@@ -205,19 +215,30 @@ template <> struct Chunk<64> {
     *reinterpret_cast<uint4*>(lut + lane * 4) =
         make_uint4(k64_dequant_pair(tab.x, scale), k64_dequant_pair(tab.x >> 16, scale),
                    k64_dequant_pair(tab.y, scale), k64_dequant_pair(tab.y >> 16, scale));
+    if constexpr (BN) lut[256 + lane] = lev * 0x10001u;   // the level in both halves
     wave_lds_sync();
     const uint32_t d[12] = {w[0].x, w[0].y, w[0].z, w[0].w, w[1].x, w[1].y,
                             w[1].z, w[1].w, w[2].x, w[2].y, w[2].z, w[2].w};
+    if constexpr (BN) {
+      const uint32_t cws[4] = {cw.x, cw.y, cw.z, cw.w};
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        k64_group_scaled(d[3 * j], d[3 * j + 1], d[3 * j + 2], cws[j], lut + 64 * j, lut + 256 + 16 * j,
+                         xv[j].x, xv[j].y, acc);
+    } else {
 #define VQ_G64(J)                                                                              \
-    k64_group<256 * J>(d[3 * J], d[3 * J + 1], d[3 * J + 2],                                   \
-                       __builtin_amdgcn_alignbit(d[3 * J + 1], d[3 * J], 30),                  \
-                       __builtin_amdgcn_alignbit(d[3 * J + 2], d[3 * J + 1], 28), base,        \
-                       xv[J].x, xv[J].y, acc);
-    VQ_G64(0) VQ_G64(1) VQ_G64(2) VQ_G64(3)
+      k64_group<256 * J>(d[3 * J], d[3 * J + 1], d[3 * J + 2],                                 \
+                         __builtin_amdgcn_alignbit(d[3 * J + 1], d[3 * J], 30),                \
+                         __builtin_amdgcn_alignbit(d[3 * J + 2], d[3 * J + 1], 28), base,      \
+                         xv[J].x, xv[J].y, acc);
+      VQ_G64(0) VQ_G64(1) VQ_G64(2) VQ_G64(3)
 #undef VQ_G64
-    acc_hazard_fence();
+      acc_hazard_fence();
+    }
   }
 };
+template <> struct Chunk<64> : Chunk64T<false> {};
+template <> struct Chunk<kFmtK64BN> : Chunk64T<true> {};
 
 // Strip (row-block rb, K-split `split` of `splits`) of problem P; may be empty.
 template <int K>
@@ -227,6 +248,7 @@ __device__ __forceinline__ Strip make_strip(const GemvProblem& P, int rb, int sp
   S.x = P.x;
   S.n_cb = n_cb;
   S.sc_rb = nullptr;
+  S.codes_rb = nullptr;
   if (K == 16 || K == kFmtK16I8) {
     const int n_pairs = k16_pairs(n_cb);
     S.idx_rb = P.idx + (size_t)rb * n_pairs * 1024;
@@ -240,10 +262,15 @@ __device__ __forceinline__ Strip make_strip(const GemvProblem& P, int rb, int sp
     S.u = (n_pairs * split) / splits;
     S.u_end = (n_pairs * (split + 1)) / splits;
     S.chunks_left = (S.u_end - S.u + 3) >> 2;
-  } else if (K == 64) {
+  } else if (K == 64 || K == kFmtK64BN) {
     const int n_quads = k64_quads(n_cb);
+    constexpr int tab_bytes = K == 64 ? kK64QuadTabBytes : kK64NQuadTabBytes;
     S.idx_rb = P.idx + (size_t)rb * n_quads * kK64QuadIdxBytes;
-    S.cb_rb = P.cb + (size_t)(rb / P.rb_per_cb) * n_quads * (kK64QuadTabBytes / 4);
+    S.cb_rb = P.cb + (size_t)(rb / P.rb_per_cb) * n_quads * (tab_bytes / 4);
+    if (K == kFmtK64BN)   // the codes follow the table records of all group rows
+      S.codes_rb = reinterpret_cast<const uint8_t*>(P.cb) +
+                   (size_t)(P.n_rb / P.rb_per_cb) * n_quads * tab_bytes +
+                   (size_t)rb * n_quads * kK64NQuadCodeBytes;
     S.u = (n_quads * split) / splits;
     S.u_end = (n_quads * (split + 1)) / splits;
     S.chunks_left = S.u_end - S.u;
@@ -399,23 +426,30 @@ template <bool D1> struct ChunkS256T {
 template <> struct ChunkS<256> : ChunkS256T<false> {};
 template <> struct ChunkS<kFmtD1K16> : ChunkS256T<true> {};
 
-template <> struct ChunkS<64> {
+template <bool BN> struct ChunkS64T {
   static constexpr int kUnits = 1;
-  static constexpr int kLutDwords = 256;
+  static constexpr int kLutDwords = BN ? 320 : 256;
+  static constexpr int kTabBytes = BN ? kK64NQuadTabBytes : kK64QuadTabBytes;
   uint4 w[3];
   uint2 tab;
   uint32_t sc;
+  uint4 cw;        // BN: see Chunk64T
+  uint32_t lev;
   int u0;          // the quad (locates the activations in LDS), wave-uniform
 
   __device__ __forceinline__ void load(const Strip& S, int u, int lane) {
     const bool ok = u < S.u_end;
     const int q = ok ? u : 0;
     u0 = u;
-    const uint8_t* tq = reinterpret_cast<const uint8_t*>(S.cb_rb) + (size_t)q * kK64QuadTabBytes;
+    const uint8_t* tq = reinterpret_cast<const uint8_t*>(S.cb_rb) + (size_t)q * kTabBytes;
     uint32_t voff = (uint32_t)lane * 16u;      // see ChunkS<16>::load
     asm volatile("" : "+v"(voff));
     tab = zero_unless(ok, *reinterpret_cast<const uint2*>(tq + (voff >> 1)));
     sc = *reinterpret_cast<const uint16_t*>(tq + 512 + (lane >> 4) * 2);
+    if constexpr (BN) {
+      lev = zero_unless(ok, (uint32_t)*reinterpret_cast<const uint16_t*>(tq + kK64NLevelOffset + lane * 2));
+      cw = *reinterpret_cast<const uint4*>(S.codes_rb + (size_t)q * kK64NQuadCodeBytes + (lane >> 3) * 16);
+    }
 #pragma unroll
     for (int p = 0; p < 3; ++p)
       w[p] = stream_load16(S.idx_rb + (size_t)q * kK64QuadIdxBytes + p * 1024 + voff);
@@ -428,26 +462,39 @@ template <> struct ChunkS<64> {
     *reinterpret_cast<uint4*>(lut + lane * 4) =
         make_uint4(k64_dequant_pair(tab.x, scale), k64_dequant_pair(tab.x >> 16, scale),
                    k64_dequant_pair(tab.y, scale), k64_dequant_pair(tab.y >> 16, scale));
+    if constexpr (BN) lut[256 + lane] = lev * 0x10001u;
     wave_lds_sync();
     const uint2* xp = reinterpret_cast<const uint2*>(x_s) + u0 * 256 + lane;   // 64 uint2 per col-block
     const uint32_t d[12] = {w[0].x, w[0].y, w[0].z, w[0].w, w[1].x, w[1].y,
                             w[1].z, w[1].w, w[2].x, w[2].y, w[2].z, w[2].w};
-    uint2 x0 = xp[0], x1 = xp[64];
+    if constexpr (BN) {
+      const uint32_t cws[4] = {cw.x, cw.y, cw.z, cw.w};
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const uint2 xj = xp[64 * j];
+        k64_group_scaled(d[3 * j], d[3 * j + 1], d[3 * j + 2], cws[j], lut + 64 * j, lut + 256 + 16 * j,
+                         xj.x, xj.y, acc);
+      }
+    } else {
+      uint2 x0 = xp[0], x1 = xp[64];
 #define VQ_G64(J, X)                                                                           \
-    k64_group<256 * J>(d[3 * J], d[3 * J + 1], d[3 * J + 2],                                   \
-                       __builtin_amdgcn_alignbit(d[3 * J + 1], d[3 * J], 30),                  \
-                       __builtin_amdgcn_alignbit(d[3 * J + 2], d[3 * J + 1], 28), base,        \
-                       X.x, X.y, acc);
-    VQ_G64(0, x0)
-    x0 = xp[128];
-    VQ_G64(1, x1)
-    x1 = xp[192];
-    VQ_G64(2, x0)
-    VQ_G64(3, x1)
+      k64_group<256 * J>(d[3 * J], d[3 * J + 1], d[3 * J + 2],                                 \
+                         __builtin_amdgcn_alignbit(d[3 * J + 1], d[3 * J], 30),                \
+                         __builtin_amdgcn_alignbit(d[3 * J + 2], d[3 * J + 1], 28), base,      \
+                         X.x, X.y, acc);
+      VQ_G64(0, x0)
+      x0 = xp[128];
+      VQ_G64(1, x1)
+      x1 = xp[192];
+      VQ_G64(2, x0)
+      VQ_G64(3, x1)
 #undef VQ_G64
-    acc_hazard_fence();
+      acc_hazard_fence();
+    }
   }
 };
+template <> struct ChunkS<64> : ChunkS64T<false> {};
+template <> struct ChunkS<kFmtK64BN> : ChunkS64T<true> {};
 
 // Zeroed col-blocks kept behind x in LDS (absent units of a ragged chunk read them).
 constexpr int kXPadColBlocks = 8;
@@ -645,6 +692,7 @@ __global__ __launch_bounds__(256) void gemv_split_kernel(const GemvBatch batch) 
     case 64: F(64); break;                    \
     case kFmtK16I8: F(kFmtK16I8); break;      \
     case kFmtD1K16: F(kFmtD1K16); break;      \
+    case kFmtK64BN: F(kFmtK64BN); break;      \
     default: F(256); break;                   \
   }
 
@@ -660,10 +708,10 @@ int gemv_stream_resident_wgs(int fmt, int max_n_cb) {
   // Occupancy of the persistent kernel for this LDS size, asked once per (device, format, size):
   // a pure function of the code object and the device, cached so that the hot path makes
   // no runtime queries.  Benign if two threads fill the same slot at once.
-  static int cached[5][16][kStreamMaxColBlocks + 1];
+  static int cached[6][16][kStreamMaxColBlocks + 1];
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) dev = 0;
-  const int fi = fmt == 16 ? 0 : fmt == 64 ? 1 : fmt == kFmtK16I8 ? 3 : fmt == kFmtD1K16 ? 4 : 2;
+  const int fi = fmt == 16 ? 0 : fmt == 64 ? 1 : fmt == kFmtK16I8 ? 3 : fmt == kFmtD1K16 ? 4 : fmt == kFmtK64BN ? 5 : 2;
   int& slot = cached[fi][dev][max_n_cb];
   if (slot == 0) {
     int per_cu = 0, cus = 0;

@@ -16,8 +16,10 @@ constexpr int kMaxProblemsPerLaunch = 256;  // the problem table travels in the 
 // the group's 16 scalars; from there on the work is that of d = 2, k = 256.
 constexpr int kFmtK16I8 = 1016;
 constexpr int kFmtD1K16 = 2016;
+constexpr int kFmtK64BN = 3064;   // k = 64, int8 tables + scale, blockwise normalisation (blocks of 32)
 inline int format_tag(const vq_desc& d) {
   if (d.d == 1) return kFmtD1K16;
+  if (d.codebook_dtype == VQ_I8_BN) return kFmtK64BN;
   if (d.k == 16 && d.codebook_dtype == VQ_I8) return kFmtK16I8;
   return d.k;
 }

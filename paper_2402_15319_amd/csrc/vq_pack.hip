@@ -134,9 +134,12 @@ __global__ __launch_bounds__(256) void pack_idx64_kernel(const uint8_t* __restri
         make_uint4(d[4 * p], d[4 * p + 1], d[4 * p + 2], d[4 * p + 3]);
 }
 
-// Tables: per (row of groups, quad) four int8 tables of 128 bytes, then their four scales.
+// Tables: per (row of groups, quad) four int8 tables of 128 bytes, then their four scales;
+// with blockwise normalisation (level_canon != nullptr, 672-byte records) also the four
+// col-blocks' 16 fp16 levels.
 __global__ __launch_bounds__(256) void pack_tab64_kernel(const uint8_t* __restrict__ q_canon,
                                                          const uint16_t* __restrict__ scale_canon,
+                                                         const uint16_t* __restrict__ level_canon,
                                                          uint8_t* __restrict__ dev, int n_cb,
                                                          long long n_grow) {
   const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
@@ -147,7 +150,12 @@ __global__ __launch_bounds__(256) void pack_tab64_kernel(const uint8_t* __restri
   const long long grow = slot / n_quads;
   const int q = (int)(slot - grow * n_quads);
   const int c = 4 * q + (lane >> 4);
-  uint8_t* dst = dev + (size_t)slot * kK64QuadTabBytes;
+  uint8_t* dst = dev + (size_t)slot * (level_canon ? kK64NQuadTabBytes : kK64QuadTabBytes);
+  if (level_canon) {
+    reinterpret_cast<uint16_t*>(dst + kK64NLevelOffset)[lane] =
+        c < n_cb ? level_canon[(grow * n_cb + c) * 16 + (lane & 15)] : (uint16_t)0;
+    if (lane < 8) reinterpret_cast<uint16_t*>(dst + kK64NLevelOffset + 128)[lane] = 0;   // padding
+  }
   const uint2 v = c < n_cb
       ? *reinterpret_cast<const uint2*>(q_canon + (size_t)(grow * n_cb + c) * 128 + (lane & 15) * 8)
       : make_uint2(0u, 0u);
@@ -157,6 +165,32 @@ __global__ __launch_bounds__(256) void pack_tab64_kernel(const uint8_t* __restri
     reinterpret_cast<uint16_t*>(dst + 512)[lane] =
         (lane < 4 && cs < n_cb) ? scale_canon[grow * n_cb + cs] : (uint16_t)0;
   }
+}
+
+// Block codes: canonical code[r][c/32] (two per byte, even block in the low nibble, 4*n_cb
+// bytes per row) -> per (8-row block, quad) 32 dwords, dword 4*b + j = codes of block b of
+// col-block 4q + j, row r in bits [4r, 4r+4).  One thread per dword.
+__global__ __launch_bounds__(256) void pack_codes64_kernel(const uint8_t* __restrict__ canon,
+                                                           uint32_t* __restrict__ dev, int n_cb,
+                                                           long long n_rb8) {
+  const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
+  const int n_quads = k64_quads(n_cb);
+  if (t >= n_rb8 * n_quads * 32) return;
+  const long long slot = t >> 5;
+  const int b = (int)(t & 31) >> 2, j = (int)(t & 3);
+  const long long rb8 = slot / n_quads;
+  const int q = (int)(slot - rb8 * n_quads);
+  const int c = 4 * q + j;
+  uint32_t w = 0;
+  if (c < n_cb) {
+    const int blk = c * 8 + b;                       // block index inside the row
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+      const uint32_t byte = canon[(size_t)(rb8 * 8 + r) * (4 * n_cb) + (blk >> 1)];
+      w |= ((blk & 1) ? byte >> 4 : byte & 15u) << (4 * r);
+    }
+  }
+  dev[t] = w;
 }
 
 // Reads n16 16-byte pieces once (non-temporal) and keeps the optimiser from dropping the loads.
@@ -199,10 +233,18 @@ hipError_t launch_pack(const vq_desc& d, const void* idx_canon, const void* cb_c
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const size_t q_bytes = ((size_t)n_grow * n_cb * 128 + 15) / 16 * 16;   // scales follow the tables
+    const bool bn = d.codebook_dtype == VQ_I8_BN;
+    const size_t s_bytes = ((size_t)n_grow * n_cb * 2 + 15) / 16 * 16;     // levels follow the padded scales
+    const uint8_t* canon = (const uint8_t*)cb_canon;
     hipLaunchKernelGGL(pack_tab64_kernel, dim3((unsigned)((n_grow * n_quads * 64 + 255) / 256)),
-                       dim3(256), 0, s, (const uint8_t*)cb_canon,
-                       (const uint16_t*)((const uint8_t*)cb_canon + q_bytes), (uint8_t*)cb_dev, n_cb,
-                       n_grow);
+                       dim3(256), 0, s, canon, (const uint16_t*)(canon + q_bytes),
+                       bn ? (const uint16_t*)(canon + q_bytes + s_bytes) : (const uint16_t*)nullptr,
+                       (uint8_t*)cb_dev, n_cb, n_grow);
+    e = hipGetLastError();
+    if (e != hipSuccess || !bn) return e;
+    hipLaunchKernelGGL(pack_codes64_kernel, dim3((unsigned)((n_rb * n_quads * 32 + 255) / 256)), dim3(256),
+                       0, s, canon + q_bytes + s_bytes + (size_t)n_grow * n_cb * 32,
+                       (uint32_t*)((uint8_t*)cb_dev + (size_t)n_grow * n_quads * kK64NQuadTabBytes), n_cb, n_rb);
     return hipGetLastError();
   }
   const int fmt = format_tag(d);

@@ -198,3 +198,21 @@ def test_quantiser_entry_points_validate_before_launch():
         assert L.vq_em_assign(ctypes.byref(bad), A, A, A, A, 0) == -3
         assert L.vq_em_update(ctypes.byref(bad), A, A, A, A, 0) == -3
     assert L.vq_em_assign(ctypes.byref(vq.make_desc(4096, 4096, 32, 4)), A, A, A, A, 0) == -2
+
+
+def test_block_normalised_representation_sizes_and_validation():
+    """VQ_I8_BN: k = 64 only; canonical = tables | scales | 16 levels per group | nibble codes;
+    device = 672-byte table records per (group row, quad) + 128 bytes of codes per (8-row block, quad)."""
+    L = vq.lib()
+    for out_f, in_f, rows in ((4096, 4096, 32), (4096, 11008, 32), (64, 768, 8)):
+        d = vq.make_desc(out_f, in_f, 64, 6, group_rows=rows, codebook_dtype=vq.VQ_I8_BN)
+        n_groups = (out_f // rows) * (in_f // 256)
+        ib, cbb = vq.vq_canonical_bytes(d)
+        assert ib == n_groups * rows * 96
+        assert cbb == (n_groups * 128 + 15) // 16 * 16 + (n_groups * 2 + 15) // 16 * 16 + n_groups * 32 + out_f * in_f // 64
+        quads = (in_f // 256 + 3) // 4
+        assert vq.vq_layout_bytes(d) == ((out_f // 8) * quads * 3072, (out_f // rows) * quads * 672 + (out_f // 8) * quads * 128)
+        assert L.vq_gemv(ctypes.byref(d), A, A, A + 2, A + 16, vq.VQ_F16, 0) == -4
+    bad = vq.make_desc(4096, 4096, 16, 4, codebook_dtype=vq.VQ_I8_BN)
+    assert L.vq_gemv(ctypes.byref(bad), A, A, A, A + 16, vq.VQ_F16, 0) == -3
+    assert L.vq_em_assign(ctypes.byref(vq.make_desc(4096, 4096, 64, 6, codebook_dtype=vq.VQ_I8_BN)), A, A + 4, A, A, 0) == -4

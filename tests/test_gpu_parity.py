@@ -599,3 +599,67 @@ def test_random_shapes_every_entry_point(env, case):
     X = workloads.make_X(s.in_features, B, seed)
     Y = _gpu_gemm(env, desc, idx_d, cb_d, X, True)
     assert oracle.normwise_rel_err(Y, oracle.gemm(f, idx, cb, X)) <= TOL_F32
+
+
+# ---------------------------------------------------------------- blockwise normalisation (k = 64, int8 tables)
+def _shape_bn(o, i, rows=32):
+    return workloads.VQShape(o, i, 64, 6, rows, 256, 2, True, True)
+
+
+def _setup_bn(env, s, seed):
+    """Device buffers and the oracle's dense W (raw fp16 bits): table decode, then the block scales."""
+    torch, vq, vqdev = env
+    idx, q, scale, levels, codes = workloads.make_weights_bn(s, seed)
+    desc = vqdev.desc_from_shape(s)
+    idx_d, cb_d = vqdev.upload_and_pack(desc, idx, vqdev.canonical_tables_bn(desc, q, scale, levels, codes))
+    f = _fmt(s)
+    W = oracle.apply_block_scales(f, oracle.decode_dense(f, idx, oracle.dequantise_codebooks(q, scale)), levels, codes)
+    return desc, W, idx_d, cb_d
+
+
+def _dense_product(W_bits, X):
+    """y = W x (or Y = W X) in fp64 from the oracle's dense W: the definition of the product."""
+    return W_bits.view(np.float16).astype(np.float64) @ np.asarray(X, dtype=np.float16).astype(np.float64)
+
+
+BN_SMALL = [_shape_bn(32, 256), _shape_bn(96, 768), _shape_bn(64, 2816), _shape_bn(40, 1280, 8),
+            _shape_bn(48, 512, 16), _shape_bn(264, 1024, 8)]
+
+
+@pytest.mark.parametrize("s", BN_SMALL, ids=str)
+def test_block_norm_decode_bit_exact(env, s):
+    desc, W, idx_d, cb_d = _setup_bn(env, s, 700)
+    np.testing.assert_array_equal(_gpu_decode(env, desc, idx_d, cb_d), W)
+
+
+@pytest.mark.parametrize("f32", [False, True], ids=["y16", "y32"])
+@pytest.mark.parametrize("s", BN_SMALL + [_shape_bn(32800, 768), _shape_bn(33024, 1280)], ids=str)
+def test_block_norm_gemv(env, s, f32):
+    """Split-K kernel on the small shapes, the streaming kernel from 4,096 row-blocks."""
+    desc, W, idx_d, cb_d = _setup_bn(env, s, 701)
+    x = workloads.make_x(s.in_features, 701)
+    y = _gpu_gemv(env, desc, idx_d, cb_d, x, f32)
+    assert oracle.normwise_rel_err(y, _dense_product(W, x)) <= (TOL_F32 if f32 else TOL_F16)
+
+
+@pytest.mark.parametrize("B", [1, 16, 40, 130, 600, 1300])
+@pytest.mark.parametrize("s", [_shape_bn(96, 768), _shape_bn(808, 512, 8)], ids=str)
+def test_block_norm_gemm(env, s, B):
+    desc, W, idx_d, cb_d = _setup_bn(env, s, 702)
+    X = workloads.make_X(s.in_features, B, 702)
+    Y = _gpu_gemm(env, desc, idx_d, cb_d, X, False, pad=8 if B == 40 else 0)
+    assert oracle.normwise_rel_err(Y, _dense_product(W, X)) <= TOL_F16
+
+
+def test_block_norm_deployed_shape(env):
+    """4096 x 11008 (43 col-blocks: a ragged last quad), 32 x 256 groups: decode in full, GEMV, and
+    48 sampled columns of the B = 2048 product."""
+    s = workloads.CONFIGS["mlp_down_4096x11008_k64_bn"]
+    desc, W, idx_d, cb_d = _setup_bn(env, s, 703)
+    np.testing.assert_array_equal(_gpu_decode(env, desc, idx_d, cb_d), W)
+    x = workloads.make_x(s.in_features, 703)
+    assert oracle.normwise_rel_err(_gpu_gemv(env, desc, idx_d, cb_d, x, False), _dense_product(W, x)) <= TOL_F16
+    X = workloads.make_X(s.in_features, 2048, 703)
+    Y = _gpu_gemm(env, desc, idx_d, cb_d, X, False)
+    cols = np.random.default_rng(4).choice(2048, size=48, replace=False)
+    assert oracle.normwise_rel_err(Y[:, cols], _dense_product(W, X[:, cols])) <= TOL_F16

@@ -22,7 +22,7 @@ import numpy as np
 __all__ = [
     "VQShape", "CONFIGS", "LLAMA7B_LAYER", "seed_for", "canonical_sizes",
     "make_weights", "make_weights_i8", "make_x", "make_X", "llama7b_pass_shapes",
-    "LLAMA7B_LAYER_K64", "LLAMA7B_LAYER_K16_I8", "LLAMA7B_LAYER_D1_K16",
+    "LLAMA7B_LAYER_K64", "LLAMA7B_LAYER_K16_I8", "LLAMA7B_LAYER_D1_K16", "LLAMA7B_LAYER_K64_BN", "make_weights_bn",
 ]
 
 
@@ -37,6 +37,8 @@ class VQShape:
     group_cols: int = 256
     d: int = 2
     int8_tables: bool = False     # int8 centroids with one fp16 scale per group (Sec. 3.1)
+    block_norm: bool = False      # blockwise normalisation on top (appendix): 16 levels per group,
+                                  # one 4-bit code per 32 weights
 
     @property
     def n_groups(self) -> int:
@@ -51,6 +53,10 @@ def canonical_sizes(s: VQShape) -> tuple[int, int]:
     """(index bytes, codebook bytes) of the canonical arrays for shape ``s``."""
     idx_group_bits = s.vectors_per_group * s.index_bits
     assert idx_group_bits % 8 == 0
+    if s.block_norm:     # tables and scales padded to 16 bytes each, 32 bytes of levels per group, nibble codes
+        return (s.n_groups * (idx_group_bits // 8),
+                (s.n_groups * s.k * s.d + 15) // 16 * 16 + (2 * s.n_groups + 15) // 16 * 16 + 32 * s.n_groups
+                + s.out_features * (s.in_features // 32) // 2)
     if s.int8_tables:    # int8 tables padded to 16 bytes, then one fp16 scale per group
         return s.n_groups * (idx_group_bits // 8), (s.n_groups * s.k * s.d + 15) // 16 * 16 + 2 * s.n_groups
     return s.n_groups * (idx_group_bits // 8), s.n_groups * s.k * s.d * 2
@@ -78,6 +84,10 @@ CONFIGS = {
     "attn_4096x4096_k64_i8": VQShape(4096, 4096, 64, 6, 32, 256, 2, True),
     "mlp_up_11008x4096_k64_i8": VQShape(11008, 4096, 64, 6, 32, 256, 2, True),
     "mlp_down_4096x11008_k64_i8": VQShape(4096, 11008, 64, 6, 32, 256, 2, True),
+    # ... with blockwise normalisation (appendix): + 16 levels per group and a 4-bit code per 32 weights
+    "attn_4096x4096_k64_bn": VQShape(4096, 4096, 64, 6, 32, 256, 2, True, True),
+    "mlp_up_11008x4096_k64_bn": VQShape(11008, 4096, 64, 6, 32, 256, 2, True, True),
+    "mlp_down_4096x11008_k64_bn": VQShape(4096, 11008, 64, 6, 32, 256, 2, True, True),
 }
 
 # One Llama-7B decoder layer as (name, shape key) in execution order.
@@ -92,6 +102,7 @@ LLAMA7B_LAYER = (
 )
 LLAMA7B_LAYER_K64 = tuple((n, k.replace("_k16", "_k64_i8")) for n, k in LLAMA7B_LAYER)
 LLAMA7B_LAYER_K16_I8 = tuple((n, k + "_i8") for n, k in LLAMA7B_LAYER)
+LLAMA7B_LAYER_K64_BN = tuple((n, k.replace("_k16", "_k64_bn")) for n, k in LLAMA7B_LAYER)
 LLAMA7B_LAYER_D1_K16 = tuple((n, k.replace("_k16", "_d1_k16")) for n, k in LLAMA7B_LAYER)
 LLAMA7B_N_LAYERS = 32
 
@@ -133,6 +144,22 @@ def make_weights_i8(s: VQShape, seed: int, w_std: float = 0.02):
     q = rng.integers(-127, 128, size=(s.n_groups, s.k, s.d), dtype=np.int8)
     scale = (3.0 * w_std / 127.0 * np.exp2(rng.uniform(-0.5, 0.5, size=s.n_groups))).astype(np.float16)
     return idx, q, scale
+
+
+def make_weights_bn(s: VQShape, seed: int, w_std: float = 0.02):
+    """As make_weights_i8, plus the blockwise normalisation data: levels float16[n_groups, 16]
+    = 2^(a_g * j + s0_g) with a_g in [0.1, 0.3] and s0_g in [-1.5, -0.5] (a log-scale grid
+    spanning one to several octaves, as the appendix describes), rounded to fp16, and uniform
+    4-bit codes uint8[out, in / 32]."""
+    assert s.block_norm and s.int8_tables
+    idx, q, scale = make_weights_i8(VQShape(s.out_features, s.in_features, s.k, s.index_bits, s.group_rows,
+                                            s.group_cols, s.d, True), seed, w_std)
+    rng = np.random.default_rng(seed ^ 0xB10C)
+    a = rng.uniform(0.1, 0.3, size=(s.n_groups, 1))
+    s0 = rng.uniform(-1.5, -0.5, size=(s.n_groups, 1))
+    levels = np.exp2(a * np.arange(16)[None, :] + s0).astype(np.float16)
+    codes = rng.integers(0, 16, size=(s.out_features, s.in_features // 32), dtype=np.uint8)
+    return idx, q, scale, levels, codes
 
 
 def make_x(n: int, seed: int) -> np.ndarray:
