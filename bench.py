@@ -208,6 +208,10 @@ def main():
                  "gemv_stream_kernel<64>"),
                 ("llama7b_pass_k16_int8_tables_2.125bpv_via_vq_gemv_multi", workloads.LLAMA7B_LAYER_K16_I8,
                  "gemv_stream_kernel<k16,int8>"),
+                # the deployed representation with blockwise normalisation on top (appendix): 16 levels
+                # per group and a 4-bit code per 32 weights, 3.28 bits per value
+                ("llama7b_pass_k64_int8_tables_block_norm_3.28bpv_via_vq_gemv_multi", workloads.LLAMA7B_LAYER_K64_BN,
+                 "gemv_stream_kernel<64,bn>"),
                 # scalar codebooks (d = 1): 16 fp16 values per 8 x 256 group, 4-bit indices, 3.47 GB
                 ("llama7b_pass_d1_k16_4.125bpv_via_vq_gemv_multi", workloads.LLAMA7B_LAYER_D1_K16,
                  "gemv_stream_kernel<d1,k16>")):
@@ -220,6 +224,13 @@ def main():
                     tab = torch.randint(0, 256, (cbb,), dtype=torch.uint8, device=dev)
                     if s.d == 1:                        # fp16 scalars
                         tab = (torch.randn(cbb // 2, device=dev) * 0.02).half().view(torch.uint8)
+                    elif s.block_norm:                  # 672-byte records (+ 64 levels, set to 1.0), then nibble codes
+                        n_rec = (s.out_features // s.group_rows) * ((s.in_features // 256 + 3) // 4)
+                        tv = tab[:n_rec * 672].view(-1, 672)
+                        tv[:, 512:528] = 0
+                        tv[:, 513:520:2] = 0x1C
+                        tv[:, 528:672] = 0
+                        tv[:, 529:656:2] = 0x3C
                     elif s.k == 64:                       # 528-byte records: 4 tables, 4 scales, padding
                         tv = tab.view(-1, 528)
                         tv[:, 512:528] = 0
