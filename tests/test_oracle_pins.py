@@ -486,3 +486,34 @@ def test_block_normalised_format_sizes():
     assert ib == oracle.canonical_sizes_i8(f)[0]
     assert tb == f.n_groups * 128 + f.n_groups * 2 + f.n_groups * 32 + 4096 * 128 // 2
     assert (ib + tb) * 8 / (4096 * 4096) == 3 + (1024 + 16 + 256) / 8192 + 4 / 32
+
+
+# ---------------------------------------------------------------- four-dimensional vectors (d = 4)
+def test_golden_four_dimensional_vectors():
+    """A vector taken down a column instead of along the row, centroid coordinates in the wrong
+    order, or vectors of a group counted column-major fail here."""
+    case = read_case("decode_2x8_k4_b2_d4_i8.txt")
+    f = _fmt(case)
+    assert f.d == 4 and f.vectors_per_group == 4
+    cb = oracle.dequantise_codebooks(case["q"].astype(np.int8), case["scale"].astype(np.float16))
+    assert cb.shape == (1, 4, 4)
+    W = oracle.decode_dense(f, case["idx"], cb).view(np.float16).astype(np.float64)
+    np.testing.assert_array_equal(W, case["W"])
+    np.testing.assert_array_equal(oracle.gemv(f, case["idx"], cb, case["x"].astype(np.float16)), case["y"])
+    for r in range(2):
+        for c in range(8):
+            bits = oracle.decode_element(f, case["idx"], cb, r, c)
+            assert np.array([bits], dtype=np.uint16).view(np.float16)[0] == case["W"][r, c]
+
+
+def test_four_dimensional_format_sizes_follow_the_bpv_formula():
+    """The 4D rows of the appendix table: 8-bit indices per 4 weights, 256 x 4 int8 tables; groups of
+    65,536 (256 x 256) give 2 + 256*4*8/65536 = 2.125 and groups of 32,768 (128 x 256) 2.25 bits
+    per value; the fp16 scale per group adds 16 bits per group on top."""
+    assert oracle.bits_per_value(256, 4, 8, 65536) == 2.125
+    assert oracle.bits_per_value(256, 4, 8, 32768) == 2.25
+    for rows, bpv in ((256, 2.125), (128, 2.25)):
+        f = VQFormat(4096, 4096, 256, 8, rows, 256, 4)
+        ib, tb = oracle.canonical_sizes_i8(f)
+        assert ib == 4096 * 4096 // 4 and tb == f.n_groups * 1024 + 2 * f.n_groups
+        assert (ib + tb - 2 * f.n_groups) * 8 / (4096 * 4096) == bpv
