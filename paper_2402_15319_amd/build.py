@@ -11,7 +11,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libvq.so")
-SOURCES = ["vq_api.hip", "vq_pack.hip", "vq_decode.hip", "vq_gemv.hip", "vq_gemm.hip", "vq_em.hip"]
+SOURCES = ["vq_api.hip", "vq_pack.hip", "vq_decode.hip", "vq_gemv.hip", "vq_gemv_d4.hip", "vq_gemm.hip", "vq_em.hip"]
 # packed-fp32 code generation is switched off on purpose for this machine pool
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",

@@ -16,7 +16,9 @@ bool is_pow2(int v) { return v > 0 && (v & (v - 1)) == 0; }
 //   rows x 256 columns (32 rows = the 8,192-weight groups of Sec. 5.1), or k = 16 with 8 x 256
 //   groups (2.125 bits per value);
 //   d = 1 (scalar codebooks): k = 16 fp16 values per 8 x 256 group, 4-bit indices (4.125 bits
-//   per value, the overhead of the 1D 4.125 row of the appendix table of VQ configurations).
+//   per value, the overhead of the 1D 4.125 row of the appendix table of VQ configurations);
+//   d = 4: k = 256 (one index byte per 4 weights), int8 tables with a scale, groups of 64, 128 or
+//   256 rows x 256 columns (128 and 256: the 4D 2.25 and 2.125 rows of that table).
 bool is_i8(const vq_desc& d) { return d.codebook_dtype == VQ_I8 || d.codebook_dtype == VQ_I8_BN; }
 bool is_bn(const vq_desc& d) { return d.codebook_dtype == VQ_I8_BN; }
 
@@ -28,9 +30,12 @@ int check_desc(const vq_desc* d) {
   if (!is_pow2(d->k) || d->k != (1 << d->index_bits)) return VQ_ERR_BAD_DESC;
   if (d->group_cols % d->d) return VQ_ERR_BAD_DESC;
   if (d->codebook_dtype != VQ_F16 && !is_i8(*d)) return VQ_ERR_UNSUPPORTED;
-  if ((d->d != 2 && d->d != 1) || d->group_cols != kGroupCols) return VQ_ERR_UNSUPPORTED;
+  if ((d->d != 2 && d->d != 1 && d->d != 4) || d->group_cols != kGroupCols) return VQ_ERR_UNSUPPORTED;
   if (d->d == 1) {
     if (d->k != 16 || is_i8(*d) || d->group_rows != kGroupRows) return VQ_ERR_UNSUPPORTED;
+  } else if (d->d == 4) {
+    if (d->k != 256 || d->codebook_dtype != VQ_I8) return VQ_ERR_UNSUPPORTED;
+    if (d->group_rows != 64 && d->group_rows != 128 && d->group_rows != 256) return VQ_ERR_UNSUPPORTED;
   } else if (is_i8(*d)) {
     if (d->k == 64) {
       if (d->group_rows != 8 && d->group_rows != 16 && d->group_rows != 32) return VQ_ERR_UNSUPPORTED;
@@ -136,6 +141,12 @@ int vq_layout_bytes(const vq_desc* desc, size_t* idx_bytes, size_t* cb_bytes) {
                                : (size_t)(desc->out_features / desc->group_rows) * n_quads * 528;
     return VQ_OK;
   }
+  if (desc->d == 4) {    // 1 KB of indices per (8-row block, pair of col-blocks); tables as in the canonical buffer
+    const size_t n_groups = (size_t)(desc->out_features / desc->group_rows) * n_cb;
+    if (idx_bytes) *idx_bytes = n_rb * ((n_cb + 1) / 2) * 1024;
+    if (cb_bytes) *cb_bytes = n_groups * 1024 + (2 * n_groups + 15) / 16 * 16;
+    return VQ_OK;
+  }
   if (desc->d == 1) {    // 1 KB of indices and 16 fp16 scalars per group
     if (idx_bytes) *idx_bytes = n_rb * n_cb * 1024;
     if (cb_bytes) *cb_bytes = n_rb * n_cb * 32;
@@ -183,6 +194,31 @@ int vq_gemv_multi(int count, const vq_desc* descs, const void* const* idx_dev,
       if (c > max_n_cb) max_n_cb = c;
     }
     const int fmt = format_tag(descs[0]);
+    if (fmt == kFmtD4) {   // one workgroup per 64 rows, see vq_gemv_d4.hip
+      GemvBatch batch;
+      memset(&batch, 0, offsetof(GemvBatch, p) + (size_t)n * sizeof(GemvProblem));
+      batch.count = n;
+      batch.y_f32 = (y_dtype == VQ_F32);
+      long long wgs = 0;
+      for (int i = 0; i < n; ++i) {
+        const vq_desc& d = descs[first + i];
+        GemvProblem& p = batch.p[i];
+        p.idx = (const uint8_t*)idx_dev[first + i];
+        p.cb = (const uint32_t*)cb_dev[first + i];
+        p.x = (const uint16_t*)x_f16[first + i];
+        p.y = y[first + i];
+        p.n_rb = d.out_features / kGroupRows;
+        p.n_cb = d.in_features / kGroupCols;
+        p.splits = 1;
+        p.rb_per_cb = d.group_rows / kGroupRows;
+        p.wg_begin = (int32_t)wgs;
+        wgs += p.n_rb / 8;
+      }
+      if (wgs > 0x7fffffffll) return VQ_ERR_UNSUPPORTED;
+      batch.total_wgs = (int32_t)wgs;
+      if (launch_gemv_d4(batch, (int)wgs, (hipStream_t)stream) != hipSuccess) return VQ_ERR_HIP;
+      continue;
+    }
     const long long stream_from = 4096;   // row-blocks from which the persistent kernel pays
     // Split-K kernel: `splits` waves share a row-block.  A wave is most efficient with exactly
     // one full chunk (its fixed costs are spread over 8 groups and nothing is double-buffered),

@@ -291,6 +291,16 @@ __device__ __forceinline__ void k64_group_scaled(uint32_t d0, uint32_t d1, uint3
   }
 }
 
+// ---- d = 4 device layout (k = 256, int8 tables) ---------------------------------------------
+// A lane owns ONE vector per row of a group: columns 4L .. 4L+3, one index byte.  Indices:
+// per (8-row block, pair of col-blocks) 1 KB; the lane's 16 bytes are its 8 row bytes of the
+// first col-block, then of the second (zero if the matrix has an odd number of col-blocks).
+// Tables: as in the canonical buffer, 1 KB of int8 (256 entries x 4) per group in group order,
+// then one fp16 scale per group.
+__device__ __forceinline__ uint2 d4_dequant_entry(uint32_t four_bytes, _Float16 scale) {
+  return make_uint2(k64_dequant_pair(four_bytes, scale), k64_dequant_pair(four_bytes >> 16, scale));
+}
+
 // Pairs of col-blocks a k=16 row-block is stored as (the last one half-empty if n_cb is odd).
 __host__ __device__ __forceinline__ int k16_pairs(int n_cb) { return (n_cb + 1) >> 1; }
 

@@ -38,7 +38,8 @@ __device__ __forceinline__ int wt_half_index(int m, int k) {   // k in halfs
 // K is the kernel format tag: 16 / 256 (fp16 codebooks), 64 (6-bit indices, int8 tables with a
 // scale per group, groups of 8*rpc rows), kFmtK16I8 (k = 16 with int8 tables).
 template <int K> constexpr int lut_dwords() {
-  return K == kFmtK16I8 ? 16 : K == kFmtD1K16 ? 256 : K == kFmtK64BN ? 80 : K;   // BN: 64 centroids + 16 levels
+  // BN: 64 centroids + 16 levels; d = 4: 256 entries of 4 halfs
+  return K == kFmtK16I8 ? 16 : K == kFmtD1K16 ? 256 : K == kFmtK64BN ? 80 : K == kFmtD4 ? 512 : K;
 }
 
 // What one wave needs to decode one group: the lane's index bytes and codebook piece.
@@ -60,6 +61,11 @@ template <> struct GroupRegs<kFmtK64BN> {
   uint32_t d0, d1, d2, two, sc;   // as for k = 64
   uint32_t cw;           // the lane's block codes of this col-block, row r in bits [4r, 4r+4)
   uint32_t lev;          // block-scale level lane & 15 (fp16)
+};
+template <> struct GroupRegs<kFmtD4> {
+  uint2 w;        // the lane's 8 index bytes (one vector per row)
+  uint4 q;        // table entries 4*lane .. 4*lane+3 (int8 x 4 each)
+  uint32_t sc;    // the group's fp16 scale
 };
 template <> struct GroupRegs<kFmtD1K16> {
   uint4 w;
@@ -86,6 +92,12 @@ __device__ __forceinline__ void load_group(GroupRegs<K>& g, const uint8_t* idx, 
     g.w = *reinterpret_cast<const uint2*>(idx + (size_t)rb * slots * 512 + k16_chunk_offset(c, lane));
     g.two = *reinterpret_cast<const uint16_t*>(tabs + ((size_t)rb * slots + c) * 32 + (lane & 15) * 2);
     g.sc = reinterpret_cast<const uint16_t*>(tabs + (size_t)n_rb * slots * 32)[(size_t)rb * slots + c];
+  } else if constexpr (K == kFmtD4) {
+    const uint8_t* tab = reinterpret_cast<const uint8_t*>(cb);
+    const size_t gi = (size_t)(rb / rpc) * n_cb + c, n_groups = (size_t)(n_rb / rpc) * n_cb;
+    g.w = *reinterpret_cast<const uint2*>(idx + ((size_t)rb * ((n_cb + 1) >> 1) + (c >> 1)) * 1024 + lane * 16 + (c & 1) * 8);
+    g.q = *reinterpret_cast<const uint4*>(tab + gi * 1024 + lane * 16);
+    g.sc = reinterpret_cast<const uint16_t*>(tab + n_groups * 1024)[gi];
   } else if constexpr (K == kFmtD1K16) {
     const size_t gi = (size_t)rb * n_cb + c;
     const uint8_t* cg = reinterpret_cast<const uint8_t*>(cb) + gi * 32;
@@ -124,7 +136,21 @@ __device__ __forceinline__ void decode_group(const GroupRegs<K>& g, uint32_t* lu
                                              int m0, int lane) {
   const char* lutb = reinterpret_cast<const char*>(lut);
   uint32_t v[16];
-  if constexpr (K == 64 || K == kFmtK64BN) {
+  if constexpr (K == kFmtD4) {
+    uint2* lut2 = reinterpret_cast<uint2*>(lut);
+    const _Float16 scale = __builtin_bit_cast(_Float16, (uint16_t)g.sc);
+    lut2[4 * lane] = d4_dequant_entry(g.q.x, scale);
+    lut2[4 * lane + 1] = d4_dequant_entry(g.q.y, scale);
+    lut2[4 * lane + 2] = d4_dequant_entry(g.q.z, scale);
+    lut2[4 * lane + 3] = d4_dequant_entry(g.q.w, scale);
+    wave_lds_sync();
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+      const uint2 t = lut2[((r < 4 ? g.w.x : g.w.y) >> (8 * (r & 3))) & 0xffu];
+      v[2 * r] = t.x;
+      v[2 * r + 1] = t.y;
+    }
+  } else if constexpr (K == 64 || K == kFmtK64BN) {
     lut[lane] = k64_dequant_pair(g.two, __builtin_bit_cast(_Float16, (uint16_t)g.sc));
     if constexpr (K == kFmtK64BN) {
       if (lane < 16) lut[64 + lane] = g.lev * 0x10001u;
@@ -709,6 +735,7 @@ hipError_t launch_gemm(const vq_desc& d, const void* idx_dev, const void* cb_dev
   if (fmt == kFmtK16I8) VQ_GEMM_DISPATCH(kFmtK16I8)
   if (fmt == kFmtD1K16) VQ_GEMM_DISPATCH(kFmtD1K16)
   if (fmt == kFmtK64BN) VQ_GEMM_DISPATCH(kFmtK64BN)
+  if (fmt == kFmtD4) VQ_GEMM_DISPATCH(kFmtD4)
   if (fmt == 16) VQ_GEMM_DISPATCH(16)
   VQ_GEMM_DISPATCH(256)
 #undef VQ_GEMM_DISPATCH

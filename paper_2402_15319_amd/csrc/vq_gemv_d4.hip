@@ -1,0 +1,110 @@
+// Batch-1 product y = W x for four-dimensional vector quantisation (Sec. 2.1 with d = 4; the
+// 4D rows of the appendix table of VQ configurations): k = 256, one index byte per 4 weights,
+// int8 tables with a scale (Sec. 3.1), groups of 64, 128 or 256 rows x 256 columns.
+//
+// A table is 256 entries x 4 values, far too large to rebuild per 8-row strip (a strip holds
+// 512 bytes of indices per col-block, the table is 1 KB), so the unit of work is a workgroup of
+// 8 waves that owns 64 consecutive rows (8 row-blocks of ONE group row): per pair of col-blocks
+// the 512 threads dequantise the two tables once (one entry each: int8 x 4 -> fp16 x 4, times
+// the scale, 8 bytes into LDS), a barrier, and every wave does its 16 lookups per lane (one
+// 8-byte LDS read returns the four weights of a vector) and 32 dot2 steps.  The tables are
+// double-buffered, so one barrier per pair of col-blocks is enough; indices, activations and
+// the next table entry are loaded one step ahead.  A lane owns columns 4L .. 4L+3 of a
+// col-block and keeps 8 row accumulators, reduced over the wave at the end exactly as in the
+// other GEMV kernels.
+#include "vq_device.h"
+#include "vq_internal.h"
+
+namespace vq {
+namespace {
+
+__device__ __forceinline__ int find_problem_d4(const GemvBatch& batch, int item) {
+  int lo = 0, hi = batch.count;
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (batch.p[mid].wg_begin <= item) lo = mid; else hi = mid;
+  }
+  return lo;
+}
+
+struct D4Step {
+  uint4 w;        // the lane's 8 + 8 index bytes of the pair
+  uint2 xa, xb;   // its activations in the two col-blocks
+  uint32_t q;     // this thread's table entry (4 int8) of col-block (tid >> 8) of the pair
+  uint32_t sc;    // that table's fp16 scale
+};
+
+__global__ __launch_bounds__(512) void gemv_d4_kernel(const GemvBatch batch) {
+  __shared__ __attribute__((aligned(16))) uint2 tabs[2][2][256];   // [buffer][col-block of the pair][entry]
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const GemvProblem& P = batch.p[find_problem_d4(batch, blockIdx.x)];
+  const int oct = blockIdx.x - P.wg_begin;          // which 64 rows
+  const int n_cb = P.n_cb, n_pairs = (n_cb + 1) >> 1;
+  const int rb = oct * 8 + wave;                    // n_rb is a multiple of 8 (groups are >= 64 rows)
+  const long long grow = (long long)(oct * 8) / P.rb_per_cb;
+  const uint8_t* tab = reinterpret_cast<const uint8_t*>(P.cb);
+  const long long n_groups = (long long)(P.n_rb / P.rb_per_cb) * n_cb;
+  const uint16_t* scales = reinterpret_cast<const uint16_t*>(tab + n_groups * 1024);
+  const uint8_t* idx_lane = P.idx + (size_t)rb * n_pairs * 1024 + lane * 16;
+  const uint16_t* x_lane = P.x + lane * 4;
+  const int h = tid >> 8, e = tid & 255;            // table duty of this thread
+
+  auto load = [&](int p, D4Step& s) {
+    const int c0 = 2 * p, c1 = 2 * p + 1;
+    const bool ok1 = c1 < n_cb;
+    const int cme = (h == 0 || ok1) ? c0 + h : c0;  // an absent second col-block re-reads the first (not used)
+    const long long g = grow * n_cb + cme;
+    s.w = *reinterpret_cast<const uint4*>(idx_lane + (size_t)p * 1024);
+    s.xa = *reinterpret_cast<const uint2*>(x_lane + (size_t)c0 * 256);
+    const uint2 xb = *reinterpret_cast<const uint2*>(x_lane + (size_t)(ok1 ? c1 : c0) * 256);
+    s.xb = ok1 ? xb : make_uint2(0u, 0u);
+    s.q = *reinterpret_cast<const uint32_t*>(tab + g * 1024 + e * 4);
+    s.sc = scales[g];
+  };
+
+  float acc[8];
+#pragma unroll
+  for (int r = 0; r < 8; ++r) acc[r] = 0.f;
+
+  D4Step cur, nxt;
+  load(0, cur);
+  for (int p = 0; p < n_pairs; ++p) {
+    load(p + 1 < n_pairs ? p + 1 : p, nxt);         // one step ahead (a harmless re-read at the end)
+    const int buf = p & 1;
+    const bool mine = h == 0 || 2 * p + 1 < n_cb;   // the absent col-block of an odd matrix gets a zero table
+    tabs[buf][h][e] = mine ? d4_dequant_entry(cur.q, __builtin_bit_cast(_Float16, (uint16_t)cur.sc))
+                           : make_uint2(0u, 0u);
+    __syncthreads();   // tables of this step complete; the other buffer is free again (see header)
+    const uint2* T0 = tabs[buf][0];
+    const uint2* T1 = tabs[buf][1];
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+      const uint32_t j0 = ((r < 4 ? cur.w.x : cur.w.y) >> (8 * (r & 3))) & 0xffu;
+      const uint32_t j1 = ((r < 4 ? cur.w.z : cur.w.w) >> (8 * (r & 3))) & 0xffu;
+      const uint2 t0 = T0[j0], t1 = T1[j1];
+      acc[r] = dot2(t0.x, cur.xa.x, acc[r]);
+      acc[r] = dot2(t0.y, cur.xa.y, acc[r]);
+      acc[r] = dot2(t1.x, cur.xb.x, acc[r]);
+      acc[r] = dot2(t1.y, cur.xb.y, acc[r]);
+    }
+    cur = nxt;
+  }
+
+  const float v = wave_reduce8(acc, lane);   // every lane: the total of row (lane >> 3) & 7
+  if ((lane & 7) == 0) {
+    const size_t o = (size_t)rb * 8 + (lane >> 3);
+    if (batch.y_f32) reinterpret_cast<float*>(P.y)[o] = v;
+    else reinterpret_cast<_Float16*>(P.y)[o] = (_Float16)v;
+  }
+}
+
+}  // namespace
+
+hipError_t launch_gemv_d4(const GemvBatch& batch, int total_wgs, hipStream_t s) {
+  hipLaunchKernelGGL(gemv_d4_kernel, dim3((unsigned)total_wgs), dim3(512), 0, s, batch);
+  return hipGetLastError();
+}
+
+}  // namespace vq

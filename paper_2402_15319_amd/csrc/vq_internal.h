@@ -17,8 +17,11 @@ constexpr int kMaxProblemsPerLaunch = 256;  // the problem table travels in the 
 constexpr int kFmtK16I8 = 1016;
 constexpr int kFmtD1K16 = 2016;
 constexpr int kFmtK64BN = 3064;   // k = 64, int8 tables + scale, blockwise normalisation (blocks of 32)
+constexpr int kFmtD4 = 4256;      // d = 4, k = 256 (one index byte per 4 weights), int8 tables + scale,
+                                  // groups of 64, 128 or 256 rows x 256 columns
 inline int format_tag(const vq_desc& d) {
   if (d.d == 1) return kFmtD1K16;
+  if (d.d == 4) return kFmtD4;
   if (d.codebook_dtype == VQ_I8_BN) return kFmtK64BN;
   if (d.k == 16 && d.codebook_dtype == VQ_I8) return kFmtK16I8;
   return d.k;
@@ -63,6 +66,8 @@ size_t gemv_stream_lds_bytes(int fmt, int max_n_cb);
 int gemv_stream_resident_wgs(int fmt, int max_n_cb);
 // Units (col-block pairs, quads or col-blocks, by format) that one chunk of the GEMV kernels holds.
 int gemv_chunk_units(int fmt);
+// d = 4: its own GEMV kernel (workgroups share a group's table; see vq_gemv_d4.hip).
+hipError_t launch_gemv_d4(const GemvBatch& batch, int total_wgs, hipStream_t s);
 hipError_t launch_gemm(const vq_desc& d, const void* idx_dev, const void* cb_dev,
                        const void* X, int B, int ldx, void* Y, int ldy, int y_f32,
                        hipStream_t s);

@@ -193,6 +193,44 @@ __global__ __launch_bounds__(256) void pack_codes64_kernel(const uint8_t* __rest
   dev[t] = w;
 }
 
+// d = 4 indices: canonical group (row of groups, c) holds group_rows x 64 bytes, byte r*64 + L =
+// row r, vector L.  One thread per (8-row block, pair of col-blocks, lane).
+__global__ __launch_bounds__(256) void pack_idx_d4_kernel(const uint8_t* __restrict__ canon,
+                                                          uint8_t* __restrict__ dev, int n_cb,
+                                                          long long n_rb8, int rpc) {
+  const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
+  const long long slot = t >> 6;
+  const int lane = (int)(t & 63);
+  const int n_pairs = (n_cb + 1) >> 1;
+  if (slot >= n_rb8 * n_pairs) return;
+  const long long rb8 = slot / n_pairs;
+  const int p = (int)(slot - rb8 * n_pairs);
+  const long long grow = rb8 / rpc;
+  const int sub = (int)(rb8 - grow * rpc);
+  uint32_t w[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const int c = 2 * p + h;
+    if (c >= n_cb) continue;
+    const uint8_t* g = canon + (size_t)(grow * n_cb + c) * ((size_t)rpc * 8 * 64) + (size_t)sub * 8 * 64 + lane;
+#pragma unroll
+    for (int r = 0; r < 8; ++r) w[2 * h + (r >> 2)] |= (uint32_t)g[r * 64] << (8 * (r & 3));
+  }
+  *reinterpret_cast<uint4*>(dev + (size_t)slot * 1024 + lane * 16) = make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+// Plain copy of n16 16-byte pieces (the last one may be partial in the source: src_bytes).
+__global__ __launch_bounds__(256) void copy16_kernel(const uint8_t* __restrict__ src, uint8_t* __restrict__ dst,
+                                                     long long n16, long long src_bytes) {
+  const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (t >= n16) return;
+  if ((t + 1) * 16 <= src_bytes) {
+    reinterpret_cast<uint4*>(dst)[t] = reinterpret_cast<const uint4*>(src)[t];
+  } else {
+    for (int i = 0; i < 16; ++i) dst[t * 16 + i] = t * 16 + i < src_bytes ? src[t * 16 + i] : (uint8_t)0;
+  }
+}
+
 // Reads n16 16-byte pieces once (non-temporal) and keeps the optimiser from dropping the loads.
 typedef unsigned int probe_u32x4_t __attribute__((ext_vector_type(4)));
 __global__ __launch_bounds__(256) void stream_read_kernel(const probe_u32x4_t* __restrict__ p,
@@ -224,6 +262,20 @@ hipError_t launch_pack(const vq_desc& d, const void* idx_canon, const void* cb_c
                        void* idx_dev, void* cb_dev, hipStream_t s) {
   const int n_cb = d.in_features / kGroupCols;
   const long long n_rb = d.out_features / kGroupRows;
+  if (d.d == 4) {
+    const int rpc = d.group_rows / kGroupRows;
+    const long long n_groups = (long long)(d.out_features / d.group_rows) * n_cb;
+    const int n_pairs = (n_cb + 1) / 2;
+    hipLaunchKernelGGL(pack_idx_d4_kernel, dim3((unsigned)((n_rb * n_pairs * 64 + 255) / 256)), dim3(256), 0, s,
+                       (const uint8_t*)idx_canon, (uint8_t*)idx_dev, n_cb, n_rb, rpc);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const long long src_bytes = n_groups * 1024 + 2 * n_groups;      // tables (a multiple of 16), then scales
+    const long long n16 = (src_bytes + 15) / 16;
+    hipLaunchKernelGGL(copy16_kernel, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, s,
+                       (const uint8_t*)cb_canon, (uint8_t*)cb_dev, n16, src_bytes);
+    return hipGetLastError();
+  }
   if (d.k == 64) {
     const int rpc = d.group_rows / kGroupRows;
     const long long n_grow = d.out_features / d.group_rows;

@@ -64,7 +64,9 @@ A = 0x1000  # a fake, 16-byte aligned, non-NULL address; validation fails before
     (dict(k=32), -2),                 # k != 2^index_bits
     (dict(out_features=0), -2),
     (dict(index_bits=0), -2),
-    (dict(d=4), -3),
+    (dict(d=4), -3),                                                      # d = 4 needs k = 256, int8 tables
+    (dict(d=4, k=256, index_bits=8, codebook_dtype=3), -3),               # ... and groups of 64, 128 or 256 rows
+    (dict(d=4, k=256, index_bits=8, group_rows=256), -3),                 # fp16 tables: not implemented
     (dict(d=1, k=256, index_bits=8), -3),                                 # scalar codebooks: k = 16 only
     (dict(d=1, codebook_dtype=3), -3),                                    # ... with fp16 values
     (dict(d=1, group_rows=32), -3),
@@ -216,3 +218,19 @@ def test_block_normalised_representation_sizes_and_validation():
     bad = vq.make_desc(4096, 4096, 16, 4, codebook_dtype=vq.VQ_I8_BN)
     assert L.vq_gemv(ctypes.byref(bad), A, A, A, A + 16, vq.VQ_F16, 0) == -3
     assert L.vq_em_assign(ctypes.byref(vq.make_desc(4096, 4096, 64, 6, codebook_dtype=vq.VQ_I8_BN)), A, A + 4, A, A, 0) == -4
+
+
+def test_four_dimensional_representation_sizes_and_entry_points():
+    """d = 4, k = 256, int8 tables + scale: canonical = out*in/4 index bytes + 1 KB + 2 B per group;
+    device = 1 KB of indices per (8-row block, pair of col-blocks), tables as canonical (padded)."""
+    L = vq.lib()
+    for out_f, in_f, rows in ((4096, 4096, 256), (4096, 11008, 256), (11008, 4096, 256), (128, 768, 64)):
+        d = vq.make_desc(out_f, in_f, 256, 8, group_rows=rows, d=4, codebook_dtype=vq.VQ_I8)
+        n_groups = (out_f // rows) * (in_f // 256)
+        assert vq.vq_canonical_bytes(d) == (out_f * in_f // 4, n_groups * 1024 + 2 * n_groups)
+        pairs = (in_f // 256 + 1) // 2
+        assert vq.vq_layout_bytes(d) == ((out_f // 8) * pairs * 1024, n_groups * 1024 + (2 * n_groups + 15) // 16 * 16)
+        r = ctypes.byref(d)
+        assert L.vq_gemv(r, A, A, A + 2, A + 16, vq.VQ_F16, 0) == -4
+        assert L.vq_gemm_batched(r, A, A, A, 16, 20, A + 16, 16, vq.VQ_F16, 0) == -4
+        assert L.vq_decode_dense(r, A, A, A + 2, 0) == -4

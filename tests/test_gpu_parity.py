@@ -663,3 +663,73 @@ def test_block_norm_deployed_shape(env):
     Y = _gpu_gemm(env, desc, idx_d, cb_d, X, False)
     cols = np.random.default_rng(4).choice(2048, size=48, replace=False)
     assert oracle.normwise_rel_err(Y[:, cols], _dense_product(W, X[:, cols])) <= TOL_F16
+
+
+# ---------------------------------------------------------------- four-dimensional vectors (d = 4, k = 256, int8 tables)
+def _shape_d4(o, i, rows=256):
+    return workloads.VQShape(o, i, 256, 8, rows, 256, 4, True)
+
+
+# odd and even col-block counts (an odd one leaves half a pair empty), every group height,
+# several workgroups (64 rows each), more than one row of groups
+D4_SMALL = [_shape_d4(64, 256, 64), _shape_d4(128, 768, 64), _shape_d4(128, 512, 128), _shape_d4(256, 1280),
+            _shape_d4(512, 2816), _shape_d4(384, 1024, 128)]
+
+
+@pytest.mark.parametrize("s", D4_SMALL, ids=str)
+def test_d4_decode_bit_exact(env, s):
+    desc, idx, cb, idx_d, cb_d = _setup_i8(env, s, 720)
+    np.testing.assert_array_equal(_gpu_decode(env, desc, idx_d, cb_d), oracle.decode_dense(_fmt(s), idx, cb))
+
+
+@pytest.mark.parametrize("f32", [False, True], ids=["y16", "y32"])
+@pytest.mark.parametrize("s", D4_SMALL, ids=str)
+def test_d4_gemv(env, s, f32):
+    desc, idx, cb, idx_d, cb_d = _setup_i8(env, s, 721)
+    x = workloads.make_x(s.in_features, 721)
+    y = _gpu_gemv(env, desc, idx_d, cb_d, x, f32)
+    assert oracle.normwise_rel_err(y, oracle.gemv(_fmt(s), idx, cb, x)) <= (TOL_F32 if f32 else TOL_F16)
+
+
+def test_d4_gemv_multi_mixed_group_heights(env):
+    """Several d = 4 problems in one launch, group heights 64 / 128 / 256 side by side."""
+    torch, vq, vqdev = env
+    shapes = [_shape_d4(128, 512, 64), _shape_d4(256, 768, 128), _shape_d4(512, 256), _shape_d4(64, 1280, 64)] * 3
+    descs, idxs, cbs, xs, ys, refs = [], [], [], [], [], []
+    for i, s in enumerate(shapes):
+        desc, idx, cb, idx_d, cb_d = _setup_i8(env, s, 730 + i)
+        x = workloads.make_x(s.in_features, 730 + i)
+        descs.append(desc); idxs.append(idx_d); cbs.append(cb_d)
+        xs.append(vqdev.to_device_bytes(x))
+        ys.append(torch.zeros(s.out_features, dtype=torch.float16, device="cuda:0"))
+        refs.append(oracle.gemv(_fmt(s), idx, cb, x))
+    vq.vq_gemv_multi(descs, idxs, cbs, xs, ys)
+    torch.cuda.synchronize()
+    for i, ref in enumerate(refs):
+        assert oracle.normwise_rel_err(ys[i].cpu().numpy(), ref) <= TOL_F16, i
+
+
+@pytest.mark.parametrize("B", [1, 16, 40, 130, 600, 1300])
+@pytest.mark.parametrize("s", [_shape_d4(128, 768, 64), _shape_d4(768, 512, 128)], ids=str)
+def test_d4_gemm(env, s, B):
+    desc, idx, cb, idx_d, cb_d = _setup_i8(env, s, 722)
+    X = workloads.make_X(s.in_features, B, 722)
+    Y = _gpu_gemm(env, desc, idx_d, cb_d, X, False, pad=8 if B == 40 else 0)
+    assert oracle.normwise_rel_err(Y, oracle.gemm(_fmt(s), idx, cb, X)) <= TOL_F16
+
+
+def test_d4_full_size_layer(env):
+    """4096 x 11008 (43 col-blocks), 256 x 256 groups, the 2.125 bpv setting: decode in full, GEMV,
+    24 and 100 batch columns (tall-matrix kernels), 48 sampled columns of B = 2048."""
+    s = workloads.CONFIGS["mlp_down_4096x11008_d4"]
+    desc, idx, cb, idx_d, cb_d = _setup_i8(env, s, 723)
+    f = _fmt(s)
+    W = oracle.decode_dense(f, idx, cb)
+    np.testing.assert_array_equal(_gpu_decode(env, desc, idx_d, cb_d), W)
+    x = workloads.make_x(s.in_features, 723)
+    assert oracle.normwise_rel_err(_gpu_gemv(env, desc, idx_d, cb_d, x, False), _dense_product(W, x)) <= TOL_F16
+    for B in (24, 100, 2048):
+        X = workloads.make_X(s.in_features, B, 723)
+        Y = _gpu_gemm(env, desc, idx_d, cb_d, X, False)
+        cols = np.random.default_rng(5).choice(B, size=min(B, 48), replace=False)
+        assert oracle.normwise_rel_err(Y[:, cols], _dense_product(W, X[:, cols])) <= TOL_F16, B
