@@ -212,6 +212,9 @@ def main():
                 # per group and a 4-bit code per 32 weights, 3.28 bits per value
                 ("llama7b_pass_k64_int8_tables_block_norm_3.28bpv_via_vq_gemv_multi", workloads.LLAMA7B_LAYER_K64_BN,
                  "gemv_stream_kernel<64,bn>"),
+                # four-dimensional vectors: k = 256, one index byte per 4 weights, 256 x 256 groups (2.125 bpv)
+                ("llama7b_pass_d4_k256_int8_tables_2.125bpv_via_vq_gemv_multi", workloads.LLAMA7B_LAYER_D4,
+                 "gemv_d4_kernel"),
                 # scalar codebooks (d = 1): 16 fp16 values per 8 x 256 group, 4-bit indices, 3.47 GB
                 ("llama7b_pass_d1_k16_4.125bpv_via_vq_gemv_multi", workloads.LLAMA7B_LAYER_D1_K16,
                  "gemv_stream_kernel<d1,k16>")):
@@ -222,7 +225,11 @@ def main():
                     desc = vqdev.desc_from_shape(s)
                     ib, cbb = vq.vq_layout_bytes(desc)
                     tab = torch.randint(0, 256, (cbb,), dtype=torch.uint8, device=dev)
-                    if s.d == 1:                        # fp16 scalars
+                    if s.d == 4:                        # 1 KB int8 tables per group, then fp16 scales (set to 2^-8)
+                        n_groups = (s.out_features // s.group_rows) * (s.in_features // 256)
+                        tab[n_groups * 1024:] = 0
+                        tab[n_groups * 1024 + 1:n_groups * 1026:2] = 0x1C
+                    elif s.d == 1:                      # fp16 scalars
                         tab = (torch.randn(cbb // 2, device=dev) * 0.02).half().view(torch.uint8)
                     elif s.block_norm:                  # 672-byte records (+ 64 levels, set to 1.0), then nibble codes
                         n_rec = (s.out_features // s.group_rows) * ((s.in_features // 256 + 3) // 4)

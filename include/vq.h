@@ -48,8 +48,10 @@
  * (32 rows: the 8,192-weight groups and 3.125 bits per value of Sec. 5.1); VQ_I8 with k = 16
  * and 8 x 256 groups (2.125 bits per value); and scalar codebooks, d = 1 (the 1D rows of the
  * appendix table of VQ configurations): VQ_F16, k = 16, 4-bit indices, 8 x 256 groups, 4.125
- * bits per value; VQ_I8_BN with k = 64 and groups of 8, 16 or 32 rows x 256 columns.  Every
- * entry point takes all of them.
+ * bits per value; VQ_I8_BN with k = 64 and groups of 8, 16 or 32 rows x 256 columns; and
+ * four-dimensional vectors, d = 4 (the 4D rows of that table): VQ_I8, k = 256 (one index byte per
+ * 4 weights), groups of 64, 128 or 256 rows x 256 columns (256 rows: 2.125 bits per value).
+ * Every entry point takes all of them.
  */
 #ifndef VQ_H_
 #define VQ_H_
@@ -83,10 +85,10 @@ typedef enum vq_dtype { VQ_F16 = 1, VQ_F32 = 2, VQ_I8 = 3, VQ_I8_BN = 4 } vq_dty
 typedef struct vq_desc {
   int32_t out_features;   /* rows of W (length of y)                                */
   int32_t in_features;    /* columns of W (length of x)                             */
-  int32_t group_rows;     /* 8 (VQ_I8: 8, 16 or 32)                                 */
+  int32_t group_rows;     /* 8 (k = 64: 8, 16 or 32; d = 4: 64, 128 or 256)         */
   int32_t group_cols;     /* 256 (Sec. 4: at most 256 columns per group)            */
-  int32_t d;              /* VQ dimensionality: 2, or 1 (scalar codebooks)          */
-  int32_t k;              /* centroids: 16 or 256 (VQ_F16), 64 or 16 (VQ_I8)        */
+  int32_t d;              /* VQ dimensionality: 2, 1 (scalar codebooks) or 4        */
+  int32_t k;              /* centroids: 16 or 256 (VQ_F16), 64 or 16 (VQ_I8), 256 (d = 4) */
   int32_t index_bits;     /* log2(k): 4, 8 or 6                                     */
   int32_t codebook_dtype; /* VQ_F16, VQ_I8 or VQ_I8_BN                              */
 } vq_desc;
