@@ -405,6 +405,25 @@ def test_scalar_codebook_equals_pair_table_of_twice_the_index_width():
         assert W[r, col] == c[g, nib, 0]
 
 
+def test_three_bit_scalar_codebook_equals_the_six_bit_pair_table():
+    """The same identity one size down: d = 1, k = 8 (3-bit) over the bytes of d = 2, k = 64 (6-bit),
+    T[j] = (c[j % 8], c[j // 8]); indices straddle byte boundaries here."""
+    rng = np.random.default_rng(42)
+    f1 = VQFormat(32, 512, 8, 3, 32, 256, 1)
+    f2 = VQFormat(32, 512, 64, 6, 32, 256, 2)
+    idx = rng.integers(0, 256, size=oracle.canonical_sizes(f1)[0], dtype=np.uint8)
+    assert oracle.canonical_sizes(f2)[0] == idx.size
+    q = rng.integers(-127, 128, size=(f1.n_groups, 8, 1), dtype=np.int8)
+    scale = np.array([0.01, 0.02], dtype=np.float16)
+    c = oracle.dequantise_codebooks(q, scale)
+    j = np.arange(64)
+    T = np.stack([c[:, j % 8, 0], c[:, j // 8, 0]], axis=2)
+    np.testing.assert_array_equal(oracle.decode_dense(f1, idx, c), oracle.decode_dense(f2, idx, T))
+    # the 3.125 row of the appendix table: 3 bits + (8 x 8-bit values per 8,192 weights) ~ 3.008; with the scale 3.0098
+    ib, tb = oracle.canonical_sizes_i8(VQFormat(4096, 4096, 8, 3, 32, 256, 1))
+    assert ib * 8 / 4096 ** 2 == 3.0 and tb == 2048 * 8 + 2048 * 2
+
+
 def test_scalar_format_sizes_follow_the_bpv_formula():
     """d = 1, k = 16, fp16 codebooks, 8 x 256 groups: 4 + 16*16/2048 = 4.125 bits per value
     (the total of the 1D 4.125 row of the appendix table, which reaches the same overhead with

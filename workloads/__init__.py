@@ -22,7 +22,7 @@ import numpy as np
 __all__ = [
     "VQShape", "CONFIGS", "LLAMA7B_LAYER", "seed_for", "canonical_sizes",
     "make_weights", "make_weights_i8", "make_x", "make_X", "llama7b_pass_shapes",
-    "LLAMA7B_LAYER_K64", "LLAMA7B_LAYER_K16_I8", "LLAMA7B_LAYER_D1_K16", "LLAMA7B_LAYER_K64_BN", "make_weights_bn", "LLAMA7B_LAYER_D4",
+    "LLAMA7B_LAYER_K64", "LLAMA7B_LAYER_K16_I8", "LLAMA7B_LAYER_D1_K16", "LLAMA7B_LAYER_K64_BN", "make_weights_bn", "LLAMA7B_LAYER_D4", "LLAMA7B_LAYER_D1_K8",
 ]
 
 
@@ -85,6 +85,10 @@ CONFIGS = {
     "attn_4096x4096_d1_k16": VQShape(4096, 4096, 16, 4, 8, 256, 1),
     "mlp_up_11008x4096_d1_k16": VQShape(11008, 4096, 16, 4, 8, 256, 1),
     "mlp_down_4096x11008_d1_k16": VQShape(4096, 11008, 16, 4, 8, 256, 1),
+    # scalar codebooks at 3 bits: k = 8 int8 values + scale per 32 x 256 group (the 1D 3.125 row)
+    "attn_4096x4096_d1_k8": VQShape(4096, 4096, 8, 3, 32, 256, 1, True),
+    "mlp_up_11008x4096_d1_k8": VQShape(11008, 4096, 8, 3, 32, 256, 1, True),
+    "mlp_down_4096x11008_d1_k8": VQShape(4096, 11008, 8, 3, 32, 256, 1, True),
     "tiny_64x512_k64_i8": VQShape(64, 512, 64, 6, 32, 256, 2, True),
     "attn_4096x4096_k64_i8": VQShape(4096, 4096, 64, 6, 32, 256, 2, True),
     "mlp_up_11008x4096_k64_i8": VQShape(11008, 4096, 64, 6, 32, 256, 2, True),
@@ -108,6 +112,7 @@ LLAMA7B_LAYER = (
 LLAMA7B_LAYER_K64 = tuple((n, k.replace("_k16", "_k64_i8")) for n, k in LLAMA7B_LAYER)
 LLAMA7B_LAYER_K16_I8 = tuple((n, k + "_i8") for n, k in LLAMA7B_LAYER)
 LLAMA7B_LAYER_K64_BN = tuple((n, k.replace("_k16", "_k64_bn")) for n, k in LLAMA7B_LAYER)
+LLAMA7B_LAYER_D1_K8 = tuple((n, k.replace("_k16", "_d1_k8")) for n, k in LLAMA7B_LAYER)
 LLAMA7B_LAYER_D4 = tuple((n, k.replace("_k16", "_d4")) for n, k in LLAMA7B_LAYER)
 LLAMA7B_LAYER_D1_K16 = tuple((n, k.replace("_k16", "_d1_k16")) for n, k in LLAMA7B_LAYER)
 LLAMA7B_N_LAYERS = 32
