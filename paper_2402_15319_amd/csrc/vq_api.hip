@@ -17,6 +17,8 @@ bool is_pow2(int v) { return v > 0 && (v & (v - 1)) == 0; }
 //   groups (2.125 bits per value);
 //   d = 1 (scalar codebooks): k = 16 fp16 values per 8 x 256 group, 4-bit indices (4.125 bits
 //   per value, the overhead of the 1D 4.125 row of the appendix table of VQ configurations);
+//   d = 1, k = 8: 3-bit indices, 8 int8 values + scale per group of 8, 16 or 32 rows x 256 columns
+//   (32 rows: the 1D 3.125 row of that table);
 //   d = 4: k = 256 (one index byte per 4 weights), int8 tables with a scale, groups of 64, 128 or
 //   256 rows x 256 columns (128 and 256: the 4D 2.25 and 2.125 rows of that table).
 bool is_i8(const vq_desc& d) { return d.codebook_dtype == VQ_I8 || d.codebook_dtype == VQ_I8_BN; }
@@ -32,7 +34,12 @@ int check_desc(const vq_desc* d) {
   if (d->codebook_dtype != VQ_F16 && !is_i8(*d)) return VQ_ERR_UNSUPPORTED;
   if ((d->d != 2 && d->d != 1 && d->d != 4) || d->group_cols != kGroupCols) return VQ_ERR_UNSUPPORTED;
   if (d->d == 1) {
-    if (d->k != 16 || is_i8(*d) || d->group_rows != kGroupRows) return VQ_ERR_UNSUPPORTED;
+    if (d->k == 8) {          // 3-bit indices, int8 values + scale, group heights of the k = 64 format
+      if (d->codebook_dtype != VQ_I8) return VQ_ERR_UNSUPPORTED;
+      if (d->group_rows != 8 && d->group_rows != 16 && d->group_rows != 32) return VQ_ERR_UNSUPPORTED;
+    } else if (d->k != 16 || is_i8(*d) || d->group_rows != kGroupRows) {
+      return VQ_ERR_UNSUPPORTED;
+    }
   } else if (d->d == 4) {
     if (d->k != 256 || d->codebook_dtype != VQ_I8) return VQ_ERR_UNSUPPORTED;
     if (d->group_rows != 64 && d->group_rows != 128 && d->group_rows != 256) return VQ_ERR_UNSUPPORTED;
@@ -73,7 +80,7 @@ void sizes(const vq_desc& d, size_t* idx_bytes, size_t* cb_bytes) {
 
 // Units a row-block of `n_cb` col-blocks is cut into (what the strips of the GEMV kernels count).
 int strip_units(int fmt, int n_cb) {
-  return (fmt == 16 || fmt == kFmtK16I8) ? (n_cb + 1) / 2 : (fmt == 64 || fmt == kFmtK64BN) ? (n_cb + 3) / 4 : n_cb;
+  return (fmt == 16 || fmt == kFmtK16I8) ? (n_cb + 1) / 2 : (fmt == 64 || fmt == kFmtK64BN || fmt == kFmtD1K8) ? (n_cb + 3) / 4 : n_cb;
 }
 
 int hip_status(hipError_t e) { return e == hipSuccess ? VQ_OK : VQ_ERR_HIP; }
@@ -145,6 +152,12 @@ int vq_layout_bytes(const vq_desc* desc, size_t* idx_bytes, size_t* cb_bytes) {
     const size_t n_groups = (size_t)(desc->out_features / desc->group_rows) * n_cb;
     if (idx_bytes) *idx_bytes = n_rb * ((n_cb + 1) / 2) * 1024;
     if (cb_bytes) *cb_bytes = n_groups * 1024 + (2 * n_groups + 15) / 16 * 16;
+    return VQ_OK;
+  }
+  if (desc->d == 1 && desc->k == 8) {   // indices as for k = 64; 48-byte table records per (group row, quad)
+    const size_t n_quads = (n_cb + 3) / 4;
+    if (idx_bytes) *idx_bytes = n_rb * n_quads * 3072;
+    if (cb_bytes) *cb_bytes = (size_t)(desc->out_features / desc->group_rows) * n_quads * 48;
     return VQ_OK;
   }
   if (desc->d == 1) {    // 1 KB of indices and 16 fp16 scalars per group

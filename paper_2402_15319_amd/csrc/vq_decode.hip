@@ -76,11 +76,15 @@ __global__ __launch_bounds__(256) void decode_kernel(const uint8_t* __restrict__
 // k = 64 (6-bit indices, int8 tables with a scale): one wave per (8-row block, col-block).
 // Lane L dequantises table entry L (fp16(scale * q), one rounding) and then copies.  BN: every
 // copied pair is first multiplied by the scale of its 32-weight block (one more fp16 rounding).
-template <bool BN>
+// MODE 0: k = 64; 1: with blockwise normalisation (BN); 2: d = 1, k = 8 (entry L of the pair table is
+// built from the group's 8 int8 values).
+template <int MODE>
 __global__ __launch_bounds__(256) void decode64_kernel(const uint8_t* __restrict__ idx,
                                                        const uint8_t* __restrict__ tab,
                                                        uint16_t* __restrict__ W, int n_cb,
                                                        long long n_items, int in_features, int rpc) {
+  constexpr bool BN = MODE == 1, D1 = MODE == 2;
+  constexpr int tab_bytes = BN ? kK64NQuadTabBytes : D1 ? kD1K8QuadTabBytes : kK64QuadTabBytes;
   __shared__ uint32_t lut_all[4][BN ? 80 : 64];
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
@@ -90,7 +94,7 @@ __global__ __launch_bounds__(256) void decode64_kernel(const uint8_t* __restrict
   const long long rb8 = item / n_cb;
   const int c = (int)(item - rb8 * n_cb);
   const int n_quads = k64_quads(n_cb), q = c >> 2, j = c & 3;
-  const uint8_t* tq = tab + (size_t)((rb8 / rpc) * n_quads + q) * (BN ? kK64NQuadTabBytes : kK64QuadTabBytes);
+  const uint8_t* tq = tab + (size_t)((rb8 / rpc) * n_quads + q) * tab_bytes;
   uint32_t cw = 0;
   if (BN) {
     const long long n_rb8 = n_items / n_cb;
@@ -98,8 +102,10 @@ __global__ __launch_bounds__(256) void decode64_kernel(const uint8_t* __restrict
     cw = *reinterpret_cast<const uint32_t*>(tab + (size_t)(n_rb8 / rpc) * n_quads * kK64NQuadTabBytes +
                                             (size_t)(rb8 * n_quads + q) * kK64NQuadCodeBytes + (lane >> 3) * 16 + j * 4);
   }
-  const uint32_t two = *reinterpret_cast<const uint16_t*>(tq + j * 128 + lane * 2);
-  const _Float16 scale = __builtin_bit_cast(_Float16, *reinterpret_cast<const uint16_t*>(tq + 512 + 2 * j));
+  const uint32_t two = D1 ? d1k8_pair(*reinterpret_cast<const uint2*>(tq + j * 8), lane)
+                          : (uint32_t)*reinterpret_cast<const uint16_t*>(tq + j * 128 + lane * 2);
+  const _Float16 scale = __builtin_bit_cast(
+      _Float16, *reinterpret_cast<const uint16_t*>(tq + (D1 ? kD1K8ScaleOffset : 512) + 2 * j));
   lut[lane] = k64_dequant_pair(two, scale);
   const uint8_t* iq = idx + (size_t)(rb8 * n_quads + q) * kK64QuadIdxBytes + lane * 16;
   uint32_t d[12];
@@ -183,15 +189,15 @@ hipError_t launch_decode(const vq_desc& d, const void* idx_dev, const void* cb_d
                        d.group_rows / kGroupRows);
     return hipGetLastError();
   }
-  if (fmt == 64 || fmt == kFmtK64BN) {
-    if (fmt == 64)
-      hipLaunchKernelGGL(decode64_kernel<false>, dim3(grid), dim3(256), 0, s, (const uint8_t*)idx_dev,
-                         (const uint8_t*)cb_dev, (uint16_t*)W, n_cb, n_groups, d.in_features,
-                         d.group_rows / kGroupRows);
-    else
-      hipLaunchKernelGGL(decode64_kernel<true>, dim3(grid), dim3(256), 0, s, (const uint8_t*)idx_dev,
-                         (const uint8_t*)cb_dev, (uint16_t*)W, n_cb, n_groups, d.in_features,
-                         d.group_rows / kGroupRows);
+  if (fmt == 64 || fmt == kFmtK64BN || fmt == kFmtD1K8) {
+#define VQ_DECODE64(MODE)                                                                            \
+    hipLaunchKernelGGL(decode64_kernel<MODE>, dim3(grid), dim3(256), 0, s, (const uint8_t*)idx_dev, \
+                       (const uint8_t*)cb_dev, (uint16_t*)W, n_cb, n_groups, d.in_features,         \
+                       d.group_rows / kGroupRows)
+    if (fmt == 64) VQ_DECODE64(0);
+    else if (fmt == kFmtK64BN) VQ_DECODE64(1);
+    else VQ_DECODE64(2);
+#undef VQ_DECODE64
     return hipGetLastError();
   }
 #define VQ_DECODE(K)                                                                                \

@@ -245,6 +245,11 @@ constexpr int kK64QuadTabBytes = 528;
 // sit the 4-bit block codes, 128 bytes per (8-row block, quad): dword 4*b + j holds the codes of
 // block b (lanes 8b .. 8b+7) of col-block j, row r in bits [4r, 4r+4), so a lane's four dwords
 // are one 16-byte load.
+// d = 1, k = 8 (3-bit indices; two neighbouring indices form the 6-bit index of the pair table
+// T[j] = (c[j % 8], c[j / 8])): indices as for k = 64; the table record of a (group row, quad)
+// is 48 bytes: four tables of 8 int8 values, four fp16 scales, 8 bytes of padding.
+constexpr int kD1K8QuadTabBytes = 48;
+constexpr int kD1K8ScaleOffset = 32;
 constexpr int kK64NQuadTabBytes = 672;
 constexpr int kK64NLevelOffset = 528;
 constexpr int kK64NQuadCodeBytes = 128;
@@ -299,6 +304,13 @@ __device__ __forceinline__ void k64_group_scaled(uint32_t d0, uint32_t d1, uint3
 // then one fp16 scale per group.
 __device__ __forceinline__ uint2 d4_dequant_entry(uint32_t four_bytes, _Float16 scale) {
   return make_uint2(k64_dequant_pair(four_bytes, scale), k64_dequant_pair(four_bytes >> 16, scale));
+}
+
+// d = 1, k = 8: the int8 pair (c[e % 8], c[e / 8]) of pair-table entry e from the group's 8 values.
+__device__ __forceinline__ uint32_t d1k8_pair(uint2 c8, int e) {
+  const uint32_t lo = ((e & 4) ? c8.y : c8.x) >> (8 * (e & 3));
+  const uint32_t hi = ((e & 32) ? c8.y : c8.x) >> (8 * ((e >> 3) & 3));
+  return (lo & 0xffu) | ((hi & 0xffu) << 8);
 }
 
 // Pairs of col-blocks a k=16 row-block is stored as (the last one half-empty if n_cb is odd).

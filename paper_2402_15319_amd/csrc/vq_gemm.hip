@@ -39,7 +39,7 @@ __device__ __forceinline__ int wt_half_index(int m, int k) {   // k in halfs
 // scale per group, groups of 8*rpc rows), kFmtK16I8 (k = 16 with int8 tables).
 template <int K> constexpr int lut_dwords() {
   // BN: 64 centroids + 16 levels; d = 4: 256 entries of 4 halfs
-  return K == kFmtK16I8 ? 16 : K == kFmtD1K16 ? 256 : K == kFmtK64BN ? 80 : K == kFmtD4 ? 512 : K;
+  return K == kFmtK16I8 ? 16 : K == kFmtD1K16 ? 256 : K == kFmtK64BN ? 80 : K == kFmtD4 ? 512 : K == kFmtD1K8 ? 64 : K;
 }
 
 // What one wave needs to decode one group: the lane's index bytes and codebook piece.
@@ -56,6 +56,9 @@ template <> struct GroupRegs<64> {
   uint32_t d0, d1, d2;   // the lane's 16 six-bit indices of the 8-row block
   uint32_t two;          // int8 pair of table entry `lane`
   uint32_t sc;           // the group's fp16 scale
+};
+template <> struct GroupRegs<kFmtD1K8> {
+  uint32_t d0, d1, d2, two, sc;   // as for k = 64: `two` is pair-table entry `lane`, built from the 8 values
 };
 template <> struct GroupRegs<kFmtK64BN> {
   uint32_t d0, d1, d2, two, sc;   // as for k = 64
@@ -104,8 +107,8 @@ __device__ __forceinline__ void load_group(GroupRegs<K>& g, const uint8_t* idx, 
     g.w = *reinterpret_cast<const uint4*>(idx + gi * 1024 + lane * 16);
     g.clo = *reinterpret_cast<const uint2*>(cg + (lane & 3) * 8);
     g.chi = *reinterpret_cast<const uint16_t*>(cg + (lane >> 2) * 2);
-  } else if constexpr (K == 64 || K == kFmtK64BN) {
-    constexpr int tab_bytes = K == 64 ? kK64QuadTabBytes : kK64NQuadTabBytes;
+  } else if constexpr (K == 64 || K == kFmtK64BN || K == kFmtD1K8) {
+    constexpr int tab_bytes = K == 64 ? kK64QuadTabBytes : K == kFmtD1K8 ? kD1K8QuadTabBytes : kK64NQuadTabBytes;
     const int n_quads = k64_quads(n_cb), q = c >> 2, j = c & 3;
     const uint8_t* iq = idx + ((size_t)rb * n_quads + q) * kK64QuadIdxBytes + lane * 16;
     const int w0 = 3 * j, w1 = 3 * j + 1, w2 = 3 * j + 2;     // the lane's dwords of col-block j
@@ -114,8 +117,13 @@ __device__ __forceinline__ void load_group(GroupRegs<K>& g, const uint8_t* idx, 
     g.d2 = *reinterpret_cast<const uint32_t*>(iq + (w2 >> 2) * 1024 + (w2 & 3) * 4);
     const uint8_t* tq = reinterpret_cast<const uint8_t*>(cb) +
                         ((size_t)(rb / rpc) * n_quads + q) * tab_bytes;
-    g.two = *reinterpret_cast<const uint16_t*>(tq + j * 128 + lane * 2);
-    g.sc = *reinterpret_cast<const uint16_t*>(tq + 512 + 2 * j);
+    if constexpr (K == kFmtD1K8) {
+      g.two = d1k8_pair(*reinterpret_cast<const uint2*>(tq + j * 8), lane);
+      g.sc = *reinterpret_cast<const uint16_t*>(tq + kD1K8ScaleOffset + 2 * j);
+    } else {
+      g.two = *reinterpret_cast<const uint16_t*>(tq + j * 128 + lane * 2);
+      g.sc = *reinterpret_cast<const uint16_t*>(tq + 512 + 2 * j);
+    }
     if constexpr (K == kFmtK64BN) {
       g.lev = *reinterpret_cast<const uint16_t*>(tq + kK64NLevelOffset + j * 32 + (lane & 15) * 2);
       g.cw = *reinterpret_cast<const uint32_t*>(reinterpret_cast<const uint8_t*>(cb) +
@@ -150,7 +158,7 @@ __device__ __forceinline__ void decode_group(const GroupRegs<K>& g, uint32_t* lu
       v[2 * r] = t.x;
       v[2 * r + 1] = t.y;
     }
-  } else if constexpr (K == 64 || K == kFmtK64BN) {
+  } else if constexpr (K == 64 || K == kFmtK64BN || K == kFmtD1K8) {
     lut[lane] = k64_dequant_pair(g.two, __builtin_bit_cast(_Float16, (uint16_t)g.sc));
     if constexpr (K == kFmtK64BN) {
       if (lane < 16) lut[64 + lane] = g.lev * 0x10001u;
@@ -736,6 +744,7 @@ hipError_t launch_gemm(const vq_desc& d, const void* idx_dev, const void* cb_dev
   if (fmt == kFmtD1K16) VQ_GEMM_DISPATCH(kFmtD1K16)
   if (fmt == kFmtK64BN) VQ_GEMM_DISPATCH(kFmtK64BN)
   if (fmt == kFmtD4) VQ_GEMM_DISPATCH(kFmtD4)
+  if (fmt == kFmtD1K8) VQ_GEMM_DISPATCH(kFmtD1K8)
   if (fmt == 16) VQ_GEMM_DISPATCH(16)
   VQ_GEMM_DISPATCH(256)
 #undef VQ_GEMM_DISPATCH

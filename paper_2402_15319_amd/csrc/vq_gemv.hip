@@ -178,10 +178,13 @@ template <> struct Chunk<kFmtD1K16> : Chunk256T<true> {};
 
 // k = 64 with int8 tables.  BN: blockwise normalisation on top (16 block-scale levels per
 // group, a 4-bit code per 32 weights); the plain C++ inner block replaces the hand-scheduled one.
-template <bool BN> struct Chunk64T {
+// MODE 2: d = 1, k = 8: the 64-entry pair table is built from the group's 8 int8 values.
+template <int MODE> struct Chunk64T {
+  static constexpr bool BN = MODE == 1, D1 = MODE == 2;
   static constexpr int kUnits = 1;        // quads of 4 col-blocks per chunk
   static constexpr int kLutDwords = BN ? 320 : 256;  // 4 groups x 64 centroids (+ 4 x 16 levels)
-  static constexpr int kTabBytes = BN ? kK64NQuadTabBytes : kK64QuadTabBytes;
+  static constexpr int kTabBytes = BN ? kK64NQuadTabBytes : D1 ? kD1K8QuadTabBytes : kK64QuadTabBytes;
+  static constexpr int kScaleOffset = D1 ? kD1K8ScaleOffset : 512;
   uint4 w[3];     // the lane's three index planes of the quad
   uint2 xv[4];    // activations of the quad's four col-blocks
   uint2 tab;      // 4 int8 centroid pairs: entries 4*(lane%16).. of table lane/16
@@ -193,8 +196,8 @@ template <bool BN> struct Chunk64T {
     const bool ok = u < S.u_end;
     const int q = ok ? u : 0;
     const uint8_t* tq = reinterpret_cast<const uint8_t*>(S.cb_rb) + (size_t)q * kTabBytes;
-    tab = zero_unless(ok, *reinterpret_cast<const uint2*>(tq + lane * 8));
-    sc = *reinterpret_cast<const uint16_t*>(tq + 512 + (lane >> 4) * 2);
+    tab = zero_unless(ok, *reinterpret_cast<const uint2*>(tq + (D1 ? (lane >> 4) * 8 : lane * 8)));
+    sc = *reinterpret_cast<const uint16_t*>(tq + kScaleOffset + (lane >> 4) * 2);
     if constexpr (BN) {
       lev = zero_unless(ok, (uint32_t)*reinterpret_cast<const uint16_t*>(tq + kK64NLevelOffset + lane * 2));
       cw = *reinterpret_cast<const uint4*>(S.codes_rb + (size_t)q * kK64NQuadCodeBytes + (lane >> 3) * 16);
@@ -212,9 +215,16 @@ template <bool BN> struct Chunk64T {
   __device__ __forceinline__ void consume(uint32_t* lut, uint32_t base, int lane,
                                           float (&acc)[8]) const {
     const _Float16 scale = __builtin_bit_cast(_Float16, (uint16_t)sc);
-    *reinterpret_cast<uint4*>(lut + lane * 4) =
-        make_uint4(k64_dequant_pair(tab.x, scale), k64_dequant_pair(tab.x >> 16, scale),
-                   k64_dequant_pair(tab.y, scale), k64_dequant_pair(tab.y >> 16, scale));
+    if constexpr (D1) {
+      const int e = 4 * (lane & 15);
+      *reinterpret_cast<uint4*>(lut + lane * 4) =
+          make_uint4(k64_dequant_pair(d1k8_pair(tab, e), scale), k64_dequant_pair(d1k8_pair(tab, e + 1), scale),
+                     k64_dequant_pair(d1k8_pair(tab, e + 2), scale), k64_dequant_pair(d1k8_pair(tab, e + 3), scale));
+    } else {
+      *reinterpret_cast<uint4*>(lut + lane * 4) =
+          make_uint4(k64_dequant_pair(tab.x, scale), k64_dequant_pair(tab.x >> 16, scale),
+                     k64_dequant_pair(tab.y, scale), k64_dequant_pair(tab.y >> 16, scale));
+    }
     if constexpr (BN) lut[256 + lane] = lev * 0x10001u;   // the level in both halves
     wave_lds_sync();
     const uint32_t d[12] = {w[0].x, w[0].y, w[0].z, w[0].w, w[1].x, w[1].y,
@@ -237,8 +247,9 @@ template <bool BN> struct Chunk64T {
     }
   }
 };
-template <> struct Chunk<64> : Chunk64T<false> {};
-template <> struct Chunk<kFmtK64BN> : Chunk64T<true> {};
+template <> struct Chunk<64> : Chunk64T<0> {};
+template <> struct Chunk<kFmtK64BN> : Chunk64T<1> {};
+template <> struct Chunk<kFmtD1K8> : Chunk64T<2> {};
 
 // Strip (row-block rb, K-split `split` of `splits`) of problem P; may be empty.
 template <int K>
@@ -262,9 +273,9 @@ __device__ __forceinline__ Strip make_strip(const GemvProblem& P, int rb, int sp
     S.u = (n_pairs * split) / splits;
     S.u_end = (n_pairs * (split + 1)) / splits;
     S.chunks_left = (S.u_end - S.u + 3) >> 2;
-  } else if (K == 64 || K == kFmtK64BN) {
+  } else if (K == 64 || K == kFmtK64BN || K == kFmtD1K8) {
     const int n_quads = k64_quads(n_cb);
-    constexpr int tab_bytes = K == 64 ? kK64QuadTabBytes : kK64NQuadTabBytes;
+    constexpr int tab_bytes = K == 64 ? kK64QuadTabBytes : K == kFmtD1K8 ? kD1K8QuadTabBytes : kK64NQuadTabBytes;
     S.idx_rb = P.idx + (size_t)rb * n_quads * kK64QuadIdxBytes;
     S.cb_rb = P.cb + (size_t)(rb / P.rb_per_cb) * n_quads * (tab_bytes / 4);
     if (K == kFmtK64BN)   // the codes follow the table records of all group rows
@@ -426,10 +437,12 @@ template <bool D1> struct ChunkS256T {
 template <> struct ChunkS<256> : ChunkS256T<false> {};
 template <> struct ChunkS<kFmtD1K16> : ChunkS256T<true> {};
 
-template <bool BN> struct ChunkS64T {
+template <int MODE> struct ChunkS64T {
+  static constexpr bool BN = MODE == 1, D1 = MODE == 2;
   static constexpr int kUnits = 1;
   static constexpr int kLutDwords = BN ? 320 : 256;
-  static constexpr int kTabBytes = BN ? kK64NQuadTabBytes : kK64QuadTabBytes;
+  static constexpr int kTabBytes = BN ? kK64NQuadTabBytes : D1 ? kD1K8QuadTabBytes : kK64QuadTabBytes;
+  static constexpr int kScaleOffset = D1 ? kD1K8ScaleOffset : 512;
   uint4 w[3];
   uint2 tab;
   uint32_t sc;
@@ -444,8 +457,8 @@ template <bool BN> struct ChunkS64T {
     const uint8_t* tq = reinterpret_cast<const uint8_t*>(S.cb_rb) + (size_t)q * kTabBytes;
     uint32_t voff = (uint32_t)lane * 16u;      // see ChunkS<16>::load
     asm volatile("" : "+v"(voff));
-    tab = zero_unless(ok, *reinterpret_cast<const uint2*>(tq + (voff >> 1)));
-    sc = *reinterpret_cast<const uint16_t*>(tq + 512 + (lane >> 4) * 2);
+    tab = zero_unless(ok, *reinterpret_cast<const uint2*>(tq + (D1 ? (uint32_t)(lane >> 4) * 8u : voff >> 1)));
+    sc = *reinterpret_cast<const uint16_t*>(tq + kScaleOffset + (lane >> 4) * 2);
     if constexpr (BN) {
       lev = zero_unless(ok, (uint32_t)*reinterpret_cast<const uint16_t*>(tq + kK64NLevelOffset + lane * 2));
       cw = *reinterpret_cast<const uint4*>(S.codes_rb + (size_t)q * kK64NQuadCodeBytes + (lane >> 3) * 16);
@@ -459,9 +472,16 @@ template <bool BN> struct ChunkS64T {
   __device__ __forceinline__ void consume(uint32_t* lut, uint32_t base, const uint32_t* x_s, int lane,
                                           float (&acc)[8]) const {
     const _Float16 scale = __builtin_bit_cast(_Float16, (uint16_t)sc);
-    *reinterpret_cast<uint4*>(lut + lane * 4) =
-        make_uint4(k64_dequant_pair(tab.x, scale), k64_dequant_pair(tab.x >> 16, scale),
-                   k64_dequant_pair(tab.y, scale), k64_dequant_pair(tab.y >> 16, scale));
+    if constexpr (D1) {
+      const int e = 4 * (lane & 15);
+      *reinterpret_cast<uint4*>(lut + lane * 4) =
+          make_uint4(k64_dequant_pair(d1k8_pair(tab, e), scale), k64_dequant_pair(d1k8_pair(tab, e + 1), scale),
+                     k64_dequant_pair(d1k8_pair(tab, e + 2), scale), k64_dequant_pair(d1k8_pair(tab, e + 3), scale));
+    } else {
+      *reinterpret_cast<uint4*>(lut + lane * 4) =
+          make_uint4(k64_dequant_pair(tab.x, scale), k64_dequant_pair(tab.x >> 16, scale),
+                     k64_dequant_pair(tab.y, scale), k64_dequant_pair(tab.y >> 16, scale));
+    }
     if constexpr (BN) lut[256 + lane] = lev * 0x10001u;
     wave_lds_sync();
     const uint2* xp = reinterpret_cast<const uint2*>(x_s) + u0 * 256 + lane;   // 64 uint2 per col-block
@@ -493,8 +513,9 @@ template <bool BN> struct ChunkS64T {
     }
   }
 };
-template <> struct ChunkS<64> : ChunkS64T<false> {};
-template <> struct ChunkS<kFmtK64BN> : ChunkS64T<true> {};
+template <> struct ChunkS<64> : ChunkS64T<0> {};
+template <> struct ChunkS<kFmtK64BN> : ChunkS64T<1> {};
+template <> struct ChunkS<kFmtD1K8> : ChunkS64T<2> {};
 
 // Zeroed col-blocks kept behind x in LDS (absent units of a ragged chunk read them).
 constexpr int kXPadColBlocks = 8;
@@ -693,6 +714,7 @@ __global__ __launch_bounds__(256) void gemv_split_kernel(const GemvBatch batch) 
     case kFmtK16I8: F(kFmtK16I8); break;      \
     case kFmtD1K16: F(kFmtD1K16); break;      \
     case kFmtK64BN: F(kFmtK64BN); break;      \
+    case kFmtD1K8: F(kFmtD1K8); break;        \
     default: F(256); break;                   \
   }
 
@@ -708,10 +730,10 @@ int gemv_stream_resident_wgs(int fmt, int max_n_cb) {
   // Occupancy of the persistent kernel for this LDS size, asked once per (device, format, size):
   // a pure function of the code object and the device, cached so that the hot path makes
   // no runtime queries.  Benign if two threads fill the same slot at once.
-  static int cached[6][16][kStreamMaxColBlocks + 1];
+  static int cached[7][16][kStreamMaxColBlocks + 1];
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) dev = 0;
-  const int fi = fmt == 16 ? 0 : fmt == 64 ? 1 : fmt == kFmtK16I8 ? 3 : fmt == kFmtD1K16 ? 4 : fmt == kFmtK64BN ? 5 : 2;
+  const int fi = fmt == 16 ? 0 : fmt == 64 ? 1 : fmt == kFmtK16I8 ? 3 : fmt == kFmtD1K16 ? 4 : fmt == kFmtK64BN ? 5 : fmt == kFmtD1K8 ? 6 : 2;
   int& slot = cached[fi][dev][max_n_cb];
   if (slot == 0) {
     int per_cu = 0, cus = 0;

@@ -167,6 +167,29 @@ __global__ __launch_bounds__(256) void pack_tab64_kernel(const uint8_t* __restri
   }
 }
 
+// d = 1, k = 8: per (row of groups, quad) four tables of 8 int8 values, four fp16 scales, padding
+// (48 bytes).  One thread per record.
+__global__ __launch_bounds__(256) void pack_tab_d1k8_kernel(const uint8_t* __restrict__ q_canon,
+                                                            const uint16_t* __restrict__ scale_canon,
+                                                            uint8_t* __restrict__ dev, int n_cb,
+                                                            long long n_grow) {
+  const long long slot = (long long)blockIdx.x * 256 + threadIdx.x;
+  const int n_quads = k64_quads(n_cb);
+  if (slot >= n_grow * n_quads) return;
+  const long long grow = slot / n_quads;
+  const int q = (int)(slot - grow * n_quads);
+  uint8_t* dst = dev + (size_t)slot * kD1K8QuadTabBytes;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int c = 4 * q + j;
+    const bool ok = c < n_cb;
+    *reinterpret_cast<uint2*>(dst + j * 8) =
+        ok ? *reinterpret_cast<const uint2*>(q_canon + (size_t)(grow * n_cb + c) * 8) : make_uint2(0u, 0u);
+    reinterpret_cast<uint16_t*>(dst + kD1K8ScaleOffset)[j] = ok ? scale_canon[grow * n_cb + c] : (uint16_t)0;
+  }
+  *reinterpret_cast<uint2*>(dst + 40) = make_uint2(0u, 0u);
+}
+
 // Block codes: canonical code[r][c/32] (two per byte, even block in the low nibble, 4*n_cb
 // bytes per row) -> per (8-row block, quad) 32 dwords, dword 4*b + j = codes of block b of
 // col-block 4q + j, row r in bits [4r, 4r+4).  One thread per dword.
@@ -276,7 +299,7 @@ hipError_t launch_pack(const vq_desc& d, const void* idx_canon, const void* cb_c
                        (const uint8_t*)cb_canon, (uint8_t*)cb_dev, n16, src_bytes);
     return hipGetLastError();
   }
-  if (d.k == 64) {
+  if (d.k == 64 || (d.d == 1 && d.k == 8)) {   // 6-bit fields: k = 64, or two 3-bit indices of d = 1
     const int rpc = d.group_rows / kGroupRows;
     const long long n_grow = d.out_features / d.group_rows;
     const int n_quads = k64_quads(n_cb);
@@ -284,6 +307,13 @@ hipError_t launch_pack(const vq_desc& d, const void* idx_canon, const void* cb_c
                        0, s, (const uint8_t*)idx_canon, (uint8_t*)idx_dev, n_cb, n_rb, rpc);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
+    if (d.d == 1) {   // k = 8 scalar tables: 8 bytes per group, padded to 16 in total, then the scales
+      const size_t q8 = ((size_t)n_grow * n_cb * 8 + 15) / 16 * 16;
+      hipLaunchKernelGGL(pack_tab_d1k8_kernel, dim3((unsigned)((n_grow * n_quads + 255) / 256)), dim3(256), 0, s,
+                         (const uint8_t*)cb_canon, (const uint16_t*)((const uint8_t*)cb_canon + q8),
+                         (uint8_t*)cb_dev, n_cb, n_grow);
+      return hipGetLastError();
+    }
     const size_t q_bytes = ((size_t)n_grow * n_cb * 128 + 15) / 16 * 16;   // scales follow the tables
     const bool bn = d.codebook_dtype == VQ_I8_BN;
     const size_t s_bytes = ((size_t)n_grow * n_cb * 2 + 15) / 16 * 16;     // levels follow the padded scales

@@ -69,6 +69,8 @@ A = 0x1000  # a fake, 16-byte aligned, non-NULL address; validation fails before
     (dict(d=4, k=256, index_bits=8, group_rows=256), -3),                 # fp16 tables: not implemented
     (dict(d=1, k=256, index_bits=8), -3),                                 # scalar codebooks: k = 16 only
     (dict(d=1, codebook_dtype=3), -3),                                    # ... with fp16 values
+    (dict(d=1, k=8, index_bits=3), -3),                                   # 3-bit scalar codebooks: int8 values
+    (dict(d=1, k=8, index_bits=3, codebook_dtype=3, group_rows=64), -3),
     (dict(d=1, group_rows=32), -3),
     (dict(group_rows=4), -3),
     (dict(group_cols=128), -3),
@@ -234,3 +236,14 @@ def test_four_dimensional_representation_sizes_and_entry_points():
         assert L.vq_gemv(r, A, A, A + 2, A + 16, vq.VQ_F16, 0) == -4
         assert L.vq_gemm_batched(r, A, A, A, 16, 20, A + 16, 16, vq.VQ_F16, 0) == -4
         assert L.vq_decode_dense(r, A, A, A + 2, 0) == -4
+
+
+def test_three_bit_scalar_representation_sizes():
+    L = vq.lib()
+    for out_f, in_f, rows in ((4096, 4096, 32), (4096, 11008, 32), (64, 768, 8)):
+        d = vq.make_desc(out_f, in_f, 8, 3, group_rows=rows, d=1, codebook_dtype=vq.VQ_I8)
+        n_groups = (out_f // rows) * (in_f // 256)
+        assert vq.vq_canonical_bytes(d) == (out_f * in_f * 3 // 8, (n_groups * 8 + 15) // 16 * 16 + 2 * n_groups)
+        quads = (in_f // 256 + 3) // 4
+        assert vq.vq_layout_bytes(d) == ((out_f // 8) * quads * 3072, (out_f // rows) * quads * 48)
+        assert L.vq_gemv(ctypes.byref(d), A, A, A + 2, A + 16, vq.VQ_F16, 0) == -4

@@ -733,3 +733,42 @@ def test_d4_full_size_layer(env):
         Y = _gpu_gemm(env, desc, idx_d, cb_d, X, False)
         cols = np.random.default_rng(5).choice(B, size=min(B, 48), replace=False)
         assert oracle.normwise_rel_err(Y[:, cols], _dense_product(W, X[:, cols])) <= TOL_F16, B
+
+
+# ---------------------------------------------------------------- scalar codebooks at 3 bits (d = 1, k = 8, int8 values)
+def _shape_d1k8(o, i, rows=32):
+    return workloads.VQShape(o, i, 8, 3, rows, 256, 1, True)
+
+
+D1K8_SMALL = [_shape_d1k8(32, 256), _shape_d1k8(96, 768), _shape_d1k8(64, 2816), _shape_d1k8(40, 1280, 8),
+              _shape_d1k8(48, 512, 16)]
+
+
+@pytest.mark.parametrize("s", D1K8_SMALL + [_shape_d1k8(32800, 768)], ids=str)
+def test_d1k8_decode_and_gemv(env, s):
+    """Decode bit for bit, GEMV with fp16 and fp32 output (split-K kernel; streaming kernel on the tall shape)."""
+    desc, idx, cb, idx_d, cb_d = _setup_i8(env, s, 740)
+    f = _fmt(s)
+    np.testing.assert_array_equal(_gpu_decode(env, desc, idx_d, cb_d), oracle.decode_dense(f, idx, cb))
+    x = workloads.make_x(s.in_features, 740)
+    ref = oracle.gemv(f, idx, cb, x)
+    assert oracle.normwise_rel_err(_gpu_gemv(env, desc, idx_d, cb_d, x, False), ref) <= TOL_F16
+    assert oracle.normwise_rel_err(_gpu_gemv(env, desc, idx_d, cb_d, x, True), ref) <= TOL_F32
+
+
+@pytest.mark.parametrize("B", [1, 16, 40, 130, 600, 1300])
+@pytest.mark.parametrize("s", [_shape_d1k8(96, 768), _shape_d1k8(808, 512, 8)], ids=str)
+def test_d1k8_gemm(env, s, B):
+    desc, idx, cb, idx_d, cb_d = _setup_i8(env, s, 741)
+    X = workloads.make_X(s.in_features, B, 741)
+    Y = _gpu_gemm(env, desc, idx_d, cb_d, X, False, pad=8 if B == 40 else 0)
+    assert oracle.normwise_rel_err(Y, oracle.gemm(_fmt(s), idx, cb, X)) <= TOL_F16
+
+
+def test_d1k8_full_size_layer(env):
+    s = workloads.CONFIGS["mlp_down_4096x11008_d1_k8"]
+    desc, idx, cb, idx_d, cb_d = _setup_i8(env, s, 742)
+    f = _fmt(s)
+    np.testing.assert_array_equal(_gpu_decode(env, desc, idx_d, cb_d), oracle.decode_dense(f, idx, cb))
+    x = workloads.make_x(s.in_features, 742)
+    assert oracle.normwise_rel_err(_gpu_gemv(env, desc, idx_d, cb_d, x, False), oracle.gemv(f, idx, cb, x)) <= TOL_F16
