@@ -215,6 +215,9 @@ def main():
                 # four-dimensional vectors: k = 256, one index byte per 4 weights, 256 x 256 groups (2.125 bpv)
                 ("llama7b_pass_d4_k256_int8_tables_2.125bpv_via_vq_gemv_multi", workloads.LLAMA7B_LAYER_D4,
                  "gemv_d4_kernel"),
+                # scalar codebooks at 3 bits: 8 int8 values + scale per 32 x 256 group (3.01 bpv)
+                ("llama7b_pass_d1_k8_int8_3.01bpv_via_vq_gemv_multi", workloads.LLAMA7B_LAYER_D1_K8,
+                 "gemv_stream_kernel<d1,k8>"),
                 # scalar codebooks (d = 1): 16 fp16 values per 8 x 256 group, 4-bit indices, 3.47 GB
                 ("llama7b_pass_d1_k16_4.125bpv_via_vq_gemv_multi", workloads.LLAMA7B_LAYER_D1_K16,
                  "gemv_stream_kernel<d1,k16>")):
@@ -229,6 +232,10 @@ def main():
                         n_groups = (s.out_features // s.group_rows) * (s.in_features // 256)
                         tab[n_groups * 1024:] = 0
                         tab[n_groups * 1024 + 1:n_groups * 1026:2] = 0x1C
+                    elif s.d == 1 and s.k == 8:         # 48-byte records: 4 x 8 int8, 4 scales (2^-8), padding
+                        tv = tab.view(-1, 48)
+                        tv[:, 32:48] = 0
+                        tv[:, 33:40:2] = 0x1C
                     elif s.d == 1:                      # fp16 scalars
                         tab = (torch.randn(cbb // 2, device=dev) * 0.02).half().view(torch.uint8)
                     elif s.block_norm:                  # 672-byte records (+ 64 levels, set to 1.0), then nibble codes
