@@ -3,7 +3,7 @@
 // of W (table lookup, Sec. 3.2) into LDS as fp16 and feeds them to the fp16
 // matrix cores (v_mfma_f32_32x32x16_f16) with fp32 accumulation.
 //
-// A workgroup has 4 waves and owns an MT x NT tile of Y, MT = 32*RBW rows.  K is
+// A workgroup has 4 (or 8) waves and owns an MT x NT tile of Y, MT = 32*RBW (x 2) rows.  K is
 // walked one col-block (256 columns) at a time:
 //   * every wave decodes RBW groups (its own row-blocks of the tile) of the
 //     col-block into the LDS tile Wt[MT][256]: indices and codebooks were loaded
@@ -14,7 +14,8 @@
 //     sub-tiles ahead in registers, 16-byte LDS stores) and forms the operand with the
 //     transposing LDS read ds_read_b64_tr_b16; the col-block is consumed in 64- / 32-deep
 //     sub-steps through two X buffers (one barrier per sub-step), wave w owns a quarter of
-//     the batch columns and all MT rows (RBW x NT/128 accumulator tiles);
+//     the batch columns and 32*RBW rows (RBW x NT/128 accumulator tiles); with WM = 2 the
+//     workgroup has 8 waves and twice the rows, the second four waves taking the lower half;
 //   * gemm_small_kernel (32 x 32 tiles, bandwidth-bound batches) and gemm_tiny_kernel
 //     (16 x 16) transpose X in registers instead: a thread loads 8 rows x 4 columns, swaps
 //     halves with v_perm and writes 4 x 16 bytes, giving Xs[k/8][n][k%8].
@@ -261,18 +262,18 @@ struct XRows {
 };
 
 // Rows row0 + j * RPP (j = 0..3) are wave-uniform; voff is the lane's part in bytes.
-template <int RPP>
+template <int RPP, int PASSES = 4>
 __device__ __forceinline__ void load_xrows(XRows& p, const uint16_t* X, long long row0, int ldx,
                                            uint32_t voff) {
   const char* base = reinterpret_cast<const char*>(X) + (size_t)row0 * ldx * 2;
 #pragma unroll
-  for (int j = 0; j < 4; ++j)
+  for (int j = 0; j < PASSES; ++j)
     p.r[j] = *reinterpret_cast<const u32x4_t*>(base + (size_t)j * RPP * ldx * 2 + voff);
 }
-template <int RPP, int NT>
+template <int RPP, int NT, int PASSES = 4>
 __device__ __forceinline__ void store_xrows(const XRows& p, char* dst) {
 #pragma unroll
-  for (int j = 0; j < 4; ++j) *reinterpret_cast<u32x4_t*>(dst + j * RPP * NT * 2) = p.r[j];
+  for (int j = 0; j < PASSES; ++j) *reinterpret_cast<u32x4_t*>(dst + j * RPP * NT * 2) = p.r[j];
 }
 // 8 consecutive k (two 4-row tiles, 4 * NT * 2 bytes apart) of the lane's column.
 template <int NT>
@@ -283,14 +284,14 @@ __device__ __forceinline__ h8_t read_x_operand(const char* src) {
   return __builtin_bit_cast(h8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
 }
 
-template <int K, int RBW, int NT>
-__global__ __launch_bounds__(256, 2) void gemm_kernel(const uint8_t* __restrict__ idx,
+template <int K, int RBW, int NT, int WM = 1>
+__global__ __launch_bounds__(256 * WM, WM == 1 ? 2 : 1) void gemm_kernel(const uint8_t* __restrict__ idx,
                                                    const uint32_t* __restrict__ cb,
                                                    const uint16_t* __restrict__ X, int B, int ldx,
                                                    void* __restrict__ Y, int ldy, int y_f32,
                                                    int n_rb, int n_cb, int n_tiles_n, int rpc) {
   static_assert(NT == 128 || NT == 256, "column tile");
-  constexpr int MT = 32 * RBW;
+  constexpr int MT = 32 * RBW * WM;
   constexpr int KS = 8192 / NT;                  // k per X sub-tile: 64 or 32
   constexpr int NSUB = 256 / KS;                 // sub-steps per col-block: 4 or 8
   constexpr int NB = NT / 128;                   // 32-column accumulator tiles per wave
@@ -302,17 +303,19 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const uint8_t* __restrict_
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wc = wave & 3, wr = wave >> 2;       // column quarter, row half
   const int mt = blockIdx.x / n_tiles_n;
   const int nt = blockIdx.x - mt * n_tiles_n;
 
   // X staging role: a sub-tile is copied in 4 passes of RPP rows; the thread owns 16 bytes
   // (8 batch columns from n_loc) of row x_row of every pass.  Columns at or beyond B are
   // loaded from column 0 instead: they only reach accumulator columns that are never written.
-  constexpr int RPP = 2048 / NT;                 // rows per pass: 8 or 16
+  constexpr int RPP = 2048 * WM / NT;            // rows per pass
+  constexpr int PASSES = 4 / WM;
   const int x_row = tid / (NT / 8);
   const int n_loc = (tid % (NT / 8)) * 8;
   const int n_glob = nt * NT + n_loc;
-  const int x_row_wave = wave * (RPP / 4);       // first row of the wave inside a pass
+  const int x_row_wave = wave * (512 / NT);      // first row of the wave inside a pass
   const int xs_off = x_row * NT * 2 + ((((n_loc >> 4) ^ (x_row & 3)) << 5) | ((n_loc & 8) << 1));
   uint32_t x_voff = (uint32_t)(((x_row - x_row_wave) * ldx + (n_glob < B ? n_glob : 0)) * 2);
   asm volatile("" : "+v"(x_voff));   // keep it one 32-bit register next to scalar row bases
@@ -321,7 +324,7 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const uint8_t* __restrict_
 #pragma unroll
   for (int b = 0; b < NB; ++b) {
     const int kq = (lane & 15) >> 2;
-    const int chunk = ((wave * NB + b) * 32 + (lane & 16)) >> 4;
+    const int chunk = ((wc * NB + b) * 32 + (lane & 16)) >> 4;
     xr_off[b] = (8 * (lane >> 5) + kq) * NT * 2 + ((chunk ^ kq) << 5) + (lane & 3) * 8;
   }
   const int n_subtiles = n_cb * NSUB;
@@ -340,18 +343,18 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const uint8_t* __restrict_
   bool rb_ok[RBW];
 #pragma unroll
   for (int a = 0; a < RBW; ++a) {
-    rbs[a] = (long long)mt * (4 * RBW) + wave * RBW + a;
+    rbs[a] = (long long)mt * (4 * RBW * WM) + wave * RBW + a;
     rb_ok[a] = rbs[a] < n_rb;
     load_group<K>(g[a], idx, cb, rb_ok[a] ? rbs[a] : 0, 0, n_cb, lane, n_rb, rpc);
   }
   XRows ring[D];   // slot t % D holds sub-tile t + 1 when sub-step t starts
   {
     XRows first;
-    load_xrows<RPP>(first, X, x_row_wave, ldx, x_voff);
+    load_xrows<RPP, PASSES>(first, X, x_row_wave, ldx, x_voff);
 #pragma unroll
     for (int i = 0; i < D; ++i)
-      load_xrows<RPP>(ring[i], X, (long long)min(i + 1, n_subtiles - 1) * KS + x_row_wave, ldx, x_voff);
-    store_xrows<RPP, NT>(first, reinterpret_cast<char*>(Xs_all[0]) + xs_off);
+      load_xrows<RPP, PASSES>(ring[i], X, (long long)min(i + 1, n_subtiles - 1) * KS + x_row_wave, ldx, x_voff);
+    store_xrows<RPP, NT, PASSES>(first, reinterpret_cast<char*>(Xs_all[0]) + xs_off);
   }
   int cur = 0;   // X buffer the next MFMA step reads
 
@@ -359,7 +362,7 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const uint8_t* __restrict_
     // every wave is past its MFMA reads of Wt (barrier at the end of the last sub-step); the
     // tables live in the X buffer that is idle while a col-block is being decoded
     uint32_t* lut = Xs_all[1 - cur] + wave * lut_dwords<K>();
-    static_assert(4 * lut_dwords<K>() <= 4096, "four tables must fit in one X buffer");
+    static_assert(4 * WM * lut_dwords<K>() <= 4096, "the waves' tables must fit in one X buffer");
 #pragma unroll
     for (int a = 0; a < RBW; ++a) {
       const int m0 = (wave * RBW + a) * 8;
@@ -383,8 +386,8 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const uint8_t* __restrict_
       // loading sub-tile t + 1 + D into the slot it leaves
       const int t = c * NSUB + sub;
       XRows& slot = ring[sub % D];
-      store_xrows<RPP, NT>(slot, reinterpret_cast<char*>(Xs_all[cur ^ 1]) + xs_off);
-      load_xrows<RPP>(slot, X, (long long)min(t + 1 + D, n_subtiles - 1) * KS + x_row_wave, ldx, x_voff);
+      store_xrows<RPP, NT, PASSES>(slot, reinterpret_cast<char*>(Xs_all[cur ^ 1]) + xs_off);
+      load_xrows<RPP, PASSES>(slot, X, (long long)min(t + 1 + D, n_subtiles - 1) * KS + x_row_wave, ldx, x_voff);
       // wave w: batch columns [32*NB*w, 32*NB*(w+1)), all MT rows, the KS k of this sub-step
 #pragma unroll
       for (int kk = 0; kk < KS / 16; ++kk) {
@@ -395,7 +398,7 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const uint8_t* __restrict_
 #pragma unroll
         for (int a = 0; a < RBW; ++a) {
           const h8_t av = *reinterpret_cast<const h8_t*>(
-              Wt + wt_half_index(32 * a + (lane & 31), sub * KS + 16 * kk + 8 * (lane >> 5)));
+              Wt + wt_half_index(wr * 32 * RBW + 32 * a + (lane & 31), sub * KS + 16 * kk + 8 * (lane >> 5)));
 #pragma unroll
           for (int b = 0; b < NB; ++b)
             acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av, bv[b], acc[a][b], 0, 0, 0);
@@ -409,13 +412,13 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const uint8_t* __restrict_
   // ---- store: accumulator register i holds row 8*(i/4) + 4*(lane/32) + i%4, column lane%32
 #pragma unroll
   for (int b = 0; b < NB; ++b) {
-    const int n = nt * NT + (wave * NB + b) * 32 + (lane & 31);
+    const int n = nt * NT + (wc * NB + b) * 32 + (lane & 31);
     if (n < B) {
 #pragma unroll
       for (int a = 0; a < RBW; ++a)
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-          const int row = mt * MT + 32 * a + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
+          const int row = mt * MT + wr * 32 * RBW + 32 * a + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
           if (row < n_rb * 8) {
             const size_t o = (size_t)row * ldy + n;
             if (y_f32) reinterpret_cast<float*>(Y)[o] = acc[a][b][i];
@@ -700,12 +703,12 @@ hipError_t launch_small(const vq_desc& d, const void* idx_dev, const void* cb_de
   return hipGetLastError();
 }
 
-template <int K, int RBW, int NT>
+template <int K, int RBW, int NT, int WM = 1>
 hipError_t launch_one(const vq_desc& d, const void* idx_dev, const void* cb_dev, const void* X, int B,
                       int ldx, void* Y, int ldy, int y_f32, hipStream_t s) {
   const int n_rb = d.out_features / kGroupRows, n_cb = d.in_features / kGroupCols;
-  const int tiles_m = (n_rb + 4 * RBW - 1) / (4 * RBW), tiles_n = (B + NT - 1) / NT;
-  hipLaunchKernelGGL((gemm_kernel<K, RBW, NT>), dim3((unsigned)(tiles_m * tiles_n)), dim3(256), 0, s,
+  const int tiles_m = (n_rb + 4 * RBW * WM - 1) / (4 * RBW * WM), tiles_n = (B + NT - 1) / NT;
+  hipLaunchKernelGGL((gemm_kernel<K, RBW, NT, WM>), dim3((unsigned)(tiles_m * tiles_n)), dim3(256 * WM), 0, s,
                      (const uint8_t*)idx_dev, (const uint32_t*)cb_dev, (const uint16_t*)X, B, ldx, Y,
                      ldy, y_f32, n_rb, n_cb, tiles_n, d.group_rows / kGroupRows);
   return hipGetLastError();
@@ -718,25 +721,39 @@ hipError_t launch_gemm(const vq_desc& d, const void* idx_dev, const void* cb_dev
   // B <= 16: 16 x 16 tiles, barrier-free (gemm_tiny_kernel).  It re-decodes W once per 16
   // columns, which still pays up to 64 columns when the matrix is too short to fill the CUs
   // with the 32-row tiles of the other kernels.  Then 32 x 32 tiles (gemm_small_kernel,
-  // bandwidth-bound) while they are few enough to run in about one wave of workgroups, and
-  // 32 x 128, 64 x 128 and 64 x 256 tiles (gemm_kernel) as the tile count grows: a larger tile
-  // reads X and the decoded W less often per product, a smaller one fills the 256 CUs sooner.
-  // The thresholds are measured on 4096 x 4096, 11008 x 4096 and 4096 x 11008, B = 24..4096.
+  // bandwidth-bound) while they are few enough to run in about one wave of workgroups, then
+  // gemm_kernel with 32 x 128 tiles while those fit the CUs once, and beyond that the cheapest
+  // of four tilings by a small cost model: 64 x 128 and 64 x 256 (4 waves, two workgroups per
+  // CU: time grows almost linearly with the tile count) and 128 x 128 and 128 x 256 (8 waves, one
+  // workgroup per CU: half the X traffic per product, but time moves in whole rounds of 256
+  // tiles).  The constants are microseconds measured at in_features = 4096 on 4096- and
+  // 11008-row matrices, B = 512..4096; only their ratios matter.
   const int n_rb = d.out_features / kGroupRows;
   const bool short_matrix = n_rb < 1024;
   const bool tiny = B <= 16 || (B <= 64 && short_matrix);
   const long long tiles_small = (long long)((n_rb + 3) / 4) * ((B + 31) / 32);
-  const long long tiles_64x128 = (long long)((n_rb + 7) / 8) * ((B + 127) / 128);
+  const long long rows64 = (n_rb + 7) / 8, rows128 = (n_rb + 15) / 16;
+  const long long cols128 = (B + 127) / 128, cols256 = (B + 255) / 256;
   const bool small = B <= 32 || tiles_small <= 768;
+  const bool one_round_32x128 = rows64 * cols128 <= 128;
+  const double est[4] = {20.0 + 0.11 * (double)(rows64 * cols128),                // 64 x 128
+                         35.0 + 0.165 * (double)(rows64 * cols256),               // 64 x 256
+                         54.0 * (double)((rows128 * cols128 + 255) / 256),        // 128 x 128
+                         79.0 * (double)((rows128 * cols256 + 255) / 256)};       // 128 x 256
+  int best = 0;
+  for (int i = 1; i < 4; ++i)
+    if (est[i] < est[best]) best = i;
 #define VQ_GEMM_DISPATCH(K)                                                                       \
   {                                                                                               \
     if (tiny) return launch_tiny<K>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);             \
     if (small) return launch_small<K>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);           \
-    if (tiles_64x128 <= 128)                                                                      \
+    if (one_round_32x128)                                                                         \
       return launch_one<K, 1, 128>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);              \
-    if (tiles_64x128 < 1024)                                                                      \
-      return launch_one<K, 2, 128>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);              \
-    return launch_one<K, 2, 256>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);                \
+    if (best == 0) return launch_one<K, 2, 128>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s); \
+    if (best == 1) return launch_one<K, 2, 256>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s); \
+    if (best == 2)                                                                                \
+      return launch_one<K, 2, 128, 2>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);           \
+    return launch_one<K, 2, 256, 2>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);             \
   }
   const int fmt = format_tag(d);
   if (fmt == 64) VQ_GEMM_DISPATCH(64)

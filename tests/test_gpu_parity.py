@@ -513,8 +513,9 @@ def test_int8_tables_gemm_tall(env, s, B):
 
 # The matrix-core kernels with 128- and 256-column tiles are chosen by tile count, so a short
 # matrix reaches them only with a wide batch: 1000 columns -> 32 x 128 tiles, 1300 -> 64 x 128,
-# 10100 -> 64 x 256 (ragged last column tile in each; 101 row-blocks leave a ragged row tile).
-@pytest.mark.parametrize("B", [1000, 1300, 10100])
+# 10100 -> 64 x 256, and the 8-wave tiles where whole rounds of 256 tiles fit best: 4600 -> 128 x 128,
+# 9200 -> 128 x 256 (ragged last column tile in each; 101 row-blocks leave a ragged row tile).
+@pytest.mark.parametrize("B", [1000, 1300, 4600, 9200, 10100])
 @pytest.mark.parametrize("s", [_shape(800, 512, 16), _shape(808, 768, 256), _shape64(800, 512),
                                _shape16i8(808, 512), _shape_d1(808, 512)], ids=str)
 def test_gemm_wide_batches(env, s, B):
