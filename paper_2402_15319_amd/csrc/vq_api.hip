@@ -10,11 +10,11 @@ using namespace vq;
 
 bool is_pow2(int v) { return v > 0 && (v & (v - 1)) == 0; }
 
-// The two representations the kernels implement:
+// The representations the kernels implement (d = 2 unless stated):
 //   fp16 codebooks, 8 x 256 groups, k = 16 (4-bit indices) or 256 (8-bit);
 //   int8 tables with one fp16 scale per group: k = 64 (6-bit indices), groups of 8, 16 or 32
 //   rows x 256 columns (32 rows = the 8,192-weight groups of Sec. 5.1), or k = 16 with 8 x 256
-//   groups (2.125 bits per value);
+//   groups (2.125 bits per value); k = 64 also with blockwise normalisation (VQ_I8_BN);
 //   d = 1 (scalar codebooks): k = 16 fp16 values per 8 x 256 group, 4-bit indices (4.125 bits
 //   per value, the overhead of the 1D 4.125 row of the appendix table of VQ configurations);
 //   d = 1, k = 8: 3-bit indices, 8 int8 values + scale per group of 8, 16 or 32 rows x 256 columns
