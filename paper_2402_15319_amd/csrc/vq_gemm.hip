@@ -433,26 +433,13 @@ __global__ __launch_bounds__(256 * WM, WM == 1 ? 2 : 1) void gemm_kernel(const u
 // 16 rows (two row-blocks) x 16 batch columns per workgroup, v_mfma_f32_16x16x32_f16.  The
 // four waves split K by col-block (wave w takes col-blocks w, w+4, ...) and share nothing
 // until the end: each wave decodes its two groups into a private LDS tile Wt[16][256],
-// transposes its X tile into a private Xt[16 columns][256 k], and multiplies; there is
+// copies its X tile unchanged into a private Xt[256 k][16 columns] (the matrix-core operand is
+// formed by the transposing LDS read), and multiplies; there is
 // no workgroup barrier inside the K loop, so the waves of a CU run out of step and hide
 // each other's latencies.  Indices, codebooks and X of the wave's next col-block load
 // into registers while the current one is processed.  The four partial 16 x 16 tiles meet
 // in LDS at the end.  Many small workgroups (out/16 per 16 columns) keep every CU streaming.
 typedef float f4v_t __attribute__((ext_vector_type(4)));
-
-// Writes a piece (8 k x 4 columns, transposed in registers) as 4 rows of Xt[column][k].
-__device__ __forceinline__ void store_xpiece_rows(const XPiece& p, uint16_t* Xt, int n_loc, int k0) {
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const uint32_t sel = (i & 1) ? 0x07060302u : 0x05040100u;
-    uint4 o;
-    o.x = __builtin_amdgcn_perm(i < 2 ? p.r[1].x : p.r[1].y, i < 2 ? p.r[0].x : p.r[0].y, sel);
-    o.y = __builtin_amdgcn_perm(i < 2 ? p.r[3].x : p.r[3].y, i < 2 ? p.r[2].x : p.r[2].y, sel);
-    o.z = __builtin_amdgcn_perm(i < 2 ? p.r[5].x : p.r[5].y, i < 2 ? p.r[4].x : p.r[4].y, sel);
-    o.w = __builtin_amdgcn_perm(i < 2 ? p.r[7].x : p.r[7].y, i < 2 ? p.r[6].x : p.r[6].y, sel);
-    *reinterpret_cast<uint4*>(Xt + wt_half_index(n_loc + i, k0)) = o;
-  }
-}
 
 template <int K>
 __global__ __launch_bounds__(256, 2) void gemm_tiny_kernel(const uint8_t* __restrict__ idx,
@@ -461,7 +448,9 @@ __global__ __launch_bounds__(256, 2) void gemm_tiny_kernel(const uint8_t* __rest
                                                            int ldx, void* __restrict__ Y, int ldy,
                                                            int y_f32, int n_rb, int n_cb, int rpc) {
   __shared__ __attribute__((aligned(16))) uint16_t Wt_all[4][16 * WS];
-  __shared__ __attribute__((aligned(16))) uint16_t Xt_all[4][16 * WS];
+  // [k][16 columns], as in memory; half a col-block at a time, which keeps the workgroup under
+  // a third of the LDS for the small-table formats (three workgroups per CU)
+  __shared__ __attribute__((aligned(16))) uint16_t Xt_all[4][128 * 16];
   __shared__ __attribute__((aligned(16))) uint32_t lut_all[4][2 * lut_dwords<K>()];
 
   const int tid = threadIdx.x;
@@ -475,16 +464,21 @@ __global__ __launch_bounds__(256, 2) void gemm_tiny_kernel(const uint8_t* __rest
   const long long rb1 = min(rb0 + 1, (long long)n_rb - 1);   // odd tail: decoded twice, stored once
   const int n0 = blockIdx.y * 16;
 
-  // the lane's two X pieces of a col-block: k-octets o and o + 16, columns 4q..4q+3
-  const int q = lane & 3, o = lane >> 2;
-  const int n_glob = n0 + 4 * q;
-  const bool n_ok = n_glob < B;
-  const int n_ld = n_ok ? n_glob : 0;
-  const uint32_t n_mask = n_ok ? 0xffffffffu : 0u;
-
+  // X of a col-block (256 rows x 16 columns) is copied to LDS unchanged in 8 passes of 32 rows:
+  // the lane owns 16 bytes (8 columns: half `xh`) of row lane / 2 of every pass, so a pass is
+  // one coalesced 1 KB load when ldx = 16.  A half that lies beyond the row (ldx < 16 columns
+  // from n0) is not loaded; columns between B and ldx hold whatever X holds there and only
+  // reach accumulator columns that are never written.
+  const int xh = lane & 1;
+  const bool x_ok = n0 + 8 * xh + 8 <= ldx;
+  const size_t x_lane = (size_t)(lane >> 1) * ldx + (x_ok ? n0 + 8 * xh : 0);
+  const int xs_off = (lane >> 1) * 32 + xh * 16;                 // bytes inside Xt
+  // operand role (ds_read_b64_tr_b16): lane i of a 16-lane block addresses row i / 4, fragment
+  // i % 4 of a 4 x 16 tile and receives column i
+  const int xr_off = (8 * (lane >> 4) + ((lane & 15) >> 2)) * 32 + (lane & 3) * 8;
   f4v_t acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
   GroupRegs<K> g[2][2];
-  XPiece xp[2][2];
+  u32x4_t xr[2][8];
 
   // every load is issued whether or not the col-block exists (clamped), so that the number
   // of loads in flight is static and the waits stay partial
@@ -493,27 +487,25 @@ __global__ __launch_bounds__(256, 2) void gemm_tiny_kernel(const uint8_t* __rest
     const int cc = min((C), n_cb - 1);                                                 \
     load_group<K>(g[SLOT][0], idx, cb, rb0, cc, n_cb, lane, n_rb, rpc);                           \
     load_group<K>(g[SLOT][1], idx, cb, rb1, cc, n_cb, lane, n_rb, rpc);                           \
-    load_xpiece(xp[SLOT][0], X, (size_t)cc * 256 + 8 * o, ldx, n_ld, true);            \
-    load_xpiece(xp[SLOT][1], X, (size_t)cc * 256 + 8 * (o + 16), ldx, n_ld, true);     \
+    _Pragma("unroll") for (int j = 0; j < 8; ++j)                                      \
+      xr[SLOT][j] = *reinterpret_cast<const u32x4_t*>(X + ((size_t)cc * 256 + 32 * j) * ldx + x_lane); \
   }
 #define VQ_PROCESS(SLOT)                                                               \
   {                                                                                    \
     decode_group<K>(g[SLOT][0], lut, Wt, 0, lane);                                     \
     decode_group<K>(g[SLOT][1], lut + lut_dwords<K>(), Wt, 8, lane);                                 \
-    _Pragma("unroll") for (int h = 0; h < 2; ++h) {                                    \
-      _Pragma("unroll") for (int r = 0; r < 8; ++r) {                                  \
-        xp[SLOT][h].r[r].x &= n_mask;                                                  \
-        xp[SLOT][h].r[r].y &= n_mask;                                                  \
+    _Pragma("unroll") for (int hf = 0; hf < 2; ++hf) {                                 \
+      _Pragma("unroll") for (int j = 0; j < 4; ++j)                                    \
+        *reinterpret_cast<u32x4_t*>(reinterpret_cast<char*>(Xt) + 1024 * j + xs_off) = \
+            x_ok ? xr[SLOT][4 * hf + j] : u32x4_t{0u, 0u, 0u, 0u};                     \
+      wave_lds_sync();                                                                 \
+      _Pragma("unroll") for (int kk = 0; kk < 4; ++kk) {                               \
+        const int k0 = 32 * (4 * hf + kk) + 8 * (lane >> 4);                           \
+        const h8_t av = *reinterpret_cast<const h8_t*>(Wt + wt_half_index(lane & 15, k0)); \
+        const h8_t bv = read_x_operand<16>(reinterpret_cast<const char*>(Xt) + 1024 * kk + xr_off); \
+        if (kk & 1) acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bv, acc1, 0, 0, 0); \
+        else acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bv, acc0, 0, 0, 0);     \
       }                                                                                \
-      store_xpiece_rows(xp[SLOT][h], Xt, 4 * q, 8 * (o + 16 * h));                     \
-    }                                                                                  \
-    wave_lds_sync();                                                                   \
-    _Pragma("unroll") for (int kk = 0; kk < 8; ++kk) {                                 \
-      const int k0 = 32 * kk + 8 * (lane >> 4);                                        \
-      const h8_t av = *reinterpret_cast<const h8_t*>(Wt + wt_half_index(lane & 15, k0)); \
-      const h8_t bv = *reinterpret_cast<const h8_t*>(Xt + wt_half_index(lane & 15, k0)); \
-      if (kk & 1) acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bv, acc1, 0, 0, 0); \
-      else acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bv, acc0, 0, 0, 0);       \
     }                                                                                  \
   }
 
