@@ -16,9 +16,10 @@
 //     sub-steps through two X buffers (one barrier per sub-step), wave w owns a quarter of
 //     the batch columns and 32*RBW rows (RBW x NT/128 accumulator tiles); with WM = 2 the
 //     workgroup has 8 waves and twice the rows, the second four waves taking the lower half;
-//   * gemm_small_kernel (32 x 32 tiles, bandwidth-bound batches) and gemm_tiny_kernel
-//     (16 x 16) transpose X in registers instead: a thread loads 8 rows x 4 columns, swaps
-//     halves with v_perm and writes 4 x 16 bytes, giving Xs[k/8][n][k%8].
+//   * gemm_tiny_kernel (16 x 16 tiles) copies X the same way, into a private tile per wave;
+//     gemm_small_kernel (32 x 32 tiles, bandwidth-bound batches) transposes X in registers
+//     instead: a thread loads 8 rows x 4 columns, swaps halves with v_perm and writes
+//     4 x 16 bytes, giving Xs[k/8][n][k%8].
 #include "vq_device.h"
 #include "vq_internal.h"
 
