@@ -16,10 +16,8 @@
 //     sub-steps through two X buffers (one barrier per sub-step), wave w owns a quarter of
 //     the batch columns and 32*RBW rows (RBW x NT/128 accumulator tiles); with WM = 2 the
 //     workgroup has 8 waves and twice the rows, the second four waves taking the lower half;
-//   * gemm_tiny_kernel (16 x 16 tiles) copies X the same way, into a private tile per wave;
-//     gemm_small_kernel (32 x 32 tiles, bandwidth-bound batches) transposes X in registers
-//     instead: a thread loads 8 rows x 4 columns, swaps halves with v_perm and writes
-//     4 x 16 bytes, giving Xs[k/8][n][k%8].
+//   * gemm_tiny_kernel (16 x 16 tiles, a private X tile per wave) and gemm_small_kernel
+//     (32 x 32 tiles, bandwidth-bound batches) copy X the same way.
 #include "vq_device.h"
 #include "vq_internal.h"
 
@@ -214,40 +212,7 @@ __device__ __forceinline__ void decode_group(const GroupRegs<K>& g, uint32_t* lu
     *reinterpret_cast<uint2*>(Wt + wt_half_index(m0 + r, 4 * lane)) = make_uint2(v[2 * r], v[2 * r + 1]);
 }
 
-// One thread's piece of an X sub-tile: 8 consecutive k x 4 consecutive batch columns.
-struct XPiece {
-  uint2 r[8];
-};
-__device__ __forceinline__ void load_xpiece(XPiece& p, const uint16_t* X, size_t k0, int ldx, int n0,
-                                            bool ok) {
-#pragma unroll
-  for (int j = 0; j < 8; ++j)
-    p.r[j] = ok ? *reinterpret_cast<const uint2*>(X + (k0 + j) * ldx + n0) : make_uint2(0, 0);
-}
-// The X sub-tile is Xs[k/8][column][8 halfs]: 16-byte units, one per (k-octet, column).  Inside
-// a k-octet row the unit of column n sits at n ^ ((n >> 3) & 3): a thread stores 4 consecutive
-// columns (units 64 bytes apart from its neighbour's), and without the swizzle the 8 lanes of one
-// pass of a 128-bit store would use only two of the eight 16-byte bank groups (4-way conflict);
-// with it they use all eight, and the 8 consecutive columns an MFMA operand read covers per pass
-// still map to eight distinct units.
-__device__ __forceinline__ int xs_unit(int n) { return n ^ ((n >> 3) & 3); }
-
-// Writes the piece transposed: 4 columns x 8 k (16 bytes per column).  dst points at the unit
-// of the piece's first column n0 (a multiple of 4) before swizzling; c = (n0 >> 3) & 3.
-__device__ __forceinline__ void store_xpiece(const XPiece& p, uint32_t* dst, int c) {
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const uint32_t sel = (i & 1) ? 0x07060302u : 0x05040100u;   // high or low halves of a dword pair
-    uint4 o;
-    o.x = __builtin_amdgcn_perm(i < 2 ? p.r[1].x : p.r[1].y, i < 2 ? p.r[0].x : p.r[0].y, sel);
-    o.y = __builtin_amdgcn_perm(i < 2 ? p.r[3].x : p.r[3].y, i < 2 ? p.r[2].x : p.r[2].y, sel);
-    o.z = __builtin_amdgcn_perm(i < 2 ? p.r[5].x : p.r[5].y, i < 2 ? p.r[4].x : p.r[4].y, sel);
-    o.w = __builtin_amdgcn_perm(i < 2 ? p.r[7].x : p.r[7].y, i < 2 ? p.r[6].x : p.r[6].y, sel);
-    *reinterpret_cast<uint4*>(dst + (i ^ c) * 4) = o;
-  }
-}
-
-// ---- X staging of gemm_kernel -----------------------------------------------------------
+// ---- X staging (all three kernels) ------------------------------------------------------
 // An X sub-tile lives in LDS as it is in memory, Xs[k][NT] halfs with the batch index
 // contiguous, and the matrix-core operand (8 consecutive k of one column per lane) is formed by
 // the transposing LDS read ds_read_b64_tr_b16.  In each block of 16 lanes, lane i hands in the
@@ -565,7 +530,9 @@ __global__ __launch_bounds__(256, 2) void gemm_small_kernel(const uint8_t* __res
                                                             int n_tiles_n, int rpc) {
   constexpr int MT = 32, NT = 32;
   __shared__ __attribute__((aligned(16))) uint16_t Wt_all[2][MT * WS];
-  __shared__ __attribute__((aligned(16))) uint32_t Xs_all[2][4096];     // [32 k-octets][32 n][8 halfs]
+  // X tile [256 k][32 n] halfs as in memory; the 32-byte chunk c of row k sits at c ^ ((k >> 1) & 1),
+  // which puts the four rows of a transposing read into four different bank groups
+  __shared__ __attribute__((aligned(16))) uint32_t Xs_all[2][4096];
   __shared__ __attribute__((aligned(16))) uint32_t lut_all[4][lut_dwords<K>()];
 
   const int tid = threadIdx.x;
@@ -575,11 +542,20 @@ __global__ __launch_bounds__(256, 2) void gemm_small_kernel(const uint8_t* __res
   const int nt = blockIdx.x - mt * n_tiles_n;
   uint32_t* lut = lut_all[wave];
 
-  const int ko = tid / (NT / 4);             // k-octet of the col-block, 0..31
-  const int n_loc = (tid % (NT / 4)) * 4;
+  // X staging role: the col-block's tile is copied unchanged in 4 passes of 64 rows; the thread
+  // owns 16 bytes (8 batch columns from n_loc) of row x_row of every pass.  A piece that lies
+  // beyond the row (ldx) is not loaded; columns between B and ldx only reach accumulator
+  // columns that are never written.
+  const int x_row = tid >> 2;
+  const int n_loc = (tid & 3) * 8;
   const int n_glob = nt * NT + n_loc;
-  const bool n_ok = n_glob < B;
-  const int xs_off = (ko * NT + n_loc) * 4;
+  const bool x_ok = n_glob + 8 <= ldx;
+  const size_t x_lane = (size_t)x_row * ldx + (x_ok ? n_glob : 0);
+  const int xs_off = x_row * 64 + ((((n_loc >> 4) ^ ((x_row >> 1) & 1)) << 5) | ((n_loc & 8) << 1));   // bytes
+  // operand role (ds_read_b64_tr_b16): lane i of a 16-lane block addresses row i / 4, fragment
+  // i % 4 of a 4 x 16 tile and receives column i; rows 8 * (lane / 32) + 0..7 of a 16-deep step
+  const int xr_kq = (lane & 15) >> 2;
+  const int xr_off = (8 * (lane >> 5) + xr_kq) * 64 + (((((lane >> 4) & 1) ^ ((xr_kq >> 1) & 1))) << 5) + (lane & 3) * 8;
 
   f16v_t acc;
 #pragma unroll
@@ -594,21 +570,22 @@ __global__ __launch_bounds__(256, 2) void gemm_small_kernel(const uint8_t* __res
   // instead: a ring of D col-blocks (indices, codebook and the X piece) is kept in
   // flight in registers.  Loads are unconditional (clamped to the last col-block) so
   // that the compiler can count them and wait only for the oldest.
+#define VQ_LOAD_X(j, c)                                                                         \
+  _Pragma("unroll") for (int pass = 0; pass < 4; ++pass)                                        \
+    xp[j].r[pass] = *reinterpret_cast<const u32x4_t*>(X + ((size_t)(c) * 256 + 64 * pass) * ldx + x_lane);
   constexpr int D = 4;
-  const int n_ld = n_ok ? n_glob : 0;
   GroupRegs<K> g[D];
-  XPiece xp[D];
+  XRows xp[D];
 #pragma unroll
   for (int j = 0; j < D; ++j) {
     const int cj = min(j, n_cb - 1);
     load_group<K>(g[j], idx, cb, rb_ld, cj, n_cb, lane, n_rb, rpc);
-    load_xpiece(xp[j], X, (size_t)cj * 256 + ko * 8, ldx, n_ld, true);
+    VQ_LOAD_X(j, cj)
   }
 
   // Ring slot j (col-block c) -> LDS buffer j & 1 (D is even); with REFILL the slot is
   // then reloaded with col-block c + D.  Everything that loads is branch-free: col-blocks
   // past the end are clamped reads whose tiles are staged but never multiplied.
-  const uint32_t n_mask = n_ok ? 0xffffffffu : 0u;
 #define VQ_STAGE(j, c, REFILL)                                                                  \
   {                                                                                             \
     uint16_t* Wt_w = Wt_all[(j) & 1];                                                           \
@@ -618,15 +595,13 @@ __global__ __launch_bounds__(256, 2) void gemm_small_kernel(const uint8_t* __res
       _Pragma("unroll") for (int r = 0; r < 8; ++r)                                             \
           *reinterpret_cast<uint2*>(Wt_w + wt_half_index(m0 + r, 4 * lane)) = make_uint2(0u, 0u); \
     }                                                                                           \
-    _Pragma("unroll") for (int r = 0; r < 8; ++r) {                                             \
-      xp[j].r[r].x &= n_mask;                                                                   \
-      xp[j].r[r].y &= n_mask;                                                                   \
-    }                                                                                           \
-    store_xpiece(xp[j], Xs_all[(j) & 1] + xs_off, (n_loc >> 3) & 3);                            \
+    _Pragma("unroll") for (int pass = 0; pass < 4; ++pass)                                      \
+      *reinterpret_cast<u32x4_t*>(reinterpret_cast<char*>(Xs_all[(j) & 1]) + 4096 * pass + xs_off) = \
+          x_ok ? xp[j].r[pass] : u32x4_t{0u, 0u, 0u, 0u};                                       \
     if (REFILL) {                                                                               \
       const int cn = min((c) + D, n_cb - 1);                                                    \
-      load_group<K>(g[j], idx, cb, rb_ld, cn, n_cb, lane, n_rb, rpc);                                      \
-      load_xpiece(xp[j], X, (size_t)cn * 256 + ko * 8, ldx, n_ld, true);                        \
+      load_group<K>(g[j], idx, cb, rb_ld, cn, n_cb, lane, n_rb, rpc);                           \
+      VQ_LOAD_X(j, cn)                                                                          \
     }                                                                                           \
   }
   // multiply col-block c (staged in buffer j & 1) if it exists, then release the buffer
@@ -634,11 +609,10 @@ __global__ __launch_bounds__(256, 2) void gemm_small_kernel(const uint8_t* __res
   {                                                                                             \
     if ((c) < n_cb) {                                                                           \
       const uint16_t* Wt = Wt_all[(j) & 1];                                                     \
-      const uint32_t* Xs = Xs_all[(j) & 1];                                                     \
+      const char* Xs = reinterpret_cast<const char*>(Xs_all[(j) & 1]);                          \
       _Pragma("unroll") for (int kk = 0; kk < 4; ++kk) {                                        \
         const int k16 = wave * 4 + kk;                                                          \
-        const h8_t bv = *reinterpret_cast<const h8_t*>(                                         \
-            Xs + ((2 * k16 + (lane >> 5)) * NT + xs_unit(lane & 31)) * 4);                      \
+        const h8_t bv = read_x_operand<NT>(Xs + 1024 * k16 + xr_off);                           \
         const h8_t av = *reinterpret_cast<const h8_t*>(                                         \
             Wt + wt_half_index(lane & 31, 16 * k16 + 8 * (lane >> 5)));                         \
         acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(av, bv, acc, 0, 0, 0);                     \
@@ -663,6 +637,7 @@ __global__ __launch_bounds__(256, 2) void gemm_small_kernel(const uint8_t* __res
   VQ_MULTIPLY(3, c0 + 3)
 #undef VQ_STAGE
 #undef VQ_MULTIPLY
+#undef VQ_LOAD_X
   static_assert(D == 4, "the unrolled ring above is written for four slots");
 
   // four partial 32 x 32 tiles (one per wave) -> LDS -> sum -> Y
