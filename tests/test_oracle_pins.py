@@ -536,3 +536,23 @@ def test_four_dimensional_format_sizes_follow_the_bpv_formula():
         ib, tb = oracle.canonical_sizes_i8(f)
         assert ib == 4096 * 4096 // 4 and tb == f.n_groups * 1024 + 2 * f.n_groups
         assert (ib + tb - 2 * f.n_groups) * 8 / (4096 * 4096) == bpv
+
+
+# ---------------------------------------------------------------- the bit stream against Python's big integers
+def test_unpack_indices_against_big_integer_arithmetic():
+    """A group's index bytes read as ONE little-endian integer: vector v is (N >> v*b) & (2^b - 1).
+    Python's arbitrary-precision integers do the shifting here, for every index width from 1 to 12 bits
+    (including widths that straddle one or two byte boundaries)."""
+    rng = np.random.default_rng(77)
+    for bits in range(1, 13):
+        k = 1 << bits
+        # group of 2 rows x 16 columns, d = 2 -> 16 vectors; 16 * bits is always a multiple of 8
+        f = VQFormat(4, 32, k, bits, 2, 16, 2)
+        nbytes = oracle.canonical_sizes(f)[0]
+        idx = rng.integers(0, 256, size=nbytes, dtype=np.uint8)
+        got = oracle.unpack_indices(f, idx)
+        gb = f.group_index_bytes
+        for g in range(f.n_groups):
+            N = int.from_bytes(bytes(idx[g * gb:(g + 1) * gb]), "little")
+            want = [(N >> (v * bits)) & (k - 1) for v in range(f.vectors_per_group)]
+            assert list(got[g]) == want, (bits, g)
