@@ -773,3 +773,60 @@ def test_d1k8_full_size_layer(env):
     np.testing.assert_array_equal(_gpu_decode(env, desc, idx_d, cb_d), oracle.decode_dense(f, idx, cb))
     x = workloads.make_x(s.in_features, 742)
     assert oracle.normwise_rel_err(_gpu_gemv(env, desc, idx_d, cb_d, x, False), oracle.gemv(f, idx, cb, x)) <= TOL_F16
+
+
+def test_newer_kernels_replay_in_a_hip_graph(env):
+    """The d = 4 GEMV (workgroup barriers, double-buffered tables), the block-normalised and
+    scalar-codebook GEMVs, an 8-wave GEMM tile and the quantiser's two steps in one HIP graph:
+    three replays with eager work in between reproduce the eager results bit for bit."""
+    torch, vq, vqdev = env
+    dev = "cuda:0"
+    s4 = _shape_d4(256, 1280)
+    d4, _, _, i4, c4 = _setup_i8(env, s4, 910)
+    sb = _shape_bn(96, 768)
+    db, _, ib, cb_b = _setup_bn(env, sb, 911)
+    s1 = _shape_d1(72, 1280)
+    d1, _, _, i1, c1 = _setup(env, s1, 912)
+    sg = _shape(808, 512, 16)
+    dg, _, _, ig, cg = _setup(env, sg, 913)
+    Bg = 4600                                              # 128 x 128 tiles
+    xs = {n: vqdev.to_device_bytes(workloads.make_x(n, 914)) for n in (1280, 768)}
+    Xg = vqdev.to_device_bytes(workloads.make_X(512, Bg, 915))
+    rng = np.random.default_rng(916)
+    Wq = vqdev.to_device_bytes(rng.normal(0, 0.02, (16, 512)).astype(np.float32))
+    hq = vqdev.to_device_bytes(rng.uniform(0.2, 5.0, 512).astype(np.float32))
+    cq = vqdev.to_device_bytes(rng.normal(0, 0.02, (4, 16, 2)).astype(np.float32))
+    dq = vq.make_desc(16, 512, 16, 4)
+
+    def outputs():
+        return [torch.zeros(256, dtype=torch.float16, device=dev), torch.zeros(96, dtype=torch.float16, device=dev),
+                torch.zeros(72, dtype=torch.float16, device=dev),
+                torch.zeros((808, Bg), dtype=torch.float16, device=dev),
+                torch.zeros((16, 256), dtype=torch.uint8, device=dev),
+                torch.zeros((4, 16, 2), dtype=torch.float32, device=dev)]
+
+    def enqueue(o):
+        vq.vq_gemv(d4, i4, c4, xs[1280], o[0])
+        vq.vq_gemv(db, ib, cb_b, xs[768], o[1])
+        vq.vq_gemv(d1, i1, c1, xs[1280], o[2])
+        vq.vq_gemm_batched(dg, ig, cg, Xg, Bg, Bg, o[3], Bg)
+        vq.vq_em_assign(dq, Wq, hq, cq, o[4])
+        vq.vq_em_update(dq, Wq, hq, o[4], o[5])
+
+    eager = outputs()
+    enqueue(eager)
+    torch.cuda.synchronize()
+    want = [t.cpu().numpy().copy() for t in eager]
+    assert np.abs(want[0].astype(np.float64)).max() > 0 and want[4].max() > 0
+    captured = outputs()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        enqueue(captured)
+    for replay in range(3):
+        for t in captured:
+            t.fill_(1)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for a, b in zip(captured, want):
+            np.testing.assert_array_equal(a.cpu().numpy().view(np.uint8), b.view(np.uint8))
