@@ -218,6 +218,9 @@ def main():
                 # scalar codebooks at 3 bits: 8 int8 values + scale per 32 x 256 group (3.01 bpv)
                 ("llama7b_pass_d1_k8_int8_3.01bpv_via_vq_gemv_multi", workloads.LLAMA7B_LAYER_D1_K8,
                  "gemv_stream_kernel<d1,k8>"),
+                # scalar codebooks at 2 bits: 4 int8 values + scale per row of a col-block (2.19 bpv)
+                ("llama7b_pass_d1_k4_int8_2.19bpv_via_vq_gemv_multi", workloads.LLAMA7B_LAYER_D1_K4,
+                 "gemv_stream_kernel<d1,k4>"),
                 # scalar codebooks (d = 1): 16 fp16 values per 8 x 256 group, 4-bit indices, 3.47 GB
                 ("llama7b_pass_d1_k16_4.125bpv_via_vq_gemv_multi", workloads.LLAMA7B_LAYER_D1_K16,
                  "gemv_stream_kernel<d1,k16>")):
@@ -236,6 +239,10 @@ def main():
                         tv = tab.view(-1, 48)
                         tv[:, 32:48] = 0
                         tv[:, 33:40:2] = 0x1C
+                    elif s.d == 1 and s.k == 4:         # 48-byte records: 8 x 4 int8, 8 scales (2^-8)
+                        tv = tab.view(-1, 48)
+                        tv[:, 32:48:2] = 0
+                        tv[:, 33:48:2] = 0x1C
                     elif s.d == 1:                      # fp16 scalars
                         tab = (torch.randn(cbb // 2, device=dev) * 0.02).half().view(torch.uint8)
                     elif s.block_norm:                  # 672-byte records (+ 64 levels, set to 1.0), then nibble codes

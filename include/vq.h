@@ -48,7 +48,10 @@
  * (32 rows: the 8,192-weight groups and 3.125 bits per value of Sec. 5.1); VQ_I8 with k = 16
  * and 8 x 256 groups (2.125 bits per value); and scalar codebooks, d = 1 (the 1D rows of the
  * appendix table of VQ configurations): VQ_F16, k = 16, 4-bit indices, 8 x 256 groups, 4.125
- * bits per value, and VQ_I8, k = 8, 3-bit indices, groups of 8, 16 or 32 rows x 256 columns; VQ_I8_BN with k = 64 and groups of 8, 16 or 32 rows x 256 columns; and
+ * bits per value; VQ_I8, k = 8, 3-bit indices, groups of 8, 16 or 32 rows x 256 columns; and
+ * VQ_I8, k = 4, 2-bit indices, groups of 1 x 256 (one codebook per row of a 256-column block,
+ * the 2.125-bit 1D row; out_features a multiple of 8); VQ_I8_BN with k = 64 and groups of 8, 16
+ * or 32 rows x 256 columns; and
  * four-dimensional vectors, d = 4 (the 4D rows of that table): VQ_I8, k = 256 (one index byte per
  * 4 weights), groups of 64, 128 or 256 rows x 256 columns (256 rows: 2.125 bits per value).
  * Every entry point takes all of them.

@@ -37,6 +37,9 @@ int check_desc(const vq_desc* d) {
     if (d->k == 8) {          // 3-bit indices, int8 values + scale, group heights of the k = 64 format
       if (d->codebook_dtype != VQ_I8) return VQ_ERR_UNSUPPORTED;
       if (d->group_rows != 8 && d->group_rows != 16 && d->group_rows != 32) return VQ_ERR_UNSUPPORTED;
+    } else if (d->k == 4) {   // 2-bit indices, int8 values + scale, one codebook per row of a col-block
+      if (d->codebook_dtype != VQ_I8 || d->group_rows != 1) return VQ_ERR_UNSUPPORTED;
+      if (d->out_features % kGroupRows) return VQ_ERR_UNSUPPORTED;
     } else if (d->k != 16 || is_i8(*d) || d->group_rows != kGroupRows) {
       return VQ_ERR_UNSUPPORTED;
     }
@@ -80,7 +83,7 @@ void sizes(const vq_desc& d, size_t* idx_bytes, size_t* cb_bytes) {
 
 // Units a row-block of `n_cb` col-blocks is cut into (what the strips of the GEMV kernels count).
 int strip_units(int fmt, int n_cb) {
-  return (fmt == 16 || fmt == kFmtK16I8) ? (n_cb + 1) / 2 : (fmt == 64 || fmt == kFmtK64BN || fmt == kFmtD1K8) ? (n_cb + 3) / 4 : n_cb;
+  return (fmt == 16 || fmt == kFmtK16I8 || fmt == kFmtD1K4) ? (n_cb + 1) / 2 : (fmt == 64 || fmt == kFmtK64BN || fmt == kFmtD1K8) ? (n_cb + 3) / 4 : n_cb;
 }
 
 int hip_status(hipError_t e) { return e == hipSuccess ? VQ_OK : VQ_ERR_HIP; }
@@ -158,6 +161,12 @@ int vq_layout_bytes(const vq_desc* desc, size_t* idx_bytes, size_t* cb_bytes) {
     const size_t n_quads = (n_cb + 3) / 4;
     if (idx_bytes) *idx_bytes = n_rb * n_quads * 3072;
     if (cb_bytes) *cb_bytes = (size_t)(desc->out_features / desc->group_rows) * n_quads * 48;
+    return VQ_OK;
+  }
+  if (desc->d == 1 && desc->k == 4) {   // indices as for k = 16; a 48-byte table record per (8-row block, col-block slot)
+    const size_t slots = 2 * ((n_cb + 1) / 2);
+    if (idx_bytes) *idx_bytes = n_rb * slots * 512;
+    if (cb_bytes) *cb_bytes = n_rb * slots * 48;
     return VQ_OK;
   }
   if (desc->d == 1) {    // 1 KB of indices and 16 fp16 scalars per group

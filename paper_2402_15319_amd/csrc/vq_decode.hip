@@ -10,13 +10,14 @@ namespace {
 
 // K: 16 or 256 with fp16 codebooks, kFmtK16I8 for k = 16 with int8 tables and a scale per group
 // (32 bytes per group slot, then one fp16 scale per slot behind all the tables), kFmtD1K16 for
-// scalar codebooks (16 fp16 values per group; a byte of indices looks up a pair of them).
+// scalar codebooks (16 fp16 values per group; a byte of indices looks up a pair of them), kFmtD1K4
+// for 2-bit scalar codebooks with one table per row (a nibble of indices looks up a pair).
 template <int K>
 __global__ __launch_bounds__(256) void decode_kernel(const uint8_t* __restrict__ idx,
                                                      const uint32_t* __restrict__ cb,
                                                      uint16_t* __restrict__ W, int n_cb,
                                                      long long n_groups, int in_features) {
-  __shared__ uint32_t lut_all[4][K == kFmtK16I8 ? 16 : K == kFmtD1K16 ? 256 : K];
+  __shared__ uint32_t lut_all[4][K == kFmtK16I8 ? 16 : K == kFmtD1K16 ? 256 : K == kFmtD1K4 ? 128 : K];
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   uint32_t* lut = lut_all[wave];
@@ -26,7 +27,31 @@ __global__ __launch_bounds__(256) void decode_kernel(const uint8_t* __restrict__
   const int c = (int)(g - rb * n_cb);
   uint16_t* out = W + (size_t)rb * 8 * in_features + (size_t)c * 256 + lane * 4;
 
-  if (K == 16 || K == kFmtK16I8) {
+  if (K == kFmtD1K4) {   // a 16-entry pair table per row: lane L builds entries 2*(L&7), +1 of row L >> 3
+    const int slots = 2 * k16_pairs(n_cb);
+    const uint8_t* rec = reinterpret_cast<const uint8_t*>(cb) + (size_t)(rb * slots + c) * kD1K4SlotTabBytes;
+    const uint32_t q4 = *reinterpret_cast<const uint32_t*>(rec + (lane >> 3) * 4);
+    const _Float16 scale = __builtin_bit_cast(
+        _Float16, *reinterpret_cast<const uint16_t*>(rec + kD1K4ScaleOffset + (lane >> 3) * 2));
+    const int j = 2 * (lane & 7);
+    *reinterpret_cast<uint2*>(lut + 2 * lane) =
+        make_uint2(k64_dequant_pair(d1k4_pair(q4, j), scale), k64_dequant_pair(d1k4_pair(q4, j + 1), scale));
+    const uint2 w = *reinterpret_cast<const uint2*>(idx + rb * slots * 512 + k16_chunk_offset(c, lane));
+    wave_lds_sync();
+    const char* lutb = reinterpret_cast<const char*>(lut);
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      uint32_t a, b;
+      k16_split_dword(h ? w.y : w.x, a, b);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const char* row_tab = lutb + (4 * h + r) * 64;
+        const uint32_t lo = *reinterpret_cast<const uint32_t*>(row_tab + ((a >> (8 * r)) & 0xffu));
+        const uint32_t hi = *reinterpret_cast<const uint32_t*>(row_tab + ((b >> (8 * r)) & 0xffu));
+        *reinterpret_cast<uint2*>(out + (size_t)(4 * h + r) * in_features) = make_uint2(lo, hi);
+      }
+    }
+  } else if (K == 16 || K == kFmtK16I8) {
     const int slots = 2 * k16_pairs(n_cb);                  // group slots per row-block
     if (K == 16) {
       if (lane < 16) lut[lane] = cb[(rb * slots + c) * 16 + lane];
@@ -205,6 +230,7 @@ hipError_t launch_decode(const vq_desc& d, const void* idx_dev, const void* cb_d
                      (const uint32_t*)cb_dev, (uint16_t*)W, n_cb, n_groups, d.in_features)
   if (fmt == kFmtK16I8) VQ_DECODE(kFmtK16I8);
   else if (fmt == kFmtD1K16) VQ_DECODE(kFmtD1K16);
+  else if (fmt == kFmtD1K4) VQ_DECODE(kFmtD1K4);
   else if (fmt == 16) VQ_DECODE(16);
   else VQ_DECODE(256);
 #undef VQ_DECODE

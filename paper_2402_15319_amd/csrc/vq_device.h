@@ -73,36 +73,38 @@ __device__ __forceinline__ void wave_lds_sync() {
 // acc_hazard_fence() after the last block of a straight run of blocks, i.e. before any
 // point where the compiler may place code of its own that reads an accumulator (a loop
 // edge or branch merge can make it copy accumulators between registers).
-#define VQ_SDWA_RD(R, T, B, OFF)                                                          \
+#define VQ_SDWA_RD(R, T, B, ROW)                                                          \
   "v_add_u32_sdwa " R ", %[base], " T                                                     \
   " dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_" #B "\n"            \
-  "ds_read_b32 " R ", " R " offset:" OFF "\n"
+  "ds_read_b32 " R ", " R " offset:%[off]+" #ROW "*%[rs]\n"
 #define VQ_MASKS(W)                                  \
   "v_and_b32 %[ta], 0x3c3c3c3c, " W "\n"             \
   "v_alignbit_b32 %[tb], " W ", " W ", 4\n"          \
   "v_and_b32 %[tb], 0x3c3c3c3c, %[tb]\n"
 #define VQ_DOT(ACC, R, X) "v_dot2c_f32_f16 " ACC ", " R ", " X "\n"
 
-template <int OFF>
+// RS: byte distance between the tables of consecutive rows (0: the 8 rows share one table;
+// 64: a 16-entry table per row, the scalar 2-bit format).
+template <int OFF, int RS = 0>
 __device__ __forceinline__ void k16_group(uint32_t w0, uint32_t w1, uint32_t base, uint32_t x0,
                                           uint32_t x1, float (&acc)[8]) {
   uint32_t ta, tb, r0, r1, r2, r3, r4, r5, r6, r7, r8, r9, r10, r11;
   asm volatile(
       VQ_MASKS("%[w0]")
-      VQ_SDWA_RD("%[r0]", "%[ta]", 0, "%[off]") VQ_SDWA_RD("%[r1]", "%[tb]", 0, "%[off]")
-      VQ_SDWA_RD("%[r2]", "%[ta]", 1, "%[off]") VQ_SDWA_RD("%[r3]", "%[tb]", 1, "%[off]")
-      VQ_SDWA_RD("%[r4]", "%[ta]", 2, "%[off]") VQ_SDWA_RD("%[r5]", "%[tb]", 2, "%[off]")
-      VQ_SDWA_RD("%[r6]", "%[ta]", 3, "%[off]") VQ_SDWA_RD("%[r7]", "%[tb]", 3, "%[off]")
+      VQ_SDWA_RD("%[r0]", "%[ta]", 0, 0) VQ_SDWA_RD("%[r1]", "%[tb]", 0, 0)
+      VQ_SDWA_RD("%[r2]", "%[ta]", 1, 1) VQ_SDWA_RD("%[r3]", "%[tb]", 1, 1)
+      VQ_SDWA_RD("%[r4]", "%[ta]", 2, 2) VQ_SDWA_RD("%[r5]", "%[tb]", 2, 2)
+      VQ_SDWA_RD("%[r6]", "%[ta]", 3, 3) VQ_SDWA_RD("%[r7]", "%[tb]", 3, 3)
       VQ_MASKS("%[w1]")
-      VQ_SDWA_RD("%[r8]", "%[ta]", 0, "%[off]") VQ_SDWA_RD("%[r9]", "%[tb]", 0, "%[off]")
-      VQ_SDWA_RD("%[r10]", "%[ta]", 1, "%[off]") VQ_SDWA_RD("%[r11]", "%[tb]", 1, "%[off]")
+      VQ_SDWA_RD("%[r8]", "%[ta]", 0, 4) VQ_SDWA_RD("%[r9]", "%[tb]", 0, 4)
+      VQ_SDWA_RD("%[r10]", "%[ta]", 1, 5) VQ_SDWA_RD("%[r11]", "%[tb]", 1, 5)
       "s_waitcnt lgkmcnt(4)\n"
       VQ_DOT("%[a0]", "%[r0]", "%[x0]") VQ_DOT("%[a1]", "%[r2]", "%[x0]")
       VQ_DOT("%[a2]", "%[r4]", "%[x0]") VQ_DOT("%[a3]", "%[r6]", "%[x0]")
       VQ_DOT("%[a0]", "%[r1]", "%[x1]") VQ_DOT("%[a1]", "%[r3]", "%[x1]")
       VQ_DOT("%[a2]", "%[r5]", "%[x1]") VQ_DOT("%[a3]", "%[r7]", "%[x1]")
-      VQ_SDWA_RD("%[r0]", "%[ta]", 2, "%[off]") VQ_SDWA_RD("%[r1]", "%[tb]", 2, "%[off]")
-      VQ_SDWA_RD("%[r2]", "%[ta]", 3, "%[off]") VQ_SDWA_RD("%[r3]", "%[tb]", 3, "%[off]")
+      VQ_SDWA_RD("%[r0]", "%[ta]", 2, 6) VQ_SDWA_RD("%[r1]", "%[tb]", 2, 6)
+      VQ_SDWA_RD("%[r2]", "%[ta]", 3, 7) VQ_SDWA_RD("%[r3]", "%[tb]", 3, 7)
       "s_waitcnt lgkmcnt(4)\n"
       VQ_DOT("%[a4]", "%[r8]", "%[x0]") VQ_DOT("%[a5]", "%[r10]", "%[x0]")
       VQ_DOT("%[a4]", "%[r9]", "%[x1]") VQ_DOT("%[a5]", "%[r11]", "%[x1]")
@@ -114,7 +116,7 @@ __device__ __forceinline__ void k16_group(uint32_t w0, uint32_t w1, uint32_t bas
         [ta] "=&v"(ta), [tb] "=&v"(tb), [r0] "=&v"(r0), [r1] "=&v"(r1), [r2] "=&v"(r2),
         [r3] "=&v"(r3), [r4] "=&v"(r4), [r5] "=&v"(r5), [r6] "=&v"(r6), [r7] "=&v"(r7),
         [r8] "=&v"(r8), [r9] "=&v"(r9), [r10] "=&v"(r10), [r11] "=&v"(r11)
-      : [w0] "v"(w0), [w1] "v"(w1), [base] "s"(base), [x0] "v"(x0), [x1] "v"(x1), [off] "n"(OFF)
+      : [w0] "v"(w0), [w1] "v"(w1), [base] "s"(base), [x0] "v"(x0), [x1] "v"(x1), [off] "n"(OFF), [rs] "n"(RS)
       : "memory");
 }
 #undef VQ_SDWA_RD
@@ -311,6 +313,26 @@ __device__ __forceinline__ uint32_t d1k8_pair(uint2 c8, int e) {
   const uint32_t lo = ((e & 4) ? c8.y : c8.x) >> (8 * (e & 3));
   const uint32_t hi = ((e & 32) ? c8.y : c8.x) >> (8 * ((e >> 3) & 3));
   return (lo & 0xffu) | ((hi & 0xffu) << 8);
+}
+
+// d = 1, k = 4 (2-bit indices, one codebook of 4 int8 values + fp16 scale per row of a
+// col-block): two neighbouring indices form the 4-bit index of the row's pair table
+// T[j] = (c[j % 4], c[j / 4]); indices in the 4-bit device layout above.  Tables: per (8-row
+// block, col-block slot) 48 bytes: the 8 rows' 4 values, then the 8 rows' scales.
+constexpr int kD1K4SlotTabBytes = 48;
+constexpr int kD1K4ScaleOffset = 32;
+// The int8 pair (c[j % 4], c[j / 4]) of pair-table entry j from a row's 4 values.
+__device__ __forceinline__ uint32_t d1k4_pair(uint32_t c4, int j) {
+  return ((c4 >> (8 * (j & 3))) & 0xffu) | (((c4 >> (8 * (j >> 2))) & 0xffu) << 8);
+}
+// Entries 8*half .. 8*half+7 of a row's pair table from its dequantised values p01 = (c0, c1),
+// p23 = (c2, c3): the low halves run through c0..c3 twice, the high half is c[2*half], then c[2*half+1].
+__device__ __forceinline__ void d1k4_entries(uint32_t p01, uint32_t p23, int half, uint4& e0, uint4& e1) {
+  const uint32_t hp = half ? p23 : p01;
+  const uint32_t ha = hp << 16, hb = hp & 0xffff0000u;
+  const uint32_t c0 = p01 & 0xffffu, c1 = p01 >> 16, c2 = p23 & 0xffffu, c3 = p23 >> 16;
+  e0 = make_uint4(c0 | ha, c1 | ha, c2 | ha, c3 | ha);
+  e1 = make_uint4(c0 | hb, c1 | hb, c2 | hb, c3 | hb);
 }
 
 // Pairs of col-blocks a k=16 row-block is stored as (the last one half-empty if n_cb is odd).

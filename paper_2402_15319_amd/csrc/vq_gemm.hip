@@ -38,8 +38,8 @@ __device__ __forceinline__ int wt_half_index(int m, int k) {   // k in halfs
 // K is the kernel format tag: 16 / 256 (fp16 codebooks), 64 (6-bit indices, int8 tables with a
 // scale per group, groups of 8*rpc rows), kFmtK16I8 (k = 16 with int8 tables).
 template <int K> constexpr int lut_dwords() {
-  // BN: 64 centroids + 16 levels; d = 4: 256 entries of 4 halfs
-  return K == kFmtK16I8 ? 16 : K == kFmtD1K16 ? 256 : K == kFmtK64BN ? 80 : K == kFmtD4 ? 512 : K == kFmtD1K8 ? 64 : K;
+  // BN: 64 centroids + 16 levels; d = 4: 256 entries of 4 halfs; scalar 2-bit: 8 rows x 16 pair entries
+  return K == kFmtK16I8 ? 16 : K == kFmtD1K16 ? 256 : K == kFmtK64BN ? 80 : K == kFmtD4 ? 512 : K == kFmtD1K8 ? 64 : K == kFmtD1K4 ? 128 : K;
 }
 
 // What one wave needs to decode one group: the lane's index bytes and codebook piece.
@@ -75,6 +75,11 @@ template <> struct GroupRegs<kFmtD1K16> {
   uint2 clo;      // scalars 4*(lane%4) .. +3 of the group's 16
   uint32_t chi;   // scalar lane/4
 };
+template <> struct GroupRegs<kFmtD1K4> {
+  uint2 w;
+  uint32_t q4;           // the 4 int8 values of row lane >> 3
+  uint32_t sc;           // ... and its fp16 scale
+};
 template <> struct GroupRegs<kFmtK16I8> {
   uint2 w;
   uint32_t two;          // int8 pair of table entry lane & 15
@@ -95,6 +100,12 @@ __device__ __forceinline__ void load_group(GroupRegs<K>& g, const uint8_t* idx, 
     g.w = *reinterpret_cast<const uint2*>(idx + (size_t)rb * slots * 512 + k16_chunk_offset(c, lane));
     g.two = *reinterpret_cast<const uint16_t*>(tabs + ((size_t)rb * slots + c) * 32 + (lane & 15) * 2);
     g.sc = reinterpret_cast<const uint16_t*>(tabs + (size_t)n_rb * slots * 32)[(size_t)rb * slots + c];
+  } else if constexpr (K == kFmtD1K4) {
+    const int slots = 2 * k16_pairs(n_cb);
+    const uint8_t* rec = reinterpret_cast<const uint8_t*>(cb) + ((size_t)rb * slots + c) * kD1K4SlotTabBytes;
+    g.w = *reinterpret_cast<const uint2*>(idx + (size_t)rb * slots * 512 + k16_chunk_offset(c, lane));
+    g.q4 = *reinterpret_cast<const uint32_t*>(rec + (lane >> 3) * 4);
+    g.sc = *reinterpret_cast<const uint16_t*>(rec + kD1K4ScaleOffset + (lane >> 3) * 2);
   } else if constexpr (K == kFmtD4) {
     const uint8_t* tab = reinterpret_cast<const uint8_t*>(cb);
     const size_t gi = (size_t)(rb / rpc) * n_cb + c, n_groups = (size_t)(n_rb / rpc) * n_cb;
@@ -178,6 +189,23 @@ __device__ __forceinline__ void decode_group(const GroupRegs<K>& g, uint32_t* lu
         const h2_t sc = __builtin_bit_cast(h2_t, lut[64 + ((g.cw >> (4 * r)) & 15u)]);
         v[2 * r] = __builtin_bit_cast(uint32_t, __builtin_bit_cast(h2_t, v[2 * r]) * sc);
         v[2 * r + 1] = __builtin_bit_cast(uint32_t, __builtin_bit_cast(h2_t, v[2 * r + 1]) * sc);
+      }
+    }
+  } else if constexpr (K == kFmtD1K4) {   // lane L: entries 2*(L&7), +1 of row L >> 3; row r looks up in table r
+    const _Float16 scale = __builtin_bit_cast(_Float16, (uint16_t)g.sc);
+    const int j = 2 * (lane & 7);
+    *reinterpret_cast<uint2*>(lut + 2 * lane) =
+        make_uint2(k64_dequant_pair(d1k4_pair(g.q4, j), scale), k64_dequant_pair(d1k4_pair(g.q4, j + 1), scale));
+    wave_lds_sync();
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      uint32_t a, b;
+      k16_split_dword(h ? g.w.y : g.w.x, a, b);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const char* row_tab = lutb + (4 * h + r) * 64;
+        v[8 * h + 2 * r] = *reinterpret_cast<const uint32_t*>(row_tab + ((a >> (8 * r)) & 0xffu));
+        v[8 * h + 2 * r + 1] = *reinterpret_cast<const uint32_t*>(row_tab + ((b >> (8 * r)) & 0xffu));
       }
     }
   } else if constexpr (K == 16 || K == kFmtK16I8) {
@@ -730,6 +758,7 @@ hipError_t launch_gemm(const vq_desc& d, const void* idx_dev, const void* cb_dev
   if (fmt == kFmtK64BN) VQ_GEMM_DISPATCH(kFmtK64BN)
   if (fmt == kFmtD4) VQ_GEMM_DISPATCH(kFmtD4)
   if (fmt == kFmtD1K8) VQ_GEMM_DISPATCH(kFmtD1K8)
+  if (fmt == kFmtD1K4) VQ_GEMM_DISPATCH(kFmtD1K4)
   if (fmt == 16) VQ_GEMM_DISPATCH(16)
   VQ_GEMM_DISPATCH(256)
 #undef VQ_GEMM_DISPATCH

@@ -26,7 +26,8 @@
 namespace vq {
 namespace {
 
-// A strip as wave-uniform scalars.  Units are col-block pairs (k=16) or col-blocks (k=256).
+// A strip as wave-uniform scalars.  Units are col-block pairs (k=16, scalar 2-bit), quads (6-bit
+// fields) or col-blocks (k=256).
 struct Strip {
   const uint8_t* idx_rb;   // indices of the row-block
   const uint32_t* cb_rb;   // codebooks / int8 tables of the row-block (dwords)
@@ -134,6 +135,52 @@ template <bool I8> struct Chunk16T {
 };
 template <> struct Chunk<16> : Chunk16T<false> {};
 template <> struct Chunk<kFmtK16I8> : Chunk16T<true> {};
+
+// d = 1, k = 4 (2-bit indices, a codebook per row of a col-block): the index bytes and the inner
+// block of k = 16, with a 16-entry pair table per row.  A chunk is 2 col-block pairs = 4 blocks of
+// 8 rows x 256 columns; lane L builds entries 8*(L&1) .. +7 of the table of (block, row) = L >> 1.
+template <> struct Chunk<kFmtD1K4> {
+  static constexpr int kUnits = 2;
+  static constexpr int kLutDwords = 512;   // 4 blocks x 8 rows x 16 entries
+  uint4 w[2];
+  uint2 xa[2], xb[2];
+  uint32_t tab;   // the 4 int8 values of (block, row) = lane >> 1
+  uint32_t sc;    // ... and its fp16 scale
+  int np;
+
+  __device__ __forceinline__ void load(const Strip& S, int u, int lane) {
+    np = max(0, min(2, S.u_end - u));
+    const int u_ld = np > 0 ? u : 0;
+    const uint8_t* tq = reinterpret_cast<const uint8_t*>(S.cb_rb) + (size_t)u_ld * (2 * kD1K4SlotTabBytes);
+    const int blk = min(lane >> 4, max(2 * np - 1, 0)), row = (lane >> 1) & 7;
+    const bool ok = (lane >> 4) < 2 * np;
+    tab = zero_unless(ok, *reinterpret_cast<const uint32_t*>(tq + blk * kD1K4SlotTabBytes + row * 4));
+    sc = zero_unless(ok, (uint32_t)*reinterpret_cast<const uint16_t*>(tq + blk * kD1K4SlotTabBytes + kD1K4ScaleOffset + row * 2));
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+      const bool oks = s < np;
+      const int q = oks ? u + s : 0;
+      const bool ok_b = oks && 2 * q + 1 < S.n_cb;
+      w[s] = stream_load16(S.idx_rb + (size_t)q * 1024 + lane * 16);
+      xa[s] = zero_unless(oks, *reinterpret_cast<const uint2*>(S.x + (2 * q) * 256 + lane * 4));
+      xb[s] = zero_unless(ok_b, *reinterpret_cast<const uint2*>(S.x + (ok_b ? 2 * q + 1 : 0) * 256 + lane * 4));
+    }
+  }
+
+  __device__ __forceinline__ void consume(uint32_t* lut, uint32_t base, int lane, float (&acc)[8]) const {
+    const _Float16 scale = __builtin_bit_cast(_Float16, (uint16_t)sc);
+    uint4 e0, e1;
+    d1k4_entries(k64_dequant_pair(tab, scale), k64_dequant_pair(tab >> 16, scale), lane & 1, e0, e1);
+    *reinterpret_cast<uint4*>(lut + lane * 8) = e0;
+    *reinterpret_cast<uint4*>(lut + lane * 8 + 4) = e1;
+    wave_lds_sync();
+    k16_group<0, 64>(w[0].x, w[0].y, base, xa[0].x, xa[0].y, acc);
+    k16_group<512, 64>(w[0].z, w[0].w, base, xb[0].x, xb[0].y, acc);
+    k16_group<1024, 64>(w[1].x, w[1].y, base, xa[1].x, xa[1].y, acc);
+    k16_group<1536, 64>(w[1].z, w[1].w, base, xb[1].x, xb[1].y, acc);
+    acc_hazard_fence();
+  }
+};
 
 // k = 256 (D1 = false), and d = 1 with k = 16 (D1 = true): the same index bytes and inner
 // block; D1 builds the 256-entry pair table from the group's 16 scalars instead of loading it.
@@ -273,6 +320,13 @@ __device__ __forceinline__ Strip make_strip(const GemvProblem& P, int rb, int sp
     S.u = (n_pairs * split) / splits;
     S.u_end = (n_pairs * (split + 1)) / splits;
     S.chunks_left = (S.u_end - S.u + 3) >> 2;
+  } else if (K == kFmtD1K4) {   // pairs as for k = 16; two 48-byte table records per pair
+    const int n_pairs = k16_pairs(n_cb);
+    S.idx_rb = P.idx + (size_t)rb * n_pairs * 1024;
+    S.cb_rb = P.cb + (size_t)rb * n_pairs * (2 * kD1K4SlotTabBytes / 4);
+    S.u = (n_pairs * split) / splits;
+    S.u_end = (n_pairs * (split + 1)) / splits;
+    S.chunks_left = (S.u_end - S.u + 1) >> 1;
   } else if (K == 64 || K == kFmtK64BN || K == kFmtD1K8) {
     const int n_quads = k64_quads(n_cb);
     constexpr int tab_bytes = K == 64 ? kK64QuadTabBytes : K == kFmtD1K8 ? kD1K8QuadTabBytes : kK64NQuadTabBytes;
@@ -393,6 +447,50 @@ template <bool I8> struct ChunkS16T {
 };
 template <> struct ChunkS<16> : ChunkS16T<false> {};
 template <> struct ChunkS<kFmtK16I8> : ChunkS16T<true> {};
+
+template <> struct ChunkS<kFmtD1K4> {
+  static constexpr int kUnits = 2;
+  static constexpr int kLutDwords = 512;
+  uint4 w[2];
+  uint32_t tab, sc;   // see Chunk<kFmtD1K4>
+  int u0;             // first pair
+
+  __device__ __forceinline__ void load(const Strip& S, int u, int lane) {
+    const int np = max(0, min(2, S.u_end - u));
+    u0 = u;
+    const int u_ld = np > 0 ? u : 0;
+    const uint8_t* tq = reinterpret_cast<const uint8_t*>(S.cb_rb) + (size_t)u_ld * (2 * kD1K4SlotTabBytes);
+    const int blk = min(lane >> 4, max(2 * np - 1, 0)), row = (lane >> 1) & 7;
+    tab = zero_unless((lane >> 4) < 2 * np,
+                      *reinterpret_cast<const uint32_t*>(tq + blk * kD1K4SlotTabBytes + row * 4));
+    sc = zero_unless((lane >> 4) < 2 * np,
+                     (uint32_t)*reinterpret_cast<const uint16_t*>(tq + blk * kD1K4SlotTabBytes + kD1K4ScaleOffset + row * 2));
+    uint32_t voff = (uint32_t)lane * 16u;      // see ChunkS<16>::load
+    asm volatile("" : "+v"(voff));
+#pragma unroll
+    for (int s = 0; s < 2; ++s)
+      w[s] = stream_load16(S.idx_rb + (size_t)(s < np ? u + s : 0) * 1024 + voff);
+  }
+
+  __device__ __forceinline__ void consume(uint32_t* lut, uint32_t base, const uint32_t* x_s, int lane,
+                                          float (&acc)[8]) const {
+    const _Float16 scale = __builtin_bit_cast(_Float16, (uint16_t)sc);
+    uint4 e0, e1;
+    d1k4_entries(k64_dequant_pair(tab, scale), k64_dequant_pair(tab >> 16, scale), lane & 1, e0, e1);
+    *reinterpret_cast<uint4*>(lut + lane * 8) = e0;
+    *reinterpret_cast<uint4*>(lut + lane * 8 + 4) = e1;
+    wave_lds_sync();
+    const uint2* xp = reinterpret_cast<const uint2*>(x_s) + u0 * 128 + lane;
+    uint2 x0 = xp[0], x1 = xp[64];
+    k16_group<0, 64>(w[0].x, w[0].y, base, x0.x, x0.y, acc);
+    x0 = xp[128];
+    k16_group<512, 64>(w[0].z, w[0].w, base, x1.x, x1.y, acc);
+    x1 = xp[192];
+    k16_group<1024, 64>(w[1].x, w[1].y, base, x0.x, x0.y, acc);
+    k16_group<1536, 64>(w[1].z, w[1].w, base, x1.x, x1.y, acc);
+    acc_hazard_fence();
+  }
+};
 
 template <bool D1> struct ChunkS256T {
   static constexpr int kUnits = 2;
@@ -715,6 +813,7 @@ __global__ __launch_bounds__(256) void gemv_split_kernel(const GemvBatch batch) 
     case kFmtD1K16: F(kFmtD1K16); break;      \
     case kFmtK64BN: F(kFmtK64BN); break;      \
     case kFmtD1K8: F(kFmtD1K8); break;        \
+    case kFmtD1K4: F(kFmtD1K4); break;        \
     default: F(256); break;                   \
   }
 
@@ -730,10 +829,10 @@ int gemv_stream_resident_wgs(int fmt, int max_n_cb) {
   // Occupancy of the persistent kernel for this LDS size, asked once per (device, format, size):
   // a pure function of the code object and the device, cached so that the hot path makes
   // no runtime queries.  Benign if two threads fill the same slot at once.
-  static int cached[7][16][kStreamMaxColBlocks + 1];
+  static int cached[8][16][kStreamMaxColBlocks + 1];
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) dev = 0;
-  const int fi = fmt == 16 ? 0 : fmt == 64 ? 1 : fmt == kFmtK16I8 ? 3 : fmt == kFmtD1K16 ? 4 : fmt == kFmtK64BN ? 5 : fmt == kFmtD1K8 ? 6 : 2;
+  const int fi = fmt == 16 ? 0 : fmt == 64 ? 1 : fmt == kFmtK16I8 ? 3 : fmt == kFmtD1K16 ? 4 : fmt == kFmtK64BN ? 5 : fmt == kFmtD1K8 ? 6 : fmt == kFmtD1K4 ? 7 : 2;
   int& slot = cached[fi][dev][max_n_cb];
   if (slot == 0) {
     int per_cu = 0, cus = 0;

@@ -18,10 +18,12 @@ constexpr int kFmtK16I8 = 1016;
 constexpr int kFmtD1K16 = 2016;
 constexpr int kFmtK64BN = 3064;   // k = 64, int8 tables + scale, blockwise normalisation (blocks of 32)
 constexpr int kFmtD1K8 = 2008;     // d = 1, k = 8 (3-bit indices), int8 values + scale: pairs index a 64-entry pair table
+constexpr int kFmtD1K4 = 2004;     // d = 1, k = 4 (2-bit indices), int8 values + scale, one codebook per row of a
+                                   // col-block (groups of 1 x 256): pairs index a 16-entry pair table per row
 constexpr int kFmtD4 = 4256;      // d = 4, k = 256 (one index byte per 4 weights), int8 tables + scale,
                                   // groups of 64, 128 or 256 rows x 256 columns
 inline int format_tag(const vq_desc& d) {
-  if (d.d == 1) return d.k == 8 ? kFmtD1K8 : kFmtD1K16;
+  if (d.d == 1) return d.k == 8 ? kFmtD1K8 : d.k == 4 ? kFmtD1K4 : kFmtD1K16;
   if (d.d == 4) return kFmtD4;
   if (d.codebook_dtype == VQ_I8_BN) return kFmtK64BN;
   if (d.k == 16 && d.codebook_dtype == VQ_I8) return kFmtK16I8;

@@ -10,10 +10,12 @@ namespace {
 // One thread per (device group slot, lane): gathers that lane's share of the group.
 // For k=16 the slots include the zero-filled pad group of row-blocks with an odd
 // number of col-blocks.
+// row_groups: the canonical groups are single rows (1 x 256, 64 bytes each, row-major), as in
+// the scalar 2-bit format, instead of 8 x 256 blocks.
 template <int K>
 __global__ __launch_bounds__(256) void pack_idx_kernel(const uint8_t* __restrict__ canon,
                                                        uint8_t* __restrict__ dev, int n_cb,
-                                                       long long n_slots) {
+                                                       long long n_slots, int row_groups) {
   const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
   const long long slot = t >> 6;
   const int lane = (int)(t & 63);
@@ -24,13 +26,16 @@ __global__ __launch_bounds__(256) void pack_idx_kernel(const uint8_t* __restrict
     const int c = (int)(slot - rb * slots_per_rb);
     uint32_t words[2] = {0u, 0u};
     if (c < n_cb) {
-      const uint8_t* src = canon + (rb * n_cb + c) * 512 + lane;   // canonical byte r*64 + lane
+      // canonical byte r*64 + lane of the block, or byte `lane` of the group of row rb*8 + r
+      const uint8_t* src = row_groups ? canon + (rb * 8 * n_cb + c) * 64 + lane
+                                      : canon + (rb * n_cb + c) * 512 + lane;
+      const size_t row_stride = row_groups ? (size_t)n_cb * 64 : 64;
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
         uint32_t lo[4], hi[4];
 #pragma unroll
         for (int b = 0; b < 4; ++b) {
-          const uint32_t byte = src[(4 * h + b) * 64];
+          const uint32_t byte = src[(4 * h + b) * row_stride];
           lo[b] = byte & 15u;
           hi[b] = byte >> 4;
         }
@@ -89,6 +94,27 @@ __global__ __launch_bounds__(256) void pack_tab16_kernel(const uint32_t* __restr
     const int c = (int)(t - rb * slots_per_rb);
     reinterpret_cast<uint16_t*>(dev + n_slots * 8)[t] = c < n_cb ? scale_canon[rb * n_cb + c] : (uint16_t)0;
   }
+}
+
+// d = 1, k = 4: per (8-row block, col-block slot) 48 bytes: the 4 int8 values of each of the 8
+// rows, then the 8 rows' fp16 scales (zero for the pad slot).  Canonical group of row R and
+// col-block c: R * n_cb + c.  One thread per (slot, row).
+__global__ __launch_bounds__(256) void pack_tab_d1k4_kernel(const uint32_t* __restrict__ q_canon,
+                                                            const uint16_t* __restrict__ scale_canon,
+                                                            uint8_t* __restrict__ dev, int n_cb,
+                                                            long long n_slots) {
+  const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (t >= n_slots * 8) return;
+  const long long slot = t >> 3;
+  const int r = (int)(t & 7);
+  const int slots_per_rb = 2 * k16_pairs(n_cb);
+  const long long rb = slot / slots_per_rb;
+  const int c = (int)(slot - rb * slots_per_rb);
+  const bool ok = c < n_cb;
+  const long long g = (rb * 8 + r) * n_cb + c;
+  uint8_t* rec = dev + (size_t)slot * kD1K4SlotTabBytes;
+  reinterpret_cast<uint32_t*>(rec)[r] = ok ? q_canon[g] : 0u;
+  reinterpret_cast<uint16_t*>(rec + kD1K4ScaleOffset)[r] = ok ? scale_canon[g] : (uint16_t)0;
 }
 
 // ---- k = 64: 6-bit indices, int8 tables with a scale per group, groups of 8*rpc rows -------
@@ -330,11 +356,22 @@ hipError_t launch_pack(const vq_desc& d, const void* idx_canon, const void* cb_c
     return hipGetLastError();
   }
   const int fmt = format_tag(d);
-  const int slots_per_rb = (fmt == 16 || fmt == kFmtK16I8) ? 2 * k16_pairs(n_cb) : n_cb;
+  const int slots_per_rb = (fmt == 16 || fmt == kFmtK16I8 || fmt == kFmtD1K4) ? 2 * k16_pairs(n_cb) : n_cb;
   const long long n_slots = n_rb * slots_per_rb;
+  if (fmt == kFmtD1K4) {
+    hipLaunchKernelGGL(pack_idx_kernel<16>, dim3((unsigned)((n_slots * 64 + 255) / 256)), dim3(256), 0, s,
+                       (const uint8_t*)idx_canon, (uint8_t*)idx_dev, n_cb, n_slots, 1);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const size_t q_bytes = ((size_t)d.out_features * n_cb * 4 + 15) / 16 * 16;   // scales follow the values
+    hipLaunchKernelGGL(pack_tab_d1k4_kernel, dim3((unsigned)((n_slots * 8 + 255) / 256)), dim3(256), 0, s,
+                       (const uint32_t*)cb_canon, (const uint16_t*)((const uint8_t*)cb_canon + q_bytes),
+                       (uint8_t*)cb_dev, n_cb, n_slots);
+    return hipGetLastError();
+  }
   if (fmt == kFmtK16I8) {
     hipLaunchKernelGGL(pack_idx_kernel<16>, dim3((unsigned)((n_slots * 64 + 255) / 256)), dim3(256), 0, s,
-                       (const uint8_t*)idx_canon, (uint8_t*)idx_dev, n_cb, n_slots);
+                       (const uint8_t*)idx_canon, (uint8_t*)idx_dev, n_cb, n_slots, 0);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const size_t q_bytes = ((size_t)n_rb * n_cb * 32 + 15) / 16 * 16;      // scales follow the tables
@@ -346,10 +383,10 @@ hipError_t launch_pack(const vq_desc& d, const void* idx_canon, const void* cb_c
   const unsigned grid = (unsigned)((n_slots * 64 + 255) / 256);
   if (fmt == 16)
     hipLaunchKernelGGL(pack_idx_kernel<16>, dim3(grid), dim3(256), 0, s,
-                       (const uint8_t*)idx_canon, (uint8_t*)idx_dev, n_cb, n_slots);
+                       (const uint8_t*)idx_canon, (uint8_t*)idx_dev, n_cb, n_slots, 0);
   else   // k = 256 bytes, or d = 1: a byte holds the two 4-bit indices of a column pair
     hipLaunchKernelGGL(pack_idx_kernel<256>, dim3(grid), dim3(256), 0, s,
-                       (const uint8_t*)idx_canon, (uint8_t*)idx_dev, n_cb, n_slots);
+                       (const uint8_t*)idx_canon, (uint8_t*)idx_dev, n_cb, n_slots, 0);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const int per_group = d.k * d.d * 2 / 16;                      // 16-byte pieces of one fp16 codebook

@@ -72,6 +72,9 @@ A = 0x1000  # a fake, 16-byte aligned, non-NULL address; validation fails before
     (dict(d=1, k=8, index_bits=3), -3),                                   # 3-bit scalar codebooks: int8 values
     (dict(d=1, k=8, index_bits=3, codebook_dtype=3, group_rows=64), -3),
     (dict(d=1, group_rows=32), -3),
+    (dict(d=1, k=4, index_bits=2, codebook_dtype=3), -3),                 # 2-bit scalar codebooks: groups of one row
+    (dict(d=1, k=4, index_bits=2, group_rows=1), -3),                     # ... with int8 values
+    (dict(d=1, k=4, index_bits=2, codebook_dtype=3, group_rows=1, out_features=4100), -3),   # rows in blocks of 8
     (dict(group_rows=4), -3),
     (dict(group_cols=128), -3),
     (dict(k=64, index_bits=6), -3),                                       # k = 64 needs int8 tables
@@ -246,4 +249,18 @@ def test_three_bit_scalar_representation_sizes():
         assert vq.vq_canonical_bytes(d) == (out_f * in_f * 3 // 8, (n_groups * 8 + 15) // 16 * 16 + 2 * n_groups)
         quads = (in_f // 256 + 3) // 4
         assert vq.vq_layout_bytes(d) == ((out_f // 8) * quads * 3072, (out_f // rows) * quads * 48)
+        assert L.vq_gemv(ctypes.byref(d), A, A, A + 2, A + 16, vq.VQ_F16, 0) == -4
+
+
+def test_two_bit_scalar_representation_sizes():
+    """d = 1, k = 4, a codebook per row of a col-block: 64 bytes of indices and 4 + 2 bytes of table
+    per 256 weights; the device layout pads row-blocks to an even number of col-blocks and stores
+    48-byte table records per (8-row block, col-block)."""
+    L = vq.lib()
+    for out_f, in_f in ((4096, 4096), (4096, 11008), (64, 768)):
+        d = vq.make_desc(out_f, in_f, 4, 2, group_rows=1, d=1, codebook_dtype=vq.VQ_I8)
+        n_groups = out_f * (in_f // 256)
+        assert vq.vq_canonical_bytes(d) == (out_f * in_f // 4, (n_groups * 4 + 15) // 16 * 16 + 2 * n_groups)
+        slots = 2 * ((in_f // 256 + 1) // 2)
+        assert vq.vq_layout_bytes(d) == ((out_f // 8) * slots * 512, (out_f // 8) * slots * 48)
         assert L.vq_gemv(ctypes.byref(d), A, A, A + 2, A + 16, vq.VQ_F16, 0) == -4

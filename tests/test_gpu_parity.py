@@ -775,6 +775,46 @@ def test_d1k8_full_size_layer(env):
     assert oracle.normwise_rel_err(_gpu_gemv(env, desc, idx_d, cb_d, x, False), oracle.gemv(f, idx, cb, x)) <= TOL_F16
 
 
+# ---------------------------------------------------------------- scalar codebooks at 2 bits (d = 1, k = 4, a codebook per row)
+def _shape_d1k4(o, i):
+    return workloads.VQShape(o, i, 4, 2, 1, 256, 1, True)
+
+
+D1K4_SMALL = [_shape_d1k4(8, 256), _shape_d1k4(96, 768), _shape_d1k4(64, 2816), _shape_d1k4(40, 1280),
+              _shape_d1k4(48, 512), _shape_d1k4(24, 5632)]
+
+
+@pytest.mark.parametrize("s", D1K4_SMALL + [_shape_d1k4(32800, 768)], ids=str)
+def test_d1k4_decode_and_gemv(env, s):
+    """Decode bit for bit, GEMV with fp16 and fp32 output (split-K kernel with one and with several
+    chunks per strip, odd and even numbers of col-blocks; streaming kernel on the tall shape)."""
+    desc, idx, cb, idx_d, cb_d = _setup_i8(env, s, 750)
+    f = _fmt(s)
+    np.testing.assert_array_equal(_gpu_decode(env, desc, idx_d, cb_d), oracle.decode_dense(f, idx, cb))
+    x = workloads.make_x(s.in_features, 750)
+    ref = oracle.gemv(f, idx, cb, x)
+    assert oracle.normwise_rel_err(_gpu_gemv(env, desc, idx_d, cb_d, x, False), ref) <= TOL_F16
+    assert oracle.normwise_rel_err(_gpu_gemv(env, desc, idx_d, cb_d, x, True), ref) <= TOL_F32
+
+
+@pytest.mark.parametrize("B", [1, 16, 40, 130, 600, 1300])
+@pytest.mark.parametrize("s", [_shape_d1k4(96, 768), _shape_d1k4(808, 512)], ids=str)
+def test_d1k4_gemm(env, s, B):
+    desc, idx, cb, idx_d, cb_d = _setup_i8(env, s, 751)
+    X = workloads.make_X(s.in_features, B, 751)
+    Y = _gpu_gemm(env, desc, idx_d, cb_d, X, False, pad=8 if B == 40 else 0)
+    assert oracle.normwise_rel_err(Y, oracle.gemm(_fmt(s), idx, cb, X)) <= TOL_F16
+
+
+def test_d1k4_full_size_layer(env):
+    s = workloads.CONFIGS["mlp_down_4096x11008_d1_k4"]
+    desc, idx, cb, idx_d, cb_d = _setup_i8(env, s, 752)
+    f = _fmt(s)
+    np.testing.assert_array_equal(_gpu_decode(env, desc, idx_d, cb_d), oracle.decode_dense(f, idx, cb))
+    x = workloads.make_x(s.in_features, 752)
+    assert oracle.normwise_rel_err(_gpu_gemv(env, desc, idx_d, cb_d, x, False), oracle.gemv(f, idx, cb, x)) <= TOL_F16
+
+
 def test_newer_kernels_replay_in_a_hip_graph(env):
     """The d = 4 GEMV (workgroup barriers, double-buffered tables), the block-normalised and
     scalar-codebook GEMVs, an 8-wave GEMM tile and the quantiser's two steps in one HIP graph:

@@ -424,6 +424,37 @@ def test_three_bit_scalar_codebook_equals_the_six_bit_pair_table():
     assert ib * 8 / 4096 ** 2 == 3.0 and tb == 2048 * 8 + 2048 * 2
 
 
+def test_two_bit_scalar_codebook_per_row_equals_the_four_bit_pair_table():
+    """One size further down, with one codebook per row of a col-block (groups of 1 x 256, the 1D
+    2.125 row of the appendix table): d = 1, k = 4 over the bytes of d = 2, k = 16 with the same
+    1 x 256 groups and T[j] = (c[j % 4], c[j // 4]); and element by element against the 2-bit
+    fields read directly from the bytes, where a wrong group order (col-block-major instead of
+    row-major) or a wrong field order inside a byte fails."""
+    rng = np.random.default_rng(43)
+    f1 = VQFormat(6, 512, 4, 2, 1, 256, 1)
+    f2 = VQFormat(6, 512, 16, 4, 1, 256, 2)
+    idx = rng.integers(0, 256, size=oracle.canonical_sizes(f1)[0], dtype=np.uint8)
+    assert idx.size == 6 * 512 // 4 == oracle.canonical_sizes(f2)[0]
+    q = rng.integers(-127, 128, size=(f1.n_groups, 4, 1), dtype=np.int8)
+    scale = rng.uniform(0.001, 0.01, size=f1.n_groups).astype(np.float16)
+    c = oracle.dequantise_codebooks(q, scale)
+    j = np.arange(16)
+    T = np.stack([c[:, j % 4, 0], c[:, j // 4, 0]], axis=2)
+    np.testing.assert_array_equal(oracle.decode_dense(f1, idx, c), oracle.decode_dense(f2, idx, T))
+    W = oracle.decode_dense(f1, idx, c).view(np.float16)
+    for (r, col) in [(0, 0), (0, 1), (0, 3), (0, 4), (3, 255), (3, 256), (5, 511), (4, 300)]:
+        g = r * 2 + col // 256
+        v = col % 256
+        field = (int(idx[g * 64 + v // 4]) >> (2 * (v % 4))) & 3
+        assert W[r, col] == np.float16(np.float16(q[g, field, 0]) * scale[g])
+    # 2 bits + (4 x 8-bit values per 256 weights) = 2.125, the figure the table prints; 2.1875 with the scale
+    assert oracle.bits_per_value(4, 1, 8, 256) == 2.125
+    ib, tb = oracle.canonical_sizes_i8(VQFormat(4096, 4096, 4, 2, 1, 256, 1))
+    assert (ib + tb) * 8 / 4096 ** 2 == 2.1875
+    s = workloads.CONFIGS["attn_4096x4096_d1_k4"]
+    assert workloads.canonical_sizes(s) == (ib, tb)
+
+
 def test_scalar_format_sizes_follow_the_bpv_formula():
     """d = 1, k = 16, fp16 codebooks, 8 x 256 groups: 4 + 16*16/2048 = 4.125 bits per value
     (the total of the 1D 4.125 row of the appendix table, which reaches the same overhead with

@@ -22,7 +22,7 @@ import numpy as np
 __all__ = [
     "VQShape", "CONFIGS", "LLAMA7B_LAYER", "seed_for", "canonical_sizes",
     "make_weights", "make_weights_i8", "make_x", "make_X", "llama7b_pass_shapes",
-    "LLAMA7B_LAYER_K64", "LLAMA7B_LAYER_K16_I8", "LLAMA7B_LAYER_D1_K16", "LLAMA7B_LAYER_K64_BN", "make_weights_bn", "LLAMA7B_LAYER_D4", "LLAMA7B_LAYER_D1_K8",
+    "LLAMA7B_LAYER_K64", "LLAMA7B_LAYER_K16_I8", "LLAMA7B_LAYER_D1_K16", "LLAMA7B_LAYER_K64_BN", "make_weights_bn", "LLAMA7B_LAYER_D4", "LLAMA7B_LAYER_D1_K8", "LLAMA7B_LAYER_D1_K4",
 ]
 
 
@@ -89,6 +89,11 @@ CONFIGS = {
     "attn_4096x4096_d1_k8": VQShape(4096, 4096, 8, 3, 32, 256, 1, True),
     "mlp_up_11008x4096_d1_k8": VQShape(11008, 4096, 8, 3, 32, 256, 1, True),
     "mlp_down_4096x11008_d1_k8": VQShape(4096, 11008, 8, 3, 32, 256, 1, True),
+    # scalar codebooks at 2 bits: k = 4 int8 values + scale per row of a col-block (groups of 1 x 256),
+    # the 1D 2.125 row of the appendix table (2.1875 with the fp16 scale counted)
+    "attn_4096x4096_d1_k4": VQShape(4096, 4096, 4, 2, 1, 256, 1, True),
+    "mlp_up_11008x4096_d1_k4": VQShape(11008, 4096, 4, 2, 1, 256, 1, True),
+    "mlp_down_4096x11008_d1_k4": VQShape(4096, 11008, 4, 2, 1, 256, 1, True),
     "tiny_64x512_k64_i8": VQShape(64, 512, 64, 6, 32, 256, 2, True),
     "attn_4096x4096_k64_i8": VQShape(4096, 4096, 64, 6, 32, 256, 2, True),
     "mlp_up_11008x4096_k64_i8": VQShape(11008, 4096, 64, 6, 32, 256, 2, True),
@@ -113,6 +118,7 @@ LLAMA7B_LAYER_K64 = tuple((n, k.replace("_k16", "_k64_i8")) for n, k in LLAMA7B_
 LLAMA7B_LAYER_K16_I8 = tuple((n, k + "_i8") for n, k in LLAMA7B_LAYER)
 LLAMA7B_LAYER_K64_BN = tuple((n, k.replace("_k16", "_k64_bn")) for n, k in LLAMA7B_LAYER)
 LLAMA7B_LAYER_D1_K8 = tuple((n, k.replace("_k16", "_d1_k8")) for n, k in LLAMA7B_LAYER)
+LLAMA7B_LAYER_D1_K4 = tuple((n, k.replace("_k16", "_d1_k4")) for n, k in LLAMA7B_LAYER)
 LLAMA7B_LAYER_D4 = tuple((n, k.replace("_k16", "_d4")) for n, k in LLAMA7B_LAYER)
 LLAMA7B_LAYER_D1_K16 = tuple((n, k.replace("_k16", "_d1_k16")) for n, k in LLAMA7B_LAYER)
 LLAMA7B_N_LAYERS = 32
