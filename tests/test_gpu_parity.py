@@ -227,6 +227,60 @@ def test_gemv_multi_llama_layer(env):
         assert err <= TOL_F16, (i, err)
 
 
+PASS_FORMATS = {
+    "k16": workloads.LLAMA7B_LAYER, "k64_i8": workloads.LLAMA7B_LAYER_K64, "k16_i8": workloads.LLAMA7B_LAYER_K16_I8,
+    "d4": workloads.LLAMA7B_LAYER_D4, "d1_k16": workloads.LLAMA7B_LAYER_D1_K16,
+    "d1_k8": workloads.LLAMA7B_LAYER_D1_K8, "d1_k4": workloads.LLAMA7B_LAYER_D1_K4,
+}
+
+
+@pytest.mark.parametrize("fmt_name", list(PASS_FORMATS))
+def test_full_pass_in_one_launch_sampled_row_blocks(env, fmt_name):
+    """All 224 matrices of the 32-layer pass in ONE vq_gemv_multi call, the launch bench.py times
+    (the persistent grid walking 224 problems), for the headline representation and the others
+    the bench times.  The oracle checks, per matrix, the first and last block of rows and two
+    drawn ones (a block = one row of groups, or 8 rows where groups are lower), each on the slices
+    of the canonical arrays that define it (groups are independent); every output row must have
+    been written."""
+    torch, vq, vqdev = env
+    rng = np.random.default_rng(224)
+    descs, idxs, cbs, xs_d, ys, checks = [], [], [], [], [], []
+    x_host = {n: workloads.make_x(n, 2240 + n) for n in (4096, 11008)}
+    x_dev = {n: vqdev.to_device_bytes(v) for n, v in x_host.items()}
+    for layer in range(workloads.LLAMA7B_N_LAYERS):
+        for m, (name, key) in enumerate(PASS_FORMATS[fmt_name]):
+            s = workloads.CONFIGS[key]
+            seed = workloads.seed_for(key, layer, m)
+            desc = vqdev.desc_from_shape(s)
+            if s.int8_tables:
+                idx, q, scale = workloads.make_weights_i8(s, seed)
+                cb = oracle.dequantise_codebooks(q, scale)
+                idx_d, cb_d = vqdev.upload_and_pack(desc, idx, vqdev.canonical_tables_i8(desc, q, scale))
+            else:
+                idx, cb = workloads.make_weights(s, seed)
+                idx_d, cb_d = vqdev.upload_and_pack(desc, idx, cb)
+            rows = max(s.group_rows, 8)                        # rows of one checked block
+            gpb = rows // s.group_rows * (s.in_features // 256)   # its groups (contiguous in canonical order)
+            gb = s.group_rows * 256 // s.d * s.index_bits // 8  # index bytes of a group
+            n_blk = s.out_features // rows
+            for blk in sorted({0, n_blk - 1, int(rng.integers(0, n_blk)), int(rng.integers(0, n_blk))}):
+                checks.append((len(descs), blk, rows, s, idx[blk * gpb * gb:(blk + 1) * gpb * gb].copy(),
+                               cb[blk * gpb:(blk + 1) * gpb].copy()))
+            descs.append(desc); idxs.append(idx_d); cbs.append(cb_d)
+            xs_d.append(x_dev[s.in_features])
+            ys.append(torch.full((s.out_features,), float("nan"), dtype=torch.float16, device="cuda:0"))
+            del idx, cb
+    assert len(descs) == 224
+    vq.vq_gemv_multi(descs, idxs, cbs, xs_d, ys)
+    torch.cuda.synchronize()
+    y_host = [y.cpu().numpy().astype(np.float64) for y in ys]
+    assert not any(np.isnan(y).any() for y in y_host), "a row was not written"
+    for (m, blk, rows, s, idx_b, cb_b) in checks:
+        sub = oracle.VQFormat(rows, s.in_features, s.k, s.index_bits, s.group_rows, 256, s.d)
+        ref = oracle.gemv(sub, idx_b, cb_b, x_host[s.in_features])
+        assert oracle.normwise_rel_err(y_host[m][blk * rows:(blk + 1) * rows], ref) <= TOL_F16, (m, blk)
+
+
 def _gpu_gemm(env, desc, idx_d, cb_d, X, f32, pad=0):
     torch, vq, vqdev = env
     in_f, B = X.shape
