@@ -869,6 +869,42 @@ def test_d1k4_full_size_layer(env):
     assert oracle.normwise_rel_err(_gpu_gemv(env, desc, idx_d, cb_d, x, False), oracle.gemv(f, idx, cb, x)) <= TOL_F16
 
 
+def _random_cases_newer(seed, n):
+    """Seeded random shapes over the representations added later: d = 4, and d = 1 at 3 and 2 bits."""
+    rng = np.random.default_rng(seed)
+    cases = []
+    for _ in range(n):
+        kind = int(rng.integers(0, 3))
+        n_cb = int(rng.integers(1, 45))
+        if kind == 0:
+            rows = int(rng.choice([64, 128, 256]))
+            cases.append(_shape_d4(rows * int(rng.integers(1, 4)), 256 * n_cb, rows))
+        elif kind == 1:
+            rows = int(rng.choice([8, 16, 32]))
+            cases.append(_shape_d1k8(rows * int(rng.integers(1, 12)), 256 * n_cb, rows))
+        else:
+            cases.append(_shape_d1k4(8 * int(rng.integers(1, 40)), 256 * n_cb))
+    return cases
+
+
+@pytest.mark.parametrize("s", _random_cases_newer(20241, 24), ids=str)
+def test_random_shapes_newer_representations(env, s):
+    """Decode (bit-exact), GEMV (fp16 and fp32 y) and the batched product on random shapes, up to
+    44 col-blocks wide (the width of the 11008-column matrices)."""
+    seed = 7100 + s.out_features + s.in_features + s.k
+    desc, idx, cb, idx_d, cb_d = _setup_i8(env, s, seed)
+    f = _fmt(s)
+    np.testing.assert_array_equal(_gpu_decode(env, desc, idx_d, cb_d), oracle.decode_dense(f, idx, cb))
+    x = workloads.make_x(s.in_features, seed)
+    ref = oracle.gemv(f, idx, cb, x)
+    assert oracle.normwise_rel_err(_gpu_gemv(env, desc, idx_d, cb_d, x, False), ref) <= TOL_F16
+    assert oracle.normwise_rel_err(_gpu_gemv(env, desc, idx_d, cb_d, x, True), ref) <= TOL_F32
+    B = int(np.random.default_rng(seed).choice([1, 3, 8, 17, 33, 72, 200]))
+    X = workloads.make_X(s.in_features, B, seed)
+    Y = _gpu_gemm(env, desc, idx_d, cb_d, X, True)
+    assert oracle.normwise_rel_err(Y, oracle.gemm(f, idx, cb, X)) <= TOL_F32
+
+
 def test_newer_kernels_replay_in_a_hip_graph(env):
     """The d = 4 GEMV (workgroup barriers, double-buffered tables), the block-normalised and
     scalar-codebook GEMVs, an 8-wave GEMM tile and the quantiser's two steps in one HIP graph:
