@@ -208,6 +208,9 @@ def main():
                  "gemv_stream_kernel<64>"),
                 ("llama7b_pass_k16_int8_tables_2.125bpv_via_vq_gemv_multi", workloads.LLAMA7B_LAYER_K16_I8,
                  "gemv_stream_kernel<k16,int8>"),
+                # the 4-bits-per-dimension 2D setting: k = 256, int8 tables shared by 128 x 256 groups (4.125 bpv)
+                ("llama7b_pass_k256_int8_tables_4.125bpv_via_vq_gemv_multi", workloads.LLAMA7B_LAYER_K256_I8,
+                 "gemv_k256i8_kernel"),
                 # the deployed representation with blockwise normalisation on top (appendix): 16 levels
                 # per group and a 4-bit code per 32 weights, 3.28 bits per value
                 ("llama7b_pass_k64_int8_tables_block_norm_3.28bpv_via_vq_gemv_multi", workloads.LLAMA7B_LAYER_K64_BN,
@@ -235,6 +238,10 @@ def main():
                         n_groups = (s.out_features // s.group_rows) * (s.in_features // 256)
                         tab[n_groups * 1024:] = 0
                         tab[n_groups * 1024 + 1:n_groups * 1026:2] = 0x1C
+                    elif s.d == 2 and s.k == 256:       # 512-byte int8 tables per group, then fp16 scales (2^-8)
+                        n_groups = (s.out_features // s.group_rows) * (s.in_features // 256)
+                        tab[n_groups * 512:] = 0
+                        tab[n_groups * 512 + 1:n_groups * 514:2] = 0x1C
                     elif s.d == 1 and s.k == 8:         # 48-byte records: 4 x 8 int8, 4 scales (2^-8), padding
                         tv = tab.view(-1, 48)
                         tv[:, 32:48] = 0

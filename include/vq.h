@@ -46,7 +46,9 @@
  * Implemented representations (d = 2 unless stated): VQ_F16 with 8 x 256 groups and k = 16
  * or 256; VQ_I8 with k = 64 (6-bit indices) and groups of 8, 16 or 32 rows x 256 columns
  * (32 rows: the 8,192-weight groups and 3.125 bits per value of Sec. 5.1); VQ_I8 with k = 16
- * and 8 x 256 groups (2.125 bits per value); and scalar codebooks, d = 1 (the 1D rows of the
+ * and 8 x 256 groups (2.125 bits per value); VQ_I8 with k = 256 and groups of 64, 128 or 256
+ * rows x 256 columns (128 rows: the 32,768-weight groups and 4.125 bits per value of the 2D
+ * 4-bits-per-dimension setting); and scalar codebooks, d = 1 (the 1D rows of the
  * appendix table of VQ configurations): VQ_F16, k = 16, 4-bit indices, 8 x 256 groups, 4.125
  * bits per value; VQ_I8, k = 8, 3-bit indices, groups of 8, 16 or 32 rows x 256 columns; and
  * VQ_I8, k = 4, 2-bit indices, groups of 1 x 256 (one codebook per row of a 256-column block,

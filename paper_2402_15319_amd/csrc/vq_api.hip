@@ -51,6 +51,8 @@ int check_desc(const vq_desc* d) {
       if (d->group_rows != 8 && d->group_rows != 16 && d->group_rows != 32) return VQ_ERR_UNSUPPORTED;
     } else if (d->k == 16 && !is_bn(*d)) {
       if (d->group_rows != kGroupRows) return VQ_ERR_UNSUPPORTED;
+    } else if (d->k == 256 && !is_bn(*d)) {   // the 4-bits-per-dimension 2D setting: large groups share a table
+      if (d->group_rows != 64 && d->group_rows != 128 && d->group_rows != 256) return VQ_ERR_UNSUPPORTED;
     } else {
       return VQ_ERR_UNSUPPORTED;
     }
@@ -163,6 +165,12 @@ int vq_layout_bytes(const vq_desc* desc, size_t* idx_bytes, size_t* cb_bytes) {
     if (cb_bytes) *cb_bytes = (size_t)(desc->out_features / desc->group_rows) * n_quads * 48;
     return VQ_OK;
   }
+  if (desc->d == 2 && desc->k == 256 && is_i8(*desc)) {   // 1 KB of indices per (8-row block, col-block); tables as canonical
+    const size_t n_groups = (size_t)(desc->out_features / desc->group_rows) * n_cb;
+    if (idx_bytes) *idx_bytes = n_rb * n_cb * 1024;
+    if (cb_bytes) *cb_bytes = n_groups * 512 + (2 * n_groups + 15) / 16 * 16;
+    return VQ_OK;
+  }
   if (desc->d == 1 && desc->k == 4) {   // indices as for k = 16; a 48-byte table record per (8-row block, col-block slot)
     const size_t slots = 2 * ((n_cb + 1) / 2);
     if (idx_bytes) *idx_bytes = n_rb * slots * 512;
@@ -216,7 +224,7 @@ int vq_gemv_multi(int count, const vq_desc* descs, const void* const* idx_dev,
       if (c > max_n_cb) max_n_cb = c;
     }
     const int fmt = format_tag(descs[0]);
-    if (fmt == kFmtD4) {   // one workgroup per 64 rows, see vq_gemv_d4.hip
+    if (fmt == kFmtD4 || fmt == kFmtK256I8) {   // one workgroup per 64 rows, see vq_gemv_d4.hip
       GemvBatch batch;
       memset(&batch, 0, offsetof(GemvBatch, p) + (size_t)n * sizeof(GemvProblem));
       batch.count = n;
@@ -238,7 +246,9 @@ int vq_gemv_multi(int count, const vq_desc* descs, const void* const* idx_dev,
       }
       if (wgs > 0x7fffffffll) return VQ_ERR_UNSUPPORTED;
       batch.total_wgs = (int32_t)wgs;
-      if (launch_gemv_d4(batch, (int)wgs, (hipStream_t)stream) != hipSuccess) return VQ_ERR_HIP;
+      const hipError_t e = fmt == kFmtD4 ? launch_gemv_d4(batch, (int)wgs, (hipStream_t)stream)
+                                         : launch_gemv_k256i8(batch, (int)wgs, (hipStream_t)stream);
+      if (e != hipSuccess) return VQ_ERR_HIP;
       continue;
     }
     const long long stream_from = 4096;   // row-blocks from which the persistent kernel pays

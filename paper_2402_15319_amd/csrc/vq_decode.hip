@@ -16,8 +16,8 @@ template <int K>
 __global__ __launch_bounds__(256) void decode_kernel(const uint8_t* __restrict__ idx,
                                                      const uint32_t* __restrict__ cb,
                                                      uint16_t* __restrict__ W, int n_cb,
-                                                     long long n_groups, int in_features) {
-  __shared__ uint32_t lut_all[4][K == kFmtK16I8 ? 16 : K == kFmtD1K16 ? 256 : K == kFmtD1K4 ? 128 : K];
+                                                     long long n_groups, int in_features, int rpc) {
+  __shared__ uint32_t lut_all[4][K == kFmtK16I8 ? 16 : (K == kFmtD1K16 || K == kFmtK256I8) ? 256 : K == kFmtD1K4 ? 128 : K];
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   uint32_t* lut = lut_all[wave];
@@ -78,7 +78,15 @@ __global__ __launch_bounds__(256) void decode_kernel(const uint8_t* __restrict__
       }
     }
   } else {
-    if (K == kFmtD1K16) {
+    if (K == kFmtK256I8) {   // int8 table of group (rb / rpc, c): lane L dequantises entries 4L .. 4L+3
+      const uint8_t* tab = reinterpret_cast<const uint8_t*>(cb);
+      const long long gt = (rb / rpc) * n_cb + c, n_tabs = (n_groups / n_cb / rpc) * n_cb;
+      const uint2 q = *reinterpret_cast<const uint2*>(tab + gt * 512 + lane * 8);
+      const _Float16 scale = __builtin_bit_cast(_Float16, reinterpret_cast<const uint16_t*>(tab + n_tabs * 512)[gt]);
+      *reinterpret_cast<uint4*>(lut + lane * 4) =
+          make_uint4(k64_dequant_pair(q.x, scale), k64_dequant_pair(q.x >> 16, scale),
+                     k64_dequant_pair(q.y, scale), k64_dequant_pair(q.y >> 16, scale));
+    } else if (K == kFmtD1K16) {
       const uint8_t* cg = reinterpret_cast<const uint8_t*>(cb) + g * 32;
       *reinterpret_cast<uint4*>(lut + lane * 4) =
           d1_pair_entries(*reinterpret_cast<const uint2*>(cg + (lane & 3) * 8),
@@ -227,10 +235,12 @@ hipError_t launch_decode(const vq_desc& d, const void* idx_dev, const void* cb_d
   }
 #define VQ_DECODE(K)                                                                                \
   hipLaunchKernelGGL(decode_kernel<K>, dim3(grid), dim3(256), 0, s, (const uint8_t*)idx_dev,       \
-                     (const uint32_t*)cb_dev, (uint16_t*)W, n_cb, n_groups, d.in_features)
+                     (const uint32_t*)cb_dev, (uint16_t*)W, n_cb, n_groups, d.in_features,          \
+                     d.group_rows >= kGroupRows ? d.group_rows / kGroupRows : 1)
   if (fmt == kFmtK16I8) VQ_DECODE(kFmtK16I8);
   else if (fmt == kFmtD1K16) VQ_DECODE(kFmtD1K16);
   else if (fmt == kFmtD1K4) VQ_DECODE(kFmtD1K4);
+  else if (fmt == kFmtK256I8) VQ_DECODE(kFmtK256I8);
   else if (fmt == 16) VQ_DECODE(16);
   else VQ_DECODE(256);
 #undef VQ_DECODE

@@ -39,7 +39,7 @@ __device__ __forceinline__ int wt_half_index(int m, int k) {   // k in halfs
 // scale per group, groups of 8*rpc rows), kFmtK16I8 (k = 16 with int8 tables).
 template <int K> constexpr int lut_dwords() {
   // BN: 64 centroids + 16 levels; d = 4: 256 entries of 4 halfs; scalar 2-bit: 8 rows x 16 pair entries
-  return K == kFmtK16I8 ? 16 : K == kFmtD1K16 ? 256 : K == kFmtK64BN ? 80 : K == kFmtD4 ? 512 : K == kFmtD1K8 ? 64 : K == kFmtD1K4 ? 128 : K;
+  return K == kFmtK16I8 ? 16 : (K == kFmtD1K16 || K == kFmtK256I8) ? 256 : K == kFmtK64BN ? 80 : K == kFmtD4 ? 512 : K == kFmtD1K8 ? 64 : K == kFmtD1K4 ? 128 : K;
 }
 
 // What one wave needs to decode one group: the lane's index bytes and codebook piece.
@@ -74,6 +74,11 @@ template <> struct GroupRegs<kFmtD1K16> {
   uint4 w;
   uint2 clo;      // scalars 4*(lane%4) .. +3 of the group's 16
   uint32_t chi;   // scalar lane/4
+};
+template <> struct GroupRegs<kFmtK256I8> {
+  uint4 w;
+  uint2 q;        // table entries 4*lane .. 4*lane+3 (int8 pairs)
+  uint32_t sc;    // the group's fp16 scale
 };
 template <> struct GroupRegs<kFmtD1K4> {
   uint2 w;
@@ -112,6 +117,12 @@ __device__ __forceinline__ void load_group(GroupRegs<K>& g, const uint8_t* idx, 
     g.w = *reinterpret_cast<const uint2*>(idx + ((size_t)rb * ((n_cb + 1) >> 1) + (c >> 1)) * 1024 + lane * 16 + (c & 1) * 8);
     g.q = *reinterpret_cast<const uint4*>(tab + gi * 1024 + lane * 16);
     g.sc = reinterpret_cast<const uint16_t*>(tab + n_groups * 1024)[gi];
+  } else if constexpr (K == kFmtK256I8) {
+    const uint8_t* tab = reinterpret_cast<const uint8_t*>(cb);
+    const size_t gt = (size_t)(rb / rpc) * n_cb + c, n_tabs = (size_t)(n_rb / rpc) * n_cb;
+    g.w = *reinterpret_cast<const uint4*>(idx + ((size_t)rb * n_cb + c) * 1024 + lane * 16);
+    g.q = *reinterpret_cast<const uint2*>(tab + gt * 512 + lane * 8);
+    g.sc = reinterpret_cast<const uint16_t*>(tab + n_tabs * 512)[gt];
   } else if constexpr (K == kFmtD1K16) {
     const size_t gi = (size_t)rb * n_cb + c;
     const uint8_t* cg = reinterpret_cast<const uint8_t*>(cb) + gi * 32;
@@ -228,8 +239,16 @@ __device__ __forceinline__ void decode_group(const GroupRegs<K>& g, uint32_t* lu
     }
   } else {
     const auto& q = g;
-    if constexpr (K == kFmtD1K16) *reinterpret_cast<uint4*>(lut + lane * 4) = d1_pair_entries(q.clo, q.chi);
-    else *reinterpret_cast<uint4*>(lut + lane * 4) = q.cbv;
+    if constexpr (K == kFmtD1K16) {
+      *reinterpret_cast<uint4*>(lut + lane * 4) = d1_pair_entries(q.clo, q.chi);
+    } else if constexpr (K == kFmtK256I8) {
+      const _Float16 scale = __builtin_bit_cast(_Float16, (uint16_t)q.sc);
+      *reinterpret_cast<uint4*>(lut + lane * 4) =
+          make_uint4(k64_dequant_pair(q.q.x, scale), k64_dequant_pair(q.q.x >> 16, scale),
+                     k64_dequant_pair(q.q.y, scale), k64_dequant_pair(q.q.y >> 16, scale));
+    } else {
+      *reinterpret_cast<uint4*>(lut + lane * 4) = q.cbv;
+    }
     wave_lds_sync();
     const uint32_t ws[4] = {q.w.x, q.w.y, q.w.z, q.w.w};
 #pragma unroll
@@ -759,6 +778,7 @@ hipError_t launch_gemm(const vq_desc& d, const void* idx_dev, const void* cb_dev
   if (fmt == kFmtD4) VQ_GEMM_DISPATCH(kFmtD4)
   if (fmt == kFmtD1K8) VQ_GEMM_DISPATCH(kFmtD1K8)
   if (fmt == kFmtD1K4) VQ_GEMM_DISPATCH(kFmtD1K4)
+  if (fmt == kFmtK256I8) VQ_GEMM_DISPATCH(kFmtK256I8)
   if (fmt == 16) VQ_GEMM_DISPATCH(16)
   VQ_GEMM_DISPATCH(256)
 #undef VQ_GEMM_DISPATCH

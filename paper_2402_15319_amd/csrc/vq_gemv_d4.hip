@@ -100,7 +100,85 @@ __global__ __launch_bounds__(512) void gemv_d4_kernel(const GemvBatch batch) {
   }
 }
 
+// ---- d = 2, k = 256, int8 tables with a scale, groups of 64, 128 or 256 rows ---------------
+// The 4-bits-per-dimension 2D setting of the appendix table of VQ configurations: a 256-entry
+// table is worth its bytes only when many rows share it, so the work is cut as above: 8 waves
+// own 64 rows of one group row, per pair of col-blocks the 512 threads dequantise the two
+// tables once (one entry each: two int8 times the scale, one dword into LDS), a barrier, and
+// every wave runs the k = 256 inner block (16 lookups and 16 dot2 per col-block and lane) on
+// its own 8 rows.  Indices are laid out as for k = 256 with fp16 codebooks (1 KB per 8-row
+// block and col-block); the tables keep the canonical order (512 bytes per group, then scales).
+struct K256Step {
+  uint4 w0, w1;   // the lane's 16 index bytes in the two col-blocks of the pair
+  uint2 xa, xb;   // its activations there
+  uint32_t q;     // this thread's table entry (2 int8) of col-block (tid >> 8) of the pair
+  uint32_t sc;    // that table's fp16 scale
+};
+
+__global__ __launch_bounds__(512) void gemv_k256i8_kernel(const GemvBatch batch) {
+  __shared__ __attribute__((aligned(16))) uint32_t tabs[2][2][256];   // [buffer][col-block of the pair][entry]
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const GemvProblem& P = batch.p[find_problem_d4(batch, blockIdx.x)];
+  const int oct = blockIdx.x - P.wg_begin;          // which 64 rows
+  const int n_cb = P.n_cb, n_pairs = (n_cb + 1) >> 1;
+  const int rb = oct * 8 + wave;
+  const long long grow = (long long)(oct * 8) / P.rb_per_cb;
+  const uint8_t* tab = reinterpret_cast<const uint8_t*>(P.cb);
+  const long long n_groups = (long long)(P.n_rb / P.rb_per_cb) * n_cb;
+  const uint16_t* scales = reinterpret_cast<const uint16_t*>(tab + n_groups * 512);
+  const uint8_t* idx_lane = P.idx + (size_t)rb * n_cb * 1024 + lane * 16;
+  const uint16_t* x_lane = P.x + lane * 4;
+  const int h = tid >> 8, e = tid & 255;            // table duty of this thread
+
+  auto load = [&](int p, K256Step& s) {
+    const int c0 = 2 * p, c1 = 2 * p + 1;
+    const bool ok1 = c1 < n_cb;
+    const int c1_ld = ok1 ? c1 : c0;                // an absent second col-block re-reads the first (not used)
+    const long long g = grow * n_cb + (h == 0 ? c0 : c1_ld);
+    s.w0 = *reinterpret_cast<const uint4*>(idx_lane + (size_t)c0 * 1024);
+    s.w1 = *reinterpret_cast<const uint4*>(idx_lane + (size_t)c1_ld * 1024);
+    s.xa = *reinterpret_cast<const uint2*>(x_lane + (size_t)c0 * 256);
+    const uint2 xb = *reinterpret_cast<const uint2*>(x_lane + (size_t)c1_ld * 256);
+    s.xb = ok1 ? xb : make_uint2(0u, 0u);
+    s.q = *reinterpret_cast<const uint16_t*>(tab + g * 512 + e * 2);
+    s.sc = scales[g];
+  };
+
+  float acc[8];
+#pragma unroll
+  for (int r = 0; r < 8; ++r) acc[r] = 0.f;
+
+  K256Step cur, nxt;
+  load(0, cur);
+  for (int p = 0; p < n_pairs; ++p) {
+    load(p + 1 < n_pairs ? p + 1 : p, nxt);         // one step ahead (a harmless re-read at the end)
+    const int buf = p & 1;
+    const bool mine = h == 0 || 2 * p + 1 < n_cb;   // the absent col-block of an odd matrix gets a zero table
+    tabs[buf][h][e] = mine ? k64_dequant_pair(cur.q, __builtin_bit_cast(_Float16, (uint16_t)cur.sc)) : 0u;
+    __syncthreads();   // tables of this step complete; the other buffer is free again
+    const uint32_t base = lds_addr(&tabs[buf][0][0]);
+    k256_group<0>(cur.w0.x, cur.w0.y, cur.w0.z, cur.w0.w, base, cur.xa.x, cur.xa.y, acc);
+    k256_group<1024>(cur.w1.x, cur.w1.y, cur.w1.z, cur.w1.w, base, cur.xb.x, cur.xb.y, acc);
+    acc_hazard_fence();
+    cur = nxt;
+  }
+
+  const float v = wave_reduce8(acc, lane);   // every lane: the total of row (lane >> 3) & 7
+  if ((lane & 7) == 0) {
+    const size_t o = (size_t)rb * 8 + (lane >> 3);
+    if (batch.y_f32) reinterpret_cast<float*>(P.y)[o] = v;
+    else reinterpret_cast<_Float16*>(P.y)[o] = (_Float16)v;
+  }
+}
+
 }  // namespace
+
+hipError_t launch_gemv_k256i8(const GemvBatch& batch, int total_wgs, hipStream_t s) {
+  hipLaunchKernelGGL(gemv_k256i8_kernel, dim3((unsigned)total_wgs), dim3(512), 0, s, batch);
+  return hipGetLastError();
+}
 
 hipError_t launch_gemv_d4(const GemvBatch& batch, int total_wgs, hipStream_t s) {
   hipLaunchKernelGGL(gemv_d4_kernel, dim3((unsigned)total_wgs), dim3(512), 0, s, batch);

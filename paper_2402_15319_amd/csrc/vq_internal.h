@@ -15,6 +15,7 @@ constexpr int kMaxProblemsPerLaunch = 256;  // the problem table travels in the 
 // 256-entry table of fp16 pairs T[j] = (c[j % 16], c[j / 16]) that the kernels build in LDS from
 // the group's 16 scalars; from there on the work is that of d = 2, k = 256.
 constexpr int kFmtK16I8 = 1016;
+constexpr int kFmtK256I8 = 1256;   // d = 2, k = 256, int8 tables + scale, groups of 64, 128 or 256 rows x 256 columns
 constexpr int kFmtD1K16 = 2016;
 constexpr int kFmtK64BN = 3064;   // k = 64, int8 tables + scale, blockwise normalisation (blocks of 32)
 constexpr int kFmtD1K8 = 2008;     // d = 1, k = 8 (3-bit indices), int8 values + scale: pairs index a 64-entry pair table
@@ -27,6 +28,7 @@ inline int format_tag(const vq_desc& d) {
   if (d.d == 4) return kFmtD4;
   if (d.codebook_dtype == VQ_I8_BN) return kFmtK64BN;
   if (d.k == 16 && d.codebook_dtype == VQ_I8) return kFmtK16I8;
+  if (d.k == 256 && d.codebook_dtype == VQ_I8) return kFmtK256I8;
   return d.k;
 }
 constexpr int kStreamMaxColBlocks = 96;   // widest x the streaming kernel stages in LDS (48 KB)
@@ -69,8 +71,10 @@ size_t gemv_stream_lds_bytes(int fmt, int max_n_cb);
 int gemv_stream_resident_wgs(int fmt, int max_n_cb);
 // Units (col-block pairs, quads or col-blocks, by format) that one chunk of the GEMV kernels holds.
 int gemv_chunk_units(int fmt);
-// d = 4: its own GEMV kernel (workgroups share a group's table; see vq_gemv_d4.hip).
+// d = 4, and d = 2 with k = 256 and int8 tables: GEMV kernels of their own (a workgroup of 8 waves
+// owns 64 rows and shares the group's dequantised table; see vq_gemv_d4.hip).
 hipError_t launch_gemv_d4(const GemvBatch& batch, int total_wgs, hipStream_t s);
+hipError_t launch_gemv_k256i8(const GemvBatch& batch, int total_wgs, hipStream_t s);
 hipError_t launch_gemm(const vq_desc& d, const void* idx_dev, const void* cb_dev,
                        const void* X, int B, int ldx, void* Y, int ldy, int y_f32,
                        hipStream_t s);

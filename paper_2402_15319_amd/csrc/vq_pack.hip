@@ -15,7 +15,7 @@ namespace {
 template <int K>
 __global__ __launch_bounds__(256) void pack_idx_kernel(const uint8_t* __restrict__ canon,
                                                        uint8_t* __restrict__ dev, int n_cb,
-                                                       long long n_slots, int row_groups) {
+                                                       long long n_slots, int row_groups, int rpc) {
   const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
   const long long slot = t >> 6;
   const int lane = (int)(t & 63);
@@ -45,8 +45,14 @@ __global__ __launch_bounds__(256) void pack_idx_kernel(const uint8_t* __restrict
     uint8_t* dst = dev + rb * slots_per_rb * 512 + k16_chunk_offset(c, lane);
     *reinterpret_cast<uint2*>(dst) = make_uint2(words[0], words[1]);
   } else {
+    // slot = (8-row block rb, col-block c); its 1 KB sits in canonical group (rb / rpc, c) of
+    // rpc 8-row blocks (rpc = 1: the group itself)
     const long long g = slot;
-    const uint8_t* src = canon + g * 1024 + 2 * lane;
+    const long long rb = slot / n_cb;
+    const int c = (int)(slot - rb * n_cb);
+    const long long grow = rb / rpc;
+    const int sub = (int)(rb - grow * rpc);
+    const uint8_t* src = canon + ((grow * n_cb + c) * rpc + sub) * 1024 + 2 * lane;
     uint32_t w[4];
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
@@ -356,11 +362,25 @@ hipError_t launch_pack(const vq_desc& d, const void* idx_canon, const void* cb_c
     return hipGetLastError();
   }
   const int fmt = format_tag(d);
+  if (fmt == kFmtK256I8) {   // indices as for k = 256, gathered from groups of rpc 8-row blocks; tables copied
+    const int rpc = d.group_rows / kGroupRows;
+    const long long n_slots = n_rb * n_cb;
+    const long long n_groups = (long long)(d.out_features / d.group_rows) * n_cb;
+    hipLaunchKernelGGL(pack_idx_kernel<256>, dim3((unsigned)((n_slots * 64 + 255) / 256)), dim3(256), 0, s,
+                       (const uint8_t*)idx_canon, (uint8_t*)idx_dev, n_cb, n_slots, 0, rpc);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const long long src_bytes = n_groups * 512 + 2 * n_groups;       // tables (a multiple of 16), then scales
+    const long long n16 = (src_bytes + 15) / 16;
+    hipLaunchKernelGGL(copy16_kernel, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, s,
+                       (const uint8_t*)cb_canon, (uint8_t*)cb_dev, n16, src_bytes);
+    return hipGetLastError();
+  }
   const int slots_per_rb = (fmt == 16 || fmt == kFmtK16I8 || fmt == kFmtD1K4) ? 2 * k16_pairs(n_cb) : n_cb;
   const long long n_slots = n_rb * slots_per_rb;
   if (fmt == kFmtD1K4) {
     hipLaunchKernelGGL(pack_idx_kernel<16>, dim3((unsigned)((n_slots * 64 + 255) / 256)), dim3(256), 0, s,
-                       (const uint8_t*)idx_canon, (uint8_t*)idx_dev, n_cb, n_slots, 1);
+                       (const uint8_t*)idx_canon, (uint8_t*)idx_dev, n_cb, n_slots, 1, 1);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const size_t q_bytes = ((size_t)d.out_features * n_cb * 4 + 15) / 16 * 16;   // scales follow the values
@@ -371,7 +391,7 @@ hipError_t launch_pack(const vq_desc& d, const void* idx_canon, const void* cb_c
   }
   if (fmt == kFmtK16I8) {
     hipLaunchKernelGGL(pack_idx_kernel<16>, dim3((unsigned)((n_slots * 64 + 255) / 256)), dim3(256), 0, s,
-                       (const uint8_t*)idx_canon, (uint8_t*)idx_dev, n_cb, n_slots, 0);
+                       (const uint8_t*)idx_canon, (uint8_t*)idx_dev, n_cb, n_slots, 0, 1);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const size_t q_bytes = ((size_t)n_rb * n_cb * 32 + 15) / 16 * 16;      // scales follow the tables
@@ -383,10 +403,10 @@ hipError_t launch_pack(const vq_desc& d, const void* idx_canon, const void* cb_c
   const unsigned grid = (unsigned)((n_slots * 64 + 255) / 256);
   if (fmt == 16)
     hipLaunchKernelGGL(pack_idx_kernel<16>, dim3(grid), dim3(256), 0, s,
-                       (const uint8_t*)idx_canon, (uint8_t*)idx_dev, n_cb, n_slots, 0);
+                       (const uint8_t*)idx_canon, (uint8_t*)idx_dev, n_cb, n_slots, 0, 1);
   else   // k = 256 bytes, or d = 1: a byte holds the two 4-bit indices of a column pair
     hipLaunchKernelGGL(pack_idx_kernel<256>, dim3(grid), dim3(256), 0, s,
-                       (const uint8_t*)idx_canon, (uint8_t*)idx_dev, n_cb, n_slots, 0);
+                       (const uint8_t*)idx_canon, (uint8_t*)idx_dev, n_cb, n_slots, 0, 1);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const int per_group = d.k * d.d * 2 / 16;                      // 16-byte pieces of one fp16 codebook

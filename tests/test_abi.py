@@ -78,7 +78,9 @@ A = 0x1000  # a fake, 16-byte aligned, non-NULL address; validation fails before
     (dict(group_rows=4), -3),
     (dict(group_cols=128), -3),
     (dict(k=64, index_bits=6), -3),                                       # k = 64 needs int8 tables
-    (dict(k=256, index_bits=8, codebook_dtype=3), -3),                    # int8 tables: k = 16 or 64
+    (dict(k=256, index_bits=8, codebook_dtype=3), -3),                    # k = 256 with int8 tables: groups of 64, 128 or 256 rows
+    (dict(k=256, index_bits=8, codebook_dtype=3, group_rows=32), -3),
+    (dict(k=256, index_bits=8, codebook_dtype=4, group_rows=128), -3),    # blockwise normalisation: k = 64 only
     (dict(codebook_dtype=3, group_rows=32), -3),                          # k = 16 int8: 8-row groups
     (dict(k=64, index_bits=6, codebook_dtype=3, group_rows=24), -3),
     (dict(k=64, index_bits=6, codebook_dtype=3, group_rows=32, out_features=4112), -3),
@@ -264,3 +266,16 @@ def test_two_bit_scalar_representation_sizes():
         slots = 2 * ((in_f // 256 + 1) // 2)
         assert vq.vq_layout_bytes(d) == ((out_f // 8) * slots * 512, (out_f // 8) * slots * 48)
         assert L.vq_gemv(ctypes.byref(d), A, A, A + 2, A + 16, vq.VQ_F16, 0) == -4
+
+
+def test_k256_int8_representation_sizes():
+    """d = 2, k = 256, int8 tables shared by groups of 64, 128 or 256 rows: one index byte per
+    vector in both layouts, 512 bytes of table and a 2-byte scale per group."""
+    L = vq.lib()
+    for out_f, in_f, rows in ((4096, 4096, 128), (11008, 4096, 128), (4096, 11008, 256), (192, 768, 64)):
+        d = vq.make_desc(out_f, in_f, 256, 8, group_rows=rows, codebook_dtype=vq.VQ_I8)
+        n_groups = (out_f // rows) * (in_f // 256)
+        assert vq.vq_canonical_bytes(d) == (out_f * in_f // 2, n_groups * 512 + 2 * n_groups)
+        assert vq.vq_layout_bytes(d) == (out_f * in_f // 2, n_groups * 512 + (2 * n_groups + 15) // 16 * 16)
+        assert L.vq_gemv(ctypes.byref(d), A, A, A + 2, A + 16, vq.VQ_F16, 0) == -4
+    assert vq.vq_layout_bytes(vq.make_desc(4096, 4096, 256, 8, group_rows=128, codebook_dtype=vq.VQ_I8))[0] * 8 / 4096 ** 2 == 4.0

@@ -229,7 +229,7 @@ def test_gemv_multi_llama_layer(env):
 
 PASS_FORMATS = {
     "k16": workloads.LLAMA7B_LAYER, "k64_i8": workloads.LLAMA7B_LAYER_K64, "k16_i8": workloads.LLAMA7B_LAYER_K16_I8,
-    "d4": workloads.LLAMA7B_LAYER_D4, "d1_k16": workloads.LLAMA7B_LAYER_D1_K16,
+    "k256_i8": workloads.LLAMA7B_LAYER_K256_I8, "d4": workloads.LLAMA7B_LAYER_D4, "d1_k16": workloads.LLAMA7B_LAYER_D1_K16,
     "d1_k8": workloads.LLAMA7B_LAYER_D1_K8, "d1_k4": workloads.LLAMA7B_LAYER_D1_K4,
 }
 
@@ -867,6 +867,62 @@ def test_d1k4_full_size_layer(env):
     np.testing.assert_array_equal(_gpu_decode(env, desc, idx_d, cb_d), oracle.decode_dense(f, idx, cb))
     x = workloads.make_x(s.in_features, 752)
     assert oracle.normwise_rel_err(_gpu_gemv(env, desc, idx_d, cb_d, x, False), oracle.gemv(f, idx, cb, x)) <= TOL_F16
+
+
+# ---------------------------------------------------------------- k = 256 with int8 tables shared by large groups
+def _shape_k256i8(o, i, rows=128):
+    return workloads.VQShape(o, i, 256, 8, rows, 256, 2, True)
+
+
+K256I8_SMALL = [_shape_k256i8(128, 256), _shape_k256i8(256, 768), _shape_k256i8(128, 2816), _shape_k256i8(192, 1280, 64),
+                _shape_k256i8(512, 512, 256), _shape_k256i8(64, 11008, 64)]
+
+
+@pytest.mark.parametrize("s", K256I8_SMALL, ids=str)
+def test_k256i8_decode_and_gemv(env, s):
+    """Decode bit for bit, GEMV with fp16 and fp32 output; odd and even numbers of col-blocks,
+    every group height, several groups per 64-row workgroup and several workgroups per group."""
+    desc, idx, cb, idx_d, cb_d = _setup_i8(env, s, 760)
+    f = _fmt(s)
+    np.testing.assert_array_equal(_gpu_decode(env, desc, idx_d, cb_d), oracle.decode_dense(f, idx, cb))
+    x = workloads.make_x(s.in_features, 760)
+    ref = oracle.gemv(f, idx, cb, x)
+    assert oracle.normwise_rel_err(_gpu_gemv(env, desc, idx_d, cb_d, x, False), ref) <= TOL_F16
+    assert oracle.normwise_rel_err(_gpu_gemv(env, desc, idx_d, cb_d, x, True), ref) <= TOL_F32
+
+
+@pytest.mark.parametrize("B", [1, 16, 40, 130, 600, 1300])
+@pytest.mark.parametrize("s", [_shape_k256i8(128, 768), _shape_k256i8(768, 512, 64)], ids=str)
+def test_k256i8_gemm(env, s, B):
+    desc, idx, cb, idx_d, cb_d = _setup_i8(env, s, 761)
+    X = workloads.make_X(s.in_features, B, 761)
+    Y = _gpu_gemm(env, desc, idx_d, cb_d, X, False, pad=8 if B == 40 else 0)
+    assert oracle.normwise_rel_err(Y, oracle.gemm(_fmt(s), idx, cb, X)) <= TOL_F16
+
+
+def test_k256i8_full_size_layer_and_multi(env):
+    """The 11008-row matrix at full size (decode bit for bit, GEMV), and q/k/v-like launches of
+    three matrices in one vq_gemv_multi call."""
+    torch, vq, vqdev = env
+    s = workloads.CONFIGS["mlp_up_11008x4096_k256_i8"]
+    desc, idx, cb, idx_d, cb_d = _setup_i8(env, s, 762)
+    f = _fmt(s)
+    np.testing.assert_array_equal(_gpu_decode(env, desc, idx_d, cb_d), oracle.decode_dense(f, idx, cb))
+    x = workloads.make_x(s.in_features, 762)
+    assert oracle.normwise_rel_err(_gpu_gemv(env, desc, idx_d, cb_d, x, False), oracle.gemv(f, idx, cb, x)) <= TOL_F16
+    shapes = [_shape_k256i8(256, 768), _shape_k256i8(128, 1280, 64), _shape_k256i8(512, 256, 256)]
+    descs, idxs, cbs, xs, ys, refs = [], [], [], [], [], []
+    for m, sm in enumerate(shapes):
+        d_, idx_, cb_, idx_d_, cb_d_ = _setup_i8(env, sm, 763 + m)
+        xm = workloads.make_x(sm.in_features, 763 + m)
+        descs.append(d_); idxs.append(idx_d_); cbs.append(cb_d_)
+        xs.append(vqdev.to_device_bytes(xm))
+        ys.append(torch.full((sm.out_features,), 7.0, dtype=torch.float32, device="cuda:0"))
+        refs.append(oracle.gemv(_fmt(sm), idx_, cb_, xm))
+    vq.vq_gemv_multi(descs, idxs, cbs, xs, ys, vq.VQ_F32)
+    torch.cuda.synchronize()
+    for y, ref in zip(ys, refs):
+        assert oracle.normwise_rel_err(y.cpu().numpy(), ref) <= TOL_F32
 
 
 def _random_cases_newer(seed, n):

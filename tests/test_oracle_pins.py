@@ -455,6 +455,37 @@ def test_two_bit_scalar_codebook_per_row_equals_the_four_bit_pair_table():
     assert workloads.canonical_sizes(s) == (ib, tb)
 
 
+def test_four_bits_per_dimension_2d_setting_sizes_and_group_sharing():
+    """The 2D 4.125 row of the appendix table: k = 256 (4 bits per dimension), 8-bit codebooks,
+    one table per 32,768 weights (128 x 256): 4 + 256*2*8/32768 = 4.125 bits per value (the
+    fp16 scale adds 16/32768).  And the rows of a tall group share its table: a group of 128
+    rows decodes like 16 groups of 8 rows given copies of the table, on the same index bytes."""
+    assert oracle.bits_per_value(256, 2, 8, 32768) == 4.125
+    s = workloads.CONFIGS["mlp_up_11008x4096_k256_i8"]
+    f = VQFormat(s.out_features, s.in_features, s.k, s.index_bits, s.group_rows, s.group_cols, s.d)
+    ib, tb = oracle.canonical_sizes_i8(f)
+    assert (ib, tb) == workloads.canonical_sizes(s)
+    assert Fraction((ib + tb) * 8, s.out_features * s.in_features) == Fraction(4125, 1000) + Fraction(16, 32768)
+    rng = np.random.default_rng(44)
+    f_tall = VQFormat(256, 512, 256, 8, 128, 256, 2)
+    f_flat = VQFormat(256, 512, 256, 8, 8, 256, 2)
+    idx = rng.integers(0, 256, size=oracle.canonical_sizes(f_tall)[0], dtype=np.uint8)
+    q = rng.integers(-127, 128, size=(f_tall.n_groups, 256, 2), dtype=np.int8)
+    scale = rng.uniform(0.0005, 0.002, size=f_tall.n_groups).astype(np.float16)
+    cb = oracle.dequantise_codebooks(q, scale)
+    # tall group (gr, c) = rows 128*gr .. +127; its index bytes are those of flat groups (16*gr + j, c), j = 0..15
+    idx_flat = np.empty_like(idx)
+    cb_flat = np.empty((f_flat.n_groups, 256, 2), dtype=cb.dtype)
+    for gr in range(2):
+        for c in range(2):
+            tall = idx[(gr * 2 + c) * 16384:(gr * 2 + c + 1) * 16384]
+            for j in range(16):
+                gf = (gr * 16 + j) * 2 + c
+                idx_flat[gf * 1024:(gf + 1) * 1024] = tall[j * 1024:(j + 1) * 1024]
+                cb_flat[gf] = cb[gr * 2 + c]
+    np.testing.assert_array_equal(oracle.decode_dense(f_tall, idx, cb), oracle.decode_dense(f_flat, idx_flat, cb_flat))
+
+
 def test_scalar_format_sizes_follow_the_bpv_formula():
     """d = 1, k = 16, fp16 codebooks, 8 x 256 groups: 4 + 16*16/2048 = 4.125 bits per value
     (the total of the 1D 4.125 row of the appendix table, which reaches the same overhead with
