@@ -416,7 +416,27 @@ def main():
                                      "vq_decode_dense_then_dense_matmul_us": ms_2 * 1e3}
                     log(f"[bench] gemm B={B}: {ms_g * 1e3:.1f} us vs dense {ms_d * 1e3:.1f} us")
                 extras["gemm_11008x4096_k256"] = gemm
-                del Wd
+                # the same product on the 4.125-bit representation of this matrix (k = 256, int8 tables
+                # shared by 128 x 256 groups); timing only, random index and table bytes, scales 2^-8
+                s8 = workloads.CONFIGS["mlp_up_11008x4096_k256_i8"]
+                d8 = vqdev.desc_from_shape(s8)
+                ib8, cb8 = vq.vq_layout_bytes(d8)
+                i8 = torch.randint(0, 256, (ib8,), dtype=torch.uint8, device=dev)
+                t8 = torch.randint(0, 256, (cb8,), dtype=torch.uint8, device=dev)
+                ng8 = (s8.out_features // s8.group_rows) * (s8.in_features // 256)
+                t8[ng8 * 512:] = 0
+                t8[ng8 * 512 + 1:ng8 * 514:2] = 0x1C
+                gemm8 = {}
+                for B in (16, 256, 2048):
+                    X = torch.randn((s8.in_features, B), device=dev, dtype=torch.float32).half()
+                    Y = torch.empty((s8.out_features, B), dtype=torch.float16, device=dev)
+                    ms_g, _ = timer.run(lambda: vq.vq_gemm_batched(d8, i8, t8, X, B, B, Y, B), 40, 10)
+                    fl = 2.0 * s8.out_features * s8.in_features * B
+                    gemm8[f"B{B}"] = {"us": ms_g * 1e3, "TFLOP/s": fl / ms_g / 1e9,
+                                      "frac_mfma_f16": fl / ms_g / 1e9 / MFMA_F16_PEAK_TFLOPS}
+                    log(f"[bench] gemm on k=256 int8 tables (4.125 bpv) B={B}: {ms_g * 1e3:.1f} us")
+                extras["gemm_11008x4096_k256_int8_tables_4.125bpv"] = gemm8
+                del Wd, i8, t8
             del copies
         extras["per_shape_vq_gemv"] = per_shape
 
