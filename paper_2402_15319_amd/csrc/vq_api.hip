@@ -14,11 +14,15 @@ bool is_pow2(int v) { return v > 0 && (v & (v - 1)) == 0; }
 //   fp16 codebooks, 8 x 256 groups, k = 16 (4-bit indices) or 256 (8-bit);
 //   int8 tables with one fp16 scale per group: k = 64 (6-bit indices), groups of 8, 16 or 32
 //   rows x 256 columns (32 rows = the 8,192-weight groups of Sec. 5.1), or k = 16 with 8 x 256
-//   groups (2.125 bits per value); k = 64 also with blockwise normalisation (VQ_I8_BN);
+//   groups (2.125 bits per value), or k = 256 with groups of 64, 128 or 256 rows x 256 columns
+//   (128 rows: the 2D 4.125 row of the appendix table); k = 64 also with blockwise
+//   normalisation (VQ_I8_BN);
 //   d = 1 (scalar codebooks): k = 16 fp16 values per 8 x 256 group, 4-bit indices (4.125 bits
 //   per value, the overhead of the 1D 4.125 row of the appendix table of VQ configurations);
 //   d = 1, k = 8: 3-bit indices, 8 int8 values + scale per group of 8, 16 or 32 rows x 256 columns
 //   (32 rows: the 1D 3.125 row of that table);
+//   d = 1, k = 4: 2-bit indices, 4 int8 values + scale per row of a 256-column block (groups of
+//   1 x 256: the 1D 2.125 row of that table);
 //   d = 4: k = 256 (one index byte per 4 weights), int8 tables with a scale, groups of 64, 128 or
 //   256 rows x 256 columns (128 and 256: the 4D 2.25 and 2.125 rows of that table).
 bool is_i8(const vq_desc& d) { return d.codebook_dtype == VQ_I8 || d.codebook_dtype == VQ_I8_BN; }
