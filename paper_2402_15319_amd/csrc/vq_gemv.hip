@@ -17,9 +17,9 @@
 //     contiguous, cost-balanced run of row-blocks, possibly across several
 //     matrices, keeps x in LDS, and each of its waves has the first chunk of its
 //     next row-block loading while the last chunk of the current one is consumed.
-//   * gemv_split_kernel (few row-blocks): one workgroup per `4/splits`
-//     row-blocks; `splits` waves share a row-block and their partial sums meet
-//     in LDS in a fixed order, so the result is deterministic.
+//   * gemv_split_kernel (few row-blocks): workgroups of 4 (or 8) waves; `splits`
+//     (1, 2, 4 or 8) waves share a row-block and their partial sums meet in LDS in
+//     a fixed order, so the result is deterministic.
 #include "vq_device.h"
 #include "vq_internal.h"
 
@@ -734,17 +734,18 @@ __global__ __launch_bounds__(kStreamWaves * 64) void gemv_stream_kernel(const Ge
 // ---- split-K kernel (few row-blocks) ---------------------------------------
 // ONE: the host guarantees that no strip of the launch is longer than one chunk; the second
 // chunk buffer and its registers disappear, and more workgroups fit on a CU.
-template <int K, bool ONE>
-__global__ __launch_bounds__(256) void gemv_split_kernel(const GemvBatch batch) {
-  __shared__ __attribute__((aligned(16))) uint32_t lut_all[4][(ONE ? 1 : 2) * Chunk<K>::kLutDwords];
-  __shared__ float part[4][8];
+// WPW: waves per workgroup, 4 or 8 (8 when 8 waves share a row-block).
+template <int K, bool ONE, int WPW>
+__global__ __launch_bounds__(64 * WPW) void gemv_split_kernel(const GemvBatch batch) {
+  __shared__ __attribute__((aligned(16))) uint32_t lut_all[WPW][(ONE ? 1 : 2) * Chunk<K>::kLutDwords];
+  __shared__ float part[WPW][8];
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wg = blockIdx.x;
   const GemvProblem& P = batch.p[find_problem(batch, wg)];
   const int splits = P.splits;
-  const int rb_per_wg = 4 / splits;
+  const int rb_per_wg = WPW / splits;
   const int wg_local = wg - P.wg_begin;
   const int rb = wg_local * rb_per_wg + wave / splits;
   const int split = wave % splits;
@@ -860,8 +861,8 @@ int gemv_chunk_units(int fmt) {
 }
 
 hipError_t launch_gemv(int fmt, const GemvBatch& batch, int mode, int grid_wgs, int max_n_cb,
-                       hipStream_t s) {
-  const dim3 grid(grid_wgs), block(256);
+                       hipStream_t s, int wpw) {
+  const dim3 grid(grid_wgs), block(64 * wpw);
   if (mode == 1) {
     const size_t lds = gemv_stream_lds_bytes(fmt, max_n_cb);
     const dim3 sblock(kStreamWaves * 64);
@@ -869,11 +870,15 @@ hipError_t launch_gemv(int fmt, const GemvBatch& batch, int mode, int grid_wgs, 
     VQ_FMT_SWITCH(fmt, VQ_F)
 #undef VQ_F
   } else if (mode == 2) {
-#define VQ_F(K) hipLaunchKernelGGL((gemv_split_kernel<K, true>), grid, block, 0, s, batch)
+#define VQ_F(K)                                                                                \
+  if (wpw == 8) hipLaunchKernelGGL((gemv_split_kernel<K, true, 8>), grid, block, 0, s, batch); \
+  else hipLaunchKernelGGL((gemv_split_kernel<K, true, 4>), grid, block, 0, s, batch)
     VQ_FMT_SWITCH(fmt, VQ_F)
 #undef VQ_F
   } else {
-#define VQ_F(K) hipLaunchKernelGGL((gemv_split_kernel<K, false>), grid, block, 0, s, batch)
+#define VQ_F(K)                                                                                 \
+  if (wpw == 8) hipLaunchKernelGGL((gemv_split_kernel<K, false, 8>), grid, block, 0, s, batch); \
+  else hipLaunchKernelGGL((gemv_split_kernel<K, false, 4>), grid, block, 0, s, batch)
     VQ_FMT_SWITCH(fmt, VQ_F)
 #undef VQ_F
   }

@@ -42,7 +42,7 @@ struct GemvProblem {
   int32_t n_rb;         // row-blocks  (out / 8)
   int32_t n_cb;         // col-blocks  (in / 256)
   int32_t wg_begin;     // first work item of this problem inside the launch (see launch_gemv)
-  int32_t splits;       // waves sharing one row-block: 1, 2 or 4
+  int32_t splits;       // waves sharing one row-block: 1, 2, 4 or 8
   int32_t cost_begin;   // groups of all earlier problems of the launch (streaming kernel)
   int32_t rb_per_cb;    // 8-row blocks that share one codebook (group_rows / 8)
 };
@@ -62,9 +62,10 @@ hipError_t launch_decode(const vq_desc& d, const void* idx_dev, const void* cb_d
                          void* W, hipStream_t s);
 // mode 1: persistent streaming kernel (total_cost/cost_begin are used, grid_wgs workgroups, x
 // of up to max_n_cb col-blocks staged in LDS); mode 0: split-K kernel, wg_begin/total_wgs count
-// workgroups (= grid_wgs); mode 2: split-K kernel for launches whose strips all fit in one chunk.
+// workgroups (= grid_wgs); mode 2: split-K kernel for launches whose strips all fit in one chunk;
+// wpw: waves per workgroup of the split-K kernel (4, or 8 when 8 waves share a row-block).
 hipError_t launch_gemv(int fmt, const GemvBatch& batch, int mode, int grid_wgs,
-                       int max_n_cb, hipStream_t s);
+                       int max_n_cb, hipStream_t s, int wpw);
 // Dynamic LDS of the persistent GEMV kernel for x of up to max_n_cb col-blocks.
 size_t gemv_stream_lds_bytes(int fmt, int max_n_cb);
 // Workgroups of the persistent GEMV kernel that fit on the current device at once.
