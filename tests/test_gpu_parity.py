@@ -656,6 +656,37 @@ def test_random_shapes_every_entry_point(env, case):
     assert oracle.normwise_rel_err(Y, oracle.gemm(f, idx, cb, X)) <= TOL_F32
 
 
+WIDE_SHORT = [(_shape(24, 256 * 33, 16), False), (_shape(40, 256 * 44, 16), False), (_shape(8, 256 * 43, 16), False),
+              (_shape(24, 256 * 9, 256), False), (_shape(40, 256 * 17, 256), False), (_shape(16, 256 * 43, 256), False),
+              (_shape64(32, 256 * 43, 32), True), (_shape64(24, 256 * 21, 8), True),
+              (_shape16i8(24, 256 * 43), True), (_shape_d1(24, 256 * 19), False)]
+
+
+@pytest.mark.parametrize("f32", [False, True], ids=["y16", "y32"])
+@pytest.mark.parametrize("case", WIDE_SHORT, ids=lambda c: str(c[0]))
+def test_gemv_wide_short_matrices(env, case, f32):
+    """Few rows and many col-blocks: the split-K kernel with 8 waves per row-block, with strips of
+    one chunk and of several, with ragged and empty strips, alone and three to a launch."""
+    torch, vq, vqdev = env
+    s, is_i8 = case
+    seed = 9100 + s.in_features // 256 + s.k
+    desc, idx, cb, idx_d, cb_d = (_setup_i8 if is_i8 else _setup)(env, s, seed)
+    f = _fmt(s)
+    x = workloads.make_x(s.in_features, seed)
+    ref = oracle.gemv(f, idx, cb, x)
+    tol = TOL_F32 if f32 else TOL_F16
+    assert oracle.normwise_rel_err(_gpu_gemv(env, desc, idx_d, cb_d, x, f32), ref) <= tol
+    # the same matrix three times in one launch (q/k/v-like), each with its own output
+    x_d = vqdev.to_device_bytes(x)
+    ys = [torch.full((s.out_features,), float("nan"), dtype=torch.float32 if f32 else torch.float16, device="cuda:0")
+          for _ in range(3)]
+    vq.vq_gemv_multi(vq.GemvMultiArgs([desc] * 3, [idx_d] * 3, [cb_d] * 3, [x_d] * 3, ys),
+                     y_dtype=vq.VQ_F32 if f32 else vq.VQ_F16)
+    torch.cuda.synchronize()
+    for y in ys:
+        assert oracle.normwise_rel_err(y.cpu().numpy().astype(np.float64), ref) <= tol
+
+
 # ---------------------------------------------------------------- blockwise normalisation (k = 64, int8 tables)
 def _shape_bn(o, i, rows=32):
     return workloads.VQShape(o, i, 64, 6, rows, 256, 2, True, True)
