@@ -28,11 +28,13 @@ typedef _Float16 h8_t __attribute__((ext_vector_type(8)));
 
 constexpr int WS = 256;   // LDS row stride of the decoded W tile, in halfs (no padding)
 
-// The W tile is stored without padding; 16-byte chunk q of row m lives at chunk q ^ (m & 7),
-// so the 8 lanes of one LDS pass of a 128-bit operand read (rows m..m+7, same k) and the
-// lanes of a decode write (same row, consecutive columns) all hit distinct banks.
+// The W tile is stored without padding; 16-byte chunk q of row m lives at chunk q ^ (m & 15),
+// so the 16 lanes of one LDS pass of a 128-bit operand read (rows m..m+15, same k: 256 bytes,
+// all 64 banks) and the lanes of a decode write (same row, consecutive columns) all hit
+// distinct banks.  (With q ^ (m & 7) rows m and m + 8 shared their banks and every operand
+// read took two passes: 8.6 against 4.7 clocks per wave-wide read in a micro-benchmark.)
 __device__ __forceinline__ int wt_half_index(int m, int k) {   // k in halfs
-  return m * WS + ((((k >> 3) ^ (m & 7)) << 3) | (k & 7));
+  return m * WS + ((((k >> 3) ^ (m & 15)) << 3) | (k & 7));
 }
 
 // K is the kernel format tag: 16 / 256 (fp16 codebooks), 64 (6-bit indices, int8 tables with a
