@@ -308,13 +308,15 @@ __global__ __launch_bounds__(256 * WM, WM == 1 ? 2 : 1) void gemm_kernel(const u
                                                    const uint32_t* __restrict__ cb,
                                                    const uint16_t* __restrict__ X, int B, int ldx,
                                                    void* __restrict__ Y, int ldy, int y_f32,
-                                                   int n_rb, int n_cb, int n_tiles_n, int rpc) {
-  static_assert(NT == 128 || NT == 256, "column tile");
+                                                   int n_rb, int n_cb, int n_tiles_n, int rpc,
+                                                   int rb0, int rb_end) {
+  // the launch covers row-blocks [rb0, rb_end) of the matrix's n_rb; tile rows count from rb0
+  static_assert(NT == 128 || NT == 256 || (NT == 512 && WM == 2), "column tile");
   constexpr int MT = 32 * RBW * WM;
   constexpr int KS = 8192 / NT;                  // k per X sub-tile: 64 or 32
   constexpr int NSUB = 256 / KS;                 // sub-steps per col-block: 4 or 8
   constexpr int NB = NT / 128;                   // 32-column accumulator tiles per wave
-  constexpr int D = 4;                           // X pieces in flight per thread (sub-tiles ahead)
+  constexpr int D = NT == 512 ? 2 : 4;           // X pieces in flight per thread (sub-tiles ahead; registers are short at 512 columns)
   static_assert(NSUB % D == 0, "ring slot must be a compile-time constant");
   __shared__ __attribute__((aligned(16))) uint16_t Wt[MT * WS];
   __shared__ __attribute__((aligned(16))) uint32_t Xs_all[2][4096];     // [KS][NT] halfs each
@@ -362,8 +364,8 @@ __global__ __launch_bounds__(256 * WM, WM == 1 ? 2 : 1) void gemm_kernel(const u
   bool rb_ok[RBW];
 #pragma unroll
   for (int a = 0; a < RBW; ++a) {
-    rbs[a] = (long long)mt * (4 * RBW * WM) + wave * RBW + a;
-    rb_ok[a] = rbs[a] < n_rb;
+    rbs[a] = rb0 + (long long)mt * (4 * RBW * WM) + wave * RBW + a;
+    rb_ok[a] = rbs[a] < rb_end;
     load_group<K>(g[a], idx, cb, rb_ok[a] ? rbs[a] : 0, 0, n_cb, lane, n_rb, rpc);
   }
   XRows ring[D];   // slot t % D holds sub-tile t + 1 when sub-step t starts
@@ -437,8 +439,8 @@ __global__ __launch_bounds__(256 * WM, WM == 1 ? 2 : 1) void gemm_kernel(const u
       for (int a = 0; a < RBW; ++a)
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-          const int row = mt * MT + wr * 32 * RBW + 32 * a + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
-          if (row < n_rb * 8) {
+          const int row = rb0 * 8 + mt * MT + wr * 32 * RBW + 32 * a + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
+          if (row < rb_end * 8) {
             const size_t o = (size_t)row * ldy + n;
             if (y_f32) reinterpret_cast<float*>(Y)[o] = acc[a][b][i];
             else reinterpret_cast<_Float16*>(Y)[o] = (_Float16)acc[a][b][i];
@@ -724,15 +726,52 @@ hipError_t launch_small(const vq_desc& d, const void* idx_dev, const void* cb_de
   return hipGetLastError();
 }
 
+// Row-blocks [rb0, rb_end) of the matrix (rb_end < 0: all of it).
 template <int K, int RBW, int NT, int WM = 1>
 hipError_t launch_one(const vq_desc& d, const void* idx_dev, const void* cb_dev, const void* X, int B,
-                      int ldx, void* Y, int ldy, int y_f32, hipStream_t s) {
+                      int ldx, void* Y, int ldy, int y_f32, hipStream_t s, int rb0 = 0, int rb_end = -1) {
   const int n_rb = d.out_features / kGroupRows, n_cb = d.in_features / kGroupCols;
-  const int tiles_m = (n_rb + 4 * RBW * WM - 1) / (4 * RBW * WM), tiles_n = (B + NT - 1) / NT;
+  if (rb_end < 0) rb_end = n_rb;
+  const int tiles_m = (rb_end - rb0 + 4 * RBW * WM - 1) / (4 * RBW * WM), tiles_n = (B + NT - 1) / NT;
   hipLaunchKernelGGL((gemm_kernel<K, RBW, NT, WM>), dim3((unsigned)(tiles_m * tiles_n)), dim3(256 * WM), 0, s,
                      (const uint8_t*)idx_dev, (const uint32_t*)cb_dev, (const uint16_t*)X, B, ldx, Y,
-                     ldy, y_f32, n_rb, n_cb, tiles_n, d.group_rows / kGroupRows);
+                     ldy, y_f32, n_rb, n_cb, tiles_n, d.group_rows / kGroupRows, rb0, rb_end);
   return hipGetLastError();
+}
+
+// Large batches on the 128-row tiles: 128 x 512 tiles decode W once per 512 batch columns instead
+// of once per 256 and take 1.73 times as long as 128 x 256 tiles for twice the area, but a launch
+// pays for whole rounds of 256 workgroups.  So the first m_a tile rows run with 512-column tiles
+// and the rest with 256-column tiles in a second launch, m_a chosen so that both launches fill
+// their rounds best (m_a = 0: 256-column tiles only).  Same units as launch_gemm's estimates.
+template <int K>
+hipError_t launch_wide(const vq_desc& d, const void* idx_dev, const void* cb_dev, const void* X, int B,
+                       int ldx, void* Y, int ldy, int y_f32, hipStream_t s) {
+  // the 512-column tile is built for the formats with fp16 codebooks only (128 accumulator
+  // registers per wave: k = 16 just fits the 256 registers, k = 256 spills four of them outside
+  // the inner loop); the formats with more decode state keep 256 columns
+  if constexpr (K != 16 && K != 256) {
+    return launch_one<K, 2, 256, 2>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);
+  } else {
+  const int n_rb = d.out_features / kGroupRows;
+  const long long rows128 = (n_rb + 15) / 16, cols256 = (B + 255) / 256, cols512 = (B + 511) / 512;
+  int m_a = 0;
+  double best = 79.0 * (double)((rows128 * cols256 + 255) / 256);
+  for (long long m = 1; m <= rows128; ++m) {
+    const long long rest = rows128 - m;
+    const double t = 137.0 * (double)((m * cols512 + 255) / 256) +
+                     (rest > 0 ? 3.0 + 79.0 * (double)((rest * cols256 + 255) / 256) : 0.0);
+    if (t < best) {
+      best = t;
+      m_a = (int)m;
+    }
+  }
+  if (m_a == 0) return launch_one<K, 2, 256, 2>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);
+  const int rb_split = m_a * 16 < n_rb ? m_a * 16 : n_rb;
+  hipError_t e = launch_one<K, 2, 512, 2>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s, 0, rb_split);
+  if (e != hipSuccess || rb_split == n_rb) return e;
+  return launch_one<K, 2, 256, 2>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s, rb_split, n_rb);
+  }
 }
 
 }  // namespace
@@ -774,7 +813,7 @@ hipError_t launch_gemm(const vq_desc& d, const void* idx_dev, const void* cb_dev
     if (best == 1) return launch_one<K, 2, 256>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s); \
     if (best == 2)                                                                                \
       return launch_one<K, 2, 128, 2>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);           \
-    return launch_one<K, 2, 256, 2>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);             \
+    return launch_wide<K>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);                       \
   }
   const int fmt = format_tag(d);
   if (fmt == 64) VQ_GEMM_DISPATCH(64)

@@ -342,6 +342,27 @@ def test_gemm_config5(env, B):
     assert err <= TOL_F16
 
 
+@pytest.mark.parametrize("f32", [False, True], ids=["y16", "y32"])
+@pytest.mark.parametrize("case", [(_shape(9000, 512, 16), 2050), (_shape(9000, 512, 256), 2050),
+                                  (_shape(4096, 256, 256), 4096), (_shape(11000, 256, 16), 1032)],
+                         ids=lambda c: f"{c[0]}-B{c[1]}")
+def test_gemm_wide_tiles(env, case, f32):
+    """Large batches on tall matrices: 128 x 512 tiles on the first tile rows and 128 x 256 tiles on
+    the rest in a second launch (or 512-column tiles alone), with a ragged last tile row and ragged
+    last columns; the whole Y against the oracle, and nothing written outside it."""
+    s, B = case
+    desc, idx, cb, idx_d, cb_d = _setup(env, s, 4500 + B)
+    X = workloads.make_X(s.in_features, B, 4500 + B)
+    Y = _gpu_gemm(env, desc, idx_d, cb_d, X, f32, pad=8)
+    ref = oracle.gemm(_fmt(s), idx, cb, X)
+    assert oracle.normwise_rel_err(Y, ref) <= (TOL_F32 if f32 else TOL_F16)
+    # per tile-sized block too, so that one wrong tile cannot hide in the norm of the whole
+    for r0 in range(0, s.out_features, 1024):
+        for c0 in range(0, B, 512):
+            blk = (slice(r0, r0 + 1024), slice(c0, c0 + 512))
+            assert oracle.normwise_rel_err(Y[blk], ref[blk]) <= (TOL_F32 if f32 else TOL_F16)
+
+
 def test_entry_points_replay_in_a_hip_graph(env):
     """Every hot-path entry point captured in one HIP graph (they allocate nothing and only
     enqueue kernels on the given stream); each replay, with eager work in between, must
