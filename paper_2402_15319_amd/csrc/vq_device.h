@@ -233,6 +233,70 @@ __device__ __forceinline__ void k64_group(uint32_t d0, uint32_t d1, uint32_t d2,
 #undef VQ_BF6_RD
 #undef VQ_DOT
 
+// k = 64 inner block with blockwise normalisation, hand-scheduled like k64_group: per row the
+// two centroid pairs and the lane's block scale (a dword with the fp16 level in both halves,
+// selected by the row's 4-bit code in cw) are looked up, both pairs are multiplied by the scale
+// (v_pk_mul_f16: one rounding, exactly the decoded weight) and go into the dot products.  The
+// lookups of row r + 4 are issued as soon as row r has been consumed, so 9 to 12 LDS reads are
+// always in flight.  OFF: byte offset of the col-block's table, LOFF: of its 16 level dwords.
+#define VQ_BN_RD(R, W, BIT, WIDTH, OFF)                  \
+  "v_bfe_u32 " R ", " W ", " #BIT ", " #WIDTH "\n"       \
+  "v_lshl_add_u32 " R ", " R ", 2, %[base]\n"            \
+  "ds_read_b32 " R ", " R " offset:" OFF "\n"
+#define VQ_BN_ROW(RA, WA, BA, RB, WB, BB, RS, ROW)                                       \
+  VQ_BN_RD(RA, WA, BA, 6, "%[off]") VQ_BN_RD(RB, WB, BB, 6, "%[off]")                    \
+  "v_bfe_u32 " RS ", %[cw], 4*" #ROW ", 4\n"                                             \
+  "v_lshl_add_u32 " RS ", " RS ", 2, %[base]\n"                                          \
+  "ds_read_b32 " RS ", " RS " offset:%[loff]\n"
+#define VQ_BN_USE(ACC, RA, RB, RS)                       \
+  "v_pk_mul_f16 " RA ", " RA ", " RS "\n"                \
+  "v_pk_mul_f16 " RB ", " RB ", " RS "\n"                \
+  "v_dot2c_f32_f16 " ACC ", " RA ", %[x0]\n"             \
+  "v_dot2c_f32_f16 " ACC ", " RB ", %[x1]\n"
+
+template <int OFF, int LOFF>
+__device__ __forceinline__ void k64_group_bn(uint32_t d0, uint32_t d1, uint32_t d2, uint32_t t5,
+                                             uint32_t t10, uint32_t cw, uint32_t base, uint32_t x0,
+                                             uint32_t x1, float (&acc)[8]) {
+  uint32_t r0, r1, r2, r3, r4, r5, r6, r7, r8, r9, r10, r11;
+  asm volatile(
+      VQ_BN_ROW("%[r0]", "%[d0]", 0, "%[r1]", "%[d0]", 6, "%[r2]", 0)
+      VQ_BN_ROW("%[r3]", "%[d0]", 12, "%[r4]", "%[d0]", 18, "%[r5]", 1)
+      VQ_BN_ROW("%[r6]", "%[d0]", 24, "%[r7]", "%[t5]", 0, "%[r8]", 2)
+      VQ_BN_ROW("%[r9]", "%[d1]", 4, "%[r10]", "%[d1]", 10, "%[r11]", 3)
+      "s_waitcnt lgkmcnt(9)\n"
+      VQ_BN_USE("%[a0]", "%[r0]", "%[r1]", "%[r2]")
+      VQ_BN_ROW("%[r0]", "%[d1]", 16, "%[r1]", "%[d1]", 22, "%[r2]", 4)
+      "s_waitcnt lgkmcnt(9)\n"
+      VQ_BN_USE("%[a1]", "%[r3]", "%[r4]", "%[r5]")
+      VQ_BN_ROW("%[r3]", "%[t10]", 0, "%[r4]", "%[d2]", 2, "%[r5]", 5)
+      "s_waitcnt lgkmcnt(9)\n"
+      VQ_BN_USE("%[a2]", "%[r6]", "%[r7]", "%[r8]")
+      VQ_BN_ROW("%[r6]", "%[d2]", 8, "%[r7]", "%[d2]", 14, "%[r8]", 6)
+      "s_waitcnt lgkmcnt(9)\n"
+      VQ_BN_USE("%[a3]", "%[r9]", "%[r10]", "%[r11]")
+      VQ_BN_ROW("%[r9]", "%[d2]", 20, "%[r10]", "%[d2]", 26, "%[r11]", 7)
+      "s_waitcnt lgkmcnt(9)\n"
+      VQ_BN_USE("%[a4]", "%[r0]", "%[r1]", "%[r2]")
+      "s_waitcnt lgkmcnt(6)\n"
+      VQ_BN_USE("%[a5]", "%[r3]", "%[r4]", "%[r5]")
+      "s_waitcnt lgkmcnt(3)\n"
+      VQ_BN_USE("%[a6]", "%[r6]", "%[r7]", "%[r8]")
+      "s_waitcnt lgkmcnt(0)\n"
+      VQ_BN_USE("%[a7]", "%[r9]", "%[r10]", "%[r11]")
+      : [a0] "+v"(acc[0]), [a1] "+v"(acc[1]), [a2] "+v"(acc[2]), [a3] "+v"(acc[3]),
+        [a4] "+v"(acc[4]), [a5] "+v"(acc[5]), [a6] "+v"(acc[6]), [a7] "+v"(acc[7]),
+        [r0] "=&v"(r0), [r1] "=&v"(r1), [r2] "=&v"(r2), [r3] "=&v"(r3), [r4] "=&v"(r4),
+        [r5] "=&v"(r5), [r6] "=&v"(r6), [r7] "=&v"(r7), [r8] "=&v"(r8), [r9] "=&v"(r9),
+        [r10] "=&v"(r10), [r11] "=&v"(r11)
+      : [d0] "v"(d0), [d1] "v"(d1), [d2] "v"(d2), [t5] "v"(t5), [t10] "v"(t10), [cw] "v"(cw),
+        [base] "s"(base), [x0] "v"(x0), [x1] "v"(x1), [off] "n"(OFF), [loff] "n"(LOFF)
+      : "memory");
+}
+#undef VQ_BN_RD
+#undef VQ_BN_ROW
+#undef VQ_BN_USE
+
 // ---- 6-bit / int8-table device layout (k = 64) -------------------------------------------
 // Indices: per (8-row block, quad of 4 col-blocks) three planes of 1 KB; the lane's 48 bytes
 // are planes' bytes [16p, 16p+16), and col-block j of the quad is its dwords 3j..3j+2 (the

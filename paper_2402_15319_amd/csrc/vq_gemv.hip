@@ -586,13 +586,20 @@ template <int MODE> struct ChunkS64T {
     const uint32_t d[12] = {w[0].x, w[0].y, w[0].z, w[0].w, w[1].x, w[1].y,
                             w[1].z, w[1].w, w[2].x, w[2].y, w[2].z, w[2].w};
     if constexpr (BN) {
-      const uint32_t cws[4] = {cw.x, cw.y, cw.z, cw.w};
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const uint2 xj = xp[64 * j];
-        k64_group_scaled(d[3 * j], d[3 * j + 1], d[3 * j + 2], cws[j], lut + 64 * j, lut + 256 + 16 * j,
-                         xj.x, xj.y, acc);
-      }
+      uint2 x0 = xp[0], x1 = xp[64];
+#define VQ_G64N(J, X, CW)                                                                      \
+      k64_group_bn<256 * J, 1024 + 64 * J>(d[3 * J], d[3 * J + 1], d[3 * J + 2],               \
+                         __builtin_amdgcn_alignbit(d[3 * J + 1], d[3 * J], 30),                \
+                         __builtin_amdgcn_alignbit(d[3 * J + 2], d[3 * J + 1], 28), CW, base,  \
+                         X.x, X.y, acc);
+      VQ_G64N(0, x0, cw.x)
+      x0 = xp[128];
+      VQ_G64N(1, x1, cw.y)
+      x1 = xp[192];
+      VQ_G64N(2, x0, cw.z)
+      VQ_G64N(3, x1, cw.w)
+#undef VQ_G64N
+      acc_hazard_fence();
     } else {
       uint2 x0 = xp[0], x1 = xp[64];
 #define VQ_G64(J, X)                                                                           \
