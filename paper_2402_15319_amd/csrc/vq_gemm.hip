@@ -747,10 +747,10 @@ hipError_t launch_one(const vq_desc& d, const void* idx_dev, const void* cb_dev,
 template <int K>
 hipError_t launch_wide(const vq_desc& d, const void* idx_dev, const void* cb_dev, const void* X, int B,
                        int ldx, void* Y, int ldy, int y_f32, hipStream_t s) {
-  // the 512-column tile is built for the formats with fp16 codebooks only (128 accumulator
-  // registers per wave: k = 16 just fits the 256 registers, k = 256 spills four of them outside
-  // the inner loop); the formats with more decode state keep 256 columns
-  if constexpr (K != 16 && K != 256) {
+  // the 512-column tile needs 128 accumulator registers per wave: most formats fit the 256
+  // registers or spill up to four of them; the block-normalised one would spill ten and keeps
+  // 256 columns
+  if constexpr (K == kFmtK64BN) {
     return launch_one<K, 2, 256, 2>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);
   } else {
   const int n_rb = d.out_features / kGroupRows;

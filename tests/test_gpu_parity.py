@@ -1068,3 +1068,19 @@ def test_newer_kernels_replay_in_a_hip_graph(env):
         torch.cuda.synchronize()
         for a, b in zip(captured, want):
             np.testing.assert_array_equal(a.cpu().numpy().view(np.uint8), b.view(np.uint8))
+
+
+@pytest.mark.parametrize("case", [(_shape64(9024, 512, 32), True), (_shape16i8(9000, 512), True),
+                                  (_shape_d1(9000, 512), False)], ids=lambda c: str(c[0]))
+def test_gemm_wide_tiles_other_formats(env, case):
+    """The same two-launch path on formats with int8 tables and scalar codebooks, B = 2050."""
+    s, is_i8 = case
+    B = 2050
+    desc, idx, cb, idx_d, cb_d = (_setup_i8 if is_i8 else _setup)(env, s, 4700)
+    X = workloads.make_X(s.in_features, B, 4700)
+    Y = _gpu_gemm(env, desc, idx_d, cb_d, X, True, pad=8)
+    ref = oracle.gemm(_fmt(s), idx, cb, X)
+    for r0 in range(0, s.out_features, 1024):
+        for c0 in range(0, B, 512):
+            blk = (slice(r0, r0 + 1024), slice(c0, c0 + 512))
+            assert oracle.normwise_rel_err(Y[blk], ref[blk]) <= TOL_F32
