@@ -717,7 +717,9 @@ __global__ __launch_bounds__(kStreamWaves * 64) void gemv_stream_kernel(const Ge
     } while (0)
 #define VQ_CONSUME(BUF, LUT, BASE, LAST, RB)                                     \
     do {                                                                         \
+      __builtin_amdgcn_s_setprio(1);   /* lookups and dot products ahead of other waves' load set-up */ \
       BUF.consume(LUT, BASE, x_s, lane, acc);                                    \
+      __builtin_amdgcn_s_setprio(0);                                             \
       if (LAST) {                                                                \
         const float v = wave_reduce8(acc, lane);                                 \
         store_rows(y, batch.y_f32, RB, lane, v);                                 \
