@@ -294,6 +294,13 @@ __device__ __forceinline__ void store_xrows(const XRows& p, char* dst) {
 #pragma unroll
   for (int j = 0; j < PASSES; ++j) *reinterpret_cast<u32x4_t*>(dst + j * RPP * NT * 2) = p.r[j];
 }
+// 8 consecutive k of the lane's column from two 4-row tiles at lo and hi.
+__device__ __forceinline__ h8_t read_x_operand2(const char* lo_src, const char* hi_src) {
+  typedef s4_t __attribute__((address_space(3))) * lds_s4_ptr;
+  const s4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4_ptr)(lo_src));
+  const s4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4_ptr)(hi_src));
+  return __builtin_bit_cast(h8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+}
 // 8 consecutive k (two 4-row tiles, 4 * NT * 2 bytes apart) of the lane's column.
 template <int NT>
 __device__ __forceinline__ h8_t read_x_operand(const char* src) {
@@ -493,10 +500,16 @@ __global__ __launch_bounds__(256, 2) void gemm_tiny_kernel(const uint8_t* __rest
   const int xh = lane & 1;
   const bool x_ok = n0 + 8 * xh + 8 <= ldx;
   const size_t x_lane = (size_t)(lane >> 1) * ldx + (x_ok ? n0 + 8 * xh : 0);
-  const int xs_off = (lane >> 1) * 32 + xh * 16;                 // bytes inside Xt
+  // Inside a pass of 32 rows, row r sits at position r ^ 4 if r & 8 (rows 8..11 and 12..15 trade
+  // places): the LDS serves a 64-bit read 32 lanes at a time, i.e. the 4 x 16 tiles of two
+  // 16-lane blocks, whose rows are 8 apart (256 bytes: the same banks) without the swap.
+  const int xs_row = lane >> 1;
+  const int xs_off = (xs_row ^ ((xs_row & 8) >> 1)) * 32 + xh * 16;   // bytes inside Xt
   // operand role (ds_read_b64_tr_b16): lane i of a 16-lane block addresses row i / 4, fragment
-  // i % 4 of a 4 x 16 tile and receives column i
-  const int xr_off = (8 * (lane >> 4) + ((lane & 15) >> 2)) * 32 + (lane & 3) * 8;
+  // i % 4 of a 4 x 16 tile and receives column i; rows 8q + kq (first read) and 8q + kq + 4
+  const int xr_base = (8 * (lane >> 4) + ((lane & 15) >> 2)) * 32 + (lane & 3) * 8;
+  const int xr_swap = ((lane >> 4) & 1) * 128;                  // odd q: the two reads trade places
+  const int xr_lo = xr_base + xr_swap, xr_hi = xr_base + 128 - xr_swap;
   f4v_t acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
   GroupRegs<K> g[2][2];
   u32x4_t xr[2][8];
@@ -523,7 +536,8 @@ __global__ __launch_bounds__(256, 2) void gemm_tiny_kernel(const uint8_t* __rest
       _Pragma("unroll") for (int kk = 0; kk < 4; ++kk) {                               \
         const int k0 = 32 * (4 * hf + kk) + 8 * (lane >> 4);                           \
         const h8_t av = *reinterpret_cast<const h8_t*>(Wt + wt_half_index(lane & 15, k0)); \
-        const h8_t bv = read_x_operand<16>(reinterpret_cast<const char*>(Xt) + 1024 * kk + xr_off); \
+        const h8_t bv = read_x_operand2(reinterpret_cast<const char*>(Xt) + 1024 * kk + xr_lo,  \
+                                        reinterpret_cast<const char*>(Xt) + 1024 * kk + xr_hi); \
         if (kk & 1) acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bv, acc1, 0, 0, 0); \
         else acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bv, acc0, 0, 0, 0);     \
       }                                                                                \
