@@ -793,8 +793,9 @@ hipError_t launch_wide(const vq_desc& d, const void* idx_dev, const void* cb_dev
 hipError_t launch_gemm(const vq_desc& d, const void* idx_dev, const void* cb_dev, const void* X,
                        int B, int ldx, void* Y, int ldy, int y_f32, hipStream_t s) {
   // B <= 16: 16 x 16 tiles, barrier-free (gemm_tiny_kernel).  It re-decodes W once per 16
-  // columns, which still pays up to 64 columns when the matrix is too short to fill the CUs
-  // with the 32-row tiles of the other kernels.  Then 32 x 32 tiles (gemm_small_kernel,
+  // columns, which still pays at 32 columns when the matrix is too short to fill the CUs
+  // with the 32-row tiles of the other kernels (4096 x 4096 at B = 48 / 64: 15.0 / 22.5 us with
+  // it, 13.7 / 13.9 us with the 32 x 32 tiles).  Then 32 x 32 tiles (gemm_small_kernel,
   // bandwidth-bound) while they are few enough to run in about one wave of workgroups, then
   // gemm_kernel with 32 x 128 tiles while those fit the CUs once, and beyond that the cheapest
   // of four tilings by a small cost model: 64 x 128 and 64 x 256 (4 waves, two workgroups per
@@ -804,7 +805,7 @@ hipError_t launch_gemm(const vq_desc& d, const void* idx_dev, const void* cb_dev
   // 11008-row matrices, B = 512..4096; only their ratios matter.
   const int n_rb = d.out_features / kGroupRows;
   const bool short_matrix = n_rb < 1024;
-  const bool tiny = B <= 16 || (B <= 64 && short_matrix);
+  const bool tiny = B <= 16 || (B <= 32 && short_matrix);
   const long long tiles_small = (long long)((n_rb + 3) / 4) * ((B + 31) / 32);
   const long long rows64 = (n_rb + 7) / 8, rows128 = (n_rb + 15) / 16;
   const long long cols128 = (B + 127) / 128, cols256 = (B + 255) / 256;
