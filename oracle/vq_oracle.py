@@ -26,8 +26,8 @@ oracle is that definition written out:
 
     W[r, c + t] = C_g[ I_g[v] ][t],   y = W x  (fp64 accumulate).
 
-Canonical byte order (the paper only says indices are "packed tightly";
-these are the readings this build fixes):
+Canonical byte order (Sec. 3.2 says only that indices are stored without
+padding bits between them; these are the readings this build fixes):
 
 * groups tile W row-block-major: g = (r // gr) * (in // gc) + (c // gc);
 * inside a group vectors are row-major: v = (r % gr) * (gc // d) + (c % gc) // d;
@@ -44,7 +44,9 @@ normalisation of the appendix: apply_block_scales, canonical_sizes_bn.
 Parity pins (tests/test_oracle_*.py): hand-written tiny cases stored under
 tests/golden/, a coordinate-revealing codebook, one-centroid and
 identity-like codebooks, relabelling invariance, the bpv closed form,
-unit-vector probes and a per-element scalar walk.
+unit-vector probes and a per-element scalar walk; hand-written hex dumps of the
+int8-table buffers for read_tables_i8 / read_tables_bn; hand-worked vectors and a
+planted wrong row for normwise_rel_err (the pass criterion of the product tests).
 """
 from __future__ import annotations
 
@@ -110,7 +112,7 @@ def unpack_indices(f: VQFormat, idx: np.ndarray) -> np.ndarray:
 
     Each group's bytes are expanded to a little-endian bit stream and cut into
     consecutive fields of ``index_bits`` bits (Sec. 2.1: one index of
-    ceil(log2 k) bits per vector; Sec. 3.2: packed tightly).
+    ceil(log2 k) bits per vector; Sec. 3.2: no padding between indices).
     """
     idx = np.ascontiguousarray(idx, dtype=np.uint8)
     if idx.size != f.n_groups * f.group_index_bytes:
@@ -208,6 +210,62 @@ def canonical_sizes_i8(f: VQFormat) -> tuple[int, int]:
     return f.n_groups * f.group_index_bytes, (q_bytes + 15) // 16 * 16 + 2 * f.n_groups
 
 
+def read_tables_i8(f: VQFormat, buf: np.ndarray) -> tuple[np.ndarray, np.ndarray]:
+    """Canonical VQ_I8 table buffer (raw bytes) -> (q int8[n_groups, k, d], scale fp16[n_groups]).
+
+    Sec. 3.1 stores a group as (indices, lookup table, scale).  Byte order of this build's
+    interchange buffer: the tables of all groups first, group after group, inside a group
+    centroid after centroid, inside a centroid coordinate after coordinate, one signed byte
+    each; zero bytes up to the next multiple of 16; then one little-endian fp16 scale per
+    group in the same group order.
+    """
+    buf = np.ascontiguousarray(buf, dtype=np.uint8).reshape(-1)
+    n_q = f.n_groups * f.k * f.d
+    off = (n_q + 15) // 16 * 16
+    if buf.size != off + 2 * f.n_groups:
+        raise ValueError("table buffer has the wrong size")
+    if np.any(buf[n_q:off]):
+        raise ValueError("padding bytes must be zero")
+    q = buf[:n_q].view(np.int8).reshape(f.n_groups, f.k, f.d).copy()
+    sb = buf[off:].reshape(f.n_groups, 2).astype(np.uint16)
+    scale = (sb[:, 0] | (sb[:, 1] << 8)).astype(np.uint16).view(np.float16)
+    return q, scale
+
+
+def read_tables_bn(f: VQFormat, buf: np.ndarray, block: int = 32):
+    """Canonical VQ_I8_BN table buffer (raw bytes) -> (q, scale, levels fp16[n_groups, 16],
+    codes uint8[out, in / block]).
+
+    Byte order: the int8 tables as in read_tables_i8, zero-padded to a multiple of 16 bytes;
+    the fp16 scales, zero-padded to a multiple of 16 bytes; 16 little-endian fp16 levels per
+    group, group after group; then the 4-bit block codes of the whole matrix (appendix
+    "Blockwise data normalization": one code per sub-row block), row after row, block after
+    block along a row, two per byte: the block with the even index in the LOW nibble.
+    """
+    buf = np.ascontiguousarray(buf, dtype=np.uint8).reshape(-1)
+    n_q = f.n_groups * f.k * f.d
+    q_end = (n_q + 15) // 16 * 16
+    s_end = q_end + (2 * f.n_groups + 15) // 16 * 16
+    l_end = s_end + 32 * f.n_groups
+    n_blk = f.in_features // block
+    if f.group_cols % block or n_blk % 2:
+        raise ValueError("blocks must tile a group's columns and pair up into bytes")
+    if buf.size != l_end + f.out_features * n_blk // 2:
+        raise ValueError("table buffer has the wrong size")
+    if np.any(buf[n_q:q_end]) or np.any(buf[q_end + 2 * f.n_groups:s_end]):
+        raise ValueError("padding bytes must be zero")
+    q = buf[:n_q].view(np.int8).reshape(f.n_groups, f.k, f.d).copy()
+    sb = buf[q_end:q_end + 2 * f.n_groups].reshape(f.n_groups, 2).astype(np.uint16)
+    scale = (sb[:, 0] | (sb[:, 1] << 8)).astype(np.uint16).view(np.float16)
+    lb = buf[s_end:l_end].reshape(f.n_groups, 16, 2).astype(np.uint16)
+    levels = (lb[..., 0] | (lb[..., 1] << 8)).astype(np.uint16).view(np.float16)
+    cbytes = buf[l_end:].reshape(f.out_features, n_blk // 2)
+    codes = np.empty((f.out_features, n_blk), dtype=np.uint8)
+    codes[:, 0::2] = cbytes & 0x0F
+    codes[:, 1::2] = cbytes >> 4
+    return q, scale, levels, codes
+
+
 def normwise_rel_err(y, y_ref) -> float:
     """||y - y_ref||_2 / ||y_ref||_2 (Frobenius for matrices), computed in fp64."""
     y = np.asarray(y, dtype=np.float64).ravel()
@@ -233,9 +291,11 @@ def normwise_rel_err(y, y_ref) -> float:
 # pseudoinverse of a zero diagonal entry is zero, so a coordinate no vector votes for (an empty
 # cluster, or weights that are all zero) becomes 0.
 #
-# Precision: the assignment is a decision taken in floating point, so it is taken in the
-# arithmetic of the GPU path, IEEE binary32 with every operation rounded separately and in this
-# order:  e_t = x_t - c_t;  q_t = e_t * e_t;  p_t = h_t * q_t;  dist = (p_0 + p_1) + ... ;
+# Precision: the assignment is a decision taken in floating point, and the paper does not fix
+# the arithmetic.  The quantiser works on binary32 weights, so the reading taken here is the
+# plainest binary32 evaluation of the printed expression: IEEE binary32, no fused operations,
+# every operation rounded separately, in this order:
+#   e_t = x_t - c_t;  q_t = e_t * e_t;  p_t = h_t * q_t;  dist = (p_0 + p_1) + ... ;
 # the smallest distance wins and the lowest m wins a tie.  The M-step has a plain definition
 # and is evaluated in binary64.
 def em_assign(f: VQFormat, W: np.ndarray, hdiag: np.ndarray, cb: np.ndarray) -> np.ndarray:
@@ -325,8 +385,8 @@ def em_objective(f: VQFormat, W: np.ndarray, hdiag: np.ndarray, cb: np.ndarray,
 # `block` consecutive weights inside a group has a 4-bit code, the code selects one of the
 # group's 16 block scales (the appendix quantises the scales in the log domain, level j being
 # 2^(a*j + s_0) with a shared by the group; here the 16 levels themselves are stored, as fp16,
-# which contains that parameterisation and keeps the reconstruction exact to state), and "the
-# inverse scaling is applied at VQ decoding": the decoded weight is the centroid value times its
+# which contains that parameterisation and keeps the reconstruction exact to state), and the
+# scaling is undone when a weight is decoded: the decoded weight is the centroid value times its
 # block's scale.  On this path the native type is fp16: the product of the two fp16 values is
 # taken exactly and rounded once to fp16 (nearest even).
 def apply_block_scales(f: VQFormat, W_bits: np.ndarray, levels: np.ndarray, codes: np.ndarray,

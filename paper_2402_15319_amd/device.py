@@ -4,7 +4,7 @@ from __future__ import annotations
 import numpy as np
 import torch
 
-from . import VQDesc, VQ_F16, VQ_I8, VQ_I8_BN, make_desc, vq_canonical_bytes, vq_layout_bytes, vq_pack_layout
+from . import VQDesc, VQ_F16, VQ_I8, VQ_I8_BN, make_desc, vq_layout_bytes, vq_pack_layout
 
 
 def desc_from_shape(s) -> VQDesc:
@@ -14,44 +14,6 @@ def desc_from_shape(s) -> VQDesc:
         dtype = VQ_I8_BN if getattr(s, "block_norm", False) else VQ_I8
     return make_desc(s.out_features, s.in_features, s.k, s.index_bits,
                      s.group_rows, s.group_cols, s.d, dtype)
-
-
-def canonical_tables_i8(desc: VQDesc, q: np.ndarray, scale: np.ndarray) -> np.ndarray:
-    """Canonical table buffer of the VQ_I8 representation: the int8 tables q[g, k, d],
-    zero-padded to a multiple of 16 bytes, then the fp16 scales scale[g] (byte copy only)."""
-    assert q.dtype == np.int8 and scale.dtype == np.float16
-    _, cb_bytes = vq_canonical_bytes(desc)
-    buf = np.zeros(cb_bytes, dtype=np.uint8)
-    qb = np.ascontiguousarray(q).view(np.uint8).reshape(-1)
-    sb = np.ascontiguousarray(scale).view(np.uint8).reshape(-1)
-    buf[:qb.size] = qb
-    off = (qb.size + 15) // 16 * 16
-    assert off + sb.size == cb_bytes
-    buf[off:] = sb
-    return buf
-
-
-def canonical_tables_bn(desc: VQDesc, q: np.ndarray, scale: np.ndarray, levels: np.ndarray,
-                        codes: np.ndarray) -> np.ndarray:
-    """Canonical table buffer of the VQ_I8_BN representation: q and scale as for VQ_I8, each
-    padded to 16 bytes, then the fp16 levels[g, 16], then the 4-bit block codes codes[out, in/32]
-    two per byte, even block in the low nibble (byte copies and nibble packing only)."""
-    assert q.dtype == np.int8 and scale.dtype == np.float16 and levels.dtype == np.float16
-    assert codes.dtype == np.uint8 and codes.shape[1] % 2 == 0
-    _, cb_bytes = vq_canonical_bytes(desc)
-    buf = np.zeros(cb_bytes, dtype=np.uint8)
-    off = 0
-    for part in (q, scale):
-        b = np.ascontiguousarray(part).view(np.uint8).reshape(-1)
-        buf[off:off + b.size] = b
-        off = (off + b.size + 15) // 16 * 16
-    lb = np.ascontiguousarray(levels).view(np.uint8).reshape(-1)
-    buf[off:off + lb.size] = lb
-    off += lb.size
-    packed = (codes[:, 0::2] | (codes[:, 1::2] << 4)).astype(np.uint8).reshape(-1)
-    assert off + packed.size == cb_bytes
-    buf[off:] = packed
-    return buf
 
 
 def to_device_bytes(a: np.ndarray, device="cuda:0") -> torch.Tensor:

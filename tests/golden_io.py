@@ -7,7 +7,7 @@ GOLDEN_DIR = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
 
 def read_case(name):
     """Parse a decode_*.txt fixture into a dict of plain arrays."""
-    out = {"codebook": [], "W": [], "q": []}
+    out = {"codebook": [], "W": [], "q": [], "tables": [], "levels": [], "codes": []}
     with open(os.path.join(GOLDEN_DIR, name)) as fh:
         for line in fh:
             line = line.strip()
@@ -25,6 +25,12 @@ def read_case(name):
                 out["q"].append([int(t) for t in rest.split()])
             elif key == "scale":      # one scale per group
                 out["scale"] = np.array([float(t) for t in rest.split()], dtype=np.float64)
+            elif key == "tables_hex":   # raw bytes of an interchange table buffer (lines are concatenated)
+                out["tables"].extend(int(t, 16) for t in rest.split())
+            elif key == "levels":     # the 16 block-scale levels of one group
+                out["levels"].append([float(t) for t in rest.split()])
+            elif key == "codes":      # the 4-bit block codes of one row
+                out["codes"].append([int(t) for t in rest.split()])
             elif key in ("x", "y"):
                 out[key] = np.array([float(t) for t in rest.split()], dtype=np.float64)
             else:
@@ -33,6 +39,9 @@ def read_case(name):
     out["codebook"] = np.array(out["codebook"], dtype=np.float64).reshape(-1, fmt["k"], fmt["d"])
     out["q"] = np.array(out["q"], dtype=np.int64).reshape(-1, fmt["k"], fmt["d"])
     out["W"] = np.array(out["W"], dtype=np.float64)
+    out["tables"] = np.array(out["tables"], dtype=np.uint8)
+    out["levels"] = np.array(out["levels"], dtype=np.float64)
+    out["codes"] = np.array(out["codes"], dtype=np.uint8)
     return out
 
 

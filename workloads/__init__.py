@@ -22,6 +22,7 @@ import numpy as np
 __all__ = [
     "VQShape", "CONFIGS", "LLAMA7B_LAYER", "seed_for", "canonical_sizes",
     "make_weights", "make_weights_i8", "make_x", "make_X", "llama7b_pass_shapes",
+    "tables_i8_bytes", "tables_bn_bytes",
     "LLAMA7B_LAYER_K64", "LLAMA7B_LAYER_K16_I8", "LLAMA7B_LAYER_D1_K16", "LLAMA7B_LAYER_K64_BN", "make_weights_bn", "LLAMA7B_LAYER_D4", "LLAMA7B_LAYER_D1_K8", "LLAMA7B_LAYER_K256_I8", "LLAMA7B_LAYER_D1_K4",
 ]
 
@@ -183,6 +184,45 @@ def make_weights_bn(s: VQShape, seed: int, w_std: float = 0.02):
     levels = np.exp2(a * np.arange(16)[None, :] + s0).astype(np.float16)
     codes = rng.integers(0, 16, size=(s.out_features, s.in_features // 32), dtype=np.uint8)
     return idx, q, scale, levels, codes
+
+
+def tables_i8_bytes(s: VQShape, q: np.ndarray, scale: np.ndarray) -> np.ndarray:
+    """The interchange table buffer of an int8-table matrix as raw bytes (byte copies only): the
+    int8 tables q[n_groups, k, d] in array order, zero bytes up to a multiple of 16, then the
+    fp16 scales scale[n_groups].  What the GPU library's pack step takes as input, and what the
+    oracle's own reader parses back into arrays in the tests."""
+    assert q.dtype == np.int8 and scale.dtype == np.float16 and s.int8_tables and not s.block_norm
+    buf = np.zeros(canonical_sizes(s)[1], dtype=np.uint8)
+    qb = np.ascontiguousarray(q).view(np.uint8).reshape(-1)
+    sb = np.ascontiguousarray(scale).view(np.uint8).reshape(-1)
+    off = (qb.size + 15) // 16 * 16
+    assert off + sb.size == buf.size
+    buf[:qb.size] = qb
+    buf[off:] = sb
+    return buf
+
+
+def tables_bn_bytes(s: VQShape, q: np.ndarray, scale: np.ndarray, levels: np.ndarray,
+                    codes: np.ndarray) -> np.ndarray:
+    """The interchange table buffer of a block-normalised matrix as raw bytes: q and scale as in
+    tables_i8_bytes, each zero-padded to a multiple of 16 bytes, then the fp16 levels[n_groups, 16],
+    then the 4-bit block codes codes[out, in / 32], two per byte, even block in the low nibble
+    (byte copies and nibble packing only)."""
+    assert q.dtype == np.int8 and scale.dtype == np.float16 and levels.dtype == np.float16
+    assert codes.dtype == np.uint8 and codes.shape[1] % 2 == 0 and s.block_norm
+    buf = np.zeros(canonical_sizes(s)[1], dtype=np.uint8)
+    off = 0
+    for part in (q, scale):
+        b = np.ascontiguousarray(part).view(np.uint8).reshape(-1)
+        buf[off:off + b.size] = b
+        off = (off + b.size + 15) // 16 * 16
+    lb = np.ascontiguousarray(levels).view(np.uint8).reshape(-1)
+    buf[off:off + lb.size] = lb
+    off += lb.size
+    packed = (codes[:, 0::2] | (codes[:, 1::2] << 4)).astype(np.uint8).reshape(-1)
+    assert off + packed.size == buf.size
+    buf[off:] = packed
+    return buf
 
 
 def make_x(n: int, seed: int) -> np.ndarray:
