@@ -3,7 +3,7 @@
  *
  * The library implements the decode-time hot path of GPTVQ (arXiv 2402.15319):
  * y = W x where W[out,in] is never stored densely.  W is tiled into groups of
- * group_rows x group_cols weights (Sec. 4: "8 rows by 256 columns"); each group
+ * group_rows x group_cols weights (Sec. 4: e.g. 8 rows x 256 columns); each group
  * owns a codebook of k centroids of d fp16 values (Sec. 2.1) and stores one
  * index of index_bits = log2(k) bits for every run of d consecutive columns of
  * a row (Sec. 4: d columns are quantised at a time).  At inference a group is
@@ -13,8 +13,12 @@
  * Conventions common to every entry point
  *   - plain C, no C++/torch types; every pointer is a DEVICE pointer unless a
  *     comment says "host";
- *   - the caller owns all buffers; the library allocates nothing and keeps no
- *     state between calls;
+ *   - the caller owns all buffers; the library allocates nothing.  The only state it
+ *     keeps between calls is a process-wide, thread-safe cache of one launch parameter
+ *     (how many workgroups of the streaming GEMV kernel fit on the device), filled by an
+ *     occupancy query of the HIP runtime the first time a (device, representation, width)
+ *     combination is used; that query enqueues nothing, so a first call may be made while
+ *     the stream is being captured into a HIP graph;
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream); calls
  *     enqueue work and return without synchronising;
  *   - return value: VQ_OK (0) or a negative vq_status.  Arguments are validated
@@ -34,8 +38,8 @@
  *     centroid value is scale[g] * q taken exactly and rounded once to fp16 (nearest even);
  *     that fp16 matrix is W for every entry point.
  *   - codebooks (VQ_I8_BN; appendix "Blockwise data normalization": every sub-row block of 32
- *     weights was divided by a scale that is quantised to 4 bits in the log domain, and "the
- *     inverse scaling is applied at VQ decoding"): q and scale as for VQ_I8, each padded to a
+ *     weights was divided by a scale that is quantised to 4 bits in the log domain, and the
+ *     division is undone when a weight is decoded): q and scale as for VQ_I8, each padded to a
  *     multiple of 16 bytes, then fp16 level[g][16], the 16 block scales a code can select in
  *     group g (level j = 2^(a_g*j + s_0) in the appendix's parameterisation; stored explicitly
  *     so that the reconstruction is exact to state), then the 4-bit codes of the whole matrix,
@@ -90,12 +94,15 @@ typedef enum vq_dtype { VQ_F16 = 1, VQ_F32 = 2, VQ_I8 = 3, VQ_I8_BN = 4 } vq_dty
 typedef struct vq_desc {
   int32_t out_features;   /* rows of W (length of y)                                */
   int32_t in_features;    /* columns of W (length of x)                             */
-  int32_t group_rows;     /* 8 (k = 64: 8, 16 or 32; d = 4: 64, 128 or 256)         */
+  int32_t group_rows;     /* rows sharing one codebook: 8 (VQ_F16); 8, 16 or 32 (k = 64, and
+                             d = 1 with k = 8); 64, 128 or 256 (VQ_I8 with k = 256, d = 2 or 4);
+                             1 (d = 1 with k = 4)                                     */
   int32_t group_cols;     /* 256 (Sec. 4: at most 256 columns per group)            */
   int32_t d;              /* VQ dimensionality: 2, 1 (scalar codebooks) or 4        */
-  int32_t k;              /* centroids: 16 or 256 (VQ_F16), 64 or 16 (VQ_I8), 256 (d = 4) */
-  int32_t index_bits;     /* log2(k): 4, 8 or 6                                     */
-  int32_t codebook_dtype; /* VQ_F16, VQ_I8 or VQ_I8_BN                              */
+  int32_t k;              /* centroids.  d = 2: 16 or 256 (VQ_F16), 16, 64 or 256 (VQ_I8),
+                             64 (VQ_I8_BN); d = 1: 16 (VQ_F16), 8 or 4 (VQ_I8); d = 4: 256 */
+  int32_t index_bits;     /* log2(k): 2, 3, 4, 6 or 8                               */
+  int32_t codebook_dtype; /* VQ_F16, VQ_I8 or VQ_I8_BN (see the list above)         */
 } vq_desc;
 
 /* Human-readable name of a status code (host pointer to a static string). */
@@ -118,8 +125,8 @@ VQ_API int vq_layout_bytes(const vq_desc* desc, size_t* idx_bytes, size_t* cb_by
 
 /*
  * One-time re-layout (off the hot path): canonical indices/codebooks ->
- * device layout (Sec. 3.2: indices and tables are "organized to enable
- * efficient vectorization").  All four buffers are device memory, 16-byte
+ * device layout (Sec. 3.2: indices and tables are arranged for wide vector
+ * accesses).  All four buffers are device memory, 16-byte
  * aligned, sized as reported above; input and output must not overlap.
  */
 VQ_API int vq_pack_layout(const vq_desc* desc, const void* idx_canon, const void* cb_canon,
@@ -197,15 +204,6 @@ VQ_API int vq_em_assign(const vq_desc* desc, const void* W_f32, const void* hdia
                         const void* cb_f32, void* assign_u8, void* stream);
 VQ_API int vq_em_update(const vq_desc* desc, const void* W_f32, const void* hdiag_f32,
                         const void* assign_u8, void* cb_f32_out, void* stream);
-
-/*
- * Measurement aid, not part of the method: reads `bytes` bytes (a multiple of 16)
- * of device memory once with the same non-temporal 128-bit loads the GEMV kernels
- * stream their indices with, and discards them.  Timing it over a buffer much
- * larger than the caches gives the HBM read rate this GPU can actually sustain,
- * which the bench reports next to the nominal peak.
- */
-VQ_API int vq_stream_read_probe(const void* buf, size_t bytes, void* stream);
 
 #ifdef __cplusplus
 }

@@ -14,13 +14,13 @@ from typing import Sequence
 __all__ = [
     "VQDesc", "VQError", "VQ_F16", "VQ_F32", "VQ_I8", "VQ_I8_BN", "lib", "lib_path", "make_desc",
     "vq_status_string", "vq_version", "vq_canonical_bytes", "vq_layout_bytes",
-    "vq_pack_layout", "vq_gemv", "vq_gemv_multi", "GemvMultiArgs", "vq_stream_read_probe", "vq_gemm_batched", "vq_decode_dense", "vq_em_assign", "vq_em_update",
+    "vq_pack_layout", "vq_gemv", "vq_gemv_multi", "GemvMultiArgs", "vq_gemm_batched", "vq_decode_dense", "vq_em_assign", "vq_em_update",
 ]
 
 VQ_F16 = 1
 VQ_F32 = 2
-VQ_I8 = 3
-VQ_I8_BN = 4   # int8 tables + scale + blockwise normalisation (16 levels per group, 4-bit code per 32 weights)     # codebook_dtype: int8 lookup tables with one fp16 scale per group
+VQ_I8 = 3      # codebook_dtype: int8 lookup tables with one fp16 scale per group
+VQ_I8_BN = 4   # the same plus blockwise normalisation (16 levels per group, a 4-bit code per 32 weights)
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libvq.so")
@@ -74,8 +74,6 @@ def lib() -> ctypes.CDLL:
                                     ctypes.POINTER(vp), ctypes.POINTER(vp), i32, vp]
         L.vq_gemm_batched.restype = i32
         L.vq_gemm_batched.argtypes = [dp, vp, vp, vp, i32, i32, vp, i32, i32, vp]
-        L.vq_stream_read_probe.restype = i32
-        L.vq_stream_read_probe.argtypes = [vp, ctypes.c_size_t, vp]
         L.vq_decode_dense.restype = i32
         L.vq_decode_dense.argtypes = [dp, vp, vp, vp, vp]
         L.vq_em_assign.restype = i32
@@ -149,7 +147,9 @@ def vq_gemv(desc: VQDesc, idx_dev, cb_dev, x, y, y_dtype: int = VQ_F16, stream=N
 
 
 class GemvMultiArgs:
-    """Pre-marshalled argument arrays for vq_gemv_multi (build once, call many times)."""
+    """Pre-marshalled argument arrays for vq_gemv_multi (build once, call many times).  Keeps a
+    reference to every tensor it was given, so the device memory behind the stored addresses
+    lives as long as this object."""
 
     def __init__(self, descs: Sequence[VQDesc], idx_dev, cb_dev, xs, ys):
         n = len(descs)
@@ -162,6 +162,7 @@ class GemvMultiArgs:
         self.cb = arr(*[_ptr(t) for t in cb_dev])
         self.x = arr(*[_ptr(t) for t in xs])
         self.y = arr(*[_ptr(t) for t in ys])
+        self._keep = (list(idx_dev), list(cb_dev), list(xs), list(ys))
 
 
 def vq_gemv_multi(args_or_descs, idx_dev=None, cb_dev=None, xs=None, ys=None,
@@ -191,7 +192,3 @@ def vq_em_assign(desc: VQDesc, W_f32, hdiag_f32, cb_f32, assign_u8, stream=None)
 def vq_em_update(desc: VQDesc, W_f32, hdiag_f32, assign_u8, cb_f32_out, stream=None) -> None:
     _check(lib().vq_em_update(ctypes.byref(desc), _ptr(W_f32), _ptr(hdiag_f32), _ptr(assign_u8),
                               _ptr(cb_f32_out), _stream(stream)), "vq_em_update")
-
-
-def vq_stream_read_probe(buf, nbytes: int, stream=None) -> None:
-    _check(lib().vq_stream_read_probe(_ptr(buf), nbytes, _stream(stream)), "vq_stream_read_probe")

@@ -11,6 +11,9 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libvq.so")
+OBJ_DIR = os.path.join(HERE, "_build")   # object files (kept out of the history)
+BENCH_LIB_PATH = os.path.join(HERE, "libvq_bench.so")   # the benchmark's read probe, not part of the product
+BENCH_SOURCES = ["vq_bench_probe.hip"]
 SOURCES = ["vq_api.hip", "vq_pack.hip", "vq_decode.hip", "vq_gemv.hip", "vq_gemv_d4.hip", "vq_gemm.hip", "vq_em.hip"]
 # packed-fp32 code generation is switched off on purpose for this machine pool
 HIPCC_FLAGS = [
@@ -20,10 +23,7 @@ HIPCC_FLAGS = [
 ]
 
 
-def build(verbose: bool = False) -> str:
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    srcs = [os.path.join(CSRC, s) for s in SOURCES]
-    cmd = [hipcc, *HIPCC_FLAGS, "-shared", "-o", LIB_PATH, *srcs]
+def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)
@@ -33,6 +33,24 @@ def build(verbose: bool = False) -> str:
         raise RuntimeError(f"hipcc failed ({res.returncode}):\n{err}")
     if verbose and err.strip():
         print(err, file=sys.stderr)
+
+
+def _link(sources, out, verbose):
+    """Compiles every source to an object file (in parallel, one hipcc per file) and links them."""
+    from concurrent.futures import ThreadPoolExecutor
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    objs = [os.path.join(OBJ_DIR, os.path.splitext(s)[0] + ".o") for s in sources]
+    cmds = [[hipcc, *HIPCC_FLAGS, "-c", os.path.join(CSRC, s), "-o", o] for s, o in zip(sources, objs)]
+    with ThreadPoolExecutor(max_workers=min(8, len(cmds))) as pool:
+        list(pool.map(lambda c: _run(c, verbose), cmds))
+    _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", out, *objs], verbose)
+
+
+def build(verbose: bool = False) -> str:
+    """Compiles libvq.so (the product) and libvq_bench.so (the benchmark's read probe)."""
+    _link(SOURCES, LIB_PATH, verbose)
+    _link(BENCH_SOURCES, BENCH_LIB_PATH, verbose)
     return LIB_PATH
 
 

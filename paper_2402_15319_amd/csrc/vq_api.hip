@@ -1,5 +1,6 @@
-// C ABI of libvq: argument validation on the host, then one launch per call.
-// Nothing here allocates, synchronises or keeps state.
+// C ABI of libvq: argument validation on the host, then one launch per call (two for the
+// widest batched products).  Nothing here allocates or synchronises; the only state the
+// library keeps is a cache of one launch parameter (see gemv_stream_resident_wgs).
 #include <stddef.h>
 #include <string.h>
 #include "vq_internal.h"
@@ -375,13 +376,6 @@ int vq_em_update(const vq_desc* desc, const void* W_f32, const void* hdiag_f32, 
     return VQ_ERR_ALIGN;
   return hip_status(launch_em_update(desc->k, desc->out_features, desc->in_features, W_f32, hdiag_f32,
                                      assign_u8, cb_f32_out, (hipStream_t)stream));
-}
-
-int vq_stream_read_probe(const void* buf, size_t bytes, void* stream) {
-  if (!buf) return VQ_ERR_NULL;
-  if (!aligned16(buf)) return VQ_ERR_ALIGN;
-  if (bytes == 0 || (bytes & 15)) return VQ_ERR_BAD_ARG;
-  return hip_status(launch_stream_read(buf, bytes, (hipStream_t)stream));
 }
 
 }  // extern "C"

@@ -20,6 +20,7 @@
 //   * gemv_split_kernel (few row-blocks): workgroups of 4 (or 8) waves; `splits`
 //     (1, 2, 4 or 8) waves share a row-block and their partial sums meet in LDS in
 //     a fixed order, so the result is deterministic.
+#include <atomic>
 #include "vq_device.h"
 #include "vq_internal.h"
 
@@ -847,14 +848,15 @@ size_t gemv_stream_lds_bytes(int fmt, int max_n_cb) {
 }
 
 int gemv_stream_resident_wgs(int fmt, int max_n_cb) {
-  // Occupancy of the persistent kernel for this LDS size, asked once per (device, format, size):
-  // a pure function of the code object and the device, cached so that the hot path makes
-  // no runtime queries.  Benign if two threads fill the same slot at once.
-  static int cached[8][16][kStreamMaxColBlocks + 1];
+  // Occupancy of the persistent kernel for this LDS size: a pure function of the code object
+  // and the device, asked of the runtime once per (device, format, size) and cached (the one
+  // piece of state the library keeps).  The slots are atomics: two threads that fill the same
+  // slot at once store the same value.  The query enqueues nothing on any stream.
+  static std::atomic<int> cached[8][16][kStreamMaxColBlocks + 1];
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) dev = 0;
   const int fi = fmt == 16 ? 0 : fmt == 64 ? 1 : fmt == kFmtK16I8 ? 3 : fmt == kFmtD1K16 ? 4 : fmt == kFmtK64BN ? 5 : fmt == kFmtD1K8 ? 6 : fmt == kFmtD1K4 ? 7 : 2;
-  int& slot = cached[fi][dev][max_n_cb];
+  int slot = cached[fi][dev][max_n_cb].load(std::memory_order_relaxed);
   if (slot == 0) {
     int per_cu = 0, cus = 0;
     const size_t lds = gemv_stream_lds_bytes(fmt, max_n_cb);
@@ -863,11 +865,16 @@ int gemv_stream_resident_wgs(int fmt, int max_n_cb) {
 #define VQ_F(K) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gemv_stream_kernel<K>, threads, lds)
     VQ_FMT_SWITCH(fmt, VQ_F)
 #undef VQ_F
-    if (e != hipSuccess || per_cu < 1) per_cu = 1;
-    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
-      cus = 256;
-    (void)hipGetLastError();
+    const bool ok = e == hipSuccess && per_cu >= 1 &&
+                    hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus >= 1;
+    if (!ok) {
+      // A refused query is not an error of the call: any grid size gives the right result, a
+      // small one only runs slower.  Nothing is cached, so the next call asks again.
+      (void)hipGetLastError();
+      return 256;
+    }
     slot = per_cu * cus;
+    cached[fi][dev][max_n_cb].store(slot, std::memory_order_relaxed);
   }
   return slot;
 }

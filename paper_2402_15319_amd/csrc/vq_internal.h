@@ -86,6 +86,4 @@ hipError_t launch_em_assign(int k, int out_features, int in_features, const void
 hipError_t launch_em_update(int k, int out_features, int in_features, const void* W, const void* hdiag,
                             const void* assign, void* cb_out, hipStream_t s);
 
-hipError_t launch_stream_read(const void* buf, size_t bytes, hipStream_t s);
-
 }  // namespace vq

@@ -286,32 +286,7 @@ __global__ __launch_bounds__(256) void copy16_kernel(const uint8_t* __restrict__
   }
 }
 
-// Reads n16 16-byte pieces once (non-temporal) and keeps the optimiser from dropping the loads.
-typedef unsigned int probe_u32x4_t __attribute__((ext_vector_type(4)));
-__global__ __launch_bounds__(256) void stream_read_kernel(const probe_u32x4_t* __restrict__ p,
-                                                          long long n16, unsigned* sink) {
-  unsigned acc = 0;
-  const long long stride = (long long)gridDim.x * 256 * 4;
-  for (long long base = (long long)blockIdx.x * 256 * 4 + threadIdx.x; base < n16; base += stride) {
-    probe_u32x4_t v[4];
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const long long i = base + u * 256;
-      v[u] = i < n16 ? __builtin_nontemporal_load(p + i) : probe_u32x4_t{0, 0, 0, 0};
-    }
-#pragma unroll
-    for (int u = 0; u < 4; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
-  }
-  if (acc == 0x9e3779b9u && sink) *sink = acc;   // never true for the fill patterns used; sink may be null
-}
-
 }  // namespace
-
-hipError_t launch_stream_read(const void* buf, size_t bytes, hipStream_t s) {
-  hipLaunchKernelGGL(stream_read_kernel, dim3(4096), dim3(256), 0, s,
-                     (const probe_u32x4_t*)buf, (long long)(bytes / 16), (unsigned*)nullptr);
-  return hipGetLastError();
-}
 
 hipError_t launch_pack(const vq_desc& d, const void* idx_canon, const void* cb_canon,
                        void* idx_dev, void* cb_dev, hipStream_t s) {

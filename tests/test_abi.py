@@ -16,6 +16,20 @@ def _declared_symbols():
     return sorted(set(re.findall(r"VQ_API\s+[\w\s\*]+?\b(vq_\w+)\s*\(", text)))
 
 
+def test_every_header_is_covered_and_the_bench_probe_is_not_in_the_product_library():
+    """include/ holds the product's header and the benchmark probe's; the probe's symbol lives in a
+    library of its own and libvq.so does not export it."""
+    assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["vq.h", "vq_bench.h"]
+    text = open(os.path.join(ROOT, "include", "vq_bench.h")).read()
+    names = re.findall(r"\b(vq_bench_\w+)\s*\(", text)
+    assert names == ["vq_bench_stream_read"]
+    from paper_2402_15319_amd import bench_probe
+    assert hasattr(bench_probe.lib(), "vq_bench_stream_read")
+    assert hasattr(bench_probe, "vq_bench_stream_read")
+    assert not hasattr(vq.lib(), "vq_bench_stream_read")
+    assert not hasattr(vq.lib(), "vq_stream_read_probe")
+
+
 def test_header_declares_the_four_hot_path_calls():
     names = _declared_symbols()
     for required in ("vq_pack_layout", "vq_gemv", "vq_gemm_batched", "vq_decode_dense"):

@@ -76,6 +76,58 @@ def test_scan_flags_an_early_read_and_accepts_a_fenced_one():
     assert len(scan(pair)) == 1
 
 
+SWAP_WAIT_STATES = 2
+
+
+def scan_swaps(lines):
+    """Lane-swap instructions (v_permlane16_swap / v_permlane32_swap) sit in asm statements too: a
+    vector instruction that writes one of their operands needs two wait states before the swap,
+    and so does a vector instruction that reads a swapped register afterwards.  Returns
+    [(line number, text)] of the swaps, or of the readers, that come too early."""
+    bad = []
+    writes = []   # (registers written by a vector instruction, wait states since)
+    swaps = []    # (registers written by a swap, wait states since)
+    for ln, line in enumerate(lines, 1):
+        t = line.split(";")[0].strip()
+        if not t or t.startswith(".") or t.endswith(":"):
+            continue
+        op, _, rest = t.partition(" ")
+        ops = [o.strip() for o in rest.split(",")]
+        if op == "s_nop":
+            n = int(ops[0]) + 1
+            writes = [(d, w + n) for d, w in writes if w + n < SWAP_WAIT_STATES]
+            swaps = [(d, w + n) for d, w in swaps if w + n < SWAP_WAIT_STATES]
+            continue
+        is_swap = op.startswith(("v_permlane16_swap", "v_permlane32_swap"))
+        regs_all = set().union(*[_regs(o) for o in ops]) if ops else set()
+        if is_swap:
+            if any(d & regs_all for d, _ in writes):
+                bad.append((ln, t))
+        elif op.startswith("v_") or op.startswith(("ds_", "global_", "buffer_", "flat_", "scratch_")):
+            src = set().union(*[_regs(o) for o in ops[1:]]) if op.startswith("v_") and len(ops) > 1 else \
+                (regs_all if not op.startswith("v_") else set())
+            if any(d & src for d, _ in swaps):
+                bad.append((ln, t))
+        writes = [(d, w + 1) for d, w in writes if w + 1 < SWAP_WAIT_STATES]
+        swaps = [(d, w + 1) for d, w in swaps if w + 1 < SWAP_WAIT_STATES]
+        if is_swap:
+            swaps.append((regs_all, 0))
+        elif op.startswith("v_") and ops and not op.startswith("v_cmp"):
+            writes.append((_regs(ops[0]), 0))
+    return bad
+
+
+def test_scan_swaps_flags_missing_wait_states():
+    ok = ["v_add_f32_e32 v1, v2, v3", "s_nop 1", "v_permlane32_swap_b32_e32 v1, v4", "s_nop 1", "v_add_f32_e32 v5, v1, v4"]
+    early_swap = ["v_add_f32_e32 v1, v2, v3", "s_nop 0", "v_permlane32_swap_b32_e32 v1, v4", "s_nop 1", "v_add_f32_e32 v5, v1, v4"]
+    early_read = ["v_add_f32_e32 v1, v2, v3", "s_nop 1", "v_permlane16_swap_b32_e32 v1, v4", "s_nop 0", "v_add_f32_e32 v5, v9, v4"]
+    unrelated = ["v_add_f32_e32 v7, v2, v3", "v_permlane16_swap_b32_e32 v1, v4", "v_add_f32_e32 v5, v9, v8"]
+    assert scan_swaps(ok) == []
+    assert len(scan_swaps(early_swap)) == 1
+    assert len(scan_swaps(early_read)) == 1
+    assert scan_swaps(unrelated) == []
+
+
 @pytest.mark.skipif(shutil.which(os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")) is None,
                     reason="hipcc not available")
 def test_no_instruction_reads_a_dot2c_result_early(tmp_path):
@@ -89,6 +141,9 @@ def test_no_instruction_reads_a_dot2c_result_early(tmp_path):
     lines = out.read_text().splitlines()
     assert sum("v_dot2c_f32_f16" in l for l in lines) > 100     # the kernels are in there
     bad = scan(lines)
+    assert bad == [], bad[:10]
+    assert sum("v_permlane32_swap" in l for l in lines) > 10    # the reductions are in there
+    bad = scan_swaps(lines)
     assert bad == [], bad[:10]
 
 
