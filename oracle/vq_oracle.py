@@ -179,6 +179,24 @@ def gemm(f: VQFormat, idx: np.ndarray, cb: np.ndarray, X: np.ndarray) -> np.ndar
     return W @ X64
 
 
+def gemv_lora(f: VQFormat, idx: np.ndarray, cb: np.ndarray, x: np.ndarray, A: np.ndarray,
+              B: np.ndarray) -> np.ndarray:
+    """y = W x + B (A x) in fp64: the frozen vector-quantised base matrix plus a low-rank adapter
+    (Sec. 5, "Combination of GPTVQ with LoRA adapters": adapters are trained on top of the
+    quantised representation and applied next to it at inference; the update is the usual
+    product of a [out, rank] and a [rank, in] matrix, any scaling folded into B).
+
+    A: fp16 [rank, in], B: fp16 [out, rank]; both widened exactly to fp64.
+    """
+    A64 = np.asarray(A, dtype=np.float16).astype(np.float64)
+    B64 = np.asarray(B, dtype=np.float16).astype(np.float64)
+    if A64.ndim != 2 or B64.ndim != 2 or A64.shape[1] != f.in_features or \
+            B64.shape != (f.out_features, A64.shape[0]):
+        raise ValueError("A is [rank, in], B is [out, rank]")
+    x64 = np.asarray(x, dtype=np.float16).astype(np.float64)
+    return gemv(f, idx, cb, x) + B64 @ (A64 @ x64)
+
+
 def dequantise_codebooks(q: np.ndarray, scale: np.ndarray) -> np.ndarray:
     """Integer lookup tables with a scale factor per group -> fp16 codebooks.
 

@@ -183,3 +183,52 @@ def test_normwise_tolerances_catch_one_wrong_row_and_one_wrong_group():
     wrong_vec[77] += 0.04 * 1.0
     e = oracle.normwise_rel_err(wrong_vec, ref)
     assert 2e-5 < e < 2e-3
+
+
+# ---------------------------------------------------------------- low-rank adapter next to the base matrix
+def test_gemv_lora_hand_worked():
+    """y = W x + B (A x) on the hand-written 4 x 8 decode fixture: W x is the fixture's y
+    (49.75, 37.75, 76.25, 63.75) with x = (1, 2, -1, 0.5, 0, 1, 3, -2); the adapter is worked by hand:
+    A row 0 = e_0 + 2 e_2 -> t_0 = 1 - 2 = -1;  A row 1 = 0.5 everywhere -> t_1 = 0.5 * 4.5 = 2.25;
+    B rows (1, 2), (-1, 0), (0, 4), (2, -2) -> B t = (3.5, 1, 9, -6.5).
+    A transposed A or B, a dropped base term, or (B A)^T fails."""
+    case = read_case("decode_2x4_k4_b2.txt")
+    f = _fmt(case)
+    cb = case["codebook"].astype(np.float16)
+    x = case["x"].astype(np.float16)
+    A = np.array([[1, 0, 2, 0, 0, 0, 0, 0], [0.5] * 8], dtype=np.float16)           # rank 2, in 8
+    B = np.array([[1, 2], [-1, 0], [0, 4], [2, -2]], dtype=np.float16)              # out 4, rank 2
+    want = np.array([53.25, 38.75, 85.25, 57.25])
+    np.testing.assert_array_equal(oracle.gemv_lora(f, case["idx"], cb, x, A, B), want)
+    with pytest.raises(ValueError):
+        oracle.gemv_lora(f, case["idx"], cb, x, A.T.copy(), B)
+    with pytest.raises(ValueError):
+        oracle.gemv_lora(f, case["idx"], cb, x, A, B.T.copy())
+
+
+def test_gemv_lora_reduces_to_known_cases():
+    """Zero adapter: the plain product.  Rank-one adapter u v^T: y = W x + u (v . x).  And the sum equals
+    the product with the dense matrix W + B A formed in exact rational arithmetic on a tiny case."""
+    from fractions import Fraction
+    s = workloads.VQShape(16, 512, 16, 4)
+    f = VQFormat(16, 512, 16, 4)
+    idx, cb = workloads.make_weights(s, 77)
+    x = workloads.make_x(512, 77)
+    rng = np.random.default_rng(78)
+    A = rng.normal(0, 0.05, (4, 512)).astype(np.float16)
+    B = rng.normal(0, 0.05, (16, 4)).astype(np.float16)
+    base = oracle.gemv(f, idx, cb, x)
+    np.testing.assert_array_equal(oracle.gemv_lora(f, idx, cb, x, np.zeros_like(A), B), base)
+    np.testing.assert_array_equal(oracle.gemv_lora(f, idx, cb, x, A, np.zeros_like(B)), base)
+    u, v = B[:, :1], A[:1, :]
+    got = oracle.gemv_lora(f, idx, cb, x, v, u)
+    vx = float(v.astype(np.float64) @ x.astype(np.float64))
+    np.testing.assert_allclose(got, base + u[:, 0].astype(np.float64) * vx, rtol=1e-13, atol=1e-13)
+    # exact rational check of two rows
+    W = oracle.decode_dense(f, idx, cb).view(np.float16)
+    for r in (0, 11):
+        exact = sum(Fraction(float(W[r, c])) * Fraction(float(x[c])) for c in range(512))
+        for j in range(4):
+            tj = sum(Fraction(float(A[j, c])) * Fraction(float(x[c])) for c in range(512))
+            exact += Fraction(float(B[r, j])) * tj
+        assert abs(float(exact) - oracle.gemv_lora(f, idx, cb, x, A, B)[r]) <= 1e-12 * max(1.0, abs(float(exact)))
