@@ -159,6 +159,39 @@ VQ_API int vq_gemv_multi(int count, const vq_desc* descs, const void* const* idx
                   int y_dtype, void* stream);
 
 /*
+ * y = W x + B (A x): the frozen vector-quantised matrix with a low-rank adapter next to it
+ * (Sec. 5, "Combination of GPTVQ with LoRA adapters": adapters are trained on top of the
+ * quantised base model and served with it; any scaling of the update is folded into B).
+ *   A_f16  fp16 [rank, in]  row-major (device), 16-byte aligned
+ *   B_f16  fp16 [out, rank] row-major (device), 16-byte aligned
+ *   rank   0 (no adapter: plain y = W x) or a multiple of 8, at most 64
+ * Two launches on `stream`: t = A x in fp32 into `workspace`, then the GEMV kernel, which
+ * adds B[row, :] . t (fp32) to every row total before it is rounded and stored.
+ * `workspace` is device memory owned by the caller, 16-byte aligned, of at least
+ * vq_lora_workspace_bytes(count) bytes (256 bytes per product); its contents are overwritten
+ * and mean nothing afterwards; calls that share a workspace must not overlap in time.
+ * Everything else as for vq_gemv / vq_gemv_multi (`lora` is a HOST array of `count`
+ * descriptors holding device pointers).  Representations with d = 4, and k = 256 with int8
+ * tables, are not implemented here (VQ_ERR_UNSUPPORTED).
+ */
+typedef struct vq_lora_desc {
+  const void* A_f16;
+  const void* B_f16;
+  int32_t rank;
+  int32_t reserved;     /* 0 */
+} vq_lora_desc;
+
+VQ_API int vq_lora_workspace_bytes(int count, size_t* bytes);
+VQ_API int vq_gemv_lora(const vq_desc* desc, const void* idx_dev, const void* cb_dev,
+                        const void* x_f16, const void* A_f16, const void* B_f16, int rank,
+                        void* workspace, size_t workspace_bytes, void* y, int y_dtype,
+                        void* stream);
+VQ_API int vq_gemv_lora_multi(int count, const vq_desc* descs, const void* const* idx_dev,
+                              const void* const* cb_dev, const void* const* x_f16,
+                              const vq_lora_desc* lora, void* workspace, size_t workspace_bytes,
+                              void* const* y, int y_dtype, void* stream);
+
+/*
  * Y[out, B] = W X[in, B]  (the batched / prefill form of the same product; a
  * dense contraction, decoded tiles go through LDS to the matrix cores).
  * X is fp16 with row stride ldx >= B elements (batch index contiguous), Y has

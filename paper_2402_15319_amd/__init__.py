@@ -14,7 +14,8 @@ from typing import Sequence
 __all__ = [
     "VQDesc", "VQError", "VQ_F16", "VQ_F32", "VQ_I8", "VQ_I8_BN", "lib", "lib_path", "make_desc",
     "vq_status_string", "vq_version", "vq_canonical_bytes", "vq_layout_bytes",
-    "vq_pack_layout", "vq_gemv", "vq_gemv_multi", "GemvMultiArgs", "vq_gemm_batched", "vq_decode_dense", "vq_em_assign", "vq_em_update",
+    "vq_pack_layout", "vq_gemv", "vq_gemv_multi", "GemvMultiArgs", "VQLoraDesc", "vq_lora_workspace_bytes", "vq_gemv_lora",
+    "vq_gemv_lora_multi", "vq_gemm_batched", "vq_decode_dense", "vq_em_assign", "vq_em_update",
 ]
 
 VQ_F16 = 1
@@ -35,6 +36,12 @@ class VQDesc(ctypes.Structure):
         ("d", ctypes.c_int32), ("k", ctypes.c_int32),
         ("index_bits", ctypes.c_int32), ("codebook_dtype", ctypes.c_int32),
     ]
+
+
+class VQLoraDesc(ctypes.Structure):
+    """Mirror of `vq_lora_desc` (include/vq.h)."""
+    _fields_ = [("A_f16", ctypes.c_void_p), ("B_f16", ctypes.c_void_p),
+                ("rank", ctypes.c_int32), ("reserved", ctypes.c_int32)]
 
 
 class VQError(RuntimeError):
@@ -72,6 +79,13 @@ def lib() -> ctypes.CDLL:
         L.vq_gemv_multi.restype = i32
         L.vq_gemv_multi.argtypes = [i32, dp, ctypes.POINTER(vp), ctypes.POINTER(vp),
                                     ctypes.POINTER(vp), ctypes.POINTER(vp), i32, vp]
+        L.vq_lora_workspace_bytes.restype = i32
+        L.vq_lora_workspace_bytes.argtypes = [i32, sz]
+        L.vq_gemv_lora.restype = i32
+        L.vq_gemv_lora.argtypes = [dp, vp, vp, vp, vp, vp, i32, vp, ctypes.c_size_t, vp, i32, vp]
+        L.vq_gemv_lora_multi.restype = i32
+        L.vq_gemv_lora_multi.argtypes = [i32, dp, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp),
+                                         ctypes.POINTER(VQLoraDesc), vp, ctypes.c_size_t, ctypes.POINTER(vp), i32, vp]
         L.vq_gemm_batched.restype = i32
         L.vq_gemm_batched.argtypes = [dp, vp, vp, vp, i32, i32, vp, i32, i32, vp]
         L.vq_decode_dense.restype = i32
@@ -171,6 +185,31 @@ def vq_gemv_multi(args_or_descs, idx_dev=None, cb_dev=None, xs=None, ys=None,
         GemvMultiArgs(args_or_descs, idx_dev, cb_dev, xs, ys)
     _check(lib().vq_gemv_multi(a.count, a.descs, a.idx, a.cb, a.x, a.y, y_dtype,
                                _stream(stream)), "vq_gemv_multi")
+
+
+def vq_lora_workspace_bytes(count: int) -> int:
+    a = ctypes.c_size_t(0)
+    _check(lib().vq_lora_workspace_bytes(count, ctypes.byref(a)), "vq_lora_workspace_bytes")
+    return a.value
+
+
+def vq_gemv_lora(desc: VQDesc, idx_dev, cb_dev, x, A, B, rank: int, workspace, y,
+                 y_dtype: int = VQ_F16, stream=None, workspace_bytes: int | None = None) -> None:
+    nb = workspace.numel() * workspace.element_size() if workspace_bytes is None else workspace_bytes
+    _check(lib().vq_gemv_lora(ctypes.byref(desc), _ptr(idx_dev), _ptr(cb_dev), _ptr(x), _ptr(A), _ptr(B), rank,
+                              _ptr(workspace), nb, _ptr(y), y_dtype, _stream(stream)), "vq_gemv_lora")
+
+
+def vq_gemv_lora_multi(args: GemvMultiArgs, As, Bs, ranks: Sequence[int], workspace,
+                       y_dtype: int = VQ_F16, stream=None, workspace_bytes: int | None = None) -> None:
+    """args as for vq_gemv_multi; As/Bs/ranks: one adapter per product (rank 0 = none)."""
+    n = args.count
+    if not (len(As) == len(Bs) == len(ranks) == n):
+        raise ValueError("vq_gemv_lora_multi: argument lists differ in length")
+    lora = (VQLoraDesc * n)(*[VQLoraDesc(_ptr(a), _ptr(b), r, 0) for a, b, r in zip(As, Bs, ranks)])
+    nb = workspace.numel() * workspace.element_size() if workspace_bytes is None else workspace_bytes
+    _check(lib().vq_gemv_lora_multi(n, args.descs, args.idx, args.cb, args.x, lora, _ptr(workspace), nb,
+                                    args.y, y_dtype, _stream(stream)), "vq_gemv_lora_multi")
 
 
 def vq_gemm_batched(desc: VQDesc, idx_dev, cb_dev, X, B: int, ldx: int, Y, ldy: int,

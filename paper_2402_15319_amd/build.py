@@ -14,7 +14,7 @@ LIB_PATH = os.path.join(HERE, "libvq.so")
 OBJ_DIR = os.path.join(HERE, "_build")   # object files (kept out of the history)
 BENCH_LIB_PATH = os.path.join(HERE, "libvq_bench.so")   # the benchmark's read probe, not part of the product
 BENCH_SOURCES = ["vq_bench_probe.hip"]
-SOURCES = ["vq_api.hip", "vq_pack.hip", "vq_decode.hip", "vq_gemv.hip", "vq_gemv_d4.hip", "vq_gemm.hip", "vq_em.hip"]
+SOURCES = ["vq_api.hip", "vq_pack.hip", "vq_decode.hip", "vq_gemv.hip", "vq_gemv_lora.hip", "vq_gemv_d4.hip", "vq_gemm.hip", "vq_em.hip"]
 # packed-fp32 code generation is switched off on purpose for this machine pool
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",

@@ -109,6 +109,170 @@ int check_em_desc(const vq_desc* d) {
   return VQ_OK;
 }
 
+// The body of vq_gemv_multi and of its variants with a low-rank adapter (lora != NULL: t_ws is
+// device memory for kLoraWorkspaceFloats floats per problem, t = A x of problem i at slot i).
+int gemv_multi_impl(int count, const vq_desc* descs, const void* const* idx_dev,
+                    const void* const* cb_dev, const void* const* x_f16, void* const* y,
+                    int y_dtype, void* stream, const vq_lora_desc* lora, float* t_ws) {
+  if (count < 1 || count > 65536) return VQ_ERR_BAD_ARG;
+  if (!descs || !idx_dev || !cb_dev || !x_f16 || !y) return VQ_ERR_NULL;
+  if (y_dtype != VQ_F16 && y_dtype != VQ_F32) return VQ_ERR_BAD_ARG;
+  for (int i = 0; i < count; ++i) {
+    const int st = check_desc(&descs[i]);
+    if (st != VQ_OK) return st;
+    if (format_tag(descs[i]) != format_tag(descs[0])) return VQ_ERR_BAD_ARG;
+    if (!idx_dev[i] || !cb_dev[i] || !x_f16[i] || !y[i]) return VQ_ERR_NULL;
+    if (!aligned16(idx_dev[i]) || !aligned16(cb_dev[i]) || !aligned16(x_f16[i]) || !aligned16(y[i]))
+      return VQ_ERR_ALIGN;
+    if (x_f16[i] == (const void*)y[i]) return VQ_ERR_BAD_ARG;
+    if (lora) {
+      const vq_lora_desc& l = lora[i];
+      if (l.rank < 0 || l.rank > kMaxLoraRank || (l.rank & 7)) return VQ_ERR_BAD_ARG;
+      if (l.rank > 0) {
+        if (!l.A_f16 || !l.B_f16) return VQ_ERR_NULL;
+        if (!aligned16(l.A_f16) || !aligned16(l.B_f16)) return VQ_ERR_ALIGN;
+      }
+      const int fmt_i = format_tag(descs[i]);
+      if (fmt_i == kFmtD4 || fmt_i == kFmtK256I8) return VQ_ERR_UNSUPPORTED;
+    }
+  }
+  for (int first = 0; first < count; first += kMaxProblemsPerLaunch) {
+    const int n = count - first < kMaxProblemsPerLaunch ? count - first : kMaxProblemsPerLaunch;
+    long long rb_launch = 0;
+    for (int i = 0; i < n; ++i) rb_launch += descs[first + i].out_features / kGroupRows;
+    int max_n_cb = 0;
+    for (int i = 0; i < n; ++i) {
+      const int c = descs[first + i].in_features / kGroupCols;
+      if (c > max_n_cb) max_n_cb = c;
+    }
+    const int fmt = format_tag(descs[0]);
+    if (lora) {   // t = A x of the launch's problems first, on the same stream
+      static_assert(sizeof(LoraDownBatch) <= 16384, "kernel arguments");
+      LoraDownBatch down;
+      memset(&down, 0, offsetof(LoraDownBatch, p));
+      int rows = 0, m = 0;
+      for (int i = 0; i < n; ++i) {
+        const vq_lora_desc& l = lora[first + i];
+        if (l.rank == 0) continue;
+        LoraDownProblem& dp = down.p[m++];
+        dp.A = (const uint16_t*)l.A_f16;
+        dp.x = (const uint16_t*)x_f16[first + i];
+        dp.t = t_ws + (size_t)(first + i) * kLoraWorkspaceFloats;
+        dp.in_features = descs[first + i].in_features;
+        dp.row_begin = rows;
+        rows += l.rank;
+      }
+      down.count = m;
+      down.total_rows = rows;
+      if (m > 0 && launch_lora_down(down, (hipStream_t)stream) != hipSuccess) return VQ_ERR_HIP;
+    }
+    if (fmt == kFmtD4 || fmt == kFmtK256I8) {   // one workgroup per 64 rows, see vq_gemv_d4.hip
+      GemvBatch batch;
+      memset(&batch, 0, offsetof(GemvBatch, p) + (size_t)n * sizeof(GemvProblem));
+      batch.count = n;
+      batch.y_f32 = (y_dtype == VQ_F32);
+      long long wgs = 0;
+      for (int i = 0; i < n; ++i) {
+        const vq_desc& d = descs[first + i];
+        GemvProblem& p = batch.p[i];
+        p.idx = (const uint8_t*)idx_dev[first + i];
+        p.cb = (const uint32_t*)cb_dev[first + i];
+        p.x = (const uint16_t*)x_f16[first + i];
+        p.y = y[first + i];
+        p.n_rb = d.out_features / kGroupRows;
+        p.n_cb = d.in_features / kGroupCols;
+        p.splits = 1;
+        p.rb_per_cb = d.group_rows / kGroupRows;
+        p.wg_begin = (int32_t)wgs;
+        wgs += p.n_rb / 8;
+      }
+      if (wgs > 0x7fffffffll) return VQ_ERR_UNSUPPORTED;
+      batch.total_wgs = (int32_t)wgs;
+      const hipError_t e = fmt == kFmtD4 ? launch_gemv_d4(batch, (int)wgs, (hipStream_t)stream)
+                                         : launch_gemv_k256i8(batch, (int)wgs, (hipStream_t)stream);
+      if (e != hipSuccess) return VQ_ERR_HIP;
+      continue;
+    }
+    const long long stream_from = 4096;   // row-blocks from which the persistent kernel pays
+    // Split-K kernel: `splits` waves share a row-block.  A wave is most efficient with exactly
+    // one full chunk (its fixed costs are spread over 8 groups and nothing is double-buffered),
+    // so take the fewest waves per row-block whose strips still fit in one chunk, and 8 if no
+    // choice does (measured on the q/k/v, o, gate/up and down launches of a 7B layer).  If every
+    // strip fits in one chunk the one-chunk variant of the kernel is used (half the registers).
+    // 8 waves per row-block (workgroups of 8 waves) pay on the wide matrices: one call on
+    // 11008 x 4096 with k = 256 went from 11.6 to 9.8 us, on 4096 x 11008 from 13.4 to 12.1 us
+    // (k = 16: 7.7 to 7.1 us); 16 waves per row-block were slower again.
+    int splits = 8, one_chunk = 0;
+    {
+      int max_units = 0;
+      for (int i = 0; i < n; ++i) {
+        const int units = strip_units(fmt, descs[first + i].in_features / kGroupCols);
+        max_units = units > max_units ? units : max_units;
+      }
+      const int cu = gemv_chunk_units(fmt);
+      for (int sp = 1; sp <= 8; sp <<= 1) {
+        if ((max_units + sp - 1) / sp <= cu) {
+          splits = sp;
+          break;
+        }
+      }
+      one_chunk = (max_units + splits - 1) / splits <= cu;
+    }
+    const int wpw = splits == 8 ? 8 : 4;   // waves per workgroup of the split-K kernel
+    // many row-blocks: the persistent streaming kernel
+    const bool stream_mode = rb_launch >= stream_from && max_n_cb <= kStreamMaxColBlocks &&
+                             gemv_stream_lds_bytes(fmt, max_n_cb) <= 65536;
+    GemvBatchLora both;                    // 20 KB on the stack; only the used entries are filled
+    GemvBatch& batch = both.base;
+    memset(&batch, 0, offsetof(GemvBatch, p) + (size_t)n * sizeof(GemvProblem));
+    batch.count = n;
+    batch.y_f32 = (y_dtype == VQ_F32);
+    if (lora) {
+      for (int i = 0; i < n; ++i) {
+        LoraProblem& lp = both.l[i];
+        lp.B = (const uint16_t*)lora[first + i].B_f16;
+        lp.t = t_ws + (size_t)(first + i) * kLoraWorkspaceFloats;
+        lp.rank = lora[first + i].rank;
+        lp.pad = 0;
+      }
+    }
+    long long items = 0;   // row-blocks (stream mode) or workgroups (split mode)
+    long long cost = 0;    // groups
+    for (int i = 0; i < n; ++i) {
+      const vq_desc& d = descs[first + i];
+      GemvProblem& p = batch.p[i];
+      p.idx = (const uint8_t*)idx_dev[first + i];
+      p.cb = (const uint32_t*)cb_dev[first + i];
+      p.x = (const uint16_t*)x_f16[first + i];
+      p.y = y[first + i];
+      p.n_rb = d.out_features / kGroupRows;
+      p.n_cb = d.in_features / kGroupCols;
+      p.splits = stream_mode ? 1 : splits;
+      p.rb_per_cb = d.group_rows / kGroupRows;
+      p.wg_begin = (int32_t)items;
+      p.cost_begin = (int32_t)cost;
+      cost += (long long)p.n_rb * p.n_cb;
+      const int rb_per_wg = wpw / p.splits;
+      items += stream_mode ? p.n_rb : (p.n_rb + rb_per_wg - 1) / rb_per_wg;
+    }
+    if (items > 0x7fffffffll || cost > 0x3fffffffll) return VQ_ERR_UNSUPPORTED;
+    batch.total_wgs = (int32_t)items;
+    batch.total_cost = (int32_t)cost;
+    int grid = (int)items;
+    if (stream_mode) {
+      const long long want = (items + 7) / 8;   // at least one row-block per wave
+      const int resident = lora ? gemv_stream_resident_wgs_lora(fmt, max_n_cb) : gemv_stream_resident_wgs(fmt, max_n_cb);
+      grid = (int)(want < resident ? want : resident);
+    }
+    const int mode = stream_mode ? 1 : one_chunk ? 2 : 0;
+    const hipError_t e = lora ? launch_gemv_lora(fmt, both, mode, grid, max_n_cb, (hipStream_t)stream, wpw)
+                              : launch_gemv(fmt, batch, mode, grid, max_n_cb, (hipStream_t)stream, wpw);
+    if (e != hipSuccess) return VQ_ERR_HIP;
+  }
+  return VQ_OK;
+}
+
+
 }  // namespace
 
 extern "C" {
@@ -207,121 +371,33 @@ int vq_pack_layout(const vq_desc* desc, const void* idx_canon, const void* cb_ca
 int vq_gemv_multi(int count, const vq_desc* descs, const void* const* idx_dev,
                   const void* const* cb_dev, const void* const* x_f16, void* const* y,
                   int y_dtype, void* stream) {
+  return gemv_multi_impl(count, descs, idx_dev, cb_dev, x_f16, y, y_dtype, stream, nullptr, nullptr);
+}
+
+int vq_lora_workspace_bytes(int count, size_t* bytes) {
   if (count < 1 || count > 65536) return VQ_ERR_BAD_ARG;
-  if (!descs || !idx_dev || !cb_dev || !x_f16 || !y) return VQ_ERR_NULL;
-  if (y_dtype != VQ_F16 && y_dtype != VQ_F32) return VQ_ERR_BAD_ARG;
-  for (int i = 0; i < count; ++i) {
-    const int st = check_desc(&descs[i]);
-    if (st != VQ_OK) return st;
-    if (format_tag(descs[i]) != format_tag(descs[0])) return VQ_ERR_BAD_ARG;
-    if (!idx_dev[i] || !cb_dev[i] || !x_f16[i] || !y[i]) return VQ_ERR_NULL;
-    if (!aligned16(idx_dev[i]) || !aligned16(cb_dev[i]) || !aligned16(x_f16[i]) || !aligned16(y[i]))
-      return VQ_ERR_ALIGN;
-    if (x_f16[i] == (const void*)y[i]) return VQ_ERR_BAD_ARG;
-  }
-  for (int first = 0; first < count; first += kMaxProblemsPerLaunch) {
-    const int n = count - first < kMaxProblemsPerLaunch ? count - first : kMaxProblemsPerLaunch;
-    long long rb_launch = 0;
-    for (int i = 0; i < n; ++i) rb_launch += descs[first + i].out_features / kGroupRows;
-    int max_n_cb = 0;
-    for (int i = 0; i < n; ++i) {
-      const int c = descs[first + i].in_features / kGroupCols;
-      if (c > max_n_cb) max_n_cb = c;
-    }
-    const int fmt = format_tag(descs[0]);
-    if (fmt == kFmtD4 || fmt == kFmtK256I8) {   // one workgroup per 64 rows, see vq_gemv_d4.hip
-      GemvBatch batch;
-      memset(&batch, 0, offsetof(GemvBatch, p) + (size_t)n * sizeof(GemvProblem));
-      batch.count = n;
-      batch.y_f32 = (y_dtype == VQ_F32);
-      long long wgs = 0;
-      for (int i = 0; i < n; ++i) {
-        const vq_desc& d = descs[first + i];
-        GemvProblem& p = batch.p[i];
-        p.idx = (const uint8_t*)idx_dev[first + i];
-        p.cb = (const uint32_t*)cb_dev[first + i];
-        p.x = (const uint16_t*)x_f16[first + i];
-        p.y = y[first + i];
-        p.n_rb = d.out_features / kGroupRows;
-        p.n_cb = d.in_features / kGroupCols;
-        p.splits = 1;
-        p.rb_per_cb = d.group_rows / kGroupRows;
-        p.wg_begin = (int32_t)wgs;
-        wgs += p.n_rb / 8;
-      }
-      if (wgs > 0x7fffffffll) return VQ_ERR_UNSUPPORTED;
-      batch.total_wgs = (int32_t)wgs;
-      const hipError_t e = fmt == kFmtD4 ? launch_gemv_d4(batch, (int)wgs, (hipStream_t)stream)
-                                         : launch_gemv_k256i8(batch, (int)wgs, (hipStream_t)stream);
-      if (e != hipSuccess) return VQ_ERR_HIP;
-      continue;
-    }
-    const long long stream_from = 4096;   // row-blocks from which the persistent kernel pays
-    // Split-K kernel: `splits` waves share a row-block.  A wave is most efficient with exactly
-    // one full chunk (its fixed costs are spread over 8 groups and nothing is double-buffered),
-    // so take the fewest waves per row-block whose strips still fit in one chunk, and 8 if no
-    // choice does (measured on the q/k/v, o, gate/up and down launches of a 7B layer).  If every
-    // strip fits in one chunk the one-chunk variant of the kernel is used (half the registers).
-    // 8 waves per row-block (workgroups of 8 waves) pay on the wide matrices: one call on
-    // 11008 x 4096 with k = 256 went from 11.6 to 9.8 us, on 4096 x 11008 from 13.4 to 12.1 us
-    // (k = 16: 7.7 to 7.1 us); 16 waves per row-block were slower again.
-    int splits = 8, one_chunk = 0;
-    {
-      int max_units = 0;
-      for (int i = 0; i < n; ++i) {
-        const int units = strip_units(fmt, descs[first + i].in_features / kGroupCols);
-        max_units = units > max_units ? units : max_units;
-      }
-      const int cu = gemv_chunk_units(fmt);
-      for (int sp = 1; sp <= 8; sp <<= 1) {
-        if ((max_units + sp - 1) / sp <= cu) {
-          splits = sp;
-          break;
-        }
-      }
-      one_chunk = (max_units + splits - 1) / splits <= cu;
-    }
-    const int wpw = splits == 8 ? 8 : 4;   // waves per workgroup of the split-K kernel
-    // many row-blocks: the persistent streaming kernel
-    const bool stream_mode = rb_launch >= stream_from && max_n_cb <= kStreamMaxColBlocks &&
-                             gemv_stream_lds_bytes(fmt, max_n_cb) <= 65536;
-    GemvBatch batch;                       // 14 KB on the stack; only the used entries are filled
-    memset(&batch, 0, offsetof(GemvBatch, p) + (size_t)n * sizeof(GemvProblem));
-    batch.count = n;
-    batch.y_f32 = (y_dtype == VQ_F32);
-    long long items = 0;   // row-blocks (stream mode) or workgroups (split mode)
-    long long cost = 0;    // groups
-    for (int i = 0; i < n; ++i) {
-      const vq_desc& d = descs[first + i];
-      GemvProblem& p = batch.p[i];
-      p.idx = (const uint8_t*)idx_dev[first + i];
-      p.cb = (const uint32_t*)cb_dev[first + i];
-      p.x = (const uint16_t*)x_f16[first + i];
-      p.y = y[first + i];
-      p.n_rb = d.out_features / kGroupRows;
-      p.n_cb = d.in_features / kGroupCols;
-      p.splits = stream_mode ? 1 : splits;
-      p.rb_per_cb = d.group_rows / kGroupRows;
-      p.wg_begin = (int32_t)items;
-      p.cost_begin = (int32_t)cost;
-      cost += (long long)p.n_rb * p.n_cb;
-      const int rb_per_wg = wpw / p.splits;
-      items += stream_mode ? p.n_rb : (p.n_rb + rb_per_wg - 1) / rb_per_wg;
-    }
-    if (items > 0x7fffffffll || cost > 0x3fffffffll) return VQ_ERR_UNSUPPORTED;
-    batch.total_wgs = (int32_t)items;
-    batch.total_cost = (int32_t)cost;
-    int grid = (int)items;
-    if (stream_mode) {
-      const long long want = (items + 7) / 8;   // at least one row-block per wave
-      const int resident = gemv_stream_resident_wgs(fmt, max_n_cb);
-      grid = (int)(want < resident ? want : resident);
-    }
-    const hipError_t e = launch_gemv(fmt, batch, stream_mode ? 1 : one_chunk ? 2 : 0, grid, max_n_cb,
-                                     (hipStream_t)stream, wpw);
-    if (e != hipSuccess) return VQ_ERR_HIP;
-  }
+  if (!bytes) return VQ_ERR_NULL;
+  *bytes = (size_t)count * kLoraWorkspaceFloats * sizeof(float);
   return VQ_OK;
+}
+
+int vq_gemv_lora_multi(int count, const vq_desc* descs, const void* const* idx_dev,
+                       const void* const* cb_dev, const void* const* x_f16, const vq_lora_desc* lora,
+                       void* workspace, size_t workspace_bytes, void* const* y, int y_dtype,
+                       void* stream) {
+  if (count < 1 || count > 65536) return VQ_ERR_BAD_ARG;
+  if (!lora || !workspace) return VQ_ERR_NULL;
+  if (!aligned16(workspace)) return VQ_ERR_ALIGN;
+  if (workspace_bytes < (size_t)count * kLoraWorkspaceFloats * sizeof(float)) return VQ_ERR_BAD_ARG;
+  return gemv_multi_impl(count, descs, idx_dev, cb_dev, x_f16, y, y_dtype, stream, lora, (float*)workspace);
+}
+
+int vq_gemv_lora(const vq_desc* desc, const void* idx_dev, const void* cb_dev, const void* x_f16,
+                 const void* A_f16, const void* B_f16, int rank, void* workspace,
+                 size_t workspace_bytes, void* y, int y_dtype, void* stream) {
+  if (!desc) return VQ_ERR_NULL;
+  const vq_lora_desc l = {A_f16, B_f16, rank, 0};
+  return vq_gemv_lora_multi(1, desc, &idx_dev, &cb_dev, &x_f16, &l, workspace, workspace_bytes, &y, y_dtype, stream);
 }
 
 int vq_gemv(const vq_desc* desc, const void* idx_dev, const void* cb_dev, const void* x_f16,

@@ -55,6 +55,35 @@ struct GemvBatch {
   GemvProblem p[kMaxProblemsPerLaunch];
 };
 
+// Low-rank adapter of one problem (y = W x + B (A x)): what the GEMV epilogue needs.
+struct LoraProblem {
+  const uint16_t* B;    // fp16 [out, rank] row-major
+  const float* t;       // t = A x, fp32 [rank] (written by the adapter's first kernel)
+  int32_t rank;         // 0 (no adapter) or a multiple of 8 up to kMaxLoraRank
+  int32_t pad;
+};
+constexpr int kMaxLoraRank = 64;
+constexpr int kLoraWorkspaceFloats = kMaxLoraRank;   // fp32 slots of workspace per problem
+
+struct GemvBatchLora {
+  GemvBatch base;
+  LoraProblem l[kMaxProblemsPerLaunch];
+};
+
+// t = A x of every problem of a launch: one wave per row of A.
+struct LoraDownProblem {
+  const uint16_t* A;    // fp16 [rank, in] row-major
+  const uint16_t* x;    // fp16 [in]
+  float* t;             // fp32 [rank]
+  int32_t in_features;
+  int32_t row_begin;    // rows of A of all earlier problems of the launch
+};
+struct LoraDownBatch {
+  int32_t count;
+  int32_t total_rows;
+  LoraDownProblem p[kMaxProblemsPerLaunch];
+};
+
 // Launchers (each returns the hipError_t of its launch).
 hipError_t launch_pack(const vq_desc& d, const void* idx_canon, const void* cb_canon,
                        void* idx_dev, void* cb_dev, hipStream_t s);
@@ -66,6 +95,12 @@ hipError_t launch_decode(const vq_desc& d, const void* idx_dev, const void* cb_d
 // wpw: waves per workgroup of the split-K kernel (4, or 8 when 8 waves share a row-block).
 hipError_t launch_gemv(int fmt, const GemvBatch& batch, int mode, int grid_wgs,
                        int max_n_cb, hipStream_t s, int wpw);
+// The same kernels with the low-rank adapter term added to every row before it is stored, and
+// the kernel that computes t = A x for the problems of a launch.
+hipError_t launch_gemv_lora(int fmt, const GemvBatchLora& batch, int mode, int grid_wgs,
+                            int max_n_cb, hipStream_t s, int wpw);
+int gemv_stream_resident_wgs_lora(int fmt, int max_n_cb);
+hipError_t launch_lora_down(const LoraDownBatch& batch, hipStream_t s);
 // Dynamic LDS of the persistent GEMV kernel for x of up to max_n_cb col-blocks.
 size_t gemv_stream_lds_bytes(int fmt, int max_n_cb);
 // Workgroups of the persistent GEMV kernel that fit on the current device at once.

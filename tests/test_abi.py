@@ -293,3 +293,38 @@ def test_k256_int8_representation_sizes():
         assert vq.vq_layout_bytes(d) == (out_f * in_f // 2, n_groups * 512 + (2 * n_groups + 15) // 16 * 16)
         assert L.vq_gemv(ctypes.byref(d), A, A, A + 2, A + 16, vq.VQ_F16, 0) == -4
     assert vq.vq_layout_bytes(vq.make_desc(4096, 4096, 256, 8, group_rows=128, codebook_dtype=vq.VQ_I8))[0] * 8 / 4096 ** 2 == 4.0
+
+
+def test_lora_entry_points_validate_on_the_host():
+    """vq_gemv_lora / vq_gemv_lora_multi: rank, workspace and adapter pointers are checked before
+    anything is launched."""
+    L = vq.lib()
+    d = vq.make_desc(4096, 4096, 16, 4)
+    r = ctypes.byref(d)
+    ws = 0x2000
+    assert vq.vq_lora_workspace_bytes(1) == 256 and vq.vq_lora_workspace_bytes(224) == 224 * 256
+    n = ctypes.c_size_t(0)
+    assert L.vq_lora_workspace_bytes(0, ctypes.byref(n)) == -6
+    assert L.vq_lora_workspace_bytes(3, None) == -1
+    good = dict(A=A, B=A, rank=16, ws=ws, nb=256)
+
+    def call(**kw):
+        a = dict(good); a.update(kw)
+        return L.vq_gemv_lora(r, A, A, A, a["A"], a["B"], a["rank"], a["ws"], a["nb"], A + 16, vq.VQ_F16, 0)
+    assert call(rank=12) == -6            # not a multiple of 8
+    assert call(rank=72) == -6            # above 64
+    assert call(rank=-8) == -6
+    assert call(A=0) == -1 and call(B=0) == -1
+    assert call(A=A + 2) == -4 and call(B=A + 8) == -4
+    assert call(ws=0) == -1
+    assert call(ws=ws + 4) == -4
+    assert call(nb=255) == -6             # workspace too small
+    # representations served by kernels of their own do not take an adapter
+    d4 = vq.make_desc(4096, 4096, 256, 8, group_rows=256, d=4, codebook_dtype=vq.VQ_I8)
+    assert L.vq_gemv_lora(ctypes.byref(d4), A, A, A, A, A, 16, ws, 256, A + 16, vq.VQ_F16, 0) == -3
+    k8 = vq.make_desc(4096, 4096, 256, 8, group_rows=128, codebook_dtype=vq.VQ_I8)
+    assert L.vq_gemv_lora(ctypes.byref(k8), A, A, A, A, A, 16, ws, 256, A + 16, vq.VQ_F16, 0) == -3
+    # the descriptor is validated like everywhere else
+    bad = vq.make_desc(4096, 4000, 16, 4)
+    assert L.vq_gemv_lora(ctypes.byref(bad), A, A, A, A, A, 16, ws, 256, A + 16, vq.VQ_F16, 0) == -3
+    assert L.vq_gemv_lora(None, A, A, A, A, A, 16, ws, 256, A + 16, vq.VQ_F16, 0) == -1

@@ -222,7 +222,7 @@ def test_gemv_lora_reduces_to_known_cases():
     np.testing.assert_array_equal(oracle.gemv_lora(f, idx, cb, x, A, np.zeros_like(B)), base)
     u, v = B[:, :1], A[:1, :]
     got = oracle.gemv_lora(f, idx, cb, x, v, u)
-    vx = float(v.astype(np.float64) @ x.astype(np.float64))
+    vx = float((v.astype(np.float64) @ x.astype(np.float64))[0])
     np.testing.assert_allclose(got, base + u[:, 0].astype(np.float64) * vx, rtol=1e-13, atol=1e-13)
     # exact rational check of two rows
     W = oracle.decode_dense(f, idx, cb).view(np.float16)
