@@ -93,13 +93,13 @@ def test_gemv_lora(env, case, f32):
     x = workloads.make_x(s.in_features, seed)
     A, B = _adapter(s, rank, seed)
     n = s.out_features
-    y = torch.full((n + 64,), 12345.0, dtype=torch.float32 if f32 else torch.float16, device="cuda:0")
+    y = torch.full((n + 64,), 12352.0, dtype=torch.float32 if f32 else torch.float16, device="cuda:0")
     ws = torch.full((64 + 16,), float("nan"), dtype=torch.float32, device="cuda:0")     # canary behind the 64 slots
     vq.vq_gemv_lora(desc, idx_d, cb_d, vqdev.to_device_bytes(x), vqdev.to_device_bytes(A), vqdev.to_device_bytes(B),
                     rank, ws, y, vq.VQ_F32 if f32 else vq.VQ_F16, workspace_bytes=256)
     torch.cuda.synchronize()
     out = y.cpu().numpy().astype(np.float64)
-    assert np.all(out[n:] == 12345.0), "wrote past the end of y"
+    assert np.all(out[n:] == 12352.0), "wrote past the end of y"
     assert np.all(np.isnan(ws.cpu().numpy()[rank:])), "wrote workspace slots beyond the rank"
     ref = _ref(base, x, A, B)
     plain = base(x)
