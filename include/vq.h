@@ -192,6 +192,22 @@ VQ_API int vq_gemv_lora_multi(int count, const vq_desc* descs, const void* const
                               void* const* y, int y_dtype, void* stream);
 
 /*
+ * vq_gemv_lora_multi for callers that cannot allocate or carry a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments without the
+ * workspace; t = A x lives in a 64 KB array that is part of the library's code object on every
+ * GPU it runs on (held until the process ends).  count <= 256, otherwise VQ_ERR_BAD_ARG.  The
+ * call allocates nothing.  All calls on one GPU share that array: calls that overlap in time on
+ * one GPU (different streams, or threads) race on it and must be serialised by the caller;
+ * calls on one stream are ordered.  Nothing in the array needs clearing between calls (every
+ * slot that is read has been written by the same call).  Results are bit-identical to
+ * vq_gemv_lora_multi.
+ */
+VQ_API int vq_gemv_lora_multi_static(int count, const vq_desc* descs, const void* const* idx_dev,
+                                     const void* const* cb_dev, const void* const* x_f16,
+                                     const vq_lora_desc* lora, void* const* y, int y_dtype,
+                                     void* stream);
+
+/*
  * Y[out, B] = W X[in, B]  (the batched / prefill form of the same product; a
  * dense contraction, decoded tiles go through LDS to the matrix cores).
  * X is fp16 with row stride ldx >= B elements (batch index contiguous), Y has

@@ -15,7 +15,7 @@ __all__ = [
     "VQDesc", "VQError", "VQ_F16", "VQ_F32", "VQ_I8", "VQ_I8_BN", "lib", "lib_path", "make_desc",
     "vq_status_string", "vq_version", "vq_canonical_bytes", "vq_layout_bytes",
     "vq_pack_layout", "vq_gemv", "vq_gemv_multi", "GemvMultiArgs", "VQLoraDesc", "vq_lora_workspace_bytes", "vq_gemv_lora",
-    "vq_gemv_lora_multi", "vq_gemm_batched", "vq_decode_dense", "vq_em_assign", "vq_em_update",
+    "vq_gemv_lora_multi", "vq_gemv_lora_multi_static", "vq_gemm_batched", "vq_decode_dense", "vq_em_assign", "vq_em_update",
 ]
 
 VQ_F16 = 1
@@ -86,6 +86,9 @@ def lib() -> ctypes.CDLL:
         L.vq_gemv_lora_multi.restype = i32
         L.vq_gemv_lora_multi.argtypes = [i32, dp, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp),
                                          ctypes.POINTER(VQLoraDesc), vp, ctypes.c_size_t, ctypes.POINTER(vp), i32, vp]
+        L.vq_gemv_lora_multi_static.restype = i32
+        L.vq_gemv_lora_multi_static.argtypes = [i32, dp, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp),
+                                                ctypes.POINTER(VQLoraDesc), ctypes.POINTER(vp), i32, vp]
         L.vq_gemm_batched.restype = i32
         L.vq_gemm_batched.argtypes = [dp, vp, vp, vp, i32, i32, vp, i32, i32, vp]
         L.vq_decode_dense.restype = i32
@@ -210,6 +213,17 @@ def vq_gemv_lora_multi(args: GemvMultiArgs, As, Bs, ranks: Sequence[int], worksp
     nb = workspace.numel() * workspace.element_size() if workspace_bytes is None else workspace_bytes
     _check(lib().vq_gemv_lora_multi(n, args.descs, args.idx, args.cb, args.x, lora, _ptr(workspace), nb,
                                     args.y, y_dtype, _stream(stream)), "vq_gemv_lora_multi")
+
+
+def vq_gemv_lora_multi_static(args: GemvMultiArgs, As, Bs, ranks: Sequence[int],
+                              y_dtype: int = VQ_F16, stream=None) -> None:
+    """vq_gemv_lora_multi without a workspace (at most 256 products; allocates nothing)."""
+    n = args.count
+    if not (len(As) == len(Bs) == len(ranks) == n):
+        raise ValueError("vq_gemv_lora_multi_static: argument lists differ in length")
+    lora = (VQLoraDesc * n)(*[VQLoraDesc(_ptr(a), _ptr(b), r, 0) for a, b, r in zip(As, Bs, ranks)])
+    _check(lib().vq_gemv_lora_multi_static(n, args.descs, args.idx, args.cb, args.x, lora, args.y, y_dtype,
+                                           _stream(stream)), "vq_gemv_lora_multi_static")
 
 
 def vq_gemm_batched(desc: VQDesc, idx_dev, cb_dev, X, B: int, ldx: int, Y, ldy: int,

@@ -3,6 +3,7 @@
 // library keeps is a cache of one launch parameter (see gemv_stream_resident_wgs).
 #include <stddef.h>
 #include <string.h>
+#include <atomic>
 #include "vq_internal.h"
 
 namespace {
@@ -109,11 +110,40 @@ int check_em_desc(const vq_desc* d) {
   return VQ_OK;
 }
 
+// Scratch of vq_gemv_lora_multi_static: t = A x of up to kStaticLoraProblems products, in place of
+// the caller's workspace.  One copy per GPU, held until the process ends.  In host code the
+// array's name is only a handle; its device address on the current GPU comes from
+// hipGetSymbolAddress and is what kernels and copies are given.
+constexpr int kStaticLoraProblems = kMaxProblemsPerLaunch;
+static __device__ __align__(256) float scratch[kStaticLoraProblems * kLoraWorkspaceFloats];   // 64 KB
+constexpr int kMaxDevices = 64;
+std::atomic<float*> g_scratch_ptr[kMaxDevices];
+
+// Device address of `scratch` on the current GPU (asked once per device, then cached).
+int static_scratch(float** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) return VQ_ERR_HIP;
+  if (dev < 0 || dev >= kMaxDevices) return VQ_ERR_UNSUPPORTED;
+  float* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!p) {
+    void* sym = nullptr;
+    if (hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch)) != hipSuccess || !sym) {
+      (void)hipGetLastError();
+      return VQ_ERR_HIP;
+    }
+    p = static_cast<float*>(sym);
+    g_scratch_ptr[dev].store(p, std::memory_order_release);   // every thread computes the same address
+  }
+  *out = p;
+  return VQ_OK;
+}
+
 // The body of vq_gemv_multi and of its variants with a low-rank adapter (lora != NULL: t_ws is
 // device memory for kLoraWorkspaceFloats floats per problem, t = A x of problem i at slot i).
 int gemv_multi_impl(int count, const vq_desc* descs, const void* const* idx_dev,
                     const void* const* cb_dev, const void* const* x_f16, void* const* y,
-                    int y_dtype, void* stream, const vq_lora_desc* lora, float* t_ws) {
+                    int y_dtype, void* stream, const vq_lora_desc* lora, float* t_ws,
+                    bool validate_only = false) {
   if (count < 1 || count > 65536) return VQ_ERR_BAD_ARG;
   if (!descs || !idx_dev || !cb_dev || !x_f16 || !y) return VQ_ERR_NULL;
   if (y_dtype != VQ_F16 && y_dtype != VQ_F32) return VQ_ERR_BAD_ARG;
@@ -136,6 +166,7 @@ int gemv_multi_impl(int count, const vq_desc* descs, const void* const* idx_dev,
       if (fmt_i == kFmtD4 || fmt_i == kFmtK256I8) return VQ_ERR_UNSUPPORTED;
     }
   }
+  if (validate_only) return VQ_OK;
   for (int first = 0; first < count; first += kMaxProblemsPerLaunch) {
     const int n = count - first < kMaxProblemsPerLaunch ? count - first : kMaxProblemsPerLaunch;
     long long rb_launch = 0;
@@ -390,6 +421,20 @@ int vq_gemv_lora_multi(int count, const vq_desc* descs, const void* const* idx_d
   if (!aligned16(workspace)) return VQ_ERR_ALIGN;
   if (workspace_bytes < (size_t)count * kLoraWorkspaceFloats * sizeof(float)) return VQ_ERR_BAD_ARG;
   return gemv_multi_impl(count, descs, idx_dev, cb_dev, x_f16, y, y_dtype, stream, lora, (float*)workspace);
+}
+
+int vq_gemv_lora_multi_static(int count, const vq_desc* descs, const void* const* idx_dev,
+                              const void* const* cb_dev, const void* const* x_f16,
+                              const vq_lora_desc* lora, void* const* y, int y_dtype, void* stream) {
+  if (count < 1 || count > kStaticLoraProblems) return VQ_ERR_BAD_ARG;   // beyond the static scratch
+  if (!lora) return VQ_ERR_NULL;
+  float* t_ws = nullptr;
+  // validate everything else first, so that argument errors need no GPU
+  const int st = gemv_multi_impl(count, descs, idx_dev, cb_dev, x_f16, y, y_dtype, stream, lora, nullptr, true);
+  if (st != VQ_OK) return st;
+  const int sp = static_scratch(&t_ws);
+  if (sp != VQ_OK) return sp;
+  return gemv_multi_impl(count, descs, idx_dev, cb_dev, x_f16, y, y_dtype, stream, lora, t_ws, false);
 }
 
 int vq_gemv_lora(const vq_desc* desc, const void* idx_dev, const void* cb_dev, const void* x_f16,
