@@ -233,7 +233,7 @@ int gemv_multi_impl(int count, const vq_desc* descs, const void* const* idx_dev,
     // 8 waves per row-block (workgroups of 8 waves) pay on the wide matrices: one call on
     // 11008 x 4096 with k = 256 went from 11.6 to 9.8 us, on 4096 x 11008 from 13.4 to 12.1 us
     // (k = 16: 7.7 to 7.1 us); 16 waves per row-block were slower again.
-    int splits = 8, one_chunk = 0;
+    int splits = 8, strip_chunks = 0;   // strip_chunks: chunks of the longest strip
     {
       int max_units = 0;
       for (int i = 0; i < n; ++i) {
@@ -247,7 +247,7 @@ int gemv_multi_impl(int count, const vq_desc* descs, const void* const* idx_dev,
           break;
         }
       }
-      one_chunk = (max_units + splits - 1) / splits <= cu;
+      strip_chunks = ((max_units + splits - 1) / splits + cu - 1) / cu;
     }
     const int wpw = splits == 8 ? 8 : 4;   // waves per workgroup of the split-K kernel
     // many row-blocks: the persistent streaming kernel
@@ -295,7 +295,8 @@ int gemv_multi_impl(int count, const vq_desc* descs, const void* const* idx_dev,
       const int resident = lora ? gemv_stream_resident_wgs_lora(fmt, max_n_cb) : gemv_stream_resident_wgs(fmt, max_n_cb);
       grid = (int)(want < resident ? want : resident);
     }
-    const int mode = stream_mode ? 1 : one_chunk ? 2 : 0;
+    // up to three chunks per strip: all loaded at once (modes 2..4); longer strips: two buffers ping-pong
+    const int mode = stream_mode ? 1 : strip_chunks <= 3 ? 1 + strip_chunks : 0;
     const hipError_t e = lora ? launch_gemv_lora(fmt, both, mode, grid, max_n_cb, (hipStream_t)stream, wpw)
                               : launch_gemv(fmt, batch, mode, grid, max_n_cb, (hipStream_t)stream, wpw);
     if (e != hipSuccess) return VQ_ERR_HIP;

@@ -783,13 +783,15 @@ __device__ __forceinline__ void consume_at_priority(const C& chunk, uint32_t* lu
 }
 
 // ---- split-K kernel (few row-blocks) ---------------------------------------
-// ONE: the host guarantees that no strip of the launch is longer than one chunk; the second
-// chunk buffer and its registers disappear, and more workgroups fit on a CU.
+// UP > 0: the host guarantees that no strip of the launch is longer than UP chunks (1, 2 or 3); all
+// of a wave's chunks are then loaded at once, so the wave waits for memory once instead of once
+// per chunk (4096 x 11008 with k = 256: three chunks per wave), and with UP = 1 the second chunk
+// buffer and its registers disappear.  UP = 0: strips of any length, two chunk buffers ping-pong.
 // WPW: waves per workgroup, 4 or 8 (8 when 8 waves share a row-block).
-template <int K, bool ONE, int WPW, bool LORA>
+template <int K, int UP, int WPW, bool LORA>
 __global__ __launch_bounds__(64 * WPW) void gemv_split_kernel(const typename BatchOf<LORA>::type arg) {
   const GemvBatch& batch = base_of(arg);
-  __shared__ __attribute__((aligned(16))) uint32_t lut_all[WPW][(ONE ? 1 : 2) * Chunk<K>::kLutDwords];
+  __shared__ __attribute__((aligned(16))) uint32_t lut_all[WPW][(UP == 1 ? 1 : 2) * Chunk<K>::kLutDwords];
   __shared__ float part[WPW][8];
 
   const int lane = threadIdx.x & 63;
@@ -803,7 +805,7 @@ __global__ __launch_bounds__(64 * WPW) void gemv_split_kernel(const typename Bat
   const int rb = wg_local * rb_per_wg + wave / splits;
   const int split = wave % splits;
   uint32_t* lut_a = lut_all[wave];
-  uint32_t* lut_b = lut_a + (ONE ? 0 : Chunk<K>::kLutDwords);
+  uint32_t* lut_b = lut_a + (UP == 1 ? 0 : Chunk<K>::kLutDwords);
   const uint32_t base_a = lds_addr(lut_a), base_b = lds_addr(lut_b);
 
   float acc[8];
@@ -820,11 +822,23 @@ __global__ __launch_bounds__(64 * WPW) void gemv_split_kernel(const typename Bat
 
   if (rb < P.n_rb) {
     Strip S = make_strip<K>(P, rb, split, splits);
-    if (ONE) {
+    if constexpr (UP == 1) {
       if (S.chunks_left > 0) {
         Chunk<K> A;
         A.load(S, S.u, lane);
         consume_at_priority(A, lut_a, base_a, lane, acc);
+      }
+    } else if constexpr (UP > 1) {
+      if (S.chunks_left > 0) {
+        constexpr int U = Chunk<K>::kUnits;
+        Chunk<K> C[UP];
+#pragma unroll
+        for (int i = 0; i < UP; ++i) C[i].load(S, S.u + i * U, lane);   // past the strip's end: dummy loads, zero data
+        consume_at_priority(C[0], lut_a, base_a, lane, acc);
+        if (S.chunks_left > 1) consume_at_priority(C[1], lut_b, base_b, lane, acc);
+        if constexpr (UP > 2) {
+          if (S.chunks_left > 2) consume_at_priority(C[2], lut_a, base_a, lane, acc);
+        }
       }
     } else if (S.chunks_left > 0) {
       constexpr int U = Chunk<K>::kUnits;
@@ -945,15 +959,23 @@ hipError_t launch_gemv_impl(int fmt, const typename BatchOf<LORA>::type& batch, 
     VQ_FMT_SWITCH(fmt, VQ_F)
 #undef VQ_F
   } else if (mode == 2) {
-#define VQ_F(K)                                                                                      \
-  if (wpw == 8) hipLaunchKernelGGL((gemv_split_kernel<K, true, 8, LORA>), grid, block, 0, s, batch); \
-  else hipLaunchKernelGGL((gemv_split_kernel<K, true, 4, LORA>), grid, block, 0, s, batch)
+#define VQ_F(K)                                                                                   \
+  if (wpw == 8) hipLaunchKernelGGL((gemv_split_kernel<K, 1, 8, LORA>), grid, block, 0, s, batch); \
+  else hipLaunchKernelGGL((gemv_split_kernel<K, 1, 4, LORA>), grid, block, 0, s, batch)
+    VQ_FMT_SWITCH(fmt, VQ_F)
+#undef VQ_F
+  } else if (wpw != 8) {
+    return hipErrorInvalidValue;    // strips longer than one chunk are always shared by 8 waves
+  } else if (mode == 3) {
+#define VQ_F(K) hipLaunchKernelGGL((gemv_split_kernel<K, 2, 8, LORA>), grid, block, 0, s, batch)
+    VQ_FMT_SWITCH(fmt, VQ_F)
+#undef VQ_F
+  } else if (mode == 4) {
+#define VQ_F(K) hipLaunchKernelGGL((gemv_split_kernel<K, 3, 8, LORA>), grid, block, 0, s, batch)
     VQ_FMT_SWITCH(fmt, VQ_F)
 #undef VQ_F
   } else {
-#define VQ_F(K)                                                                                       \
-  if (wpw == 8) hipLaunchKernelGGL((gemv_split_kernel<K, false, 8, LORA>), grid, block, 0, s, batch); \
-  else hipLaunchKernelGGL((gemv_split_kernel<K, false, 4, LORA>), grid, block, 0, s, batch)
+#define VQ_F(K) hipLaunchKernelGGL((gemv_split_kernel<K, 0, 8, LORA>), grid, block, 0, s, batch)
     VQ_FMT_SWITCH(fmt, VQ_F)
 #undef VQ_F
   }

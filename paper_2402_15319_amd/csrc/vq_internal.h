@@ -91,8 +91,10 @@ hipError_t launch_decode(const vq_desc& d, const void* idx_dev, const void* cb_d
                          void* W, hipStream_t s);
 // mode 1: persistent streaming kernel (total_cost/cost_begin are used, grid_wgs workgroups, x
 // of up to max_n_cb col-blocks staged in LDS); mode 0: split-K kernel, wg_begin/total_wgs count
-// workgroups (= grid_wgs); mode 2: split-K kernel for launches whose strips all fit in one chunk;
-// wpw: waves per workgroup of the split-K kernel (4, or 8 when 8 waves share a row-block).
+// workgroups (= grid_wgs); modes 2, 3, 4: split-K kernel for launches whose strips all fit in one,
+// two or three chunks (all of them loaded at once);
+// wpw: waves per workgroup of the split-K kernel (4, or 8 when 8 waves share a row-block; strips
+// longer than one chunk only occur with 8).
 hipError_t launch_gemv(int fmt, const GemvBatch& batch, int mode, int grid_wgs,
                        int max_n_cb, hipStream_t s, int wpw);
 // The same kernels with the low-rank adapter term added to every row before it is stored, and
