@@ -467,10 +467,9 @@ def main():
                               "cold_in_hip_graph_us": us_g, "cold_in_hip_graph_GB/s": nb / us_g / 1e3,
                               "cold_in_hip_graph_frac_hbm": nb / us_g / 1e3 / HBM_PEAK_GBS}
             log(f"[bench] {key}: cold {ms_c * 1e3:.2f} us, hot {ms_h * 1e3:.2f} us, cold in a HIP graph {us_g:.2f} us")
+            # batched / prefill GEMM on the same matrix, next to a dense fp16 GEMM on decoded W
+            Wd = torch.empty((s0.out_features, s0.in_features), dtype=torch.float16, device=dev)
             if key == "mlp_up_11008x4096_k256":
-                # batched / prefill GEMM on the same matrix, next to a dense fp16 GEMM on decoded W
-                Wd = torch.empty((s0.out_features, s0.in_features), dtype=torch.float16, device=dev)
-
                 def decode_cold():
                     a, b = copies[state["i"] % len(copies)]
                     state["i"] += 1
@@ -481,26 +480,28 @@ def main():
                     "us": ms_dec * 1e3, "bytes_in_plus_out": nb_dec, "GB/s": nb_dec / ms_dec / 1e6,
                     "frac_hbm": nb_dec / ms_dec / 1e6 / HBM_PEAK_GBS}
                 log(f"[bench] decode_dense {key}: {ms_dec * 1e3:.1f} us, {nb_dec / ms_dec / 1e6:.0f} GB/s in+out")
-                vq.vq_decode_dense(desc, copies[0][0], copies[0][1], Wd)
-                gemm = {}
-                for B in (16, 256, 2048):
-                    X = torch.randn((s0.in_features, B), device=dev, dtype=torch.float32).half()
-                    Y = torch.empty((s0.out_features, B), dtype=torch.float16, device=dev)
-                    ms_g, _ = timer.run(lambda: vq.vq_gemm_batched(desc, copies[0][0], copies[0][1], X, B, B, Y, B),
-                                        40, 10)
-                    ms_d, _ = timer.run(lambda: torch.matmul(Wd, X, out=Y), 40, 10)
-                    fl = 2.0 * s0.out_features * s0.in_features * B
-                    # the two-step alternative with a caller-owned dense buffer: decode, then dense GEMM
-                    def two_step():
-                        vq.vq_decode_dense(desc, copies[0][0], copies[0][1], Wd)
-                        torch.matmul(Wd, X, out=Y)
-                    ms_2, _ = timer.run(two_step, 40, 10)
-                    gemm[f"B{B}"] = {"us": ms_g * 1e3, "TFLOP/s": fl / ms_g / 1e9,
-                                     "frac_mfma_f16": fl / ms_g / 1e9 / MFMA_F16_PEAK_TFLOPS,
-                                     "dense_fp16_matmul_us": ms_d * 1e3,
-                                     "vq_decode_dense_then_dense_matmul_us": ms_2 * 1e3}
-                    log(f"[bench] gemm B={B}: {ms_g * 1e3:.1f} us vs dense {ms_d * 1e3:.1f} us")
-                extras["gemm_11008x4096_k256"] = gemm
+            vq.vq_decode_dense(desc, copies[0][0], copies[0][1], Wd)
+            gemm = {}
+            for B in (16, 256, 2048):
+                X = torch.randn((s0.in_features, B), device=dev, dtype=torch.float32).half()
+                Y = torch.empty((s0.out_features, B), dtype=torch.float16, device=dev)
+                ms_g, _ = timer.run(lambda: vq.vq_gemm_batched(desc, copies[0][0], copies[0][1], X, B, B, Y, B),
+                                    40, 10)
+                ms_d, _ = timer.run(lambda: torch.matmul(Wd, X, out=Y), 40, 10)
+                fl = 2.0 * s0.out_features * s0.in_features * B
+                # the two-step alternative with a caller-owned dense buffer: decode, then dense GEMM
+                def two_step():
+                    vq.vq_decode_dense(desc, copies[0][0], copies[0][1], Wd)
+                    torch.matmul(Wd, X, out=Y)
+                ms_2, _ = timer.run(two_step, 40, 10)
+                gemm[f"B{B}"] = {"us": ms_g * 1e3, "TFLOP/s": fl / ms_g / 1e9,
+                                 "frac_mfma_f16": fl / ms_g / 1e9 / MFMA_F16_PEAK_TFLOPS,
+                                 "dense_fp16_matmul_us": ms_d * 1e3,
+                                 "vq_decode_dense_then_dense_matmul_us": ms_2 * 1e3}
+                log(f"[bench] gemm {s0.out_features}x{s0.in_features} B={B}: {ms_g * 1e3:.1f} us vs dense {ms_d * 1e3:.1f} us "
+                    f"(decode + dense {ms_2 * 1e3:.1f} us)")
+            extras[f"gemm_{s0.out_features}x{s0.in_features}_k256"] = gemm
+            if key == "mlp_up_11008x4096_k256":
                 # the same product on the 4.125-bit representation of this matrix (k = 256, int8 tables
                 # shared by 128 x 256 groups); timing only, random index and table bytes, scales 2^-8
                 s8 = workloads.CONFIGS["mlp_up_11008x4096_k256_i8"]
@@ -521,7 +522,8 @@ def main():
                                       "frac_mfma_f16": fl / ms_g / 1e9 / MFMA_F16_PEAK_TFLOPS}
                     log(f"[bench] gemm on k=256 int8 tables (4.125 bpv) B={B}: {ms_g * 1e3:.1f} us")
                 extras["gemm_11008x4096_k256_int8_tables_4.125bpv"] = gemm8
-                del Wd, i8, t8
+                del i8, t8
+            del Wd
             del copies
         extras["per_shape_vq_gemv"] = per_shape
 

@@ -14,11 +14,12 @@
  *   - plain C, no C++/torch types; every pointer is a DEVICE pointer unless a
  *     comment says "host";
  *   - the caller owns all buffers; the library allocates nothing.  The only state it
- *     keeps between calls is a process-wide, thread-safe cache of one launch parameter
- *     (how many workgroups of the streaming GEMV kernel fit on the device), filled by an
- *     occupancy query of the HIP runtime the first time a (device, representation, width)
- *     combination is used; that query enqueues nothing, so a first call may be made while
- *     the stream is being captured into a HIP graph;
+ *     keeps between calls is a process-wide, thread-safe cache of launch parameters that
+ *     depend on the device only (its number of compute units, how many workgroups of the
+ *     streaming GEMV kernel fit on it, the address of the scratch array of
+ *     vq_gemv_lora_multi_static), each asked of the HIP runtime the first time it is needed;
+ *     those queries enqueue nothing, so a first call may be made while the stream is being
+ *     captured into a HIP graph;
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream); calls
  *     enqueue work and return without synchronising;
  *   - return value: VQ_OK (0) or a negative vq_status.  Arguments are validated

@@ -1,6 +1,7 @@
 // C ABI of libvq: argument validation on the host, then one launch per call (two for the
 // widest batched products).  Nothing here allocates or synchronises; the only state the
-// library keeps is a cache of one launch parameter (see gemv_stream_resident_wgs).
+// library keeps is a cache of device-dependent launch parameters (compute units, resident
+// workgroups of the streaming kernel, the address of the static adapter scratch).
 #include <stddef.h>
 #include <string.h>
 #include <atomic>

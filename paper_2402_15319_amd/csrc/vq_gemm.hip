@@ -18,6 +18,7 @@
 //     workgroup has 8 waves and twice the rows, the second four waves taking the lower half;
 //   * gemm_tiny_kernel (16 x 16 tiles, a private X tile per wave) and gemm_small_kernel
 //     (32 x 32 tiles, bandwidth-bound batches) copy X the same way.
+#include <atomic>
 #include "vq_device.h"
 #include "vq_internal.h"
 
@@ -753,11 +754,30 @@ hipError_t launch_one(const vq_desc& d, const void* idx_dev, const void* cb_dev,
   return hipGetLastError();
 }
 
+// Compute units of the current device: the 8-wave tiles run one workgroup per CU, so their time
+// moves in whole rounds of that many tiles.  Asked once per device, then cached.
+int device_cus() {
+  static std::atomic<int> cached[64];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) dev = 0;
+  int cus = cached[dev].load(std::memory_order_relaxed);
+  if (cus == 0) {
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) {
+      (void)hipGetLastError();
+      return 256;
+    }
+    cached[dev].store(cus, std::memory_order_relaxed);
+  }
+  return cus;
+}
+
 // Large batches on the 128-row tiles: 128 x 512 tiles decode W once per 512 batch columns instead
 // of once per 256 and take 1.73 times as long as 128 x 256 tiles for twice the area, but a launch
-// pays for whole rounds of 256 workgroups.  So the first m_a tile rows run with 512-column tiles
-// and the rest with 256-column tiles in a second launch, m_a chosen so that both launches fill
-// their rounds best (m_a = 0: 256-column tiles only).  Same units as launch_gemm's estimates.
+// pays for whole rounds of one workgroup per CU.  So the first m_a tile rows run with 512-column
+// tiles and the rest with 256-column tiles in a second launch, m_a chosen so that both launches
+// fill their rounds best (m_a = 0: 256-column tiles only).  Same units as launch_gemm's estimates:
+// microseconds at in_features = 4096, scaled by kscale = in_features / 4096 (a tile's time is its
+// K loop); the 3 us of the second launch do not scale.
 template <int K>
 hipError_t launch_wide(const vq_desc& d, const void* idx_dev, const void* cb_dev, const void* X, int B,
                        int ldx, void* Y, int ldy, int y_f32, hipStream_t s) {
@@ -770,11 +790,13 @@ hipError_t launch_wide(const vq_desc& d, const void* idx_dev, const void* cb_dev
   const int n_rb = d.out_features / kGroupRows;
   const long long rows128 = (n_rb + 15) / 16, cols256 = (B + 255) / 256, cols512 = (B + 511) / 512;
   int m_a = 0;
-  double best = 79.0 * (double)((rows128 * cols256 + 255) / 256);
+  const long long cus = device_cus();
+  const double kscale = (double)d.in_features / 4096.0;
+  double best = 79.0 * kscale * (double)((rows128 * cols256 + cus - 1) / cus);
   for (long long m = 1; m <= rows128; ++m) {
     const long long rest = rows128 - m;
-    const double t = 137.0 * (double)((m * cols512 + 255) / 256) +
-                     (rest > 0 ? 3.0 + 79.0 * (double)((rest * cols256 + 255) / 256) : 0.0);
+    const double t = 137.0 * kscale * (double)((m * cols512 + cus - 1) / cus) +
+                     (rest > 0 ? 3.0 + 79.0 * kscale * (double)((rest * cols256 + cus - 1) / cus) : 0.0);
     if (t < best) {
       best = t;
       m_a = (int)m;
@@ -801,20 +823,24 @@ hipError_t launch_gemm(const vq_desc& d, const void* idx_dev, const void* cb_dev
   // of four tilings by a small cost model: 64 x 128 and 64 x 256 (4 waves, two workgroups per
   // CU: time grows almost linearly with the tile count) and 128 x 128 and 128 x 256 (8 waves, one
   // workgroup per CU: half the X traffic per product, but time moves in whole rounds of 256
-  // tiles).  The constants are microseconds measured at in_features = 4096 on 4096- and
-  // 11008-row matrices, B = 512..4096; only their ratios matter.
+  // one tile per CU).  The constants are microseconds measured at in_features = 4096 on 4096- and
+  // 11008-row matrices, B = 512..4096, on 256 CUs.  A tile's time is its K loop, so every term
+  // scales with in_features and only the ratios matter here; the 4-wave tiles run two per CU, so
+  // their per-tile slope scales with 256 / CUs.
   const int n_rb = d.out_features / kGroupRows;
   const bool short_matrix = n_rb < 1024;
   const bool tiny = B <= 16 || (B <= 32 && short_matrix);
   const long long tiles_small = (long long)((n_rb + 3) / 4) * ((B + 31) / 32);
   const long long rows64 = (n_rb + 7) / 8, rows128 = (n_rb + 15) / 16;
   const long long cols128 = (B + 127) / 128, cols256 = (B + 255) / 256;
-  const bool small = B <= 32 || tiles_small <= 768;
-  const bool one_round_32x128 = rows64 * cols128 <= 128;
-  const double est[4] = {20.0 + 0.11 * (double)(rows64 * cols128),                // 64 x 128
-                         35.0 + 0.165 * (double)(rows64 * cols256),               // 64 x 256
-                         54.0 * (double)((rows128 * cols128 + 255) / 256),        // 128 x 128
-                         79.0 * (double)((rows128 * cols256 + 255) / 256)};       // 128 x 256
+  const long long cus = device_cus();
+  const bool small = B <= 32 || tiles_small <= 3 * cus;
+  const bool one_round_32x128 = rows64 * cols128 <= cus / 2;
+  const double per_cu = 256.0 / (double)cus;
+  const double est[4] = {20.0 + 0.11 * per_cu * (double)(rows64 * cols128),              // 64 x 128
+                         35.0 + 0.165 * per_cu * (double)(rows64 * cols256),             // 64 x 256
+                         54.0 * (double)((rows128 * cols128 + cus - 1) / cus),           // 128 x 128
+                         79.0 * (double)((rows128 * cols256 + cus - 1) / cus)};          // 128 x 256
   int best = 0;
   for (int i = 1; i < 4; ++i)
     if (est[i] < est[best]) best = i;

@@ -29,8 +29,8 @@ def _read_em_case(name):
     return out
 
 
-def _case():
-    c = _read_em_case("em_2x4_k2.txt")
+def _case(name="em_2x4_k2.txt"):
+    c = _read_em_case(name)
     fm = c["format"]
     f = VQFormat(fm["out"], fm["in"], fm["k"], fm["index_bits"], fm["group_rows"], fm["group_cols"], fm["d"])
     W = np.array(c["W"], dtype=np.float32)
@@ -60,6 +60,35 @@ def test_golden_m_step():
     np.testing.assert_allclose(got, want, rtol=1e-15)
     n, d = c["objective_after_num_den"]
     assert abs(oracle.em_objective(f, W, h, got, a) - n / d) < 1e-12
+
+
+@pytest.mark.parametrize("name", ["em_2x4_k2_d1.txt", "em_2x8_k2_d4.txt"])
+def test_golden_e_and_m_step_other_dimensionalities(name):
+    """Scalar codebooks (d = 1) and four-dimensional vectors (d = 4), worked by hand: the weights of
+    the wrong columns, a sum over t that stops at two coordinates, vectors cut at the wrong column
+    stride or an unweighted mean change an assignment, the objective or a centroid."""
+    c, f, W, h, cb = _case(name)
+    a = oracle.em_assign(f, W, h, cb)
+    np.testing.assert_array_equal(a, np.array(c["assign"], dtype=np.int64))
+    assert oracle.em_objective(f, W, h, cb, a) == c["objective"][0]
+    got = oracle.em_update(f, W, h, a)
+    want = (np.array(c["updated_num"]) / np.array(c["updated_den"])).reshape(1, f.k, f.d)
+    np.testing.assert_allclose(got, want, rtol=1e-15)
+
+
+def test_tall_groups_use_their_own_codebook_and_sum_over_all_their_rows():
+    """Two groups of 2 rows x 2 columns stacked (out = 4): the same vector (1,1) is nearest to centroid 0
+    of the upper group and to centroid 1 of the lower one, whose codebook is the upper one's swapped;
+    the M-step of a group averages over both of its rows."""
+    f = VQFormat(4, 2, 2, 4, 2, 2, 2)          # (4 index bits so that a group's two indices fill a byte)
+    W = np.array([[1, 1], [3, 1], [1, 1], [9, 9]], dtype=np.float32)
+    h = np.array([1, 3], dtype=np.float32)
+    cb = np.array([[[0, 0], [10, 10]], [[10, 10], [0, 0]]], dtype=np.float32)
+    a = oracle.em_assign(f, W, h, cb)
+    np.testing.assert_array_equal(a, [[0], [0], [1], [0]])
+    new = oracle.em_update(f, W, h, a)
+    np.testing.assert_array_equal(new[0], [[2, 1], [0, 0]])       # rows 0 and 1 together: ((1+3)/2, (3*1+3*1)/6)
+    np.testing.assert_array_equal(new[1], [[9, 9], [1, 1]])
 
 
 def test_ties_go_to_the_lowest_index_and_empty_clusters_become_zero():
