@@ -230,19 +230,22 @@ VQ_API int vq_decode_dense(const vq_desc* desc, const void* idx_dev, const void*
 
 /*
  * Quantiser side (offline; paragraph "Codebook Initialization"): the two steps of the
- * Hessian-weighted EM that initialises the codebook of every group, for d = 2, 8 x 256 groups
- * and k = 16, 64 or 256 (desc->codebook_dtype is ignored: weights and codebooks are fp32 here).
+ * Hessian-weighted EM that initialises the codebook of every group (desc->codebook_dtype is
+ * ignored: weights and codebooks are fp32 here).  Implemented for d = 1, 2 or 4, k = 4, 8, 16,
+ * 64 or 256, and groups of 1, 8, 16, 32, 64, 128 or 256 rows x 256 columns (one row: k * d <= 64),
+ * which covers the group shapes of every representation the decode side takes; out_features is
+ * a multiple of max(group_rows, 8).
  *
  *   W_f32      fp32 W[out, in], row-major, contiguous
  *   hdiag_f32  fp32 h[in], h[c] = 1 / [H^-1]_cc: the diagonal D of eq. "kmeans_objective"; the
- *              vector on columns c, c+1 uses D_i = diag(h[c], h[c+1])
- *   cb_f32     fp32 cb[g][m][t] in the canonical group order
- *   assign_u8  one byte per vector, assign[r][c/2], row-major (out x in/2 bytes)
+ *              vector on columns c .. c+d-1 uses D_i = diag(h[c], ..., h[c+d-1])
+ *   cb_f32     fp32 cb[g][m][t] in the canonical group order, t < d
+ *   assign_u8  one byte per vector, assign[r][c/d], row-major (out x in/d bytes)
  *
  * vq_em_assign (E-step, eq. "hessian_e_step"; also the VQ_quant operation of Algorithm 2):
- *   assign[r][v] = argmin_m  h[c]*(W[r][c] - cb[g][m][0])^2 + h[c+1]*(W[r][c+1] - cb[g][m][1])^2,
- *   c = 2v, evaluated in binary32 with every operation rounded separately in the order
- *   subtract, square, times weight, add; the lowest m wins a tie.
+ *   assign[r][v] = argmin_m  sum_t h[c+t]*(W[r][c+t] - cb[g][m][t])^2,  c = d*v,
+ *   evaluated in binary32 with every operation rounded separately in the order subtract, square,
+ *   times weight, add (t ascending); the lowest m wins a tie.
  * vq_em_update (M-step, closed form below eq. "hessian_m_step"):
  *   cb_out[g][m][t] = sum h[c+t]*W[r][c+t] / sum h[c+t] over the vectors of group g with
  *   assign = m, and 0 where that sum of weights is 0 (the pseudoinverse of the text: an empty

@@ -104,9 +104,12 @@ int check_em_desc(const vq_desc* d) {
       d->d <= 0 || d->k <= 0 || d->index_bits <= 0 || d->index_bits > 16)
     return VQ_ERR_BAD_DESC;
   if (!is_pow2(d->k) || d->k != (1 << d->index_bits)) return VQ_ERR_BAD_DESC;
-  if (d->d != 2 || d->group_rows != kGroupRows || d->group_cols != kGroupCols) return VQ_ERR_UNSUPPORTED;
-  if (d->k != 16 && d->k != 64 && d->k != 256) return VQ_ERR_UNSUPPORTED;
-  if (d->out_features % kGroupRows || d->in_features % kGroupCols) return VQ_ERR_UNSUPPORTED;
+  if ((d->d != 1 && d->d != 2 && d->d != 4) || d->group_cols != kGroupCols) return VQ_ERR_UNSUPPORTED;
+  if (d->k != 4 && d->k != 8 && d->k != 16 && d->k != 64 && d->k != 256) return VQ_ERR_UNSUPPORTED;
+  const int gr = d->group_rows;
+  if (gr != 1 && gr != 8 && gr != 16 && gr != 32 && gr != 64 && gr != 128 && gr != 256) return VQ_ERR_UNSUPPORTED;
+  if (gr == 1 && d->k * d->d > 64) return VQ_ERR_UNSUPPORTED;   // a codebook per row: small codebooks only
+  if (d->out_features % (gr > kGroupRows ? gr : kGroupRows) || d->in_features % kGroupCols) return VQ_ERR_UNSUPPORTED;
   if ((long long)d->out_features * d->in_features > (1ll << 40)) return VQ_ERR_UNSUPPORTED;
   return VQ_OK;
 }
@@ -486,8 +489,7 @@ int vq_em_assign(const vq_desc* desc, const void* W_f32, const void* hdiag_f32, 
   if (!W_f32 || !hdiag_f32 || !cb_f32 || !assign_u8) return VQ_ERR_NULL;
   if (!aligned16(W_f32) || !aligned16(hdiag_f32) || !aligned16(cb_f32) || !aligned16(assign_u8))
     return VQ_ERR_ALIGN;
-  return hip_status(launch_em_assign(desc->k, desc->out_features, desc->in_features, W_f32, hdiag_f32,
-                                     cb_f32, assign_u8, (hipStream_t)stream));
+  return hip_status(launch_em_assign(*desc, W_f32, hdiag_f32, cb_f32, assign_u8, (hipStream_t)stream));
 }
 
 int vq_em_update(const vq_desc* desc, const void* W_f32, const void* hdiag_f32, const void* assign_u8,
@@ -497,8 +499,7 @@ int vq_em_update(const vq_desc* desc, const void* W_f32, const void* hdiag_f32, 
   if (!W_f32 || !hdiag_f32 || !assign_u8 || !cb_f32_out) return VQ_ERR_NULL;
   if (!aligned16(W_f32) || !aligned16(hdiag_f32) || !aligned16(assign_u8) || !aligned16(cb_f32_out))
     return VQ_ERR_ALIGN;
-  return hip_status(launch_em_update(desc->k, desc->out_features, desc->in_features, W_f32, hdiag_f32,
-                                     assign_u8, cb_f32_out, (hipStream_t)stream));
+  return hip_status(launch_em_update(*desc, W_f32, hdiag_f32, assign_u8, cb_f32_out, (hipStream_t)stream));
 }
 
 }  // extern "C"

@@ -6,8 +6,10 @@
 //   M-step:  c_m[t] = sum_{i in I_m} h[c_i+t] * x_i[t] / sum_{i in I_m} h[c_i+t]   (0 if the sum of weights is 0)
 //
 // with x_i = W[r, c .. c+d-1] and h[c] = 1 / [H^-1]_cc, the diagonal weight of column c.
-// d = 2, groups of 8 x 256 weights.  One wave per group, lane L owns columns 4L .. 4L+3 (two
-// vectors) of the group's 8 rows, exactly as in the matrix-vector kernels.
+// em_assign_kernel / em_update_kernel: d = 2, groups of 8 x 256 weights.  One wave per group, lane
+// L owns columns 4L .. 4L+3 (two vectors) of the group's 8 rows, exactly as in the matrix-vector
+// kernels.  em_assign_any_kernel / em_update_any_kernel: d = 1, 2 or 4 and groups of 1, 8, 16, ...
+// 256 rows x 256 columns (every group shape the decode formats use), the same lane ownership.
 //
 // The E-step is a decision taken in floating point, so its arithmetic is fixed: binary32,
 // every operation rounded on its own (no fused multiply-add), in the order subtract, square,
@@ -140,35 +142,253 @@ __global__ __launch_bounds__(128) void em_update_kernel(const float* __restrict_
   }
 }
 
+
+// ---- any dimensionality and group height ---------------------------------------------------
+// E-step.  One wave per (8-row block, col-block); the codebook is that of the group the block
+// lies in, or (PR: groups of one row) one codebook per row.  D values per centroid, 4 / D vectors
+// per row and lane.  Same arithmetic as em_assign_kernel: unfused binary32, sum over t in order.
+template <int K, int D, bool PR>
+__global__ __launch_bounds__(256) void em_assign_any_kernel(const float* __restrict__ W,
+                                                            const float* __restrict__ hdiag,
+                                                            const float* __restrict__ cb,
+                                                            uint8_t* __restrict__ assign, int n_cb,
+                                                            long long n_blocks, int in_features,
+                                                            int group_rows) {
+#pragma clang fp contract(off)
+  constexpr int V = 4 / D;                 // vectors per row and lane
+  constexpr int NCB = PR ? 8 : 1;          // codebooks a wave works with
+  __shared__ __attribute__((aligned(16))) float cbs_all[4][NCB * K * D];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  float* cbs = cbs_all[wave];
+  const long long b = (long long)blockIdx.x * 4 + wave;
+  if (b >= n_blocks) return;   // whole waves leave; no workgroup barrier below
+  const long long rb = b / n_cb;
+  const int c = (int)(b - rb * n_cb);
+
+#pragma unroll
+  for (int q = 0; q < NCB; ++q) {
+    const long long g = PR ? (rb * 8 + q) * n_cb + c : (rb * 8 / group_rows) * n_cb + c;
+    const float* cg = cb + g * (K * D);
+    for (int i = lane; i < K * D; i += 64) cbs[q * K * D + i] = cg[i];
+  }
+  const float4 h4 = *reinterpret_cast<const float4*>(hdiag + (size_t)c * 256 + lane * 4);
+  const float h[4] = {h4.x, h4.y, h4.z, h4.w};
+  float x[8][4];
+#pragma unroll
+  for (int r = 0; r < 8; ++r) {
+    const float4 t = *reinterpret_cast<const float4*>(W + (size_t)(rb * 8 + r) * in_features + (size_t)c * 256 + lane * 4);
+    x[r][0] = t.x; x[r][1] = t.y; x[r][2] = t.z; x[r][3] = t.w;
+  }
+  wave_lds_sync();
+
+  float best[8 * V];
+  uint32_t arg[8 * V];
+#pragma unroll
+  for (int v = 0; v < 8 * V; ++v) {
+    best[v] = __builtin_inff();
+    arg[v] = 0;
+  }
+  for (int m = 0; m < K; ++m) {
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+      const float* cm = cbs + (PR ? r * K * D : 0) + m * D;   // the same address in every lane: broadcast reads
+#pragma unroll
+      for (int v = 0; v < V; ++v) {
+        const float e0 = x[r][v * D] - cm[0];
+        float dist = h[v * D] * (e0 * e0);
+#pragma unroll
+        for (int t = 1; t < D; ++t) {
+          const float e = x[r][v * D + t] - cm[t];
+          dist = dist + h[v * D + t] * (e * e);
+        }
+        if (dist < best[r * V + v]) { best[r * V + v] = dist; arg[r * V + v] = m; }
+      }
+    }
+  }
+#pragma unroll
+  for (int r = 0; r < 8; ++r) {
+    uint8_t* a = assign + (size_t)(rb * 8 + r) * (in_features / D) + (size_t)c * (256 / D) + lane * V;
+    if constexpr (V == 4)
+      *reinterpret_cast<uint32_t*>(a) = arg[4 * r] | (arg[4 * r + 1] << 8) | (arg[4 * r + 2] << 16) | (arg[4 * r + 3] << 24);
+    else if constexpr (V == 2)
+      *reinterpret_cast<uint16_t*>(a) = (uint16_t)(arg[2 * r] | (arg[2 * r + 1] << 8));
+    else
+      *a = (uint8_t)arg[r];
+  }
+}
+
+// M-step.  One wave per group of n_rows rows (group_rows, or 1) x 256 columns.  A lane keeps the
+// partial sums of 64 quantities in its LDS row: (numerator[D], weight[D]) of 32 / D centroids; the
+// group's rows are walked once per such set of centroids (row after row, a lane's vectors left to
+// right), then lane q sums quantity q over the 64 lanes in lane order: a fixed order, deterministic.
+template <int K, int D>
+__global__ __launch_bounds__(128) void em_update_any_kernel(const float* __restrict__ W,
+                                                            const float* __restrict__ hdiag,
+                                                            const uint8_t* __restrict__ assign,
+                                                            float* __restrict__ cb_out, int n_cb,
+                                                            long long n_groups, int in_features,
+                                                            int n_rows) {
+  constexpr int V = 4 / D;
+  constexpr int CP = 32 / D;               // centroids per pass
+  __shared__ __attribute__((aligned(16))) float red_all[2][64 * kRedStride];
+  __shared__ float tot_all[2][64];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  float* red = red_all[wave];
+  float* tot = tot_all[wave];
+  const long long g = (long long)blockIdx.x * 2 + wave;
+  if (g >= n_groups) return;   // whole waves leave; no workgroup barrier below
+  const long long gr = g / n_cb;
+  const int c = (int)(g - gr * n_cb);
+  const long long row0 = gr * n_rows;
+
+  const float4 h4 = *reinterpret_cast<const float4*>(hdiag + (size_t)c * 256 + lane * 4);
+  const float h[4] = {h4.x, h4.y, h4.z, h4.w};
+  float* row = red + lane * kRedStride;
+  for (int m0 = 0; m0 < K; m0 += CP) {
+#pragma unroll
+    for (int j = 0; j < 64; ++j) row[j] = 0.f;
+    for (int r = 0; r < n_rows; ++r) {
+      const float4 t = *reinterpret_cast<const float4*>(W + (size_t)(row0 + r) * in_features + (size_t)c * 256 + lane * 4);
+      const float x[4] = {t.x, t.y, t.z, t.w};
+      const uint8_t* ap = assign + (size_t)(row0 + r) * (in_features / D) + (size_t)c * (256 / D) + lane * V;
+      uint32_t a[V];
+      if constexpr (V == 4) {
+        const uint32_t w = *reinterpret_cast<const uint32_t*>(ap);
+        a[0] = w & 0xffu; a[1] = (w >> 8) & 0xffu; a[2] = (w >> 16) & 0xffu; a[3] = w >> 24;
+      } else if constexpr (V == 2) {
+        const uint32_t w = *reinterpret_cast<const uint16_t*>(ap);
+        a[0] = w & 0xffu; a[1] = w >> 8;
+      } else {
+        a[0] = *ap;
+      }
+#pragma unroll
+      for (int v = 0; v < V; ++v) {
+        const uint32_t j = a[v] - m0;
+        if (j < (uint32_t)CP && a[v] < (uint32_t)K) {   // also keeps an out-of-range assignment byte out of the table
+          float* slot = row + j * 2 * D;
+#pragma unroll
+          for (int tt = 0; tt < D; ++tt) {
+            slot[tt] += h[v * D + tt] * x[v * D + tt];
+            slot[D + tt] += h[v * D + tt];
+          }
+        }
+      }
+    }
+    wave_lds_sync();
+    float s = 0.f;
+    for (int l = 0; l < 64; ++l) s += red[l * kRedStride + lane];
+    tot[lane] = s;
+    wave_lds_sync();
+    if (lane < CP * D) {
+      const int j = lane / D, t = lane % D;
+      if (m0 + j < K) {
+        const float num = tot[j * 2 * D + t], den = tot[j * 2 * D + D + t];
+        cb_out[(g * K + m0 + j) * D + t] = den != 0.f ? num / den : 0.f;
+      }
+    }
+    wave_lds_sync();   // tot and red are rewritten by the next set of centroids
+  }
+}
+
 }  // namespace
 
-hipError_t launch_em_assign(int k, int out_features, int in_features, const void* W, const void* hdiag,
-                            const void* cb, void* assign, hipStream_t s) {
+// Calls F(K) for the codebook size k (4, 8, 16, 64 or 256).
+#define VQ_EM_K_SWITCH(k, F) \
+  switch (k) {               \
+    case 4: F(4); break;     \
+    case 8: F(8); break;     \
+    case 16: F(16); break;   \
+    case 64: F(64); break;   \
+    default: F(256); break;  \
+  }
+
+hipError_t launch_em_assign(const vq_desc& d, const void* W, const void* hdiag, const void* cb, void* assign,
+                            hipStream_t s) {
+  const int k = d.k, out_features = d.out_features, in_features = d.in_features;
   const int n_cb = in_features / kGroupCols;
-  const long long n_groups = (long long)(out_features / kGroupRows) * n_cb;
-  const unsigned grid = (unsigned)((n_groups + 3) / 4);
+  const long long n_blocks = (long long)(out_features / kGroupRows) * n_cb;
+  const unsigned grid = (unsigned)((n_blocks + 3) / 4);
+  if (d.d == 2 && d.group_rows == kGroupRows && (k == 16 || k == 64 || k == 256)) {
 #define VQ_EM(K)                                                                                   \
   hipLaunchKernelGGL(em_assign_kernel<K>, dim3(grid), dim3(256), 0, s, (const float*)W,            \
-                     (const float*)hdiag, (const float*)cb, (uint8_t*)assign, n_cb, n_groups, in_features)
-  if (k == 16) VQ_EM(16);
-  else if (k == 64) VQ_EM(64);
-  else VQ_EM(256);
+                     (const float*)hdiag, (const float*)cb, (uint8_t*)assign, n_cb, n_blocks, in_features)
+    if (k == 16) VQ_EM(16);
+    else if (k == 64) VQ_EM(64);
+    else VQ_EM(256);
 #undef VQ_EM
+    return hipGetLastError();
+  }
+#define VQ_EM_ANY(K, D, PR)                                                                              \
+  hipLaunchKernelGGL((em_assign_any_kernel<K, D, PR>), dim3(grid), dim3(256), 0, s, (const float*)W,     \
+                     (const float*)hdiag, (const float*)cb, (uint8_t*)assign, n_cb, n_blocks, in_features, \
+                     d.group_rows)
+  if (d.group_rows == 1) {   // a codebook per row: k * d <= 64 (checked by the caller)
+    if (d.d == 1) {
+#define VQ_F(K) if constexpr (K <= 64) VQ_EM_ANY(K, 1, true)
+      VQ_EM_K_SWITCH(k, VQ_F)
+#undef VQ_F
+    } else if (d.d == 2) {
+#define VQ_F(K) if constexpr (K <= 16) VQ_EM_ANY(K, 2, true)
+      VQ_EM_K_SWITCH(k, VQ_F)
+#undef VQ_F
+    } else {
+#define VQ_F(K) if constexpr (K <= 16) VQ_EM_ANY(K, 4, true)
+      VQ_EM_K_SWITCH(k, VQ_F)
+#undef VQ_F
+    }
+  } else if (d.d == 1) {
+#define VQ_F(K) VQ_EM_ANY(K, 1, false)
+    VQ_EM_K_SWITCH(k, VQ_F)
+#undef VQ_F
+  } else if (d.d == 2) {
+#define VQ_F(K) VQ_EM_ANY(K, 2, false)
+    VQ_EM_K_SWITCH(k, VQ_F)
+#undef VQ_F
+  } else {
+#define VQ_F(K) VQ_EM_ANY(K, 4, false)
+    VQ_EM_K_SWITCH(k, VQ_F)
+#undef VQ_F
+  }
+#undef VQ_EM_ANY
   return hipGetLastError();
 }
 
-hipError_t launch_em_update(int k, int out_features, int in_features, const void* W, const void* hdiag,
-                            const void* assign, void* cb_out, hipStream_t s) {
+hipError_t launch_em_update(const vq_desc& d, const void* W, const void* hdiag, const void* assign,
+                            void* cb_out, hipStream_t s) {
+  const int k = d.k, out_features = d.out_features, in_features = d.in_features;
   const int n_cb = in_features / kGroupCols;
-  const long long n_groups = (long long)(out_features / kGroupRows) * n_cb;
+  const long long n_groups = (long long)(out_features / d.group_rows) * n_cb;
   const unsigned grid = (unsigned)((n_groups + 1) / 2);
+  if (d.d == 2 && d.group_rows == kGroupRows && (k == 16 || k == 64 || k == 256)) {
 #define VQ_EM(K)                                                                                   \
   hipLaunchKernelGGL(em_update_kernel<K>, dim3(grid), dim3(128), 0, s, (const float*)W,            \
                      (const float*)hdiag, (const uint8_t*)assign, (float*)cb_out, n_cb, n_groups, in_features)
-  if (k == 16) VQ_EM(16);
-  else if (k == 64) VQ_EM(64);
-  else VQ_EM(256);
+    if (k == 16) VQ_EM(16);
+    else if (k == 64) VQ_EM(64);
+    else VQ_EM(256);
 #undef VQ_EM
+    return hipGetLastError();
+  }
+#define VQ_EM_ANY(K, D)                                                                                   \
+  hipLaunchKernelGGL((em_update_any_kernel<K, D>), dim3(grid), dim3(128), 0, s, (const float*)W,          \
+                     (const float*)hdiag, (const uint8_t*)assign, (float*)cb_out, n_cb, n_groups, in_features, \
+                     d.group_rows)
+  if (d.d == 1) {
+#define VQ_F(K) VQ_EM_ANY(K, 1)
+    VQ_EM_K_SWITCH(k, VQ_F)
+#undef VQ_F
+  } else if (d.d == 2) {
+#define VQ_F(K) VQ_EM_ANY(K, 2)
+    VQ_EM_K_SWITCH(k, VQ_F)
+#undef VQ_F
+  } else {
+#define VQ_F(K) VQ_EM_ANY(K, 4)
+    VQ_EM_K_SWITCH(k, VQ_F)
+#undef VQ_F
+  }
+#undef VQ_EM_ANY
   return hipGetLastError();
 }
 

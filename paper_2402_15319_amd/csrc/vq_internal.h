@@ -117,10 +117,11 @@ hipError_t launch_gemm(const vq_desc& d, const void* idx_dev, const void* cb_dev
                        const void* X, int B, int ldx, void* Y, int ldy, int y_f32,
                        hipStream_t s);
 
-// E- and M-step of the codebook initialisation (d = 2, 8 x 256 groups, k in {16, 64, 256}).
-hipError_t launch_em_assign(int k, int out_features, int in_features, const void* W, const void* hdiag,
-                            const void* cb, void* assign, hipStream_t s);
-hipError_t launch_em_update(int k, int out_features, int in_features, const void* W, const void* hdiag,
-                            const void* assign, void* cb_out, hipStream_t s);
+// E- and M-step of the codebook initialisation (d in {1, 2, 4}, k in {4, 8, 16, 64, 256}, groups
+// of 1, 8, 16, 32, 64, 128 or 256 rows x 256 columns; one row only with k * d <= 64).
+hipError_t launch_em_assign(const vq_desc& d, const void* W, const void* hdiag, const void* cb,
+                            void* assign, hipStream_t s);
+hipError_t launch_em_update(const vq_desc& d, const void* W, const void* hdiag, const void* assign,
+                            void* cb_out, hipStream_t s);
 
 }  // namespace vq

@@ -216,8 +216,15 @@ def test_quantiser_entry_points_validate_before_launch():
     assert L.vq_em_assign(r, A, A + 4, A, A, 0) == -4
     assert L.vq_em_update(r, A, A, 0, A, 0) == -1
     assert L.vq_em_update(r, A + 8, A, A, A, 0) == -4
-    for bad in (vq.make_desc(4096, 4096, 16, 4, d=1), vq.make_desc(4096, 4096, 64, 6, group_rows=32),
-                vq.make_desc(4096, 4096, 4, 2), vq.make_desc(4100, 4096, 16, 4)):
+    # every group shape of the decode formats is taken, validated like the 8 x 256 case
+    for ok in (vq.make_desc(4096, 4096, 16, 4, d=1), vq.make_desc(4096, 4096, 64, 6, group_rows=32),
+               vq.make_desc(4096, 4096, 4, 2, group_rows=1, d=1), vq.make_desc(4096, 4096, 8, 3, group_rows=32, d=1),
+               vq.make_desc(4096, 4096, 256, 8, group_rows=128), vq.make_desc(4096, 4096, 256, 8, group_rows=256, d=4)):
+        assert L.vq_em_assign(ctypes.byref(ok), A, A + 4, A, A, 0) == -4
+        assert L.vq_em_update(ctypes.byref(ok), A, A, 0, A, 0) == -1
+    for bad in (vq.make_desc(4096, 4096, 16, 4, d=8), vq.make_desc(4096, 4096, 64, 6, group_rows=24),
+                vq.make_desc(4096, 4096, 2, 1), vq.make_desc(4100, 4096, 16, 4), vq.make_desc(4096, 4096, 64, 6, group_rows=1),
+                vq.make_desc(4096 + 64, 4096, 256, 8, group_rows=128), vq.make_desc(4096, 4096, 16, 4, group_cols=128)):
         assert L.vq_em_assign(ctypes.byref(bad), A, A, A, A, 0) == -3
         assert L.vq_em_update(ctypes.byref(bad), A, A, A, A, 0) == -3
     assert L.vq_em_assign(ctypes.byref(vq.make_desc(4096, 4096, 32, 4)), A, A, A, A, 0) == -2

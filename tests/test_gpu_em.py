@@ -158,3 +158,93 @@ def test_full_size_layer(env):
         want = oracle.em_update(sub, W[rb * 8:(rb + 1) * 8, c * 256:(c + 1) * 256], h[c * 256:(c + 1) * 256],
                                 a[rb * 8:(rb + 1) * 8, c * 128:(c + 1) * 128])
         assert np.abs(new[g] - want[0]).max() <= 1.5e-4 * np.abs(W).max()
+
+
+# ---------------------------------------------------------------- other dimensionalities and group heights
+def _inputs_any(out_f, in_f, k, d, group_rows, seed, from_data=True):
+    rng = np.random.default_rng(seed)
+    W = rng.normal(0, 0.02, (out_f, in_f)).astype(np.float32)
+    h = rng.uniform(0.2, 5.0, in_f).astype(np.float32)
+    n_cb = in_f // 256
+    n_groups = (out_f // group_rows) * n_cb
+    if from_data:
+        cb = np.zeros((n_groups, k, d), dtype=np.float32)
+        for g in range(n_groups):
+            gr, c = divmod(g, n_cb)
+            X = W[gr * group_rows:(gr + 1) * group_rows, c * 256:(c + 1) * 256].reshape(-1, d)
+            cb[g] = X[rng.choice(X.shape[0], size=k, replace=X.shape[0] < k)]
+    else:
+        cb = rng.normal(0, 0.02, (n_groups, k, d)).astype(np.float32)
+    return W, h, cb
+
+
+# (out, in, k, d, group_rows): the group shapes of the decode formats, with block counts that are not
+# multiples of the waves of a workgroup
+ANY_SHAPES = [
+    (8, 256, 16, 1, 8), (40, 768, 16, 1, 8),          # scalar codebooks, 4-bit
+    (64, 512, 8, 1, 32), (96, 256, 8, 1, 16),         # 3-bit, 32- and 16-row groups
+    (8, 512, 4, 1, 1), (24, 768, 4, 1, 1),            # 2-bit, a codebook per row
+    (64, 512, 64, 2, 32), (48, 256, 64, 2, 16),       # d = 2 with taller groups
+    (256, 512, 256, 2, 128), (64, 256, 256, 2, 64),
+    (128, 512, 256, 4, 64), (256, 256, 256, 4, 256), (256, 768, 256, 4, 128),   # four-dimensional vectors
+    (16, 256, 16, 4, 8), (8, 256, 4, 2, 1),           # combinations no decode format uses, same kernels
+]
+
+
+def _gpu_em_any(env, shape, W, h, cb):
+    torch, vq, vqdev = env
+    out_f, in_f, k, d, gr = shape
+    bits = {4: 2, 8: 3, 16: 4, 64: 6, 256: 8}[k]
+    desc = vq.make_desc(out_f, in_f, k, bits, group_rows=gr, d=d)
+    a = torch.full((out_f, in_f // d), 255, dtype=torch.uint8, device="cuda:0")
+    W_d, h_d = vqdev.to_device_bytes(W), vqdev.to_device_bytes(h)
+    vq.vq_em_assign(desc, W_d, h_d, vqdev.to_device_bytes(cb), a)
+    new = torch.full(cb.shape, 777.0, dtype=torch.float32, device="cuda:0")
+    vq.vq_em_update(desc, W_d, h_d, a, new)
+    torch.cuda.synchronize()
+    return a.cpu().numpy(), new.cpu().numpy()
+
+
+@pytest.mark.parametrize("shape", ANY_SHAPES, ids=str)
+def test_e_and_m_step_any_dimensionality_and_group_height(env, shape):
+    """E-step bit for bit; M-step (on the E-step's own assignments) within the binary32 summation
+    bound: a lane sums at most n / 64 terms one after the other, then 64 lane totals are added, so the
+    error is at most (n / 64 + 64) * 2^-24 relative to the sum of magnitudes, for numerator and
+    denominator each; with weights within a factor 25 of each other that is below
+    (n / 64 + 64) * 2^-24 * 2 * 25 * max|W| -- the test uses that bound, which is 1.5e-4 max|W| for the
+    8 x 256 groups."""
+    out_f, in_f, k, d, gr = shape
+    # big codebooks start from random centroids, so that some clusters stay empty
+    W, h, cb = _inputs_any(out_f, in_f, k, d, gr, 1200 + out_f + k + d, from_data=(k < 256))
+    f = oracle.VQFormat(out_f, in_f, k, 8, gr, 256, d)
+    want_a = oracle.em_assign(f, W, h, cb)
+    a, new = _gpu_em_any(env, shape, W, h, cb)
+    np.testing.assert_array_equal(a, want_a)
+    want = oracle.em_update(f, W, h, want_a)
+    n = gr * 256 // d
+    bound = max(1.5e-4, (n / 64 + 64) * 2.0 ** -24 * 50) * np.abs(W).max()
+    assert np.abs(new - want).max() <= bound
+    n_cb = in_f // 256
+    counts = np.zeros((f.n_groups, k), dtype=np.int64)
+    for g in range(f.n_groups):
+        gi, c = divmod(g, n_cb)
+        counts[g] = np.bincount(want_a[gi * gr:(gi + 1) * gr, c * (256 // d):(c + 1) * (256 // d)].reshape(-1), minlength=k)
+    assert np.all(new[counts == 0] == 0.0)
+
+
+def test_em_rounds_on_a_deployed_group_shape(env):
+    """Four E/M rounds with k = 64, 32 x 256 groups (the deployed representation's groups): each
+    E-step equals the oracle's on the GPU's own centroids, the objective never rises."""
+    shape = (64, 512, 64, 2, 32)
+    out_f, in_f, k, d, gr = shape
+    W, h, cb = _inputs_any(out_f, in_f, k, d, gr, 1300)
+    f = oracle.VQFormat(out_f, in_f, k, 6, gr, 256, d)
+    last = np.inf
+    for _ in range(4):
+        a, new = _gpu_em_any(env, shape, W, h, cb)
+        np.testing.assert_array_equal(a, oracle.em_assign(f, W, h, cb))
+        obj_e = oracle.em_objective(f, W, h, cb, a)
+        assert obj_e <= last * (1 + 1e-6)
+        cb = new
+        last = oracle.em_objective(f, W, h, cb, a)
+        assert last <= obj_e * (1 + 1e-6)
