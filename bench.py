@@ -31,9 +31,10 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled by a copy kernel of known size; the summary
 # and the commands are in profiles/gemv_stream_k16_llama7b_pass.md.  The figure belongs to one
 # build of the kernel: it is reported only while the library still has the version it was
-# measured on (vq_version() is raised whenever a kernel or the device layout changes).
-TRAFFIC_BYTES_PER_LAUNCH = 1857648128
-TRAFFIC_MEASURED_ON_VERSION = 1
+# measured on (vq_version() is raised whenever a kernel, the device layout or the set of entry
+# points changes).
+TRAFFIC_BYTES_PER_LAUNCH = 1857737421
+TRAFFIC_MEASURED_ON_VERSION = 2
 MFMA_F16_PEAK_TFLOPS = 2500.0  # MI355X published dense fp16 matrix peak
 FP32_VECTOR_PEAK_TFLOPS = 157.3   # published fp32 vector peak (fused multiply-add = 2 flops)
 

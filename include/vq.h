@@ -109,7 +109,8 @@ typedef struct vq_desc {
 /* Human-readable name of a status code (host pointer to a static string). */
 VQ_API const char* vq_status_string(int status);
 
-/* Library ABI version (increments when a signature or the device layout changes). */
+/* Library version: increments when an entry point is added, a signature or the device layout
+ * changes, or a kernel of the decode path is rewritten (measurements quote the version). */
 VQ_API int vq_version(void);
 
 /*

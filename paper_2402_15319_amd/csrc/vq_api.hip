@@ -326,7 +326,7 @@ const char* vq_status_string(int status) {
   }
 }
 
-int vq_version(void) { return 1; }
+int vq_version(void) { return 2; }
 
 int vq_canonical_bytes(const vq_desc* desc, size_t* idx_bytes, size_t* cb_bytes) {
   // The canonical format is defined for any consistent descriptor, also ones the
