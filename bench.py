@@ -391,7 +391,33 @@ def main():
                 "us_per_launch": ms_lw * 1e3 / len(seq), "tokens_per_s_weight_stream": 1e3 / ms_lw}
             log(f"[bench] pass as {len(seq)} launches (qkv | o | gate,up | down) in a HIP graph: "
                 f"{ms_lw * 1e3:.1f} us/step")
-            del graph, seq
+            del graph
+
+            # the same sequence with a rank-16 adapter next to every matrix (y = W x + B (A x)):
+            # each step is two launches (t = A x, then the product with the adapter term); the
+            # entry point without a workspace, so the graph captures no allocation
+            rank = 16
+            lA = {n: (torch.randn((rank, n), device=dev) / n ** 0.5).half() for n in (4096, 11008)}
+            lB = {n: (torch.randn((n, rank), device=dev) * 0.02).half() for n in (4096, 11008)}
+            lsel = [[7 * l + i for i in sel] for l in range(args.layers) for sel in ((0, 1, 2), (3,), (4, 5), (6,))]
+            lAs = [[lA[mats[i][1].in_features] for i in ii] for ii in lsel]
+            lBs = [[lB[mats[i][1].out_features] for i in ii] for ii in lsel]
+
+            def step_layerwise_lora():
+                for a, As, Bs in zip(seq, lAs, lBs):
+                    vq.vq_gemv_lora_multi_static(a, As, Bs, [rank] * a.count)
+            step_layerwise_lora()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                step_layerwise_lora()
+            ms_ll, _ = timer.run(graph.replay, max(2, args.steps // 4), 3)
+            lora_bytes = sum(2 * rank * (mats[i][1].in_features + mats[i][1].out_features) for ii in lsel for i in ii)
+            extras["pass_as_4_launches_per_layer_with_rank16_adapters_in_hip_graph"] = {
+                "us_per_pass": ms_ll * 1e3, "GB/s": (pass_bytes + lora_bytes) / ms_ll / 1e6,
+                "adapter_bytes": lora_bytes, "launches": 2 * len(seq),
+                "us_per_step_of_two_launches": ms_ll * 1e3 / len(seq)}
+            log(f"[bench] the same with rank-{rank} adapters ({2 * len(seq)} launches): {ms_ll * 1e3:.1f} us/step")
+            del graph, seq, lAs, lBs
 
         # per-shape us/call: HBM-cold (rotate over the distinct matrices of the pass) and
         # cache-resident (same matrix every call), both as plain calls from Python (bounded below
