@@ -469,6 +469,8 @@ __global__ __launch_bounds__(256 * WM, WM == 1 ? 2 : 1) void gemm_kernel(const u
 // into registers while the current one is processed.  The four partial 16 x 16 tiles meet
 // in LDS at the end.  Many small workgroups (out/16 per 16 columns) keep every CU streaming.
 typedef float f4v_t __attribute__((ext_vector_type(4)));
+constexpr int kTinyXRows = 64;                 // rows of X a wave stages at a time
+constexpr int kTinyXPasses = kTinyXRows / 32;  // 32-row passes (1 KB each) per staging step
 
 template <int K>
 __global__ __launch_bounds__(256, 2) void gemm_tiny_kernel(const uint8_t* __restrict__ idx,
@@ -477,9 +479,10 @@ __global__ __launch_bounds__(256, 2) void gemm_tiny_kernel(const uint8_t* __rest
                                                            int ldx, void* __restrict__ Y, int ldy,
                                                            int y_f32, int n_rb, int n_cb, int rpc) {
   __shared__ __attribute__((aligned(16))) uint16_t Wt_all[4][16 * WS];
-  // [k][16 columns], as in memory; half a col-block at a time, which keeps the workgroup under
-  // a third of the LDS for the small-table formats (three workgroups per CU)
-  __shared__ __attribute__((aligned(16))) uint16_t Xt_all[4][128 * 16];
+  // [k][16 columns], as in memory; a quarter of a col-block at a time, which keeps the workgroup
+  // under a third of the LDS for every format but d = 4 (three workgroups per CU; fewer than 170
+  // registers, so the registers allow three as well)
+  __shared__ __attribute__((aligned(16))) uint16_t Xt_all[4][kTinyXRows * 16];
   __shared__ __attribute__((aligned(16))) uint32_t lut_all[4][2 * lut_dwords<K>()];
 
   const int tid = threadIdx.x;
@@ -529,13 +532,13 @@ __global__ __launch_bounds__(256, 2) void gemm_tiny_kernel(const uint8_t* __rest
   {                                                                                    \
     decode_group<K>(g[SLOT][0], lut, Wt, 0, lane);                                     \
     decode_group<K>(g[SLOT][1], lut + lut_dwords<K>(), Wt, 8, lane);                                 \
-    _Pragma("unroll") for (int hf = 0; hf < 2; ++hf) {                                 \
-      _Pragma("unroll") for (int j = 0; j < 4; ++j)                                    \
+    _Pragma("unroll") for (int hf = 0; hf < 8 / kTinyXPasses; ++hf) {                  \
+      _Pragma("unroll") for (int j = 0; j < kTinyXPasses; ++j)                         \
         *reinterpret_cast<u32x4_t*>(reinterpret_cast<char*>(Xt) + 1024 * j + xs_off) = \
-            x_ok ? xr[SLOT][4 * hf + j] : u32x4_t{0u, 0u, 0u, 0u};                     \
+            x_ok ? xr[SLOT][kTinyXPasses * hf + j] : u32x4_t{0u, 0u, 0u, 0u};          \
       wave_lds_sync();                                                                 \
-      _Pragma("unroll") for (int kk = 0; kk < 4; ++kk) {                               \
-        const int k0 = 32 * (4 * hf + kk) + 8 * (lane >> 4);                           \
+      _Pragma("unroll") for (int kk = 0; kk < kTinyXPasses; ++kk) {                    \
+        const int k0 = 32 * (kTinyXPasses * hf + kk) + 8 * (lane >> 4);                \
         const h8_t av = *reinterpret_cast<const h8_t*>(Wt + wt_half_index(lane & 15, k0)); \
         const h8_t bv = read_x_operand2(reinterpret_cast<const char*>(Xt) + 1024 * kk + xr_lo,  \
                                         reinterpret_cast<const char*>(Xt) + 1024 * kk + xr_hi); \
