@@ -149,6 +149,24 @@ def test_no_instruction_reads_a_dot2c_result_early(tmp_path):
 
 @pytest.mark.skipif(shutil.which(os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")) is None,
                     reason="hipcc not available")
+def test_wide_group_kernels_read_no_dot2c_result_early(tmp_path):
+    """The same two checks on the kernels of the formats whose tables are shared by 64 rows or more
+    (d = 4: compiler-scheduled dot products; k = 256 with int8 tables: the hand-scheduled block)."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    out = tmp_path / "vq_gemv_d4.s"
+    flags = [f for f in vqbuild.HIPCC_FLAGS if f != "-fPIC"]
+    cmd = [hipcc, *flags, "-S", "--cuda-device-only", "-o", str(out),
+           os.path.join(vqbuild.CSRC, "vq_gemv_d4.hip")]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    assert res.returncode == 0, res.stderr[-2000:]
+    lines = out.read_text().splitlines()
+    assert sum("v_dot2c_f32_f16" in l for l in lines) >= 32 + 32   # both kernels' dot products are in there
+    assert scan(lines) == []
+    assert scan_swaps(lines) == []
+
+
+@pytest.mark.skipif(shutil.which(os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")) is None,
+                    reason="hipcc not available")
 def test_e_step_kernel_has_no_fused_multiply_add(tmp_path):
     """The E-step's distance is defined with every operation rounded on its own (the CPU
     oracle takes the same decision with the same roundings); a contraction into a fused
