@@ -173,8 +173,7 @@ VQ_API int vq_gemv_multi(int count, const vq_desc* descs, const void* const* idx
  * vq_lora_workspace_bytes(count) bytes (256 bytes per product); its contents are overwritten
  * and mean nothing afterwards; calls that share a workspace must not overlap in time.
  * Everything else as for vq_gemv / vq_gemv_multi (`lora` is a HOST array of `count`
- * descriptors holding device pointers).  Representations with d = 4, and k = 256 with int8
- * tables, are not implemented here (VQ_ERR_UNSUPPORTED).
+ * descriptors holding device pointers); every representation that vq_gemv takes.
  */
 typedef struct vq_lora_desc {
   const void* A_f16;

@@ -166,8 +166,6 @@ int gemv_multi_impl(int count, const vq_desc* descs, const void* const* idx_dev,
         if (!l.A_f16 || !l.B_f16) return VQ_ERR_NULL;
         if (!aligned16(l.A_f16) || !aligned16(l.B_f16)) return VQ_ERR_ALIGN;
       }
-      const int fmt_i = format_tag(descs[i]);
-      if (fmt_i == kFmtD4 || fmt_i == kFmtK256I8) return VQ_ERR_UNSUPPORTED;
     }
   }
   if (validate_only) return VQ_OK;
@@ -202,8 +200,18 @@ int gemv_multi_impl(int count, const vq_desc* descs, const void* const* idx_dev,
       if (m > 0 && launch_lora_down(down, (hipStream_t)stream) != hipSuccess) return VQ_ERR_HIP;
     }
     if (fmt == kFmtD4 || fmt == kFmtK256I8) {   // one workgroup per 64 rows, see vq_gemv_d4.hip
-      GemvBatch batch;
+      GemvBatchLora both;                       // 20 KB on the stack; only the used entries are filled
+      GemvBatch& batch = both.base;
       memset(&batch, 0, offsetof(GemvBatch, p) + (size_t)n * sizeof(GemvProblem));
+      if (lora) {
+        for (int i = 0; i < n; ++i) {
+          LoraProblem& lp = both.l[i];
+          lp.B = (const uint16_t*)lora[first + i].B_f16;
+          lp.t = t_ws + (size_t)(first + i) * kLoraWorkspaceFloats;
+          lp.rank = lora[first + i].rank;
+          lp.pad = 0;
+        }
+      }
       batch.count = n;
       batch.y_f32 = (y_dtype == VQ_F32);
       long long wgs = 0;
@@ -223,8 +231,11 @@ int gemv_multi_impl(int count, const vq_desc* descs, const void* const* idx_dev,
       }
       if (wgs > 0x7fffffffll) return VQ_ERR_UNSUPPORTED;
       batch.total_wgs = (int32_t)wgs;
-      const hipError_t e = fmt == kFmtD4 ? launch_gemv_d4(batch, (int)wgs, (hipStream_t)stream)
-                                         : launch_gemv_k256i8(batch, (int)wgs, (hipStream_t)stream);
+      const hipError_t e =
+          lora ? (fmt == kFmtD4 ? launch_gemv_d4_lora(both, (int)wgs, (hipStream_t)stream)
+                                : launch_gemv_k256i8_lora(both, (int)wgs, (hipStream_t)stream))
+               : (fmt == kFmtD4 ? launch_gemv_d4(batch, (int)wgs, (hipStream_t)stream)
+                                : launch_gemv_k256i8(batch, (int)wgs, (hipStream_t)stream));
       if (e != hipSuccess) return VQ_ERR_HIP;
       continue;
     }

@@ -12,8 +12,7 @@
 // the next table entry are loaded one step ahead.  A lane owns columns 4L .. 4L+3 of a
 // col-block and keeps 8 row accumulators, reduced over the wave at the end exactly as in the
 // other GEMV kernels.
-#include "vq_device.h"
-#include "vq_internal.h"
+#include "vq_gemv_impl.h"
 
 namespace vq {
 namespace {
@@ -34,12 +33,15 @@ struct D4Step {
   uint32_t sc;    // that table's fp16 scale
 };
 
-__global__ __launch_bounds__(512) void gemv_d4_kernel(const GemvBatch batch) {
+template <bool LORA>
+__global__ __launch_bounds__(512) void gemv_d4_kernel(const typename BatchOf<LORA>::type arg) {
+  const GemvBatch& batch = base_of(arg);
   __shared__ __attribute__((aligned(16))) uint2 tabs[2][2][256];   // [buffer][col-block of the pair][entry]
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const GemvProblem& P = batch.p[find_problem_d4(batch, blockIdx.x)];
+  const int pi = find_problem_d4(batch, blockIdx.x);
+  const GemvProblem& P = batch.p[pi];
   const int oct = blockIdx.x - P.wg_begin;          // which 64 rows
   const int n_cb = P.n_cb, n_pairs = (n_cb + 1) >> 1;
   const int rb = oct * 8 + wave;                    // n_rb is a multiple of 8 (groups are >= 64 rows)
@@ -67,6 +69,13 @@ __global__ __launch_bounds__(512) void gemv_d4_kernel(const GemvBatch batch) {
   float acc[8];
 #pragma unroll
   for (int r = 0; r < 8; ++r) acc[r] = 0.f;
+  float tv[8];
+  uint4 lb = make_uint4(0, 0, 0, 0);
+  (void)tv; (void)lb; (void)pi;
+  if constexpr (LORA) {      // issued ahead of the main loop, used after the reduction
+    lora_load_t(arg.l[pi], P.x, lane, tv);
+    lb = lora_load_b(arg.l[pi], P.x, rb, lane);
+  }
 
   D4Step cur, nxt;
   load(0, cur);
@@ -92,7 +101,8 @@ __global__ __launch_bounds__(512) void gemv_d4_kernel(const GemvBatch batch) {
     cur = nxt;
   }
 
-  const float v = wave_reduce8(acc, lane);   // every lane: the total of row (lane >> 3) & 7
+  float v = wave_reduce8(acc, lane);   // every lane: the total of row (lane >> 3) & 7
+  if constexpr (LORA) v += lora_term(lb, tv);
   if ((lane & 7) == 0) {
     const size_t o = (size_t)rb * 8 + (lane >> 3);
     if (batch.y_f32) reinterpret_cast<float*>(P.y)[o] = v;
@@ -115,12 +125,15 @@ struct K256Step {
   uint32_t sc;    // that table's fp16 scale
 };
 
-__global__ __launch_bounds__(512) void gemv_k256i8_kernel(const GemvBatch batch) {
+template <bool LORA>
+__global__ __launch_bounds__(512) void gemv_k256i8_kernel(const typename BatchOf<LORA>::type arg) {
+  const GemvBatch& batch = base_of(arg);
   __shared__ __attribute__((aligned(16))) uint32_t tabs[2][2][256];   // [buffer][col-block of the pair][entry]
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const GemvProblem& P = batch.p[find_problem_d4(batch, blockIdx.x)];
+  const int pi = find_problem_d4(batch, blockIdx.x);
+  const GemvProblem& P = batch.p[pi];
   const int oct = blockIdx.x - P.wg_begin;          // which 64 rows
   const int n_cb = P.n_cb, n_pairs = (n_cb + 1) >> 1;
   const int rb = oct * 8 + wave;
@@ -149,6 +162,13 @@ __global__ __launch_bounds__(512) void gemv_k256i8_kernel(const GemvBatch batch)
   float acc[8];
 #pragma unroll
   for (int r = 0; r < 8; ++r) acc[r] = 0.f;
+  float tv[8];
+  uint4 lb = make_uint4(0, 0, 0, 0);
+  (void)tv; (void)lb; (void)pi;
+  if constexpr (LORA) {      // issued ahead of the main loop, used after the reduction
+    lora_load_t(arg.l[pi], P.x, lane, tv);
+    lb = lora_load_b(arg.l[pi], P.x, rb, lane);
+  }
 
   K256Step cur, nxt;
   load(0, cur);
@@ -165,7 +185,8 @@ __global__ __launch_bounds__(512) void gemv_k256i8_kernel(const GemvBatch batch)
     cur = nxt;
   }
 
-  const float v = wave_reduce8(acc, lane);   // every lane: the total of row (lane >> 3) & 7
+  float v = wave_reduce8(acc, lane);   // every lane: the total of row (lane >> 3) & 7
+  if constexpr (LORA) v += lora_term(lb, tv);
   if ((lane & 7) == 0) {
     const size_t o = (size_t)rb * 8 + (lane >> 3);
     if (batch.y_f32) reinterpret_cast<float*>(P.y)[o] = v;
@@ -176,12 +197,23 @@ __global__ __launch_bounds__(512) void gemv_k256i8_kernel(const GemvBatch batch)
 }  // namespace
 
 hipError_t launch_gemv_k256i8(const GemvBatch& batch, int total_wgs, hipStream_t s) {
-  hipLaunchKernelGGL(gemv_k256i8_kernel, dim3((unsigned)total_wgs), dim3(512), 0, s, batch);
+  hipLaunchKernelGGL(gemv_k256i8_kernel<false>, dim3((unsigned)total_wgs), dim3(512), 0, s, batch);
   return hipGetLastError();
 }
 
 hipError_t launch_gemv_d4(const GemvBatch& batch, int total_wgs, hipStream_t s) {
-  hipLaunchKernelGGL(gemv_d4_kernel, dim3((unsigned)total_wgs), dim3(512), 0, s, batch);
+  hipLaunchKernelGGL(gemv_d4_kernel<false>, dim3((unsigned)total_wgs), dim3(512), 0, s, batch);
+  return hipGetLastError();
+}
+
+// The same two kernels with the low-rank adapter term added to every row before it is stored.
+hipError_t launch_gemv_k256i8_lora(const GemvBatchLora& batch, int total_wgs, hipStream_t s) {
+  hipLaunchKernelGGL(gemv_k256i8_kernel<true>, dim3((unsigned)total_wgs), dim3(512), 0, s, batch);
+  return hipGetLastError();
+}
+
+hipError_t launch_gemv_d4_lora(const GemvBatchLora& batch, int total_wgs, hipStream_t s) {
+  hipLaunchKernelGGL(gemv_d4_kernel<true>, dim3((unsigned)total_wgs), dim3(512), 0, s, batch);
   return hipGetLastError();
 }
 

@@ -113,6 +113,8 @@ int gemv_chunk_units(int fmt);
 // owns 64 rows and shares the group's dequantised table; see vq_gemv_d4.hip).
 hipError_t launch_gemv_d4(const GemvBatch& batch, int total_wgs, hipStream_t s);
 hipError_t launch_gemv_k256i8(const GemvBatch& batch, int total_wgs, hipStream_t s);
+hipError_t launch_gemv_d4_lora(const GemvBatchLora& batch, int total_wgs, hipStream_t s);
+hipError_t launch_gemv_k256i8_lora(const GemvBatchLora& batch, int total_wgs, hipStream_t s);
 hipError_t launch_gemm(const vq_desc& d, const void* idx_dev, const void* cb_dev,
                        const void* X, int B, int ldx, void* Y, int ldy, int y_f32,
                        hipStream_t s);

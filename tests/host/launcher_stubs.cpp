@@ -82,6 +82,14 @@ void check_gemv(int fmt, const GemvBatch& b, int mode, int grid_wgs, int max_n_c
   }
 }
 
+void check_adapters(const GemvBatchLora& batch) {
+  for (int i = 0; i < batch.base.count; ++i) {
+    const LoraProblem& l = batch.l[i];
+    REQUIRE(l.rank >= 0 && l.rank <= kMaxLoraRank && l.rank % 8 == 0, "problem %d: rank %d", i, l.rank);
+    REQUIRE(l.rank == 0 || (l.B && l.t), "problem %d: adapter with a null pointer", i);
+  }
+}
+
 }  // namespace
 
 long long stub_launch_count() { return g_launches; }
@@ -103,12 +111,8 @@ hipError_t launch_gemv(int fmt, const GemvBatch& batch, int mode, int grid_wgs, 
 hipError_t launch_gemv_lora(int fmt, const GemvBatchLora& batch, int mode, int grid_wgs, int max_n_cb, hipStream_t,
                             int wpw) {
   check_gemv(fmt, batch.base, mode, grid_wgs, max_n_cb, wpw);
-  REQUIRE(fmt != kFmtD4 && fmt != kFmtK256I8, "adapter launch for format %d", fmt);
-  for (int i = 0; i < batch.base.count; ++i) {
-    const LoraProblem& l = batch.l[i];
-    REQUIRE(l.rank >= 0 && l.rank <= kMaxLoraRank && l.rank % 8 == 0, "problem %d: rank %d", i, l.rank);
-    REQUIRE(l.rank == 0 || (l.B && l.t), "problem %d: adapter with a null pointer", i);
-  }
+  REQUIRE(fmt != kFmtD4 && fmt != kFmtK256I8, "split-K / streaming launch for format %d", fmt);
+  check_adapters(batch);
   return hipSuccess;
 }
 int gemv_stream_resident_wgs_lora(int, int) { return 512; }
@@ -143,6 +147,13 @@ hipError_t launch_gemv_d4(const GemvBatch& b, int total_wgs, hipStream_t) {
   return hipSuccess;
 }
 hipError_t launch_gemv_k256i8(const GemvBatch& b, int total_wgs, hipStream_t s) { return launch_gemv_d4(b, total_wgs, s); }
+hipError_t launch_gemv_d4_lora(const GemvBatchLora& b, int total_wgs, hipStream_t s) {
+  check_adapters(b);
+  return launch_gemv_d4(b.base, total_wgs, s);
+}
+hipError_t launch_gemv_k256i8_lora(const GemvBatchLora& b, int total_wgs, hipStream_t s) {
+  return launch_gemv_d4_lora(b, total_wgs, s);
+}
 hipError_t launch_gemm(const vq_desc& d, const void* a, const void* b, const void* X, int B, int ldx, void* Y, int ldy,
                        int y_f32, hipStream_t) {
   ++g_launches;

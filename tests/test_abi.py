@@ -326,11 +326,11 @@ def test_lora_entry_points_validate_on_the_host():
     assert call(ws=0) == -1
     assert call(ws=ws + 4) == -4
     assert call(nb=255) == -6             # workspace too small
-    # representations served by kernels of their own do not take an adapter
+    # the representations served by kernels of their own are validated the same way
     d4 = vq.make_desc(4096, 4096, 256, 8, group_rows=256, d=4, codebook_dtype=vq.VQ_I8)
-    assert L.vq_gemv_lora(ctypes.byref(d4), A, A, A, A, A, 16, ws, 256, A + 16, vq.VQ_F16, 0) == -3
+    assert L.vq_gemv_lora(ctypes.byref(d4), A, A, A, A, A, 12, ws, 256, A + 16, vq.VQ_F16, 0) == -6
     k8 = vq.make_desc(4096, 4096, 256, 8, group_rows=128, codebook_dtype=vq.VQ_I8)
-    assert L.vq_gemv_lora(ctypes.byref(k8), A, A, A, A, A, 16, ws, 256, A + 16, vq.VQ_F16, 0) == -3
+    assert L.vq_gemv_lora(ctypes.byref(k8), A, A, A, A, 0, 16, ws, 256, A + 16, vq.VQ_F16, 0) == -1
     # the descriptor is validated like everywhere else
     bad = vq.make_desc(4096, 4000, 16, 4)
     assert L.vq_gemv_lora(ctypes.byref(bad), A, A, A, A, A, 16, ws, 256, A + 16, vq.VQ_F16, 0) == -3

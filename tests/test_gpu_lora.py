@@ -77,6 +77,8 @@ CASES = [
     (V(96, 2816, 64, 6, 32, 256, 2, True), 16), (V(40, 768, 16, 4, 8, 256, 2, True), 40),
     (V(72, 1280, 16, 4, 8, 256, 1), 16), (V(96, 768, 8, 3, 32, 256, 1, True), 16), (V(40, 1280, 4, 2, 1, 256, 1, True), 56),
     (V(96, 768, 64, 6, 32, 256, 2, True, True), 16),
+    (V(128, 768, 256, 8, 64, 256, 4, True), 16), (V(512, 256 * 5, 256, 8, 256, 256, 4, True), 64),    # d = 4
+    (V(256, 1280, 256, 8, 128, 256, 2, True), 24), (V(64, 256 * 3, 256, 8, 64, 256, 2, True), 8),      # k = 256, int8 tables
     (V(32776, 768, 16, 4), 16), (V(32776, 2816, 16, 4), 64), (V(33000, 1280, 256, 8), 8),
     (V(32800, 1280, 64, 6, 32, 256, 2, True), 32), (V(32800, 768, 64, 6, 32, 256, 2, True, True), 16),
     (V(32776, 768, 16, 4, 8, 256, 1), 48),
@@ -191,6 +193,34 @@ def test_gemv_lora_multi_more_than_one_launch(env):
     torch.cuda.synchronize()
     for i, ref in enumerate(refs):
         assert oracle.normwise_rel_err(ys[i].cpu().numpy(), ref) <= TOL_F32, i
+
+
+@pytest.mark.parametrize("d", [4, 2], ids=["d4", "k256_int8_tables"])
+def test_gemv_lora_multi_wide_group_formats(env, d):
+    """The formats whose tables are shared by 64 to 256 rows (kernels of their own: a workgroup per 64
+    rows): five matrices of mixed group heights and widths in one call, ranks 0, 8, 24, 40, 64."""
+    torch, vq, vqdev = env
+    shapes = [V(256, 768, 256, 8, 64, 256, d, True), V(256, 256 * 5, 256, 8, 128, 256, d, True),
+              V(512, 512, 256, 8, 256, 256, d, True), V(64, 256, 256, 8, 64, 256, d, True),
+              V(1024, 1280, 256, 8, 256, 256, d, True)]
+    descs, idxs, cbs, xs, ys, As, Bs, ranks, refs = [], [], [], [], [], [], [], [], []
+    for i, (s, rank) in enumerate(zip(shapes, (0, 8, 24, 40, 64))):
+        desc, idx_d, cb_d, base = _pack(env, s, 8800 + 10 * d + i)
+        x = workloads.make_x(s.in_features, 8800 + i)
+        A, B = _adapter(s, max(rank, 8), 8800 + i)
+        descs.append(desc); idxs.append(idx_d); cbs.append(cb_d); xs.append(vqdev.to_device_bytes(x))
+        ys.append(torch.full((s.out_features,), float("nan"), dtype=torch.float32, device="cuda:0"))
+        As.append(vqdev.to_device_bytes(A) if rank else None)
+        Bs.append(vqdev.to_device_bytes(B) if rank else None)
+        ranks.append(rank)
+        refs.append(_ref(base, x, A, B) if rank else base(x))
+    ws = torch.zeros(vq.vq_lora_workspace_bytes(len(shapes)) // 4, dtype=torch.float32, device="cuda:0")
+    vq.vq_gemv_lora_multi(vq.GemvMultiArgs(descs, idxs, cbs, xs, ys), As, Bs, ranks, ws, vq.VQ_F32)
+    torch.cuda.synchronize()
+    for i, ref in enumerate(refs):
+        y = ys[i].cpu().numpy().astype(np.float64)
+        assert not np.isnan(y).any(), i
+        assert oracle.normwise_rel_err(y, ref) <= TOL_F32, i
 
 
 def test_lora_replays_in_a_hip_graph(env):
