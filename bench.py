@@ -280,6 +280,9 @@ def main():
                 # per group and a 4-bit code per 32 weights, 3.28 bits per value
                 ("llama7b_pass_k64_int8_tables_block_norm_3.28bpv_via_vq_gemv_multi", workloads.LLAMA7B_LAYER_K64_BN,
                  "gemv_stream_kernel<64,bn>"),
+                # the 2.125 bpv setting with blockwise normalisation on top: 2.38 bits per value
+                ("llama7b_pass_k16_int8_tables_block_norm_2.38bpv_via_vq_gemv_multi", workloads.LLAMA7B_LAYER_K16_BN,
+                 "gemv_stream_kernel<k16,bn>"),
                 # four-dimensional vectors: k = 256, one index byte per 4 weights, 256 x 256 groups (2.125 bpv)
                 ("llama7b_pass_d4_k256_int8_tables_2.125bpv_via_vq_gemv_multi", workloads.LLAMA7B_LAYER_D4,
                  "gemv_d4_kernel"),
@@ -317,6 +320,13 @@ def main():
                         tv[:, 33:48:2] = 0x1C
                     elif s.d == 1:                      # fp16 scalars
                         tab = (torch.randn(cbb // 2, device=dev) * 0.02).half().view(torch.uint8)
+                    elif s.block_norm and s.k == 16:    # tables, scales (2^-8), padding, levels (1.0), nibble codes
+                        n_slots = (s.out_features // 8) * 2 * ((s.in_features // 256 + 1) // 2)
+                        lev0 = (34 * n_slots + 15) // 16 * 16
+                        tab[n_slots * 32:lev0] = 0
+                        tab[n_slots * 32 + 1:n_slots * 34:2] = 0x1C
+                        tab[lev0:lev0 + 32 * n_slots:2] = 0
+                        tab[lev0 + 1:lev0 + 32 * n_slots:2] = 0x3C
                     elif s.block_norm:                  # 672-byte records (+ 64 levels, set to 1.0), then nibble codes
                         n_rec = (s.out_features // s.group_rows) * ((s.in_features // 256 + 3) // 4)
                         tv = tab[:n_rec * 672].view(-1, 672)

@@ -18,7 +18,7 @@ bool is_pow2(int v) { return v > 0 && (v & (v - 1)) == 0; }
 //   int8 tables with one fp16 scale per group: k = 64 (6-bit indices), groups of 8, 16 or 32
 //   rows x 256 columns (32 rows = the 8,192-weight groups of Sec. 5.1), or k = 16 with 8 x 256
 //   groups (2.125 bits per value), or k = 256 with groups of 64, 128 or 256 rows x 256 columns
-//   (128 rows: the 2D 4.125 row of the appendix table); k = 64 also with blockwise
+//   (128 rows: the 2D 4.125 row of the appendix table); k = 64 and k = 16 also with blockwise
 //   normalisation (VQ_I8_BN);
 //   d = 1 (scalar codebooks): k = 16 fp16 values per 8 x 256 group, 4-bit indices (4.125 bits
 //   per value, the overhead of the 1D 4.125 row of the appendix table of VQ configurations);
@@ -56,7 +56,7 @@ int check_desc(const vq_desc* d) {
   } else if (is_i8(*d)) {
     if (d->k == 64) {
       if (d->group_rows != 8 && d->group_rows != 16 && d->group_rows != 32) return VQ_ERR_UNSUPPORTED;
-    } else if (d->k == 16 && !is_bn(*d)) {
+    } else if (d->k == 16) {                  // with or without blockwise normalisation
       if (d->group_rows != kGroupRows) return VQ_ERR_UNSUPPORTED;
     } else if (d->k == 256 && !is_bn(*d)) {   // the 4-bits-per-dimension 2D setting: large groups share a table
       if (d->group_rows != 64 && d->group_rows != 128 && d->group_rows != 256) return VQ_ERR_UNSUPPORTED;
@@ -92,7 +92,7 @@ void sizes(const vq_desc& d, size_t* idx_bytes, size_t* cb_bytes) {
 
 // Units a row-block of `n_cb` col-blocks is cut into (what the strips of the GEMV kernels count).
 int strip_units(int fmt, int n_cb) {
-  return (fmt == 16 || fmt == kFmtK16I8 || fmt == kFmtD1K4) ? (n_cb + 1) / 2 : (fmt == 64 || fmt == kFmtK64BN || fmt == kFmtD1K8) ? (n_cb + 3) / 4 : n_cb;
+  return (fmt == 16 || fmt == kFmtK16I8 || fmt == kFmtK16BN || fmt == kFmtD1K4) ? (n_cb + 1) / 2 : (fmt == 64 || fmt == kFmtK64BN || fmt == kFmtD1K8) ? (n_cb + 3) / 4 : n_cb;
 }
 
 int hip_status(hipError_t e) { return e == hipSuccess ? VQ_OK : VQ_ERR_HIP; }
@@ -400,7 +400,9 @@ int vq_layout_bytes(const vq_desc* desc, size_t* idx_bytes, size_t* cb_bytes) {
   }
   const size_t slots = desc->k == 16 ? 2 * ((n_cb + 1) / 2) : n_cb;
   if (idx_bytes) *idx_bytes = n_rb * slots * (1024 * (size_t)desc->index_bits / 8);
-  if (cb_bytes) *cb_bytes = is_i8(*desc) ? n_rb * slots * 34 : n_rb * slots * (size_t)desc->k * 4;
+  if (cb_bytes)   // k = 16 with blockwise normalisation: levels and block codes behind tables and scales
+    *cb_bytes = is_bn(*desc) ? k16bn_table_bytes(n_rb * slots)
+                             : is_i8(*desc) ? n_rb * slots * 34 : n_rb * slots * (size_t)desc->k * 4;
   return VQ_OK;
 }
 

@@ -17,7 +17,8 @@ __global__ __launch_bounds__(256) void decode_kernel(const uint8_t* __restrict__
                                                      const uint32_t* __restrict__ cb,
                                                      uint16_t* __restrict__ W, int n_cb,
                                                      long long n_groups, int in_features, int rpc) {
-  __shared__ uint32_t lut_all[4][K == kFmtK16I8 ? 16 : (K == kFmtD1K16 || K == kFmtK256I8) ? 256 : K == kFmtD1K4 ? 128 : K];
+  // (k = 16 with blockwise normalisation: 16 table entries, then the group's 16 levels)
+  __shared__ uint32_t lut_all[4][K == kFmtK16I8 ? 16 : K == kFmtK16BN ? 32 : (K == kFmtD1K16 || K == kFmtK256I8) ? 256 : K == kFmtD1K4 ? 128 : K];
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   uint32_t* lut = lut_all[wave];
@@ -51,17 +52,26 @@ __global__ __launch_bounds__(256) void decode_kernel(const uint8_t* __restrict__
         *reinterpret_cast<uint2*>(out + (size_t)(4 * h + r) * in_features) = make_uint2(lo, hi);
       }
     }
-  } else if (K == 16 || K == kFmtK16I8) {
+  } else if (K == 16 || K == kFmtK16I8 || K == kFmtK16BN) {
     const int slots = 2 * k16_pairs(n_cb);                  // group slots per row-block
+    uint32_t cw = 0;                                        // BN: the lane's block codes, row r in bits [4r, 4r+4)
     if (K == 16) {
       if (lane < 16) lut[lane] = cb[(rb * slots + c) * 16 + lane];
-    } else if (lane < 16) {
+    } else {
       const long long n_rb = n_groups / n_cb;
-      const uint8_t* tq = reinterpret_cast<const uint8_t*>(cb) + (size_t)(rb * slots + c) * 32;
-      const uint16_t* sc = reinterpret_cast<const uint16_t*>(reinterpret_cast<const uint8_t*>(cb) +
-                                                             (size_t)n_rb * slots * 32);
-      lut[lane] = k64_dequant_pair(*reinterpret_cast<const uint16_t*>(tq + lane * 2),
-                                   __builtin_bit_cast(_Float16, sc[rb * slots + c]));
+      const uint8_t* tb = reinterpret_cast<const uint8_t*>(cb);
+      if (lane < 16) {
+        const uint8_t* tq = tb + (size_t)(rb * slots + c) * 32;
+        const uint16_t* sc = reinterpret_cast<const uint16_t*>(tb + (size_t)n_rb * slots * 32);
+        lut[lane] = k64_dequant_pair(*reinterpret_cast<const uint16_t*>(tq + lane * 2),
+                                     __builtin_bit_cast(_Float16, sc[rb * slots + c]));
+      }
+      if (K == kFmtK16BN) {
+        const size_t n_slots = (size_t)n_rb * slots;
+        if (lane < 16)
+          lut[16 + lane] = 0x10001u * reinterpret_cast<const uint16_t*>(tb + k16bn_level_offset(n_slots))[(rb * slots + c) * 16 + lane];
+        cw = reinterpret_cast<const uint32_t*>(tb + k16bn_code_offset(n_slots))[((rb * slots + c) >> 1) * 16 + 2 * (lane >> 3) + (c & 1)];
+      }
     }
     const uint2 w = *reinterpret_cast<const uint2*>(idx + rb * slots * 512 + k16_chunk_offset(c, lane));
     wave_lds_sync();
@@ -72,8 +82,13 @@ __global__ __launch_bounds__(256) void decode_kernel(const uint8_t* __restrict__
       k16_split_dword(h ? w.y : w.x, a, b);
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        const uint32_t lo = *reinterpret_cast<const uint32_t*>(lutb + ((a >> (8 * r)) & 0xffu));
-        const uint32_t hi = *reinterpret_cast<const uint32_t*>(lutb + ((b >> (8 * r)) & 0xffu));
+        uint32_t lo = *reinterpret_cast<const uint32_t*>(lutb + ((a >> (8 * r)) & 0xffu));
+        uint32_t hi = *reinterpret_cast<const uint32_t*>(lutb + ((b >> (8 * r)) & 0xffu));
+        if (K == kFmtK16BN) {   // times the scale of the row's 32-weight block: one more fp16 rounding
+          const h2_t sc = __builtin_bit_cast(h2_t, lut[16 + ((cw >> (4 * (4 * h + r))) & 15u)]);
+          lo = __builtin_bit_cast(uint32_t, __builtin_bit_cast(h2_t, lo) * sc);
+          hi = __builtin_bit_cast(uint32_t, __builtin_bit_cast(h2_t, hi) * sc);
+        }
         *reinterpret_cast<uint2*>(out + (size_t)(4 * h + r) * in_features) = make_uint2(lo, hi);
       }
     }
@@ -238,6 +253,7 @@ hipError_t launch_decode(const vq_desc& d, const void* idx_dev, const void* cb_d
                      (const uint32_t*)cb_dev, (uint16_t*)W, n_cb, n_groups, d.in_features,          \
                      d.group_rows >= kGroupRows ? d.group_rows / kGroupRows : 1)
   if (fmt == kFmtK16I8) VQ_DECODE(kFmtK16I8);
+  else if (fmt == kFmtK16BN) VQ_DECODE(kFmtK16BN);
   else if (fmt == kFmtD1K16) VQ_DECODE(kFmtD1K16);
   else if (fmt == kFmtD1K4) VQ_DECODE(kFmtD1K4);
   else if (fmt == kFmtK256I8) VQ_DECODE(kFmtK256I8);

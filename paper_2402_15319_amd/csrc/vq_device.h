@@ -424,6 +424,41 @@ __device__ __forceinline__ void k16_split_dword(uint32_t w, uint32_t& a, uint32_
   b = __builtin_amdgcn_alignbit(w, w, 4) & 0x3c3c3c3cu;
 }
 
+// ---- k = 16 with int8 tables and blockwise normalisation: device layout of the table buffer ----
+// (S = group slots of the matrix = row-blocks x 2 x col-block pairs; pad slots are all zero)
+//   [0, 32 S)              int8 tables, 32 bytes per slot                      (as without BN)
+//   [32 S, 34 S)           one fp16 scale per slot                             (as without BN)
+//   [A, A + 32 S)          A = 34 S rounded up to 16: the slot's 16 fp16 levels
+//   [A + 32 S, A + 64 S)   block codes, 64 bytes per col-block pair: dword 2b + e holds the codes of
+//                          block b (lanes 8b .. 8b+7: 32 columns) of the pair's col-block e, row r in
+//                          bits [4r, 4r+4): a lane's codes of a pair are one 8-byte load
+// (offsets: k16bn_level_offset, k16bn_code_offset, k16bn_table_bytes in vq_internal.h)
+
+// k = 16 inner block with block scales, in plain C++ like k64_group_scaled: w0 / w1 hold rows
+// 0..3 / 4..7 in the pre-scaled 4-bit layout, cw the lane's code dword; tab: the group's 16-entry
+// table, lev: its 16 level dwords (fp16 in both halves).  Each looked-up centroid pair is
+// multiplied by the row's block scale (one fp16 rounding: exactly the decoded weight).
+__device__ __forceinline__ void k16_group_scaled(uint32_t w0, uint32_t w1, uint32_t cw, const uint32_t* tab,
+                                                 const uint32_t* lev, uint32_t x0, uint32_t x1,
+                                                 float (&acc)[8]) {
+  const h2_t xa = __builtin_bit_cast(h2_t, x0), xb = __builtin_bit_cast(h2_t, x1);
+  const char* tb = reinterpret_cast<const char*>(tab);
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    uint32_t a, b;
+    k16_split_dword(h ? w1 : w0, a, b);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const h2_t sc = __builtin_bit_cast(h2_t, lev[(cw >> (4 * (4 * h + r))) & 15u]);
+      const h2_t ta = __builtin_bit_cast(h2_t, *reinterpret_cast<const uint32_t*>(tb + ((a >> (8 * r)) & 0xffu))) * sc;
+      const h2_t tv = __builtin_bit_cast(h2_t, *reinterpret_cast<const uint32_t*>(tb + ((b >> (8 * r)) & 0xffu))) * sc;
+      acc[4 * h + r] = __builtin_amdgcn_fdot2(ta, xa, acc[4 * h + r], false);
+      acc[4 * h + r] = __builtin_amdgcn_fdot2(tv, xb, acc[4 * h + r], false);
+    }
+  }
+}
+
+
 // Sum 8 per-lane row accumulators over the 64 lanes.  Returns, in every lane, the
 // total of row (lane >> 3) & 7.  Halving exchange without LDS traffic: the two
 // cross-row steps use the gfx950 lane-swap instructions (v_permlane32_swap exchanges

@@ -42,7 +42,7 @@ __device__ __forceinline__ int wt_half_index(int m, int k) {   // k in halfs
 // scale per group, groups of 8*rpc rows), kFmtK16I8 (k = 16 with int8 tables).
 template <int K> constexpr int lut_dwords() {
   // BN: 64 centroids + 16 levels; d = 4: 256 entries of 4 halfs; scalar 2-bit: 8 rows x 16 pair entries
-  return K == kFmtK16I8 ? 16 : (K == kFmtD1K16 || K == kFmtK256I8) ? 256 : K == kFmtK64BN ? 80 : K == kFmtD4 ? 512 : K == kFmtD1K8 ? 64 : K == kFmtD1K4 ? 128 : K;
+  return K == kFmtK16I8 ? 16 : K == kFmtK16BN ? 32 : (K == kFmtD1K16 || K == kFmtK256I8) ? 256 : K == kFmtK64BN ? 80 : K == kFmtD4 ? 512 : K == kFmtD1K8 ? 64 : K == kFmtD1K4 ? 128 : K;
 }
 
 // What one wave needs to decode one group: the lane's index bytes and codebook piece.
@@ -93,6 +93,12 @@ template <> struct GroupRegs<kFmtK16I8> {
   uint32_t two;          // int8 pair of table entry lane & 15
   uint32_t sc;
 };
+template <> struct GroupRegs<kFmtK16BN> {
+  uint2 w;
+  uint32_t two, sc;      // as for k = 16 with int8 tables
+  uint32_t cw;           // the lane's block codes of this col-block, row r in bits [4r, 4r+4)
+  uint32_t lev;          // block-scale level lane & 15 (fp16)
+};
 
 template <int K>
 __device__ __forceinline__ void load_group(GroupRegs<K>& g, const uint8_t* idx, const uint32_t* cb,
@@ -102,12 +108,17 @@ __device__ __forceinline__ void load_group(GroupRegs<K>& g, const uint8_t* idx, 
     const int slots = 2 * k16_pairs(n_cb);
     g.w = *reinterpret_cast<const uint2*>(idx + (size_t)rb * slots * 512 + k16_chunk_offset(c, lane));
     g.cbv = cb[((size_t)rb * slots + c) * 16 + (lane & 15)];
-  } else if constexpr (K == kFmtK16I8) {
+  } else if constexpr (K == kFmtK16I8 || K == kFmtK16BN) {
     const int slots = 2 * k16_pairs(n_cb);
     const uint8_t* tabs = reinterpret_cast<const uint8_t*>(cb);
     g.w = *reinterpret_cast<const uint2*>(idx + (size_t)rb * slots * 512 + k16_chunk_offset(c, lane));
     g.two = *reinterpret_cast<const uint16_t*>(tabs + ((size_t)rb * slots + c) * 32 + (lane & 15) * 2);
     g.sc = reinterpret_cast<const uint16_t*>(tabs + (size_t)n_rb * slots * 32)[(size_t)rb * slots + c];
+    if constexpr (K == kFmtK16BN) {
+      const size_t n_slots = (size_t)n_rb * slots, slot = (size_t)rb * slots + c;
+      g.lev = reinterpret_cast<const uint16_t*>(tabs + k16bn_level_offset(n_slots))[slot * 16 + (lane & 15)];
+      g.cw = reinterpret_cast<const uint32_t*>(tabs + k16bn_code_offset(n_slots))[(slot >> 1) * 16 + 2 * (lane >> 3) + (c & 1)];
+    }
   } else if constexpr (K == kFmtD1K4) {
     const int slots = 2 * k16_pairs(n_cb);
     const uint8_t* rec = reinterpret_cast<const uint8_t*>(cb) + ((size_t)rb * slots + c) * kD1K4SlotTabBytes;
@@ -222,11 +233,14 @@ __device__ __forceinline__ void decode_group(const GroupRegs<K>& g, uint32_t* lu
         v[8 * h + 2 * r + 1] = *reinterpret_cast<const uint32_t*>(row_tab + ((b >> (8 * r)) & 0xffu));
       }
     }
-  } else if constexpr (K == 16 || K == kFmtK16I8) {
+  } else if constexpr (K == 16 || K == kFmtK16I8 || K == kFmtK16BN) {
     if constexpr (K == 16) {
       if (lane < 16) lut[lane] = g.cbv;
     } else {
       if (lane < 16) lut[lane] = k64_dequant_pair(g.two, __builtin_bit_cast(_Float16, (uint16_t)g.sc));
+      if constexpr (K == kFmtK16BN) {
+        if (lane < 16) lut[16 + lane] = g.lev * 0x10001u;   // the level in both halves
+      }
     }
     const auto& q = g;
     wave_lds_sync();
@@ -238,6 +252,14 @@ __device__ __forceinline__ void decode_group(const GroupRegs<K>& g, uint32_t* lu
       for (int r = 0; r < 4; ++r) {
         v[8 * h + 2 * r] = *reinterpret_cast<const uint32_t*>(lutb + ((a >> (8 * r)) & 0xffu));
         v[8 * h + 2 * r + 1] = *reinterpret_cast<const uint32_t*>(lutb + ((b >> (8 * r)) & 0xffu));
+      }
+    }
+    if constexpr (K == kFmtK16BN) {     // times the block scale of the lane's 32-weight block, per row
+#pragma unroll
+      for (int r = 0; r < 8; ++r) {
+        const h2_t sc = __builtin_bit_cast(h2_t, lut[16 + ((q.cw >> (4 * r)) & 15u)]);
+        v[2 * r] = __builtin_bit_cast(uint32_t, __builtin_bit_cast(h2_t, v[2 * r]) * sc);
+        v[2 * r + 1] = __builtin_bit_cast(uint32_t, __builtin_bit_cast(h2_t, v[2 * r + 1]) * sc);
       }
     }
   } else {
@@ -785,9 +807,9 @@ template <int K>
 hipError_t launch_wide(const vq_desc& d, const void* idx_dev, const void* cb_dev, const void* X, int B,
                        int ldx, void* Y, int ldy, int y_f32, hipStream_t s) {
   // the 512-column tile needs 128 accumulator registers per wave: most formats fit the 256
-  // registers or spill up to four of them; the block-normalised one would spill ten and keeps
-  // 256 columns
-  if constexpr (K == kFmtK64BN) {
+  // registers or spill up to four of them; the block-normalised ones would spill seven to ten and
+  // keep 256 columns
+  if constexpr (K == kFmtK64BN || K == kFmtK16BN) {
     return launch_one<K, 2, 256, 2>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);
   } else {
   const int n_rb = d.out_features / kGroupRows;
@@ -862,6 +884,7 @@ hipError_t launch_gemm(const vq_desc& d, const void* idx_dev, const void* cb_dev
   const int fmt = format_tag(d);
   if (fmt == 64) VQ_GEMM_DISPATCH(64)
   if (fmt == kFmtK16I8) VQ_GEMM_DISPATCH(kFmtK16I8)
+  if (fmt == kFmtK16BN) VQ_GEMM_DISPATCH(kFmtK16BN)
   if (fmt == kFmtD1K16) VQ_GEMM_DISPATCH(kFmtD1K16)
   if (fmt == kFmtK64BN) VQ_GEMM_DISPATCH(kFmtK64BN)
   if (fmt == kFmtD4) VQ_GEMM_DISPATCH(kFmtD4)

@@ -16,6 +16,7 @@ struct Strip {
   const uint32_t* cb_rb;   // codebooks / int8 tables of the row-block (dwords)
   const uint16_t* sc_rb;   // fp16 scales of the row-block's groups (k=16 with int8 tables)
   const uint8_t* codes_rb; // 4-bit block codes of the row-block (blockwise normalisation)
+  const uint8_t* lev_rb;   // fp16 block-scale levels of the row-block's groups (k=16 with blockwise normalisation)
   const uint16_t* x;
   int u;                   // next unit to load
   int u_end;               // end of this strip's units
@@ -47,17 +48,22 @@ __device__ __forceinline__ uint4 stream_load16(const void* p) {
 // ---- chunks with activations in registers (split-K kernel) ------------------
 template <int K> struct Chunk;
 
-// k = 16.  I8: the tables are int8 with a scale per group (32 + 2 bytes per group instead of
-// 64), dequantised into the LDS table when the chunk is consumed.
-template <bool I8> struct Chunk16T {
+// k = 16.  MODE 1 (I8): the tables are int8 with a scale per group (32 + 2 bytes per group instead
+// of 64), dequantised into the LDS table when the chunk is consumed.  MODE 2 (BN): blockwise
+// normalisation on top (16 block-scale levels per group next to the tables in LDS, a 4-bit code
+// per 32 weights); the plain C++ inner block replaces the hand-scheduled one.
+template <int MODE> struct Chunk16T {
+  static constexpr bool I8 = MODE >= 1, BN = MODE == 2;
   static constexpr int kUnits = 4;        // col-block pairs per chunk
-  static constexpr int kLutDwords = 128;  // 8 groups x 16 centroids
+  static constexpr int kLutDwords = BN ? 256 : 128;  // 8 groups x 16 centroids (+ 8 x 16 levels)
   uint4 w[4];     // slot s: the lane's 16 index bytes of pair u+s
   uint2 xa[4];    // activations of the first group of the slot
   uint2 xb[4];    // ... and of the second
   uint4 cbv;      // fp16: this lane's 16 bytes of the chunk's codebooks (lanes 0..31)
   uint32_t tab;   // int8: this lane's two centroid pairs (4 bytes of the chunk's tables)
   uint32_t sc;    // int8: the fp16 scale of the group those pairs belong to
+  uint2 cw[4];    // BN: the lane's block codes of the two groups of pair u+s
+  uint32_t lev;   // BN: levels 2*(lane%8), +1 of group lane/8 of the chunk (two fp16)
   int np;         // pairs present (wave-uniform)
 
   // The chunk's tables: pairs u .. u+np-1 of the row-block (np may be 0: nothing is kept).
@@ -68,6 +74,9 @@ template <bool I8> struct Chunk16T {
       tab = zero_unless(lane * 4 < np_ * 64,
                         *reinterpret_cast<const uint32_t*>(tq + min(lane * 4, max(np_ * 64 - 4, 0))));
       sc = S.sc_rb[u_ld * 2 + min(lane >> 3, max(2 * np_ - 1, 0))];
+      if constexpr (BN)
+        lev = zero_unless(lane * 4 < np_ * 64,
+                          *reinterpret_cast<const uint32_t*>(S.lev_rb + (size_t)u_ld * 64 + min(lane * 4, max(np_ * 64 - 4, 0))));
     } else {
       const int cb_off = min(lane * 4, max(np_ * 32 - 4, 0));
       cbv = zero_unless(lane * 4 < np_ * 32, stream_load16(S.cb_rb + (size_t)u_ld * 32 + cb_off));
@@ -78,6 +87,8 @@ template <bool I8> struct Chunk16T {
       const _Float16 scale = __builtin_bit_cast(_Float16, (uint16_t)sc);
       *reinterpret_cast<uint2*>(lut + lane * 2) =
           make_uint2(k64_dequant_pair(tab, scale), k64_dequant_pair(tab >> 16, scale));
+      if constexpr (BN)   // each level as a dword with the fp16 value in both halves
+        *reinterpret_cast<uint2*>(lut + 128 + lane * 2) = make_uint2((lev & 0xffffu) * 0x10001u, (lev >> 16) * 0x10001u);
     } else {
       if (lane < 32) *reinterpret_cast<uint4*>(lut + lane * 4) = cbv;
     }
@@ -92,6 +103,7 @@ template <bool I8> struct Chunk16T {
       const int q = ok ? u + s : 0;                              // pair 0 always exists
       const bool ok_b = ok && 2 * q + 1 < S.n_cb;                // the pad group has no x
       w[s] = stream_load16(S.idx_rb + (size_t)q * 1024 + lane * 16);
+      if constexpr (BN) cw[s] = *reinterpret_cast<const uint2*>(S.codes_rb + (size_t)q * 64 + (lane >> 3) * 8);
       xa[s] = zero_unless(ok, *reinterpret_cast<const uint2*>(S.x + (2 * q) * 256 + lane * 4));
       xb[s] = zero_unless(ok_b, *reinterpret_cast<const uint2*>(S.x + (ok_b ? 2 * q + 1 : 0) * 256 + lane * 4));
     }
@@ -103,6 +115,15 @@ template <bool I8> struct Chunk16T {
                                           float (&acc)[8]) const {
     stage_tables(lut, lane);
     wave_lds_sync();
+    if constexpr (BN) {
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        if (s == 2 && np <= 2) break;      // short strips of a finely split row-block: half the work
+        k16_group_scaled(w[s].x, w[s].y, cw[s].x, lut + 32 * s, lut + 128 + 32 * s, xa[s].x, xa[s].y, acc);
+        k16_group_scaled(w[s].z, w[s].w, cw[s].y, lut + 32 * s + 16, lut + 128 + 32 * s + 16, xb[s].x, xb[s].y, acc);
+      }
+      return;
+    }
     k16_group<0>(w[0].x, w[0].y, base, xa[0].x, xa[0].y, acc);
     k16_group<64>(w[0].z, w[0].w, base, xb[0].x, xb[0].y, acc);
     k16_group<128>(w[1].x, w[1].y, base, xa[1].x, xa[1].y, acc);
@@ -116,8 +137,9 @@ template <bool I8> struct Chunk16T {
     acc_hazard_fence();
   }
 };
-template <> struct Chunk<16> : Chunk16T<false> {};
-template <> struct Chunk<kFmtK16I8> : Chunk16T<true> {};
+template <> struct Chunk<16> : Chunk16T<0> {};
+template <> struct Chunk<kFmtK16I8> : Chunk16T<1> {};
+template <> struct Chunk<kFmtK16BN> : Chunk16T<2> {};
 
 // d = 1, k = 4 (2-bit indices, a codebook per row of a col-block): the index bytes and the inner
 // block of k = 16, with a 16-entry pair table per row.  A chunk is 2 col-block pairs = 4 blocks of
@@ -290,7 +312,8 @@ __device__ __forceinline__ Strip make_strip(const GemvProblem& P, int rb, int sp
   S.n_cb = n_cb;
   S.sc_rb = nullptr;
   S.codes_rb = nullptr;
-  if (K == 16 || K == kFmtK16I8) {
+  S.lev_rb = nullptr;
+  if (K == 16 || K == kFmtK16I8 || K == kFmtK16BN) {
     const int n_pairs = k16_pairs(n_cb);
     S.idx_rb = P.idx + (size_t)rb * n_pairs * 1024;
     if (K == 16) {
@@ -299,6 +322,12 @@ __device__ __forceinline__ Strip make_strip(const GemvProblem& P, int rb, int sp
       S.cb_rb = P.cb + (size_t)rb * n_pairs * 16;
       S.sc_rb = reinterpret_cast<const uint16_t*>(P.cb + (size_t)P.n_rb * n_pairs * 16) +
                 (size_t)rb * n_pairs * 2;
+      if (K == kFmtK16BN) {   // levels (32 bytes per slot) and codes (64 bytes per pair) behind the scales
+        const size_t n_slots = (size_t)P.n_rb * n_pairs * 2;
+        const uint8_t* tb = reinterpret_cast<const uint8_t*>(P.cb);
+        S.lev_rb = tb + k16bn_level_offset(n_slots) + (size_t)rb * n_pairs * 64;
+        S.codes_rb = tb + k16bn_code_offset(n_slots) + (size_t)rb * n_pairs * 64;
+      }
     }
     S.u = (n_pairs * split) / splits;
     S.u_end = (n_pairs * (split + 1)) / splits;
@@ -405,13 +434,16 @@ __device__ __forceinline__ int find_problem(const GemvBatch& batch, int item) {
 // by zeroed col-blocks that the absent units of a ragged chunk read.
 template <int K> struct ChunkS;
 
-template <bool I8> struct ChunkS16T {
+template <int MODE> struct ChunkS16T {
+  static constexpr bool I8 = MODE >= 1, BN = MODE == 2;
   static constexpr int kUnits = 4;
-  static constexpr int kLutDwords = 128;
+  static constexpr int kLutDwords = BN ? 256 : 128;
   uint4 w[4];
   uint4 cbv;       // fp16 codebooks (lanes 0..31), or
   uint32_t tab;    // two int8 centroid pairs and
   uint32_t sc;     // their group's fp16 scale
+  uint2 cw[4];     // BN: see Chunk16T
+  uint32_t lev;
   int u0;          // first pair (locates the activations in LDS), wave-uniform
 
   __device__ __forceinline__ void load(const Strip& S, int u, int lane) {
@@ -423,6 +455,13 @@ template <bool I8> struct ChunkS16T {
       tab = zero_unless(lane * 4 < np * 64,
                         *reinterpret_cast<const uint32_t*>(tq + min(lane * 4, max(np * 64 - 4, 0))));
       sc = S.sc_rb[u_ld * 2 + min(lane >> 3, max(2 * np - 1, 0))];
+      if constexpr (BN) {
+        lev = zero_unless(lane * 4 < np * 64,
+                          *reinterpret_cast<const uint32_t*>(S.lev_rb + (size_t)u_ld * 64 + min(lane * 4, max(np * 64 - 4, 0))));
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+          cw[s] = *reinterpret_cast<const uint2*>(S.codes_rb + (size_t)(s < np ? u + s : 0) * 64 + (lane >> 3) * 8);
+      }
     } else {
       const int cb_off = min(lane * 4, max(np * 32 - 4, 0));
       cbv = zero_unless(lane * 4 < np * 32, stream_load16(S.cb_rb + (size_t)u_ld * 32 + cb_off));
@@ -445,11 +484,22 @@ template <bool I8> struct ChunkS16T {
       const _Float16 scale = __builtin_bit_cast(_Float16, (uint16_t)sc);
       *reinterpret_cast<uint2*>(lut + lane * 2) =
           make_uint2(k64_dequant_pair(tab, scale), k64_dequant_pair(tab >> 16, scale));
+      if constexpr (BN)
+        *reinterpret_cast<uint2*>(lut + 128 + lane * 2) = make_uint2((lev & 0xffffu) * 0x10001u, (lev >> 16) * 0x10001u);
     } else {
       if (lane < 32) *reinterpret_cast<uint4*>(lut + lane * 4) = cbv;
     }
     wave_lds_sync();
     const uint2* xp = reinterpret_cast<const uint2*>(x_s) + u0 * 128 + lane;   // 64 uint2 per col-block
+    if constexpr (BN) {       // absent pairs: zero tables and levels against the zeroed col-blocks behind x
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        const uint2 xa = xp[128 * s], xb = xp[128 * s + 64];
+        k16_group_scaled(w[s].x, w[s].y, cw[s].x, lut + 32 * s, lut + 128 + 32 * s, xa.x, xa.y, acc);
+        k16_group_scaled(w[s].z, w[s].w, cw[s].y, lut + 32 * s + 16, lut + 128 + 32 * s + 16, xb.x, xb.y, acc);
+      }
+      return;
+    }
     uint2 x0 = xp[0], x1 = xp[64];
     k16_group<0>(w[0].x, w[0].y, base, x0.x, x0.y, acc);
     x0 = xp[128];
@@ -468,8 +518,9 @@ template <bool I8> struct ChunkS16T {
     acc_hazard_fence();
   }
 };
-template <> struct ChunkS<16> : ChunkS16T<false> {};
-template <> struct ChunkS<kFmtK16I8> : ChunkS16T<true> {};
+template <> struct ChunkS<16> : ChunkS16T<0> {};
+template <> struct ChunkS<kFmtK16I8> : ChunkS16T<1> {};
+template <> struct ChunkS<kFmtK16BN> : ChunkS16T<2> {};
 
 template <> struct ChunkS<kFmtD1K4> {
   static constexpr int kUnits = 2;
@@ -892,6 +943,7 @@ __global__ __launch_bounds__(64 * WPW) void gemv_split_kernel(const typename Bat
     case kFmtK16I8: F(kFmtK16I8); break;      \
     case kFmtD1K16: F(kFmtD1K16); break;      \
     case kFmtK64BN: F(kFmtK64BN); break;      \
+    case kFmtK16BN: F(kFmtK16BN); break;      \
     case kFmtD1K8: F(kFmtD1K8); break;        \
     case kFmtD1K4: F(kFmtD1K4); break;        \
     default: F(256); break;                   \
@@ -913,10 +965,10 @@ inline size_t stream_lds_bytes_impl(int fmt, int max_n_cb) {
 // piece of state the library keeps).  The slots are atomics: two threads that fill the same
 // slot at once store the same value.  The query enqueues nothing on any stream.
 template <bool LORA> int stream_resident_wgs_impl(int fmt, int max_n_cb) {
-  static std::atomic<int> cached[8][16][kStreamMaxColBlocks + 1];
+  static std::atomic<int> cached[9][16][kStreamMaxColBlocks + 1];
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) dev = 0;
-  const int fi = fmt == 16 ? 0 : fmt == 64 ? 1 : fmt == kFmtK16I8 ? 3 : fmt == kFmtD1K16 ? 4 : fmt == kFmtK64BN ? 5 : fmt == kFmtD1K8 ? 6 : fmt == kFmtD1K4 ? 7 : 2;
+  const int fi = fmt == 16 ? 0 : fmt == 64 ? 1 : fmt == kFmtK16I8 ? 3 : fmt == kFmtD1K16 ? 4 : fmt == kFmtK64BN ? 5 : fmt == kFmtD1K8 ? 6 : fmt == kFmtD1K4 ? 7 : fmt == kFmtK16BN ? 8 : 2;
   int slot = cached[fi][dev][max_n_cb].load(std::memory_order_relaxed);
   if (slot == 0) {
     int per_cu = 0, cus = 0;

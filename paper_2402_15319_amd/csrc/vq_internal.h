@@ -18,6 +18,7 @@ constexpr int kFmtK16I8 = 1016;
 constexpr int kFmtK256I8 = 1256;   // d = 2, k = 256, int8 tables + scale, groups of 64, 128 or 256 rows x 256 columns
 constexpr int kFmtD1K16 = 2016;
 constexpr int kFmtK64BN = 3064;   // k = 64, int8 tables + scale, blockwise normalisation (blocks of 32)
+constexpr int kFmtK16BN = 3016;   // k = 16, int8 tables + scale, blockwise normalisation (blocks of 32)
 constexpr int kFmtD1K8 = 2008;     // d = 1, k = 8 (3-bit indices), int8 values + scale: pairs index a 64-entry pair table
 constexpr int kFmtD1K4 = 2004;     // d = 1, k = 4 (2-bit indices), int8 values + scale, one codebook per row of a
                                    // col-block (groups of 1 x 256): pairs index a 16-entry pair table per row
@@ -26,11 +27,17 @@ constexpr int kFmtD4 = 4256;      // d = 4, k = 256 (one index byte per 4 weight
 inline int format_tag(const vq_desc& d) {
   if (d.d == 1) return d.k == 8 ? kFmtD1K8 : d.k == 4 ? kFmtD1K4 : kFmtD1K16;
   if (d.d == 4) return kFmtD4;
-  if (d.codebook_dtype == VQ_I8_BN) return kFmtK64BN;
+  if (d.codebook_dtype == VQ_I8_BN) return d.k == 16 ? kFmtK16BN : kFmtK64BN;
   if (d.k == 16 && d.codebook_dtype == VQ_I8) return kFmtK16I8;
   if (d.k == 256 && d.codebook_dtype == VQ_I8) return kFmtK256I8;
   return d.k;
 }
+// k = 16 with int8 tables and blockwise normalisation: byte offsets of the levels and of the block
+// codes inside the device-layout table buffer of a matrix with n_slots group slots, and its size
+// (the layout itself is described in vq_device.h).
+__host__ __device__ constexpr size_t k16bn_level_offset(size_t n_slots) { return (34 * n_slots + 15) / 16 * 16; }
+__host__ __device__ constexpr size_t k16bn_code_offset(size_t n_slots) { return k16bn_level_offset(n_slots) + 32 * n_slots; }
+__host__ __device__ constexpr size_t k16bn_table_bytes(size_t n_slots) { return k16bn_code_offset(n_slots) + 32 * n_slots; }
 constexpr int kStreamMaxColBlocks = 96;   // widest x the streaming kernel stages in LDS (48 KB)
 
 // One matrix-vector product as the kernels see it (lives in the kernel arguments).

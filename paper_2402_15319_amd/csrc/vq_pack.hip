@@ -102,6 +102,38 @@ __global__ __launch_bounds__(256) void pack_tab16_kernel(const uint32_t* __restr
   }
 }
 
+// k = 16 with blockwise normalisation: the levels and block codes behind tables and scales.
+// Levels: canonical lev[group][16] fp16 -> 8 dwords per slot (zero for the pad slot).  Codes:
+// canonical code[r][c/32] (two per byte, even block in the low nibble, 4*n_cb bytes per row) ->
+// 16 dwords per col-block pair: dword 2*b + e = codes of block b of the pair's col-block e, row r
+// in bits [4r, 4r+4).  One thread per (slot, j < 8): level dword j and the code dword of block j.
+__global__ __launch_bounds__(256) void pack_bn16_kernel(const uint32_t* __restrict__ lev_canon,
+                                                        const uint8_t* __restrict__ code_canon,
+                                                        uint32_t* __restrict__ lev_dev,
+                                                        uint32_t* __restrict__ code_dev, int n_cb,
+                                                        long long n_slots) {
+  const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (t >= n_slots * 8) return;
+  const int slots_per_rb = 2 * k16_pairs(n_cb);
+  const long long slot = t >> 3;
+  const int j = (int)(t & 7);
+  const long long rb = slot / slots_per_rb;
+  const int c = (int)(slot - rb * slots_per_rb);
+  const bool ok = c < n_cb;
+  lev_dev[t] = ok ? lev_canon[(rb * n_cb + c) * 8 + j] : 0u;
+  uint32_t w = 0;
+  if (ok) {
+    const int blk = c * 8 + j;                       // block index inside the row
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+      const uint32_t byte = code_canon[(size_t)(rb * 8 + r) * (4 * n_cb) + (blk >> 1)];
+      w |= ((blk & 1) ? byte >> 4 : byte & 15u) << (4 * r);
+    }
+  }
+  // slot = rb * slots_per_rb + c: pair c / 2, col-block e = c & 1 of the pair
+  code_dev[(slot >> 1) * 16 + 2 * j + (c & 1)] = w;
+}
+
 // d = 1, k = 4: per (8-row block, col-block slot) 48 bytes: the 4 int8 values of each of the 8
 // rows, then the 8 rows' fp16 scales (zero for the pad slot).  Canonical group of row R and
 // col-block c: R * n_cb + c.  One thread per (slot, row).
@@ -351,7 +383,7 @@ hipError_t launch_pack(const vq_desc& d, const void* idx_canon, const void* cb_c
                        (const uint8_t*)cb_canon, (uint8_t*)cb_dev, n16, src_bytes);
     return hipGetLastError();
   }
-  const int slots_per_rb = (fmt == 16 || fmt == kFmtK16I8 || fmt == kFmtD1K4) ? 2 * k16_pairs(n_cb) : n_cb;
+  const int slots_per_rb = (fmt == 16 || fmt == kFmtK16I8 || fmt == kFmtK16BN || fmt == kFmtD1K4) ? 2 * k16_pairs(n_cb) : n_cb;
   const long long n_slots = n_rb * slots_per_rb;
   if (fmt == kFmtD1K4) {
     hipLaunchKernelGGL(pack_idx_kernel<16>, dim3((unsigned)((n_slots * 64 + 255) / 256)), dim3(256), 0, s,
@@ -364,7 +396,7 @@ hipError_t launch_pack(const vq_desc& d, const void* idx_canon, const void* cb_c
                        (uint8_t*)cb_dev, n_cb, n_slots);
     return hipGetLastError();
   }
-  if (fmt == kFmtK16I8) {
+  if (fmt == kFmtK16I8 || fmt == kFmtK16BN) {
     hipLaunchKernelGGL(pack_idx_kernel<16>, dim3((unsigned)((n_slots * 64 + 255) / 256)), dim3(256), 0, s,
                        (const uint8_t*)idx_canon, (uint8_t*)idx_dev, n_cb, n_slots, 0, 1);
     hipError_t e = hipGetLastError();
@@ -373,6 +405,17 @@ hipError_t launch_pack(const vq_desc& d, const void* idx_canon, const void* cb_c
     hipLaunchKernelGGL(pack_tab16_kernel, dim3((unsigned)((n_slots * 8 + 255) / 256)), dim3(256), 0, s,
                        (const uint32_t*)cb_canon, (const uint16_t*)((const uint8_t*)cb_canon + q_bytes),
                        (uint32_t*)cb_dev, n_cb, n_slots);
+    e = hipGetLastError();
+    if (e != hipSuccess || fmt == kFmtK16I8) return e;
+    // blockwise normalisation: levels follow the scales (padded to 16 bytes), codes follow the levels;
+    // the bytes between the scales and the levels of the device buffer (up to 15) are never read
+    const size_t s_bytes = ((size_t)n_rb * n_cb * 2 + 15) / 16 * 16;
+    const uint8_t* canon = (const uint8_t*)cb_canon;
+    const uint8_t* lev_canon = canon + q_bytes + s_bytes;
+    hipLaunchKernelGGL(pack_bn16_kernel, dim3((unsigned)((n_slots * 8 + 255) / 256)), dim3(256), 0, s,
+                       (const uint32_t*)lev_canon, lev_canon + (size_t)n_rb * n_cb * 32,
+                       (uint32_t*)((uint8_t*)cb_dev + k16bn_level_offset((size_t)n_slots)),
+                       (uint32_t*)((uint8_t*)cb_dev + k16bn_code_offset((size_t)n_slots)), n_cb, n_slots);
     return hipGetLastError();
   }
   const unsigned grid = (unsigned)((n_slots * 64 + 255) / 256);

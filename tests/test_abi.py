@@ -231,7 +231,7 @@ def test_quantiser_entry_points_validate_before_launch():
 
 
 def test_block_normalised_representation_sizes_and_validation():
-    """VQ_I8_BN: k = 64 only; canonical = tables | scales | 16 levels per group | nibble codes;
+    """VQ_I8_BN: k = 64 and k = 16; canonical = tables | scales | 16 levels per group | nibble codes;
     device = 672-byte table records per (group row, quad) + 128 bytes of codes per (8-row block, quad)."""
     L = vq.lib()
     for out_f, in_f, rows in ((4096, 4096, 32), (4096, 11008, 32), (64, 768, 8)):
@@ -243,8 +243,24 @@ def test_block_normalised_representation_sizes_and_validation():
         quads = (in_f // 256 + 3) // 4
         assert vq.vq_layout_bytes(d) == ((out_f // 8) * quads * 3072, (out_f // rows) * quads * 672 + (out_f // 8) * quads * 128)
         assert L.vq_gemv(ctypes.byref(d), A, A, A + 2, A + 16, vq.VQ_F16, 0) == -4
-    bad = vq.make_desc(4096, 4096, 16, 4, codebook_dtype=vq.VQ_I8_BN)
-    assert L.vq_gemv(ctypes.byref(bad), A, A, A, A + 16, vq.VQ_F16, 0) == -3
+    # k = 16 (8 x 256 groups): 64 bytes of levels and codes per group on top of the int8-table format;
+    # device = 34 bytes of table and scale per slot, padded to 16, then 32 + 32 bytes per slot
+    for out_f, in_f in ((4096, 4096), (4096, 11008), (8, 256)):
+        d = vq.make_desc(out_f, in_f, 16, 4, codebook_dtype=vq.VQ_I8_BN)
+        n_groups = (out_f // 8) * (in_f // 256)
+        ib, cbb = vq.vq_canonical_bytes(d)
+        assert ib == out_f * in_f // 4
+        assert cbb == n_groups * 32 + (n_groups * 2 + 15) // 16 * 16 + n_groups * 32 + out_f * in_f // 64
+        assert (ib + cbb) * 8 / (out_f * in_f) == pytest.approx(2.3828125 + ((n_groups * 2 + 15) // 16 * 16 - n_groups * 2) * 8 / (out_f * in_f))
+        slots = (out_f // 8) * 2 * ((in_f // 256 + 1) // 2)
+        assert vq.vq_layout_bytes(d) == (slots * 512, (34 * slots + 15) // 16 * 16 + 64 * slots)
+        assert L.vq_gemv(ctypes.byref(d), A, A, A + 2, A + 16, vq.VQ_F16, 0) == -4
+    # the other representations do not take block scales
+    for bad in (vq.make_desc(4096, 4096, 256, 8, group_rows=128, codebook_dtype=vq.VQ_I8_BN),
+                vq.make_desc(4096, 4096, 8, 3, group_rows=32, d=1, codebook_dtype=vq.VQ_I8_BN),
+                vq.make_desc(4096, 4096, 256, 8, group_rows=256, d=4, codebook_dtype=vq.VQ_I8_BN),
+                vq.make_desc(4096, 4096, 16, 4, group_rows=16, codebook_dtype=vq.VQ_I8_BN)):
+        assert L.vq_gemv(ctypes.byref(bad), A, A, A, A + 16, vq.VQ_F16, 0) == -3
     assert L.vq_em_assign(ctypes.byref(vq.make_desc(4096, 4096, 64, 6, codebook_dtype=vq.VQ_I8_BN)), A, A + 4, A, A, 0) == -4
 
 

@@ -231,7 +231,7 @@ PASS_FORMATS = {
     "k16": workloads.LLAMA7B_LAYER, "k64_i8": workloads.LLAMA7B_LAYER_K64, "k16_i8": workloads.LLAMA7B_LAYER_K16_I8,
     "k256_i8": workloads.LLAMA7B_LAYER_K256_I8, "d4": workloads.LLAMA7B_LAYER_D4, "d1_k16": workloads.LLAMA7B_LAYER_D1_K16,
     "d1_k8": workloads.LLAMA7B_LAYER_D1_K8, "d1_k4": workloads.LLAMA7B_LAYER_D1_K4,
-    "k64_bn": workloads.LLAMA7B_LAYER_K64_BN,
+    "k64_bn": workloads.LLAMA7B_LAYER_K64_BN, "k16_bn": workloads.LLAMA7B_LAYER_K16_BN,
 }
 
 
@@ -891,6 +891,58 @@ def test_block_norm_deployed_shape(env):
     _assert_tiles_match(_gpu_gemm(env, desc, idx_d, cb_d, X, False), _dense_product(W, X))
 
 
+# ---------------------------------------------------------------- blockwise normalisation on the k = 16 int8-table format
+def _shape_bn16(o, i):
+    return workloads.VQShape(o, i, 16, 4, 8, 256, 2, True, True)
+
+
+# one and several chunks per strip, odd col-block counts (a pad group), one to eight waves per row-block
+BN16_SMALL = [_shape_bn16(8, 256), _shape_bn16(40, 768), _shape_bn16(24, 2816), _shape_bn16(264, 1024),
+              _shape_bn16(16, 256 * 43), _shape_bn16(72, 256 * 9)]
+
+
+@pytest.mark.parametrize("s", BN16_SMALL, ids=str)
+def test_block_norm_k16_decode_bit_exact(env, s):
+    desc, W, idx_d, cb_d = _setup_bn(env, s, 710)
+    np.testing.assert_array_equal(_gpu_decode(env, desc, idx_d, cb_d), W)
+
+
+@pytest.mark.parametrize("f32", [False, True], ids=["y16", "y32"])
+@pytest.mark.parametrize("s", BN16_SMALL + [_shape_bn16(32776, 768), _shape_bn16(32776, 2816)], ids=str)
+def test_block_norm_k16_gemv(env, s, f32):
+    """Split-K kernel on the small shapes, the streaming kernel from 4,096 row-blocks."""
+    desc, W, idx_d, cb_d = _setup_bn(env, s, 711)
+    x = workloads.make_x(s.in_features, 711)
+    y = _gpu_gemv(env, desc, idx_d, cb_d, x, f32)
+    ref = _dense_product(W, x)
+    assert oracle.normwise_rel_err(y, ref) <= (TOL_F32 if f32 else TOL_F16)
+    if s.out_features >= 4096:
+        _assert_rows_match(y, ref, f32, str(s))
+
+
+@pytest.mark.parametrize("B", [1, 16, 40, 130, 600, 1300])
+@pytest.mark.parametrize("s", [_shape_bn16(96, 768), _shape_bn16(808, 512)], ids=str)
+def test_block_norm_k16_gemm(env, s, B):
+    desc, W, idx_d, cb_d = _setup_bn(env, s, 712)
+    X = workloads.make_X(s.in_features, B, 712)
+    Y = _gpu_gemm(env, desc, idx_d, cb_d, X, False, pad=8 if B == 40 else 0)
+    assert oracle.normwise_rel_err(Y, _dense_product(W, X)) <= TOL_F16
+
+
+@pytest.mark.timeout(600)
+def test_block_norm_k16_full_size(env):
+    """4096 x 11008 (43 col-blocks: a pad group in every row-block): decode in full, GEMV with both
+    output types element by element, and the whole B = 2048 product, tile by tile."""
+    s = workloads.CONFIGS["mlp_down_4096x11008_k16_bn"]
+    desc, W, idx_d, cb_d = _setup_bn(env, s, 713)
+    np.testing.assert_array_equal(_gpu_decode(env, desc, idx_d, cb_d), W)
+    x = workloads.make_x(s.in_features, 713)
+    _assert_rows_match(_gpu_gemv(env, desc, idx_d, cb_d, x, False), _dense_product(W, x), False, "bn16 y16")
+    _assert_rows_match(_gpu_gemv(env, desc, idx_d, cb_d, x, True), _dense_product(W, x), True, "bn16 y32")
+    X = workloads.make_X(s.in_features, 2048, 713)
+    _assert_tiles_match(_gpu_gemm(env, desc, idx_d, cb_d, X, False), _dense_product(W, X))
+
+
 # ---------------------------------------------------------------- four-dimensional vectors (d = 4, k = 256, int8 tables)
 def _shape_d4(o, i, rows=256):
     return workloads.VQShape(o, i, 256, 8, rows, 256, 4, True)
@@ -1136,6 +1188,37 @@ def test_random_shapes_newer_representations(env, s):
     X = workloads.make_X(s.in_features, B, seed)
     Y = _gpu_gemm(env, desc, idx_d, cb_d, X, True)
     assert oracle.normwise_rel_err(Y, oracle.gemm(f, idx, cb, X)) <= TOL_F32
+
+
+def _random_cases_bn(seed, n):
+    """Seeded random shapes of the two block-normalised representations (k = 64 with 8-, 16- or 32-row
+    groups; k = 16), up to 44 col-blocks wide."""
+    rng = np.random.default_rng(seed)
+    cases = []
+    for _ in range(n):
+        n_cb = int(rng.integers(1, 45))
+        if rng.integers(0, 2):
+            cases.append(_shape_bn16(8 * int(rng.integers(1, 40)), 256 * n_cb))
+        else:
+            rows = int(rng.choice([8, 16, 32]))
+            cases.append(_shape_bn(rows * int(rng.integers(1, 12)), 256 * n_cb, rows))
+    return cases
+
+
+@pytest.mark.parametrize("s", _random_cases_bn(20242, 16), ids=str)
+def test_random_shapes_block_normalised(env, s):
+    """Decode (bit-exact), GEMV (fp16 and fp32 y) and the batched product on random shapes."""
+    seed = 7200 + s.out_features + s.in_features + s.k
+    desc, W, idx_d, cb_d = _setup_bn(env, s, seed)
+    np.testing.assert_array_equal(_gpu_decode(env, desc, idx_d, cb_d), W)
+    x = workloads.make_x(s.in_features, seed)
+    ref = _dense_product(W, x)
+    assert oracle.normwise_rel_err(_gpu_gemv(env, desc, idx_d, cb_d, x, False), ref) <= TOL_F16
+    assert oracle.normwise_rel_err(_gpu_gemv(env, desc, idx_d, cb_d, x, True), ref) <= TOL_F32
+    B = int(np.random.default_rng(seed).choice([1, 3, 8, 17, 33, 72, 200]))
+    X = workloads.make_X(s.in_features, B, seed)
+    Y = _gpu_gemm(env, desc, idx_d, cb_d, X, True)
+    assert oracle.normwise_rel_err(Y, _dense_product(W, X)) <= TOL_F32
 
 
 def test_newer_kernels_replay_in_a_hip_graph(env):

@@ -23,7 +23,7 @@ __all__ = [
     "VQShape", "CONFIGS", "LLAMA7B_LAYER", "seed_for", "canonical_sizes",
     "make_weights", "make_weights_i8", "make_x", "make_X", "llama7b_pass_shapes",
     "tables_i8_bytes", "tables_bn_bytes",
-    "LLAMA7B_LAYER_K64", "LLAMA7B_LAYER_K16_I8", "LLAMA7B_LAYER_D1_K16", "LLAMA7B_LAYER_K64_BN", "make_weights_bn", "LLAMA7B_LAYER_D4", "LLAMA7B_LAYER_D1_K8", "LLAMA7B_LAYER_K256_I8", "LLAMA7B_LAYER_D1_K4",
+    "LLAMA7B_LAYER_K64", "LLAMA7B_LAYER_K16_I8", "LLAMA7B_LAYER_D1_K16", "LLAMA7B_LAYER_K64_BN", "LLAMA7B_LAYER_K16_BN", "make_weights_bn", "LLAMA7B_LAYER_D4", "LLAMA7B_LAYER_D1_K8", "LLAMA7B_LAYER_K256_I8", "LLAMA7B_LAYER_D1_K4",
 ]
 
 
@@ -108,6 +108,10 @@ CONFIGS = {
     "attn_4096x4096_k64_bn": VQShape(4096, 4096, 64, 6, 32, 256, 2, True, True),
     "mlp_up_11008x4096_k64_bn": VQShape(11008, 4096, 64, 6, 32, 256, 2, True, True),
     "mlp_down_4096x11008_k64_bn": VQShape(4096, 11008, 64, 6, 32, 256, 2, True, True),
+    # k = 16 (the 2.125 bpv setting) with blockwise normalisation: + 16 levels and 64 codes per group
+    "attn_4096x4096_k16_bn": VQShape(4096, 4096, 16, 4, 8, 256, 2, True, True),
+    "mlp_up_11008x4096_k16_bn": VQShape(11008, 4096, 16, 4, 8, 256, 2, True, True),
+    "mlp_down_4096x11008_k16_bn": VQShape(4096, 11008, 16, 4, 8, 256, 2, True, True),
 }
 
 # One Llama-7B decoder layer as (name, shape key) in execution order.
@@ -124,6 +128,7 @@ LLAMA7B_LAYER_K64 = tuple((n, k.replace("_k16", "_k64_i8")) for n, k in LLAMA7B_
 LLAMA7B_LAYER_K256_I8 = tuple((n, k.replace("_k16", "_k256_i8")) for n, k in LLAMA7B_LAYER)
 LLAMA7B_LAYER_K16_I8 = tuple((n, k + "_i8") for n, k in LLAMA7B_LAYER)
 LLAMA7B_LAYER_K64_BN = tuple((n, k.replace("_k16", "_k64_bn")) for n, k in LLAMA7B_LAYER)
+LLAMA7B_LAYER_K16_BN = tuple((n, k + "_bn") for n, k in LLAMA7B_LAYER)
 LLAMA7B_LAYER_D1_K8 = tuple((n, k.replace("_k16", "_d1_k8")) for n, k in LLAMA7B_LAYER)
 LLAMA7B_LAYER_D1_K4 = tuple((n, k.replace("_k16", "_d1_k4")) for n, k in LLAMA7B_LAYER)
 LLAMA7B_LAYER_D4 = tuple((n, k.replace("_k16", "_d4")) for n, k in LLAMA7B_LAYER)
