@@ -567,6 +567,11 @@ def test_block_normalised_format_sizes():
     assert ib == oracle.canonical_sizes_i8(f)[0]
     assert tb == f.n_groups * 128 + f.n_groups * 2 + f.n_groups * 32 + 4096 * 128 // 2
     assert (ib + tb) * 8 / (4096 * 4096) == 3 + (1024 + 16 + 256) / 8192 + 4 / 32
+    # 8 x 256 groups, k = 16, 4-bit (the 2.125 bpv setting): 2 + (16*2*8 + 16 + 16*16)/2048 + 4/32 = 2.383
+    f = VQFormat(4096, 4096, 16, 4, 8, 256, 2)
+    ib, tb = oracle.canonical_sizes_bn(f)
+    assert ib == oracle.canonical_sizes_i8(f)[0]
+    assert (ib + tb) * 8 / (4096 * 4096) == 2 + (256 + 16 + 256) / 2048 + 4 / 32 == 2.3828125
 
 
 # ---------------------------------------------------------------- four-dimensional vectors (d = 4)
