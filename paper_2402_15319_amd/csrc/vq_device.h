@@ -239,15 +239,25 @@ __device__ __forceinline__ void k64_group(uint32_t d0, uint32_t d1, uint32_t d2,
 // (v_pk_mul_f16: one rounding, exactly the decoded weight) and go into the dot products.  The
 // lookups of row r + 4 are issued as soon as row r has been consumed, so 9 to 12 LDS reads are
 // always in flight.  OFF: byte offset of the col-block's table, LOFF: of its 16 level dwords.
+// The codes are spread once per block into two dwords of pre-scaled bytes (ca: 4 * code of rows
+// 0, 2, 4, 6; cb: of rows 1, 3, 5, 7), so that a level's address is one SDWA add.
 #define VQ_BN_RD(R, W, BIT, WIDTH, OFF)                  \
   "v_bfe_u32 " R ", " W ", " #BIT ", " #WIDTH "\n"       \
   "v_lshl_add_u32 " R ", " R ", 2, %[base]\n"            \
   "ds_read_b32 " R ", " R " offset:" OFF "\n"
 #define VQ_BN_ROW(RA, WA, BA, RB, WB, BB, RS, ROW)                                       \
   VQ_BN_RD(RA, WA, BA, 6, "%[off]") VQ_BN_RD(RB, WB, BB, 6, "%[off]")                    \
-  "v_bfe_u32 " RS ", %[cw], 4*" #ROW ", 4\n"                                             \
-  "v_lshl_add_u32 " RS ", " RS ", 2, %[base]\n"                                          \
+  "v_add_u32_sdwa " RS ", %[base], %[c" #ROW "]"                                          \
+  " dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_" VQ_BN_BYTE_##ROW "\n" \
   "ds_read_b32 " RS ", " RS " offset:%[loff]\n"
+#define VQ_BN_BYTE_0 "0"
+#define VQ_BN_BYTE_1 "0"
+#define VQ_BN_BYTE_2 "1"
+#define VQ_BN_BYTE_3 "1"
+#define VQ_BN_BYTE_4 "2"
+#define VQ_BN_BYTE_5 "2"
+#define VQ_BN_BYTE_6 "3"
+#define VQ_BN_BYTE_7 "3"
 #define VQ_BN_USE(ACC, RA, RB, RS)                       \
   "v_pk_mul_f16 " RA ", " RA ", " RS "\n"                \
   "v_pk_mul_f16 " RB ", " RB ", " RS "\n"                \
@@ -259,6 +269,7 @@ __device__ __forceinline__ void k64_group_bn(uint32_t d0, uint32_t d1, uint32_t 
                                              uint32_t t10, uint32_t cw, uint32_t base, uint32_t x0,
                                              uint32_t x1, float (&acc)[8]) {
   uint32_t r0, r1, r2, r3, r4, r5, r6, r7, r8, r9, r10, r11;
+  const uint32_t ca = (cw << 2) & 0x3c3c3c3cu, cb = (cw >> 2) & 0x3c3c3c3cu;
   asm volatile(
       VQ_BN_ROW("%[r0]", "%[d0]", 0, "%[r1]", "%[d0]", 6, "%[r2]", 0)
       VQ_BN_ROW("%[r3]", "%[d0]", 12, "%[r4]", "%[d0]", 18, "%[r5]", 1)
@@ -289,13 +300,22 @@ __device__ __forceinline__ void k64_group_bn(uint32_t d0, uint32_t d1, uint32_t 
         [r0] "=&v"(r0), [r1] "=&v"(r1), [r2] "=&v"(r2), [r3] "=&v"(r3), [r4] "=&v"(r4),
         [r5] "=&v"(r5), [r6] "=&v"(r6), [r7] "=&v"(r7), [r8] "=&v"(r8), [r9] "=&v"(r9),
         [r10] "=&v"(r10), [r11] "=&v"(r11)
-      : [d0] "v"(d0), [d1] "v"(d1), [d2] "v"(d2), [t5] "v"(t5), [t10] "v"(t10), [cw] "v"(cw),
-        [base] "s"(base), [x0] "v"(x0), [x1] "v"(x1), [off] "n"(OFF), [loff] "n"(LOFF)
+      : [d0] "v"(d0), [d1] "v"(d1), [d2] "v"(d2), [t5] "v"(t5), [t10] "v"(t10),
+        [c0] "v"(ca), [c1] "v"(cb), [c2] "v"(ca), [c3] "v"(cb), [c4] "v"(ca), [c5] "v"(cb), [c6] "v"(ca),
+        [c7] "v"(cb), [base] "s"(base), [x0] "v"(x0), [x1] "v"(x1), [off] "n"(OFF), [loff] "n"(LOFF)
       : "memory");
 }
 #undef VQ_BN_RD
 #undef VQ_BN_ROW
 #undef VQ_BN_USE
+#undef VQ_BN_BYTE_0
+#undef VQ_BN_BYTE_1
+#undef VQ_BN_BYTE_2
+#undef VQ_BN_BYTE_3
+#undef VQ_BN_BYTE_4
+#undef VQ_BN_BYTE_5
+#undef VQ_BN_BYTE_6
+#undef VQ_BN_BYTE_7
 
 // ---- 6-bit / int8-table device layout (k = 64) -------------------------------------------
 // Indices: per (8-row block, quad of 4 col-blocks) three planes of 1 KB; the lane's 48 bytes
