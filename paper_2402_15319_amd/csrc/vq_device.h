@@ -53,6 +53,13 @@ __device__ __forceinline__ void wave_lds_sync() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// The pre-scaled 4-bit layout of a dword (4 rows x 2 vectors): a = 4 * index of vector 2L in each
+// byte, b = 4 * index of vector 2L + 1.
+__device__ __forceinline__ void k16_split_dword(uint32_t w, uint32_t& a, uint32_t& b) {
+  a = w & 0x3c3c3c3cu;
+  b = __builtin_amdgcn_alignbit(w, w, 4) & 0x3c3c3c3cu;
+}
+
 // ---------------------------------------------------------------------------
 // k = 16 inner block: all 16 lookups + dot products of one lane's share of one
 // group (two dwords = 8 rows x 2 vectors), hand-scheduled.
@@ -122,6 +129,71 @@ __device__ __forceinline__ void k16_group(uint32_t w0, uint32_t w1, uint32_t bas
 #undef VQ_SDWA_RD
 #undef VQ_MASKS
 #undef VQ_DOT
+
+// k = 16 inner block with blockwise normalisation, hand-scheduled (the streaming kernel's
+// version of k16_group_scaled): per row the two centroid pairs and the row's block scale (a dword
+// with the fp16 level in both halves, selected by the row's 4-bit code in cw) are looked up, both
+// pairs are multiplied by the scale (one rounding: exactly the decoded weight) and go into the
+// dot products.  Index bytes as in k16_group; the codes are spread once per block into two dwords
+// of pre-scaled bytes (ca: 4 * code of rows 0, 2, 4, 6; cb: of rows 1, 3, 5, 7), so every address
+// is one SDWA add.  Rows r + 4 are requested as soon as row r has been consumed: 9 to 12 LDS reads
+// in flight.  OFF: byte offset of the group's table, LOFF: of its 16 level dwords.
+#define VQ_B16_RD(R, T, B, OFF)                                                          \
+  "v_add_u32_sdwa " R ", %[base], " T                                                    \
+  " dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_" #B "\n"           \
+  "ds_read_b32 " R ", " R " offset:" OFF "\n"
+#define VQ_B16_ROW(RA, RB, RS, TA, TB, B, C, CB)                                         \
+  VQ_B16_RD(RA, TA, B, "%[off]") VQ_B16_RD(RB, TB, B, "%[off]") VQ_B16_RD(RS, C, CB, "%[loff]")
+#define VQ_B16_USE(ACC, RA, RB, RS)                      \
+  "v_pk_mul_f16 " RA ", " RA ", " RS "\n"                \
+  "v_pk_mul_f16 " RB ", " RB ", " RS "\n"                \
+  "v_dot2c_f32_f16 " ACC ", " RA ", %[x0]\n"             \
+  "v_dot2c_f32_f16 " ACC ", " RB ", %[x1]\n"
+template <int OFF, int LOFF>
+__device__ __forceinline__ void k16_group_bn(uint32_t w0, uint32_t w1, uint32_t cw, uint32_t base,
+                                             uint32_t x0, uint32_t x1, float (&acc)[8]) {
+  uint32_t r0, r1, r2, r3, r4, r5, r6, r7, r8, r9, r10, r11;
+  const uint32_t ca = (cw << 2) & 0x3c3c3c3cu, cb = (cw >> 2) & 0x3c3c3c3cu;
+  uint32_t ta0, tb0, ta1, tb1;
+  k16_split_dword(w0, ta0, tb0);
+  k16_split_dword(w1, ta1, tb1);
+  asm volatile(
+      VQ_B16_ROW("%[r0]", "%[r1]", "%[r2]", "%[ta0]", "%[tb0]", 0, "%[ca]", 0)
+      VQ_B16_ROW("%[r3]", "%[r4]", "%[r5]", "%[ta0]", "%[tb0]", 1, "%[cb]", 0)
+      VQ_B16_ROW("%[r6]", "%[r7]", "%[r8]", "%[ta0]", "%[tb0]", 2, "%[ca]", 1)
+      VQ_B16_ROW("%[r9]", "%[r10]", "%[r11]", "%[ta0]", "%[tb0]", 3, "%[cb]", 1)
+      "s_waitcnt lgkmcnt(9)\n"
+      VQ_B16_USE("%[a0]", "%[r0]", "%[r1]", "%[r2]")
+      VQ_B16_ROW("%[r0]", "%[r1]", "%[r2]", "%[ta1]", "%[tb1]", 0, "%[ca]", 2)
+      "s_waitcnt lgkmcnt(9)\n"
+      VQ_B16_USE("%[a1]", "%[r3]", "%[r4]", "%[r5]")
+      VQ_B16_ROW("%[r3]", "%[r4]", "%[r5]", "%[ta1]", "%[tb1]", 1, "%[cb]", 2)
+      "s_waitcnt lgkmcnt(9)\n"
+      VQ_B16_USE("%[a2]", "%[r6]", "%[r7]", "%[r8]")
+      VQ_B16_ROW("%[r6]", "%[r7]", "%[r8]", "%[ta1]", "%[tb1]", 2, "%[ca]", 3)
+      "s_waitcnt lgkmcnt(9)\n"
+      VQ_B16_USE("%[a3]", "%[r9]", "%[r10]", "%[r11]")
+      VQ_B16_ROW("%[r9]", "%[r10]", "%[r11]", "%[ta1]", "%[tb1]", 3, "%[cb]", 3)
+      "s_waitcnt lgkmcnt(9)\n"
+      VQ_B16_USE("%[a4]", "%[r0]", "%[r1]", "%[r2]")
+      "s_waitcnt lgkmcnt(6)\n"
+      VQ_B16_USE("%[a5]", "%[r3]", "%[r4]", "%[r5]")
+      "s_waitcnt lgkmcnt(3)\n"
+      VQ_B16_USE("%[a6]", "%[r6]", "%[r7]", "%[r8]")
+      "s_waitcnt lgkmcnt(0)\n"
+      VQ_B16_USE("%[a7]", "%[r9]", "%[r10]", "%[r11]")
+      : [a0] "+v"(acc[0]), [a1] "+v"(acc[1]), [a2] "+v"(acc[2]), [a3] "+v"(acc[3]),
+        [a4] "+v"(acc[4]), [a5] "+v"(acc[5]), [a6] "+v"(acc[6]), [a7] "+v"(acc[7]),
+        [r0] "=&v"(r0), [r1] "=&v"(r1), [r2] "=&v"(r2), [r3] "=&v"(r3), [r4] "=&v"(r4),
+        [r5] "=&v"(r5), [r6] "=&v"(r6), [r7] "=&v"(r7), [r8] "=&v"(r8), [r9] "=&v"(r9),
+        [r10] "=&v"(r10), [r11] "=&v"(r11)
+      : [ta0] "v"(ta0), [tb0] "v"(tb0), [ta1] "v"(ta1), [tb1] "v"(tb1), [ca] "v"(ca), [cb] "v"(cb),
+        [base] "s"(base), [x0] "v"(x0), [x1] "v"(x1), [off] "n"(OFF), [loff] "n"(LOFF)
+      : "memory");
+}
+#undef VQ_B16_RD
+#undef VQ_B16_ROW
+#undef VQ_B16_USE
 
 // ---------------------------------------------------------------------------
 // d = 1, k = 16 (scalar codebooks): a byte of the index stream holds the 4-bit indices of two
@@ -438,10 +510,6 @@ __device__ __forceinline__ uint32_t k16_encode_dword(const uint32_t lo[4], const
     w |= (hi[b] >> 2) << (8 * ((b + 1) & 3));
   }
   return w;
-}
-__device__ __forceinline__ void k16_split_dword(uint32_t w, uint32_t& a, uint32_t& b) {
-  a = w & 0x3c3c3c3cu;
-  b = __builtin_amdgcn_alignbit(w, w, 4) & 0x3c3c3c3cu;
 }
 
 // ---- k = 16 with int8 tables and blockwise normalisation: device layout of the table buffer ----

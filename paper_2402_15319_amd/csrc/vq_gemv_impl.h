@@ -492,12 +492,22 @@ template <int MODE> struct ChunkS16T {
     wave_lds_sync();
     const uint2* xp = reinterpret_cast<const uint2*>(x_s) + u0 * 128 + lane;   // 64 uint2 per col-block
     if constexpr (BN) {       // absent pairs: zero tables and levels against the zeroed col-blocks behind x
-#pragma unroll
-      for (int s = 0; s < 4; ++s) {
-        const uint2 xa = xp[128 * s], xb = xp[128 * s + 64];
-        k16_group_scaled(w[s].x, w[s].y, cw[s].x, lut + 32 * s, lut + 128 + 32 * s, xa.x, xa.y, acc);
-        k16_group_scaled(w[s].z, w[s].w, cw[s].y, lut + 32 * s + 16, lut + 128 + 32 * s + 16, xb.x, xb.y, acc);
-      }
+      uint2 x0 = xp[0], x1 = xp[64];
+      k16_group_bn<0, 512>(w[0].x, w[0].y, cw[0].x, base, x0.x, x0.y, acc);
+      x0 = xp[128];
+      k16_group_bn<64, 576>(w[0].z, w[0].w, cw[0].y, base, x1.x, x1.y, acc);
+      x1 = xp[192];
+      k16_group_bn<128, 640>(w[1].x, w[1].y, cw[1].x, base, x0.x, x0.y, acc);
+      x0 = xp[256];
+      k16_group_bn<192, 704>(w[1].z, w[1].w, cw[1].y, base, x1.x, x1.y, acc);
+      x1 = xp[320];
+      k16_group_bn<256, 768>(w[2].x, w[2].y, cw[2].x, base, x0.x, x0.y, acc);
+      x0 = xp[384];
+      k16_group_bn<320, 832>(w[2].z, w[2].w, cw[2].y, base, x1.x, x1.y, acc);
+      x1 = xp[448];
+      k16_group_bn<384, 896>(w[3].x, w[3].y, cw[3].x, base, x0.x, x0.y, acc);
+      k16_group_bn<448, 960>(w[3].z, w[3].w, cw[3].y, base, x1.x, x1.y, acc);
+      acc_hazard_fence();
       return;
     }
     uint2 x0 = xp[0], x1 = xp[64];
