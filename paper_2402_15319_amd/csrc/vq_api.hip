@@ -27,7 +27,8 @@ bool is_pow2(int v) { return v > 0 && (v & (v - 1)) == 0; }
 //   d = 1, k = 4: 2-bit indices, 4 int8 values + scale per row of a 256-column block (groups of
 //   1 x 256: the 1D 2.125 row of that table);
 //   d = 4: k = 256 (one index byte per 4 weights), int8 tables with a scale, groups of 64, 128 or
-//   256 rows x 256 columns (128 and 256: the 4D 2.25 and 2.125 rows of that table).
+//   256 rows x 256 columns (128 and 256: the 4D 2.25 and 2.125 rows of that table); also with fp16
+//   tables (2 KB per group).
 bool is_i8(const vq_desc& d) { return d.codebook_dtype == VQ_I8 || d.codebook_dtype == VQ_I8_BN; }
 bool is_bn(const vq_desc& d) { return d.codebook_dtype == VQ_I8_BN; }
 
@@ -50,8 +51,8 @@ int check_desc(const vq_desc* d) {
     } else if (d->k != 16 || is_i8(*d) || d->group_rows != kGroupRows) {
       return VQ_ERR_UNSUPPORTED;
     }
-  } else if (d->d == 4) {
-    if (d->k != 256 || d->codebook_dtype != VQ_I8) return VQ_ERR_UNSUPPORTED;
+  } else if (d->d == 4) {                     // int8 tables with a scale, or fp16 tables
+    if (d->k != 256 || (d->codebook_dtype != VQ_I8 && d->codebook_dtype != VQ_F16)) return VQ_ERR_UNSUPPORTED;
     if (d->group_rows != 64 && d->group_rows != 128 && d->group_rows != 256) return VQ_ERR_UNSUPPORTED;
   } else if (is_i8(*d)) {
     if (d->k == 64) {
@@ -199,7 +200,8 @@ int gemv_multi_impl(int count, const vq_desc* descs, const void* const* idx_dev,
       down.total_rows = rows;
       if (m > 0 && launch_lora_down(down, (hipStream_t)stream) != hipSuccess) return VQ_ERR_HIP;
     }
-    if (fmt == kFmtD4 || fmt == kFmtK256I8) {   // one workgroup per 64 rows, see vq_gemv_d4.hip
+    const bool d4 = fmt == kFmtD4 || fmt == kFmtD4F16;
+    if (d4 || fmt == kFmtK256I8) {   // one workgroup per 64 rows, see vq_gemv_d4.hip
       GemvBatchLora both;                       // 20 KB on the stack; only the used entries are filled
       GemvBatch& batch = both.base;
       memset(&batch, 0, offsetof(GemvBatch, p) + (size_t)n * sizeof(GemvProblem));
@@ -232,10 +234,10 @@ int gemv_multi_impl(int count, const vq_desc* descs, const void* const* idx_dev,
       if (wgs > 0x7fffffffll) return VQ_ERR_UNSUPPORTED;
       batch.total_wgs = (int32_t)wgs;
       const hipError_t e =
-          lora ? (fmt == kFmtD4 ? launch_gemv_d4_lora(both, (int)wgs, (hipStream_t)stream)
-                                : launch_gemv_k256i8_lora(both, (int)wgs, (hipStream_t)stream))
-               : (fmt == kFmtD4 ? launch_gemv_d4(batch, (int)wgs, (hipStream_t)stream)
-                                : launch_gemv_k256i8(batch, (int)wgs, (hipStream_t)stream));
+          lora ? (d4 ? launch_gemv_d4_lora(both, (int)wgs, (hipStream_t)stream, fmt == kFmtD4F16)
+                     : launch_gemv_k256i8_lora(both, (int)wgs, (hipStream_t)stream))
+               : (d4 ? launch_gemv_d4(batch, (int)wgs, (hipStream_t)stream, fmt == kFmtD4F16)
+                     : launch_gemv_k256i8(batch, (int)wgs, (hipStream_t)stream));
       if (e != hipSuccess) return VQ_ERR_HIP;
       continue;
     }
@@ -372,7 +374,7 @@ int vq_layout_bytes(const vq_desc* desc, size_t* idx_bytes, size_t* cb_bytes) {
   if (desc->d == 4) {    // 1 KB of indices per (8-row block, pair of col-blocks); tables as in the canonical buffer
     const size_t n_groups = (size_t)(desc->out_features / desc->group_rows) * n_cb;
     if (idx_bytes) *idx_bytes = n_rb * ((n_cb + 1) / 2) * 1024;
-    if (cb_bytes) *cb_bytes = n_groups * 1024 + (2 * n_groups + 15) / 16 * 16;
+    if (cb_bytes) *cb_bytes = is_i8(*desc) ? n_groups * 1024 + (2 * n_groups + 15) / 16 * 16 : n_groups * 2048;
     return VQ_OK;
   }
   if (desc->d == 1 && desc->k == 8) {   // indices as for k = 64; 48-byte table records per (group row, quad)

@@ -192,6 +192,7 @@ __global__ __launch_bounds__(256) void decode64_kernel(const uint8_t* __restrict
 // d = 4 (k = 256, int8 tables with a scale): one wave per (8-row block, col-block).  Lane L
 // dequantises table entries 4L .. 4L+3 into the wave's 2 KB table, then copies one 8-byte entry
 // per row (its vector: columns 4L .. 4L+3).
+template <bool F16>    // F16: fp16 tables (2 KB per group) instead of int8 tables with a scale
 __global__ __launch_bounds__(256) void decode_d4_kernel(const uint8_t* __restrict__ idx,
                                                         const uint8_t* __restrict__ tab,
                                                         uint16_t* __restrict__ W, int n_cb,
@@ -206,12 +207,18 @@ __global__ __launch_bounds__(256) void decode_d4_kernel(const uint8_t* __restric
   const int c = (int)(item - rb8 * n_cb);
   const long long n_groups = (n_items / n_cb / rpc) * n_cb;
   const long long g = (rb8 / rpc) * n_cb + c;
-  const uint4 q = *reinterpret_cast<const uint4*>(tab + g * 1024 + lane * 16);
-  const _Float16 scale = __builtin_bit_cast(_Float16, reinterpret_cast<const uint16_t*>(tab + n_groups * 1024)[g]);
-  lut[4 * lane] = d4_dequant_entry(q.x, scale);
-  lut[4 * lane + 1] = d4_dequant_entry(q.y, scale);
-  lut[4 * lane + 2] = d4_dequant_entry(q.z, scale);
-  lut[4 * lane + 3] = d4_dequant_entry(q.w, scale);
+  if constexpr (F16) {
+    const uint4* src = reinterpret_cast<const uint4*>(tab + g * 2048 + lane * 32);
+    *reinterpret_cast<uint4*>(lut + 4 * lane) = src[0];
+    *reinterpret_cast<uint4*>(lut + 4 * lane + 2) = src[1];
+  } else {
+    const uint4 q = *reinterpret_cast<const uint4*>(tab + g * 1024 + lane * 16);
+    const _Float16 scale = __builtin_bit_cast(_Float16, reinterpret_cast<const uint16_t*>(tab + n_groups * 1024)[g]);
+    lut[4 * lane] = d4_dequant_entry(q.x, scale);
+    lut[4 * lane + 1] = d4_dequant_entry(q.y, scale);
+    lut[4 * lane + 2] = d4_dequant_entry(q.z, scale);
+    lut[4 * lane + 3] = d4_dequant_entry(q.w, scale);
+  }
   const int n_pairs = (n_cb + 1) >> 1;
   const uint2 w = *reinterpret_cast<const uint2*>(idx + (size_t)(rb8 * n_pairs + (c >> 1)) * 1024 + lane * 16 + (c & 1) * 8);
   wave_lds_sync();
@@ -231,10 +238,15 @@ hipError_t launch_decode(const vq_desc& d, const void* idx_dev, const void* cb_d
   const long long n_groups = (long long)(d.out_features / kGroupRows) * n_cb;   // 8-row items
   const unsigned grid = (unsigned)((n_groups + 3) / 4);
   const int fmt = format_tag(d);
-  if (fmt == kFmtD4) {
-    hipLaunchKernelGGL(decode_d4_kernel, dim3(grid), dim3(256), 0, s, (const uint8_t*)idx_dev,
-                       (const uint8_t*)cb_dev, (uint16_t*)W, n_cb, n_groups, d.in_features,
-                       d.group_rows / kGroupRows);
+  if (fmt == kFmtD4 || fmt == kFmtD4F16) {
+    if (fmt == kFmtD4)
+      hipLaunchKernelGGL(decode_d4_kernel<false>, dim3(grid), dim3(256), 0, s, (const uint8_t*)idx_dev,
+                         (const uint8_t*)cb_dev, (uint16_t*)W, n_cb, n_groups, d.in_features,
+                         d.group_rows / kGroupRows);
+    else
+      hipLaunchKernelGGL(decode_d4_kernel<true>, dim3(grid), dim3(256), 0, s, (const uint8_t*)idx_dev,
+                         (const uint8_t*)cb_dev, (uint16_t*)W, n_cb, n_groups, d.in_features,
+                         d.group_rows / kGroupRows);
     return hipGetLastError();
   }
   if (fmt == 64 || fmt == kFmtK64BN || fmt == kFmtD1K8) {

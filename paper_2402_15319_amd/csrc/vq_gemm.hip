@@ -42,7 +42,7 @@ __device__ __forceinline__ int wt_half_index(int m, int k) {   // k in halfs
 // scale per group, groups of 8*rpc rows), kFmtK16I8 (k = 16 with int8 tables).
 template <int K> constexpr int lut_dwords() {
   // BN: 64 centroids + 16 levels; d = 4: 256 entries of 4 halfs; scalar 2-bit: 8 rows x 16 pair entries
-  return K == kFmtK16I8 ? 16 : K == kFmtK16BN ? 32 : (K == kFmtD1K16 || K == kFmtK256I8) ? 256 : K == kFmtK64BN ? 80 : K == kFmtD4 ? 512 : K == kFmtD1K8 ? 64 : K == kFmtD1K4 ? 128 : K;
+  return K == kFmtK16I8 ? 16 : K == kFmtK16BN ? 32 : (K == kFmtD1K16 || K == kFmtK256I8) ? 256 : K == kFmtK64BN ? 80 : (K == kFmtD4 || K == kFmtD4F16) ? 512 : K == kFmtD1K8 ? 64 : K == kFmtD1K4 ? 128 : K;
 }
 
 // What one wave needs to decode one group: the lane's index bytes and codebook piece.
@@ -72,6 +72,10 @@ template <> struct GroupRegs<kFmtD4> {
   uint2 w;        // the lane's 8 index bytes (one vector per row)
   uint4 q;        // table entries 4*lane .. 4*lane+3 (int8 x 4 each)
   uint32_t sc;    // the group's fp16 scale
+};
+template <> struct GroupRegs<kFmtD4F16> {
+  uint2 w;
+  uint4 q0, q1;   // table entries 4*lane .. 4*lane+3 (fp16 x 4 each)
 };
 template <> struct GroupRegs<kFmtD1K16> {
   uint4 w;
@@ -125,6 +129,12 @@ __device__ __forceinline__ void load_group(GroupRegs<K>& g, const uint8_t* idx, 
     g.w = *reinterpret_cast<const uint2*>(idx + (size_t)rb * slots * 512 + k16_chunk_offset(c, lane));
     g.q4 = *reinterpret_cast<const uint32_t*>(rec + (lane >> 3) * 4);
     g.sc = *reinterpret_cast<const uint16_t*>(rec + kD1K4ScaleOffset + (lane >> 3) * 2);
+  } else if constexpr (K == kFmtD4F16) {
+    const uint8_t* tab = reinterpret_cast<const uint8_t*>(cb);
+    const size_t gi = (size_t)(rb / rpc) * n_cb + c;
+    g.w = *reinterpret_cast<const uint2*>(idx + ((size_t)rb * ((n_cb + 1) >> 1) + (c >> 1)) * 1024 + lane * 16 + (c & 1) * 8);
+    g.q0 = *reinterpret_cast<const uint4*>(tab + gi * 2048 + lane * 32);
+    g.q1 = *reinterpret_cast<const uint4*>(tab + gi * 2048 + lane * 32 + 16);
   } else if constexpr (K == kFmtD4) {
     const uint8_t* tab = reinterpret_cast<const uint8_t*>(cb);
     const size_t gi = (size_t)(rb / rpc) * n_cb + c, n_groups = (size_t)(n_rb / rpc) * n_cb;
@@ -180,13 +190,18 @@ __device__ __forceinline__ void decode_group(const GroupRegs<K>& g, uint32_t* lu
                                              int m0, int lane) {
   const char* lutb = reinterpret_cast<const char*>(lut);
   uint32_t v[16];
-  if constexpr (K == kFmtD4) {
+  if constexpr (K == kFmtD4 || K == kFmtD4F16) {
     uint2* lut2 = reinterpret_cast<uint2*>(lut);
-    const _Float16 scale = __builtin_bit_cast(_Float16, (uint16_t)g.sc);
-    lut2[4 * lane] = d4_dequant_entry(g.q.x, scale);
-    lut2[4 * lane + 1] = d4_dequant_entry(g.q.y, scale);
-    lut2[4 * lane + 2] = d4_dequant_entry(g.q.z, scale);
-    lut2[4 * lane + 3] = d4_dequant_entry(g.q.w, scale);
+    if constexpr (K == kFmtD4F16) {
+      *reinterpret_cast<uint4*>(lut2 + 4 * lane) = g.q0;
+      *reinterpret_cast<uint4*>(lut2 + 4 * lane + 2) = g.q1;
+    } else {
+      const _Float16 scale = __builtin_bit_cast(_Float16, (uint16_t)g.sc);
+      lut2[4 * lane] = d4_dequant_entry(g.q.x, scale);
+      lut2[4 * lane + 1] = d4_dequant_entry(g.q.y, scale);
+      lut2[4 * lane + 2] = d4_dequant_entry(g.q.z, scale);
+      lut2[4 * lane + 3] = d4_dequant_entry(g.q.w, scale);
+    }
     wave_lds_sync();
 #pragma unroll
     for (int r = 0; r < 8; ++r) {
@@ -888,6 +903,7 @@ hipError_t launch_gemm(const vq_desc& d, const void* idx_dev, const void* cb_dev
   if (fmt == kFmtD1K16) VQ_GEMM_DISPATCH(kFmtD1K16)
   if (fmt == kFmtK64BN) VQ_GEMM_DISPATCH(kFmtK64BN)
   if (fmt == kFmtD4) VQ_GEMM_DISPATCH(kFmtD4)
+  if (fmt == kFmtD4F16) VQ_GEMM_DISPATCH(kFmtD4F16)
   if (fmt == kFmtD1K8) VQ_GEMM_DISPATCH(kFmtD1K8)
   if (fmt == kFmtD1K4) VQ_GEMM_DISPATCH(kFmtD1K4)
   if (fmt == kFmtK256I8) VQ_GEMM_DISPATCH(kFmtK256I8)

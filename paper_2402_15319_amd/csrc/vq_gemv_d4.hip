@@ -29,11 +29,12 @@ __device__ __forceinline__ int find_problem_d4(const GemvBatch& batch, int item)
 struct D4Step {
   uint4 w;        // the lane's 8 + 8 index bytes of the pair
   uint2 xa, xb;   // its activations in the two col-blocks
-  uint32_t q;     // this thread's table entry (4 int8) of col-block (tid >> 8) of the pair
-  uint32_t sc;    // that table's fp16 scale
+  uint2 q;        // this thread's table entry of col-block (tid >> 8) of the pair: 4 int8 in .x, or 4 fp16
+  uint32_t sc;    // int8 tables: that table's fp16 scale
 };
 
-template <bool LORA>
+// F16: the tables are fp16 (2 KB per group, copied to LDS as they are) instead of int8 with a scale.
+template <bool LORA, bool F16>
 __global__ __launch_bounds__(512) void gemv_d4_kernel(const typename BatchOf<LORA>::type arg) {
   const GemvBatch& batch = base_of(arg);
   __shared__ __attribute__((aligned(16))) uint2 tabs[2][2][256];   // [buffer][col-block of the pair][entry]
@@ -48,7 +49,7 @@ __global__ __launch_bounds__(512) void gemv_d4_kernel(const typename BatchOf<LOR
   const long long grow = (long long)(oct * 8) / P.rb_per_cb;
   const uint8_t* tab = reinterpret_cast<const uint8_t*>(P.cb);
   const long long n_groups = (long long)(P.n_rb / P.rb_per_cb) * n_cb;
-  const uint16_t* scales = reinterpret_cast<const uint16_t*>(tab + n_groups * 1024);
+  const uint16_t* scales = reinterpret_cast<const uint16_t*>(tab + n_groups * 1024);   // int8 tables only
   const uint8_t* idx_lane = P.idx + (size_t)rb * n_pairs * 1024 + lane * 16;
   const uint16_t* x_lane = P.x + lane * 4;
   const int h = tid >> 8, e = tid & 255;            // table duty of this thread
@@ -62,8 +63,13 @@ __global__ __launch_bounds__(512) void gemv_d4_kernel(const typename BatchOf<LOR
     s.xa = *reinterpret_cast<const uint2*>(x_lane + (size_t)c0 * 256);
     const uint2 xb = *reinterpret_cast<const uint2*>(x_lane + (size_t)(ok1 ? c1 : c0) * 256);
     s.xb = ok1 ? xb : make_uint2(0u, 0u);
-    s.q = *reinterpret_cast<const uint32_t*>(tab + g * 1024 + e * 4);
-    s.sc = scales[g];
+    if constexpr (F16) {
+      s.q = *reinterpret_cast<const uint2*>(tab + g * 2048 + e * 8);
+      s.sc = 0;
+    } else {
+      s.q = make_uint2(*reinterpret_cast<const uint32_t*>(tab + g * 1024 + e * 4), 0u);
+      s.sc = scales[g];
+    }
   };
 
   float acc[8];
@@ -83,8 +89,8 @@ __global__ __launch_bounds__(512) void gemv_d4_kernel(const typename BatchOf<LOR
     load(p + 1 < n_pairs ? p + 1 : p, nxt);         // one step ahead (a harmless re-read at the end)
     const int buf = p & 1;
     const bool mine = h == 0 || 2 * p + 1 < n_cb;   // the absent col-block of an odd matrix gets a zero table
-    tabs[buf][h][e] = mine ? d4_dequant_entry(cur.q, __builtin_bit_cast(_Float16, (uint16_t)cur.sc))
-                           : make_uint2(0u, 0u);
+    tabs[buf][h][e] = !mine ? make_uint2(0u, 0u)
+                      : F16 ? cur.q : d4_dequant_entry(cur.q.x, __builtin_bit_cast(_Float16, (uint16_t)cur.sc));
     __syncthreads();   // tables of this step complete; the other buffer is free again (see header)
     const uint2* T0 = tabs[buf][0];
     const uint2* T1 = tabs[buf][1];
@@ -201,8 +207,9 @@ hipError_t launch_gemv_k256i8(const GemvBatch& batch, int total_wgs, hipStream_t
   return hipGetLastError();
 }
 
-hipError_t launch_gemv_d4(const GemvBatch& batch, int total_wgs, hipStream_t s) {
-  hipLaunchKernelGGL(gemv_d4_kernel<false>, dim3((unsigned)total_wgs), dim3(512), 0, s, batch);
+hipError_t launch_gemv_d4(const GemvBatch& batch, int total_wgs, hipStream_t s, bool f16_tables) {
+  if (f16_tables) hipLaunchKernelGGL((gemv_d4_kernel<false, true>), dim3((unsigned)total_wgs), dim3(512), 0, s, batch);
+  else hipLaunchKernelGGL((gemv_d4_kernel<false, false>), dim3((unsigned)total_wgs), dim3(512), 0, s, batch);
   return hipGetLastError();
 }
 
@@ -212,8 +219,9 @@ hipError_t launch_gemv_k256i8_lora(const GemvBatchLora& batch, int total_wgs, hi
   return hipGetLastError();
 }
 
-hipError_t launch_gemv_d4_lora(const GemvBatchLora& batch, int total_wgs, hipStream_t s) {
-  hipLaunchKernelGGL(gemv_d4_kernel<true>, dim3((unsigned)total_wgs), dim3(512), 0, s, batch);
+hipError_t launch_gemv_d4_lora(const GemvBatchLora& batch, int total_wgs, hipStream_t s, bool f16_tables) {
+  if (f16_tables) hipLaunchKernelGGL((gemv_d4_kernel<true, true>), dim3((unsigned)total_wgs), dim3(512), 0, s, batch);
+  else hipLaunchKernelGGL((gemv_d4_kernel<true, false>), dim3((unsigned)total_wgs), dim3(512), 0, s, batch);
   return hipGetLastError();
 }
 

@@ -24,9 +24,10 @@ constexpr int kFmtD1K4 = 2004;     // d = 1, k = 4 (2-bit indices), int8 values 
                                    // col-block (groups of 1 x 256): pairs index a 16-entry pair table per row
 constexpr int kFmtD4 = 4256;      // d = 4, k = 256 (one index byte per 4 weights), int8 tables + scale,
                                   // groups of 64, 128 or 256 rows x 256 columns
+constexpr int kFmtD4F16 = 4257;   // the same with fp16 tables (2 KB per group, no scale)
 inline int format_tag(const vq_desc& d) {
   if (d.d == 1) return d.k == 8 ? kFmtD1K8 : d.k == 4 ? kFmtD1K4 : kFmtD1K16;
-  if (d.d == 4) return kFmtD4;
+  if (d.d == 4) return d.codebook_dtype == VQ_F16 ? kFmtD4F16 : kFmtD4;
   if (d.codebook_dtype == VQ_I8_BN) return d.k == 16 ? kFmtK16BN : kFmtK64BN;
   if (d.k == 16 && d.codebook_dtype == VQ_I8) return kFmtK16I8;
   if (d.k == 256 && d.codebook_dtype == VQ_I8) return kFmtK256I8;
@@ -118,9 +119,9 @@ int gemv_stream_resident_wgs(int fmt, int max_n_cb);
 int gemv_chunk_units(int fmt);
 // d = 4, and d = 2 with k = 256 and int8 tables: GEMV kernels of their own (a workgroup of 8 waves
 // owns 64 rows and shares the group's dequantised table; see vq_gemv_d4.hip).
-hipError_t launch_gemv_d4(const GemvBatch& batch, int total_wgs, hipStream_t s);
+hipError_t launch_gemv_d4(const GemvBatch& batch, int total_wgs, hipStream_t s, bool f16_tables = false);
 hipError_t launch_gemv_k256i8(const GemvBatch& batch, int total_wgs, hipStream_t s);
-hipError_t launch_gemv_d4_lora(const GemvBatchLora& batch, int total_wgs, hipStream_t s);
+hipError_t launch_gemv_d4_lora(const GemvBatchLora& batch, int total_wgs, hipStream_t s, bool f16_tables = false);
 hipError_t launch_gemv_k256i8_lora(const GemvBatchLora& batch, int total_wgs, hipStream_t s);
 hipError_t launch_gemm(const vq_desc& d, const void* idx_dev, const void* cb_dev,
                        const void* X, int B, int ldx, void* Y, int ldy, int y_f32,

@@ -332,7 +332,8 @@ hipError_t launch_pack(const vq_desc& d, const void* idx_canon, const void* cb_c
                        (const uint8_t*)idx_canon, (uint8_t*)idx_dev, n_cb, n_rb, rpc);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    const long long src_bytes = n_groups * 1024 + 2 * n_groups;      // tables (a multiple of 16), then scales
+    // int8 tables (a multiple of 16 bytes), then the scales; or fp16 tables alone: copied as they are
+    const long long src_bytes = d.codebook_dtype == VQ_F16 ? n_groups * 2048 : n_groups * 1024 + 2 * n_groups;
     const long long n16 = (src_bytes + 15) / 16;
     hipLaunchKernelGGL(copy16_kernel, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, s,
                        (const uint8_t*)cb_canon, (uint8_t*)cb_dev, n16, src_bytes);

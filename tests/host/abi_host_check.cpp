@@ -59,6 +59,7 @@ std::vector<vq_desc> supported(int out_mult, int n_cb) {
   for (int gr : {8, 16, 32}) v.push_back(make(gr * out_mult, in, gr, 1, 8, 3, VQ_I8));
   v.push_back(make(8 * out_mult, in, 1, 1, 4, 2, VQ_I8));
   for (int gr : {64, 128, 256}) v.push_back(make(gr * out_mult, in, gr, 4, 256, 8, VQ_I8));
+  for (int gr : {64, 128, 256}) v.push_back(make(gr * out_mult, in, gr, 4, 256, 8, VQ_F16));
   return v;
 }
 

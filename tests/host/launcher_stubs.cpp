@@ -134,7 +134,7 @@ hipError_t launch_lora_down(const LoraDownBatch& b, hipStream_t) {
 }
 size_t gemv_stream_lds_bytes(int, int max_n_cb) { return 8 * 2048 + (size_t)(max_n_cb + 8) * 512; }
 int gemv_chunk_units(int fmt) { return chunk_units(fmt); }
-hipError_t launch_gemv_d4(const GemvBatch& b, int total_wgs, hipStream_t) {
+hipError_t launch_gemv_d4(const GemvBatch& b, int total_wgs, hipStream_t, bool) {
   ++g_launches;
   long long wgs = 0;
   for (int i = 0; i < b.count; ++i) {
@@ -146,13 +146,13 @@ hipError_t launch_gemv_d4(const GemvBatch& b, int total_wgs, hipStream_t) {
   REQUIRE(total_wgs == wgs && b.total_wgs == wgs, "total_wgs %d", total_wgs);
   return hipSuccess;
 }
-hipError_t launch_gemv_k256i8(const GemvBatch& b, int total_wgs, hipStream_t s) { return launch_gemv_d4(b, total_wgs, s); }
-hipError_t launch_gemv_d4_lora(const GemvBatchLora& b, int total_wgs, hipStream_t s) {
+hipError_t launch_gemv_k256i8(const GemvBatch& b, int total_wgs, hipStream_t s) { return launch_gemv_d4(b, total_wgs, s, false); }
+hipError_t launch_gemv_d4_lora(const GemvBatchLora& b, int total_wgs, hipStream_t s, bool f16_tables) {
   check_adapters(b);
-  return launch_gemv_d4(b.base, total_wgs, s);
+  return launch_gemv_d4(b.base, total_wgs, s, f16_tables);
 }
 hipError_t launch_gemv_k256i8_lora(const GemvBatchLora& b, int total_wgs, hipStream_t s) {
-  return launch_gemv_d4_lora(b, total_wgs, s);
+  return launch_gemv_d4_lora(b, total_wgs, s, false);
 }
 hipError_t launch_gemm(const vq_desc& d, const void* a, const void* b, const void* X, int B, int ldx, void* Y, int ldy,
                        int y_f32, hipStream_t) {

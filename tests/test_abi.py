@@ -80,7 +80,8 @@ A = 0x1000  # a fake, 16-byte aligned, non-NULL address; validation fails before
     (dict(index_bits=0), -2),
     (dict(d=4), -3),                                                      # d = 4 needs k = 256, int8 tables
     (dict(d=4, k=256, index_bits=8, codebook_dtype=3), -3),               # ... and groups of 64, 128 or 256 rows
-    (dict(d=4, k=256, index_bits=8, group_rows=256), -3),                 # fp16 tables: not implemented
+    (dict(d=4, k=256, index_bits=8, group_rows=32), -3),                  # fp16 tables: the same group heights
+    (dict(d=4, k=256, index_bits=8, group_rows=256, codebook_dtype=4), -3),   # no blockwise normalisation for d = 4
     (dict(d=1, k=256, index_bits=8), -3),                                 # scalar codebooks: k = 16 only
     (dict(d=1, codebook_dtype=3), -3),                                    # ... with fp16 values
     (dict(d=1, k=8, index_bits=3), -3),                                   # 3-bit scalar codebooks: int8 values
@@ -94,7 +95,7 @@ A = 0x1000  # a fake, 16-byte aligned, non-NULL address; validation fails before
     (dict(k=64, index_bits=6), -3),                                       # k = 64 needs int8 tables
     (dict(k=256, index_bits=8, codebook_dtype=3), -3),                    # k = 256 with int8 tables: groups of 64, 128 or 256 rows
     (dict(k=256, index_bits=8, codebook_dtype=3, group_rows=32), -3),
-    (dict(k=256, index_bits=8, codebook_dtype=4, group_rows=128), -3),    # blockwise normalisation: k = 64 only
+    (dict(k=256, index_bits=8, codebook_dtype=4, group_rows=128), -3),    # blockwise normalisation: k = 64 and k = 16 only
     (dict(codebook_dtype=3, group_rows=32), -3),                          # k = 16 int8: 8-row groups
     (dict(k=64, index_bits=6, codebook_dtype=3, group_rows=24), -3),
     (dict(k=64, index_bits=6, codebook_dtype=3, group_rows=32, out_features=4112), -3),
@@ -278,6 +279,13 @@ def test_four_dimensional_representation_sizes_and_entry_points():
         assert L.vq_gemv(r, A, A, A + 2, A + 16, vq.VQ_F16, 0) == -4
         assert L.vq_gemm_batched(r, A, A, A, 16, 20, A + 16, 16, vq.VQ_F16, 0) == -4
         assert L.vq_decode_dense(r, A, A, A + 2, 0) == -4
+        # the same with fp16 tables: 2 KB per group and no scale; 256 x 256 groups: 2 + 256*4*16/65536 = 2.25 bpv
+        f = vq.make_desc(out_f, in_f, 256, 8, group_rows=rows, d=4)
+        assert vq.vq_canonical_bytes(f) == (out_f * in_f // 4, n_groups * 2048)
+        assert vq.vq_layout_bytes(f) == ((out_f // 8) * pairs * 1024, n_groups * 2048)
+        if rows == 256:
+            assert sum(vq.vq_canonical_bytes(f)) * 8 / (out_f * in_f) == 2.25
+        assert L.vq_gemv(ctypes.byref(f), A, A, A + 2, A + 16, vq.VQ_F16, 0) == -4
 
 
 def test_three_bit_scalar_representation_sizes():

@@ -954,6 +954,45 @@ D4_SMALL = [_shape_d4(64, 256, 64), _shape_d4(128, 768, 64), _shape_d4(128, 512,
             _shape_d4(512, 2816), _shape_d4(384, 1024, 128)]
 
 
+def _shape_d4f(o, i, rows=256):
+    return workloads.VQShape(o, i, 256, 8, rows, 256, 4)
+
+
+D4F_SMALL = [_shape_d4f(64, 256, 64), _shape_d4f(128, 768, 64), _shape_d4f(128, 512, 128), _shape_d4f(256, 1280),
+             _shape_d4f(512, 2816), _shape_d4f(384, 1024, 128)]
+
+
+@pytest.mark.parametrize("s", D4F_SMALL, ids=str)
+def test_d4_fp16_tables_every_entry_point(env, s):
+    """d = 4 with fp16 tables (2 KB per group, no scale): decode bit-exact, GEMV with both output
+    types, the batched product at three batch sizes."""
+    desc, idx, cb, idx_d, cb_d = _setup(env, s, 930)
+    f = _fmt(s)
+    np.testing.assert_array_equal(_gpu_decode(env, desc, idx_d, cb_d), oracle.decode_dense(f, idx, cb))
+    x = workloads.make_x(s.in_features, 930)
+    ref = oracle.gemv(f, idx, cb, x)
+    assert oracle.normwise_rel_err(_gpu_gemv(env, desc, idx_d, cb_d, x, False), ref) <= TOL_F16
+    assert oracle.normwise_rel_err(_gpu_gemv(env, desc, idx_d, cb_d, x, True), ref) <= TOL_F32
+    for B in (3, 40, 300):
+        X = workloads.make_X(s.in_features, B, 931)
+        Y = _gpu_gemm(env, desc, idx_d, cb_d, X, True, pad=8 if B == 40 else 0)
+        assert oracle.normwise_rel_err(Y, oracle.gemm(f, idx, cb, X)) <= TOL_F32
+
+
+@pytest.mark.timeout(600)
+def test_d4_fp16_tables_full_size(env):
+    """4096 x 11008 with 256 x 256 groups (2.25 bits per value): decode in full, GEMV element by
+    element with both output types."""
+    s = _shape_d4f(4096, 11008)
+    desc, idx, cb, idx_d, cb_d = _setup(env, s, 932)
+    f = _fmt(s)
+    np.testing.assert_array_equal(_gpu_decode(env, desc, idx_d, cb_d), oracle.decode_dense(f, idx, cb))
+    x = workloads.make_x(s.in_features, 932)
+    ref = oracle.gemv(f, idx, cb, x)
+    _assert_rows_match(_gpu_gemv(env, desc, idx_d, cb_d, x, False), ref, False, "d4 fp16 tables y16")
+    _assert_rows_match(_gpu_gemv(env, desc, idx_d, cb_d, x, True), ref, True, "d4 fp16 tables y32")
+
+
 @pytest.mark.parametrize("s", D4_SMALL, ids=str)
 def test_d4_decode_bit_exact(env, s):
     desc, idx, cb, idx_d, cb_d = _setup_i8(env, s, 720)
