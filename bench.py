@@ -619,7 +619,7 @@ def main():
                      "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": pass_bytes / n_launch / launch_us / 1e3 / HBM_PEAK_GBS,
                      "traffic": traffic,
-                     "kernel": "gemv_stream_kernel<16>",
+                     "kernel": "gemv_stream_kernel<16, false>",
                      # HIP events around the K timed launches on the launch stream, per launch
                      "event_avg_us_per_launch": launch_us, "bytes_per_launch": pass_bytes / n_launch,
                      "measured_stream_read_GB/s": stream_read_gbs,
