@@ -289,6 +289,9 @@ def main():
                 # scalar codebooks at 3 bits: 8 int8 values + scale per 32 x 256 group (3.01 bpv)
                 ("llama7b_pass_d1_k8_int8_3.01bpv_via_vq_gemv_multi", workloads.LLAMA7B_LAYER_D1_K8,
                  "gemv_stream_kernel<d1,k8>"),
+                # the same with blockwise normalisation on top: 3.17 bits per value
+                ("llama7b_pass_d1_k8_int8_block_norm_3.17bpv_via_vq_gemv_multi", workloads.LLAMA7B_LAYER_D1_K8_BN,
+                 "gemv_stream_kernel<d1,k8,bn>"),
                 # scalar codebooks at 2 bits: 4 int8 values + scale per row of a col-block (2.19 bpv)
                 ("llama7b_pass_d1_k4_int8_2.19bpv_via_vq_gemv_multi", workloads.LLAMA7B_LAYER_D1_K4,
                  "gemv_stream_kernel<d1,k4>"),
@@ -310,6 +313,12 @@ def main():
                         n_groups = (s.out_features // s.group_rows) * (s.in_features // 256)
                         tab[n_groups * 512:] = 0
                         tab[n_groups * 512 + 1:n_groups * 514:2] = 0x1C
+                    elif s.d == 1 and s.k == 8 and s.block_norm:   # 176-byte records: the same + 64 levels (1.0); then codes
+                        n_rec = (s.out_features // s.group_rows) * ((s.in_features // 256 + 3) // 4)
+                        tv = tab[:n_rec * 176].view(-1, 176)
+                        tv[:, 32:176] = 0
+                        tv[:, 33:40:2] = 0x1C
+                        tv[:, 49:176:2] = 0x3C
                     elif s.d == 1 and s.k == 8:         # 48-byte records: 4 x 8 int8, 4 scales (2^-8), padding
                         tv = tab.view(-1, 48)
                         tv[:, 32:48] = 0

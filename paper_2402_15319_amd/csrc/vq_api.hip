@@ -42,8 +42,8 @@ int check_desc(const vq_desc* d) {
   if (d->codebook_dtype != VQ_F16 && !is_i8(*d)) return VQ_ERR_UNSUPPORTED;
   if ((d->d != 2 && d->d != 1 && d->d != 4) || d->group_cols != kGroupCols) return VQ_ERR_UNSUPPORTED;
   if (d->d == 1) {
-    if (d->k == 8) {          // 3-bit indices, int8 values + scale, group heights of the k = 64 format
-      if (d->codebook_dtype != VQ_I8) return VQ_ERR_UNSUPPORTED;
+    if (d->k == 8) {          // 3-bit indices, int8 values + scale (also block-normalised), group heights of the k = 64 format
+      if (!is_i8(*d)) return VQ_ERR_UNSUPPORTED;
       if (d->group_rows != 8 && d->group_rows != 16 && d->group_rows != 32) return VQ_ERR_UNSUPPORTED;
     } else if (d->k == 4) {   // 2-bit indices, int8 values + scale, one codebook per row of a col-block
       if (d->codebook_dtype != VQ_I8 || d->group_rows != 1) return VQ_ERR_UNSUPPORTED;
@@ -93,7 +93,7 @@ void sizes(const vq_desc& d, size_t* idx_bytes, size_t* cb_bytes) {
 
 // Units a row-block of `n_cb` col-blocks is cut into (what the strips of the GEMV kernels count).
 int strip_units(int fmt, int n_cb) {
-  return (fmt == 16 || fmt == kFmtK16I8 || fmt == kFmtK16BN || fmt == kFmtD1K4) ? (n_cb + 1) / 2 : (fmt == 64 || fmt == kFmtK64BN || fmt == kFmtD1K8) ? (n_cb + 3) / 4 : n_cb;
+  return (fmt == 16 || fmt == kFmtK16I8 || fmt == kFmtK16BN || fmt == kFmtD1K4) ? (n_cb + 1) / 2 : (fmt == 64 || fmt == kFmtK64BN || fmt == kFmtD1K8 || fmt == kFmtD1K8BN) ? (n_cb + 3) / 4 : n_cb;
 }
 
 int hip_status(hipError_t e) { return e == hipSuccess ? VQ_OK : VQ_ERR_HIP; }
@@ -380,7 +380,9 @@ int vq_layout_bytes(const vq_desc* desc, size_t* idx_bytes, size_t* cb_bytes) {
   if (desc->d == 1 && desc->k == 8) {   // indices as for k = 64; 48-byte table records per (group row, quad)
     const size_t n_quads = (n_cb + 3) / 4;
     if (idx_bytes) *idx_bytes = n_rb * n_quads * 3072;
-    if (cb_bytes) *cb_bytes = (size_t)(desc->out_features / desc->group_rows) * n_quads * 48;
+    if (cb_bytes)   // with blockwise normalisation: 176-byte records, then 128 bytes of codes per (8-row block, quad)
+      *cb_bytes = is_bn(*desc) ? (size_t)(desc->out_features / desc->group_rows) * n_quads * 176 + n_rb * n_quads * 128
+                               : (size_t)(desc->out_features / desc->group_rows) * n_quads * 48;
     return VQ_OK;
   }
   if (desc->d == 2 && desc->k == 256 && is_i8(*desc)) {   // 1 KB of indices per (8-row block, col-block); tables as canonical

@@ -125,14 +125,15 @@ __global__ __launch_bounds__(256) void decode_kernel(const uint8_t* __restrict__
 // Lane L dequantises table entry L (fp16(scale * q), one rounding) and then copies.  BN: every
 // copied pair is first multiplied by the scale of its 32-weight block (one more fp16 rounding).
 // MODE 0: k = 64; 1: with blockwise normalisation (BN); 2: d = 1, k = 8 (entry L of the pair table is
-// built from the group's 8 int8 values).
+// built from the group's 8 int8 values); 3: d = 1, k = 8 with blockwise normalisation.
 template <int MODE>
 __global__ __launch_bounds__(256) void decode64_kernel(const uint8_t* __restrict__ idx,
                                                        const uint8_t* __restrict__ tab,
                                                        uint16_t* __restrict__ W, int n_cb,
                                                        long long n_items, int in_features, int rpc) {
-  constexpr bool BN = MODE == 1, D1 = MODE == 2;
-  constexpr int tab_bytes = BN ? kK64NQuadTabBytes : D1 ? kD1K8QuadTabBytes : kK64QuadTabBytes;
+  constexpr bool BN = MODE == 1 || MODE == 3, D1 = MODE >= 2;
+  constexpr int tab_bytes = D1 ? (BN ? kD1K8NQuadTabBytes : kD1K8QuadTabBytes) : BN ? kK64NQuadTabBytes : kK64QuadTabBytes;
+  constexpr int level_offset = D1 ? kD1K8NLevelOffset : kK64NLevelOffset;
   __shared__ uint32_t lut_all[4][BN ? 80 : 64];
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
@@ -146,8 +147,8 @@ __global__ __launch_bounds__(256) void decode64_kernel(const uint8_t* __restrict
   uint32_t cw = 0;
   if (BN) {
     const long long n_rb8 = n_items / n_cb;
-    if (lane < 16) lut[64 + lane] = *reinterpret_cast<const uint16_t*>(tq + kK64NLevelOffset + j * 32 + lane * 2) * 0x10001u;
-    cw = *reinterpret_cast<const uint32_t*>(tab + (size_t)(n_rb8 / rpc) * n_quads * kK64NQuadTabBytes +
+    if (lane < 16) lut[64 + lane] = *reinterpret_cast<const uint16_t*>(tq + level_offset + j * 32 + lane * 2) * 0x10001u;
+    cw = *reinterpret_cast<const uint32_t*>(tab + (size_t)(n_rb8 / rpc) * n_quads * tab_bytes +
                                             (size_t)(rb8 * n_quads + q) * kK64NQuadCodeBytes + (lane >> 3) * 16 + j * 4);
   }
   const uint32_t two = D1 ? d1k8_pair(*reinterpret_cast<const uint2*>(tq + j * 8), lane)
@@ -249,13 +250,14 @@ hipError_t launch_decode(const vq_desc& d, const void* idx_dev, const void* cb_d
                          d.group_rows / kGroupRows);
     return hipGetLastError();
   }
-  if (fmt == 64 || fmt == kFmtK64BN || fmt == kFmtD1K8) {
+  if (fmt == 64 || fmt == kFmtK64BN || fmt == kFmtD1K8 || fmt == kFmtD1K8BN) {
 #define VQ_DECODE64(MODE)                                                                            \
     hipLaunchKernelGGL(decode64_kernel<MODE>, dim3(grid), dim3(256), 0, s, (const uint8_t*)idx_dev, \
                        (const uint8_t*)cb_dev, (uint16_t*)W, n_cb, n_groups, d.in_features,         \
                        d.group_rows / kGroupRows)
     if (fmt == 64) VQ_DECODE64(0);
     else if (fmt == kFmtK64BN) VQ_DECODE64(1);
+    else if (fmt == kFmtD1K8BN) VQ_DECODE64(3);
     else VQ_DECODE64(2);
 #undef VQ_DECODE64
     return hipGetLastError();

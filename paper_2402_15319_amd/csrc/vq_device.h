@@ -408,6 +408,10 @@ constexpr int kK64QuadTabBytes = 528;
 // is 48 bytes: four tables of 8 int8 values, four fp16 scales, 8 bytes of padding.
 constexpr int kD1K8QuadTabBytes = 48;
 constexpr int kD1K8ScaleOffset = 32;
+// ... with blockwise normalisation: the 48-byte record, then the four col-blocks' 16 fp16 levels;
+// the block codes behind all records exactly as for k = 64.
+constexpr int kD1K8NQuadTabBytes = 176;
+constexpr int kD1K8NLevelOffset = 48;
 constexpr int kK64NQuadTabBytes = 672;
 constexpr int kK64NLevelOffset = 528;
 constexpr int kK64NQuadCodeBytes = 128;

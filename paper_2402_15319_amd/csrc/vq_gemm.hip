@@ -42,7 +42,7 @@ __device__ __forceinline__ int wt_half_index(int m, int k) {   // k in halfs
 // scale per group, groups of 8*rpc rows), kFmtK16I8 (k = 16 with int8 tables).
 template <int K> constexpr int lut_dwords() {
   // BN: 64 centroids + 16 levels; d = 4: 256 entries of 4 halfs; scalar 2-bit: 8 rows x 16 pair entries
-  return K == kFmtK16I8 ? 16 : K == kFmtK16BN ? 32 : (K == kFmtD1K16 || K == kFmtK256I8) ? 256 : K == kFmtK64BN ? 80 : (K == kFmtD4 || K == kFmtD4F16) ? 512 : K == kFmtD1K8 ? 64 : K == kFmtD1K4 ? 128 : K;
+  return K == kFmtK16I8 ? 16 : K == kFmtK16BN ? 32 : (K == kFmtD1K16 || K == kFmtK256I8) ? 256 : (K == kFmtK64BN || K == kFmtD1K8BN) ? 80 : (K == kFmtD4 || K == kFmtD4F16) ? 512 : K == kFmtD1K8 ? 64 : K == kFmtD1K4 ? 128 : K;
 }
 
 // What one wave needs to decode one group: the lane's index bytes and codebook piece.
@@ -67,6 +67,9 @@ template <> struct GroupRegs<kFmtK64BN> {
   uint32_t d0, d1, d2, two, sc;   // as for k = 64
   uint32_t cw;           // the lane's block codes of this col-block, row r in bits [4r, 4r+4)
   uint32_t lev;          // block-scale level lane & 15 (fp16)
+};
+template <> struct GroupRegs<kFmtD1K8BN> {
+  uint32_t d0, d1, d2, two, sc, cw, lev;   // as for d = 1, k = 8, plus the block scales
 };
 template <> struct GroupRegs<kFmtD4> {
   uint2 w;        // the lane's 8 index bytes (one vector per row)
@@ -153,8 +156,10 @@ __device__ __forceinline__ void load_group(GroupRegs<K>& g, const uint8_t* idx, 
     g.w = *reinterpret_cast<const uint4*>(idx + gi * 1024 + lane * 16);
     g.clo = *reinterpret_cast<const uint2*>(cg + (lane & 3) * 8);
     g.chi = *reinterpret_cast<const uint16_t*>(cg + (lane >> 2) * 2);
-  } else if constexpr (K == 64 || K == kFmtK64BN || K == kFmtD1K8) {
-    constexpr int tab_bytes = K == 64 ? kK64QuadTabBytes : K == kFmtD1K8 ? kD1K8QuadTabBytes : kK64NQuadTabBytes;
+  } else if constexpr (K == 64 || K == kFmtK64BN || K == kFmtD1K8 || K == kFmtD1K8BN) {
+    constexpr int tab_bytes = K == 64 ? kK64QuadTabBytes : K == kFmtD1K8 ? kD1K8QuadTabBytes
+                              : K == kFmtD1K8BN ? kD1K8NQuadTabBytes : kK64NQuadTabBytes;
+    constexpr int level_offset = K == kFmtD1K8BN ? kD1K8NLevelOffset : kK64NLevelOffset;
     const int n_quads = k64_quads(n_cb), q = c >> 2, j = c & 3;
     const uint8_t* iq = idx + ((size_t)rb * n_quads + q) * kK64QuadIdxBytes + lane * 16;
     const int w0 = 3 * j, w1 = 3 * j + 1, w2 = 3 * j + 2;     // the lane's dwords of col-block j
@@ -163,15 +168,15 @@ __device__ __forceinline__ void load_group(GroupRegs<K>& g, const uint8_t* idx, 
     g.d2 = *reinterpret_cast<const uint32_t*>(iq + (w2 >> 2) * 1024 + (w2 & 3) * 4);
     const uint8_t* tq = reinterpret_cast<const uint8_t*>(cb) +
                         ((size_t)(rb / rpc) * n_quads + q) * tab_bytes;
-    if constexpr (K == kFmtD1K8) {
+    if constexpr (K == kFmtD1K8 || K == kFmtD1K8BN) {
       g.two = d1k8_pair(*reinterpret_cast<const uint2*>(tq + j * 8), lane);
       g.sc = *reinterpret_cast<const uint16_t*>(tq + kD1K8ScaleOffset + 2 * j);
     } else {
       g.two = *reinterpret_cast<const uint16_t*>(tq + j * 128 + lane * 2);
       g.sc = *reinterpret_cast<const uint16_t*>(tq + 512 + 2 * j);
     }
-    if constexpr (K == kFmtK64BN) {
-      g.lev = *reinterpret_cast<const uint16_t*>(tq + kK64NLevelOffset + j * 32 + (lane & 15) * 2);
+    if constexpr (K == kFmtK64BN || K == kFmtD1K8BN) {
+      g.lev = *reinterpret_cast<const uint16_t*>(tq + level_offset + j * 32 + (lane & 15) * 2);
       g.cw = *reinterpret_cast<const uint32_t*>(reinterpret_cast<const uint8_t*>(cb) +
                                                 (size_t)(n_rb / rpc) * n_quads * tab_bytes +
                                                 ((size_t)rb * n_quads + q) * kK64NQuadCodeBytes +
@@ -209,9 +214,9 @@ __device__ __forceinline__ void decode_group(const GroupRegs<K>& g, uint32_t* lu
       v[2 * r] = t.x;
       v[2 * r + 1] = t.y;
     }
-  } else if constexpr (K == 64 || K == kFmtK64BN || K == kFmtD1K8) {
+  } else if constexpr (K == 64 || K == kFmtK64BN || K == kFmtD1K8 || K == kFmtD1K8BN) {
     lut[lane] = k64_dequant_pair(g.two, __builtin_bit_cast(_Float16, (uint16_t)g.sc));
-    if constexpr (K == kFmtK64BN) {
+    if constexpr (K == kFmtK64BN || K == kFmtD1K8BN) {
       if (lane < 16) lut[64 + lane] = g.lev * 0x10001u;
     }
     wave_lds_sync();
@@ -223,7 +228,7 @@ __device__ __forceinline__ void decode_group(const GroupRegs<K>& g, uint32_t* lu
       if (pos < 64 && pos > 58) t |= (unsigned long long)g.d2 << (64 - pos);
       v[i] = lut[(uint32_t)t & 63u];
     }
-    if constexpr (K == kFmtK64BN) {     // times the block scale of the lane's 32-weight block, per row
+    if constexpr (K == kFmtK64BN || K == kFmtD1K8BN) {     // times the block scale of the lane's 32-weight block, per row
 #pragma unroll
       for (int r = 0; r < 8; ++r) {
         const h2_t sc = __builtin_bit_cast(h2_t, lut[64 + ((g.cw >> (4 * r)) & 15u)]);
@@ -824,7 +829,7 @@ hipError_t launch_wide(const vq_desc& d, const void* idx_dev, const void* cb_dev
   // the 512-column tile needs 128 accumulator registers per wave: most formats fit the 256
   // registers or spill up to four of them; the block-normalised ones would spill seven to ten and
   // keep 256 columns
-  if constexpr (K == kFmtK64BN || K == kFmtK16BN) {
+  if constexpr (K == kFmtK64BN || K == kFmtK16BN || K == kFmtD1K8BN) {
     return launch_one<K, 2, 256, 2>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);
   } else {
   const int n_rb = d.out_features / kGroupRows;
@@ -905,6 +910,7 @@ hipError_t launch_gemm(const vq_desc& d, const void* idx_dev, const void* cb_dev
   if (fmt == kFmtD4) VQ_GEMM_DISPATCH(kFmtD4)
   if (fmt == kFmtD4F16) VQ_GEMM_DISPATCH(kFmtD4F16)
   if (fmt == kFmtD1K8) VQ_GEMM_DISPATCH(kFmtD1K8)
+  if (fmt == kFmtD1K8BN) VQ_GEMM_DISPATCH(kFmtD1K8BN)
   if (fmt == kFmtD1K4) VQ_GEMM_DISPATCH(kFmtD1K4)
   if (fmt == kFmtK256I8) VQ_GEMM_DISPATCH(kFmtK256I8)
   if (fmt == 16) VQ_GEMM_DISPATCH(16)

@@ -230,13 +230,15 @@ template <> struct Chunk<kFmtD1K16> : Chunk256T<true> {};
 
 // k = 64 with int8 tables.  BN: blockwise normalisation on top (16 block-scale levels per
 // group, a 4-bit code per 32 weights); the plain C++ inner block replaces the hand-scheduled one.
-// MODE 2: d = 1, k = 8: the 64-entry pair table is built from the group's 8 int8 values.
+// MODE 2: d = 1, k = 8: the 64-entry pair table is built from the group's 8 int8 values; MODE 3:
+// the same with blockwise normalisation.
 template <int MODE> struct Chunk64T {
-  static constexpr bool BN = MODE == 1, D1 = MODE == 2;
+  static constexpr bool BN = MODE == 1 || MODE == 3, D1 = MODE >= 2;
   static constexpr int kUnits = 1;        // quads of 4 col-blocks per chunk
   static constexpr int kLutDwords = BN ? 320 : 256;  // 4 groups x 64 centroids (+ 4 x 16 levels)
-  static constexpr int kTabBytes = BN ? kK64NQuadTabBytes : D1 ? kD1K8QuadTabBytes : kK64QuadTabBytes;
+  static constexpr int kTabBytes = D1 ? (BN ? kD1K8NQuadTabBytes : kD1K8QuadTabBytes) : BN ? kK64NQuadTabBytes : kK64QuadTabBytes;
   static constexpr int kScaleOffset = D1 ? kD1K8ScaleOffset : 512;
+  static constexpr int kLevelOffset = D1 ? kD1K8NLevelOffset : kK64NLevelOffset;
   uint4 w[3];     // the lane's three index planes of the quad
   uint2 xv[4];    // activations of the quad's four col-blocks
   uint2 tab;      // 4 int8 centroid pairs: entries 4*(lane%16).. of table lane/16
@@ -251,7 +253,7 @@ template <int MODE> struct Chunk64T {
     tab = zero_unless(ok, *reinterpret_cast<const uint2*>(tq + (D1 ? (lane >> 4) * 8 : lane * 8)));
     sc = *reinterpret_cast<const uint16_t*>(tq + kScaleOffset + (lane >> 4) * 2);
     if constexpr (BN) {
-      lev = zero_unless(ok, (uint32_t)*reinterpret_cast<const uint16_t*>(tq + kK64NLevelOffset + lane * 2));
+      lev = zero_unless(ok, (uint32_t)*reinterpret_cast<const uint16_t*>(tq + kLevelOffset + lane * 2));
       cw = *reinterpret_cast<const uint4*>(S.codes_rb + (size_t)q * kK64NQuadCodeBytes + (lane >> 3) * 16);
     }
 #pragma unroll
@@ -302,6 +304,7 @@ template <int MODE> struct Chunk64T {
 template <> struct Chunk<64> : Chunk64T<0> {};
 template <> struct Chunk<kFmtK64BN> : Chunk64T<1> {};
 template <> struct Chunk<kFmtD1K8> : Chunk64T<2> {};
+template <> struct Chunk<kFmtD1K8BN> : Chunk64T<3> {};
 
 // Strip (row-block rb, K-split `split` of `splits`) of problem P; may be empty.
 template <int K>
@@ -339,12 +342,13 @@ __device__ __forceinline__ Strip make_strip(const GemvProblem& P, int rb, int sp
     S.u = (n_pairs * split) / splits;
     S.u_end = (n_pairs * (split + 1)) / splits;
     S.chunks_left = (S.u_end - S.u + 1) >> 1;
-  } else if (K == 64 || K == kFmtK64BN || K == kFmtD1K8) {
+  } else if (K == 64 || K == kFmtK64BN || K == kFmtD1K8 || K == kFmtD1K8BN) {
     const int n_quads = k64_quads(n_cb);
-    constexpr int tab_bytes = K == 64 ? kK64QuadTabBytes : K == kFmtD1K8 ? kD1K8QuadTabBytes : kK64NQuadTabBytes;
+    constexpr int tab_bytes = K == 64 ? kK64QuadTabBytes : K == kFmtD1K8 ? kD1K8QuadTabBytes
+                              : K == kFmtD1K8BN ? kD1K8NQuadTabBytes : kK64NQuadTabBytes;
     S.idx_rb = P.idx + (size_t)rb * n_quads * kK64QuadIdxBytes;
     S.cb_rb = P.cb + (size_t)(rb / P.rb_per_cb) * n_quads * (tab_bytes / 4);
-    if (K == kFmtK64BN)   // the codes follow the table records of all group rows
+    if (K == kFmtK64BN || K == kFmtD1K8BN)   // the codes follow the table records of all group rows
       S.codes_rb = reinterpret_cast<const uint8_t*>(P.cb) +
                    (size_t)(P.n_rb / P.rb_per_cb) * n_quads * tab_bytes +
                    (size_t)rb * n_quads * kK64NQuadCodeBytes;
@@ -620,11 +624,12 @@ template <> struct ChunkS<256> : ChunkS256T<false> {};
 template <> struct ChunkS<kFmtD1K16> : ChunkS256T<true> {};
 
 template <int MODE> struct ChunkS64T {
-  static constexpr bool BN = MODE == 1, D1 = MODE == 2;
+  static constexpr bool BN = MODE == 1 || MODE == 3, D1 = MODE >= 2;
   static constexpr int kUnits = 1;
   static constexpr int kLutDwords = BN ? 320 : 256;
-  static constexpr int kTabBytes = BN ? kK64NQuadTabBytes : D1 ? kD1K8QuadTabBytes : kK64QuadTabBytes;
+  static constexpr int kTabBytes = D1 ? (BN ? kD1K8NQuadTabBytes : kD1K8QuadTabBytes) : BN ? kK64NQuadTabBytes : kK64QuadTabBytes;
   static constexpr int kScaleOffset = D1 ? kD1K8ScaleOffset : 512;
+  static constexpr int kLevelOffset = D1 ? kD1K8NLevelOffset : kK64NLevelOffset;
   uint4 w[3];
   uint2 tab;
   uint32_t sc;
@@ -642,7 +647,7 @@ template <int MODE> struct ChunkS64T {
     tab = zero_unless(ok, *reinterpret_cast<const uint2*>(tq + (D1 ? (uint32_t)(lane >> 4) * 8u : voff >> 1)));
     sc = *reinterpret_cast<const uint16_t*>(tq + kScaleOffset + (lane >> 4) * 2);
     if constexpr (BN) {
-      lev = zero_unless(ok, (uint32_t)*reinterpret_cast<const uint16_t*>(tq + kK64NLevelOffset + lane * 2));
+      lev = zero_unless(ok, (uint32_t)*reinterpret_cast<const uint16_t*>(tq + kLevelOffset + lane * 2));
       cw = *reinterpret_cast<const uint4*>(S.codes_rb + (size_t)q * kK64NQuadCodeBytes + (lane >> 3) * 16);
     }
 #pragma unroll
@@ -705,6 +710,7 @@ template <int MODE> struct ChunkS64T {
 template <> struct ChunkS<64> : ChunkS64T<0> {};
 template <> struct ChunkS<kFmtK64BN> : ChunkS64T<1> {};
 template <> struct ChunkS<kFmtD1K8> : ChunkS64T<2> {};
+template <> struct ChunkS<kFmtD1K8BN> : ChunkS64T<3> {};
 
 // Zeroed col-blocks kept behind x in LDS (absent units of a ragged chunk read them).
 constexpr int kXPadColBlocks = 8;
@@ -954,6 +960,7 @@ __global__ __launch_bounds__(64 * WPW) void gemv_split_kernel(const typename Bat
     case kFmtD1K16: F(kFmtD1K16); break;      \
     case kFmtK64BN: F(kFmtK64BN); break;      \
     case kFmtK16BN: F(kFmtK16BN); break;      \
+    case kFmtD1K8BN: F(kFmtD1K8BN); break;    \
     case kFmtD1K8: F(kFmtD1K8); break;        \
     case kFmtD1K4: F(kFmtD1K4); break;        \
     default: F(256); break;                   \
@@ -975,10 +982,10 @@ inline size_t stream_lds_bytes_impl(int fmt, int max_n_cb) {
 // piece of state the library keeps).  The slots are atomics: two threads that fill the same
 // slot at once store the same value.  The query enqueues nothing on any stream.
 template <bool LORA> int stream_resident_wgs_impl(int fmt, int max_n_cb) {
-  static std::atomic<int> cached[9][16][kStreamMaxColBlocks + 1];
+  static std::atomic<int> cached[10][16][kStreamMaxColBlocks + 1];
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) dev = 0;
-  const int fi = fmt == 16 ? 0 : fmt == 64 ? 1 : fmt == kFmtK16I8 ? 3 : fmt == kFmtD1K16 ? 4 : fmt == kFmtK64BN ? 5 : fmt == kFmtD1K8 ? 6 : fmt == kFmtD1K4 ? 7 : fmt == kFmtK16BN ? 8 : 2;
+  const int fi = fmt == 16 ? 0 : fmt == 64 ? 1 : fmt == kFmtK16I8 ? 3 : fmt == kFmtD1K16 ? 4 : fmt == kFmtK64BN ? 5 : fmt == kFmtD1K8 ? 6 : fmt == kFmtD1K4 ? 7 : fmt == kFmtK16BN ? 8 : fmt == kFmtD1K8BN ? 9 : 2;
   int slot = cached[fi][dev][max_n_cb].load(std::memory_order_relaxed);
   if (slot == 0) {
     int per_cu = 0, cus = 0;

@@ -18,6 +18,7 @@ constexpr int kFmtK16I8 = 1016;
 constexpr int kFmtK256I8 = 1256;   // d = 2, k = 256, int8 tables + scale, groups of 64, 128 or 256 rows x 256 columns
 constexpr int kFmtD1K16 = 2016;
 constexpr int kFmtK64BN = 3064;   // k = 64, int8 tables + scale, blockwise normalisation (blocks of 32)
+constexpr int kFmtD1K8BN = 3008;  // d = 1, k = 8, int8 values + scale, blockwise normalisation
 constexpr int kFmtK16BN = 3016;   // k = 16, int8 tables + scale, blockwise normalisation (blocks of 32)
 constexpr int kFmtD1K8 = 2008;     // d = 1, k = 8 (3-bit indices), int8 values + scale: pairs index a 64-entry pair table
 constexpr int kFmtD1K4 = 2004;     // d = 1, k = 4 (2-bit indices), int8 values + scale, one codebook per row of a
@@ -26,7 +27,7 @@ constexpr int kFmtD4 = 4256;      // d = 4, k = 256 (one index byte per 4 weight
                                   // groups of 64, 128 or 256 rows x 256 columns
 constexpr int kFmtD4F16 = 4257;   // the same with fp16 tables (2 KB per group, no scale)
 inline int format_tag(const vq_desc& d) {
-  if (d.d == 1) return d.k == 8 ? kFmtD1K8 : d.k == 4 ? kFmtD1K4 : kFmtD1K16;
+  if (d.d == 1) return d.k == 8 ? (d.codebook_dtype == VQ_I8_BN ? kFmtD1K8BN : kFmtD1K8) : d.k == 4 ? kFmtD1K4 : kFmtD1K16;
   if (d.d == 4) return d.codebook_dtype == VQ_F16 ? kFmtD4F16 : kFmtD4;
   if (d.codebook_dtype == VQ_I8_BN) return d.k == 16 ? kFmtK16BN : kFmtK64BN;
   if (d.k == 16 && d.codebook_dtype == VQ_I8) return kFmtK16I8;

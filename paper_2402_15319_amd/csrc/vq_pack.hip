@@ -233,8 +233,11 @@ __global__ __launch_bounds__(256) void pack_tab64_kernel(const uint8_t* __restri
 
 // d = 1, k = 8: per (row of groups, quad) four tables of 8 int8 values, four fp16 scales, padding
 // (48 bytes).  One thread per record.
+// With blockwise normalisation (level_canon != nullptr): 176-byte records, the four col-blocks'
+// 16 fp16 levels behind the 48 bytes.
 __global__ __launch_bounds__(256) void pack_tab_d1k8_kernel(const uint8_t* __restrict__ q_canon,
                                                             const uint16_t* __restrict__ scale_canon,
+                                                            const uint16_t* __restrict__ level_canon,
                                                             uint8_t* __restrict__ dev, int n_cb,
                                                             long long n_grow) {
   const long long slot = (long long)blockIdx.x * 256 + threadIdx.x;
@@ -242,7 +245,17 @@ __global__ __launch_bounds__(256) void pack_tab_d1k8_kernel(const uint8_t* __res
   if (slot >= n_grow * n_quads) return;
   const long long grow = slot / n_quads;
   const int q = (int)(slot - grow * n_quads);
-  uint8_t* dst = dev + (size_t)slot * kD1K8QuadTabBytes;
+  uint8_t* dst = dev + (size_t)slot * (level_canon ? kD1K8NQuadTabBytes : kD1K8QuadTabBytes);
+  if (level_canon) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int c = 4 * q + j;
+      uint4* lv = reinterpret_cast<uint4*>(dst + kD1K8NLevelOffset + j * 32);
+      const uint4* src = reinterpret_cast<const uint4*>(level_canon + (size_t)(grow * n_cb + (c < n_cb ? c : 0)) * 16);
+      lv[0] = c < n_cb ? src[0] : make_uint4(0, 0, 0, 0);
+      lv[1] = c < n_cb ? src[1] : make_uint4(0, 0, 0, 0);
+    }
+  }
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     const int c = 4 * q + j;
@@ -349,9 +362,18 @@ hipError_t launch_pack(const vq_desc& d, const void* idx_canon, const void* cb_c
     if (e != hipSuccess) return e;
     if (d.d == 1) {   // k = 8 scalar tables: 8 bytes per group, padded to 16 in total, then the scales
       const size_t q8 = ((size_t)n_grow * n_cb * 8 + 15) / 16 * 16;
+      const bool bn8 = d.codebook_dtype == VQ_I8_BN;
+      const size_t s8 = ((size_t)n_grow * n_cb * 2 + 15) / 16 * 16;        // levels follow the padded scales
+      const uint8_t* canon8 = (const uint8_t*)cb_canon;
       hipLaunchKernelGGL(pack_tab_d1k8_kernel, dim3((unsigned)((n_grow * n_quads + 255) / 256)), dim3(256), 0, s,
-                         (const uint8_t*)cb_canon, (const uint16_t*)((const uint8_t*)cb_canon + q8),
+                         canon8, (const uint16_t*)(canon8 + q8),
+                         bn8 ? (const uint16_t*)(canon8 + q8 + s8) : (const uint16_t*)nullptr,
                          (uint8_t*)cb_dev, n_cb, n_grow);
+      e = hipGetLastError();
+      if (e != hipSuccess || !bn8) return e;
+      hipLaunchKernelGGL(pack_codes64_kernel, dim3((unsigned)((n_rb * n_quads * 32 + 255) / 256)), dim3(256),
+                         0, s, canon8 + q8 + s8 + (size_t)n_grow * n_cb * 32,
+                         (uint32_t*)((uint8_t*)cb_dev + (size_t)n_grow * n_quads * kD1K8NQuadTabBytes), n_cb, n_rb);
       return hipGetLastError();
     }
     const size_t q_bytes = ((size_t)n_grow * n_cb * 128 + 15) / 16 * 16;   // scales follow the tables

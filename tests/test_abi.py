@@ -256,9 +256,23 @@ def test_block_normalised_representation_sizes_and_validation():
         slots = (out_f // 8) * 2 * ((in_f // 256 + 1) // 2)
         assert vq.vq_layout_bytes(d) == (slots * 512, (34 * slots + 15) // 16 * 16 + 64 * slots)
         assert L.vq_gemv(ctypes.byref(d), A, A, A + 2, A + 16, vq.VQ_F16, 0) == -4
+    # d = 1, k = 8: 176-byte records (4 x 8 values, 4 scales, padding to 48, 4 x 16 levels) per (group row,
+    # quad), then the codes as for k = 64; 3 + (64 + 16 + 256) / 8192 + 1 / 8 = 3.166 bits per value
+    for out_f, in_f, rows in ((4096, 4096, 32), (4096, 11008, 32), (64, 768, 8)):
+        d = vq.make_desc(out_f, in_f, 8, 3, group_rows=rows, d=1, codebook_dtype=vq.VQ_I8_BN)
+        n_groups = (out_f // rows) * (in_f // 256)
+        ib, cbb = vq.vq_canonical_bytes(d)
+        assert ib == out_f * in_f * 3 // 8
+        assert cbb == (n_groups * 8 + 15) // 16 * 16 + (n_groups * 2 + 15) // 16 * 16 + n_groups * 32 + out_f * in_f // 64
+        if rows == 32:
+            assert (ib + cbb) * 8 / (out_f * in_f) == pytest.approx(3 + 336 / 8192 + 0.125, abs=1e-4)
+        quads = (in_f // 256 + 3) // 4
+        assert vq.vq_layout_bytes(d) == ((out_f // 8) * quads * 3072, (out_f // rows) * quads * 176 + (out_f // 8) * quads * 128)
+        assert L.vq_gemv(ctypes.byref(d), A, A, A + 2, A + 16, vq.VQ_F16, 0) == -4
     # the other representations do not take block scales
     for bad in (vq.make_desc(4096, 4096, 256, 8, group_rows=128, codebook_dtype=vq.VQ_I8_BN),
-                vq.make_desc(4096, 4096, 8, 3, group_rows=32, d=1, codebook_dtype=vq.VQ_I8_BN),
+                vq.make_desc(4096, 4096, 16, 4, d=1, codebook_dtype=vq.VQ_I8_BN),
+                vq.make_desc(4096, 4096, 4, 2, group_rows=1, d=1, codebook_dtype=vq.VQ_I8_BN),
                 vq.make_desc(4096, 4096, 256, 8, group_rows=256, d=4, codebook_dtype=vq.VQ_I8_BN),
                 vq.make_desc(4096, 4096, 16, 4, group_rows=16, codebook_dtype=vq.VQ_I8_BN)):
         assert L.vq_gemv(ctypes.byref(bad), A, A, A, A + 16, vq.VQ_F16, 0) == -3

@@ -232,6 +232,7 @@ PASS_FORMATS = {
     "k256_i8": workloads.LLAMA7B_LAYER_K256_I8, "d4": workloads.LLAMA7B_LAYER_D4, "d1_k16": workloads.LLAMA7B_LAYER_D1_K16,
     "d1_k8": workloads.LLAMA7B_LAYER_D1_K8, "d1_k4": workloads.LLAMA7B_LAYER_D1_K4,
     "k64_bn": workloads.LLAMA7B_LAYER_K64_BN, "k16_bn": workloads.LLAMA7B_LAYER_K16_BN,
+    "d1_k8_bn": workloads.LLAMA7B_LAYER_D1_K8_BN,
 }
 
 
@@ -1229,6 +1230,67 @@ def test_random_shapes_newer_representations(env, s):
     assert oracle.normwise_rel_err(Y, oracle.gemm(f, idx, cb, X)) <= TOL_F32
 
 
+# ---------------------------------------------------------------- blockwise normalisation on scalar codebooks (d = 1, k = 8)
+def _shape_bn8(o, i, rows=32):
+    return workloads.VQShape(o, i, 8, 3, rows, 256, 1, True, True)
+
+
+# whole and ragged quads of col-blocks, the three group heights, one to many row-blocks
+BN8_SMALL = [_shape_bn8(32, 256), _shape_bn8(96, 768), _shape_bn8(64, 2816), _shape_bn8(40, 1280, 8),
+             _shape_bn8(48, 512, 16), _shape_bn8(264, 1024, 8), _shape_bn8(32, 256 * 43)]
+
+
+@pytest.mark.parametrize("s", BN8_SMALL, ids=str)
+def test_block_norm_d1k8_decode_bit_exact(env, s):
+    desc, W, idx_d, cb_d = _setup_bn(env, s, 720)
+    np.testing.assert_array_equal(_gpu_decode(env, desc, idx_d, cb_d), W)
+
+
+@pytest.mark.parametrize("f32", [False, True], ids=["y16", "y32"])
+@pytest.mark.parametrize("s", BN8_SMALL + [_shape_bn8(32800, 768), _shape_bn8(33024, 1280, 16)], ids=str)
+def test_block_norm_d1k8_gemv(env, s, f32):
+    """Split-K kernel on the small shapes, the streaming kernel from 4,096 row-blocks."""
+    desc, W, idx_d, cb_d = _setup_bn(env, s, 721)
+    x = workloads.make_x(s.in_features, 721)
+    y = _gpu_gemv(env, desc, idx_d, cb_d, x, f32)
+    ref = _dense_product(W, x)
+    assert oracle.normwise_rel_err(y, ref) <= (TOL_F32 if f32 else TOL_F16)
+    if s.out_features >= 4096:
+        _assert_rows_match(y, ref, f32, str(s))
+
+
+@pytest.mark.parametrize("B", [1, 16, 40, 130, 600, 1300])
+@pytest.mark.parametrize("s", [_shape_bn8(96, 768), _shape_bn8(808, 512, 8)], ids=str)
+def test_block_norm_d1k8_gemm(env, s, B):
+    desc, W, idx_d, cb_d = _setup_bn(env, s, 722)
+    X = workloads.make_X(s.in_features, B, 722)
+    Y = _gpu_gemm(env, desc, idx_d, cb_d, X, False, pad=8 if B == 40 else 0)
+    assert oracle.normwise_rel_err(Y, _dense_product(W, X)) <= TOL_F16
+
+
+@pytest.mark.timeout(600)
+def test_block_norm_d1k8_full_size(env):
+    """4096 x 11008 (43 col-blocks: a ragged last quad), 32 x 256 groups: decode in full, GEMV with
+    both output types element by element, and the whole B = 2048 product, tile by tile."""
+    s = workloads.CONFIGS["mlp_down_4096x11008_d1_k8_bn"]
+    desc, W, idx_d, cb_d = _setup_bn(env, s, 723)
+    np.testing.assert_array_equal(_gpu_decode(env, desc, idx_d, cb_d), W)
+    x = workloads.make_x(s.in_features, 723)
+    _assert_rows_match(_gpu_gemv(env, desc, idx_d, cb_d, x, False), _dense_product(W, x), False, "bn8 y16")
+    _assert_rows_match(_gpu_gemv(env, desc, idx_d, cb_d, x, True), _dense_product(W, x), True, "bn8 y32")
+    X = workloads.make_X(s.in_features, 2048, 723)
+    _assert_tiles_match(_gpu_gemm(env, desc, idx_d, cb_d, X, False), _dense_product(W, X))
+
+
+def _random_cases_bn8(seed, n):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for _ in range(n):
+        rows = int(rng.choice([8, 16, 32]))
+        cases.append(_shape_bn8(rows * int(rng.integers(1, 12)), 256 * int(rng.integers(1, 45)), rows))
+    return cases
+
+
 def _random_cases_bn(seed, n):
     """Seeded random shapes of the two block-normalised representations (k = 64 with 8-, 16- or 32-row
     groups; k = 16), up to 44 col-blocks wide."""
@@ -1244,7 +1306,7 @@ def _random_cases_bn(seed, n):
     return cases
 
 
-@pytest.mark.parametrize("s", _random_cases_bn(20242, 16), ids=str)
+@pytest.mark.parametrize("s", _random_cases_bn(20242, 16) + _random_cases_bn8(20243, 8), ids=str)
 def test_random_shapes_block_normalised(env, s):
     """Decode (bit-exact), GEMV (fp16 and fp32 y) and the batched product on random shapes."""
     seed = 7200 + s.out_features + s.in_features + s.k

@@ -23,7 +23,7 @@ __all__ = [
     "VQShape", "CONFIGS", "LLAMA7B_LAYER", "seed_for", "canonical_sizes",
     "make_weights", "make_weights_i8", "make_x", "make_X", "llama7b_pass_shapes",
     "tables_i8_bytes", "tables_bn_bytes",
-    "LLAMA7B_LAYER_K64", "LLAMA7B_LAYER_K16_I8", "LLAMA7B_LAYER_D1_K16", "LLAMA7B_LAYER_K64_BN", "LLAMA7B_LAYER_K16_BN", "make_weights_bn", "LLAMA7B_LAYER_D4", "LLAMA7B_LAYER_D1_K8", "LLAMA7B_LAYER_K256_I8", "LLAMA7B_LAYER_D1_K4",
+    "LLAMA7B_LAYER_K64", "LLAMA7B_LAYER_K16_I8", "LLAMA7B_LAYER_D1_K16", "LLAMA7B_LAYER_K64_BN", "LLAMA7B_LAYER_K16_BN", "make_weights_bn", "LLAMA7B_LAYER_D4", "LLAMA7B_LAYER_D1_K8", "LLAMA7B_LAYER_D1_K8_BN", "LLAMA7B_LAYER_K256_I8", "LLAMA7B_LAYER_D1_K4",
 ]
 
 
@@ -112,6 +112,10 @@ CONFIGS = {
     "attn_4096x4096_k16_bn": VQShape(4096, 4096, 16, 4, 8, 256, 2, True, True),
     "mlp_up_11008x4096_k16_bn": VQShape(11008, 4096, 16, 4, 8, 256, 2, True, True),
     "mlp_down_4096x11008_k16_bn": VQShape(4096, 11008, 16, 4, 8, 256, 2, True, True),
+    # scalar codebooks at 3 bits with blockwise normalisation: 3.17 bpv at 32 x 256 groups
+    "attn_4096x4096_d1_k8_bn": VQShape(4096, 4096, 8, 3, 32, 256, 1, True, True),
+    "mlp_up_11008x4096_d1_k8_bn": VQShape(11008, 4096, 8, 3, 32, 256, 1, True, True),
+    "mlp_down_4096x11008_d1_k8_bn": VQShape(4096, 11008, 8, 3, 32, 256, 1, True, True),
 }
 
 # One Llama-7B decoder layer as (name, shape key) in execution order.
@@ -130,6 +134,7 @@ LLAMA7B_LAYER_K16_I8 = tuple((n, k + "_i8") for n, k in LLAMA7B_LAYER)
 LLAMA7B_LAYER_K64_BN = tuple((n, k.replace("_k16", "_k64_bn")) for n, k in LLAMA7B_LAYER)
 LLAMA7B_LAYER_K16_BN = tuple((n, k + "_bn") for n, k in LLAMA7B_LAYER)
 LLAMA7B_LAYER_D1_K8 = tuple((n, k.replace("_k16", "_d1_k8")) for n, k in LLAMA7B_LAYER)
+LLAMA7B_LAYER_D1_K8_BN = tuple((n, k.replace("_k16", "_d1_k8_bn")) for n, k in LLAMA7B_LAYER)
 LLAMA7B_LAYER_D1_K4 = tuple((n, k.replace("_k16", "_d1_k4")) for n, k in LLAMA7B_LAYER)
 LLAMA7B_LAYER_D4 = tuple((n, k.replace("_k16", "_d4")) for n, k in LLAMA7B_LAYER)
 LLAMA7B_LAYER_D1_K16 = tuple((n, k.replace("_k16", "_d1_k16")) for n, k in LLAMA7B_LAYER)
