@@ -283,6 +283,11 @@ def main():
                 # the 2.125 bpv setting with blockwise normalisation on top: 2.38 bits per value
                 ("llama7b_pass_k16_int8_tables_block_norm_2.38bpv_via_vq_gemv_multi", workloads.LLAMA7B_LAYER_K16_BN,
                  "gemv_stream_kernel<k16,bn>"),
+                # the 4.125 bpv 2D setting and the 4D setting with blockwise normalisation on top
+                ("llama7b_pass_k256_int8_tables_block_norm_4.26bpv_via_vq_gemv_multi", workloads.LLAMA7B_LAYER_K256_BN,
+                 "gemv_k256i8_kernel<bn>"),
+                ("llama7b_pass_d4_k256_int8_tables_block_norm_2.25bpv_via_vq_gemv_multi", workloads.LLAMA7B_LAYER_D4_BN,
+                 "gemv_d4_kernel<bn>"),
                 # four-dimensional vectors: k = 256, one index byte per 4 weights, 256 x 256 groups (2.125 bpv)
                 ("llama7b_pass_d4_k256_int8_tables_2.125bpv_via_vq_gemv_multi", workloads.LLAMA7B_LAYER_D4,
                  "gemv_d4_kernel"),
@@ -305,14 +310,15 @@ def main():
                     desc = vqdev.desc_from_shape(s)
                     ib, cbb = vq.vq_layout_bytes(desc)
                     tab = torch.randint(0, 256, (cbb,), dtype=torch.uint8, device=dev)
-                    if s.d == 4:                        # 1 KB int8 tables per group, then fp16 scales (set to 2^-8)
-                        n_groups = (s.out_features // s.group_rows) * (s.in_features // 256)
-                        tab[n_groups * 1024:] = 0
-                        tab[n_groups * 1024 + 1:n_groups * 1026:2] = 0x1C
-                    elif s.d == 2 and s.k == 256:       # 512-byte int8 tables per group, then fp16 scales (2^-8)
-                        n_groups = (s.out_features // s.group_rows) * (s.in_features // 256)
-                        tab[n_groups * 512:] = 0
-                        tab[n_groups * 512 + 1:n_groups * 514:2] = 0x1C
+                    if s.int8_tables and s.k == 256:    # 1 KB (d = 4) or 512-byte int8 tables per group, then fp16 scales (2^-8);
+                        n_groups = (s.out_features // s.group_rows) * (s.in_features // 256)   # block-normalised: + levels (1.0), codes
+                        t_end = n_groups * (1024 if s.d == 4 else 512)
+                        s_end = t_end + (2 * n_groups + 15) // 16 * 16
+                        tab[t_end:s_end] = 0
+                        tab[t_end + 1:t_end + 2 * n_groups:2] = 0x1C
+                        if s.block_norm:
+                            tab[s_end:s_end + 32 * n_groups:2] = 0
+                            tab[s_end + 1:s_end + 32 * n_groups:2] = 0x3C
                     elif s.d == 1 and s.k == 8 and s.block_norm:   # 176-byte records: the same + 64 levels (1.0); then codes
                         n_rec = (s.out_features // s.group_rows) * ((s.in_features // 256 + 3) // 4)
                         tv = tab[:n_rec * 176].view(-1, 176)

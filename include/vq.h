@@ -58,8 +58,9 @@
  * bits per value; VQ_I8, k = 8, 3-bit indices, groups of 8, 16 or 32 rows x 256 columns; and
  * VQ_I8, k = 4, 2-bit indices, groups of 1 x 256 (one codebook per row of a 256-column block,
  * the 2.125-bit 1D row; out_features a multiple of 8); VQ_I8_BN with k = 64 and groups of 8, 16
- * or 32 rows x 256 columns, with k = 16 and 8 x 256 groups, or with d = 1, k = 8 and groups of
- * 8, 16 or 32 rows x 256 columns; and
+ * or 32 rows x 256 columns, with k = 16 and 8 x 256 groups, with d = 1, k = 8 and groups of
+ * 8, 16 or 32 rows x 256 columns, or with k = 256 (d = 2 or 4) and groups of 64, 128 or 256 rows,
+ * i.e. on every int8-table representation but the one-row groups of d = 1, k = 4; and
  * four-dimensional vectors, d = 4 (the 4D rows of that table): VQ_I8 or VQ_F16, k = 256 (one index
  * byte per 4 weights), groups of 64, 128 or 256 rows x 256 columns (256 rows: 2.125 bits per value
  * with int8 tables, 2.25 with fp16 tables).
@@ -103,8 +104,8 @@ typedef struct vq_desc {
   int32_t group_cols;     /* 256 (Sec. 4: at most 256 columns per group)            */
   int32_t d;              /* VQ dimensionality: 2, 1 (scalar codebooks) or 4        */
   int32_t k;              /* centroids.  d = 2: 16 or 256 (VQ_F16), 16, 64 or 256 (VQ_I8),
-                             64 or 16 (VQ_I8_BN); d = 1: 16 (VQ_F16), 8 or 4 (VQ_I8), 8 (VQ_I8_BN); d = 4: 256
-                             (VQ_I8 or VQ_F16) */
+                             16, 64 or 256 (VQ_I8_BN); d = 1: 16 (VQ_F16), 8 or 4 (VQ_I8), 8 (VQ_I8_BN);
+                             d = 4: 256 (VQ_I8, VQ_I8_BN or VQ_F16) */
   int32_t index_bits;     /* log2(k): 2, 3, 4, 6 or 8                               */
   int32_t codebook_dtype; /* VQ_F16, VQ_I8 or VQ_I8_BN (see the list above)         */
 } vq_desc;

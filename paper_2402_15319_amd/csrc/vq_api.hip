@@ -51,15 +51,15 @@ int check_desc(const vq_desc* d) {
     } else if (d->k != 16 || is_i8(*d) || d->group_rows != kGroupRows) {
       return VQ_ERR_UNSUPPORTED;
     }
-  } else if (d->d == 4) {                     // int8 tables with a scale, or fp16 tables
-    if (d->k != 256 || (d->codebook_dtype != VQ_I8 && d->codebook_dtype != VQ_F16)) return VQ_ERR_UNSUPPORTED;
+  } else if (d->d == 4) {                     // int8 tables with a scale (also block-normalised), or fp16 tables
+    if (d->k != 256) return VQ_ERR_UNSUPPORTED;
     if (d->group_rows != 64 && d->group_rows != 128 && d->group_rows != 256) return VQ_ERR_UNSUPPORTED;
   } else if (is_i8(*d)) {
     if (d->k == 64) {
       if (d->group_rows != 8 && d->group_rows != 16 && d->group_rows != 32) return VQ_ERR_UNSUPPORTED;
     } else if (d->k == 16) {                  // with or without blockwise normalisation
       if (d->group_rows != kGroupRows) return VQ_ERR_UNSUPPORTED;
-    } else if (d->k == 256 && !is_bn(*d)) {   // the 4-bits-per-dimension 2D setting: large groups share a table
+    } else if (d->k == 256) {                 // the 4-bits-per-dimension 2D setting: large groups share a table
       if (d->group_rows != 64 && d->group_rows != 128 && d->group_rows != 256) return VQ_ERR_UNSUPPORTED;
     } else {
       return VQ_ERR_UNSUPPORTED;
@@ -200,8 +200,8 @@ int gemv_multi_impl(int count, const vq_desc* descs, const void* const* idx_dev,
       down.total_rows = rows;
       if (m > 0 && launch_lora_down(down, (hipStream_t)stream) != hipSuccess) return VQ_ERR_HIP;
     }
-    const bool d4 = fmt == kFmtD4 || fmt == kFmtD4F16;
-    if (d4 || fmt == kFmtK256I8) {   // one workgroup per 64 rows, see vq_gemv_d4.hip
+    const bool d4 = fmt == kFmtD4 || fmt == kFmtD4F16 || fmt == kFmtD4BN;
+    if (d4 || fmt == kFmtK256I8 || fmt == kFmtK256I8BN) {   // one workgroup per 64 rows, see vq_gemv_d4.hip
       GemvBatchLora both;                       // 20 KB on the stack; only the used entries are filled
       GemvBatch& batch = both.base;
       memset(&batch, 0, offsetof(GemvBatch, p) + (size_t)n * sizeof(GemvProblem));
@@ -234,10 +234,10 @@ int gemv_multi_impl(int count, const vq_desc* descs, const void* const* idx_dev,
       if (wgs > 0x7fffffffll) return VQ_ERR_UNSUPPORTED;
       batch.total_wgs = (int32_t)wgs;
       const hipError_t e =
-          lora ? (d4 ? launch_gemv_d4_lora(both, (int)wgs, (hipStream_t)stream, fmt == kFmtD4F16)
-                     : launch_gemv_k256i8_lora(both, (int)wgs, (hipStream_t)stream))
-               : (d4 ? launch_gemv_d4(batch, (int)wgs, (hipStream_t)stream, fmt == kFmtD4F16)
-                     : launch_gemv_k256i8(batch, (int)wgs, (hipStream_t)stream));
+          lora ? (d4 ? launch_gemv_d4_lora(both, (int)wgs, (hipStream_t)stream, fmt)
+                     : launch_gemv_k256i8_lora(both, (int)wgs, (hipStream_t)stream, fmt))
+               : (d4 ? launch_gemv_d4(batch, (int)wgs, (hipStream_t)stream, fmt)
+                     : launch_gemv_k256i8(batch, (int)wgs, (hipStream_t)stream, fmt));
       if (e != hipSuccess) return VQ_ERR_HIP;
       continue;
     }
@@ -374,7 +374,9 @@ int vq_layout_bytes(const vq_desc* desc, size_t* idx_bytes, size_t* cb_bytes) {
   if (desc->d == 4) {    // 1 KB of indices per (8-row block, pair of col-blocks); tables as in the canonical buffer
     const size_t n_groups = (size_t)(desc->out_features / desc->group_rows) * n_cb;
     if (idx_bytes) *idx_bytes = n_rb * ((n_cb + 1) / 2) * 1024;
-    if (cb_bytes) *cb_bytes = is_i8(*desc) ? n_groups * 1024 + (2 * n_groups + 15) / 16 * 16 : n_groups * 2048;
+    if (cb_bytes)   // with blockwise normalisation: + 32 bytes of levels per group and 64 of codes per (8-row block, pair)
+      *cb_bytes = is_bn(*desc) ? wide_bn_code_offset(n_groups, 1024) + n_rb * ((n_cb + 1) / 2) * 64
+                  : is_i8(*desc) ? n_groups * 1024 + (2 * n_groups + 15) / 16 * 16 : n_groups * 2048;
     return VQ_OK;
   }
   if (desc->d == 1 && desc->k == 8) {   // indices as for k = 64; 48-byte table records per (group row, quad)
@@ -388,7 +390,9 @@ int vq_layout_bytes(const vq_desc* desc, size_t* idx_bytes, size_t* cb_bytes) {
   if (desc->d == 2 && desc->k == 256 && is_i8(*desc)) {   // 1 KB of indices per (8-row block, col-block); tables as canonical
     const size_t n_groups = (size_t)(desc->out_features / desc->group_rows) * n_cb;
     if (idx_bytes) *idx_bytes = n_rb * n_cb * 1024;
-    if (cb_bytes) *cb_bytes = n_groups * 512 + (2 * n_groups + 15) / 16 * 16;
+    if (cb_bytes)
+      *cb_bytes = is_bn(*desc) ? wide_bn_code_offset(n_groups, 512) + n_rb * ((n_cb + 1) / 2) * 64
+                               : n_groups * 512 + (2 * n_groups + 15) / 16 * 16;
     return VQ_OK;
   }
   if (desc->d == 1 && desc->k == 4) {   // indices as for k = 16; a 48-byte table record per (8-row block, col-block slot)

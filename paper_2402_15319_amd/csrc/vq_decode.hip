@@ -18,7 +18,7 @@ __global__ __launch_bounds__(256) void decode_kernel(const uint8_t* __restrict__
                                                      uint16_t* __restrict__ W, int n_cb,
                                                      long long n_groups, int in_features, int rpc) {
   // (k = 16 with blockwise normalisation: 16 table entries, then the group's 16 levels)
-  __shared__ uint32_t lut_all[4][K == kFmtK16I8 ? 16 : K == kFmtK16BN ? 32 : (K == kFmtD1K16 || K == kFmtK256I8) ? 256 : K == kFmtD1K4 ? 128 : K];
+  __shared__ uint32_t lut_all[4][K == kFmtK16I8 ? 16 : K == kFmtK16BN ? 32 : (K == kFmtD1K16 || K == kFmtK256I8) ? 256 : K == kFmtK256I8BN ? 272 : K == kFmtD1K4 ? 128 : K];
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   uint32_t* lut = lut_all[wave];
@@ -93,9 +93,16 @@ __global__ __launch_bounds__(256) void decode_kernel(const uint8_t* __restrict__
       }
     }
   } else {
-    if (K == kFmtK256I8) {   // int8 table of group (rb / rpc, c): lane L dequantises entries 4L .. 4L+3
+    uint32_t cw = 0;         // block-normalised: the lane's block codes, row r in bits [4r, 4r+4)
+    if (K == kFmtK256I8 || K == kFmtK256I8BN) {   // int8 table of group (rb / rpc, c): lane L dequantises entries 4L .. 4L+3
       const uint8_t* tab = reinterpret_cast<const uint8_t*>(cb);
       const long long gt = (rb / rpc) * n_cb + c, n_tabs = (n_groups / n_cb / rpc) * n_cb;
+      if (K == kFmtK256I8BN) {
+        if (lane < 16)
+          lut[256 + lane] = 0x10001u * reinterpret_cast<const uint16_t*>(tab + wide_bn_level_offset((size_t)n_tabs, 512))[gt * 16 + lane];
+        cw = reinterpret_cast<const uint32_t*>(tab + wide_bn_code_offset((size_t)n_tabs, 512))
+                 [(rb * k16_pairs(n_cb) + (c >> 1)) * 16 + 2 * (lane >> 3) + (c & 1)];
+      }
       const uint2 q = *reinterpret_cast<const uint2*>(tab + gt * 512 + lane * 8);
       const _Float16 scale = __builtin_bit_cast(_Float16, reinterpret_cast<const uint16_t*>(tab + n_tabs * 512)[gt]);
       *reinterpret_cast<uint4*>(lut + lane * 4) =
@@ -115,8 +122,13 @@ __global__ __launch_bounds__(256) void decode_kernel(const uint8_t* __restrict__
 #pragma unroll
     for (int r = 0; r < 8; ++r) {
       const uint32_t half = ws[r >> 1] >> (16 * (r & 1));
-      *reinterpret_cast<uint2*>(out + (size_t)r * in_features) =
-          make_uint2(lut[half & 255u], lut[(half >> 8) & 255u]);
+      uint32_t lo = lut[half & 255u], hi = lut[(half >> 8) & 255u];
+      if (K == kFmtK256I8BN) {   // times the scale of the row's 32-weight block: one more fp16 rounding
+        const uint32_t sc = lut[256 + ((cw >> (4 * r)) & 15u)];
+        lo = scale_pair(lo, sc);
+        hi = scale_pair(hi, sc);
+      }
+      *reinterpret_cast<uint2*>(out + (size_t)r * in_features) = make_uint2(lo, hi);
     }
   }
 }
@@ -193,15 +205,20 @@ __global__ __launch_bounds__(256) void decode64_kernel(const uint8_t* __restrict
 // d = 4 (k = 256, int8 tables with a scale): one wave per (8-row block, col-block).  Lane L
 // dequantises table entries 4L .. 4L+3 into the wave's 2 KB table, then copies one 8-byte entry
 // per row (its vector: columns 4L .. 4L+3).
-template <bool F16>    // F16: fp16 tables (2 KB per group) instead of int8 tables with a scale
+// MODE 1 (F16): fp16 tables (2 KB per group) instead of int8 tables with a scale; MODE 2 (BN):
+// int8 tables with blockwise normalisation (every copied vector times the scale of its block).
+template <int MODE>
 __global__ __launch_bounds__(256) void decode_d4_kernel(const uint8_t* __restrict__ idx,
                                                         const uint8_t* __restrict__ tab,
                                                         uint16_t* __restrict__ W, int n_cb,
                                                         long long n_items, int in_features, int rpc) {
+  constexpr bool F16 = MODE == 1, BN = MODE == 2;
   __shared__ __attribute__((aligned(16))) uint2 lut_all[4][256];
+  __shared__ uint32_t lev_all[4][16];
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   uint2* lut = lut_all[wave];
+  uint32_t* lev = lev_all[wave];
   const long long item = (long long)blockIdx.x * 4 + wave;
   if (item >= n_items) return;   // whole waves leave; no workgroup barrier below
   const long long rb8 = item / n_cb;
@@ -221,13 +238,25 @@ __global__ __launch_bounds__(256) void decode_d4_kernel(const uint8_t* __restric
     lut[4 * lane + 3] = d4_dequant_entry(q.w, scale);
   }
   const int n_pairs = (n_cb + 1) >> 1;
+  uint32_t cw = 0;
+  if constexpr (BN) {
+    if (lane < 16)
+      lev[lane] = 0x10001u * reinterpret_cast<const uint16_t*>(tab + wide_bn_level_offset((size_t)n_groups, 1024))[g * 16 + lane];
+    cw = reinterpret_cast<const uint32_t*>(tab + wide_bn_code_offset((size_t)n_groups, 1024))
+             [(rb8 * n_pairs + (c >> 1)) * 16 + 2 * (lane >> 3) + (c & 1)];
+  }
   const uint2 w = *reinterpret_cast<const uint2*>(idx + (size_t)(rb8 * n_pairs + (c >> 1)) * 1024 + lane * 16 + (c & 1) * 8);
   wave_lds_sync();
   uint16_t* out = W + (size_t)rb8 * 8 * in_features + (size_t)c * 256 + lane * 4;
 #pragma unroll
   for (int r = 0; r < 8; ++r) {
     const uint32_t j = ((r < 4 ? w.x : w.y) >> (8 * (r & 3))) & 0xffu;
-    *reinterpret_cast<uint2*>(out + (size_t)r * in_features) = lut[j];
+    uint2 t = lut[j];
+    if constexpr (BN) {
+      const uint32_t sc = lev[(cw >> (4 * r)) & 15u];
+      t = make_uint2(scale_pair(t.x, sc), scale_pair(t.y, sc));
+    }
+    *reinterpret_cast<uint2*>(out + (size_t)r * in_features) = t;
   }
 }
 
@@ -239,15 +268,15 @@ hipError_t launch_decode(const vq_desc& d, const void* idx_dev, const void* cb_d
   const long long n_groups = (long long)(d.out_features / kGroupRows) * n_cb;   // 8-row items
   const unsigned grid = (unsigned)((n_groups + 3) / 4);
   const int fmt = format_tag(d);
-  if (fmt == kFmtD4 || fmt == kFmtD4F16) {
-    if (fmt == kFmtD4)
-      hipLaunchKernelGGL(decode_d4_kernel<false>, dim3(grid), dim3(256), 0, s, (const uint8_t*)idx_dev,
-                         (const uint8_t*)cb_dev, (uint16_t*)W, n_cb, n_groups, d.in_features,
-                         d.group_rows / kGroupRows);
-    else
-      hipLaunchKernelGGL(decode_d4_kernel<true>, dim3(grid), dim3(256), 0, s, (const uint8_t*)idx_dev,
-                         (const uint8_t*)cb_dev, (uint16_t*)W, n_cb, n_groups, d.in_features,
-                         d.group_rows / kGroupRows);
+  if (fmt == kFmtD4 || fmt == kFmtD4F16 || fmt == kFmtD4BN) {
+#define VQ_DECODE_D4(MODE)                                                                            \
+    hipLaunchKernelGGL(decode_d4_kernel<MODE>, dim3(grid), dim3(256), 0, s, (const uint8_t*)idx_dev, \
+                       (const uint8_t*)cb_dev, (uint16_t*)W, n_cb, n_groups, d.in_features,          \
+                       d.group_rows / kGroupRows)
+    if (fmt == kFmtD4) VQ_DECODE_D4(0);
+    else if (fmt == kFmtD4F16) VQ_DECODE_D4(1);
+    else VQ_DECODE_D4(2);
+#undef VQ_DECODE_D4
     return hipGetLastError();
   }
   if (fmt == 64 || fmt == kFmtK64BN || fmt == kFmtD1K8 || fmt == kFmtD1K8BN) {
@@ -271,6 +300,7 @@ hipError_t launch_decode(const vq_desc& d, const void* idx_dev, const void* cb_d
   else if (fmt == kFmtD1K16) VQ_DECODE(kFmtD1K16);
   else if (fmt == kFmtD1K4) VQ_DECODE(kFmtD1K4);
   else if (fmt == kFmtK256I8) VQ_DECODE(kFmtK256I8);
+  else if (fmt == kFmtK256I8BN) VQ_DECODE(kFmtK256I8BN);
   else if (fmt == 16) VQ_DECODE(16);
   else VQ_DECODE(256);
 #undef VQ_DECODE

@@ -458,6 +458,31 @@ __device__ __forceinline__ void k64_group_scaled(uint32_t d0, uint32_t d1, uint3
   }
 }
 
+// One fp16 pair times a block scale held in both halves of a dword (one rounding per half).
+__device__ __forceinline__ uint32_t scale_pair(uint32_t pair, uint32_t scale2) {
+  return __builtin_bit_cast(uint32_t, __builtin_bit_cast(h2_t, pair) * __builtin_bit_cast(h2_t, scale2));
+}
+
+// k = 256 inner block with block scales, in plain C++ like k64_group_scaled: w0 .. w3 hold the
+// lane's 16 index bytes of one group (byte 2r + e = row r, vector 2L + e), cw its block codes
+// (row r in bits [4r, 4r+4)), tab the group's 256 dequantised entries, lev its 16 level dwords.
+__device__ __forceinline__ void k256_group_scaled(uint32_t w0, uint32_t w1, uint32_t w2, uint32_t w3,
+                                                  uint32_t cw, const uint32_t* tab, const uint32_t* lev,
+                                                  uint32_t x0, uint32_t x1, float (&acc)[8]) {
+  const uint32_t ws[4] = {w0, w1, w2, w3};
+  const h2_t xa = __builtin_bit_cast(h2_t, x0), xb = __builtin_bit_cast(h2_t, x1);
+  uint32_t t[16], sv[8];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) t[i] = tab[(ws[i >> 2] >> (8 * (i & 3))) & 0xffu];
+#pragma unroll
+  for (int r = 0; r < 8; ++r) sv[r] = lev[(cw >> (4 * r)) & 15u];
+#pragma unroll
+  for (int r = 0; r < 8; ++r) {
+    acc[r] = __builtin_amdgcn_fdot2(__builtin_bit_cast(h2_t, scale_pair(t[2 * r], sv[r])), xa, acc[r], false);
+    acc[r] = __builtin_amdgcn_fdot2(__builtin_bit_cast(h2_t, scale_pair(t[2 * r + 1], sv[r])), xb, acc[r], false);
+  }
+}
+
 // ---- d = 4 device layout (k = 256, int8 tables) ---------------------------------------------
 // A lane owns ONE vector per row of a group: columns 4L .. 4L+3, one index byte.  Indices:
 // per (8-row block, pair of col-blocks) 1 KB; the lane's 16 bytes are its 8 row bytes of the

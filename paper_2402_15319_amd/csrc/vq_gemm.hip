@@ -42,7 +42,7 @@ __device__ __forceinline__ int wt_half_index(int m, int k) {   // k in halfs
 // scale per group, groups of 8*rpc rows), kFmtK16I8 (k = 16 with int8 tables).
 template <int K> constexpr int lut_dwords() {
   // BN: 64 centroids + 16 levels; d = 4: 256 entries of 4 halfs; scalar 2-bit: 8 rows x 16 pair entries
-  return K == kFmtK16I8 ? 16 : K == kFmtK16BN ? 32 : (K == kFmtD1K16 || K == kFmtK256I8) ? 256 : (K == kFmtK64BN || K == kFmtD1K8BN) ? 80 : (K == kFmtD4 || K == kFmtD4F16) ? 512 : K == kFmtD1K8 ? 64 : K == kFmtD1K4 ? 128 : K;
+  return K == kFmtK16I8 ? 16 : K == kFmtK16BN ? 32 : (K == kFmtD1K16 || K == kFmtK256I8) ? 256 : K == kFmtK256I8BN ? 272 : (K == kFmtK64BN || K == kFmtD1K8BN) ? 80 : (K == kFmtD4 || K == kFmtD4F16 || K == kFmtD4BN) ? 512 : K == kFmtD1K8 ? 64 : K == kFmtD1K4 ? 128 : K;
 }
 
 // What one wave needs to decode one group: the lane's index bytes and codebook piece.
@@ -75,6 +75,19 @@ template <> struct GroupRegs<kFmtD4> {
   uint2 w;        // the lane's 8 index bytes (one vector per row)
   uint4 q;        // table entries 4*lane .. 4*lane+3 (int8 x 4 each)
   uint32_t sc;    // the group's fp16 scale
+};
+template <> struct GroupRegs<kFmtD4BN> {
+  uint2 w;
+  uint4 q;
+  uint32_t sc;    // as for d = 4 with int8 tables
+  uint32_t cw;    // the lane's block codes of this col-block, row r in bits [4r, 4r+4)
+  uint32_t lev;   // block-scale level lane & 15 (fp16)
+};
+template <> struct GroupRegs<kFmtK256I8BN> {
+  uint4 w;
+  uint2 q;
+  uint32_t sc;    // as for k = 256 with int8 tables
+  uint32_t cw, lev;
 };
 template <> struct GroupRegs<kFmtD4F16> {
   uint2 w;
@@ -138,18 +151,28 @@ __device__ __forceinline__ void load_group(GroupRegs<K>& g, const uint8_t* idx, 
     g.w = *reinterpret_cast<const uint2*>(idx + ((size_t)rb * ((n_cb + 1) >> 1) + (c >> 1)) * 1024 + lane * 16 + (c & 1) * 8);
     g.q0 = *reinterpret_cast<const uint4*>(tab + gi * 2048 + lane * 32);
     g.q1 = *reinterpret_cast<const uint4*>(tab + gi * 2048 + lane * 32 + 16);
-  } else if constexpr (K == kFmtD4) {
+  } else if constexpr (K == kFmtD4 || K == kFmtD4BN) {
     const uint8_t* tab = reinterpret_cast<const uint8_t*>(cb);
     const size_t gi = (size_t)(rb / rpc) * n_cb + c, n_groups = (size_t)(n_rb / rpc) * n_cb;
     g.w = *reinterpret_cast<const uint2*>(idx + ((size_t)rb * ((n_cb + 1) >> 1) + (c >> 1)) * 1024 + lane * 16 + (c & 1) * 8);
     g.q = *reinterpret_cast<const uint4*>(tab + gi * 1024 + lane * 16);
     g.sc = reinterpret_cast<const uint16_t*>(tab + n_groups * 1024)[gi];
-  } else if constexpr (K == kFmtK256I8) {
+    if constexpr (K == kFmtD4BN) {
+      g.lev = reinterpret_cast<const uint16_t*>(tab + wide_bn_level_offset(n_groups, 1024))[gi * 16 + (lane & 15)];
+      g.cw = reinterpret_cast<const uint32_t*>(tab + wide_bn_code_offset(n_groups, 1024))
+                 [((size_t)rb * ((n_cb + 1) >> 1) + (c >> 1)) * 16 + 2 * (lane >> 3) + (c & 1)];
+    }
+  } else if constexpr (K == kFmtK256I8 || K == kFmtK256I8BN) {
     const uint8_t* tab = reinterpret_cast<const uint8_t*>(cb);
     const size_t gt = (size_t)(rb / rpc) * n_cb + c, n_tabs = (size_t)(n_rb / rpc) * n_cb;
     g.w = *reinterpret_cast<const uint4*>(idx + ((size_t)rb * n_cb + c) * 1024 + lane * 16);
     g.q = *reinterpret_cast<const uint2*>(tab + gt * 512 + lane * 8);
     g.sc = reinterpret_cast<const uint16_t*>(tab + n_tabs * 512)[gt];
+    if constexpr (K == kFmtK256I8BN) {
+      g.lev = reinterpret_cast<const uint16_t*>(tab + wide_bn_level_offset(n_tabs, 512))[gt * 16 + (lane & 15)];
+      g.cw = reinterpret_cast<const uint32_t*>(tab + wide_bn_code_offset(n_tabs, 512))
+                 [((size_t)rb * ((n_cb + 1) >> 1) + (c >> 1)) * 16 + 2 * (lane >> 3) + (c & 1)];
+    }
   } else if constexpr (K == kFmtD1K16) {
     const size_t gi = (size_t)rb * n_cb + c;
     const uint8_t* cg = reinterpret_cast<const uint8_t*>(cb) + gi * 32;
@@ -189,13 +212,16 @@ __device__ __forceinline__ void load_group(GroupRegs<K>& g, const uint8_t* idx, 
   }
 }
 
+template <int K> __device__ __forceinline__ uint32_t g_level2(const GroupRegs<K>&) { return 0u; }
+template <> __device__ __forceinline__ uint32_t g_level2<kFmtD4BN>(const GroupRegs<kFmtD4BN>& g) { return g.lev * 0x10001u; }
+
 // Decodes one group into rows [m0, m0+8) of the W tile (lane L owns columns 4L..4L+3).
 template <int K>
 __device__ __forceinline__ void decode_group(const GroupRegs<K>& g, uint32_t* lut, uint16_t* Wt,
                                              int m0, int lane) {
   const char* lutb = reinterpret_cast<const char*>(lut);
   uint32_t v[16];
-  if constexpr (K == kFmtD4 || K == kFmtD4F16) {
+  if constexpr (K == kFmtD4 || K == kFmtD4F16 || K == kFmtD4BN) {
     uint2* lut2 = reinterpret_cast<uint2*>(lut);
     if constexpr (K == kFmtD4F16) {
       *reinterpret_cast<uint4*>(lut2 + 4 * lane) = g.q0;
@@ -207,12 +233,21 @@ __device__ __forceinline__ void decode_group(const GroupRegs<K>& g, uint32_t* lu
       lut2[4 * lane + 2] = d4_dequant_entry(g.q.z, scale);
       lut2[4 * lane + 3] = d4_dequant_entry(g.q.w, scale);
     }
+    // d = 4 with block scales: the table fills the wave's whole region, so the 16 levels stay in
+    // registers (lane L holds level L & 15, the value in both halves) and a lane fetches the one
+    // its code selects with a cross-lane read.
+    const uint32_t lev2 = K == kFmtD4BN ? g_level2(g) : 0u;
     wave_lds_sync();
 #pragma unroll
     for (int r = 0; r < 8; ++r) {
       const uint2 t = lut2[((r < 4 ? g.w.x : g.w.y) >> (8 * (r & 3))) & 0xffu];
       v[2 * r] = t.x;
       v[2 * r + 1] = t.y;
+      if constexpr (K == kFmtD4BN) {     // times the block scale of the lane's 32-weight block
+        const uint32_t sc = (uint32_t)__builtin_amdgcn_ds_bpermute((int)(((g.cw >> (4 * r)) & 15u) << 2), (int)lev2);
+        v[2 * r] = scale_pair(t.x, sc);
+        v[2 * r + 1] = scale_pair(t.y, sc);
+      }
     }
   } else if constexpr (K == 64 || K == kFmtK64BN || K == kFmtD1K8 || K == kFmtD1K8BN) {
     lut[lane] = k64_dequant_pair(g.two, __builtin_bit_cast(_Float16, (uint16_t)g.sc));
@@ -286,11 +321,14 @@ __device__ __forceinline__ void decode_group(const GroupRegs<K>& g, uint32_t* lu
     const auto& q = g;
     if constexpr (K == kFmtD1K16) {
       *reinterpret_cast<uint4*>(lut + lane * 4) = d1_pair_entries(q.clo, q.chi);
-    } else if constexpr (K == kFmtK256I8) {
+    } else if constexpr (K == kFmtK256I8 || K == kFmtK256I8BN) {
       const _Float16 scale = __builtin_bit_cast(_Float16, (uint16_t)q.sc);
       *reinterpret_cast<uint4*>(lut + lane * 4) =
           make_uint4(k64_dequant_pair(q.q.x, scale), k64_dequant_pair(q.q.x >> 16, scale),
                      k64_dequant_pair(q.q.y, scale), k64_dequant_pair(q.q.y >> 16, scale));
+      if constexpr (K == kFmtK256I8BN) {
+        if (lane < 16) lut[256 + lane] = q.lev * 0x10001u;
+      }
     } else {
       *reinterpret_cast<uint4*>(lut + lane * 4) = q.cbv;
     }
@@ -298,6 +336,14 @@ __device__ __forceinline__ void decode_group(const GroupRegs<K>& g, uint32_t* lu
     const uint32_t ws[4] = {q.w.x, q.w.y, q.w.z, q.w.w};
 #pragma unroll
     for (int i = 0; i < 16; ++i) v[i] = lut[(ws[i >> 2] >> (8 * (i & 3))) & 0xffu];
+    if constexpr (K == kFmtK256I8BN) {
+#pragma unroll
+      for (int r = 0; r < 8; ++r) {
+        const uint32_t sc = lut[256 + ((q.cw >> (4 * r)) & 15u)];
+        v[2 * r] = scale_pair(v[2 * r], sc);
+        v[2 * r + 1] = scale_pair(v[2 * r + 1], sc);
+      }
+    }
   }
 #pragma unroll
   for (int r = 0; r < 8; ++r)
@@ -829,7 +875,7 @@ hipError_t launch_wide(const vq_desc& d, const void* idx_dev, const void* cb_dev
   // the 512-column tile needs 128 accumulator registers per wave: most formats fit the 256
   // registers or spill up to four of them; the block-normalised ones would spill seven to ten and
   // keep 256 columns
-  if constexpr (K == kFmtK64BN || K == kFmtK16BN || K == kFmtD1K8BN) {
+  if constexpr (K == kFmtK64BN || K == kFmtK16BN || K == kFmtD1K8BN || K == kFmtD4BN || K == kFmtK256I8BN) {
     return launch_one<K, 2, 256, 2>(d, idx_dev, cb_dev, X, B, ldx, Y, ldy, y_f32, s);
   } else {
   const int n_rb = d.out_features / kGroupRows;
@@ -909,6 +955,8 @@ hipError_t launch_gemm(const vq_desc& d, const void* idx_dev, const void* cb_dev
   if (fmt == kFmtK64BN) VQ_GEMM_DISPATCH(kFmtK64BN)
   if (fmt == kFmtD4) VQ_GEMM_DISPATCH(kFmtD4)
   if (fmt == kFmtD4F16) VQ_GEMM_DISPATCH(kFmtD4F16)
+  if (fmt == kFmtD4BN) VQ_GEMM_DISPATCH(kFmtD4BN)
+  if (fmt == kFmtK256I8BN) VQ_GEMM_DISPATCH(kFmtK256I8BN)
   if (fmt == kFmtD1K8) VQ_GEMM_DISPATCH(kFmtD1K8)
   if (fmt == kFmtD1K8BN) VQ_GEMM_DISPATCH(kFmtD1K8BN)
   if (fmt == kFmtD1K4) VQ_GEMM_DISPATCH(kFmtD1K4)

@@ -26,10 +26,12 @@ constexpr int kFmtD1K4 = 2004;     // d = 1, k = 4 (2-bit indices), int8 values 
 constexpr int kFmtD4 = 4256;      // d = 4, k = 256 (one index byte per 4 weights), int8 tables + scale,
                                   // groups of 64, 128 or 256 rows x 256 columns
 constexpr int kFmtD4F16 = 4257;   // the same with fp16 tables (2 KB per group, no scale)
+constexpr int kFmtD4BN = 4258;    // d = 4 with int8 tables + scale and blockwise normalisation (blocks of 32)
+constexpr int kFmtK256I8BN = 1257;   // d = 2, k = 256 with int8 tables + scale and blockwise normalisation
 inline int format_tag(const vq_desc& d) {
   if (d.d == 1) return d.k == 8 ? (d.codebook_dtype == VQ_I8_BN ? kFmtD1K8BN : kFmtD1K8) : d.k == 4 ? kFmtD1K4 : kFmtD1K16;
-  if (d.d == 4) return d.codebook_dtype == VQ_F16 ? kFmtD4F16 : kFmtD4;
-  if (d.codebook_dtype == VQ_I8_BN) return d.k == 16 ? kFmtK16BN : kFmtK64BN;
+  if (d.d == 4) return d.codebook_dtype == VQ_F16 ? kFmtD4F16 : d.codebook_dtype == VQ_I8_BN ? kFmtD4BN : kFmtD4;
+  if (d.codebook_dtype == VQ_I8_BN) return d.k == 16 ? kFmtK16BN : d.k == 256 ? kFmtK256I8BN : kFmtK64BN;
   if (d.k == 16 && d.codebook_dtype == VQ_I8) return kFmtK16I8;
   if (d.k == 256 && d.codebook_dtype == VQ_I8) return kFmtK256I8;
   return d.k;
@@ -40,6 +42,17 @@ inline int format_tag(const vq_desc& d) {
 __host__ __device__ constexpr size_t k16bn_level_offset(size_t n_slots) { return (34 * n_slots + 15) / 16 * 16; }
 __host__ __device__ constexpr size_t k16bn_code_offset(size_t n_slots) { return k16bn_level_offset(n_slots) + 32 * n_slots; }
 __host__ __device__ constexpr size_t k16bn_table_bytes(size_t n_slots) { return k16bn_code_offset(n_slots) + 32 * n_slots; }
+// The formats whose tables are shared by 64 or more rows (d = 4, and d = 2 with k = 256 and int8
+// tables), with blockwise normalisation: the table buffer is the canonical one up to and including
+// the levels (tables of tab_bytes each, scales padded to 16 bytes, 32 bytes of levels per group);
+// then 64 bytes of block codes per (8-row block, pair of col-blocks): dword 2b + e holds the codes
+// of block b (lanes 8b .. 8b+7) of the pair's col-block e, row r in bits [4r, 4r+4).
+__host__ __device__ constexpr size_t wide_bn_level_offset(size_t n_groups, size_t tab_bytes) {
+  return n_groups * tab_bytes + (2 * n_groups + 15) / 16 * 16;
+}
+__host__ __device__ constexpr size_t wide_bn_code_offset(size_t n_groups, size_t tab_bytes) {
+  return wide_bn_level_offset(n_groups, tab_bytes) + 32 * n_groups;
+}
 constexpr int kStreamMaxColBlocks = 96;   // widest x the streaming kernel stages in LDS (48 KB)
 
 // One matrix-vector product as the kernels see it (lives in the kernel arguments).
@@ -120,10 +133,11 @@ int gemv_stream_resident_wgs(int fmt, int max_n_cb);
 int gemv_chunk_units(int fmt);
 // d = 4, and d = 2 with k = 256 and int8 tables: GEMV kernels of their own (a workgroup of 8 waves
 // owns 64 rows and shares the group's dequantised table; see vq_gemv_d4.hip).
-hipError_t launch_gemv_d4(const GemvBatch& batch, int total_wgs, hipStream_t s, bool f16_tables = false);
-hipError_t launch_gemv_k256i8(const GemvBatch& batch, int total_wgs, hipStream_t s);
-hipError_t launch_gemv_d4_lora(const GemvBatchLora& batch, int total_wgs, hipStream_t s, bool f16_tables = false);
-hipError_t launch_gemv_k256i8_lora(const GemvBatchLora& batch, int total_wgs, hipStream_t s);
+// fmt: kFmtD4, kFmtD4F16 or kFmtD4BN; kFmtK256I8 or kFmtK256I8BN.
+hipError_t launch_gemv_d4(const GemvBatch& batch, int total_wgs, hipStream_t s, int fmt);
+hipError_t launch_gemv_k256i8(const GemvBatch& batch, int total_wgs, hipStream_t s, int fmt);
+hipError_t launch_gemv_d4_lora(const GemvBatchLora& batch, int total_wgs, hipStream_t s, int fmt);
+hipError_t launch_gemv_k256i8_lora(const GemvBatchLora& batch, int total_wgs, hipStream_t s, int fmt);
 hipError_t launch_gemm(const vq_desc& d, const void* idx_dev, const void* cb_dev,
                        const void* X, int B, int ldx, void* Y, int ldy, int y_f32,
                        hipStream_t s);

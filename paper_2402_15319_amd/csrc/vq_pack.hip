@@ -134,6 +134,31 @@ __global__ __launch_bounds__(256) void pack_bn16_kernel(const uint32_t* __restri
   code_dev[(slot >> 1) * 16 + 2 * j + (c & 1)] = w;
 }
 
+// Block codes of the formats with tall groups (d = 4; d = 2 with k = 256 and int8 tables): the
+// same 64 bytes per (8-row block, pair of col-blocks) as above.  One thread per (8-row block,
+// col-block slot, block j < 8); the slot of an absent last col-block gets zeros.
+__global__ __launch_bounds__(256) void pack_codes_pair_kernel(const uint8_t* __restrict__ code_canon,
+                                                              uint32_t* __restrict__ code_dev, int n_cb,
+                                                              long long n_slots) {
+  const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (t >= n_slots * 8) return;
+  const int slots_per_rb = 2 * k16_pairs(n_cb);
+  const long long slot = t >> 3;
+  const int j = (int)(t & 7);
+  const long long rb = slot / slots_per_rb;
+  const int c = (int)(slot - rb * slots_per_rb);
+  uint32_t w = 0;
+  if (c < n_cb) {
+    const int blk = c * 8 + j;
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+      const uint32_t byte = code_canon[(size_t)(rb * 8 + r) * (4 * n_cb) + (blk >> 1)];
+      w |= ((blk & 1) ? byte >> 4 : byte & 15u) << (4 * r);
+    }
+  }
+  code_dev[(slot >> 1) * 16 + 2 * j + (c & 1)] = w;
+}
+
 // d = 1, k = 4: per (8-row block, col-block slot) 48 bytes: the 4 int8 values of each of the 8
 // rows, then the 8 rows' fp16 scales (zero for the pad slot).  Canonical group of row R and
 // col-block c: R * n_cb + c.  One thread per (slot, row).
@@ -345,11 +370,19 @@ hipError_t launch_pack(const vq_desc& d, const void* idx_canon, const void* cb_c
                        (const uint8_t*)idx_canon, (uint8_t*)idx_dev, n_cb, n_rb, rpc);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    // int8 tables (a multiple of 16 bytes), then the scales; or fp16 tables alone: copied as they are
-    const long long src_bytes = d.codebook_dtype == VQ_F16 ? n_groups * 2048 : n_groups * 1024 + 2 * n_groups;
+    // int8 tables (a multiple of 16 bytes), then the scales; or fp16 tables alone: copied as they are.
+    // Blockwise normalisation: the padded scales and the levels are copied too, the codes are regrouped.
+    const bool bn = d.codebook_dtype == VQ_I8_BN;
+    const long long src_bytes = d.codebook_dtype == VQ_F16 ? n_groups * 2048
+                                : bn ? (long long)wide_bn_code_offset((size_t)n_groups, 1024) : n_groups * 1024 + 2 * n_groups;
     const long long n16 = (src_bytes + 15) / 16;
     hipLaunchKernelGGL(copy16_kernel, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, s,
                        (const uint8_t*)cb_canon, (uint8_t*)cb_dev, n16, src_bytes);
+    e = hipGetLastError();
+    if (e != hipSuccess || !bn) return e;
+    const long long n_slots = n_rb * 2 * n_pairs;
+    hipLaunchKernelGGL(pack_codes_pair_kernel, dim3((unsigned)((n_slots * 8 + 255) / 256)), dim3(256), 0, s,
+                       (const uint8_t*)cb_canon + src_bytes, (uint32_t*)((uint8_t*)cb_dev + src_bytes), n_cb, n_slots);
     return hipGetLastError();
   }
   if (d.k == 64 || (d.d == 1 && d.k == 8)) {   // 6-bit fields: k = 64, or two 3-bit indices of d = 1
@@ -392,7 +425,7 @@ hipError_t launch_pack(const vq_desc& d, const void* idx_canon, const void* cb_c
     return hipGetLastError();
   }
   const int fmt = format_tag(d);
-  if (fmt == kFmtK256I8) {   // indices as for k = 256, gathered from groups of rpc 8-row blocks; tables copied
+  if (fmt == kFmtK256I8 || fmt == kFmtK256I8BN) {   // indices as for k = 256, gathered from groups of rpc 8-row blocks; tables copied
     const int rpc = d.group_rows / kGroupRows;
     const long long n_slots = n_rb * n_cb;
     const long long n_groups = (long long)(d.out_features / d.group_rows) * n_cb;
@@ -400,10 +433,17 @@ hipError_t launch_pack(const vq_desc& d, const void* idx_canon, const void* cb_c
                        (const uint8_t*)idx_canon, (uint8_t*)idx_dev, n_cb, n_slots, 0, rpc);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    const long long src_bytes = n_groups * 512 + 2 * n_groups;       // tables (a multiple of 16), then scales
+    // tables (a multiple of 16), then scales; blockwise normalisation: + padding and levels, codes regrouped
+    const bool bn = fmt == kFmtK256I8BN;
+    const long long src_bytes = bn ? (long long)wide_bn_code_offset((size_t)n_groups, 512) : n_groups * 512 + 2 * n_groups;
     const long long n16 = (src_bytes + 15) / 16;
     hipLaunchKernelGGL(copy16_kernel, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, s,
                        (const uint8_t*)cb_canon, (uint8_t*)cb_dev, n16, src_bytes);
+    e = hipGetLastError();
+    if (e != hipSuccess || !bn) return e;
+    const long long n_code_slots = n_rb * 2 * k16_pairs(n_cb);
+    hipLaunchKernelGGL(pack_codes_pair_kernel, dim3((unsigned)((n_code_slots * 8 + 255) / 256)), dim3(256), 0, s,
+                       (const uint8_t*)cb_canon + src_bytes, (uint32_t*)((uint8_t*)cb_dev + src_bytes), n_cb, n_code_slots);
     return hipGetLastError();
   }
   const int slots_per_rb = (fmt == 16 || fmt == kFmtK16I8 || fmt == kFmtK16BN || fmt == kFmtD1K4) ? 2 * k16_pairs(n_cb) : n_cb;

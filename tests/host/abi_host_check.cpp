@@ -61,6 +61,8 @@ std::vector<vq_desc> supported(int out_mult, int n_cb) {
   v.push_back(make(8 * out_mult, in, 1, 1, 4, 2, VQ_I8));
   for (int gr : {64, 128, 256}) v.push_back(make(gr * out_mult, in, gr, 4, 256, 8, VQ_I8));
   for (int gr : {64, 128, 256}) v.push_back(make(gr * out_mult, in, gr, 4, 256, 8, VQ_F16));
+  for (int gr : {64, 128, 256}) v.push_back(make(gr * out_mult, in, gr, 4, 256, 8, VQ_I8_BN));
+  for (int gr : {64, 128, 256}) v.push_back(make(gr * out_mult, in, gr, 2, 256, 8, VQ_I8_BN));
   return v;
 }
 
@@ -117,7 +119,7 @@ int main(int argc, char** argv) {
 
   // ---- several matrices per launch, with and without adapters: random mixes of shapes
   for (int trial = 0; trial < 400; ++trial) {
-    const int fmt_pick = rnd() % 12;
+    const int fmt_pick = rnd() % 14;
     const int count = 1 + rnd() % (trial % 7 == 0 ? 600 : 12);
     std::vector<vq_desc> descs;
     std::vector<const void*> idxs, cbs, xs;
@@ -139,6 +141,8 @@ int main(int argc, char** argv) {
         case 8: d = make(256 * m, 256 * n_cb, pick({64, 128, 256}), 4, 256, 8, VQ_I8); break;
         case 9: d = make(8 * m, 256 * n_cb, 8, 2, 16, 4, VQ_I8_BN); break;
         case 10: d = make(32 * m, 256 * n_cb, pick({8, 16, 32}), 1, 8, 3, VQ_I8_BN); break;
+        case 11: d = make(256 * m, 256 * n_cb, pick({64, 128, 256}), 4, 256, 8, VQ_I8_BN); break;
+        case 12: d = make(256 * m, 256 * n_cb, pick({64, 128, 256}), 2, 256, 8, VQ_I8_BN); break;
         default: d = make(256 * m, 256 * n_cb, pick({64, 128, 256}), 2, 256, 8, VQ_I8); break;
       }
       descs.push_back(d);

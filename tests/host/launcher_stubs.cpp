@@ -111,7 +111,8 @@ hipError_t launch_gemv(int fmt, const GemvBatch& batch, int mode, int grid_wgs, 
 hipError_t launch_gemv_lora(int fmt, const GemvBatchLora& batch, int mode, int grid_wgs, int max_n_cb, hipStream_t,
                             int wpw) {
   check_gemv(fmt, batch.base, mode, grid_wgs, max_n_cb, wpw);
-  REQUIRE(fmt != kFmtD4 && fmt != kFmtK256I8, "split-K / streaming launch for format %d", fmt);
+  REQUIRE(fmt != kFmtD4 && fmt != kFmtD4F16 && fmt != kFmtD4BN && fmt != kFmtK256I8 && fmt != kFmtK256I8BN,
+          "split-K / streaming launch for format %d", fmt);
   check_adapters(batch);
   return hipSuccess;
 }
@@ -134,7 +135,7 @@ hipError_t launch_lora_down(const LoraDownBatch& b, hipStream_t) {
 }
 size_t gemv_stream_lds_bytes(int, int max_n_cb) { return 8 * 2048 + (size_t)(max_n_cb + 8) * 512; }
 int gemv_chunk_units(int fmt) { return chunk_units(fmt); }
-hipError_t launch_gemv_d4(const GemvBatch& b, int total_wgs, hipStream_t, bool) {
+static hipError_t check_wide(const GemvBatch& b, int total_wgs) {
   ++g_launches;
   long long wgs = 0;
   for (int i = 0; i < b.count; ++i) {
@@ -146,13 +147,21 @@ hipError_t launch_gemv_d4(const GemvBatch& b, int total_wgs, hipStream_t, bool) 
   REQUIRE(total_wgs == wgs && b.total_wgs == wgs, "total_wgs %d", total_wgs);
   return hipSuccess;
 }
-hipError_t launch_gemv_k256i8(const GemvBatch& b, int total_wgs, hipStream_t s) { return launch_gemv_d4(b, total_wgs, s, false); }
-hipError_t launch_gemv_d4_lora(const GemvBatchLora& b, int total_wgs, hipStream_t s, bool f16_tables) {
-  check_adapters(b);
-  return launch_gemv_d4(b.base, total_wgs, s, f16_tables);
+hipError_t launch_gemv_d4(const GemvBatch& b, int total_wgs, hipStream_t, int fmt) {
+  REQUIRE(fmt == kFmtD4 || fmt == kFmtD4F16 || fmt == kFmtD4BN, "d = 4 launch for format %d", fmt);
+  return check_wide(b, total_wgs);
 }
-hipError_t launch_gemv_k256i8_lora(const GemvBatchLora& b, int total_wgs, hipStream_t s) {
-  return launch_gemv_d4_lora(b, total_wgs, s, false);
+hipError_t launch_gemv_k256i8(const GemvBatch& b, int total_wgs, hipStream_t, int fmt) {
+  REQUIRE(fmt == kFmtK256I8 || fmt == kFmtK256I8BN, "k = 256 int8-table launch for format %d", fmt);
+  return check_wide(b, total_wgs);
+}
+hipError_t launch_gemv_d4_lora(const GemvBatchLora& b, int total_wgs, hipStream_t s, int fmt) {
+  check_adapters(b);
+  return launch_gemv_d4(b.base, total_wgs, s, fmt);
+}
+hipError_t launch_gemv_k256i8_lora(const GemvBatchLora& b, int total_wgs, hipStream_t s, int fmt) {
+  check_adapters(b);
+  return launch_gemv_k256i8(b.base, total_wgs, s, fmt);
 }
 hipError_t launch_gemm(const vq_desc& d, const void* a, const void* b, const void* X, int B, int ldx, void* Y, int ldy,
                        int y_f32, hipStream_t) {

@@ -81,7 +81,7 @@ A = 0x1000  # a fake, 16-byte aligned, non-NULL address; validation fails before
     (dict(d=4), -3),                                                      # d = 4 needs k = 256, int8 tables
     (dict(d=4, k=256, index_bits=8, codebook_dtype=3), -3),               # ... and groups of 64, 128 or 256 rows
     (dict(d=4, k=256, index_bits=8, group_rows=32), -3),                  # fp16 tables: the same group heights
-    (dict(d=4, k=256, index_bits=8, group_rows=256, codebook_dtype=4), -3),   # no blockwise normalisation for d = 4
+    (dict(d=4, k=256, index_bits=8, group_rows=16, codebook_dtype=4), -3),    # block-normalised: the same group heights
     (dict(d=1, k=256, index_bits=8), -3),                                 # scalar codebooks: k = 16 only
     (dict(d=1, codebook_dtype=3), -3),                                    # ... with fp16 values
     (dict(d=1, k=8, index_bits=3), -3),                                   # 3-bit scalar codebooks: int8 values
@@ -95,7 +95,8 @@ A = 0x1000  # a fake, 16-byte aligned, non-NULL address; validation fails before
     (dict(k=64, index_bits=6), -3),                                       # k = 64 needs int8 tables
     (dict(k=256, index_bits=8, codebook_dtype=3), -3),                    # k = 256 with int8 tables: groups of 64, 128 or 256 rows
     (dict(k=256, index_bits=8, codebook_dtype=3, group_rows=32), -3),
-    (dict(k=256, index_bits=8, codebook_dtype=4, group_rows=128), -3),    # blockwise normalisation: k = 64 and k = 16 only
+    (dict(k=256, index_bits=8, codebook_dtype=4, group_rows=8), -3),      # block-normalised k = 256: tall groups only
+    (dict(d=1, codebook_dtype=4), -3),                                    # no blockwise normalisation on fp16 scalar codebooks
     (dict(codebook_dtype=3, group_rows=32), -3),                          # k = 16 int8: 8-row groups
     (dict(k=64, index_bits=6, codebook_dtype=3, group_rows=24), -3),
     (dict(k=64, index_bits=6, codebook_dtype=3, group_rows=32, out_features=4112), -3),
@@ -270,10 +271,22 @@ def test_block_normalised_representation_sizes_and_validation():
         assert vq.vq_layout_bytes(d) == ((out_f // 8) * quads * 3072, (out_f // rows) * quads * 176 + (out_f // 8) * quads * 128)
         assert L.vq_gemv(ctypes.byref(d), A, A, A + 2, A + 16, vq.VQ_F16, 0) == -4
     # the other representations do not take block scales
-    for bad in (vq.make_desc(4096, 4096, 256, 8, group_rows=128, codebook_dtype=vq.VQ_I8_BN),
+    # the formats with tall groups (d = 4; d = 2 with k = 256): the canonical buffer up to the levels, then
+    # 64 bytes of codes per (8-row block, pair of col-blocks)
+    for out_f, in_f, rows, d, tb in ((4096, 4096, 256, 4, 1024), (4096, 11008, 256, 4, 1024), (128, 768, 64, 4, 1024),
+                                     (4096, 4096, 128, 2, 512), (4096, 11008, 128, 2, 512), (192, 1280, 64, 2, 512)):
+        dd = vq.make_desc(out_f, in_f, 256, 8, group_rows=rows, d=d, codebook_dtype=vq.VQ_I8_BN)
+        n_groups = (out_f // rows) * (in_f // 256)
+        head = n_groups * tb + (n_groups * 2 + 15) // 16 * 16 + n_groups * 32
+        assert vq.vq_canonical_bytes(dd) == (out_f * in_f // d, head + out_f * in_f // 64)
+        pairs = (in_f // 256 + 1) // 2
+        idx_dev = (out_f // 8) * pairs * 1024 if d == 4 else (out_f // 8) * (in_f // 256) * 1024
+        assert vq.vq_layout_bytes(dd) == (idx_dev, head + (out_f // 8) * pairs * 64)
+        assert L.vq_gemv(ctypes.byref(dd), A, A, A + 2, A + 16, vq.VQ_F16, 0) == -4
+    for bad in (vq.make_desc(4096, 4096, 256, 8, codebook_dtype=vq.VQ_I8_BN),
                 vq.make_desc(4096, 4096, 16, 4, d=1, codebook_dtype=vq.VQ_I8_BN),
                 vq.make_desc(4096, 4096, 4, 2, group_rows=1, d=1, codebook_dtype=vq.VQ_I8_BN),
-                vq.make_desc(4096, 4096, 256, 8, group_rows=256, d=4, codebook_dtype=vq.VQ_I8_BN),
+                vq.make_desc(4096, 4096, 256, 8, group_rows=32, d=4, codebook_dtype=vq.VQ_I8_BN),
                 vq.make_desc(4096, 4096, 16, 4, group_rows=16, codebook_dtype=vq.VQ_I8_BN)):
         assert L.vq_gemv(ctypes.byref(bad), A, A, A, A + 16, vq.VQ_F16, 0) == -3
     assert L.vq_em_assign(ctypes.byref(vq.make_desc(4096, 4096, 64, 6, codebook_dtype=vq.VQ_I8_BN)), A, A + 4, A, A, 0) == -4

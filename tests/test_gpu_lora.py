@@ -78,6 +78,7 @@ CASES = [
     (V(72, 1280, 16, 4, 8, 256, 1), 16), (V(96, 768, 8, 3, 32, 256, 1, True), 16), (V(40, 1280, 4, 2, 1, 256, 1, True), 56),
     (V(96, 768, 64, 6, 32, 256, 2, True, True), 16), (V(40, 256 * 5, 16, 4, 8, 256, 2, True, True), 24),
     (V(48, 256 * 5, 8, 3, 16, 256, 1, True, True), 24), (V(32800, 768, 8, 3, 32, 256, 1, True, True), 8),  # d = 1, k = 8, block scales
+    (V(256, 256 * 5, 256, 8, 128, 256, 4, True, True), 16), (V(128, 768, 256, 8, 64, 256, 2, True, True), 40),  # tall groups, block scales
     (V(128, 768, 256, 8, 64, 256, 4), 32),                                                            # d = 4, fp16 tables
     (V(128, 768, 256, 8, 64, 256, 4, True), 16), (V(512, 256 * 5, 256, 8, 256, 256, 4, True), 64),    # d = 4
     (V(256, 1280, 256, 8, 128, 256, 2, True), 24), (V(64, 256 * 3, 256, 8, 64, 256, 2, True), 8),      # k = 256, int8 tables

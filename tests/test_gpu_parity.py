@@ -232,7 +232,8 @@ PASS_FORMATS = {
     "k256_i8": workloads.LLAMA7B_LAYER_K256_I8, "d4": workloads.LLAMA7B_LAYER_D4, "d1_k16": workloads.LLAMA7B_LAYER_D1_K16,
     "d1_k8": workloads.LLAMA7B_LAYER_D1_K8, "d1_k4": workloads.LLAMA7B_LAYER_D1_K4,
     "k64_bn": workloads.LLAMA7B_LAYER_K64_BN, "k16_bn": workloads.LLAMA7B_LAYER_K16_BN,
-    "d1_k8_bn": workloads.LLAMA7B_LAYER_D1_K8_BN,
+    "d1_k8_bn": workloads.LLAMA7B_LAYER_D1_K8_BN, "k256_bn": workloads.LLAMA7B_LAYER_K256_BN,
+    "d4_bn": workloads.LLAMA7B_LAYER_D4_BN,
 }
 
 
@@ -1282,6 +1283,71 @@ def test_block_norm_d1k8_full_size(env):
     _assert_tiles_match(_gpu_gemm(env, desc, idx_d, cb_d, X, False), _dense_product(W, X))
 
 
+# ---------------------------------------------------------------- blockwise normalisation on the formats with tall groups
+def _shape_bnw(o, i, rows, d):
+    """d = 4, or d = 2 with k = 256 and int8 tables, with block scales (groups of 64, 128 or 256 rows)."""
+    return workloads.VQShape(o, i, 256, 8, rows, 256, d, True, True)
+
+
+# even and odd col-block counts (an absent second col-block of the last pair), the three group
+# heights, one and several 64-row workgroups per group row
+BNW_SMALL = [_shape_bnw(64, 256, 64, 4), _shape_bnw(128, 768, 64, 4), _shape_bnw(256, 1280, 256, 4),
+             _shape_bnw(384, 1024, 128, 4), _shape_bnw(512, 2816, 256, 4),
+             _shape_bnw(128, 256, 128, 2), _shape_bnw(256, 768, 128, 2), _shape_bnw(192, 1280, 64, 2),
+             _shape_bnw(512, 512, 256, 2), _shape_bnw(64, 11008, 64, 2)]
+
+
+@pytest.mark.parametrize("s", BNW_SMALL, ids=str)
+def test_block_norm_tall_groups_decode_bit_exact(env, s):
+    desc, W, idx_d, cb_d = _setup_bn(env, s, 730)
+    np.testing.assert_array_equal(_gpu_decode(env, desc, idx_d, cb_d), W)
+
+
+@pytest.mark.parametrize("f32", [False, True], ids=["y16", "y32"])
+@pytest.mark.parametrize("s", BNW_SMALL, ids=str)
+def test_block_norm_tall_groups_gemv(env, s, f32):
+    desc, W, idx_d, cb_d = _setup_bn(env, s, 731)
+    x = workloads.make_x(s.in_features, 731)
+    y = _gpu_gemv(env, desc, idx_d, cb_d, x, f32)
+    ref = _dense_product(W, x)
+    assert oracle.normwise_rel_err(y, ref) <= (TOL_F32 if f32 else TOL_F16)
+    _assert_rows_match(y, ref, f32, str(s))
+
+
+@pytest.mark.parametrize("B", [1, 16, 40, 130, 600, 1300])
+@pytest.mark.parametrize("s", [_shape_bnw(128, 768, 64, 4), _shape_bnw(768, 512, 128, 4),
+                               _shape_bnw(128, 768, 128, 2), _shape_bnw(768, 512, 64, 2)], ids=str)
+def test_block_norm_tall_groups_gemm(env, s, B):
+    desc, W, idx_d, cb_d = _setup_bn(env, s, 732)
+    X = workloads.make_X(s.in_features, B, 732)
+    Y = _gpu_gemm(env, desc, idx_d, cb_d, X, False, pad=8 if B == 40 else 0)
+    assert oracle.normwise_rel_err(Y, _dense_product(W, X)) <= TOL_F16
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("key", ["mlp_down_4096x11008_d4_bn", "mlp_down_4096x11008_k256_bn"])
+def test_block_norm_tall_groups_full_size(env, key):
+    """4096 x 11008 (43 col-blocks: the last pair has one col-block): decode in full, GEMV with both
+    output types element by element, and the whole B = 2048 product, tile by tile."""
+    s = workloads.CONFIGS[key]
+    desc, W, idx_d, cb_d = _setup_bn(env, s, 733)
+    np.testing.assert_array_equal(_gpu_decode(env, desc, idx_d, cb_d), W)
+    x = workloads.make_x(s.in_features, 733)
+    _assert_rows_match(_gpu_gemv(env, desc, idx_d, cb_d, x, False), _dense_product(W, x), False, key + " y16")
+    _assert_rows_match(_gpu_gemv(env, desc, idx_d, cb_d, x, True), _dense_product(W, x), True, key + " y32")
+    X = workloads.make_X(s.in_features, 2048, 733)
+    _assert_tiles_match(_gpu_gemm(env, desc, idx_d, cb_d, X, False), _dense_product(W, X))
+
+
+def _random_cases_bnw(seed, n):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for _ in range(n):
+        rows = int(rng.choice([64, 128, 256]))
+        cases.append(_shape_bnw(rows * int(rng.integers(1, 4)), 256 * int(rng.integers(1, 45)), rows, int(rng.choice([2, 4]))))
+    return cases
+
+
 def _random_cases_bn8(seed, n):
     rng = np.random.default_rng(seed)
     cases = []
@@ -1306,7 +1372,7 @@ def _random_cases_bn(seed, n):
     return cases
 
 
-@pytest.mark.parametrize("s", _random_cases_bn(20242, 16) + _random_cases_bn8(20243, 8), ids=str)
+@pytest.mark.parametrize("s", _random_cases_bn(20242, 16) + _random_cases_bn8(20243, 8) + _random_cases_bnw(20244, 8), ids=str)
 def test_random_shapes_block_normalised(env, s):
     """Decode (bit-exact), GEMV (fp16 and fp32 y) and the batched product on random shapes."""
     seed = 7200 + s.out_features + s.in_features + s.k

@@ -23,7 +23,7 @@ __all__ = [
     "VQShape", "CONFIGS", "LLAMA7B_LAYER", "seed_for", "canonical_sizes",
     "make_weights", "make_weights_i8", "make_x", "make_X", "llama7b_pass_shapes",
     "tables_i8_bytes", "tables_bn_bytes",
-    "LLAMA7B_LAYER_K64", "LLAMA7B_LAYER_K16_I8", "LLAMA7B_LAYER_D1_K16", "LLAMA7B_LAYER_K64_BN", "LLAMA7B_LAYER_K16_BN", "make_weights_bn", "LLAMA7B_LAYER_D4", "LLAMA7B_LAYER_D1_K8", "LLAMA7B_LAYER_D1_K8_BN", "LLAMA7B_LAYER_K256_I8", "LLAMA7B_LAYER_D1_K4",
+    "LLAMA7B_LAYER_K64", "LLAMA7B_LAYER_K16_I8", "LLAMA7B_LAYER_D1_K16", "LLAMA7B_LAYER_K64_BN", "LLAMA7B_LAYER_K16_BN", "make_weights_bn", "LLAMA7B_LAYER_D4", "LLAMA7B_LAYER_D1_K8", "LLAMA7B_LAYER_D1_K8_BN", "LLAMA7B_LAYER_K256_BN", "LLAMA7B_LAYER_D4_BN", "LLAMA7B_LAYER_K256_I8", "LLAMA7B_LAYER_D1_K4",
 ]
 
 
@@ -116,6 +116,14 @@ CONFIGS = {
     "attn_4096x4096_d1_k8_bn": VQShape(4096, 4096, 8, 3, 32, 256, 1, True, True),
     "mlp_up_11008x4096_d1_k8_bn": VQShape(11008, 4096, 8, 3, 32, 256, 1, True, True),
     "mlp_down_4096x11008_d1_k8_bn": VQShape(4096, 11008, 8, 3, 32, 256, 1, True, True),
+    # the 4.125 bpv 2D setting and the 2.125 bpv 4D setting with blockwise normalisation (+ 0.125 bpv of
+    # codes and 16 levels per group)
+    "attn_4096x4096_k256_bn": VQShape(4096, 4096, 256, 8, 128, 256, 2, True, True),
+    "mlp_up_11008x4096_k256_bn": VQShape(11008, 4096, 256, 8, 128, 256, 2, True, True),
+    "mlp_down_4096x11008_k256_bn": VQShape(4096, 11008, 256, 8, 128, 256, 2, True, True),
+    "attn_4096x4096_d4_bn": VQShape(4096, 4096, 256, 8, 256, 256, 4, True, True),
+    "mlp_up_11008x4096_d4_bn": VQShape(11008, 4096, 256, 8, 256, 256, 4, True, True),
+    "mlp_down_4096x11008_d4_bn": VQShape(4096, 11008, 256, 8, 256, 256, 4, True, True),
 }
 
 # One Llama-7B decoder layer as (name, shape key) in execution order.
@@ -135,6 +143,8 @@ LLAMA7B_LAYER_K64_BN = tuple((n, k.replace("_k16", "_k64_bn")) for n, k in LLAMA
 LLAMA7B_LAYER_K16_BN = tuple((n, k + "_bn") for n, k in LLAMA7B_LAYER)
 LLAMA7B_LAYER_D1_K8 = tuple((n, k.replace("_k16", "_d1_k8")) for n, k in LLAMA7B_LAYER)
 LLAMA7B_LAYER_D1_K8_BN = tuple((n, k.replace("_k16", "_d1_k8_bn")) for n, k in LLAMA7B_LAYER)
+LLAMA7B_LAYER_K256_BN = tuple((n, k.replace("_k16", "_k256_bn")) for n, k in LLAMA7B_LAYER)
+LLAMA7B_LAYER_D4_BN = tuple((n, k.replace("_k16", "_d4_bn")) for n, k in LLAMA7B_LAYER)
 LLAMA7B_LAYER_D1_K4 = tuple((n, k.replace("_k16", "_d1_k4")) for n, k in LLAMA7B_LAYER)
 LLAMA7B_LAYER_D4 = tuple((n, k.replace("_k16", "_d4")) for n, k in LLAMA7B_LAYER)
 LLAMA7B_LAYER_D1_K16 = tuple((n, k.replace("_k16", "_d1_k16")) for n, k in LLAMA7B_LAYER)
