@@ -976,16 +976,33 @@ inline size_t stream_lds_bytes_impl(int fmt, int max_n_cb) {
   return (size_t)kStreamWaves * 2 * lut_dwords * 4 + 16 + (size_t)(max_n_cb + kXPadColBlocks) * 512;
 }
 
+// Slot of a kernel format tag in per-format tables (the formats VQ_FMT_SWITCH knows; 256 is the default).
+constexpr int kStreamFormats = 10;
+inline int stream_format_slot(int fmt) {
+  switch (fmt) {
+    case 16: return 0;
+    case 64: return 1;
+    case kFmtK16I8: return 3;
+    case kFmtD1K16: return 4;
+    case kFmtK64BN: return 5;
+    case kFmtD1K8: return 6;
+    case kFmtD1K4: return 7;
+    case kFmtK16BN: return 8;
+    case kFmtD1K8BN: return 9;
+    default: return 2;
+  }
+}
+
 // Workgroups of the persistent kernel that fit on the current device at once.
 // Occupancy of the persistent kernel for this LDS size: a pure function of the code object
 // and the device, asked of the runtime once per (device, format, size) and cached (the one
 // piece of state the library keeps).  The slots are atomics: two threads that fill the same
 // slot at once store the same value.  The query enqueues nothing on any stream.
 template <bool LORA> int stream_resident_wgs_impl(int fmt, int max_n_cb) {
-  static std::atomic<int> cached[10][16][kStreamMaxColBlocks + 1];
+  static std::atomic<int> cached[kStreamFormats][16][kStreamMaxColBlocks + 1];
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) dev = 0;
-  const int fi = fmt == 16 ? 0 : fmt == 64 ? 1 : fmt == kFmtK16I8 ? 3 : fmt == kFmtD1K16 ? 4 : fmt == kFmtK64BN ? 5 : fmt == kFmtD1K8 ? 6 : fmt == kFmtD1K4 ? 7 : fmt == kFmtK16BN ? 8 : fmt == kFmtD1K8BN ? 9 : 2;
+  const int fi = stream_format_slot(fmt);
   int slot = cached[fi][dev][max_n_cb].load(std::memory_order_relaxed);
   if (slot == 0) {
     int per_cu = 0, cus = 0;
