@@ -322,6 +322,61 @@ def _assert_rows_match(y, ref, f32, what):
     assert bad.size == 0, (what, bad[:8], y[bad[:8]], ref[bad[:8]])
 
 
+@pytest.mark.timeout(600)
+def test_decoder_order_launch_sequence_in_a_hip_graph(env):
+    """The pass as a decoder's data dependencies allow it: per layer q/k/v in one launch, o, gate/up
+    in one launch, down; 32 layers = 128 vq_gemv_multi launches captured in one HIP graph (the
+    sequence bench.py times next to the headline).  Four distinct layers of weights and activations
+    are cycled through the 32 layers, every layer writes its own outputs (fp32), and every output
+    of every launch is compared with the oracle, element by element, on each of three replays with
+    eager work and a synchronisation between them."""
+    torch, vq, vqdev = env
+    n_sets = 4
+    sets = []
+    for k in range(n_sets):
+        x_host = {n: workloads.make_x(n, 2300 + 17 * k + n) for n in (4096, 11008)}
+        x_dev = {n: vqdev.to_device_bytes(v) for n, v in x_host.items()}
+        mats = []
+        for m, (name, key) in enumerate(workloads.LLAMA7B_LAYER):
+            s = workloads.CONFIGS[key]
+            desc, idx_d, cb_d, ref = _make_and_pack(env, s, workloads.seed_for(key, 40 + k, m))
+            mats.append((desc, idx_d, cb_d, x_dev[s.in_features], ref(x_host[s.in_features])))
+            del ref
+        sets.append(mats)
+        print(f"weight set {k} built and its oracle outputs computed", flush=True)
+    ys, seq = [], []
+    for layer in range(workloads.LLAMA7B_N_LAYERS):
+        mats = sets[layer % n_sets]
+        ys_l = [torch.empty(m[0].out_features, dtype=torch.float32, device="cuda:0") for m in mats]
+        ys.append(ys_l)
+        for sel in ((0, 1, 2), (3,), (4, 5), (6,)):
+            seq.append(vq.GemvMultiArgs([mats[i][0] for i in sel], [mats[i][1] for i in sel], [mats[i][2] for i in sel],
+                                        [mats[i][3] for i in sel], [ys_l[i] for i in sel]))
+    assert len(seq) == 128
+
+    def run_sequence():
+        for a in seq:
+            vq.vq_gemv_multi(a, y_dtype=vq.VQ_F32)
+
+    run_sequence()                       # eager once (also the first use of every kernel in the process)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        run_sequence()
+    scratch = torch.zeros(1 << 20, device="cuda:0")
+    for replay in range(3):
+        for ys_l in ys:
+            for y in ys_l:
+                y.fill_(float("nan"))
+        scratch.add_(1.0)                # eager work between the replays
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for layer, ys_l in enumerate(ys):
+            for m, y in enumerate(ys_l):
+                _assert_rows_match(y.cpu().numpy(), sets[layer % n_sets][m][4], True, (replay, layer, m))
+
+
 @pytest.mark.timeout(1200)
 def test_full_pass_k16_every_row_of_the_timed_launch(env):
     """The launch bench.py times (224 matrices, k = 16, one vq_gemv_multi call) with EVERY output
