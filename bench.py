@@ -273,6 +273,9 @@ def main():
                  "gemv_stream_kernel<64>"),
                 ("llama7b_pass_k16_int8_tables_2.125bpv_via_vq_gemv_multi", workloads.LLAMA7B_LAYER_K16_I8,
                  "gemv_stream_kernel<k16,int8>"),
+                # the same with groups of 4 x 256 weights (the appendix table's 2D row at 2.25 bpv; 2.27 with the scales)
+                ("llama7b_pass_k16_int8_tables_4row_groups_2.27bpv_via_vq_gemv_multi", workloads.LLAMA7B_LAYER_K16_I8_G4,
+                 "gemv_stream_kernel<k16,i8,4-row groups>"),
                 # the 4-bits-per-dimension 2D setting: k = 256, int8 tables shared by 128 x 256 groups (4.125 bpv)
                 ("llama7b_pass_k256_int8_tables_4.125bpv_via_vq_gemv_multi", workloads.LLAMA7B_LAYER_K256_I8,
                  "gemv_k256i8_kernel"),
@@ -353,7 +356,7 @@ def main():
                         tv = tab.view(-1, 528)
                         tv[:, 512:528] = 0
                         tv[:, 513:520:2] = 0x1C
-                    else:                               # 32 bytes per slot, then 2 bytes of scale per slot
+                    else:                               # 32 bytes per table, then 2 bytes of scale per table (4-row groups: two per slot)
                         n_slots = cbb // 34
                         tab[n_slots * 32::2] = 0
                         tab[n_slots * 32 + 1::2] = 0x1C

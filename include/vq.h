@@ -51,7 +51,8 @@
  * Implemented representations (d = 2 unless stated): VQ_F16 with 8 x 256 groups and k = 16
  * or 256; VQ_I8 with k = 64 (6-bit indices) and groups of 8, 16 or 32 rows x 256 columns
  * (32 rows: the 8,192-weight groups and 3.125 bits per value of Sec. 5.1); VQ_I8 with k = 16
- * and 8 x 256 groups (2.125 bits per value); VQ_I8 with k = 256 and groups of 64, 128 or 256
+ * and 8 x 256 groups (2.125 bits per value) or 4 x 256 groups (1,024 weights: the 2.25-bit 2D row
+ * of the appendix table; out_features a multiple of 8); VQ_I8 with k = 256 and groups of 64, 128 or 256
  * rows x 256 columns (128 rows: the 32,768-weight groups and 4.125 bits per value of the 2D
  * 4-bits-per-dimension setting); and scalar codebooks, d = 1 (the 1D rows of the
  * appendix table of VQ configurations): VQ_F16, k = 16, 4-bit indices, 8 x 256 groups, 4.125
@@ -100,7 +101,7 @@ typedef struct vq_desc {
   int32_t in_features;    /* columns of W (length of x)                             */
   int32_t group_rows;     /* rows sharing one codebook: 8 (VQ_F16); 8, 16 or 32 (k = 64, and
                              d = 1 with k = 8); 64, 128 or 256 (VQ_I8 with k = 256, d = 2 or 4);
-                             1 (d = 1 with k = 4)                                     */
+                             8 or 4 (VQ_I8 with k = 16); 1 (d = 1 with k = 4)         */
   int32_t group_cols;     /* 256 (Sec. 4: at most 256 columns per group)            */
   int32_t d;              /* VQ dimensionality: 2, 1 (scalar codebooks) or 4        */
   int32_t k;              /* centroids.  d = 2: 16 or 256 (VQ_F16), 16, 64 or 256 (VQ_I8),
@@ -236,7 +237,8 @@ VQ_API int vq_decode_dense(const vq_desc* desc, const void* idx_dev, const void*
  * Quantiser side (offline; paragraph "Codebook Initialization"): the two steps of the
  * Hessian-weighted EM that initialises the codebook of every group (desc->codebook_dtype is
  * ignored: weights and codebooks are fp32 here).  Implemented for d = 1, 2 or 4, k = 4, 8, 16,
- * 64 or 256, and groups of 1, 8, 16, 32, 64, 128 or 256 rows x 256 columns (one row: k * d <= 64),
+ * 64 or 256, and groups of 1, 4, 8, 16, 32, 64, 128 or 256 rows x 256 columns (one row: k * d <= 64;
+ * 4 rows: d = 1 or 2),
  * which covers the group shapes of every representation the decode side takes; out_features is
  * a multiple of max(group_rows, 8).
  *

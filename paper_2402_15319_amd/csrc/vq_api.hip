@@ -57,8 +57,8 @@ int check_desc(const vq_desc* d) {
   } else if (is_i8(*d)) {
     if (d->k == 64) {
       if (d->group_rows != 8 && d->group_rows != 16 && d->group_rows != 32) return VQ_ERR_UNSUPPORTED;
-    } else if (d->k == 16) {                  // with or without blockwise normalisation
-      if (d->group_rows != kGroupRows) return VQ_ERR_UNSUPPORTED;
+    } else if (d->k == 16) {                  // 8 x 256 groups, with or without blockwise normalisation; or 4 x 256 groups
+      if (d->group_rows != kGroupRows && !(d->group_rows == 4 && !is_bn(*d))) return VQ_ERR_UNSUPPORTED;
     } else if (d->k == 256) {                 // the 4-bits-per-dimension 2D setting: large groups share a table
       if (d->group_rows != 64 && d->group_rows != 128 && d->group_rows != 256) return VQ_ERR_UNSUPPORTED;
     } else {
@@ -68,7 +68,8 @@ int check_desc(const vq_desc* d) {
     if (d->k != 16 && d->k != 256) return VQ_ERR_UNSUPPORTED;
     if (d->group_rows != kGroupRows) return VQ_ERR_UNSUPPORTED;
   }
-  if (d->out_features % d->group_rows || d->in_features % kGroupCols) return VQ_ERR_UNSUPPORTED;
+  if (d->out_features % d->group_rows || d->out_features % kGroupRows || d->in_features % kGroupCols)
+    return VQ_ERR_UNSUPPORTED;
   // index arithmetic inside the kernels uses 32-bit element offsets into x / rows
   if ((long long)d->out_features * d->in_features > (1ll << 40)) return VQ_ERR_UNSUPPORTED;
   return VQ_OK;
@@ -93,7 +94,7 @@ void sizes(const vq_desc& d, size_t* idx_bytes, size_t* cb_bytes) {
 
 // Units a row-block of `n_cb` col-blocks is cut into (what the strips of the GEMV kernels count).
 int strip_units(int fmt, int n_cb) {
-  return (fmt == 16 || fmt == kFmtK16I8 || fmt == kFmtK16BN || fmt == kFmtD1K4) ? (n_cb + 1) / 2 : (fmt == 64 || fmt == kFmtK64BN || fmt == kFmtD1K8 || fmt == kFmtD1K8BN) ? (n_cb + 3) / 4 : n_cb;
+  return (fmt == 16 || fmt == kFmtK16I8 || fmt == kFmtK16BN || fmt == kFmtK16I8H || fmt == kFmtD1K4) ? (n_cb + 1) / 2 : (fmt == 64 || fmt == kFmtK64BN || fmt == kFmtD1K8 || fmt == kFmtD1K8BN) ? (n_cb + 3) / 4 : n_cb;
 }
 
 int hip_status(hipError_t e) { return e == hipSuccess ? VQ_OK : VQ_ERR_HIP; }
@@ -108,8 +109,9 @@ int check_em_desc(const vq_desc* d) {
   if ((d->d != 1 && d->d != 2 && d->d != 4) || d->group_cols != kGroupCols) return VQ_ERR_UNSUPPORTED;
   if (d->k != 4 && d->k != 8 && d->k != 16 && d->k != 64 && d->k != 256) return VQ_ERR_UNSUPPORTED;
   const int gr = d->group_rows;
-  if (gr != 1 && gr != 8 && gr != 16 && gr != 32 && gr != 64 && gr != 128 && gr != 256) return VQ_ERR_UNSUPPORTED;
+  if (gr != 1 && gr != 4 && gr != 8 && gr != 16 && gr != 32 && gr != 64 && gr != 128 && gr != 256) return VQ_ERR_UNSUPPORTED;
   if (gr == 1 && d->k * d->d > 64) return VQ_ERR_UNSUPPORTED;   // a codebook per row: small codebooks only
+  if (gr == 4 && d->d == 4) return VQ_ERR_UNSUPPORTED;          // groups of 4 rows: d = 1 or 2
   if (d->out_features % (gr > kGroupRows ? gr : kGroupRows) || d->in_features % kGroupCols) return VQ_ERR_UNSUPPORTED;
   if ((long long)d->out_features * d->in_features > (1ll << 40)) return VQ_ERR_UNSUPPORTED;
   return VQ_OK;
@@ -410,7 +412,8 @@ int vq_layout_bytes(const vq_desc* desc, size_t* idx_bytes, size_t* cb_bytes) {
   if (idx_bytes) *idx_bytes = n_rb * slots * (1024 * (size_t)desc->index_bits / 8);
   if (cb_bytes)   // k = 16 with blockwise normalisation: levels and block codes behind tables and scales
     *cb_bytes = is_bn(*desc) ? k16bn_table_bytes(n_rb * slots)
-                             : is_i8(*desc) ? n_rb * slots * 34 : n_rb * slots * (size_t)desc->k * 4;
+                : is_i8(*desc) ? n_rb * slots * (desc->group_rows == 4 ? 68 : 34)   // 4-row groups: two tables and scales per slot
+                               : n_rb * slots * (size_t)desc->k * 4;
   return VQ_OK;
 }
 

@@ -83,7 +83,7 @@ __device__ __forceinline__ void k16_split_dword(uint32_t w, uint32_t& a, uint32_
 #define VQ_SDWA_RD(R, T, B, ROW)                                                          \
   "v_add_u32_sdwa " R ", %[base], " T                                                     \
   " dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_" #B "\n"            \
-  "ds_read_b32 " R ", " R " offset:%[off]+" #ROW "*%[rs]\n"
+  "ds_read_b32 " R ", " R " offset:%[off]+" #ROW "*%[rs]+(" #ROW "/4)*%[hs]\n"
 #define VQ_MASKS(W)                                  \
   "v_and_b32 %[ta], 0x3c3c3c3c, " W "\n"             \
   "v_alignbit_b32 %[tb], " W ", " W ", 4\n"          \
@@ -91,8 +91,9 @@ __device__ __forceinline__ void k16_split_dword(uint32_t w, uint32_t& a, uint32_
 #define VQ_DOT(ACC, R, X) "v_dot2c_f32_f16 " ACC ", " R ", " X "\n"
 
 // RS: byte distance between the tables of consecutive rows (0: the 8 rows share one table;
-// 64: a 16-entry table per row, the scalar 2-bit format).
-template <int OFF, int RS = 0>
+// 64: a 16-entry table per row, the scalar 2-bit format).  HS: byte distance between the table
+// of rows 0..3 and that of rows 4..7 (64 for groups of 4 rows, else 0).
+template <int OFF, int RS = 0, int HS = 0>
 __device__ __forceinline__ void k16_group(uint32_t w0, uint32_t w1, uint32_t base, uint32_t x0,
                                           uint32_t x1, float (&acc)[8]) {
   uint32_t ta, tb, r0, r1, r2, r3, r4, r5, r6, r7, r8, r9, r10, r11;
@@ -123,7 +124,7 @@ __device__ __forceinline__ void k16_group(uint32_t w0, uint32_t w1, uint32_t bas
         [ta] "=&v"(ta), [tb] "=&v"(tb), [r0] "=&v"(r0), [r1] "=&v"(r1), [r2] "=&v"(r2),
         [r3] "=&v"(r3), [r4] "=&v"(r4), [r5] "=&v"(r5), [r6] "=&v"(r6), [r7] "=&v"(r7),
         [r8] "=&v"(r8), [r9] "=&v"(r9), [r10] "=&v"(r10), [r11] "=&v"(r11)
-      : [w0] "v"(w0), [w1] "v"(w1), [base] "s"(base), [x0] "v"(x0), [x1] "v"(x1), [off] "n"(OFF), [rs] "n"(RS)
+      : [w0] "v"(w0), [w1] "v"(w1), [base] "s"(base), [x0] "v"(x0), [x1] "v"(x1), [off] "n"(OFF), [rs] "n"(RS), [hs] "n"(HS)
       : "memory");
 }
 #undef VQ_SDWA_RD

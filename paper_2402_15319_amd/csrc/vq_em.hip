@@ -145,9 +145,10 @@ __global__ __launch_bounds__(128) void em_update_kernel(const float* __restrict_
 
 // ---- any dimensionality and group height ---------------------------------------------------
 // E-step.  One wave per (8-row block, col-block); the codebook is that of the group the block
-// lies in, or (PR: groups of one row) one codebook per row.  D values per centroid, 4 / D vectors
-// per row and lane.  Same arithmetic as em_assign_kernel: unfused binary32, sum over t in order.
-template <int K, int D, bool PR>
+// lies in (NCB = 1), one codebook per row (NCB = 8: groups of one row) or one per 4 rows (NCB = 2).
+// D values per centroid, 4 / D vectors per row and lane.  Same arithmetic as em_assign_kernel:
+// unfused binary32, sum over t in order.
+template <int K, int D, int NCB>
 __global__ __launch_bounds__(256) void em_assign_any_kernel(const float* __restrict__ W,
                                                             const float* __restrict__ hdiag,
                                                             const float* __restrict__ cb,
@@ -156,7 +157,7 @@ __global__ __launch_bounds__(256) void em_assign_any_kernel(const float* __restr
                                                             int group_rows) {
 #pragma clang fp contract(off)
   constexpr int V = 4 / D;                 // vectors per row and lane
-  constexpr int NCB = PR ? 8 : 1;          // codebooks a wave works with
+  constexpr int RPC = 8 / NCB;             // rows of the block that share a codebook
   __shared__ __attribute__((aligned(16))) float cbs_all[4][NCB * K * D];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -168,7 +169,7 @@ __global__ __launch_bounds__(256) void em_assign_any_kernel(const float* __restr
 
 #pragma unroll
   for (int q = 0; q < NCB; ++q) {
-    const long long g = PR ? (rb * 8 + q) * n_cb + c : (rb * 8 / group_rows) * n_cb + c;
+    const long long g = ((rb * 8 + q * RPC) / group_rows) * n_cb + c;
     const float* cg = cb + g * (K * D);
     for (int i = lane; i < K * D; i += 64) cbs[q * K * D + i] = cg[i];
   }
@@ -192,7 +193,7 @@ __global__ __launch_bounds__(256) void em_assign_any_kernel(const float* __restr
   for (int m = 0; m < K; ++m) {
 #pragma unroll
     for (int r = 0; r < 8; ++r) {
-      const float* cm = cbs + (PR ? r * K * D : 0) + m * D;   // the same address in every lane: broadcast reads
+      const float* cm = cbs + (r / RPC) * K * D + m * D;   // the same address in every lane: broadcast reads
 #pragma unroll
       for (int v = 0; v < V; ++v) {
         const float e0 = x[r][v * D] - cm[0];
@@ -320,34 +321,44 @@ hipError_t launch_em_assign(const vq_desc& d, const void* W, const void* hdiag, 
 #undef VQ_EM
     return hipGetLastError();
   }
-#define VQ_EM_ANY(K, D, PR)                                                                              \
-  hipLaunchKernelGGL((em_assign_any_kernel<K, D, PR>), dim3(grid), dim3(256), 0, s, (const float*)W,     \
+#define VQ_EM_ANY(K, D, NCB)                                                                             \
+  hipLaunchKernelGGL((em_assign_any_kernel<K, D, NCB>), dim3(grid), dim3(256), 0, s, (const float*)W,     \
                      (const float*)hdiag, (const float*)cb, (uint8_t*)assign, n_cb, n_blocks, in_features, \
                      d.group_rows)
   if (d.group_rows == 1) {   // a codebook per row: k * d <= 64 (checked by the caller)
     if (d.d == 1) {
-#define VQ_F(K) if constexpr (K <= 64) VQ_EM_ANY(K, 1, true)
+#define VQ_F(K) if constexpr (K <= 64) VQ_EM_ANY(K, 1, 8)
       VQ_EM_K_SWITCH(k, VQ_F)
 #undef VQ_F
     } else if (d.d == 2) {
-#define VQ_F(K) if constexpr (K <= 16) VQ_EM_ANY(K, 2, true)
+#define VQ_F(K) if constexpr (K <= 16) VQ_EM_ANY(K, 2, 8)
       VQ_EM_K_SWITCH(k, VQ_F)
 #undef VQ_F
     } else {
-#define VQ_F(K) if constexpr (K <= 16) VQ_EM_ANY(K, 4, true)
+#define VQ_F(K) if constexpr (K <= 16) VQ_EM_ANY(K, 4, 8)
+      VQ_EM_K_SWITCH(k, VQ_F)
+#undef VQ_F
+    }
+  } else if (d.group_rows == 4) {   // two codebooks per 8-row block (d = 1 or 2, checked by the caller)
+    if (d.d == 1) {
+#define VQ_F(K) VQ_EM_ANY(K, 1, 2)
+      VQ_EM_K_SWITCH(k, VQ_F)
+#undef VQ_F
+    } else {
+#define VQ_F(K) VQ_EM_ANY(K, 2, 2)
       VQ_EM_K_SWITCH(k, VQ_F)
 #undef VQ_F
     }
   } else if (d.d == 1) {
-#define VQ_F(K) VQ_EM_ANY(K, 1, false)
+#define VQ_F(K) VQ_EM_ANY(K, 1, 1)
     VQ_EM_K_SWITCH(k, VQ_F)
 #undef VQ_F
   } else if (d.d == 2) {
-#define VQ_F(K) VQ_EM_ANY(K, 2, false)
+#define VQ_F(K) VQ_EM_ANY(K, 2, 1)
     VQ_EM_K_SWITCH(k, VQ_F)
 #undef VQ_F
   } else {
-#define VQ_F(K) VQ_EM_ANY(K, 4, false)
+#define VQ_F(K) VQ_EM_ANY(K, 4, 1)
     VQ_EM_K_SWITCH(k, VQ_F)
 #undef VQ_F
   }

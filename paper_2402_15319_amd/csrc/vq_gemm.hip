@@ -42,7 +42,7 @@ __device__ __forceinline__ int wt_half_index(int m, int k) {   // k in halfs
 // scale per group, groups of 8*rpc rows), kFmtK16I8 (k = 16 with int8 tables).
 template <int K> constexpr int lut_dwords() {
   // BN: 64 centroids + 16 levels; d = 4: 256 entries of 4 halfs; scalar 2-bit: 8 rows x 16 pair entries
-  return K == kFmtK16I8 ? 16 : K == kFmtK16BN ? 32 : (K == kFmtD1K16 || K == kFmtK256I8) ? 256 : K == kFmtK256I8BN ? 272 : (K == kFmtK64BN || K == kFmtD1K8BN) ? 80 : (K == kFmtD4 || K == kFmtD4F16 || K == kFmtD4BN) ? 512 : K == kFmtD1K8 ? 64 : K == kFmtD1K4 ? 128 : K;
+  return K == kFmtK16I8 ? 16 : (K == kFmtK16BN || K == kFmtK16I8H) ? 32 : (K == kFmtD1K16 || K == kFmtK256I8) ? 256 : K == kFmtK256I8BN ? 272 : (K == kFmtK64BN || K == kFmtD1K8BN) ? 80 : (K == kFmtD4 || K == kFmtD4F16 || K == kFmtD4BN) ? 512 : K == kFmtD1K8 ? 64 : K == kFmtD1K4 ? 128 : K;
 }
 
 // What one wave needs to decode one group: the lane's index bytes and codebook piece.
@@ -113,6 +113,11 @@ template <> struct GroupRegs<kFmtK16I8> {
   uint32_t two;          // int8 pair of table entry lane & 15
   uint32_t sc;
 };
+template <> struct GroupRegs<kFmtK16I8H> {
+  uint2 w;
+  uint32_t two;          // int8 pair of entry lane & 15 of table (lane >> 4) & 1 (rows 0..3 / rows 4..7)
+  uint32_t sc;           // that table's scale
+};
 template <> struct GroupRegs<kFmtK16BN> {
   uint2 w;
   uint32_t two, sc;      // as for k = 16 with int8 tables
@@ -139,6 +144,13 @@ __device__ __forceinline__ void load_group(GroupRegs<K>& g, const uint8_t* idx, 
       g.lev = reinterpret_cast<const uint16_t*>(tabs + k16bn_level_offset(n_slots))[slot * 16 + (lane & 15)];
       g.cw = reinterpret_cast<const uint32_t*>(tabs + k16bn_code_offset(n_slots))[(slot >> 1) * 16 + 2 * (lane >> 3) + (c & 1)];
     }
+  } else if constexpr (K == kFmtK16I8H) {
+    const int slots = 2 * k16_pairs(n_cb);
+    const uint8_t* tabs = reinterpret_cast<const uint8_t*>(cb);
+    const size_t slot = (size_t)rb * slots + c;
+    g.w = *reinterpret_cast<const uint2*>(idx + (size_t)rb * slots * 512 + k16_chunk_offset(c, lane));
+    g.two = *reinterpret_cast<const uint16_t*>(tabs + slot * 64 + (lane & 31) * 2);
+    g.sc = reinterpret_cast<const uint16_t*>(tabs + (size_t)n_rb * slots * 64)[slot * 2 + ((lane >> 4) & 1)];
   } else if constexpr (K == kFmtD1K4) {
     const int slots = 2 * k16_pairs(n_cb);
     const uint8_t* rec = reinterpret_cast<const uint8_t*>(cb) + ((size_t)rb * slots + c) * kD1K4SlotTabBytes;
@@ -288,9 +300,11 @@ __device__ __forceinline__ void decode_group(const GroupRegs<K>& g, uint32_t* lu
         v[8 * h + 2 * r + 1] = *reinterpret_cast<const uint32_t*>(row_tab + ((b >> (8 * r)) & 0xffu));
       }
     }
-  } else if constexpr (K == 16 || K == kFmtK16I8 || K == kFmtK16BN) {
+  } else if constexpr (K == 16 || K == kFmtK16I8 || K == kFmtK16BN || K == kFmtK16I8H) {
     if constexpr (K == 16) {
       if (lane < 16) lut[lane] = g.cbv;
+    } else if constexpr (K == kFmtK16I8H) {
+      if (lane < 32) lut[lane] = k64_dequant_pair(g.two, __builtin_bit_cast(_Float16, (uint16_t)g.sc));
     } else {
       if (lane < 16) lut[lane] = k64_dequant_pair(g.two, __builtin_bit_cast(_Float16, (uint16_t)g.sc));
       if constexpr (K == kFmtK16BN) {
@@ -305,8 +319,9 @@ __device__ __forceinline__ void decode_group(const GroupRegs<K>& g, uint32_t* lu
       k16_split_dword(h ? q.w.y : q.w.x, a, b);
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        v[8 * h + 2 * r] = *reinterpret_cast<const uint32_t*>(lutb + ((a >> (8 * r)) & 0xffu));
-        v[8 * h + 2 * r + 1] = *reinterpret_cast<const uint32_t*>(lutb + ((b >> (8 * r)) & 0xffu));
+        const char* lut_h = lutb + (K == kFmtK16I8H ? 64 * h : 0);   // groups of 4 rows: rows 4..7 use the second table
+        v[8 * h + 2 * r] = *reinterpret_cast<const uint32_t*>(lut_h + ((a >> (8 * r)) & 0xffu));
+        v[8 * h + 2 * r + 1] = *reinterpret_cast<const uint32_t*>(lut_h + ((b >> (8 * r)) & 0xffu));
       }
     }
     if constexpr (K == kFmtK16BN) {     // times the block scale of the lane's 32-weight block, per row
@@ -954,6 +969,7 @@ hipError_t launch_gemm(const vq_desc& d, const void* idx_dev, const void* cb_dev
   if (fmt == kFmtD1K16) VQ_GEMM_DISPATCH(kFmtD1K16)
   if (fmt == kFmtK64BN) VQ_GEMM_DISPATCH(kFmtK64BN)
   if (fmt == kFmtD4) VQ_GEMM_DISPATCH(kFmtD4)
+  if (fmt == kFmtK16I8H) VQ_GEMM_DISPATCH(kFmtK16I8H)
   if (fmt == kFmtD4F16) VQ_GEMM_DISPATCH(kFmtD4F16)
   if (fmt == kFmtD4BN) VQ_GEMM_DISPATCH(kFmtD4BN)
   if (fmt == kFmtK256I8BN) VQ_GEMM_DISPATCH(kFmtK256I8BN)

@@ -52,15 +52,18 @@ template <int K> struct Chunk;
 // of 64), dequantised into the LDS table when the chunk is consumed.  MODE 2 (BN): blockwise
 // normalisation on top (16 block-scale levels per group next to the tables in LDS, a 4-bit code
 // per 32 weights); the plain C++ inner block replaces the hand-scheduled one.
+// MODE 3 (H4): int8 tables for groups of 4 rows: two tables per 8-row block and col-block (rows
+// 0..3, rows 4..7), 64 + 4 bytes per slot; the hand-scheduled block reads rows 4..7 from the second.
 template <int MODE> struct Chunk16T {
-  static constexpr bool I8 = MODE >= 1, BN = MODE == 2;
+  static constexpr bool I8 = MODE >= 1, BN = MODE == 2, H4 = MODE == 3;
   static constexpr int kUnits = 4;        // col-block pairs per chunk
-  static constexpr int kLutDwords = BN ? 256 : 128;  // 8 groups x 16 centroids (+ 8 x 16 levels)
+  static constexpr int kLutDwords = (BN || H4) ? 256 : 128;  // 8 groups x 16 centroids (+ 8 x 16 levels, or x 2 tables)
   uint4 w[4];     // slot s: the lane's 16 index bytes of pair u+s
   uint2 xa[4];    // activations of the first group of the slot
   uint2 xb[4];    // ... and of the second
   uint4 cbv;      // fp16: this lane's 16 bytes of the chunk's codebooks (lanes 0..31)
   uint32_t tab;   // int8: this lane's two centroid pairs (4 bytes of the chunk's tables)
+  uint32_t tab2;  // H4: two more (the lane holds 8 bytes of the chunk's 512 bytes of tables)
   uint32_t sc;    // int8: the fp16 scale of the group those pairs belong to
   uint2 cw[4];    // BN: the lane's block codes of the two groups of pair u+s
   uint32_t lev;   // BN: levels 2*(lane%8), +1 of group lane/8 of the chunk (two fp16)
@@ -69,7 +72,14 @@ template <int MODE> struct Chunk16T {
   // The chunk's tables: pairs u .. u+np-1 of the row-block (np may be 0: nothing is kept).
   __device__ __forceinline__ void load_tables(const Strip& S, int u, int lane, int np_) {
     const int u_ld = np_ > 0 ? u : 0;
-    if constexpr (I8) {
+    if constexpr (H4) {
+      const uint8_t* tq = reinterpret_cast<const uint8_t*>(S.cb_rb) + (size_t)u_ld * 128;
+      const uint2 t2 = zero_unless(lane * 8 < np_ * 128,
+                                   *reinterpret_cast<const uint2*>(tq + min(lane * 8, max(np_ * 128 - 8, 0))));
+      tab = t2.x;
+      tab2 = t2.y;
+      sc = S.sc_rb[u_ld * 4 + min(lane >> 2, max(4 * np_ - 1, 0))];
+    } else if constexpr (I8) {
       const uint8_t* tq = reinterpret_cast<const uint8_t*>(S.cb_rb) + (size_t)u_ld * 64;
       tab = zero_unless(lane * 4 < np_ * 64,
                         *reinterpret_cast<const uint32_t*>(tq + min(lane * 4, max(np_ * 64 - 4, 0))));
@@ -83,7 +93,12 @@ template <int MODE> struct Chunk16T {
     }
   }
   __device__ __forceinline__ void stage_tables(uint32_t* lut, int lane) const {
-    if constexpr (I8) {
+    if constexpr (H4) {
+      const _Float16 scale = __builtin_bit_cast(_Float16, (uint16_t)sc);
+      *reinterpret_cast<uint4*>(lut + lane * 4) =
+          make_uint4(k64_dequant_pair(tab, scale), k64_dequant_pair(tab >> 16, scale),
+                     k64_dequant_pair(tab2, scale), k64_dequant_pair(tab2 >> 16, scale));
+    } else if constexpr (I8) {
       const _Float16 scale = __builtin_bit_cast(_Float16, (uint16_t)sc);
       *reinterpret_cast<uint2*>(lut + lane * 2) =
           make_uint2(k64_dequant_pair(tab, scale), k64_dequant_pair(tab >> 16, scale));
@@ -124,20 +139,22 @@ template <int MODE> struct Chunk16T {
       }
       return;
     }
-    k16_group<0>(w[0].x, w[0].y, base, xa[0].x, xa[0].y, acc);
-    k16_group<64>(w[0].z, w[0].w, base, xb[0].x, xb[0].y, acc);
-    k16_group<128>(w[1].x, w[1].y, base, xa[1].x, xa[1].y, acc);
-    k16_group<192>(w[1].z, w[1].w, base, xb[1].x, xb[1].y, acc);
+    constexpr int T = H4 ? 128 : 64, HS = H4 ? 64 : 0;   // bytes of tables per group slot; rows 4..7
+    k16_group<0, 0, HS>(w[0].x, w[0].y, base, xa[0].x, xa[0].y, acc);
+    k16_group<T, 0, HS>(w[0].z, w[0].w, base, xb[0].x, xb[0].y, acc);
+    k16_group<2 * T, 0, HS>(w[1].x, w[1].y, base, xa[1].x, xa[1].y, acc);
+    k16_group<3 * T, 0, HS>(w[1].z, w[1].w, base, xb[1].x, xb[1].y, acc);
     acc_hazard_fence();       // before the branch: the compiler may copy accumulators at it
     if (np <= 2) return;      // short strips of a finely split row-block: half the work
-    k16_group<256>(w[2].x, w[2].y, base, xa[2].x, xa[2].y, acc);
-    k16_group<320>(w[2].z, w[2].w, base, xb[2].x, xb[2].y, acc);
-    k16_group<384>(w[3].x, w[3].y, base, xa[3].x, xa[3].y, acc);
-    k16_group<448>(w[3].z, w[3].w, base, xb[3].x, xb[3].y, acc);
+    k16_group<4 * T, 0, HS>(w[2].x, w[2].y, base, xa[2].x, xa[2].y, acc);
+    k16_group<5 * T, 0, HS>(w[2].z, w[2].w, base, xb[2].x, xb[2].y, acc);
+    k16_group<6 * T, 0, HS>(w[3].x, w[3].y, base, xa[3].x, xa[3].y, acc);
+    k16_group<7 * T, 0, HS>(w[3].z, w[3].w, base, xb[3].x, xb[3].y, acc);
     acc_hazard_fence();
   }
 };
 template <> struct Chunk<16> : Chunk16T<0> {};
+template <> struct Chunk<kFmtK16I8H> : Chunk16T<3> {};
 template <> struct Chunk<kFmtK16I8> : Chunk16T<1> {};
 template <> struct Chunk<kFmtK16BN> : Chunk16T<2> {};
 
@@ -316,11 +333,15 @@ __device__ __forceinline__ Strip make_strip(const GemvProblem& P, int rb, int sp
   S.sc_rb = nullptr;
   S.codes_rb = nullptr;
   S.lev_rb = nullptr;
-  if (K == 16 || K == kFmtK16I8 || K == kFmtK16BN) {
+  if (K == 16 || K == kFmtK16I8 || K == kFmtK16BN || K == kFmtK16I8H) {
     const int n_pairs = k16_pairs(n_cb);
     S.idx_rb = P.idx + (size_t)rb * n_pairs * 1024;
     if (K == 16) {
       S.cb_rb = P.cb + (size_t)rb * n_pairs * 32;
+    } else if (K == kFmtK16I8H) {   // two 32-byte tables per group slot, then all the scales (4 bytes per slot)
+      S.cb_rb = P.cb + (size_t)rb * n_pairs * 32;
+      S.sc_rb = reinterpret_cast<const uint16_t*>(P.cb + (size_t)P.n_rb * n_pairs * 32) +
+                (size_t)rb * n_pairs * 4;
     } else {   // int8 tables: 32 bytes per group slot, then all the scales (2 bytes per slot)
       S.cb_rb = P.cb + (size_t)rb * n_pairs * 16;
       S.sc_rb = reinterpret_cast<const uint16_t*>(P.cb + (size_t)P.n_rb * n_pairs * 16) +
@@ -439,11 +460,12 @@ __device__ __forceinline__ int find_problem(const GemvBatch& batch, int item) {
 template <int K> struct ChunkS;
 
 template <int MODE> struct ChunkS16T {
-  static constexpr bool I8 = MODE >= 1, BN = MODE == 2;
+  static constexpr bool I8 = MODE >= 1, BN = MODE == 2, H4 = MODE == 3;
   static constexpr int kUnits = 4;
-  static constexpr int kLutDwords = BN ? 256 : 128;
+  static constexpr int kLutDwords = (BN || H4) ? 256 : 128;
   uint4 w[4];
   uint4 cbv;       // fp16 codebooks (lanes 0..31), or
+  uint32_t tab2;   // H4: see Chunk16T
   uint32_t tab;    // two int8 centroid pairs and
   uint32_t sc;     // their group's fp16 scale
   uint2 cw[4];     // BN: see Chunk16T
@@ -454,7 +476,14 @@ template <int MODE> struct ChunkS16T {
     const int np = max(0, min(4, S.u_end - u));
     u0 = u;
     const int u_ld = np > 0 ? u : 0;
-    if constexpr (I8) {
+    if constexpr (H4) {
+      const uint8_t* tq = reinterpret_cast<const uint8_t*>(S.cb_rb) + (size_t)u_ld * 128;
+      const uint2 t2 = zero_unless(lane * 8 < np * 128,
+                                   *reinterpret_cast<const uint2*>(tq + min(lane * 8, max(np * 128 - 8, 0))));
+      tab = t2.x;
+      tab2 = t2.y;
+      sc = S.sc_rb[u_ld * 4 + min(lane >> 2, max(4 * np - 1, 0))];
+    } else if constexpr (I8) {
       const uint8_t* tq = reinterpret_cast<const uint8_t*>(S.cb_rb) + (size_t)u_ld * 64;
       tab = zero_unless(lane * 4 < np * 64,
                         *reinterpret_cast<const uint32_t*>(tq + min(lane * 4, max(np * 64 - 4, 0))));
@@ -484,7 +513,12 @@ template <int MODE> struct ChunkS16T {
   // read for block b+1 is issued before block b, so only the first one is waited for.
   __device__ __forceinline__ void consume(uint32_t* lut, uint32_t base, const uint32_t* x_s, int lane,
                                           float (&acc)[8]) const {
-    if constexpr (I8) {
+    if constexpr (H4) {
+      const _Float16 scale = __builtin_bit_cast(_Float16, (uint16_t)sc);
+      *reinterpret_cast<uint4*>(lut + lane * 4) =
+          make_uint4(k64_dequant_pair(tab, scale), k64_dequant_pair(tab >> 16, scale),
+                     k64_dequant_pair(tab2, scale), k64_dequant_pair(tab2 >> 16, scale));
+    } else if constexpr (I8) {
       const _Float16 scale = __builtin_bit_cast(_Float16, (uint16_t)sc);
       *reinterpret_cast<uint2*>(lut + lane * 2) =
           make_uint2(k64_dequant_pair(tab, scale), k64_dequant_pair(tab >> 16, scale));
@@ -514,25 +548,27 @@ template <int MODE> struct ChunkS16T {
       acc_hazard_fence();
       return;
     }
+    constexpr int T = H4 ? 128 : 64, HS = H4 ? 64 : 0;   // bytes of tables per group slot; rows 4..7
     uint2 x0 = xp[0], x1 = xp[64];
-    k16_group<0>(w[0].x, w[0].y, base, x0.x, x0.y, acc);
+    k16_group<0, 0, HS>(w[0].x, w[0].y, base, x0.x, x0.y, acc);
     x0 = xp[128];
-    k16_group<64>(w[0].z, w[0].w, base, x1.x, x1.y, acc);
+    k16_group<T, 0, HS>(w[0].z, w[0].w, base, x1.x, x1.y, acc);
     x1 = xp[192];
-    k16_group<128>(w[1].x, w[1].y, base, x0.x, x0.y, acc);
+    k16_group<2 * T, 0, HS>(w[1].x, w[1].y, base, x0.x, x0.y, acc);
     x0 = xp[256];
-    k16_group<192>(w[1].z, w[1].w, base, x1.x, x1.y, acc);
+    k16_group<3 * T, 0, HS>(w[1].z, w[1].w, base, x1.x, x1.y, acc);
     x1 = xp[320];
-    k16_group<256>(w[2].x, w[2].y, base, x0.x, x0.y, acc);
+    k16_group<4 * T, 0, HS>(w[2].x, w[2].y, base, x0.x, x0.y, acc);
     x0 = xp[384];
-    k16_group<320>(w[2].z, w[2].w, base, x1.x, x1.y, acc);
+    k16_group<5 * T, 0, HS>(w[2].z, w[2].w, base, x1.x, x1.y, acc);
     x1 = xp[448];
-    k16_group<384>(w[3].x, w[3].y, base, x0.x, x0.y, acc);
-    k16_group<448>(w[3].z, w[3].w, base, x1.x, x1.y, acc);
+    k16_group<6 * T, 0, HS>(w[3].x, w[3].y, base, x0.x, x0.y, acc);
+    k16_group<7 * T, 0, HS>(w[3].z, w[3].w, base, x1.x, x1.y, acc);
     acc_hazard_fence();
   }
 };
 template <> struct ChunkS<16> : ChunkS16T<0> {};
+template <> struct ChunkS<kFmtK16I8H> : ChunkS16T<3> {};
 template <> struct ChunkS<kFmtK16I8> : ChunkS16T<1> {};
 template <> struct ChunkS<kFmtK16BN> : ChunkS16T<2> {};
 
@@ -957,6 +993,7 @@ __global__ __launch_bounds__(64 * WPW) void gemv_split_kernel(const typename Bat
     case 16: F(16); break;                    \
     case 64: F(64); break;                    \
     case kFmtK16I8: F(kFmtK16I8); break;      \
+    case kFmtK16I8H: F(kFmtK16I8H); break;    \
     case kFmtD1K16: F(kFmtD1K16); break;      \
     case kFmtK64BN: F(kFmtK64BN); break;      \
     case kFmtK16BN: F(kFmtK16BN); break;      \
@@ -977,7 +1014,7 @@ inline size_t stream_lds_bytes_impl(int fmt, int max_n_cb) {
 }
 
 // Slot of a kernel format tag in per-format tables (the formats VQ_FMT_SWITCH knows; 256 is the default).
-constexpr int kStreamFormats = 10;
+constexpr int kStreamFormats = 11;
 inline int stream_format_slot(int fmt) {
   switch (fmt) {
     case 16: return 0;
@@ -989,6 +1026,7 @@ inline int stream_format_slot(int fmt) {
     case kFmtD1K4: return 7;
     case kFmtK16BN: return 8;
     case kFmtD1K8BN: return 9;
+    case kFmtK16I8H: return 10;
     default: return 2;
   }
 }

@@ -15,6 +15,7 @@ constexpr int kMaxProblemsPerLaunch = 256;  // the problem table travels in the 
 // 256-entry table of fp16 pairs T[j] = (c[j % 16], c[j / 16]) that the kernels build in LDS from
 // the group's 16 scalars; from there on the work is that of d = 2, k = 256.
 constexpr int kFmtK16I8 = 1016;
+constexpr int kFmtK16I8H = 1416;   // k = 16, int8 tables + scale, groups of 4 rows x 256 columns (two tables per 8-row block)
 constexpr int kFmtK256I8 = 1256;   // d = 2, k = 256, int8 tables + scale, groups of 64, 128 or 256 rows x 256 columns
 constexpr int kFmtD1K16 = 2016;
 constexpr int kFmtK64BN = 3064;   // k = 64, int8 tables + scale, blockwise normalisation (blocks of 32)
@@ -32,7 +33,7 @@ inline int format_tag(const vq_desc& d) {
   if (d.d == 1) return d.k == 8 ? (d.codebook_dtype == VQ_I8_BN ? kFmtD1K8BN : kFmtD1K8) : d.k == 4 ? kFmtD1K4 : kFmtD1K16;
   if (d.d == 4) return d.codebook_dtype == VQ_F16 ? kFmtD4F16 : d.codebook_dtype == VQ_I8_BN ? kFmtD4BN : kFmtD4;
   if (d.codebook_dtype == VQ_I8_BN) return d.k == 16 ? kFmtK16BN : d.k == 256 ? kFmtK256I8BN : kFmtK64BN;
-  if (d.k == 16 && d.codebook_dtype == VQ_I8) return kFmtK16I8;
+  if (d.k == 16 && d.codebook_dtype == VQ_I8) return d.group_rows == 4 ? kFmtK16I8H : kFmtK16I8;
   if (d.k == 256 && d.codebook_dtype == VQ_I8) return kFmtK256I8;
   return d.k;
 }
@@ -143,7 +144,8 @@ hipError_t launch_gemm(const vq_desc& d, const void* idx_dev, const void* cb_dev
                        hipStream_t s);
 
 // E- and M-step of the codebook initialisation (d in {1, 2, 4}, k in {4, 8, 16, 64, 256}, groups
-// of 1, 8, 16, 32, 64, 128 or 256 rows x 256 columns; one row only with k * d <= 64).
+// of 1, 4, 8, 16, 32, 64, 128 or 256 rows x 256 columns; one row only with k * d <= 64, 4 rows
+// only with d <= 2).
 hipError_t launch_em_assign(const vq_desc& d, const void* W, const void* hdiag, const void* cb,
                             void* assign, hipStream_t s);
 hipError_t launch_em_update(const vq_desc& d, const void* W, const void* hdiag, const void* assign,

@@ -10,8 +10,9 @@ namespace {
 // One thread per (device group slot, lane): gathers that lane's share of the group.
 // For k=16 the slots include the zero-filled pad group of row-blocks with an odd
 // number of col-blocks.
-// row_groups: the canonical groups are single rows (1 x 256, 64 bytes each, row-major), as in
-// the scalar 2-bit format, instead of 8 x 256 blocks.
+// row_groups = 1: the canonical groups are single rows (1 x 256, 64 bytes each, row-major), as in
+// the scalar 2-bit format, instead of 8 x 256 blocks; row_groups = 4: groups of 4 rows (256 bytes
+// each), two per block.
 template <int K>
 __global__ __launch_bounds__(256) void pack_idx_kernel(const uint8_t* __restrict__ canon,
                                                        uint8_t* __restrict__ dev, int n_cb,
@@ -27,15 +28,17 @@ __global__ __launch_bounds__(256) void pack_idx_kernel(const uint8_t* __restrict
     uint32_t words[2] = {0u, 0u};
     if (c < n_cb) {
       // canonical byte r*64 + lane of the block, or byte `lane` of the group of row rb*8 + r
-      const uint8_t* src = row_groups ? canon + (rb * 8 * n_cb + c) * 64 + lane
-                                      : canon + (rb * n_cb + c) * 512 + lane;
-      const size_t row_stride = row_groups ? (size_t)n_cb * 64 : 64;
+      const uint8_t* src = row_groups == 1 ? canon + (rb * 8 * n_cb + c) * 64 + lane
+                           : row_groups == 4 ? canon + (rb * 2 * n_cb + c) * 256 + lane
+                                             : canon + (rb * n_cb + c) * 512 + lane;
+      const size_t row_stride = row_groups == 1 ? (size_t)n_cb * 64 : 64;
+      const size_t half_skip = row_groups == 4 ? (size_t)(n_cb - 1) * 256 : 0;   // rows 4..7: the group below
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
         uint32_t lo[4], hi[4];
 #pragma unroll
         for (int b = 0; b < 4; ++b) {
-          const uint32_t byte = src[(4 * h + b) * row_stride];
+          const uint32_t byte = src[(4 * h + b) * row_stride + h * half_skip];
           lo[b] = byte & 15u;
           hi[b] = byte >> 4;
         }
@@ -99,6 +102,33 @@ __global__ __launch_bounds__(256) void pack_tab16_kernel(const uint32_t* __restr
     const long long rb = t / slots_per_rb;
     const int c = (int)(t - rb * slots_per_rb);
     reinterpret_cast<uint16_t*>(dev + n_slots * 8)[t] = c < n_cb ? scale_canon[rb * n_cb + c] : (uint16_t)0;
+  }
+}
+
+// k = 16 with int8 tables and groups of 4 rows: 64 bytes per group slot (the table of rows 0..3,
+// then that of rows 4..7; zero for the pad group), then two fp16 scales per slot.  Canonical
+// group of half-block (rb, half) and col-block c: (2 * rb + half) * n_cb + c.  One thread per
+// dword of tables; the first 2 * n_slots threads also copy a scale.
+__global__ __launch_bounds__(256) void pack_tab16h_kernel(const uint32_t* __restrict__ q_canon,
+                                                          const uint16_t* __restrict__ scale_canon,
+                                                          uint32_t* __restrict__ dev, int n_cb,
+                                                          long long n_slots) {
+  const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (t >= n_slots * 16) return;
+  const int slots_per_rb = 2 * k16_pairs(n_cb);
+  {
+    const long long slot = t >> 4;
+    const int half = (int)(t >> 3) & 1, piece = (int)(t & 7);
+    const long long rb = slot / slots_per_rb;
+    const int c = (int)(slot - rb * slots_per_rb);
+    dev[t] = c < n_cb ? q_canon[((2 * rb + half) * n_cb + c) * 8 + piece] : 0u;
+  }
+  if (t < n_slots * 2) {
+    const long long slot = t >> 1;
+    const int half = (int)(t & 1);
+    const long long rb = slot / slots_per_rb;
+    const int c = (int)(slot - rb * slots_per_rb);
+    reinterpret_cast<uint16_t*>(dev + n_slots * 16)[t] = c < n_cb ? scale_canon[(2 * rb + half) * n_cb + c] : (uint16_t)0;
   }
 }
 
@@ -446,7 +476,7 @@ hipError_t launch_pack(const vq_desc& d, const void* idx_canon, const void* cb_c
                        (const uint8_t*)cb_canon + src_bytes, (uint32_t*)((uint8_t*)cb_dev + src_bytes), n_cb, n_code_slots);
     return hipGetLastError();
   }
-  const int slots_per_rb = (fmt == 16 || fmt == kFmtK16I8 || fmt == kFmtK16BN || fmt == kFmtD1K4) ? 2 * k16_pairs(n_cb) : n_cb;
+  const int slots_per_rb = (fmt == 16 || fmt == kFmtK16I8 || fmt == kFmtK16BN || fmt == kFmtK16I8H || fmt == kFmtD1K4) ? 2 * k16_pairs(n_cb) : n_cb;
   const long long n_slots = n_rb * slots_per_rb;
   if (fmt == kFmtD1K4) {
     hipLaunchKernelGGL(pack_idx_kernel<16>, dim3((unsigned)((n_slots * 64 + 255) / 256)), dim3(256), 0, s,
@@ -457,6 +487,17 @@ hipError_t launch_pack(const vq_desc& d, const void* idx_canon, const void* cb_c
     hipLaunchKernelGGL(pack_tab_d1k4_kernel, dim3((unsigned)((n_slots * 8 + 255) / 256)), dim3(256), 0, s,
                        (const uint32_t*)cb_canon, (const uint16_t*)((const uint8_t*)cb_canon + q_bytes),
                        (uint8_t*)cb_dev, n_cb, n_slots);
+    return hipGetLastError();
+  }
+  if (fmt == kFmtK16I8H) {
+    hipLaunchKernelGGL(pack_idx_kernel<16>, dim3((unsigned)((n_slots * 64 + 255) / 256)), dim3(256), 0, s,
+                       (const uint8_t*)idx_canon, (uint8_t*)idx_dev, n_cb, n_slots, 4, 1);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const size_t q_bytes = ((size_t)n_rb * 2 * n_cb * 32 + 15) / 16 * 16;   // scales follow the tables
+    hipLaunchKernelGGL(pack_tab16h_kernel, dim3((unsigned)((n_slots * 16 + 255) / 256)), dim3(256), 0, s,
+                       (const uint32_t*)cb_canon, (const uint16_t*)((const uint8_t*)cb_canon + q_bytes),
+                       (uint32_t*)cb_dev, n_cb, n_slots);
     return hipGetLastError();
   }
   if (fmt == kFmtK16I8 || fmt == kFmtK16BN) {

@@ -26,11 +26,11 @@ long long g_launches = 0;
 // Units one chunk of the GEMV kernels holds: 4 col-block pairs (k = 16), 2 pairs (d = 1, k = 4),
 // one quad of col-blocks (the k = 64 layouts), 2 col-blocks (the k = 256 layouts).
 int chunk_units(int fmt) {
-  return (fmt == 16 || fmt == kFmtK16I8 || fmt == kFmtK16BN) ? 4 : (fmt == 64 || fmt == kFmtK64BN || fmt == kFmtD1K8 || fmt == kFmtD1K8BN) ? 1 : 2;
+  return (fmt == 16 || fmt == kFmtK16I8 || fmt == kFmtK16BN || fmt == kFmtK16I8H) ? 4 : (fmt == 64 || fmt == kFmtK64BN || fmt == kFmtD1K8 || fmt == kFmtD1K8BN) ? 1 : 2;
 }
 
 int strip_units(int fmt, int n_cb) {
-  return (fmt == 16 || fmt == kFmtK16I8 || fmt == kFmtK16BN || fmt == kFmtD1K4) ? (n_cb + 1) / 2
+  return (fmt == 16 || fmt == kFmtK16I8 || fmt == kFmtK16BN || fmt == kFmtK16I8H || fmt == kFmtD1K4) ? (n_cb + 1) / 2
          : (fmt == 64 || fmt == kFmtK64BN || fmt == kFmtD1K8 || fmt == kFmtD1K8BN) ? (n_cb + 3) / 4 : n_cb;
 }
 
@@ -175,13 +175,13 @@ hipError_t launch_gemm(const vq_desc& d, const void* a, const void* b, const voi
 hipError_t launch_em_assign(const vq_desc& d, const void* W, const void* h, const void* cb, void* a, hipStream_t) {
   ++g_launches;
   REQUIRE(W && h && cb && a, "E-step with a null pointer");
-  REQUIRE(d.group_rows == 1 || d.group_rows % 8 == 0, "E-step group_rows %d", d.group_rows);
+  REQUIRE(d.group_rows == 1 || (d.group_rows == 4 && d.d <= 2) || d.group_rows % 8 == 0, "E-step group_rows %d", d.group_rows);
   return hipSuccess;
 }
 hipError_t launch_em_update(const vq_desc& d, const void* W, const void* h, const void* a, void* cb, hipStream_t) {
   ++g_launches;
   REQUIRE(W && h && cb && a, "M-step with a null pointer");
-  REQUIRE(d.group_rows == 1 || d.group_rows % 8 == 0, "M-step group_rows %d", d.group_rows);
+  REQUIRE(d.group_rows == 1 || (d.group_rows == 4 && d.d <= 2) || d.group_rows % 8 == 0, "M-step group_rows %d", d.group_rows);
   return hipSuccess;
 }
 

@@ -142,6 +142,18 @@ def test_int8_table_representation_sizes_and_entry_points():
     assert (ib + cbb) * 8 * 2048 == 4096 * 11008 * (2 * 2048 + 16 * 2 * 8 + 16)
     assert vq.vq_layout_bytes(d) == (512 * 44 * 512, 512 * 44 * 34)
     assert L.vq_gemm_batched(ctypes.byref(d), A, A, A, 0, 16, A + 16, 16, vq.VQ_F16, 0) == -6   # accepted, then B < 1
+    # the same with groups of 4 rows (the 2.25 bpv 2D row of the appendix table): 2 + (16*2*8 + 16)/1024
+    # bits per value; two tables and two scales per device slot
+    d = vq.make_desc(4096, 11008, 16, 4, group_rows=4, codebook_dtype=vq.VQ_I8)
+    ib, cbb = vq.vq_canonical_bytes(d)
+    assert (ib + cbb) * 8 * 1024 == 4096 * 11008 * (2 * 1024 + 16 * 2 * 8 + 16)
+    assert vq.vq_layout_bytes(d) == (512 * 44 * 512, 512 * 44 * 68)
+    assert L.vq_gemv(ctypes.byref(d), A, A, A + 2, A + 16, vq.VQ_F16, 0) == -4
+    for bad in (vq.make_desc(4096, 4096, 16, 4, group_rows=4),                                  # fp16 codebooks: 8-row groups
+                vq.make_desc(4096, 4096, 16, 4, group_rows=4, codebook_dtype=vq.VQ_I8_BN),      # no block scales on 4-row groups
+                vq.make_desc(4100, 4096, 16, 4, group_rows=4, codebook_dtype=vq.VQ_I8),         # rows in blocks of 8
+                vq.make_desc(4096, 4096, 16, 4, group_rows=2, codebook_dtype=vq.VQ_I8)):
+        assert L.vq_gemv(ctypes.byref(bad), A, A, A, A + 16, vq.VQ_F16, 0) == -3
     d16 = vq.make_desc(4096, 4096, 16, 4)
     d64 = vq.make_desc(4096, 4096, 64, 6, group_rows=32, codebook_dtype=vq.VQ_I8)
     descs = (vq.VQDesc * 2)(d64, d16)

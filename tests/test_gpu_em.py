@@ -187,6 +187,7 @@ ANY_SHAPES = [
     (64, 512, 64, 2, 32), (48, 256, 64, 2, 16),       # d = 2 with taller groups
     (256, 512, 256, 2, 128), (64, 256, 256, 2, 64),
     (128, 512, 256, 4, 64), (256, 256, 256, 4, 256), (256, 768, 256, 4, 128),   # four-dimensional vectors
+    (8, 256, 16, 2, 4), (40, 768, 16, 2, 4), (24, 512, 16, 1, 4),   # groups of 4 rows: two codebooks per 8-row block
     (16, 256, 16, 4, 8), (8, 256, 4, 2, 1),           # combinations no decode format uses, same kernels
 ]
 

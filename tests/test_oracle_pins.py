@@ -449,6 +449,8 @@ def test_two_bit_scalar_codebook_per_row_equals_the_four_bit_pair_table():
         assert W[r, col] == np.float16(np.float16(q[g, field, 0]) * scale[g])
     # 2 bits + (4 x 8-bit values per 256 weights) = 2.125, the figure the table prints; 2.1875 with the scale
     assert oracle.bits_per_value(4, 1, 8, 256) == 2.125
+    # the 2D rows at 2 bits per dimension: groups of 2,048 weights give 2.125, groups of 1,024 give 2.25
+    assert oracle.bits_per_value(16, 2, 8, 2048) == 2.125 and oracle.bits_per_value(16, 2, 8, 1024) == 2.25
     ib, tb = oracle.canonical_sizes_i8(VQFormat(4096, 4096, 4, 2, 1, 256, 1))
     assert (ib + tb) * 8 / 4096 ** 2 == 2.1875
     s = workloads.CONFIGS["attn_4096x4096_d1_k4"]
