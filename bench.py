@@ -273,6 +273,9 @@ def main():
                  "gemv_stream_kernel<64>"),
                 ("llama7b_pass_k16_int8_tables_2.125bpv_via_vq_gemv_multi", workloads.LLAMA7B_LAYER_K16_I8,
                  "gemv_stream_kernel<k16,int8>"),
+                # k = 32, 5-bit indices (the appendix table's 2.5-bits-per-dimension 2D row): 2.76 bits per value
+                ("llama7b_pass_k32_int8_tables_2.76bpv_via_vq_gemv_multi", workloads.LLAMA7B_LAYER_K32,
+                 "gemv_stream_kernel<k32>"),
                 # the same with groups of 4 x 256 weights (the appendix table's 2D row at 2.25 bpv; 2.27 with the scales)
                 ("llama7b_pass_k16_int8_tables_4row_groups_2.27bpv_via_vq_gemv_multi", workloads.LLAMA7B_LAYER_K16_I8_G4,
                  "gemv_stream_kernel<k16,i8,4-row groups>"),
@@ -356,6 +359,10 @@ def main():
                         tv = tab.view(-1, 528)
                         tv[:, 512:528] = 0
                         tv[:, 513:520:2] = 0x1C
+                    elif s.k == 32:                     # 64 bytes of table per slot, then 2 bytes of scale per slot
+                        n_slots = cbb // 66
+                        tab[n_slots * 64::2] = 0
+                        tab[n_slots * 64 + 1::2] = 0x1C
                     else:                               # 32 bytes per table, then 2 bytes of scale per table (4-row groups: two per slot)
                         n_slots = cbb // 34
                         tab[n_slots * 32::2] = 0

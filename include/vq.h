@@ -52,7 +52,8 @@
  * or 256; VQ_I8 with k = 64 (6-bit indices) and groups of 8, 16 or 32 rows x 256 columns
  * (32 rows: the 8,192-weight groups and 3.125 bits per value of Sec. 5.1); VQ_I8 with k = 16
  * and 8 x 256 groups (2.125 bits per value) or 4 x 256 groups (1,024 weights: the 2.25-bit 2D row
- * of the appendix table; out_features a multiple of 8); VQ_I8 with k = 256 and groups of 64, 128 or 256
+ * of the appendix table; out_features a multiple of 8); VQ_I8 with k = 32 (5-bit indices, the
+ * 2.5-bits-per-dimension row: 2.75 bits per value) and 8 x 256 groups; VQ_I8 with k = 256 and groups of 64, 128 or 256
  * rows x 256 columns (128 rows: the 32,768-weight groups and 4.125 bits per value of the 2D
  * 4-bits-per-dimension setting); and scalar codebooks, d = 1 (the 1D rows of the
  * appendix table of VQ configurations): VQ_F16, k = 16, 4-bit indices, 8 x 256 groups, 4.125
@@ -104,10 +105,10 @@ typedef struct vq_desc {
                              8 or 4 (VQ_I8 with k = 16); 1 (d = 1 with k = 4)         */
   int32_t group_cols;     /* 256 (Sec. 4: at most 256 columns per group)            */
   int32_t d;              /* VQ dimensionality: 2, 1 (scalar codebooks) or 4        */
-  int32_t k;              /* centroids.  d = 2: 16 or 256 (VQ_F16), 16, 64 or 256 (VQ_I8),
+  int32_t k;              /* centroids.  d = 2: 16 or 256 (VQ_F16), 16, 32, 64 or 256 (VQ_I8),
                              16, 64 or 256 (VQ_I8_BN); d = 1: 16 (VQ_F16), 8 or 4 (VQ_I8), 8 (VQ_I8_BN);
                              d = 4: 256 (VQ_I8, VQ_I8_BN or VQ_F16) */
-  int32_t index_bits;     /* log2(k): 2, 3, 4, 6 or 8                               */
+  int32_t index_bits;     /* log2(k): 2, 3, 4, 5, 6 or 8                            */
   int32_t codebook_dtype; /* VQ_F16, VQ_I8 or VQ_I8_BN (see the list above)         */
 } vq_desc;
 
@@ -237,7 +238,7 @@ VQ_API int vq_decode_dense(const vq_desc* desc, const void* idx_dev, const void*
  * Quantiser side (offline; paragraph "Codebook Initialization"): the two steps of the
  * Hessian-weighted EM that initialises the codebook of every group (desc->codebook_dtype is
  * ignored: weights and codebooks are fp32 here).  Implemented for d = 1, 2 or 4, k = 4, 8, 16,
- * 64 or 256, and groups of 1, 4, 8, 16, 32, 64, 128 or 256 rows x 256 columns (one row: k * d <= 64;
+ * 32, 64 or 256, and groups of 1, 4, 8, 16, 32, 64, 128 or 256 rows x 256 columns (one row: k * d <= 64;
  * 4 rows: d = 1 or 2),
  * which covers the group shapes of every representation the decode side takes; out_features is
  * a multiple of max(group_rows, 8).

@@ -59,6 +59,8 @@ int check_desc(const vq_desc* d) {
       if (d->group_rows != 8 && d->group_rows != 16 && d->group_rows != 32) return VQ_ERR_UNSUPPORTED;
     } else if (d->k == 16) {                  // 8 x 256 groups, with or without blockwise normalisation; or 4 x 256 groups
       if (d->group_rows != kGroupRows && !(d->group_rows == 4 && !is_bn(*d))) return VQ_ERR_UNSUPPORTED;
+    } else if (d->k == 32) {                  // 5-bit indices (the 2.5-bits-per-dimension rows): 8 x 256 groups
+      if (d->group_rows != kGroupRows || is_bn(*d)) return VQ_ERR_UNSUPPORTED;
     } else if (d->k == 256) {                 // the 4-bits-per-dimension 2D setting: large groups share a table
       if (d->group_rows != 64 && d->group_rows != 128 && d->group_rows != 256) return VQ_ERR_UNSUPPORTED;
     } else {
@@ -94,7 +96,7 @@ void sizes(const vq_desc& d, size_t* idx_bytes, size_t* cb_bytes) {
 
 // Units a row-block of `n_cb` col-blocks is cut into (what the strips of the GEMV kernels count).
 int strip_units(int fmt, int n_cb) {
-  return (fmt == 16 || fmt == kFmtK16I8 || fmt == kFmtK16BN || fmt == kFmtK16I8H || fmt == kFmtD1K4) ? (n_cb + 1) / 2 : (fmt == 64 || fmt == kFmtK64BN || fmt == kFmtD1K8 || fmt == kFmtD1K8BN) ? (n_cb + 3) / 4 : n_cb;
+  return (fmt == 16 || fmt == kFmtK16I8 || fmt == kFmtK16BN || fmt == kFmtK16I8H || fmt == kFmtK32 || fmt == kFmtD1K4) ? (n_cb + 1) / 2 : (fmt == 64 || fmt == kFmtK64BN || fmt == kFmtD1K8 || fmt == kFmtD1K8BN) ? (n_cb + 3) / 4 : n_cb;
 }
 
 int hip_status(hipError_t e) { return e == hipSuccess ? VQ_OK : VQ_ERR_HIP; }
@@ -107,7 +109,7 @@ int check_em_desc(const vq_desc* d) {
     return VQ_ERR_BAD_DESC;
   if (!is_pow2(d->k) || d->k != (1 << d->index_bits)) return VQ_ERR_BAD_DESC;
   if ((d->d != 1 && d->d != 2 && d->d != 4) || d->group_cols != kGroupCols) return VQ_ERR_UNSUPPORTED;
-  if (d->k != 4 && d->k != 8 && d->k != 16 && d->k != 64 && d->k != 256) return VQ_ERR_UNSUPPORTED;
+  if (d->k != 4 && d->k != 8 && d->k != 16 && d->k != 32 && d->k != 64 && d->k != 256) return VQ_ERR_UNSUPPORTED;
   const int gr = d->group_rows;
   if (gr != 1 && gr != 4 && gr != 8 && gr != 16 && gr != 32 && gr != 64 && gr != 128 && gr != 256) return VQ_ERR_UNSUPPORTED;
   if (gr == 1 && d->k * d->d > 64) return VQ_ERR_UNSUPPORTED;   // a codebook per row: small codebooks only
@@ -406,6 +408,12 @@ int vq_layout_bytes(const vq_desc* desc, size_t* idx_bytes, size_t* cb_bytes) {
   if (desc->d == 1) {    // 1 KB of indices and 16 fp16 scalars per group
     if (idx_bytes) *idx_bytes = n_rb * n_cb * 1024;
     if (cb_bytes) *cb_bytes = n_rb * n_cb * 32;
+    return VQ_OK;
+  }
+  if (desc->k == 32) {   // nibbles as for k = 16 plus a plane of fifth bits (640 bytes per slot); 64-byte tables + scale
+    const size_t slots32 = 2 * ((n_cb + 1) / 2);
+    if (idx_bytes) *idx_bytes = n_rb * slots32 * 640;
+    if (cb_bytes) *cb_bytes = n_rb * slots32 * 66;
     return VQ_OK;
   }
   const size_t slots = desc->k == 16 ? 2 * ((n_cb + 1) / 2) : n_cb;

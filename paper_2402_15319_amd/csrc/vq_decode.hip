@@ -18,7 +18,7 @@ __global__ __launch_bounds__(256) void decode_kernel(const uint8_t* __restrict__
                                                      uint16_t* __restrict__ W, int n_cb,
                                                      long long n_groups, int in_features, int rpc) {
   // (k = 16 with blockwise normalisation: 16 table entries, then the group's 16 levels)
-  __shared__ uint32_t lut_all[4][K == kFmtK16I8 ? 16 : (K == kFmtK16BN || K == kFmtK16I8H) ? 32 : (K == kFmtD1K16 || K == kFmtK256I8) ? 256 : K == kFmtK256I8BN ? 272 : K == kFmtD1K4 ? 128 : K];
+  __shared__ uint32_t lut_all[4][K == kFmtK16I8 ? 16 : (K == kFmtK16BN || K == kFmtK16I8H || K == kFmtK32) ? 32 : (K == kFmtD1K16 || K == kFmtK256I8) ? 256 : K == kFmtK256I8BN ? 272 : K == kFmtD1K4 ? 128 : K];
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   uint32_t* lut = lut_all[wave];
@@ -52,11 +52,21 @@ __global__ __launch_bounds__(256) void decode_kernel(const uint8_t* __restrict__
         *reinterpret_cast<uint2*>(out + (size_t)(4 * h + r) * in_features) = make_uint2(lo, hi);
       }
     }
-  } else if (K == 16 || K == kFmtK16I8 || K == kFmtK16BN || K == kFmtK16I8H) {
+  } else if (K == 16 || K == kFmtK16I8 || K == kFmtK16BN || K == kFmtK16I8H || K == kFmtK32) {
     const int slots = 2 * k16_pairs(n_cb);                  // group slots per row-block
     uint32_t cw = 0;                                        // BN: the lane's block codes, row r in bits [4r, 4r+4)
+    uint32_t plane = 0;                                     // k = 32: the lane's fifth bits of the pair
     if (K == 16) {
       if (lane < 16) lut[lane] = cb[(rb * slots + c) * 16 + lane];
+    } else if (K == kFmtK32) {      // a 32-entry table per group; fifth bits behind the nibbles of the whole matrix
+      const long long n_rb = n_groups / n_cb;
+      const uint8_t* tb = reinterpret_cast<const uint8_t*>(cb);
+      if (lane < 32) {
+        const uint16_t* sc = reinterpret_cast<const uint16_t*>(tb + (size_t)n_rb * slots * 64);
+        lut[lane] = k64_dequant_pair(*reinterpret_cast<const uint16_t*>(tb + (size_t)(rb * slots + c) * 64 + lane * 2),
+                                     __builtin_bit_cast(_Float16, sc[rb * slots + c]));
+      }
+      plane = reinterpret_cast<const uint32_t*>(idx + (size_t)n_rb * slots * 512)[(rb * (slots / 2) + (c >> 1)) * 64 + lane];
     } else if (K == kFmtK16I8H) {   // groups of 4 rows: the table of rows 0..3, then that of rows 4..7
       const long long n_rb = n_groups / n_cb;
       const uint8_t* tb = reinterpret_cast<const uint8_t*>(cb);
@@ -91,8 +101,10 @@ __global__ __launch_bounds__(256) void decode_kernel(const uint8_t* __restrict__
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         const char* lut_h = lutb + (K == kFmtK16I8H ? 64 * h : 0);
-        uint32_t lo = *reinterpret_cast<const uint32_t*>(lut_h + ((a >> (8 * r)) & 0xffu));
-        uint32_t hi = *reinterpret_cast<const uint32_t*>(lut_h + ((b >> (8 * r)) & 0xffu));
+        uint32_t lo = *reinterpret_cast<const uint32_t*>(lut_h + ((a >> (8 * r)) & 0xffu) +
+                                                         (K == kFmtK32 ? 64 * k32_plane_bit(plane, c & 1, 4 * h + r, 0) : 0));
+        uint32_t hi = *reinterpret_cast<const uint32_t*>(lut_h + ((b >> (8 * r)) & 0xffu) +
+                                                         (K == kFmtK32 ? 64 * k32_plane_bit(plane, c & 1, 4 * h + r, 1) : 0));
         if (K == kFmtK16BN) {   // times the scale of the row's 32-weight block: one more fp16 rounding
           const h2_t sc = __builtin_bit_cast(h2_t, lut[16 + ((cw >> (4 * (4 * h + r))) & 15u)]);
           lo = __builtin_bit_cast(uint32_t, __builtin_bit_cast(h2_t, lo) * sc);
@@ -306,6 +318,7 @@ hipError_t launch_decode(const vq_desc& d, const void* idx_dev, const void* cb_d
                      d.group_rows >= kGroupRows ? d.group_rows / kGroupRows : 1)
   if (fmt == kFmtK16I8) VQ_DECODE(kFmtK16I8);
   else if (fmt == kFmtK16I8H) VQ_DECODE(kFmtK16I8H);
+  else if (fmt == kFmtK32) VQ_DECODE(kFmtK32);
   else if (fmt == kFmtK16BN) VQ_DECODE(kFmtK16BN);
   else if (fmt == kFmtD1K16) VQ_DECODE(kFmtD1K16);
   else if (fmt == kFmtD1K4) VQ_DECODE(kFmtD1K4);

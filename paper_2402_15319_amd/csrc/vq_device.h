@@ -127,9 +127,88 @@ __device__ __forceinline__ void k16_group(uint32_t w0, uint32_t w1, uint32_t bas
       : [w0] "v"(w0), [w1] "v"(w1), [base] "s"(base), [x0] "v"(x0), [x1] "v"(x1), [off] "n"(OFF), [rs] "n"(RS), [hs] "n"(HS)
       : "memory");
 }
+// k = 32 (5-bit indices): the low four bits of every index are stored exactly as for k = 16, the
+// fifth bits in a separate plane (see the layout in vq_internal.h); the caller shifts the lane's
+// plane dword so that e0 .. e3 carry, at bits 6, 14, 22 and 30, the fifth bits of (rows 0..3,
+// vector 2L), (rows 0..3, vector 2L+1), (rows 4..7, vector 2L), (rows 4..7, vector 2L+1).  One
+// v_and_or_b32 per four lookups merges them into the "4 * index" bytes (a byte then holds
+// 4 * (index mod 16) + 64 * (index / 16) = 4 * index); the rest is the k = 16 block on a
+// 32-entry table.  hb: 0x40404040 in a scalar register.
+#define VQ_MASKS32(W, EA, EB)                        \
+  VQ_MASKS(W)                                        \
+  "v_and_or_b32 %[ta], " EA ", %[hb], %[ta]\n"       \
+  "v_and_or_b32 %[tb], " EB ", %[hb], %[tb]\n"
+template <int OFF>
+__device__ __forceinline__ void k32_group(uint32_t w0, uint32_t w1, uint32_t e0, uint32_t e1, uint32_t e2,
+                                          uint32_t e3, uint32_t hb, uint32_t base, uint32_t x0, uint32_t x1,
+                                          float (&acc)[8]) {
+  uint32_t ta, tb, r0, r1, r2, r3, r4, r5, r6, r7, r8, r9, r10, r11;
+  asm volatile(
+      VQ_MASKS32("%[w0]", "%[e0]", "%[e1]")
+      VQ_SDWA_RD("%[r0]", "%[ta]", 0, 0) VQ_SDWA_RD("%[r1]", "%[tb]", 0, 0)
+      VQ_SDWA_RD("%[r2]", "%[ta]", 1, 1) VQ_SDWA_RD("%[r3]", "%[tb]", 1, 1)
+      VQ_SDWA_RD("%[r4]", "%[ta]", 2, 2) VQ_SDWA_RD("%[r5]", "%[tb]", 2, 2)
+      VQ_SDWA_RD("%[r6]", "%[ta]", 3, 3) VQ_SDWA_RD("%[r7]", "%[tb]", 3, 3)
+      VQ_MASKS32("%[w1]", "%[e2]", "%[e3]")
+      VQ_SDWA_RD("%[r8]", "%[ta]", 0, 4) VQ_SDWA_RD("%[r9]", "%[tb]", 0, 4)
+      VQ_SDWA_RD("%[r10]", "%[ta]", 1, 5) VQ_SDWA_RD("%[r11]", "%[tb]", 1, 5)
+      "s_waitcnt lgkmcnt(4)\n"
+      VQ_DOT("%[a0]", "%[r0]", "%[x0]") VQ_DOT("%[a1]", "%[r2]", "%[x0]")
+      VQ_DOT("%[a2]", "%[r4]", "%[x0]") VQ_DOT("%[a3]", "%[r6]", "%[x0]")
+      VQ_DOT("%[a0]", "%[r1]", "%[x1]") VQ_DOT("%[a1]", "%[r3]", "%[x1]")
+      VQ_DOT("%[a2]", "%[r5]", "%[x1]") VQ_DOT("%[a3]", "%[r7]", "%[x1]")
+      VQ_SDWA_RD("%[r0]", "%[ta]", 2, 6) VQ_SDWA_RD("%[r1]", "%[tb]", 2, 6)
+      VQ_SDWA_RD("%[r2]", "%[ta]", 3, 7) VQ_SDWA_RD("%[r3]", "%[tb]", 3, 7)
+      "s_waitcnt lgkmcnt(4)\n"
+      VQ_DOT("%[a4]", "%[r8]", "%[x0]") VQ_DOT("%[a5]", "%[r10]", "%[x0]")
+      VQ_DOT("%[a4]", "%[r9]", "%[x1]") VQ_DOT("%[a5]", "%[r11]", "%[x1]")
+      "s_waitcnt lgkmcnt(0)\n"
+      VQ_DOT("%[a6]", "%[r0]", "%[x0]") VQ_DOT("%[a7]", "%[r2]", "%[x0]")
+      VQ_DOT("%[a6]", "%[r1]", "%[x1]") VQ_DOT("%[a7]", "%[r3]", "%[x1]")
+      : [a0] "+v"(acc[0]), [a1] "+v"(acc[1]), [a2] "+v"(acc[2]), [a3] "+v"(acc[3]),
+        [a4] "+v"(acc[4]), [a5] "+v"(acc[5]), [a6] "+v"(acc[6]), [a7] "+v"(acc[7]),
+        [ta] "=&v"(ta), [tb] "=&v"(tb), [r0] "=&v"(r0), [r1] "=&v"(r1), [r2] "=&v"(r2),
+        [r3] "=&v"(r3), [r4] "=&v"(r4), [r5] "=&v"(r5), [r6] "=&v"(r6), [r7] "=&v"(r7),
+        [r8] "=&v"(r8), [r9] "=&v"(r9), [r10] "=&v"(r10), [r11] "=&v"(r11)
+      : [w0] "v"(w0), [w1] "v"(w1), [e0] "v"(e0), [e1] "v"(e1), [e2] "v"(e2), [e3] "v"(e3), [hb] "s"(hb),
+        [base] "s"(base), [x0] "v"(x0), [x1] "v"(x1), [off] "n"(OFF), [rs] "n"(0), [hs] "n"(0)
+      : "memory");
+}
+#undef VQ_MASKS32
 #undef VQ_SDWA_RD
 #undef VQ_MASKS
 #undef VQ_DOT
+
+// The four shifted copies of a fifth-bit plane dword that k32_group takes, for the first (SLOT 0)
+// or second (SLOT 1) col-block of a pair: set j of slot 0 sits at bits 6 - j of every byte, set j
+// of slot 1 at bits 2 - j (j < 3) and at bit 7 (j = 3).
+template <int SLOT>
+__device__ __forceinline__ void k32_plane_sets(uint32_t e, uint32_t& e0, uint32_t& e1, uint32_t& e2, uint32_t& e3) {
+  if constexpr (SLOT == 0) {
+    e0 = e; e1 = e << 1; e2 = e << 2; e3 = e << 3;
+  } else {
+    e0 = e << 4; e1 = e << 5; e2 = e << 6; e3 = e >> 1;
+  }
+}
+// The fifth bit of the index of (row r, vector 2L + t) of slot SLOT in a plane dword (plain form of the above).
+__device__ __forceinline__ uint32_t k32_plane_bit(uint32_t e, int slot, int r, int t) {
+  const int j = 2 * (r >> 2) + t;                      // the set
+  const int pos = slot == 0 ? 6 - j : (j < 3 ? 2 - j : 7);
+  return (e >> (8 * (r & 3) + pos)) & 1u;
+}
+__device__ __forceinline__ uint32_t k32_plane_encode(const uint32_t bits_a[16], const uint32_t bits_b[16]) {
+  // bits_x[2 * r + t]: the fifth bit of (row r, vector 2L + t) of the pair's first / second col-block
+  uint32_t e = 0;
+#pragma unroll
+  for (int r = 0; r < 8; ++r)
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      const int j = 2 * (r >> 2) + t;
+      e |= (bits_a[2 * r + t] & 1u) << (8 * (r & 3) + 6 - j);
+      e |= (bits_b[2 * r + t] & 1u) << (8 * (r & 3) + (j < 3 ? 2 - j : 7));
+    }
+  return e;
+}
 
 // k = 16 inner block with blockwise normalisation, hand-scheduled (the streaming kernel's
 // version of k16_group_scaled): per row the two centroid pairs and the row's block scale (a dword

@@ -301,6 +301,7 @@ __global__ __launch_bounds__(128) void em_update_any_kernel(const float* __restr
     case 4: F(4); break;     \
     case 8: F(8); break;     \
     case 16: F(16); break;   \
+    case 32: F(32); break;   \
     case 64: F(64); break;   \
     default: F(256); break;  \
   }

@@ -42,7 +42,7 @@ __device__ __forceinline__ int wt_half_index(int m, int k) {   // k in halfs
 // scale per group, groups of 8*rpc rows), kFmtK16I8 (k = 16 with int8 tables).
 template <int K> constexpr int lut_dwords() {
   // BN: 64 centroids + 16 levels; d = 4: 256 entries of 4 halfs; scalar 2-bit: 8 rows x 16 pair entries
-  return K == kFmtK16I8 ? 16 : (K == kFmtK16BN || K == kFmtK16I8H) ? 32 : (K == kFmtD1K16 || K == kFmtK256I8) ? 256 : K == kFmtK256I8BN ? 272 : (K == kFmtK64BN || K == kFmtD1K8BN) ? 80 : (K == kFmtD4 || K == kFmtD4F16 || K == kFmtD4BN) ? 512 : K == kFmtD1K8 ? 64 : K == kFmtD1K4 ? 128 : K;
+  return K == kFmtK16I8 ? 16 : (K == kFmtK16BN || K == kFmtK16I8H || K == kFmtK32) ? 32 : (K == kFmtD1K16 || K == kFmtK256I8) ? 256 : K == kFmtK256I8BN ? 272 : (K == kFmtK64BN || K == kFmtD1K8BN) ? 80 : (K == kFmtD4 || K == kFmtD4F16 || K == kFmtD4BN) ? 512 : K == kFmtD1K8 ? 64 : K == kFmtD1K4 ? 128 : K;
 }
 
 // What one wave needs to decode one group: the lane's index bytes and codebook piece.
@@ -118,6 +118,13 @@ template <> struct GroupRegs<kFmtK16I8H> {
   uint32_t two;          // int8 pair of entry lane & 15 of table (lane >> 4) & 1 (rows 0..3 / rows 4..7)
   uint32_t sc;           // that table's scale
 };
+template <> struct GroupRegs<kFmtK32> {
+  uint2 w;               // the low four bits of the lane's 16 indices, as for k = 16
+  uint32_t plane;        // the fifth bits of the lane's indices in both col-blocks of the pair
+  uint32_t two;          // int8 pair of table entry lane & 31
+  uint32_t sc;
+  int slot;              // which col-block of the pair
+};
 template <> struct GroupRegs<kFmtK16BN> {
   uint2 w;
   uint32_t two, sc;      // as for k = 16 with int8 tables
@@ -144,6 +151,15 @@ __device__ __forceinline__ void load_group(GroupRegs<K>& g, const uint8_t* idx, 
       g.lev = reinterpret_cast<const uint16_t*>(tabs + k16bn_level_offset(n_slots))[slot * 16 + (lane & 15)];
       g.cw = reinterpret_cast<const uint32_t*>(tabs + k16bn_code_offset(n_slots))[(slot >> 1) * 16 + 2 * (lane >> 3) + (c & 1)];
     }
+  } else if constexpr (K == kFmtK32) {
+    const int slots = 2 * k16_pairs(n_cb);
+    const uint8_t* tabs = reinterpret_cast<const uint8_t*>(cb);
+    const size_t slot = (size_t)rb * slots + c;
+    g.w = *reinterpret_cast<const uint2*>(idx + (size_t)rb * slots * 512 + k16_chunk_offset(c, lane));
+    g.plane = reinterpret_cast<const uint32_t*>(idx + (size_t)n_rb * slots * 512)[(slot >> 1) * 64 + lane];
+    g.two = *reinterpret_cast<const uint16_t*>(tabs + slot * 64 + (lane & 31) * 2);
+    g.sc = reinterpret_cast<const uint16_t*>(tabs + (size_t)n_rb * slots * 64)[slot];
+    g.slot = c & 1;
   } else if constexpr (K == kFmtK16I8H) {
     const int slots = 2 * k16_pairs(n_cb);
     const uint8_t* tabs = reinterpret_cast<const uint8_t*>(cb);
@@ -300,10 +316,10 @@ __device__ __forceinline__ void decode_group(const GroupRegs<K>& g, uint32_t* lu
         v[8 * h + 2 * r + 1] = *reinterpret_cast<const uint32_t*>(row_tab + ((b >> (8 * r)) & 0xffu));
       }
     }
-  } else if constexpr (K == 16 || K == kFmtK16I8 || K == kFmtK16BN || K == kFmtK16I8H) {
+  } else if constexpr (K == 16 || K == kFmtK16I8 || K == kFmtK16BN || K == kFmtK16I8H || K == kFmtK32) {
     if constexpr (K == 16) {
       if (lane < 16) lut[lane] = g.cbv;
-    } else if constexpr (K == kFmtK16I8H) {
+    } else if constexpr (K == kFmtK16I8H || K == kFmtK32) {
       if (lane < 32) lut[lane] = k64_dequant_pair(g.two, __builtin_bit_cast(_Float16, (uint16_t)g.sc));
     } else {
       if (lane < 16) lut[lane] = k64_dequant_pair(g.two, __builtin_bit_cast(_Float16, (uint16_t)g.sc));
@@ -320,8 +336,13 @@ __device__ __forceinline__ void decode_group(const GroupRegs<K>& g, uint32_t* lu
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         const char* lut_h = lutb + (K == kFmtK16I8H ? 64 * h : 0);   // groups of 4 rows: rows 4..7 use the second table
-        v[8 * h + 2 * r] = *reinterpret_cast<const uint32_t*>(lut_h + ((a >> (8 * r)) & 0xffu));
-        v[8 * h + 2 * r + 1] = *reinterpret_cast<const uint32_t*>(lut_h + ((b >> (8 * r)) & 0xffu));
+        uint32_t oa = (a >> (8 * r)) & 0xffu, ob = (b >> (8 * r)) & 0xffu;
+        if constexpr (K == kFmtK32) {                                // the fifth bit selects the upper half of the table
+          oa += 64 * k32_plane_bit(q.plane, q.slot, 4 * h + r, 0);
+          ob += 64 * k32_plane_bit(q.plane, q.slot, 4 * h + r, 1);
+        }
+        v[8 * h + 2 * r] = *reinterpret_cast<const uint32_t*>(lut_h + oa);
+        v[8 * h + 2 * r + 1] = *reinterpret_cast<const uint32_t*>(lut_h + ob);
       }
     }
     if constexpr (K == kFmtK16BN) {     // times the block scale of the lane's 32-weight block, per row
@@ -970,6 +991,7 @@ hipError_t launch_gemm(const vq_desc& d, const void* idx_dev, const void* cb_dev
   if (fmt == kFmtK64BN) VQ_GEMM_DISPATCH(kFmtK64BN)
   if (fmt == kFmtD4) VQ_GEMM_DISPATCH(kFmtD4)
   if (fmt == kFmtK16I8H) VQ_GEMM_DISPATCH(kFmtK16I8H)
+  if (fmt == kFmtK32) VQ_GEMM_DISPATCH(kFmtK32)
   if (fmt == kFmtD4F16) VQ_GEMM_DISPATCH(kFmtD4F16)
   if (fmt == kFmtD4BN) VQ_GEMM_DISPATCH(kFmtD4BN)
   if (fmt == kFmtK256I8BN) VQ_GEMM_DISPATCH(kFmtK256I8BN)

@@ -54,10 +54,13 @@ template <int K> struct Chunk;
 // per 32 weights); the plain C++ inner block replaces the hand-scheduled one.
 // MODE 3 (H4): int8 tables for groups of 4 rows: two tables per 8-row block and col-block (rows
 // 0..3, rows 4..7), 64 + 4 bytes per slot; the hand-scheduled block reads rows 4..7 from the second.
+// MODE 4 (K32): k = 32, 5-bit indices: 64 bytes of int8 table per group (staged like the two tables
+// of a 4-row-group slot) and a plane of fifth bits next to the nibbles (one dword per lane and pair).
 template <int MODE> struct Chunk16T {
-  static constexpr bool I8 = MODE >= 1, BN = MODE == 2, H4 = MODE == 3;
+  static constexpr bool I8 = MODE >= 1, BN = MODE == 2, K32 = MODE == 4, H4 = MODE == 3 || K32;   // H4: 64 bytes of tables per slot
   static constexpr int kUnits = 4;        // col-block pairs per chunk
   static constexpr int kLutDwords = (BN || H4) ? 256 : 128;  // 8 groups x 16 centroids (+ 8 x 16 levels, or x 2 tables)
+  uint4 ev;       // K32: the lane's fifth-bit plane dwords of pairs u .. u+3
   uint4 w[4];     // slot s: the lane's 16 index bytes of pair u+s
   uint2 xa[4];    // activations of the first group of the slot
   uint2 xb[4];    // ... and of the second
@@ -78,7 +81,8 @@ template <int MODE> struct Chunk16T {
                                    *reinterpret_cast<const uint2*>(tq + min(lane * 8, max(np_ * 128 - 8, 0))));
       tab = t2.x;
       tab2 = t2.y;
-      sc = S.sc_rb[u_ld * 4 + min(lane >> 2, max(4 * np_ - 1, 0))];
+      sc = K32 ? S.sc_rb[u_ld * 2 + min(lane >> 3, max(2 * np_ - 1, 0))]     // one scale per 64-byte table
+               : S.sc_rb[u_ld * 4 + min(lane >> 2, max(4 * np_ - 1, 0))];
     } else if constexpr (I8) {
       const uint8_t* tq = reinterpret_cast<const uint8_t*>(S.cb_rb) + (size_t)u_ld * 64;
       tab = zero_unless(lane * 4 < np_ * 64,
@@ -112,6 +116,13 @@ template <int MODE> struct Chunk16T {
   __device__ __forceinline__ void load(const Strip& S, int u, int lane) {
     np = max(0, min(4, S.u_end - u));
     load_tables(S, u, lane, np);
+    if constexpr (K32) {
+      uint32_t e[4];
+#pragma unroll
+      for (int s = 0; s < 4; ++s)
+        e[s] = *reinterpret_cast<const uint32_t*>(S.codes_rb + (size_t)(s < np ? u + s : 0) * 256 + lane * 4);
+      ev = make_uint4(e[0], e[1], e[2], e[3]);
+    }
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
       const bool ok = s < np;
@@ -139,6 +150,25 @@ template <int MODE> struct Chunk16T {
       }
       return;
     }
+    if constexpr (K32) {
+      const uint32_t es[4] = {ev.x, ev.y, ev.z, ev.w};
+      const uint32_t hb = 0x40404040u;
+#define VQ_K32(S, OFFA)                                                                                     \
+      {                                                                                                     \
+        uint32_t e0, e1, e2, e3;                                                                            \
+        k32_plane_sets<0>(es[S], e0, e1, e2, e3);                                                           \
+        k32_group<OFFA>(w[S].x, w[S].y, e0, e1, e2, e3, hb, base, xa[S].x, xa[S].y, acc);                   \
+        k32_plane_sets<1>(es[S], e0, e1, e2, e3);                                                           \
+        k32_group<OFFA + 128>(w[S].z, w[S].w, e0, e1, e2, e3, hb, base, xb[S].x, xb[S].y, acc);             \
+      }
+      VQ_K32(0, 0) VQ_K32(1, 256)
+      acc_hazard_fence();
+      if (np <= 2) return;
+      VQ_K32(2, 512) VQ_K32(3, 768)
+#undef VQ_K32
+      acc_hazard_fence();
+      return;
+    }
     constexpr int T = H4 ? 128 : 64, HS = H4 ? 64 : 0;   // bytes of tables per group slot; rows 4..7
     k16_group<0, 0, HS>(w[0].x, w[0].y, base, xa[0].x, xa[0].y, acc);
     k16_group<T, 0, HS>(w[0].z, w[0].w, base, xb[0].x, xb[0].y, acc);
@@ -155,6 +185,7 @@ template <int MODE> struct Chunk16T {
 };
 template <> struct Chunk<16> : Chunk16T<0> {};
 template <> struct Chunk<kFmtK16I8H> : Chunk16T<3> {};
+template <> struct Chunk<kFmtK32> : Chunk16T<4> {};
 template <> struct Chunk<kFmtK16I8> : Chunk16T<1> {};
 template <> struct Chunk<kFmtK16BN> : Chunk16T<2> {};
 
@@ -333,11 +364,16 @@ __device__ __forceinline__ Strip make_strip(const GemvProblem& P, int rb, int sp
   S.sc_rb = nullptr;
   S.codes_rb = nullptr;
   S.lev_rb = nullptr;
-  if (K == 16 || K == kFmtK16I8 || K == kFmtK16BN || K == kFmtK16I8H) {
+  if (K == 16 || K == kFmtK16I8 || K == kFmtK16BN || K == kFmtK16I8H || K == kFmtK32) {
     const int n_pairs = k16_pairs(n_cb);
     S.idx_rb = P.idx + (size_t)rb * n_pairs * 1024;
     if (K == 16) {
       S.cb_rb = P.cb + (size_t)rb * n_pairs * 32;
+    } else if (K == kFmtK32) {      // a 64-byte table per group slot, then all the scales; fifth bits behind all nibbles
+      S.cb_rb = P.cb + (size_t)rb * n_pairs * 32;
+      S.sc_rb = reinterpret_cast<const uint16_t*>(P.cb + (size_t)P.n_rb * n_pairs * 32) +
+                (size_t)rb * n_pairs * 2;
+      S.codes_rb = P.idx + (size_t)P.n_rb * n_pairs * 1024 + (size_t)rb * n_pairs * 256;
     } else if (K == kFmtK16I8H) {   // two 32-byte tables per group slot, then all the scales (4 bytes per slot)
       S.cb_rb = P.cb + (size_t)rb * n_pairs * 32;
       S.sc_rb = reinterpret_cast<const uint16_t*>(P.cb + (size_t)P.n_rb * n_pairs * 32) +
@@ -460,9 +496,10 @@ __device__ __forceinline__ int find_problem(const GemvBatch& batch, int item) {
 template <int K> struct ChunkS;
 
 template <int MODE> struct ChunkS16T {
-  static constexpr bool I8 = MODE >= 1, BN = MODE == 2, H4 = MODE == 3;
+  static constexpr bool I8 = MODE >= 1, BN = MODE == 2, K32 = MODE == 4, H4 = MODE == 3 || K32;   // see Chunk16T
   static constexpr int kUnits = 4;
   static constexpr int kLutDwords = (BN || H4) ? 256 : 128;
+  uint4 ev;        // K32: fifth-bit plane dwords of the chunk's pairs
   uint4 w[4];
   uint4 cbv;       // fp16 codebooks (lanes 0..31), or
   uint32_t tab2;   // H4: see Chunk16T
@@ -482,7 +519,15 @@ template <int MODE> struct ChunkS16T {
                                    *reinterpret_cast<const uint2*>(tq + min(lane * 8, max(np * 128 - 8, 0))));
       tab = t2.x;
       tab2 = t2.y;
-      sc = S.sc_rb[u_ld * 4 + min(lane >> 2, max(4 * np - 1, 0))];
+      sc = K32 ? S.sc_rb[u_ld * 2 + min(lane >> 3, max(2 * np - 1, 0))]
+               : S.sc_rb[u_ld * 4 + min(lane >> 2, max(4 * np - 1, 0))];
+      if constexpr (K32) {
+        uint32_t e[4];
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+          e[s] = *reinterpret_cast<const uint32_t*>(S.codes_rb + (size_t)(s < np ? u + s : 0) * 256 + lane * 4);
+        ev = make_uint4(e[0], e[1], e[2], e[3]);
+      }
     } else if constexpr (I8) {
       const uint8_t* tq = reinterpret_cast<const uint8_t*>(S.cb_rb) + (size_t)u_ld * 64;
       tab = zero_unless(lane * 4 < np * 64,
@@ -548,6 +593,31 @@ template <int MODE> struct ChunkS16T {
       acc_hazard_fence();
       return;
     }
+    if constexpr (K32) {      // absent pairs: zero tables against the zeroed col-blocks behind x
+      const uint32_t es[4] = {ev.x, ev.y, ev.z, ev.w};
+      const uint32_t hb = 0x40404040u;
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        const uint2 xa = xp[128 * s], xb = xp[128 * s + 64];
+        const uint32_t wa0 = s == 0 ? w[0].x : s == 1 ? w[1].x : s == 2 ? w[2].x : w[3].x;
+        const uint32_t wa1 = s == 0 ? w[0].y : s == 1 ? w[1].y : s == 2 ? w[2].y : w[3].y;
+        const uint32_t wb0 = s == 0 ? w[0].z : s == 1 ? w[1].z : s == 2 ? w[2].z : w[3].z;
+        const uint32_t wb1 = s == 0 ? w[0].w : s == 1 ? w[1].w : s == 2 ? w[2].w : w[3].w;
+        uint32_t e0, e1, e2, e3;
+        k32_plane_sets<0>(es[s], e0, e1, e2, e3);
+        if (s == 0) k32_group<0>(wa0, wa1, e0, e1, e2, e3, hb, base, xa.x, xa.y, acc);
+        else if (s == 1) k32_group<256>(wa0, wa1, e0, e1, e2, e3, hb, base, xa.x, xa.y, acc);
+        else if (s == 2) k32_group<512>(wa0, wa1, e0, e1, e2, e3, hb, base, xa.x, xa.y, acc);
+        else k32_group<768>(wa0, wa1, e0, e1, e2, e3, hb, base, xa.x, xa.y, acc);
+        k32_plane_sets<1>(es[s], e0, e1, e2, e3);
+        if (s == 0) k32_group<128>(wb0, wb1, e0, e1, e2, e3, hb, base, xb.x, xb.y, acc);
+        else if (s == 1) k32_group<384>(wb0, wb1, e0, e1, e2, e3, hb, base, xb.x, xb.y, acc);
+        else if (s == 2) k32_group<640>(wb0, wb1, e0, e1, e2, e3, hb, base, xb.x, xb.y, acc);
+        else k32_group<896>(wb0, wb1, e0, e1, e2, e3, hb, base, xb.x, xb.y, acc);
+      }
+      acc_hazard_fence();
+      return;
+    }
     constexpr int T = H4 ? 128 : 64, HS = H4 ? 64 : 0;   // bytes of tables per group slot; rows 4..7
     uint2 x0 = xp[0], x1 = xp[64];
     k16_group<0, 0, HS>(w[0].x, w[0].y, base, x0.x, x0.y, acc);
@@ -569,6 +639,7 @@ template <int MODE> struct ChunkS16T {
 };
 template <> struct ChunkS<16> : ChunkS16T<0> {};
 template <> struct ChunkS<kFmtK16I8H> : ChunkS16T<3> {};
+template <> struct ChunkS<kFmtK32> : ChunkS16T<4> {};
 template <> struct ChunkS<kFmtK16I8> : ChunkS16T<1> {};
 template <> struct ChunkS<kFmtK16BN> : ChunkS16T<2> {};
 
@@ -994,6 +1065,7 @@ __global__ __launch_bounds__(64 * WPW) void gemv_split_kernel(const typename Bat
     case 64: F(64); break;                    \
     case kFmtK16I8: F(kFmtK16I8); break;      \
     case kFmtK16I8H: F(kFmtK16I8H); break;    \
+    case kFmtK32: F(kFmtK32); break;          \
     case kFmtD1K16: F(kFmtD1K16); break;      \
     case kFmtK64BN: F(kFmtK64BN); break;      \
     case kFmtK16BN: F(kFmtK16BN); break;      \
@@ -1014,7 +1086,7 @@ inline size_t stream_lds_bytes_impl(int fmt, int max_n_cb) {
 }
 
 // Slot of a kernel format tag in per-format tables (the formats VQ_FMT_SWITCH knows; 256 is the default).
-constexpr int kStreamFormats = 11;
+constexpr int kStreamFormats = 12;
 inline int stream_format_slot(int fmt) {
   switch (fmt) {
     case 16: return 0;
@@ -1027,6 +1099,7 @@ inline int stream_format_slot(int fmt) {
     case kFmtK16BN: return 8;
     case kFmtD1K8BN: return 9;
     case kFmtK16I8H: return 10;
+    case kFmtK32: return 11;
     default: return 2;
   }
 }

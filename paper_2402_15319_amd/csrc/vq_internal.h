@@ -16,6 +16,11 @@ constexpr int kMaxProblemsPerLaunch = 256;  // the problem table travels in the 
 // the group's 16 scalars; from there on the work is that of d = 2, k = 256.
 constexpr int kFmtK16I8 = 1016;
 constexpr int kFmtK16I8H = 1416;   // k = 16, int8 tables + scale, groups of 4 rows x 256 columns (two tables per 8-row block)
+constexpr int kFmtK32 = 1032;     // k = 32 (5-bit indices), int8 tables + scale, 8 x 256 groups.  Indices: the low four bits
+                                  // of every index in the k = 16 layout (1 KB per col-block pair); behind the nibbles of
+                                  // the whole matrix, the fifth bits: 256 bytes per (8-row block, pair), one dword per
+                                  // lane (bit positions: k32_plane_encode in vq_device.h).  Tables: 64 bytes per group
+                                  // slot, then one fp16 scale per slot.
 constexpr int kFmtK256I8 = 1256;   // d = 2, k = 256, int8 tables + scale, groups of 64, 128 or 256 rows x 256 columns
 constexpr int kFmtD1K16 = 2016;
 constexpr int kFmtK64BN = 3064;   // k = 64, int8 tables + scale, blockwise normalisation (blocks of 32)
@@ -34,6 +39,7 @@ inline int format_tag(const vq_desc& d) {
   if (d.d == 4) return d.codebook_dtype == VQ_F16 ? kFmtD4F16 : d.codebook_dtype == VQ_I8_BN ? kFmtD4BN : kFmtD4;
   if (d.codebook_dtype == VQ_I8_BN) return d.k == 16 ? kFmtK16BN : d.k == 256 ? kFmtK256I8BN : kFmtK64BN;
   if (d.k == 16 && d.codebook_dtype == VQ_I8) return d.group_rows == 4 ? kFmtK16I8H : kFmtK16I8;
+  if (d.k == 32) return kFmtK32;
   if (d.k == 256 && d.codebook_dtype == VQ_I8) return kFmtK256I8;
   return d.k;
 }
@@ -143,7 +149,7 @@ hipError_t launch_gemm(const vq_desc& d, const void* idx_dev, const void* cb_dev
                        const void* X, int B, int ldx, void* Y, int ldy, int y_f32,
                        hipStream_t s);
 
-// E- and M-step of the codebook initialisation (d in {1, 2, 4}, k in {4, 8, 16, 64, 256}, groups
+// E- and M-step of the codebook initialisation (d in {1, 2, 4}, k in {4, 8, 16, 32, 64, 256}, groups
 // of 1, 4, 8, 16, 32, 64, 128 or 256 rows x 256 columns; one row only with k * d <= 64, 4 rows
 // only with d <= 2).
 hipError_t launch_em_assign(const vq_desc& d, const void* W, const void* hdiag, const void* cb,

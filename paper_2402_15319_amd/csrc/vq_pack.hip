@@ -164,6 +164,72 @@ __global__ __launch_bounds__(256) void pack_bn16_kernel(const uint32_t* __restri
   code_dev[(slot >> 1) * 16 + 2 * j + (c & 1)] = w;
 }
 
+// k = 32: one thread per (col-block pair, lane): the lane's two 8-byte nibble shares (the low four
+// bits of its 16 indices in each col-block, in the k = 16 layout) and its dword of fifth bits.
+// Canonical group: a little-endian stream of 5-bit fields, vector v of row r at bit 5 * (128 r + v).
+__global__ __launch_bounds__(256) void pack_idx32_kernel(const uint8_t* __restrict__ canon,
+                                                         uint8_t* __restrict__ nib_dev,
+                                                         uint32_t* __restrict__ plane_dev, int n_cb,
+                                                         long long n_pair_slots) {
+  const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
+  const long long ps = t >> 6;                 // (row-block, pair)
+  const int lane = (int)(t & 63);
+  if (ps >= n_pair_slots) return;
+  const int n_pairs = k16_pairs(n_cb);
+  const long long rb = ps / n_pairs;
+  const int p = (int)(ps - rb * n_pairs);
+  uint32_t bits[2][16];
+  uint32_t words[2][2];
+#pragma unroll
+  for (int e = 0; e < 2; ++e) {
+    const int c = 2 * p + e;
+    const bool ok = c < n_cb;
+    const uint8_t* g = canon + (size_t)(rb * n_cb + (ok ? c : 0)) * 640;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      uint32_t lo[4], hi[4];
+#pragma unroll
+      for (int b = 0; b < 4; ++b) {
+        const int r = 4 * h + b;
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt) {
+          const int bit0 = 5 * (128 * r + 2 * lane + tt);
+          const uint32_t two = g[bit0 >> 3] | ((uint32_t)g[(bit0 >> 3) + ((bit0 & 7) > 3 ? 1 : 0)] << 8);
+          const uint32_t v = ok ? (two >> (bit0 & 7)) & 31u : 0u;
+          (tt ? hi : lo)[b] = v & 15u;
+          bits[e][2 * r + tt] = v >> 4;
+        }
+      }
+      words[e][h] = k16_encode_dword(lo, hi);
+    }
+  }
+  *reinterpret_cast<uint4*>(nib_dev + ps * 1024 + lane * 16) = make_uint4(words[0][0], words[0][1], words[1][0], words[1][1]);
+  plane_dev[ps * 64 + lane] = k32_plane_encode(bits[0], bits[1]);
+}
+
+// k = 32 tables: 64 bytes per group slot (zero for the pad group), then one fp16 scale per slot.
+// One thread per dword of tables; the first n_slots threads also copy a scale.
+__global__ __launch_bounds__(256) void pack_tab32_kernel(const uint32_t* __restrict__ q_canon,
+                                                         const uint16_t* __restrict__ scale_canon,
+                                                         uint32_t* __restrict__ dev, int n_cb,
+                                                         long long n_slots) {
+  const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (t >= n_slots * 16) return;
+  const int slots_per_rb = 2 * k16_pairs(n_cb);
+  {
+    const long long slot = t >> 4;
+    const int piece = (int)(t & 15);
+    const long long rb = slot / slots_per_rb;
+    const int c = (int)(slot - rb * slots_per_rb);
+    dev[t] = c < n_cb ? q_canon[(rb * n_cb + c) * 16 + piece] : 0u;
+  }
+  if (t < n_slots) {
+    const long long rb = t / slots_per_rb;
+    const int c = (int)(t - rb * slots_per_rb);
+    reinterpret_cast<uint16_t*>(dev + n_slots * 16)[t] = c < n_cb ? scale_canon[rb * n_cb + c] : (uint16_t)0;
+  }
+}
+
 // Block codes of the formats with tall groups (d = 4; d = 2 with k = 256 and int8 tables): the
 // same 64 bytes per (8-row block, pair of col-blocks) as above.  One thread per (8-row block,
 // col-block slot, block j < 8); the slot of an absent last col-block gets zeros.
@@ -476,8 +542,21 @@ hipError_t launch_pack(const vq_desc& d, const void* idx_canon, const void* cb_c
                        (const uint8_t*)cb_canon + src_bytes, (uint32_t*)((uint8_t*)cb_dev + src_bytes), n_cb, n_code_slots);
     return hipGetLastError();
   }
-  const int slots_per_rb = (fmt == 16 || fmt == kFmtK16I8 || fmt == kFmtK16BN || fmt == kFmtK16I8H || fmt == kFmtD1K4) ? 2 * k16_pairs(n_cb) : n_cb;
+  const int slots_per_rb = (fmt == 16 || fmt == kFmtK16I8 || fmt == kFmtK16BN || fmt == kFmtK16I8H || fmt == kFmtK32 || fmt == kFmtD1K4) ? 2 * k16_pairs(n_cb) : n_cb;
   const long long n_slots = n_rb * slots_per_rb;
+  if (fmt == kFmtK32) {
+    const long long n_pair_slots = n_slots / 2;
+    hipLaunchKernelGGL(pack_idx32_kernel, dim3((unsigned)((n_pair_slots * 64 + 255) / 256)), dim3(256), 0, s,
+                       (const uint8_t*)idx_canon, (uint8_t*)idx_dev,
+                       (uint32_t*)((uint8_t*)idx_dev + (size_t)n_pair_slots * 1024), n_cb, n_pair_slots);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const size_t q_bytes = ((size_t)n_rb * n_cb * 64 + 15) / 16 * 16;   // scales follow the tables
+    hipLaunchKernelGGL(pack_tab32_kernel, dim3((unsigned)((n_slots * 16 + 255) / 256)), dim3(256), 0, s,
+                       (const uint32_t*)cb_canon, (const uint16_t*)((const uint8_t*)cb_canon + q_bytes),
+                       (uint32_t*)cb_dev, n_cb, n_slots);
+    return hipGetLastError();
+  }
   if (fmt == kFmtD1K4) {
     hipLaunchKernelGGL(pack_idx_kernel<16>, dim3((unsigned)((n_slots * 64 + 255) / 256)), dim3(256), 0, s,
                        (const uint8_t*)idx_canon, (uint8_t*)idx_dev, n_cb, n_slots, 1, 1);

@@ -52,6 +52,7 @@ std::vector<vq_desc> supported(int out_mult, int n_cb) {
   v.push_back(make(8 * out_mult, in, 8, 2, 256, 8, VQ_F16));
   v.push_back(make(8 * out_mult, in, 8, 2, 16, 4, VQ_I8));
   v.push_back(make(8 * out_mult, in, 4, 2, 16, 4, VQ_I8));
+  v.push_back(make(8 * out_mult, in, 8, 2, 32, 5, VQ_I8));
   for (int gr : {8, 16, 32}) v.push_back(make(gr * out_mult, in, gr, 2, 64, 6, VQ_I8));
   for (int gr : {8, 16, 32}) v.push_back(make(gr * out_mult, in, gr, 2, 64, 6, VQ_I8_BN));
   v.push_back(make(8 * out_mult, in, 8, 2, 16, 4, VQ_I8_BN));
@@ -120,7 +121,7 @@ int main(int argc, char** argv) {
 
   // ---- several matrices per launch, with and without adapters: random mixes of shapes
   for (int trial = 0; trial < 400; ++trial) {
-    const int fmt_pick = rnd() % 15;
+    const int fmt_pick = rnd() % 16;
     const int count = 1 + rnd() % (trial % 7 == 0 ? 600 : 12);
     std::vector<vq_desc> descs;
     std::vector<const void*> idxs, cbs, xs;
@@ -145,6 +146,7 @@ int main(int argc, char** argv) {
         case 11: d = make(256 * m, 256 * n_cb, pick({64, 128, 256}), 4, 256, 8, VQ_I8_BN); break;
         case 12: d = make(256 * m, 256 * n_cb, pick({64, 128, 256}), 2, 256, 8, VQ_I8_BN); break;
         case 13: d = make(8 * m, 256 * n_cb, 4, 2, 16, 4, VQ_I8); break;
+        case 14: d = make(8 * m, 256 * n_cb, 8, 2, 32, 5, VQ_I8); break;
         default: d = make(256 * m, 256 * n_cb, pick({64, 128, 256}), 2, 256, 8, VQ_I8); break;
       }
       descs.push_back(d);
@@ -173,7 +175,7 @@ int main(int argc, char** argv) {
 
   // ---- quantiser steps: every group shape of the decode formats
   for (int d : {1, 2, 4})
-    for (int k : {4, 8, 16, 64, 256})
+    for (int k : {4, 8, 16, 32, 64, 256})
       for (int gr : {1, 4, 8, 16, 32, 64, 128, 256}) {
         int bits = 0;
         while ((1 << bits) < k) ++bits;

@@ -26,11 +26,11 @@ long long g_launches = 0;
 // Units one chunk of the GEMV kernels holds: 4 col-block pairs (k = 16), 2 pairs (d = 1, k = 4),
 // one quad of col-blocks (the k = 64 layouts), 2 col-blocks (the k = 256 layouts).
 int chunk_units(int fmt) {
-  return (fmt == 16 || fmt == kFmtK16I8 || fmt == kFmtK16BN || fmt == kFmtK16I8H) ? 4 : (fmt == 64 || fmt == kFmtK64BN || fmt == kFmtD1K8 || fmt == kFmtD1K8BN) ? 1 : 2;
+  return (fmt == 16 || fmt == kFmtK16I8 || fmt == kFmtK16BN || fmt == kFmtK16I8H || fmt == kFmtK32) ? 4 : (fmt == 64 || fmt == kFmtK64BN || fmt == kFmtD1K8 || fmt == kFmtD1K8BN) ? 1 : 2;
 }
 
 int strip_units(int fmt, int n_cb) {
-  return (fmt == 16 || fmt == kFmtK16I8 || fmt == kFmtK16BN || fmt == kFmtK16I8H || fmt == kFmtD1K4) ? (n_cb + 1) / 2
+  return (fmt == 16 || fmt == kFmtK16I8 || fmt == kFmtK16BN || fmt == kFmtK16I8H || fmt == kFmtK32 || fmt == kFmtD1K4) ? (n_cb + 1) / 2
          : (fmt == 64 || fmt == kFmtK64BN || fmt == kFmtD1K8 || fmt == kFmtD1K8BN) ? (n_cb + 3) / 4 : n_cb;
 }
 

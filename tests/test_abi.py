@@ -149,6 +149,18 @@ def test_int8_table_representation_sizes_and_entry_points():
     assert (ib + cbb) * 8 * 1024 == 4096 * 11008 * (2 * 1024 + 16 * 2 * 8 + 16)
     assert vq.vq_layout_bytes(d) == (512 * 44 * 512, 512 * 44 * 68)
     assert L.vq_gemv(ctypes.byref(d), A, A, A + 2, A + 16, vq.VQ_F16, 0) == -4
+    # k = 32 with 5-bit indices (the 2.5-bits-per-dimension row): 2.5 + (32*2*8 + 16)/2048 = 2.7578 bits per value;
+    # device: 512 bytes of nibbles and 128 of fifth bits per group slot, 64-byte tables and a scale
+    d = vq.make_desc(4096, 11008, 32, 5, codebook_dtype=vq.VQ_I8)
+    ib, cbb = vq.vq_canonical_bytes(d)
+    assert ib == 4096 * 11008 * 5 // 16 and (ib + cbb) * 8 * 2048 == 4096 * 11008 * (5 * 1024 + 32 * 2 * 8 + 16)
+    assert vq.vq_layout_bytes(d) == (512 * 44 * 640, 512 * 44 * 66)
+    assert L.vq_gemv(ctypes.byref(d), A, A, A + 2, A + 16, vq.VQ_F16, 0) == -4
+    for bad in (vq.make_desc(4096, 4096, 32, 5),                                                # k = 32: int8 tables only
+                vq.make_desc(4096, 4096, 32, 5, codebook_dtype=vq.VQ_I8_BN),
+                vq.make_desc(4096, 4096, 32, 5, group_rows=4, codebook_dtype=vq.VQ_I8),
+                vq.make_desc(4096, 4096, 32, 5, d=1, codebook_dtype=vq.VQ_I8)):
+        assert L.vq_gemv(ctypes.byref(bad), A, A, A, A + 16, vq.VQ_F16, 0) == -3
     for bad in (vq.make_desc(4096, 4096, 16, 4, group_rows=4),                                  # fp16 codebooks: 8-row groups
                 vq.make_desc(4096, 4096, 16, 4, group_rows=4, codebook_dtype=vq.VQ_I8_BN),      # no block scales on 4-row groups
                 vq.make_desc(4100, 4096, 16, 4, group_rows=4, codebook_dtype=vq.VQ_I8),         # rows in blocks of 8

@@ -188,6 +188,7 @@ ANY_SHAPES = [
     (256, 512, 256, 2, 128), (64, 256, 256, 2, 64),
     (128, 512, 256, 4, 64), (256, 256, 256, 4, 256), (256, 768, 256, 4, 128),   # four-dimensional vectors
     (8, 256, 16, 2, 4), (40, 768, 16, 2, 4), (24, 512, 16, 1, 4),   # groups of 4 rows: two codebooks per 8-row block
+    (8, 256, 32, 2, 8), (40, 768, 32, 2, 8),          # k = 32 (5-bit indices)
     (16, 256, 16, 4, 8), (8, 256, 4, 2, 1),           # combinations no decode format uses, same kernels
 ]
 
@@ -195,7 +196,7 @@ ANY_SHAPES = [
 def _gpu_em_any(env, shape, W, h, cb):
     torch, vq, vqdev = env
     out_f, in_f, k, d, gr = shape
-    bits = {4: 2, 8: 3, 16: 4, 64: 6, 256: 8}[k]
+    bits = {4: 2, 8: 3, 16: 4, 32: 5, 64: 6, 256: 8}[k]
     desc = vq.make_desc(out_f, in_f, k, bits, group_rows=gr, d=d)
     a = torch.full((out_f, in_f // d), 255, dtype=torch.uint8, device="cuda:0")
     W_d, h_d = vqdev.to_device_bytes(W), vqdev.to_device_bytes(h)

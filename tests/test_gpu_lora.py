@@ -76,6 +76,7 @@ CASES = [
     (V(72, 1280, 256, 8), 16), (V(16, 256 * 43, 256, 8), 32),
     (V(96, 2816, 64, 6, 32, 256, 2, True), 16), (V(40, 768, 16, 4, 8, 256, 2, True), 40),
     (V(40, 256 * 5, 16, 4, 4, 256, 2, True), 24), (V(32776, 768, 16, 4, 4, 256, 2, True), 8),   # k = 16, int8 tables, 4-row groups
+    (V(40, 256 * 5, 32, 5, 8, 256, 2, True), 24), (V(32776, 768, 32, 5, 8, 256, 2, True), 8),   # k = 32, 5-bit indices
     (V(72, 1280, 16, 4, 8, 256, 1), 16), (V(96, 768, 8, 3, 32, 256, 1, True), 16), (V(40, 1280, 4, 2, 1, 256, 1, True), 56),
     (V(96, 768, 64, 6, 32, 256, 2, True, True), 16), (V(40, 256 * 5, 16, 4, 8, 256, 2, True, True), 24),
     (V(48, 256 * 5, 8, 3, 16, 256, 1, True, True), 24), (V(32800, 768, 8, 3, 32, 256, 1, True, True), 8),  # d = 1, k = 8, block scales

@@ -234,6 +234,7 @@ PASS_FORMATS = {
     "k64_bn": workloads.LLAMA7B_LAYER_K64_BN, "k16_bn": workloads.LLAMA7B_LAYER_K16_BN,
     "d1_k8_bn": workloads.LLAMA7B_LAYER_D1_K8_BN, "k256_bn": workloads.LLAMA7B_LAYER_K256_BN,
     "d4_bn": workloads.LLAMA7B_LAYER_D4_BN, "k16_i8_g4": workloads.LLAMA7B_LAYER_K16_I8_G4,
+    "k32": workloads.LLAMA7B_LAYER_K32,
 }
 
 
@@ -797,6 +798,85 @@ def _random_cases_g4(seed, n):
 @pytest.mark.parametrize("s", _random_cases_g4(20245, 10), ids=str)
 def test_random_shapes_k16_int8_4row_groups(env, s):
     seed = 7300 + s.out_features + s.in_features
+    desc, idx, cb, idx_d, cb_d = _setup_i8(env, s, seed)
+    f = _fmt(s)
+    np.testing.assert_array_equal(_gpu_decode(env, desc, idx_d, cb_d), oracle.decode_dense(f, idx, cb))
+    x = workloads.make_x(s.in_features, seed)
+    ref = oracle.gemv(f, idx, cb, x)
+    assert oracle.normwise_rel_err(_gpu_gemv(env, desc, idx_d, cb_d, x, False), ref) <= TOL_F16
+    assert oracle.normwise_rel_err(_gpu_gemv(env, desc, idx_d, cb_d, x, True), ref) <= TOL_F32
+    B = int(np.random.default_rng(seed).choice([1, 3, 8, 17, 33, 72, 200]))
+    X = workloads.make_X(s.in_features, B, seed)
+    Y = _gpu_gemm(env, desc, idx_d, cb_d, X, True)
+    assert oracle.normwise_rel_err(Y, oracle.gemm(f, idx, cb, X)) <= TOL_F32
+
+
+# ---------------------------------------------------------------- k = 32, 5-bit indices, int8 tables (2.75 bpv)
+def _shape32(o, i):
+    return workloads.VQShape(o, i, 32, 5, 8, 256, 2, True)
+
+
+SMALL32 = [_shape32(8, 256), _shape32(40, 768), _shape32(24, 2816), _shape32(264, 1024),
+           _shape32(16, 256 * 43), _shape32(72, 256 * 9)]
+FULL32 = ["attn_4096x4096_k32", "mlp_up_11008x4096_k32", "mlp_down_4096x11008_k32"]
+
+
+@pytest.mark.parametrize("s", SMALL32 + [workloads.CONFIGS[k] for k in FULL32], ids=str)
+def test_k32_decode_bit_exact(env, s):
+    desc, idx, cb, idx_d, cb_d = _setup_i8(env, s, 695)
+    np.testing.assert_array_equal(_gpu_decode(env, desc, idx_d, cb_d), oracle.decode_dense(_fmt(s), idx, cb))
+
+
+@pytest.mark.parametrize("f32", [False, True], ids=["y16", "y32"])
+@pytest.mark.parametrize("s", SMALL32 + [workloads.CONFIGS[k] for k in FULL32] +
+                         [_shape32(32776, 768), _shape32(32776, 2816)], ids=str)
+def test_k32_gemv(env, s, f32):
+    """Split-K kernel on the small and the layer shapes, the streaming kernel from 4,096 row-blocks."""
+    desc, idx, cb, idx_d, cb_d = _setup_i8(env, s, 696)
+    x = workloads.make_x(s.in_features, 696)
+    y = _gpu_gemv(env, desc, idx_d, cb_d, x, f32)
+    ref = oracle.gemv(_fmt(s), idx, cb, x)
+    assert oracle.normwise_rel_err(y, ref) <= (TOL_F32 if f32 else TOL_F16)
+    if s.out_features >= 4096:
+        _assert_rows_match(y, ref, f32, str(s))
+
+
+def test_k32_unit_vectors_pick_columns(env):
+    s = _shape32(24, 1280)
+    desc, idx, cb, idx_d, cb_d = _setup_i8(env, s, 697)
+    W = oracle.decode_dense(_fmt(s), idx, cb).view(np.float16).astype(np.float64)
+    for c in (0, 1, 255, 256, 1023, 1024, 1279):
+        e = np.zeros(s.in_features, dtype=np.float16)
+        e[c] = 1
+        np.testing.assert_array_equal(_gpu_gemv(env, desc, idx_d, cb_d, e, True), W[:, c])
+
+
+@pytest.mark.parametrize("B", [1, 16, 40, 130, 600, 1300])
+@pytest.mark.parametrize("s", [_shape32(96, 768), _shape32(808, 512)], ids=str)
+def test_k32_gemm(env, s, B):
+    desc, idx, cb, idx_d, cb_d = _setup_i8(env, s, 698)
+    X = workloads.make_X(s.in_features, B, 698)
+    Y = _gpu_gemm(env, desc, idx_d, cb_d, X, False, pad=8 if B == 40 else 0)
+    assert oracle.normwise_rel_err(Y, oracle.gemm(_fmt(s), idx, cb, X)) <= TOL_F16
+
+
+@pytest.mark.timeout(600)
+def test_k32_full_size_gemm(env):
+    s = workloads.CONFIGS["mlp_down_4096x11008_k32"]
+    desc, idx, cb, idx_d, cb_d = _setup_i8(env, s, 699)
+    X = workloads.make_X(s.in_features, 2048, 699)
+    W = oracle.decode_dense(_fmt(s), idx, cb)
+    _assert_tiles_match(_gpu_gemm(env, desc, idx_d, cb_d, X, False), _dense_product(W, X))
+
+
+def _random_cases_k32(seed, n):
+    rng = np.random.default_rng(seed)
+    return [_shape32(8 * int(rng.integers(1, 40)), 256 * int(rng.integers(1, 45))) for _ in range(n)]
+
+
+@pytest.mark.parametrize("s", _random_cases_k32(20246, 10), ids=str)
+def test_random_shapes_k32(env, s):
+    seed = 7400 + s.out_features + s.in_features
     desc, idx, cb, idx_d, cb_d = _setup_i8(env, s, seed)
     f = _fmt(s)
     np.testing.assert_array_equal(_gpu_decode(env, desc, idx_d, cb_d), oracle.decode_dense(f, idx, cb))

@@ -185,5 +185,5 @@ def test_e_step_kernel_has_no_fused_multiply_add(tmp_path):
             inside = False
         elif inside and re.match(r"\s+v_(fma|fmac|mac|mad|pk_fma|pk_mul|pk_add)_f32", line):
             fused.append(line.strip())
-    assert seen == 3 + 25 + 10            # d = 2, 8-row groups: k = 16, 64, 256; 25 kernels for the other (k, d, group) cases; 10 for 4-row groups
+    assert seen == 3 + 25 + 10 + 6        # d = 2, 8-row groups: k = 16, 64, 256; 25 kernels for the other (k, d, group) cases; 10 for 4-row groups; 6 for k = 32
     assert fused == []

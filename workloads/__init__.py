@@ -23,7 +23,7 @@ __all__ = [
     "VQShape", "CONFIGS", "LLAMA7B_LAYER", "seed_for", "canonical_sizes",
     "make_weights", "make_weights_i8", "make_x", "make_X", "llama7b_pass_shapes",
     "tables_i8_bytes", "tables_bn_bytes",
-    "LLAMA7B_LAYER_K64", "LLAMA7B_LAYER_K16_I8", "LLAMA7B_LAYER_K16_I8_G4", "LLAMA7B_LAYER_D1_K16", "LLAMA7B_LAYER_K64_BN", "LLAMA7B_LAYER_K16_BN", "make_weights_bn", "LLAMA7B_LAYER_D4", "LLAMA7B_LAYER_D1_K8", "LLAMA7B_LAYER_D1_K8_BN", "LLAMA7B_LAYER_K256_BN", "LLAMA7B_LAYER_D4_BN", "LLAMA7B_LAYER_K256_I8", "LLAMA7B_LAYER_D1_K4",
+    "LLAMA7B_LAYER_K64", "LLAMA7B_LAYER_K16_I8", "LLAMA7B_LAYER_K16_I8_G4", "LLAMA7B_LAYER_K32", "LLAMA7B_LAYER_D1_K16", "LLAMA7B_LAYER_K64_BN", "LLAMA7B_LAYER_K16_BN", "make_weights_bn", "LLAMA7B_LAYER_D4", "LLAMA7B_LAYER_D1_K8", "LLAMA7B_LAYER_D1_K8_BN", "LLAMA7B_LAYER_K256_BN", "LLAMA7B_LAYER_D4_BN", "LLAMA7B_LAYER_K256_I8", "LLAMA7B_LAYER_D1_K4",
 ]
 
 
@@ -77,6 +77,10 @@ CONFIGS = {
     "attn_4096x4096_k16_i8": VQShape(4096, 4096, 16, 4, 8, 256, 2, True),
     "mlp_up_11008x4096_k16_i8": VQShape(11008, 4096, 16, 4, 8, 256, 2, True),
     "mlp_down_4096x11008_k16_i8": VQShape(4096, 11008, 16, 4, 8, 256, 2, True),
+    # the 2.5-bits-per-dimension 2D row of the appendix table: k = 32, 5-bit indices, int8 tables, 8 x 256 groups: 2.75 bpv
+    "attn_4096x4096_k32": VQShape(4096, 4096, 32, 5, 8, 256, 2, True),
+    "mlp_up_11008x4096_k32": VQShape(11008, 4096, 32, 5, 8, 256, 2, True),
+    "mlp_down_4096x11008_k32": VQShape(4096, 11008, 32, 5, 8, 256, 2, True),
     # the paper's 2.25-bit 2D setting: the same with groups of 1,024 weights (4 rows x 256 columns)
     "attn_4096x4096_k16_i8_g4": VQShape(4096, 4096, 16, 4, 4, 256, 2, True),
     "mlp_up_11008x4096_k16_i8_g4": VQShape(11008, 4096, 16, 4, 4, 256, 2, True),
@@ -143,6 +147,7 @@ LLAMA7B_LAYER = (
 LLAMA7B_LAYER_K64 = tuple((n, k.replace("_k16", "_k64_i8")) for n, k in LLAMA7B_LAYER)
 LLAMA7B_LAYER_K256_I8 = tuple((n, k.replace("_k16", "_k256_i8")) for n, k in LLAMA7B_LAYER)
 LLAMA7B_LAYER_K16_I8 = tuple((n, k + "_i8") for n, k in LLAMA7B_LAYER)
+LLAMA7B_LAYER_K32 = tuple((n, k.replace("_k16", "_k32")) for n, k in LLAMA7B_LAYER)
 LLAMA7B_LAYER_K16_I8_G4 = tuple((n, k + "_i8_g4") for n, k in LLAMA7B_LAYER)
 LLAMA7B_LAYER_K64_BN = tuple((n, k.replace("_k16", "_k64_bn")) for n, k in LLAMA7B_LAYER)
 LLAMA7B_LAYER_K16_BN = tuple((n, k + "_bn") for n, k in LLAMA7B_LAYER)
